@@ -1,0 +1,104 @@
+"""Dense networks in float64: forward, loss, backward (oracle side).
+
+`step` in the paper (Section 3, Eq. 2) is one gradient-descent update of a
+member's weights theta given its hyperparameters h; this module supplies the
+gradient of the training objective for the fully connected workloads.  A
+network is a list of (W, b) pairs with W of shape (fan_in, fan_out); a layer
+computes a @ W + b and every layer but the last is followed by the activation.
+Nothing here is blocked, fused or reordered: each function is the textbook
+definition written out.
+"""
+import numpy as np
+from scipy.special import erf
+
+ACT_NONE, ACT_RELU, ACT_GELU, ACT_LEAKY_RELU, ACT_TANH = 0, 1, 2, 3, 4
+LEAKY_SLOPE = 0.2
+
+
+def act(z, kind):
+    if kind == ACT_NONE:
+        return z
+    if kind == ACT_RELU:
+        return np.where(z > 0.0, z, 0.0)
+    if kind == ACT_GELU:                       # exact form: z * Phi(z)
+        return 0.5 * z * (1.0 + erf(z / np.sqrt(2.0)))
+    if kind == ACT_LEAKY_RELU:
+        return np.where(z > 0.0, z, LEAKY_SLOPE * z)
+    if kind == ACT_TANH:
+        return np.tanh(z)
+    raise ValueError(kind)
+
+
+def act_grad(z, kind):
+    """d act(z) / dz, elementwise."""
+    if kind == ACT_NONE:
+        return np.ones_like(z)
+    if kind == ACT_RELU:
+        return np.where(z > 0.0, 1.0, 0.0)
+    if kind == ACT_GELU:                       # Phi(z) + z * phi(z)
+        return 0.5 * (1.0 + erf(z / np.sqrt(2.0))) + z * np.exp(-0.5 * z * z) / np.sqrt(2.0 * np.pi)
+    if kind == ACT_LEAKY_RELU:
+        return np.where(z > 0.0, 1.0, LEAKY_SLOPE)
+    if kind == ACT_TANH:
+        return 1.0 - np.tanh(z) ** 2
+    raise ValueError(kind)
+
+
+def mlp_forward(params, x, hidden_act, out_act=ACT_NONE):
+    """Returns (output, cache).  cache = (inputs to each layer, pre-activations)."""
+    a = np.asarray(x, dtype=np.float64)
+    ins, zs = [], []
+    L = len(params)
+    for l, (W, b) in enumerate(params):
+        ins.append(a)
+        z = a @ W + b
+        zs.append(z)
+        a = act(z, hidden_act if l < L - 1 else out_act)
+    return a, (ins, zs)
+
+
+def mlp_backward(params, cache, d_out, hidden_act, out_act=ACT_NONE):
+    """Given dLoss/d(output), returns ([(dW, db), ...], dLoss/d(input))."""
+    ins, zs = cache
+    L = len(params)
+    grads = [None] * L
+    da = d_out
+    for l in range(L - 1, -1, -1):
+        W, _ = params[l]
+        dz = da * act_grad(zs[l], hidden_act if l < L - 1 else out_act)
+        grads[l] = (ins[l].T @ dz, dz.sum(axis=0))
+        da = dz @ W.T
+    return grads, da
+
+
+def log_softmax(logits):
+    m = logits.max(axis=-1, keepdims=True)
+    s = logits - m
+    return s - np.log(np.exp(s).sum(axis=-1, keepdims=True))
+
+
+def softmax_xent(logits, labels, smoothing=0.0):
+    """Mean over rows of the cross-entropy between the (label-smoothed) target
+    distribution and softmax(logits).  Returns (loss, dLoss/dlogits).
+    Target: (1 - smoothing) on the label plus smoothing / C on every class."""
+    n, C = logits.shape
+    lsm = log_softmax(logits)
+    q = np.full((n, C), smoothing / C)
+    q[np.arange(n), labels] += 1.0 - smoothing
+    loss = -(q * lsm).sum() / n
+    dlogits = (np.exp(lsm) - q) / n
+    return loss, dlogits
+
+
+def classifier_loss_and_grads(params, x, labels, hidden_act):
+    """Training objective of the classifier workloads: mean softmax cross-entropy."""
+    logits, cache = mlp_forward(params, x, hidden_act)
+    loss, dlogits = softmax_xent(logits, labels)
+    grads, _ = mlp_backward(params, cache, dlogits, hidden_act)
+    return loss, grads
+
+
+def classifier_eval_loss(params, x, labels, hidden_act):
+    logits, _ = mlp_forward(params, x, hidden_act)
+    loss, _ = softmax_xent(logits, labels)
+    return loss

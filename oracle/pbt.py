@@ -1,0 +1,178 @@
+"""Population Based Training: the population store and the exploit/explore
+pass, in the synchronous form (oracle side).
+
+Follows Algorithm 1 of the paper (Section 3) executed with the partial
+synchrony of Appendix A.1: every member is advanced by `step` for a fixed
+number of iterations, then `eval` scores every member and the
+exploit-and-explore procedure runs over the whole population, and the cycle
+repeats.  `exploit` is truncation selection (Section 4.1.1, Exploit (b)): rank
+all members by score; each member of the bottom set samples a donor uniformly
+from the top set and takes over its weights and hyperparameters.  `explore` is
+perturb (Section 4.1.1, Explore (a)): every hyperparameter of a member that was
+overwritten is multiplied, independently, by one of two factors.  Members that
+were not overwritten are left exactly as they were (the `theta != theta'`
+test of Algorithm 1).
+
+Readings where the paper is silent (kept identical, as text, on the GPU side):
+  * the sizes of top and bottom set are one integer `n_trunc`, 2 n_trunc <= P;
+  * order = score descending, ties by lower member index first, -inf after
+    every finite score, NaN after -inf;
+  * donors are drawn independently per recipient (with replacement) from one
+    Philox word: top[(x * n_trunc) >> 32];
+  * factor = low bit of a Philox word: 0 -> lower factor, 1 -> upper factor;
+  * the multiply is an IEEE float32 multiply of the donor's float32
+    hyperparameter by the float32-rounded factor, followed by an upper clamp
+    for hyperparameters that are probabilities (no clamp to the prior range);
+  * the optimiser state and the update count are copied with the weights, and
+    so are the donor's score and score history (re-evaluating a byte-identical
+    copy, as Algorithm 1 does after explore, would return the same number).
+"""
+import copy
+import math
+import numpy as np
+
+from . import philox
+
+
+class Member:
+    """One tuple (theta, h, p, t) of the population, plus optimiser state and
+    the index of the member it last copied from."""
+
+    def __init__(self, theta, h, opt_state=None, index=0):
+        self.theta = theta                        # list of float64 arrays
+        self.opt = opt_state if opt_state is not None else {}
+        self.h = np.asarray(h, dtype=np.float32).copy()
+        self.p = np.float32(-np.inf)
+        self.t = 0                                # optimiser updates applied
+        self.parent = index
+        self.hist = None                          # optional score history
+
+
+def rank_order(scores):
+    """Member indices from best to worst."""
+    s = np.asarray(scores, dtype=np.float32)
+
+    def key(i):
+        v = float(s[i])
+        if math.isnan(v):
+            return (1, 0.0, i)
+        return (0, -v, i)
+    return sorted(range(len(s)), key=key)
+
+
+def truncation_select(scores, n_trunc, round_index, seed):
+    """Returns (order, donor): donor[i] = member i copies from, or -1."""
+    P = len(scores)
+    if not 0 <= 2 * n_trunc <= P:
+        raise ValueError("need 0 <= 2*n_trunc <= P")
+    order = rank_order(scores)
+    donor = np.full(P, -1, dtype=np.int32)
+    if n_trunc == 0:
+        return order, donor
+    top = order[:n_trunc]
+    bottom = order[P - n_trunc:]
+    for r in bottom:
+        x = philox.words(seed, round_index, r, philox.DOMAIN_DONOR, 0)[0]
+        donor[r] = top[int(philox.bounded(x, n_trunc))]
+    return order, donor
+
+
+def perturb(h_src, round_index, r, seed, factor_lo, factor_hi, h_max=None):
+    """Explore for recipient r: float32 multiply of every hyperparameter of the
+    source vector by factor_lo or factor_hi."""
+    h_src = np.asarray(h_src, dtype=np.float32)
+    out = np.empty_like(h_src)
+    f_lo = np.float32(factor_lo)
+    f_hi = np.float32(factor_hi)
+    for k in range(len(h_src)):
+        bit = int(philox.words(seed, round_index, r, philox.DOMAIN_EXPLORE, k)[0]) & 1
+        f = f_hi if bit else f_lo
+        # product of two float32 values is exact in float64; one rounding to
+        # float32 is the IEEE float32 multiply
+        v = np.float32(np.float64(h_src[k]) * np.float64(f))
+        if h_max is not None and v > np.float32(h_max[k]):
+            v = np.float32(h_max[k])
+        out[k] = v
+    return out
+
+
+def exploit_explore(pop, round_index, seed, n_trunc, factor_lo=0.8, factor_hi=1.2, h_max=None,
+                    scores=None, explore_fn=None):
+    """One exploit-and-explore pass over the population, in place.
+    `scores` overrides the members' stored p (float32).  `explore_fn(h, round,
+    r)` replaces the perturb rule (used by the toy example).  Returns (order, donor)."""
+    if scores is None:
+        scores = np.array([m.p for m in pop], dtype=np.float32)
+    else:
+        scores = np.asarray(scores, dtype=np.float32)
+        for m, s in zip(pop, scores):
+            m.p = np.float32(s)
+    order, donor = truncation_select(scores, n_trunc, round_index, seed)
+    for r in range(len(pop)):
+        d = int(donor[r])
+        if d < 0:
+            continue
+        src, dst = pop[d], pop[r]
+        dst.theta = copy.deepcopy(src.theta)
+        dst.opt = copy.deepcopy(src.opt)
+        dst.t = src.t
+        dst.p = src.p
+        dst.hist = copy.deepcopy(src.hist)
+        if explore_fn is None:
+            dst.h = perturb(src.h, round_index, r, seed, factor_lo, factor_hi, h_max)
+        else:
+            dst.h = np.asarray(explore_fn(src.h, round_index, r), dtype=np.float32)
+        dst.parent = d
+    return order, donor
+
+
+def train(pop, n_steps, step_fn, eval_fn, ready_interval, exploit_explore_fn, log=None):
+    """Algorithm 1 in lock-step.  step_fn(member, i, s) applies one update,
+    eval_fn(member, i) returns the score, exploit_explore_fn(pop, round) runs
+    the pass.  Returns the index of the member with the highest score."""
+    round_index = 0
+    for s in range(n_steps):
+        for i, m in enumerate(pop):
+            step_fn(m, i, s)
+        if ready_interval > 0 and (s + 1) % ready_interval == 0:
+            for i, m in enumerate(pop):
+                m.p = np.float32(eval_fn(m, i))
+            res = exploit_explore_fn(pop, round_index)
+            if log is not None:
+                log(s, round_index, res)
+            round_index += 1
+    for i, m in enumerate(pop):
+        m.p = np.float32(eval_fn(m, i))
+    return rank_order([m.p for m in pop])[0]
+
+
+# ----------------------------------------------------------------------------
+# The toy example of Figure 2: maximise Q(theta) = 1.2 - (theta0^2 + theta1^2)
+# by gradient ascent on the surrogate Qhat(theta|h) = 1.2 - (h0 theta0^2 + h1 theta1^2).
+
+def toy_Q(theta):
+    return 1.2 - float(theta[0] ** 2 + theta[1] ** 2)
+
+
+def toy_step(member, lr):
+    th = member.theta[0]
+    h = member.h.astype(np.float64)
+    member.theta[0] = th + lr * (-2.0 * h * th)       # ascent on Qhat
+    member.t += 1
+
+
+def toy_run(n_steps, lr, use_pbt, noise=None, ready_interval=4):
+    """Two workers from theta = [0.9, 0.9] with h = [1, 0] and [0, 1].  With
+    use_pbt the weaker copies the better every `ready_interval` iterations and
+    adds noise[round] (shape (2,)) to the copied h.  Returns final Q per worker."""
+    pop = [Member([np.array([0.9, 0.9])], [1.0, 0.0], index=0),
+           Member([np.array([0.9, 0.9])], [0.0, 1.0], index=1)]
+
+    def ee(pop, rnd):
+        if not use_pbt:
+            return None
+        return exploit_explore(pop, rnd, seed=0, n_trunc=1,
+                               explore_fn=lambda h, rr, r: h + np.asarray(noise[rr], dtype=np.float32))
+    train(pop, n_steps, lambda m, i, s: toy_step(m, lr), lambda m, i: toy_Q(m.theta[0]),
+          ready_interval, ee)
+    return [toy_Q(m.theta[0]) for m in pop]

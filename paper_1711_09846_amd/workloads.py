@@ -1,0 +1,105 @@
+"""Workload definitions and seeded synthetic inputs.
+
+This module holds no arithmetic of the method: it only names shapes and
+constants of the synthetic workloads and draws their inputs (data sets,
+initial weights, initial hyperparameters) from numpy's seeded generator.  The
+same arrays are handed to the GPU library and to whatever they are checked
+against, so input generation is never a surface on which the two can differ.
+
+The workloads stand in for the paper's experiments (Section 4), whose data sets
+and environments are not redistributable with a benchmark: Gaussian-mixture
+classifiers for generic supervised learning (Section 3), an MLP GAN for the
+CIFAR GAN of Section 4.3, a small decoder-only transformer for the translation
+model of Section 4.2 and an actor-critic MLP for the agents of Section 4.1.
+"""
+import math
+import numpy as np
+
+ACT_NONE, ACT_RELU, ACT_GELU, ACT_LEAKY_RELU, ACT_TANH = 0, 1, 2, 3, 4
+OPT_SGD_MOMENTUM, OPT_ADAM, OPT_RMSPROP = 0, 1, 2
+DTYPE_FP32, DTYPE_BF16 = 0, 1
+ROLE_LR, ROLE_BETA1, ROLE_WD = 0, 1, 2
+WL_CLASSIFIER = 1
+
+POPULATION_SEED = 2017          # Philox key of the population
+
+
+def trunc_count(P, percent):
+    """Size of the top and of the bottom set: floor(P * percent / 100), at least 1."""
+    return max(1, (P * percent) // 100)
+
+
+class Workload:
+    def __init__(self, **kw):
+        self.__dict__.update(kw)
+
+    def replace(self, **kw):
+        d = dict(self.__dict__)
+        d.update(kw)
+        return Workload(**d)
+
+
+# Two-layer fp32 MLPs, SGD with momentum; lr is the one hyperparameter.
+MLP_SMALL = Workload(
+    name="mlp_small_fp32", kind=WL_CLASSIFIER, P=8, dims=[32, 64, 4], act=ACT_RELU,
+    dtype=DTYPE_FP32, optimizer=OPT_SGD_MOMENTUM, batch=64, n_train=4096, n_eval=1024,
+    n_classes=4, roles=[ROLE_LR], priors=[("log", 1e-3, 1e-1)], h_max=[math.inf],
+    ready_interval=50, n_trunc=trunc_count(8, 25), total_steps=1000,
+    opt_const=dict(momentum=0.9), data_seed=1001, perturb=(0.8, 1.2))
+
+# bf16 MLPs with fp32 master weights, Adam; lr, beta1 and weight decay per member.
+MLP_WIDE = Workload(
+    name="mlp_wide_bf16", kind=WL_CLASSIFIER, P=64, dims=[256, 1024, 1024, 10], act=ACT_GELU,
+    dtype=DTYPE_BF16, optimizer=OPT_ADAM, batch=128, n_train=65536, n_eval=8192,
+    n_classes=10, roles=[ROLE_LR, ROLE_BETA1, ROLE_WD],
+    priors=[("log", 1e-4, 1e-2), ("uniform", 0.8, 0.95), ("log", 1e-6, 1e-3)],
+    h_max=[math.inf, 0.999, math.inf],
+    ready_interval=200, n_trunc=trunc_count(64, 20), total_steps=10000,
+    opt_const=dict(beta2=0.999, eps=1e-8), data_seed=1002, perturb=(0.8, 1.2))
+
+WORKLOADS = {1: MLP_SMALL, 2: MLP_WIDE}
+
+
+def gaussian_mixture(n_classes, dim, n_train, n_eval, seed):
+    """Class means ~ N(0, I); x = mean[label] + N(0, I); labels uniform."""
+    rng = np.random.default_rng(seed)
+    means = rng.standard_normal((n_classes, dim))
+    out = []
+    for n in (n_train, n_eval):
+        y = rng.integers(0, n_classes, size=n).astype(np.int32)
+        x = (means[y] + rng.standard_normal((n, dim))).astype(np.float32)
+        out.append((x, y))
+    return out[0], out[1]
+
+
+def classifier_data(wl):
+    return gaussian_mixture(wl.n_classes, wl.dims[0], wl.n_train, wl.n_eval, wl.data_seed)
+
+
+def initial_hypers(wl, seed):
+    """float32 array [P][n_h] drawn from the priors ("log" = log-uniform)."""
+    rng = np.random.default_rng(seed)
+    H = np.empty((wl.P, len(wl.priors)), dtype=np.float32)
+    for k, (kind, lo, hi) in enumerate(wl.priors):
+        u = rng.random(wl.P)
+        if kind == "log":
+            H[:, k] = np.exp(math.log(lo) + u * (math.log(hi) - math.log(lo)))
+        else:
+            H[:, k] = lo + u * (hi - lo)
+    return H
+
+
+def initial_mlp_weights(dims, P, seed):
+    """Per member a list of (W[fan_in][fan_out], b[fan_out]) float32 arrays,
+    uniform in +-1/sqrt(fan_in)."""
+    rng = np.random.default_rng(seed)
+    pop = []
+    for _ in range(P):
+        layers = []
+        for fi, fo in zip(dims[:-1], dims[1:]):
+            bound = 1.0 / math.sqrt(fi)
+            W = rng.uniform(-bound, bound, size=(fi, fo)).astype(np.float32)
+            b = rng.uniform(-bound, bound, size=(fo,)).astype(np.float32)
+            layers.append((W, b))
+        pop.append(layers)
+    return pop

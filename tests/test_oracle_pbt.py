@@ -1,0 +1,232 @@
+"""Pins for the oracle's exploit/explore pass and training loop: brute force on
+tiny populations, the invariants the paper states in prose (Section 4.1.1,
+Algorithm 1) and the toy example of Figure 2."""
+import itertools
+import math
+import os
+import numpy as np
+import pytest
+
+from oracle import pbt, philox, classifier, nets
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "toy_figure2.txt")
+
+
+def _beats(sa, a, sb, b):
+    """Textbook strict order: does member a rank above member b?"""
+    na, nb = math.isnan(sa), math.isnan(sb)
+    if na != nb:
+        return nb
+    if not na and sa != sb:
+        return sa > sb
+    return a < b
+
+
+def test_rank_bruteforce_with_ties_nan_inf():
+    vals = [0.5, 0.5, -1.0, float("nan"), float("-inf"), float("inf"), 2.0, float("nan")]
+    for P in range(1, 6):
+        for combo in itertools.product(vals, repeat=P):
+            order = pbt.rank_order(np.array(combo, dtype=np.float32))
+            # rank by counting how many members beat me
+            pos = [sum(_beats(combo[j], j, combo[i], i) for j in range(P) if j != i) for i in range(P)]
+            assert sorted(pos) == list(range(P))
+            assert [order[pos[i]] for i in range(P)] == list(range(P))
+
+
+def _mk_pop(P, n_h=2, rng=None):
+    rng = rng or np.random.default_rng(0)
+    pop = []
+    for i in range(P):
+        m = pbt.Member([rng.standard_normal(5), rng.standard_normal((2, 3))],
+                       rng.uniform(0.01, 1.0, size=n_h),
+                       {"s0": [rng.standard_normal(5), rng.standard_normal((2, 3))]}, i)
+        m.t = 10 + i
+        pop.append(m)
+    return pop
+
+
+def _snapshot(m):
+    return (b"".join(a.tobytes() for a in m.theta), b"".join(a.tobytes() for a in m.opt["s0"]),
+            m.h.tobytes(), m.t, np.float32(m.p).tobytes(), m.parent)
+
+
+@pytest.mark.parametrize("P", [5, 6, 7, 8])
+def test_truncation_exhaustive(P):
+    base = np.linspace(-1.0, 1.0, P)
+    perms = list(itertools.permutations(range(P)))
+    if len(perms) > 720:
+        perms = perms[::len(perms) // 720]
+    for n_trunc in range(0, P // 2 + 1):
+        for rnd, perm in enumerate(perms):
+            scores = base[list(perm)].astype(np.float32)
+            pop = _mk_pop(P)
+            for m, s in zip(pop, scores):
+                m.p = s
+            before = [_snapshot(m) for m in pop]
+            anc_before = len({m.parent for m in pop})
+            order, donor = pbt.exploit_explore(pop, rnd, seed=99, n_trunc=n_trunc)
+            srt = sorted(range(P), key=lambda i: -scores[i])
+            top, bottom = set(srt[:n_trunc]), set(srt[P - n_trunc:]) if n_trunc else set()
+            assert order == srt
+            for i in range(P):
+                if i in bottom:
+                    d = donor[i]
+                    assert d in top                                   # donor from the top set
+                    assert _snapshot(pop[i])[:2] == before[d][:2]      # weights + optimiser state, byte for byte
+                    assert pop[i].t == pop[d].t and pop[i].parent == d
+                    assert np.float32(pop[i].p) == scores[d]
+                    for k in range(2):                                # exactly one of the two factors
+                        lo = np.float32(np.float32(before_h(before[d])[k]) * np.float32(0.8))
+                        hi = np.float32(np.float32(before_h(before[d])[k]) * np.float32(1.2))
+                        assert pop[i].h[k].tobytes() in (lo.tobytes(), hi.tobytes())
+                else:
+                    assert donor[i] == -1
+                    assert _snapshot(pop[i]) == before[i]             # untouched, hyperparameters included
+            assert len({m.parent for m in pop}) <= anc_before       # ancestors can only disappear
+
+
+def before_h(snap):
+    return np.frombuffer(snap[2], dtype=np.float32)
+
+
+
+def test_distinct_ancestors_never_increase():
+    # Section 4.4 (lineages): copying can only remove ancestors from the population.
+    P = 10
+    rng = np.random.default_rng(4)
+    anc = list(range(P))
+    pop = _mk_pop(P)
+    n_prev = P
+    for rnd in range(40):
+        scores = rng.standard_normal(P).astype(np.float32)
+        _, donor = pbt.exploit_explore(pop, rnd, seed=5, n_trunc=2, scores=scores)
+        anc = [anc[d] if d >= 0 else anc[i] for i, d in enumerate(donor)]
+        assert len(set(anc)) <= n_prev
+        n_prev = len(set(anc))
+    assert n_prev < P
+
+
+def test_donor_uniform_over_top_and_with_replacement():
+    P, n_trunc = 20, 4
+    scores = np.arange(P, dtype=np.float32)          # top = 19, 18, 17, 16
+    hits = np.zeros(P, dtype=int)
+    repeats = 0
+    for rnd in range(3000):
+        _, donor = pbt.truncation_select(scores, n_trunc, rnd, seed=2017)
+        ds = donor[donor >= 0]
+        assert len(ds) == n_trunc and set(np.nonzero(donor >= 0)[0]) == {0, 1, 2, 3}
+        repeats += len(set(ds)) < n_trunc
+        for d in ds:
+            hits[d] += 1
+    assert hits[:16].sum() == 0
+    assert np.all(np.abs(hits[16:] / hits.sum() - 0.25) < 0.02)
+    assert repeats > 0
+
+
+def test_donor_index_formula():
+    scores = np.array([3, 1, 2, 0, 5, 4], dtype=np.float32)      # order 4,5,0,2,1,3
+    _, donor = pbt.truncation_select(scores, 2, 7, seed=123)
+    for r in (1, 3):
+        x = int(philox.philox4x32_10([7, r, philox.DOMAIN_DONOR, 0], [123, 0])[0])
+        assert donor[r] == [4, 5][(x * 2) >> 32]
+
+
+def test_perturb_factors_and_frequency():
+    h = np.array([0.013, 0.9, 1e-5], dtype=np.float32)
+    n_hi = 0
+    for rnd in range(4000):
+        out = pbt.perturb(h, rnd, 3, seed=11, factor_lo=0.8, factor_hi=1.2)
+        for k in range(3):
+            bit = int(philox.philox4x32_10([rnd, 3, philox.DOMAIN_EXPLORE, k], [11, 0])[0]) & 1
+            ref = h[k] * (np.float32(1.2) if bit else np.float32(0.8))     # numpy float32 multiply
+            assert out[k].tobytes() == np.float32(ref).tobytes()
+            n_hi += bit
+    assert abs(n_hi / 12000 - 0.5) < 0.02
+
+
+def test_perturb_clamp_and_zero():
+    out = pbt.perturb(np.array([0.95, 0.0], dtype=np.float32), 0, 0, seed=1, factor_lo=1.2, factor_hi=1.2,
+                      h_max=[0.999, math.inf])
+    assert out[0] == np.float32(0.999) and out[1] == 0.0
+
+
+def test_nan_member_is_replaced():
+    pop = _mk_pop(6)
+    scores = np.array([0.1, np.nan, 0.3, 0.2, 0.5, 0.4], dtype=np.float32)
+    pop[1].theta[0][:] = np.nan
+    _, donor = pbt.exploit_explore(pop, 0, seed=3, n_trunc=1, scores=scores)
+    assert donor[1] == 4 and np.isfinite(pop[1].theta[0]).all()
+
+
+def test_truncation_rejects_overlap():
+    with pytest.raises(ValueError):
+        pbt.truncation_select(np.zeros(5, dtype=np.float32), 3, 0, 0)
+
+
+def _gold():
+    d = {}
+    for line in open(GOLD):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, v = line.split()
+        d[k] = float(v)
+    return d
+
+
+def test_toy_figure2():
+    gold = _gold()
+    q = pbt.toy_run(400, 0.02, use_pbt=False)
+    assert abs(q[0] - gold["fixed_h_final_Q"]) < 1e-6 and abs(q[1] - gold["fixed_h_final_Q"]) < 1e-6
+    assert abs(round(q[0], 1) - gold["fixed_h_paper_value"]) < 1e-12
+    rng = np.random.default_rng(0)
+    for trial in range(5):
+        noise = rng.normal(0.0, 0.1, size=(200, 2))
+        q = pbt.toy_run(800, 0.02, use_pbt=True, noise=noise)
+        assert max(q) > gold["pbt_final_Q"] - 1e-2, q
+
+
+def _tiny_spec(optimizer, roles):
+    return classifier.ClassifierSpec([3, 5, 2], nets.ACT_RELU, optimizer, batch=4, roles=roles, seed=42)
+
+
+def test_member_independence_and_random_search_limit():
+    # With n_trunc = 0 PBT is random search (Section 4.1.2): each member's trajectory
+    # equals a run of that member alone.
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((32, 3)).astype(np.float32)
+    y = rng.integers(0, 2, 32).astype(np.int32)
+    spec = _tiny_spec(classifier.OPT_ADAM, [classifier.ROLE_LR, classifier.ROLE_BETA1, classifier.ROLE_WD])
+
+    def make(i):
+        r = np.random.default_rng(100 + i)
+        theta = [(r.standard_normal((3, 5)), r.standard_normal(5)), (r.standard_normal((5, 2)), r.standard_normal(2))]
+        return classifier.new_member(spec, theta, [0.01 * (i + 1), 0.9, 1e-4], i)
+
+    pop = [make(i) for i in range(4)]
+    pbt.train(pop, 12, lambda m, i, s: classifier.step(spec, m, i, s, x, y),
+              lambda m, i: classifier.evaluate(spec, m, x, y), 4,
+              lambda pop, rnd: pbt.exploit_explore(pop, rnd, spec.seed, 0))
+    solo = make(2)
+    for s in range(12):
+        classifier.step(spec, solo, 2, s, x, y)
+    for a, b in zip(solo.theta, pop[2].theta):
+        assert a.tobytes() == b.tobytes()
+    assert pop[2].t == 12 and pop[2].parent == 2
+
+
+def test_training_reduces_loss_and_batch_rows():
+    rng = np.random.default_rng(2)
+    means = rng.standard_normal((2, 3)) * 2
+    y = rng.integers(0, 2, 256).astype(np.int32)
+    x = (means[y] + rng.standard_normal((256, 3))).astype(np.float32)
+    spec = _tiny_spec(classifier.OPT_SGD_MOMENTUM, [classifier.ROLE_LR])
+    r = np.random.default_rng(9)
+    theta = [(r.standard_normal((3, 5)) * 0.3, np.zeros(5)), (r.standard_normal((5, 2)) * 0.3, np.zeros(2))]
+    m = classifier.new_member(spec, theta, [0.05], 0)
+    l0 = -classifier.evaluate(spec, m, x, y)
+    for s in range(200):
+        classifier.step(spec, m, 0, s, x, y)
+    assert -classifier.evaluate(spec, m, x, y) < 0.6 * l0
+    rows = classifier.batch_rows(42, 5, 1, 4, 256)
+    ref = [(int(philox.philox4x32_10([5, 1, philox.DOMAIN_BATCH, j], [42, 0])[0]) * 256) >> 32 for j in range(4)]
+    assert list(rows) == ref
