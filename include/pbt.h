@@ -1,0 +1,197 @@
+/*
+ * pbt.h -- C ABI of the MI355X population step of Population Based Training
+ * (Jaderberg et al., "Population Based Training of Neural Networks").
+ *
+ * The entry points follow the paper's decomposition of the method (Section 3,
+ * Algorithm 1): `step` (one gradient update of every member under its own
+ * hyperparameters, Eq. 2), `eval` (the score of every member, Eq. 1), `ready`
+ * (stays with the caller: a test on the step count), and `exploit` + `explore`
+ * (truncation selection and perturb, Section 4.1.1), executed for the whole
+ * population in lock-step as in the partially synchronous scheme of
+ * Appendix A.1.  The population store (theta, h, p, t) of Algorithm 1 lives
+ * in device memory for the whole run.
+ *
+ * Conventions
+ *   memory    Every pointer named d_* is DEVICE memory, h_* is HOST memory.
+ *             The caller allocates and owns all device memory; the library
+ *             owns only the host-side handle.  pbt_step, pbt_eval and
+ *             pbt_exploit_explore allocate nothing and never synchronise:
+ *             they enqueue kernels on `hip_stream` (a hipStream_t passed as
+ *             void*, NULL = the null stream) and return.
+ *   errors    Every call returns a pbt_status; 0 is success.  Arguments are
+ *             validated before anything is launched.  pbt_last_error()
+ *             returns a human-readable description of the most recent failure.
+ *   determinism  All results are a pure function of (state, inputs, step or
+ *             round index, seed): no atomics, fixed reduction orders.
+ *   layout    A member's parameters are one flat vector: for every dense
+ *             layer l the matrix W_l[fan_in][fan_out] (row-major) followed by
+ *             the bias b_l[fan_out]; each of the two starts at a multiple of
+ *             64 elements; the per-member stride is a multiple of 256 elements.
+ *             Padding elements are zero and stay zero.  pbt_query_sizes()
+ *             reports the offsets.  Population arrays are member-major:
+ *             X[P][stride].
+ *   random numbers  Philox4x32-10, key = (seed low word, seed high word),
+ *             counter = (step or round index, member, domain tag, element):
+ *             domain 1 = mini-batch row -> data-set row floor(x*n_train/2^32);
+ *             domain 2 = donor -> position floor(x*n_trunc/2^32) in the top set;
+ *             domain 3 = explore, element = hyperparameter k, bit 0 of word 0:
+ *             0 -> perturb_lo, 1 -> perturb_hi.
+ */
+#ifndef PBT_H
+#define PBT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PBT_MAX_DIMS 16
+#define PBT_MAX_HYPER 8
+#define PBT_MAX_P 1024
+
+typedef struct pbt_handle pbt_handle; /* opaque; host memory owned by the library */
+
+typedef enum {
+  PBT_OK = 0,
+  PBT_EINVAL = -1,       /* bad argument or inconsistent configuration */
+  PBT_ENOMEM = -2,       /* a caller-provided buffer is too small */
+  PBT_EDEVICE = -3,      /* a HIP call or kernel launch failed */
+  PBT_ESTATE = -4,       /* call not valid in the handle's current state */
+  PBT_EUNSUPPORTED = -5  /* valid request that this build has no kernel for */
+} pbt_status;
+
+enum { PBT_WL_CLASSIFIER = 1 };                       /* workload families */
+enum { PBT_ACT_NONE = 0, PBT_ACT_RELU = 1, PBT_ACT_GELU = 2, PBT_ACT_LEAKY_RELU = 3, PBT_ACT_TANH = 4 };
+enum { PBT_OPT_SGD_MOMENTUM = 0, PBT_OPT_ADAM = 1, PBT_OPT_RMSPROP = 2 };
+enum { PBT_DTYPE_FP32 = 0, PBT_DTYPE_BF16 = 1 };      /* BF16 = bf16 operands, fp32 accumulate, fp32 master weights */
+enum { PBT_ROLE_LR = 0, PBT_ROLE_BETA1 = 1, PBT_ROLE_WD = 2 }; /* meaning of a hyperparameter column */
+
+/* Arrays of the population store that pbt_get_state / pbt_set_state address. */
+enum {
+  PBT_ARR_W32 = 0,    /* float  [P][stride]  master weights theta                     */
+  PBT_ARR_OPT0 = 1,   /* float  [P][stride]  momentum / Adam m / RMSProp mean square  */
+  PBT_ARR_OPT1 = 2,   /* float  [P][stride]  Adam v (Adam only)                       */
+  PBT_ARR_W16 = 3,    /* bf16   [P][stride]  shadow of theta (BF16 only)              */
+  PBT_ARR_GRAD = 4,   /* float  [P][stride]  gradient of the last step (scratch)      */
+  PBT_ARR_HYPER = 5,  /* float  [P][n_hyper] hyperparameters h                        */
+  PBT_ARR_SCORE = 6,  /* float  [P]          p, written by pbt_eval                   */
+  PBT_ARR_LOSS = 7,   /* float  [P]          training loss of the last step           */
+  PBT_ARR_T = 8,      /* int32  [P]          optimiser updates applied (travels with theta) */
+  PBT_ARR_ORDER = 9,  /* int32  [P]          members from best to worst, last exploit */
+  PBT_ARR_DONOR = 10, /* int32  [P]          donor of the last exploit, -1 = kept     */
+  PBT_ARR_PARENT = 11,/* int32  [P]          member last copied from (initially self) */
+  PBT_ARR_COUNT = 12
+};
+
+typedef struct {
+  int32_t workload;                 /* PBT_WL_* */
+  int32_t P;                        /* population size, 1..PBT_MAX_P */
+  int32_t batch;                    /* rows per member per step */
+  int32_t n_layers;                 /* dense layers; dims[0..n_layers] are the widths */
+  int32_t dims[PBT_MAX_DIMS];
+  int32_t act;                      /* hidden activation, PBT_ACT_* (the output layer is linear) */
+  int32_t optimizer;                /* PBT_OPT_* */
+  int32_t compute_dtype;            /* PBT_DTYPE_* */
+  int32_t n_hyper;                  /* columns of h, 1..PBT_MAX_HYPER */
+  int32_t hyper_role[PBT_MAX_HYPER];/* PBT_ROLE_* of each column */
+  float hyper_max[PBT_MAX_HYPER];   /* upper clamp applied after explore; INFINITY = none */
+  int32_t n_trunc;                  /* size of top and of bottom set; 0 disables exploit; 2*n_trunc <= P */
+  float perturb_lo, perturb_hi;     /* explore factors, 0.8f and 1.2f in the paper's RL and translation runs */
+  float opt_const[4];               /* SGD: {momentum}.  Adam: {beta1, beta2, eps, weight decay} (beta1 / decay are
+                                       defaults for when no column has that role).  RMSProp: {rho, eps}. */
+  int32_t n_train, n_eval;          /* rows of the training and of the held-out set */
+  int32_t eval_chunk;               /* rows of the held-out set scored per pass (bounds scratch); 0 = library picks */
+  uint64_t seed;                    /* Philox key */
+} pbt_config;
+
+/* Offsets (in elements) inside one member's flat parameter vector. */
+typedef struct {
+  int64_t stride;                   /* elements per member */
+  int64_t n_params;                 /* elements that are parameters (rest is padding) */
+  int64_t w_off[PBT_MAX_DIMS];      /* start of W_l */
+  int64_t b_off[PBT_MAX_DIMS];      /* start of b_l */
+} pbt_layout;
+
+/* Sizes of the two device buffers pbt_init needs, and the parameter layout.
+ * Any output pointer may be NULL.  Host-only; touches no device. */
+pbt_status pbt_query_sizes(const pbt_config* cfg, size_t* state_bytes, size_t* scratch_bytes, pbt_layout* layout);
+
+/* Algorithm 1, initial population.  Carves the population store out of
+ * d_state (>= state_bytes, 256-byte aligned) and working buffers out of
+ * d_scratch, zero-fills the store with kernels on hip_stream, sets t = 0,
+ * parent[i] = i, score = -inf.  Weights and hyperparameters are then uploaded
+ * with pbt_set_state.  *out is a new handle (free with pbt_destroy); on
+ * failure *out is NULL.  The two buffers must outlive the handle. */
+pbt_status pbt_init(const pbt_config* cfg, void* d_state, size_t state_bytes, void* d_scratch, size_t scratch_bytes,
+                    void* hip_stream, pbt_handle** out);
+
+/* Section 3, Eq. 2: theta_i <- step(theta_i | h_i) for every member i, n_steps
+ * times (step indices step_index .. step_index + n_steps - 1).  One step:
+ * draw the member's mini-batch rows (Philox domain 1), forward, loss,
+ * backward, optimiser update with lr / beta1 / weight decay read from h_i on
+ * the device, t_i += 1.  Writes loss[P] (mean mini-batch loss before the last
+ * update).  d_inputs for PBT_WL_CLASSIFIER: {train_x float[n_train][dims[0]],
+ * train_y int32[n_train]}, device pointers in a HOST array of n_inputs = 2. */
+pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, int64_t step_index, int32_t n_steps,
+                    void* hip_stream);
+
+/* Section 3, Eq. 1: p_i <- eval(theta_i) for every member; writes score[P].
+ * PBT_WL_CLASSIFIER: minus the mean cross-entropy over the held-out set,
+ * d_inputs = {eval_x float[n_eval][dims[0]], eval_y int32[n_eval]}. */
+pbt_status pbt_eval(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, void* hip_stream);
+
+/* Section 4.1.1, Exploit (b) + Explore (a), for the whole population at once
+ * (Appendix A.1).  Ranks score[P] (descending; ties: lower index first; -inf
+ * then NaN last); every member of the bottom n_trunc draws a donor from the
+ * top n_trunc (Philox domain 2) and receives a byte copy of the donor's
+ * weights, optimiser state, bf16 shadow, update count and score; its
+ * hyperparameters become the donor's times perturb_lo or perturb_hi per
+ * column (Philox domain 3; one IEEE float multiply, then min with hyper_max).
+ * All other members are left untouched.  d_scores_override (float[P], device)
+ * replaces score[P] first when not NULL.  Writes order[P], donor[P], parent. */
+pbt_status pbt_exploit_explore(pbt_handle* h, int64_t round_index, const float* d_scores_override, void* hip_stream);
+
+/* Copies one array of the population store (PBT_ARR_*) to host memory.
+ * member = -1: the whole array, else that member's row.  Synchronises
+ * hip_stream.  dst_bytes must equal the size of what is copied. */
+pbt_status pbt_get_state(pbt_handle* h, int32_t which, int32_t member, void* h_dst, size_t dst_bytes, void* hip_stream);
+
+/* Inverse of pbt_get_state (used to upload an initial population or to resume
+ * from a dump).  Writing PBT_ARR_W32 with BF16 compute also refreshes the bf16
+ * shadow.  Synchronises hip_stream. */
+pbt_status pbt_set_state(pbt_handle* h, int32_t which, int32_t member, const void* h_src, size_t src_bytes,
+                         void* hip_stream);
+
+/* Device address and size in bytes of one array of the store (no copy, no
+ * sync), for callers that read results on the device. */
+pbt_status pbt_state_ptr(pbt_handle* h, int32_t which, void** d_ptr, size_t* bytes);
+
+/* Frees the handle (not the device buffers).  NULL is allowed. */
+pbt_status pbt_destroy(pbt_handle* h);
+
+/* Message for the most recent failure on this handle; with h = NULL, of the
+ * most recent failed call that had no handle (per thread).  Never NULL; owned
+ * by the library; valid until the next failing call. */
+const char* pbt_last_error(const pbt_handle* h);
+
+/* The population-batched GEMM used for every dense contraction of forward and
+ * backward (Section 3, `step`), exposed for measurement and unit tests:
+ *   C_i[M][N] = op(A_i) * op(B_i)   for i = 0..batch-1, bf16 operands, fp32 accumulate.
+ * a_m_contig = 0: A_i is stored [M][K] with K contiguous (lda = row pitch);
+ * 1: A_i is stored [K][M] with M contiguous.  b_k_contig = 0: B_i is stored
+ * [K][N] with N contiguous; 1: B_i is stored [N][K] with K contiguous.
+ * Pitches and batch strides are in elements and must be multiples of 8 (every
+ * row 16-byte aligned, base pointers too); a batch stride of 0 shares the
+ * operand between members.  c_is_bf16 selects bf16 or float output (ldc, stride_c
+ * in elements of that type).  All pointers are device memory; M, N, K, batch > 0. */
+pbt_status pbt_batched_gemm_bf16(const void* d_a, int64_t lda, int64_t stride_a, int32_t a_m_contig, const void* d_b,
+                                 int64_t ldb, int64_t stride_b, int32_t b_k_contig, void* d_c, int64_t ldc,
+                                 int64_t stride_c, int32_t c_is_bf16, int32_t M, int32_t N, int32_t K, int32_t batch,
+                                 void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PBT_H */

@@ -18,7 +18,8 @@ ROLE_LR, ROLE_BETA1, ROLE_WD = 0, 1, 2
 
 class ClassifierSpec:
     def __init__(self, dims, hidden_act, optimizer, batch, roles, seed,
-                 momentum=0.9, beta1=0.9, beta2=0.999, eps=1e-8, wd=0.0, rho=0.99, rms_eps=1e-5):
+                 momentum=0.9, beta1=0.9, beta2=0.999, eps=1e-8, wd=0.0, rho=0.99, rms_eps=1e-5,
+                 bf16_storage=False):
         self.dims = list(dims)
         self.hidden_act = hidden_act
         self.optimizer = optimizer
@@ -27,6 +28,8 @@ class ClassifierSpec:
         self.seed = seed
         self.momentum, self.beta1, self.beta2, self.eps, self.wd = momentum, beta1, beta2, eps, wd
         self.rho, self.rms_eps = rho, rms_eps
+        # mixed precision: contraction operands and stored hidden tensors rounded to bfloat16
+        self.q = nets.round_bf16 if bf16_storage else nets.identity
 
 
 def batch_rows(seed, s, i, batch, n_train):
@@ -76,11 +79,11 @@ def step(spec, member, i, s, train_x, train_y):
     """One `step`.  Returns the mini-batch loss (before the update)."""
     rows = batch_rows(spec.seed, s, i, spec.batch, len(train_y))
     loss, grads = nets.classifier_loss_and_grads(params_of(member), train_x[rows], train_y[rows],
-                                                 spec.hidden_act)
+                                                 spec.hidden_act, spec.q)
     apply_optimizer(spec, member, [a for g in grads for a in g])
     return loss
 
 
 def evaluate(spec, member, eval_x, eval_y):
     """`eval`: negative mean cross-entropy on the held-out set."""
-    return -nets.classifier_eval_loss(params_of(member), eval_x, eval_y, spec.hidden_act)
+    return -nets.classifier_eval_loss(params_of(member), eval_x, eval_y, spec.hidden_act, spec.q)

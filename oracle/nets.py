@@ -44,21 +44,49 @@ def act_grad(z, kind):
     raise ValueError(kind)
 
 
-def mlp_forward(params, x, hidden_act, out_act=ACT_NONE):
-    """Returns (output, cache).  cache = (inputs to each layer, pre-activations)."""
-    a = np.asarray(x, dtype=np.float64)
+def round_bf16(x):
+    """Nearest bfloat16 value (8 significant bits), ties to even, returned as float64.
+    bfloat16 keeps 7 of float64's 52 stored mantissa bits, so the low 45 bits are
+    rounded away.  (Below 2**-126, where bfloat16 goes subnormal, this keeps more
+    precision than the real format; nothing here lives there.)"""
+    u = np.ascontiguousarray(x, dtype=np.float64).view(np.uint64)
+    lsb = (u >> np.uint64(45)) & np.uint64(1)
+    u = u + np.uint64((1 << 44) - 1) + lsb
+    u = u & ~np.uint64((1 << 45) - 1)
+    return u.view(np.float64)
+
+
+def identity(x):
+    return x
+
+
+def mlp_forward(params, x, hidden_act, out_act=ACT_NONE, q=identity):
+    """Returns (output, cache).  cache = (inputs to each layer, pre-activations).
+
+    q is the storage rounding of mixed-precision training (identity for full
+    precision, round_bf16 for "bf16 compute with fp32 master weights"): the two
+    operands of every dense contraction -- layer inputs and weights -- and every
+    hidden tensor kept for the backward pass are rounded by q; biases, the
+    output layer's result and all sums are not."""
+    a = q(np.asarray(x, dtype=np.float64))
     ins, zs = [], []
     L = len(params)
     for l, (W, b) in enumerate(params):
         ins.append(a)
-        z = a @ W + b
-        zs.append(z)
-        a = act(z, hidden_act if l < L - 1 else out_act)
+        z = a @ q(W) + b
+        if l < L - 1:
+            zs.append(q(z))
+            a = q(act(z, hidden_act))
+        else:
+            zs.append(z)
+            a = act(z, out_act)
     return a, (ins, zs)
 
 
-def mlp_backward(params, cache, d_out, hidden_act, out_act=ACT_NONE):
-    """Given dLoss/d(output), returns ([(dW, db), ...], dLoss/d(input))."""
+def mlp_backward(params, cache, d_out, hidden_act, out_act=ACT_NONE, q=identity):
+    """Given dLoss/d(output), returns ([(dW, db), ...], dLoss/d(input)).
+    With a storage rounding q, the gradient with respect to every hidden
+    pre-activation is rounded before it enters the next contractions."""
     ins, zs = cache
     L = len(params)
     grads = [None] * L
@@ -66,8 +94,10 @@ def mlp_backward(params, cache, d_out, hidden_act, out_act=ACT_NONE):
     for l in range(L - 1, -1, -1):
         W, _ = params[l]
         dz = da * act_grad(zs[l], hidden_act if l < L - 1 else out_act)
+        if l < L - 1:
+            dz = q(dz)
         grads[l] = (ins[l].T @ dz, dz.sum(axis=0))
-        da = dz @ W.T
+        da = dz @ q(W).T
     return grads, da
 
 
@@ -90,15 +120,15 @@ def softmax_xent(logits, labels, smoothing=0.0):
     return loss, dlogits
 
 
-def classifier_loss_and_grads(params, x, labels, hidden_act):
+def classifier_loss_and_grads(params, x, labels, hidden_act, q=identity):
     """Training objective of the classifier workloads: mean softmax cross-entropy."""
-    logits, cache = mlp_forward(params, x, hidden_act)
+    logits, cache = mlp_forward(params, x, hidden_act, q=q)
     loss, dlogits = softmax_xent(logits, labels)
-    grads, _ = mlp_backward(params, cache, dlogits, hidden_act)
+    grads, _ = mlp_backward(params, cache, dlogits, hidden_act, q=q)
     return loss, grads
 
 
-def classifier_eval_loss(params, x, labels, hidden_act):
-    logits, _ = mlp_forward(params, x, hidden_act)
+def classifier_eval_loss(params, x, labels, hidden_act, q=identity):
+    logits, _ = mlp_forward(params, x, hidden_act, q=q)
     loss, _ = softmax_xent(logits, labels)
     return loss

@@ -1,0 +1,232 @@
+"""ctypes binding of the C-ABI library `libpbt.so` (declared in include/pbt.h).
+
+Argument marshalling only: every step of the population pass runs in the
+library's HIP kernels.  PyTorch supplies device memory (`torch.empty` on
+`cuda`) and the current HIP stream.  If the library has not been built the
+import of a symbol fails loudly; there is no fallback path.
+"""
+import ctypes as C
+import math
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpbt.so")
+
+PBT_MAX_DIMS, PBT_MAX_HYPER = 16, 8
+(ARR_W32, ARR_OPT0, ARR_OPT1, ARR_W16, ARR_GRAD, ARR_HYPER, ARR_SCORE, ARR_LOSS, ARR_T, ARR_ORDER, ARR_DONOR,
+ ARR_PARENT) = range(12)
+_ARR_DTYPE = {ARR_W32: np.float32, ARR_OPT0: np.float32, ARR_OPT1: np.float32, ARR_W16: np.uint16,
+              ARR_GRAD: np.float32, ARR_HYPER: np.float32, ARR_SCORE: np.float32, ARR_LOSS: np.float32,
+              ARR_T: np.int32, ARR_ORDER: np.int32, ARR_DONOR: np.int32, ARR_PARENT: np.int32}
+
+EXPORTS = ["pbt_query_sizes", "pbt_init", "pbt_step", "pbt_eval", "pbt_exploit_explore", "pbt_get_state",
+           "pbt_set_state", "pbt_state_ptr", "pbt_destroy", "pbt_last_error", "pbt_batched_gemm_bf16"]
+
+
+class PbtConfig(C.Structure):
+    _fields_ = [("workload", C.c_int32), ("P", C.c_int32), ("batch", C.c_int32), ("n_layers", C.c_int32),
+                ("dims", C.c_int32 * PBT_MAX_DIMS), ("act", C.c_int32), ("optimizer", C.c_int32),
+                ("compute_dtype", C.c_int32), ("n_hyper", C.c_int32), ("hyper_role", C.c_int32 * PBT_MAX_HYPER),
+                ("hyper_max", C.c_float * PBT_MAX_HYPER), ("n_trunc", C.c_int32), ("perturb_lo", C.c_float),
+                ("perturb_hi", C.c_float), ("opt_const", C.c_float * 4), ("n_train", C.c_int32),
+                ("n_eval", C.c_int32), ("eval_chunk", C.c_int32), ("seed", C.c_uint64)]
+
+
+class PbtLayout(C.Structure):
+    _fields_ = [("stride", C.c_int64), ("n_params", C.c_int64), ("w_off", C.c_int64 * PBT_MAX_DIMS),
+                ("b_off", C.c_int64 * PBT_MAX_DIMS)]
+
+
+class PbtError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("pbt status %d: %s" % (status, message))
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """Opens libpbt.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s is missing: build it with `python -m paper_1711_09846_amd.build`" % LIB_PATH)
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+        L.pbt_query_sizes.argtypes = [C.POINTER(PbtConfig), C.POINTER(sz), C.POINTER(sz), C.POINTER(PbtLayout)]
+        L.pbt_init.argtypes = [C.POINTER(PbtConfig), vp, sz, vp, sz, vp, C.POINTER(vp)]
+        L.pbt_step.argtypes = [vp, C.POINTER(vp), i32, i64, i32, vp]
+        L.pbt_eval.argtypes = [vp, C.POINTER(vp), i32, vp]
+        L.pbt_exploit_explore.argtypes = [vp, i64, vp, vp]
+        L.pbt_get_state.argtypes = [vp, i32, i32, vp, sz, vp]
+        L.pbt_set_state.argtypes = [vp, i32, i32, vp, sz, vp]
+        L.pbt_state_ptr.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(sz)]
+        L.pbt_destroy.argtypes = [vp]
+        L.pbt_last_error.argtypes = [vp]
+        L.pbt_last_error.restype = C.c_char_p
+        L.pbt_batched_gemm_bf16.argtypes = [vp, i64, i64, i32, vp, i64, i64, i32, vp, i64, i64, i32, i32, i32, i32, i32, vp]
+        for name in EXPORTS:
+            if name != "pbt_last_error":
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def make_config(wl, seed, P=None, n_trunc=None, eval_chunk=0):
+    """PbtConfig from a workloads.Workload description."""
+    c = PbtConfig()
+    c.workload = wl.kind
+    c.P = wl.P if P is None else P
+    c.batch = wl.batch
+    c.n_layers = len(wl.dims) - 1
+    for k, d in enumerate(wl.dims):
+        c.dims[k] = d
+    c.act, c.optimizer, c.compute_dtype = wl.act, wl.optimizer, wl.dtype
+    c.n_hyper = len(wl.roles)
+    for k, r in enumerate(wl.roles):
+        c.hyper_role[k] = r
+        c.hyper_max[k] = wl.h_max[k]
+    c.n_trunc = wl.n_trunc if n_trunc is None else n_trunc
+    c.perturb_lo, c.perturb_hi = wl.perturb
+    oc = wl.opt_const
+    if wl.optimizer == 0:
+        vals = [oc.get("momentum", 0.9), 0, 0, 0]
+    elif wl.optimizer == 1:
+        vals = [oc.get("beta1", 0.9), oc.get("beta2", 0.999), oc.get("eps", 1e-8), oc.get("wd", 0.0)]
+    else:
+        vals = [oc.get("rho", 0.99), oc.get("eps", 1e-5), 0, 0]
+    for k, v in enumerate(vals):
+        c.opt_const[k] = v
+    c.n_train, c.n_eval, c.eval_chunk = wl.n_train, wl.n_eval, eval_chunk
+    c.seed = seed
+    return c
+
+
+def query_sizes(cfg):
+    st, sc, lay = C.c_size_t(), C.c_size_t(), PbtLayout()
+    rc = lib().pbt_query_sizes(C.byref(cfg), C.byref(st), C.byref(sc), C.byref(lay))
+    if rc != 0:
+        raise PbtError(rc, lib().pbt_last_error(None).decode())
+    return st.value, sc.value, lay
+
+
+def pack_params(lay, layers):
+    """[(W[fan_in][fan_out], b[fan_out]), ...] -> flat float32 vector of one member (padding = 0)."""
+    flat = np.zeros(lay.stride, dtype=np.float32)
+    for l, (W, b) in enumerate(layers):
+        flat[lay.w_off[l]:lay.w_off[l] + W.size] = np.asarray(W, dtype=np.float32).ravel()
+        flat[lay.b_off[l]:lay.b_off[l] + b.size] = np.asarray(b, dtype=np.float32).ravel()
+    return flat
+
+
+def unpack_params(lay, dims, flat):
+    out = []
+    for l, (fi, fo) in enumerate(zip(dims[:-1], dims[1:])):
+        W = np.array(flat[lay.w_off[l]:lay.w_off[l] + fi * fo]).reshape(fi, fo)
+        b = np.array(flat[lay.b_off[l]:lay.b_off[l] + fo])
+        out.append((W, b))
+    return out
+
+
+class Population:
+    """Owns the device buffers (through torch) and a library handle."""
+
+    def __init__(self, cfg, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        state_bytes, scratch_bytes, self.layout = query_sizes(cfg)
+        self.state = torch.empty(state_bytes, dtype=torch.uint8, device=self.device)
+        self.scratch = torch.empty(scratch_bytes, dtype=torch.uint8, device=self.device)
+        self._h = C.c_void_p()
+        with torch.cuda.device(self.device):
+            rc = lib().pbt_init(C.byref(cfg), self.state.data_ptr(), state_bytes, self.scratch.data_ptr(),
+                                scratch_bytes, self._stream(), C.byref(self._h))
+        if rc != 0:
+            raise PbtError(rc, lib().pbt_last_error(None).decode())
+        self.dims = [cfg.dims[k] for k in range(cfg.n_layers + 1)]
+
+    def _stream(self):
+        return C.c_void_p(self.torch.cuda.current_stream(self.device).cuda_stream)
+
+    def _check(self, rc):
+        if rc != 0:
+            raise PbtError(rc, lib().pbt_last_error(self._h).decode())
+
+    @staticmethod
+    def _ptrs(tensors):
+        arr = (C.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+        return arr
+
+    def step(self, inputs, step_index, n_steps=1):
+        self._check(lib().pbt_step(self._h, self._ptrs(inputs), len(inputs), step_index, n_steps, self._stream()))
+
+    def eval(self, inputs):
+        self._check(lib().pbt_eval(self._h, self._ptrs(inputs), len(inputs), self._stream()))
+
+    def exploit_explore(self, round_index, scores_override=None):
+        p = None if scores_override is None else C.c_void_p(scores_override.data_ptr())
+        self._check(lib().pbt_exploit_explore(self._h, round_index, p, self._stream()))
+
+    def _shape(self, which):
+        P = self.cfg.P
+        if which in (ARR_W32, ARR_OPT0, ARR_OPT1, ARR_W16, ARR_GRAD):
+            return (P, self.layout.stride)
+        if which == ARR_HYPER:
+            return (P, self.cfg.n_hyper)
+        return (P,)
+
+    def get(self, which, member=-1):
+        shape = self._shape(which)
+        if member >= 0:
+            shape = shape[1:] if len(shape) > 1 else (1,)
+        out = np.empty(shape, dtype=_ARR_DTYPE[which])
+        self._check(lib().pbt_get_state(self._h, which, member, out.ctypes.data, out.nbytes, self._stream()))
+        return out
+
+    def set(self, which, values, member=-1):
+        a = np.ascontiguousarray(values, dtype=_ARR_DTYPE[which])
+        self._check(lib().pbt_set_state(self._h, which, member, a.ctypes.data, a.nbytes, self._stream()))
+
+    def device_view(self, which):
+        """Zero-copy torch view of one array of the store."""
+        ptr, nbytes = C.c_void_p(), C.c_size_t()
+        self._check(lib().pbt_state_ptr(self._h, which, C.byref(ptr), C.byref(nbytes)))
+        base = self.state if self.state.data_ptr() <= ptr.value < self.state.data_ptr() + self.state.numel() else self.scratch
+        off = ptr.value - base.data_ptr()
+        tdt = {np.float32: self.torch.float32, np.int32: self.torch.int32, np.uint16: self.torch.int16}[_ARR_DTYPE[which]]
+        return base[off:off + nbytes.value].view(tdt).view(self._shape(which))
+
+    def set_members(self, layers_per_member, H):
+        """Uploads initial weights ([(W, b), ...] per member) and hyperparameters [P][n_h]."""
+        flat = np.stack([pack_params(self.layout, m) for m in layers_per_member])
+        self.set(ARR_W32, flat)
+        self.set(ARR_HYPER, np.asarray(H, dtype=np.float32))
+
+    def member_params(self, member, which=ARR_W32):
+        return unpack_params(self.layout, self.dims, self.get(which, member))
+
+    def close(self):
+        if self._h:
+            lib().pbt_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def batched_gemm_bf16(a, b, c, M, N, K, batch, lda, sa, a_m_contig, ldb, sb, b_k_contig, ldc, sc):
+    """c (torch float32 or bfloat16), a, b (torch bfloat16) on the device."""
+    import torch
+    rc = lib().pbt_batched_gemm_bf16(a.data_ptr(), lda, sa, int(a_m_contig), b.data_ptr(), ldb, sb, int(b_k_contig),
+                                     c.data_ptr(), ldc, sc, int(c.dtype == torch.bfloat16), M, N, K, batch,
+                                     C.c_void_p(torch.cuda.current_stream(a.device).cuda_stream))
+    if rc != 0:
+        raise PbtError(rc, lib().pbt_last_error(None).decode())

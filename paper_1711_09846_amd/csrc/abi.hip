@@ -1,0 +1,522 @@
+// C ABI of the population step: configuration checks, carving of the caller's device buffers,
+// and the kernel sequences behind pbt_step / pbt_eval / pbt_exploit_explore.
+#include "../../include/pbt.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "internal.h"
+
+using namespace pbt;
+
+namespace {
+
+thread_local std::string g_last_error = "";
+
+constexpr int64_t SEG_ALIGN = 64;      // elements: start of every W_l and b_l
+constexpr int64_t STRIDE_ALIGN = 256;  // elements: per-member stride
+constexpr size_t BUF_ALIGN = 256;      // bytes: every carved array
+
+int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+struct Carver {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    const size_t o = off;
+    off += (bytes + BUF_ALIGN - 1) / BUF_ALIGN * BUF_ALIGN;
+    return o;
+  }
+};
+
+struct Plan {
+  pbt_layout lay;
+  // offsets in bytes inside d_state
+  size_t o_w32, o_opt0, o_opt1, o_w16, o_hyper, o_score, o_loss, o_t, o_order, o_donor, o_parent, o_recip;
+  size_t state_bytes;
+  // offsets in bytes inside d_scratch
+  size_t o_grad, o_y, o_dlogits, o_rowloss, o_x32;
+  size_t o_act[PBT_MAX_DIMS], o_z[PBT_MAX_DIMS], o_dz[PBT_MAX_DIMS];
+  size_t o_evalx, o_evala[2], o_evalrow;
+  size_t scratch_bytes;
+  int eval_chunk;
+  bool fused_small;  // fp32: the whole step runs in one LDS-resident kernel
+  int col_lr, col_beta1, col_wd;
+};
+
+}  // namespace
+
+struct pbt_handle {
+  pbt_config cfg;
+  Plan plan;
+  char* state;
+  char* scratch;
+  std::string err;
+  template <class T> T* st(size_t off) const { return reinterpret_cast<T*>(state + off); }
+  template <class T> T* sc(size_t off) const { return reinterpret_cast<T*>(scratch + off); }
+};
+
+namespace {
+
+pbt_status fail(pbt_handle* h, pbt_status code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (h) h->err = buf;
+  g_last_error = buf;
+  return code;
+}
+
+#define PBT_HIP(h, call)                                                                        \
+  do {                                                                                          \
+    hipError_t e_ = (call);                                                                     \
+    if (e_ != hipSuccess) return fail(h, PBT_EDEVICE, "%s failed: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+pbt_status check_config(const pbt_config* c, Plan* pl) {
+  if (!c) return fail(nullptr, PBT_EINVAL, "config is NULL");
+  if (c->workload != PBT_WL_CLASSIFIER) return fail(nullptr, PBT_EUNSUPPORTED, "workload %d not built", c->workload);
+  if (c->P < 1 || c->P > PBT_MAX_P) return fail(nullptr, PBT_EINVAL, "P = %d outside 1..%d", c->P, PBT_MAX_P);
+  if (c->batch < 1) return fail(nullptr, PBT_EINVAL, "batch must be positive");
+  if (c->n_layers < 1 || c->n_layers >= PBT_MAX_DIMS) return fail(nullptr, PBT_EINVAL, "n_layers = %d outside 1..%d", c->n_layers, PBT_MAX_DIMS - 1);
+  for (int l = 0; l <= c->n_layers; ++l)
+    if (c->dims[l] < 1) return fail(nullptr, PBT_EINVAL, "dims[%d] must be positive", l);
+  if (c->act < PBT_ACT_NONE || c->act > PBT_ACT_TANH) return fail(nullptr, PBT_EINVAL, "unknown activation %d", c->act);
+  if (c->optimizer < PBT_OPT_SGD_MOMENTUM || c->optimizer > PBT_OPT_RMSPROP) return fail(nullptr, PBT_EINVAL, "unknown optimizer %d", c->optimizer);
+  if (c->compute_dtype != PBT_DTYPE_FP32 && c->compute_dtype != PBT_DTYPE_BF16) return fail(nullptr, PBT_EINVAL, "unknown compute_dtype %d", c->compute_dtype);
+  if (c->n_hyper < 1 || c->n_hyper > PBT_MAX_HYPER) return fail(nullptr, PBT_EINVAL, "n_hyper = %d outside 1..%d", c->n_hyper, PBT_MAX_HYPER);
+  if (c->n_trunc < 0 || 2 * (int64_t)c->n_trunc > c->P) return fail(nullptr, PBT_EINVAL, "need 0 <= 2*n_trunc <= P (top and bottom sets must not overlap)");
+  if (c->n_train < 1 || c->n_eval < 1) return fail(nullptr, PBT_EINVAL, "n_train and n_eval must be positive");
+  if (c->dims[c->n_layers] > 32) return fail(nullptr, PBT_EUNSUPPORTED, "more than 32 classes");
+  pl->col_lr = pl->col_beta1 = pl->col_wd = -1;
+  for (int k = 0; k < c->n_hyper; ++k) {
+    if (c->hyper_role[k] == PBT_ROLE_LR) pl->col_lr = k;
+    else if (c->hyper_role[k] == PBT_ROLE_BETA1) pl->col_beta1 = k;
+    else if (c->hyper_role[k] == PBT_ROLE_WD) pl->col_wd = k;
+    else return fail(nullptr, PBT_EINVAL, "unknown hyper_role[%d] = %d", k, c->hyper_role[k]);
+    if (std::isnan(c->hyper_max[k])) return fail(nullptr, PBT_EINVAL, "hyper_max[%d] is NaN", k);
+  }
+  if (pl->col_lr < 0) return fail(nullptr, PBT_EINVAL, "no hyperparameter column has the learning-rate role");
+  if (c->optimizer != PBT_OPT_ADAM && (pl->col_beta1 >= 0 || pl->col_wd >= 0))
+    return fail(nullptr, PBT_EINVAL, "beta1 / weight-decay columns need the Adam optimizer");
+  return PBT_OK;
+}
+
+pbt_status make_plan(const pbt_config* c, Plan* pl) {
+  pbt_status st = check_config(c, pl);
+  if (st != PBT_OK) return st;
+  const int L = c->n_layers;
+  const int64_t P = c->P, B = c->batch;
+  // parameter layout
+  pbt_layout& lay = pl->lay;
+  std::memset(&lay, 0, sizeof lay);
+  int64_t off = 0, n_params = 0;
+  for (int l = 0; l < L; ++l) {
+    lay.w_off[l] = off;
+    off = round_up(off + (int64_t)c->dims[l] * c->dims[l + 1], SEG_ALIGN);
+    lay.b_off[l] = off;
+    off = round_up(off + c->dims[l + 1], SEG_ALIGN);
+    n_params += (int64_t)c->dims[l] * c->dims[l + 1] + c->dims[l + 1];
+  }
+  lay.stride = round_up(off, STRIDE_ALIGN);
+  lay.n_params = n_params;
+  const bool bf16 = c->compute_dtype == PBT_DTYPE_BF16;
+  const bool adam = c->optimizer == PBT_OPT_ADAM;
+
+  Carver s;
+  const size_t pw = (size_t)P * lay.stride;
+  pl->o_w32 = s.take(pw * 4);
+  pl->o_opt0 = s.take(pw * 4);
+  pl->o_opt1 = adam ? s.take(pw * 4) : 0;
+  pl->o_w16 = bf16 ? s.take(pw * 2) : 0;
+  pl->o_hyper = s.take((size_t)P * c->n_hyper * 4);
+  pl->o_score = s.take(P * 4);
+  pl->o_loss = s.take(P * 4);
+  pl->o_t = s.take(P * 4);
+  pl->o_order = s.take(P * 4);
+  pl->o_donor = s.take(P * 4);
+  pl->o_parent = s.take(P * 4);
+  pl->o_recip = s.take(P * 4);
+  pl->state_bytes = s.off;
+
+  Carver w;
+  pl->o_grad = w.take(pw * 4);
+  pl->fused_small = false;
+  pl->eval_chunk = 0;
+  if (!bf16) {
+    FusedSmallArgs fa;
+    std::memset(&fa, 0, sizeof fa);
+    fa.stride = lay.stride; fa.B = (int)B; fa.n_layers = L; fa.optimizer = c->optimizer;
+    for (int l = 0; l <= L; ++l) fa.dims[l] = c->dims[l];
+    if (lay.stride > (1 << 20) || fused_small_plan(fa, false) > FUSED_SMALL_MAX_LDS)
+      return fail(nullptr, PBT_EUNSUPPORTED,
+                  "fp32 compute is built only for networks whose weights, optimiser state and one mini-batch of "
+                  "activations fit the 160 KB LDS of a compute unit; use bf16 compute for larger ones");
+    pl->fused_small = true;
+  } else {
+    for (int l = 0; l < L; ++l) {
+      const bool head = l == L - 1;
+      if (!head && (c->dims[l] % 8 || c->dims[l + 1] % 8))
+        return fail(nullptr, PBT_EUNSUPPORTED, "bf16 hidden layers need widths that are multiples of 8 (layer %d)", l);
+    }
+    if (L >= 2 && c->dims[L - 1] % 8) return fail(nullptr, PBT_EUNSUPPORTED, "last hidden width must be a multiple of 8");
+    pl->o_y = w.take(P * B * 4);
+    pl->o_dlogits = w.take((size_t)P * B * c->dims[L] * 4);
+    pl->o_rowloss = w.take(P * B * 4);
+    for (int l = 0; l < L; ++l) {
+      pl->o_act[l] = w.take((size_t)P * B * c->dims[l] * 2);       // input of layer l
+      if (l < L - 1) {
+        pl->o_z[l] = w.take((size_t)P * B * c->dims[l + 1] * 2);   // pre-activation of layer l
+        pl->o_dz[l] = w.take((size_t)P * B * c->dims[l + 1] * 2);  // gradient w.r.t. it
+      }
+    }
+    // eval: held-out set in bf16 (shared), two ping-pong activation buffers per chunk, per-row losses
+    int64_t maxh = 8;
+    for (int l = 1; l < L; ++l) maxh = c->dims[l] > maxh ? c->dims[l] : maxh;
+    int chunk = c->eval_chunk;
+    if (chunk <= 0) {
+      const int64_t budget = (int64_t)256 << 20;  // bytes per ping-pong buffer
+      chunk = (int)(budget / (P * maxh * 2));
+      if (chunk > c->n_eval) chunk = c->n_eval;
+      if (chunk >= 128) chunk = chunk / 128 * 128;
+      if (chunk < 1) chunk = 1;
+    }
+    if (chunk > c->n_eval) chunk = c->n_eval;
+    pl->eval_chunk = chunk;
+    pl->o_evalx = w.take((size_t)c->n_eval * c->dims[0] * 2);
+    pl->o_evala[0] = w.take((size_t)P * chunk * maxh * 2);
+    pl->o_evala[1] = w.take((size_t)P * chunk * maxh * 2);
+    pl->o_evalrow = w.take((size_t)P * c->n_eval * 4);
+  }
+  pl->scratch_bytes = w.off;
+  return PBT_OK;
+}
+
+struct ArrInfo { size_t off; size_t elem; int64_t cols; bool in_scratch; };
+
+pbt_status arr_info(pbt_handle* h, int which, ArrInfo* ai) {
+  const Plan& p = h->plan;
+  const pbt_config& c = h->cfg;
+  const int64_t S = p.lay.stride;
+  switch (which) {
+    case PBT_ARR_W32: *ai = {p.o_w32, 4, S, false}; return PBT_OK;
+    case PBT_ARR_OPT0: *ai = {p.o_opt0, 4, S, false}; return PBT_OK;
+    case PBT_ARR_OPT1:
+      if (c.optimizer != PBT_OPT_ADAM) return fail(h, PBT_EINVAL, "OPT1 exists only with Adam");
+      *ai = {p.o_opt1, 4, S, false}; return PBT_OK;
+    case PBT_ARR_W16:
+      if (c.compute_dtype != PBT_DTYPE_BF16) return fail(h, PBT_EINVAL, "W16 exists only with bf16 compute");
+      *ai = {p.o_w16, 2, S, false}; return PBT_OK;
+    case PBT_ARR_GRAD: *ai = {p.o_grad, 4, S, true}; return PBT_OK;
+    case PBT_ARR_HYPER: *ai = {p.o_hyper, 4, c.n_hyper, false}; return PBT_OK;
+    case PBT_ARR_SCORE: *ai = {p.o_score, 4, 1, false}; return PBT_OK;
+    case PBT_ARR_LOSS: *ai = {p.o_loss, 4, 1, false}; return PBT_OK;
+    case PBT_ARR_T: *ai = {p.o_t, 4, 1, false}; return PBT_OK;
+    case PBT_ARR_ORDER: *ai = {p.o_order, 4, 1, false}; return PBT_OK;
+    case PBT_ARR_DONOR: *ai = {p.o_donor, 4, 1, false}; return PBT_OK;
+    case PBT_ARR_PARENT: *ai = {p.o_parent, 4, 1, false}; return PBT_OK;
+    default: return fail(h, PBT_EINVAL, "unknown array id %d", which);
+  }
+}
+
+void fill_fused(pbt_handle* h, FusedSmallArgs* fa) {
+  const pbt_config& c = h->cfg;
+  const Plan& p = h->plan;
+  std::memset(fa, 0, sizeof *fa);
+  fa->W32 = h->st<float>(p.o_w32);
+  fa->S0 = h->st<float>(p.o_opt0);
+  fa->S1 = c.optimizer == PBT_OPT_ADAM ? h->st<float>(p.o_opt1) : nullptr;
+  fa->G = h->sc<float>(p.o_grad);
+  fa->H = h->st<float>(p.o_hyper);
+  fa->t = h->st<int32_t>(p.o_t);
+  fa->loss = h->st<float>(p.o_loss);
+  fa->score = h->st<float>(p.o_score);
+  fa->stride = p.lay.stride;
+  fa->P = c.P; fa->B = c.batch; fa->n_layers = c.n_layers;
+  for (int l = 0; l <= c.n_layers; ++l) fa->dims[l] = c.dims[l];
+  for (int l = 0; l < c.n_layers; ++l) { fa->w_off[l] = (int)p.lay.w_off[l]; fa->b_off[l] = (int)p.lay.b_off[l]; }
+  fa->act = c.act; fa->optimizer = c.optimizer; fa->n_hyper = c.n_hyper;
+  fa->col_lr = p.col_lr; fa->col_beta1 = p.col_beta1; fa->col_wd = p.col_wd;
+  fa->c0 = c.opt_const[0]; fa->c1 = c.opt_const[1]; fa->c2 = c.opt_const[2]; fa->c3 = c.opt_const[3];
+  fa->seed = c.seed;
+}
+
+// One population step on the bf16 path: the kernel sequence of forward, loss, backward, update.
+pbt_status step_bf16(pbt_handle* h, const float* train_x, const int32_t* train_y, uint32_t step, hipStream_t s) {
+  const pbt_config& c = h->cfg;
+  const Plan& p = h->plan;
+  const int L = c.n_layers, P = c.P, B = c.batch;
+  const int64_t S = p.lay.stride;
+  float* W32 = h->st<float>(p.o_w32);
+  bf16_t* W16 = h->st<bf16_t>(p.o_w16);
+  float* G = h->sc<float>(p.o_grad);
+  int32_t* Y = h->sc<int32_t>(p.o_y);
+  float* dlogits = h->sc<float>(p.o_dlogits);
+  float* rowloss = h->sc<float>(p.o_rowloss);
+
+  PBT_HIP(h, gather_batch(train_x, train_y, c.n_train, c.dims[0], P, B, step, c.seed, h->sc<bf16_t>(p.o_act[0]), nullptr,
+                          Y, h->st<int32_t>(p.o_t), s));
+  for (int l = 0; l < L - 1; ++l) {
+    GemmOperands o{h->sc<bf16_t>(p.o_act[l]), c.dims[l], (int64_t)B * c.dims[l], false,
+                   W16 + p.lay.w_off[l], c.dims[l + 1], S, false, B, c.dims[l + 1], c.dims[l], P};
+    PBT_HIP(h, gemm_bias_act(o, W32 + p.lay.b_off[l], S, h->sc<bf16_t>(p.o_z[l]), h->sc<bf16_t>(p.o_act[l + 1]),
+                             c.dims[l + 1], (int64_t)B * c.dims[l + 1], c.act, s));
+  }
+  const int Kh = c.dims[L - 1], C = c.dims[L];
+  PBT_HIP(h, head_fwd_loss(h->sc<bf16_t>(p.o_act[L - 1]), (int64_t)B * Kh, W16 + p.lay.w_off[L - 1], S,
+                           W32 + p.lay.b_off[L - 1], S, Y, B, P, B, Kh, C, 1.f / (float)B, dlogits, rowloss, B, s));
+  PBT_HIP(h, row_reduce(rowloss, B, P, B, 1.f / (float)B, h->st<float>(p.o_loss), s));
+  PBT_HIP(h, head_wgrad(h->sc<bf16_t>(p.o_act[L - 1]), (int64_t)B * Kh, dlogits, P, B, Kh, C, G + p.lay.w_off[L - 1],
+                        G + p.lay.b_off[L - 1], S, s));
+  if (L >= 2)
+    PBT_HIP(h, head_dgrad(dlogits, W16 + p.lay.w_off[L - 1], S, h->sc<bf16_t>(p.o_z[L - 2]), h->sc<bf16_t>(p.o_dz[L - 2]),
+                          P, B, Kh, C, c.act, s));
+  for (int l = L - 2; l >= 0; --l) {
+    const int K = c.dims[l], N = c.dims[l + 1];
+    // dW_l[K][N] = X_l^T dZ_l (contraction over the B rows)
+    GemmOperands wg{h->sc<bf16_t>(p.o_act[l]), K, (int64_t)B * K, true, h->sc<bf16_t>(p.o_dz[l]), N, (int64_t)B * N, false,
+                    K, N, B, P};
+    PBT_HIP(h, gemm_store_f32(wg, G + p.lay.w_off[l], N, S, s));
+    PBT_HIP(h, bias_grad(h->sc<bf16_t>(p.o_dz[l]), P, B, N, G + p.lay.b_off[l], S, s));
+    if (l > 0) {
+      // dZ_{l-1}[B][K] = (dZ_l W_l^T) * act'(Z_{l-1})
+      GemmOperands dg{h->sc<bf16_t>(p.o_dz[l]), N, (int64_t)B * N, false, W16 + p.lay.w_off[l], N, S, true, B, K, N, P};
+      PBT_HIP(h, gemm_dgrad_act(dg, h->sc<bf16_t>(p.o_z[l - 1]), h->sc<bf16_t>(p.o_dz[l - 1]), K, (int64_t)B * K, c.act, s));
+    }
+  }
+  OptArgs oa{W32, h->st<float>(p.o_opt0), c.optimizer == PBT_OPT_ADAM ? h->st<float>(p.o_opt1) : nullptr, W16, G,
+             h->st<float>(p.o_hyper), h->st<int32_t>(p.o_t), S, P, c.n_hyper, c.optimizer, p.col_lr, p.col_beta1, p.col_wd,
+             c.opt_const[0], c.opt_const[1], c.opt_const[2], c.opt_const[3]};
+  PBT_HIP(h, optimizer_step(oa, s));
+  return PBT_OK;
+}
+
+pbt_status eval_bf16(pbt_handle* h, const float* eval_x, const int32_t* eval_y, hipStream_t s) {
+  const pbt_config& c = h->cfg;
+  const Plan& p = h->plan;
+  const int L = c.n_layers, P = c.P;
+  const int64_t S = p.lay.stride;
+  float* W32 = h->st<float>(p.o_w32);
+  bf16_t* W16 = h->st<bf16_t>(p.o_w16);
+  bf16_t* ex = h->sc<bf16_t>(p.o_evalx);
+  float* rowloss = h->sc<float>(p.o_evalrow);
+  PBT_HIP(h, f32_to_bf16(eval_x, ex, (int64_t)c.n_eval * c.dims[0], s));
+  for (int r0 = 0; r0 < c.n_eval; r0 += p.eval_chunk) {
+    const int rows = c.n_eval - r0 < p.eval_chunk ? c.n_eval - r0 : p.eval_chunk;
+    const bf16_t* in = ex + (int64_t)r0 * c.dims[0];
+    int64_t in_stride = 0;  // the held-out rows are shared by all members
+    for (int l = 0; l < L - 1; ++l) {
+      bf16_t* out = h->sc<bf16_t>(p.o_evala[l & 1]);
+      GemmOperands o{in, c.dims[l], in_stride, false, W16 + p.lay.w_off[l], c.dims[l + 1], S, false,
+                     rows, c.dims[l + 1], c.dims[l], P};
+      PBT_HIP(h, gemm_bias_act(o, W32 + p.lay.b_off[l], S, nullptr, out, c.dims[l + 1], (int64_t)rows * c.dims[l + 1],
+                               c.act, s));
+      in = out;
+      in_stride = (int64_t)rows * c.dims[l + 1];
+    }
+    PBT_HIP(h, head_fwd_loss(in, in_stride, W16 + p.lay.w_off[L - 1], S, W32 + p.lay.b_off[L - 1], S, eval_y + r0, 0, P,
+                             rows, c.dims[L - 1], c.dims[L], 0.f, nullptr, rowloss + r0, c.n_eval, s));
+  }
+  PBT_HIP(h, row_reduce(rowloss, c.n_eval, P, c.n_eval, -1.f / (float)c.n_eval, h->st<float>(p.o_score), s));
+  return PBT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+pbt_status pbt_query_sizes(const pbt_config* cfg, size_t* state_bytes, size_t* scratch_bytes, pbt_layout* layout) {
+  Plan pl;
+  pbt_status st = make_plan(cfg, &pl);
+  if (st != PBT_OK) return st;
+  if (state_bytes) *state_bytes = pl.state_bytes;
+  if (scratch_bytes) *scratch_bytes = pl.scratch_bytes;
+  if (layout) *layout = pl.lay;
+  return PBT_OK;
+}
+
+pbt_status pbt_init(const pbt_config* cfg, void* d_state, size_t state_bytes, void* d_scratch, size_t scratch_bytes,
+                    void* hip_stream, pbt_handle** out) {
+  if (!out) return fail(nullptr, PBT_EINVAL, "out is NULL");
+  *out = nullptr;
+  Plan pl;
+  pbt_status st = make_plan(cfg, &pl);
+  if (st != PBT_OK) return st;
+  if (!d_state || !d_scratch) return fail(nullptr, PBT_EINVAL, "device buffers must not be NULL");
+  if (((uintptr_t)d_state | (uintptr_t)d_scratch) % BUF_ALIGN) return fail(nullptr, PBT_EINVAL, "device buffers must be 256-byte aligned");
+  if (state_bytes < pl.state_bytes) return fail(nullptr, PBT_ENOMEM, "state buffer: %zu bytes given, %zu needed", state_bytes, pl.state_bytes);
+  if (scratch_bytes < pl.scratch_bytes) return fail(nullptr, PBT_ENOMEM, "scratch buffer: %zu bytes given, %zu needed", scratch_bytes, pl.scratch_bytes);
+  pbt_handle* h = new (std::nothrow) pbt_handle();
+  if (!h) return fail(nullptr, PBT_ENOMEM, "out of host memory");
+  h->cfg = *cfg;
+  h->plan = pl;
+  h->state = static_cast<char*>(d_state);
+  h->scratch = static_cast<char*>(d_scratch);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = fill_u32(h->st<uint32_t>(0), 0u, (int64_t)(pl.state_bytes / 4), s);
+  if (e == hipSuccess) e = fill_u32(h->sc<uint32_t>(pl.o_grad), 0u, (int64_t)cfg->P * pl.lay.stride, s);
+  if (e == hipSuccess) e = fill_u32(h->st<uint32_t>(pl.o_score), 0xff800000u, cfg->P, s);  // -inf
+  if (e == hipSuccess) e = fill_u32(h->st<uint32_t>(pl.o_donor), 0xffffffffu, cfg->P, s);  // -1
+  if (e == hipSuccess) e = iota_i32(h->st<int32_t>(pl.o_parent), cfg->P, s);
+  if (e == hipSuccess) e = iota_i32(h->st<int32_t>(pl.o_order), cfg->P, s);
+  if (e != hipSuccess) {
+    delete h;
+    return fail(nullptr, PBT_EDEVICE, "initialising the population store failed: %s", hipGetErrorString(e));
+  }
+  *out = h;
+  return PBT_OK;
+}
+
+pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, int64_t step_index, int32_t n_steps,
+                    void* hip_stream) {
+  if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  if (!d_inputs || n_inputs != 2 || !d_inputs[0] || !d_inputs[1])
+    return fail(h, PBT_EINVAL, "classifier step needs 2 inputs: train_x, train_y");
+  if (n_steps < 0 || step_index < 0 || step_index + n_steps > 0xffffffffLL) return fail(h, PBT_EINVAL, "step range outside 0..2^32-1");
+  if (n_steps == 0) return PBT_OK;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const float* x = static_cast<const float*>(d_inputs[0]);
+  const int32_t* y = static_cast<const int32_t*>(d_inputs[1]);
+  if (h->plan.fused_small) {
+    FusedSmallArgs fa;
+    fill_fused(h, &fa);
+    fa.x = x; fa.y = y; fa.n_rows = h->cfg.n_train;
+    fa.step0 = (uint32_t)step_index; fa.n_steps = n_steps;
+    fused_small_plan(fa, false);
+    PBT_HIP(h, fused_small_step(fa, s));
+    return PBT_OK;
+  }
+  for (int k = 0; k < n_steps; ++k) {
+    pbt_status st = step_bf16(h, x, y, (uint32_t)(step_index + k), s);
+    if (st != PBT_OK) return st;
+  }
+  return PBT_OK;
+}
+
+pbt_status pbt_eval(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, void* hip_stream) {
+  if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  if (!d_inputs || n_inputs != 2 || !d_inputs[0] || !d_inputs[1])
+    return fail(h, PBT_EINVAL, "classifier eval needs 2 inputs: eval_x, eval_y");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const float* x = static_cast<const float*>(d_inputs[0]);
+  const int32_t* y = static_cast<const int32_t*>(d_inputs[1]);
+  if (h->plan.fused_small) {
+    FusedSmallArgs fa;
+    fill_fused(h, &fa);
+    fa.x = x; fa.y = y; fa.n_rows = h->cfg.n_eval;
+    fused_small_plan(fa, true);
+    PBT_HIP(h, fused_small_eval(fa, s));
+    return PBT_OK;
+  }
+  return eval_bf16(h, x, y, s);
+}
+
+pbt_status pbt_exploit_explore(pbt_handle* h, int64_t round_index, const float* d_scores_override, void* hip_stream) {
+  if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  if (round_index < 0 || round_index > 0xffffffffLL) return fail(h, PBT_EINVAL, "round index outside 0..2^32-1");
+  const pbt_config& c = h->cfg;
+  const Plan& p = h->plan;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  ExploitArgs a;
+  a.score = h->st<float>(p.o_score);
+  a.score_override = d_scores_override;
+  a.H = h->st<float>(p.o_hyper);
+  a.t = h->st<int32_t>(p.o_t);
+  a.order = h->st<int32_t>(p.o_order);
+  a.donor = h->st<int32_t>(p.o_donor);
+  a.parent = h->st<int32_t>(p.o_parent);
+  a.recip = h->st<int32_t>(p.o_recip);
+  a.P = c.P; a.n_trunc = c.n_trunc; a.n_hyper = c.n_hyper;
+  a.f_lo = c.perturb_lo; a.f_hi = c.perturb_hi;
+  for (int k = 0; k < 8; ++k) a.h_max[k] = k < c.n_hyper ? c.hyper_max[k] : INFINITY;
+  a.round = (uint32_t)round_index; a.seed = c.seed;
+  PBT_HIP(h, rank_select_explore(a, s));
+  CopyArrays ca;
+  ca.n = 0;
+  const int64_t S = p.lay.stride;
+  ca.base[ca.n] = h->st<char>(p.o_w32); ca.row_bytes[ca.n++] = S * 4;
+  ca.base[ca.n] = h->st<char>(p.o_opt0); ca.row_bytes[ca.n++] = S * 4;
+  if (c.optimizer == PBT_OPT_ADAM) { ca.base[ca.n] = h->st<char>(p.o_opt1); ca.row_bytes[ca.n++] = S * 4; }
+  if (c.compute_dtype == PBT_DTYPE_BF16) { ca.base[ca.n] = h->st<char>(p.o_w16); ca.row_bytes[ca.n++] = S * 2; }
+  PBT_HIP(h, gather_copy(ca, a.recip, a.donor, c.n_trunc, s));
+  return PBT_OK;
+}
+
+static pbt_status xfer(pbt_handle* h, int32_t which, int32_t member, void* host, size_t bytes, void* hip_stream, bool to_host) {
+  if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  if (!host) return fail(h, PBT_EINVAL, "host pointer is NULL");
+  ArrInfo ai;
+  pbt_status st = arr_info(h, which, &ai);
+  if (st != PBT_OK) return st;
+  if (member < -1 || member >= h->cfg.P) return fail(h, PBT_EINVAL, "member %d outside -1..P-1", member);
+  const size_t row = ai.elem * (size_t)ai.cols;
+  const size_t want = member < 0 ? row * h->cfg.P : row;
+  if (bytes != want) return fail(h, PBT_EINVAL, "buffer is %zu bytes, the selection is %zu", bytes, want);
+  char* dev = (ai.in_scratch ? h->scratch : h->state) + ai.off + (member < 0 ? 0 : row * (size_t)member);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (to_host) {
+    PBT_HIP(h, hipMemcpyAsync(host, dev, want, hipMemcpyDeviceToHost, s));
+  } else {
+    PBT_HIP(h, hipMemcpyAsync(dev, host, want, hipMemcpyHostToDevice, s));
+    if (which == PBT_ARR_W32 && h->cfg.compute_dtype == PBT_DTYPE_BF16) {
+      const size_t eoff = (size_t)(dev - (h->state + h->plan.o_w32)) / 4;
+      PBT_HIP(h, f32_to_bf16(reinterpret_cast<const float*>(dev), h->st<bf16_t>(h->plan.o_w16) + eoff, (int64_t)(want / 4), s));
+    }
+  }
+  PBT_HIP(h, hipStreamSynchronize(s));
+  return PBT_OK;
+}
+
+pbt_status pbt_get_state(pbt_handle* h, int32_t which, int32_t member, void* h_dst, size_t dst_bytes, void* hip_stream) {
+  return xfer(h, which, member, h_dst, dst_bytes, hip_stream, true);
+}
+
+pbt_status pbt_set_state(pbt_handle* h, int32_t which, int32_t member, const void* h_src, size_t src_bytes,
+                         void* hip_stream) {
+  if (which == PBT_ARR_GRAD || which == PBT_ARR_ORDER || which == PBT_ARR_DONOR || which == PBT_ARR_LOSS)
+    return fail(h, PBT_EINVAL, "array %d is an output and cannot be set", which);
+  return xfer(h, which, member, const_cast<void*>(h_src), src_bytes, hip_stream, false);
+}
+
+pbt_status pbt_state_ptr(pbt_handle* h, int32_t which, void** d_ptr, size_t* bytes) {
+  if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  ArrInfo ai;
+  pbt_status st = arr_info(h, which, &ai);
+  if (st != PBT_OK) return st;
+  if (d_ptr) *d_ptr = (ai.in_scratch ? h->scratch : h->state) + ai.off;
+  if (bytes) *bytes = ai.elem * (size_t)ai.cols * h->cfg.P;
+  return PBT_OK;
+}
+
+pbt_status pbt_destroy(pbt_handle* h) {
+  delete h;
+  return PBT_OK;
+}
+
+const char* pbt_last_error(const pbt_handle* h) { return h ? h->err.c_str() : g_last_error.c_str(); }
+
+pbt_status pbt_batched_gemm_bf16(const void* d_a, int64_t lda, int64_t stride_a, int32_t a_m_contig, const void* d_b,
+                                 int64_t ldb, int64_t stride_b, int32_t b_k_contig, void* d_c, int64_t ldc,
+                                 int64_t stride_c, int32_t c_is_bf16, int32_t M, int32_t N, int32_t K, int32_t batch,
+                                 void* hip_stream) {
+  if (!d_a || !d_b || !d_c) return fail(nullptr, PBT_EINVAL, "NULL operand");
+  if (M < 1 || N < 1 || K < 1 || batch < 1) return fail(nullptr, PBT_EINVAL, "M, N, K, batch must be positive");
+  if (lda % 8 || ldb % 8 || stride_a % 8 || stride_b % 8 || ((uintptr_t)d_a | (uintptr_t)d_b) % 16)
+    return fail(nullptr, PBT_EINVAL, "operand pitches / strides must be multiples of 8 elements and bases 16-byte aligned");
+  if (lda < (a_m_contig ? M : K) || ldb < (b_k_contig ? K : N) || ldc < N) return fail(nullptr, PBT_EINVAL, "pitch smaller than the row");
+  GemmOperands o{static_cast<const bf16_t*>(d_a), lda, stride_a, a_m_contig != 0,
+                 static_cast<const bf16_t*>(d_b), ldb, stride_b, b_k_contig != 0, M, N, K, batch};
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = c_is_bf16 ? gemm_store_bf16(o, static_cast<bf16_t*>(d_c), ldc, stride_c, s)
+                           : gemm_store_f32(o, static_cast<float*>(d_c), ldc, stride_c, s);
+  if (e != hipSuccess) return fail(nullptr, PBT_EDEVICE, "GEMM launch failed: %s", hipGetErrorString(e));
+  return PBT_OK;
+}
+
+}  // extern "C"

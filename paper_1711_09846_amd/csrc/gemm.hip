@@ -1,0 +1,27 @@
+// Instantiations of the population-batched bf16 MFMA GEMM for the epilogues the step uses.
+#include "gemm_bf16.h"
+#include "internal.h"
+
+namespace pbt {
+
+template <class E>
+static hipError_t run(const GemmOperands& o, const E& e, hipStream_t s) {
+  return launch_gemm_bf16<E>(o.A, o.lda, o.sa, o.a_m_contig, o.B, o.ldb, o.sb, o.b_k_contig, o.M, o.N, o.K, o.batch, e, s);
+}
+
+hipError_t gemm_store_f32(const GemmOperands& o, float* C, int64_t ldc, int64_t sc, hipStream_t s) {
+  return run(o, EpiStoreF32{C, ldc, sc}, s);
+}
+hipError_t gemm_store_bf16(const GemmOperands& o, bf16_t* C, int64_t ldc, int64_t sc, hipStream_t s) {
+  return run(o, EpiStoreBF16{C, ldc, sc}, s);
+}
+hipError_t gemm_bias_act(const GemmOperands& o, const float* bias, int64_t sbias, bf16_t* Z, bf16_t* Aout, int64_t ld,
+                         int64_t so, int act, hipStream_t s) {
+  return run(o, EpiBiasAct{bias, sbias, Z, Aout, ld, so, act}, s);
+}
+hipError_t gemm_dgrad_act(const GemmOperands& o, const bf16_t* Zprev, bf16_t* dZ, int64_t ld, int64_t so, int act,
+                          hipStream_t s) {
+  return run(o, EpiDgradAct{Zprev, dZ, ld, so, act}, s);
+}
+
+}  // namespace pbt

@@ -1,0 +1,296 @@
+// Population-batched GEMM on the gfx950 matrix cores: bf16 operands, fp32
+// accumulate, one output tile per workgroup, member index = batch dimension.
+//
+// This is the dense contraction of `step` (Section 3, Eq. 2 of the PBT paper):
+// forward Y = X W, input gradient dX = dY W^T and weight gradient dW = X^T dY
+// for every member of the population in one launch.
+//
+// Tiling (wave64): a workgroup of 256 threads = 4 wavefronts owns a BM x BN
+// tile of C; each wavefront owns a (BM/WM) x (BN/WN) sub-tile made of 32x32
+// accumulator blocks fed by v_mfma_f32_32x32x16_bf16.  The K loop moves
+// BK = 64 wide slabs of A and B from HBM into registers (16-byte loads), then
+// into LDS in a "K-contiguous" layout, so that every MFMA operand is one
+// 16-byte LDS read.  Operands whose memory layout is contiguous along M or N
+// instead of K (W in the forward pass, X and dY in the weight gradient) are
+// transposed in registers on their way into LDS.  The loads of slab k+1 are in
+// flight while slab k is multiplied.
+//
+// The epilogue is a functor applied to every accumulator element; it fuses
+// bias + activation (forward) or the activation derivative (input gradient).
+#pragma once
+#include "common.h"
+
+namespace pbt {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+struct GemmArgs {
+  const bf16_t* A;
+  int64_t lda, sa;
+  const bf16_t* B;
+  int64_t ldb, sb;
+  int M, N, K, batch;
+  int tiles_m, tiles_n;
+};
+
+constexpr int GEMM_THREADS = 256;
+constexpr int GEMM_BK = 64;
+constexpr int GEMM_PITCH = GEMM_BK + 8;  // LDS row pitch in elements (144 B: keeps 16-byte alignment, skews banks)
+
+// ---- global -> register staging -------------------------------------------------------------
+// Operand tile of ROWS x BK (ROWS along M or N).  KCONTIG: memory is [row][k].
+// Otherwise memory is [k][row] and a thread fetches a KB x 8 block (KB k-rows of
+// 8 consecutive rows each) that it transposes before the LDS write.
+
+template <int ROWS, bool KCONTIG>
+struct TileLoader {
+  static constexpr int CHUNKS = ROWS * GEMM_BK / 8;            // 16-byte pieces per tile
+  static constexpr int PER_THREAD = CHUNKS / GEMM_THREADS;     // pieces per thread
+  static constexpr int KB = PER_THREAD;                        // k-rows per thread in the transposed case
+  static_assert(CHUNKS % GEMM_THREADS == 0, "tile must divide evenly over the workgroup");
+  uint4 r[PER_THREAD];
+
+  // base points at this member's operand; row0 / k0 select the tile; nrows / K bound it.
+  __device__ __forceinline__ void load(const bf16_t* __restrict__ base, int64_t ld, int row0, int k0, int nrows, int K) {
+    const int t = threadIdx.x;
+    if constexpr (KCONTIG) {
+#pragma unroll
+      for (int j = 0; j < PER_THREAD; ++j) {
+        const int c = t + GEMM_THREADS * j;
+        const int row = row0 + c / (GEMM_BK / 8);
+        const int k = k0 + (c % (GEMM_BK / 8)) * 8;
+        r[j] = fetch8(base, (int64_t)row * ld + k, row < nrows, K - k);
+      }
+    } else {
+      const int rb = t % (ROWS / 8);
+      const int kb = t / (ROWS / 8);
+      const int row = row0 + rb * 8;
+#pragma unroll
+      for (int j = 0; j < KB; ++j) {
+        const int k = k0 + kb * KB + j;
+        r[j] = fetch8(base, (int64_t)k * ld + row, k < K, nrows - row);
+      }
+    }
+  }
+
+  // 8 consecutive elements starting at base[off]; `valid` false or `left` <= 0 gives zeros,
+  // 0 < left < 8 loads only the first `left` elements.
+  static __device__ __forceinline__ uint4 fetch8(const bf16_t* __restrict__ base, int64_t off, bool valid, int left) {
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (valid && left >= 8) {
+      v = *reinterpret_cast<const uint4*>(base + off);
+    } else if (valid && left > 0) {
+      bf16_t e[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) e[i] = i < left ? base[off + i] : (bf16_t)0;
+      v.x = e[0] | ((uint32_t)e[1] << 16);
+      v.y = e[2] | ((uint32_t)e[3] << 16);
+      v.z = e[4] | ((uint32_t)e[5] << 16);
+      v.w = e[6] | ((uint32_t)e[7] << 16);
+    }
+    return v;
+  }
+
+  __device__ __forceinline__ void store(bf16_t* __restrict__ lds) const {
+    const int t = threadIdx.x;
+    if constexpr (KCONTIG) {
+#pragma unroll
+      for (int j = 0; j < PER_THREAD; ++j) {
+        const int c = t + GEMM_THREADS * j;
+        const int row = c / (GEMM_BK / 8);
+        const int k = (c % (GEMM_BK / 8)) * 8;
+        *reinterpret_cast<uint4*>(lds + row * GEMM_PITCH + k) = r[j];
+      }
+    } else {
+      const int rb = t % (ROWS / 8);
+      const int kb = t / (ROWS / 8);
+      // r[j] holds rows rb*8 .. rb*8+7 at k = kb*KB + j.  Emit, per row, KB consecutive k values.
+      const uint32_t* w = reinterpret_cast<const uint32_t*>(r);  // w[j*4 + q]: rows 2q (low half), 2q+1 (high half)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        uint32_t lo[KB / 2 > 0 ? KB / 2 : 1], hi[KB / 2 > 0 ? KB / 2 : 1];
+#pragma unroll
+        for (int j = 0; j < KB; j += 2) {
+          const uint32_t a = w[j * 4 + q], b = w[(j + 1) * 4 + q];
+          lo[j / 2] = (a & 0xffffu) | (b << 16);          // row 2q:   k = j, j+1
+          hi[j / 2] = (a >> 16) | (b & 0xffff0000u);      // row 2q+1: k = j, j+1
+        }
+        bf16_t* p0 = lds + (rb * 8 + 2 * q) * GEMM_PITCH + kb * KB;
+        bf16_t* p1 = p0 + GEMM_PITCH;
+        if constexpr (KB == 2) {
+          *reinterpret_cast<uint32_t*>(p0) = lo[0];
+          *reinterpret_cast<uint32_t*>(p1) = hi[0];
+        } else if constexpr (KB == 4) {
+          *reinterpret_cast<uint2*>(p0) = make_uint2(lo[0], lo[1]);
+          *reinterpret_cast<uint2*>(p1) = make_uint2(hi[0], hi[1]);
+        } else {
+          static_assert(KB == 8, "unsupported tile shape");
+          *reinterpret_cast<uint4*>(p0) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+          *reinterpret_cast<uint4*>(p1) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+        }
+      }
+    }
+  }
+};
+
+// Workgroups are handed to the 8 XCDs round-robin by linear id.  Remap the id
+// so that each XCD works on a contiguous run of tiles (neighbouring tiles
+// share an A or B slab, which then stays in that XCD's L2).
+__device__ __forceinline__ int xcd_remap(int id, int total) {
+  constexpr int XCDS = 8;
+  const int per = total / XCDS;
+  if (id >= per * XCDS) return id;  // ragged tail keeps its place
+  return (id % XCDS) * per + id / XCDS;
+}
+
+template <int BM, int BN, int WM, int WN, bool A_MCONTIG, bool B_KCONTIG, class Epilogue>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs g, Epilogue epi) {
+  static_assert(WM * WN == 4, "four wavefronts per workgroup");
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  __shared__ __attribute__((aligned(16))) bf16_t As[BM * GEMM_PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * GEMM_PITCH];
+
+  const int total = g.tiles_m * g.tiles_n * g.batch;
+  int id = xcd_remap(blockIdx.x, total);
+  const int tn = id % g.tiles_n;
+  id /= g.tiles_n;
+  const int tm = id % g.tiles_m;
+  const int member = id / g.tiles_m;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const bf16_t* __restrict__ A = g.A + (int64_t)member * g.sa;
+  const bf16_t* __restrict__ B = g.B + (int64_t)member * g.sb;
+
+  TileLoader<BM, !A_MCONTIG> la;
+  TileLoader<BN, B_KCONTIG> lb;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  la.load(A, g.lda, m0, 0, g.M, g.K);
+  lb.load(B, g.ldb, n0, 0, g.N, g.K);
+
+  for (int k0 = 0; k0 < g.K; k0 += GEMM_BK) {
+    __syncthreads();  // previous slab fully consumed
+    la.store(As);
+    lb.store(Bs);
+    __syncthreads();
+    if (k0 + GEMM_BK < g.K) {
+      la.load(A, g.lda, m0, k0 + GEMM_BK, g.M, g.K);
+      lb.load(B, g.ldb, n0, k0 + GEMM_BK, g.N, g.K);
+    }
+#pragma unroll
+    for (int kk = 0; kk < GEMM_BK; kk += 16) {
+      bf16x8_t af[TM], bfr[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        af[i] = *reinterpret_cast<const bf16x8_t*>(As + (wm * (BM / WM) + i * 32 + frag_row) * GEMM_PITCH + kk + frag_k);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        bfr[j] = *reinterpret_cast<const bf16x8_t*>(Bs + (wn * (BN / WN) + j * 32 + frag_row) * GEMM_PITCH + kk + frag_k);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  // Accumulator layout of the 32x32 block: lane -> column (lane % 32); register e -> row
+  // 8*(e/4) + 4*(lane/32) + e%4.
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = n0 + wn * (BN / WN) + j * 32 + (lane & 31);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (e / 4) + 4 * (lane >> 5) + (e % 4);
+        if (m < g.M && n < g.N) epi(member, m, n, acc[i][j][e]);
+      }
+    }
+}
+
+// ---- epilogues ------------------------------------------------------------------------------
+
+struct EpiStoreF32 {
+  float* C;
+  int64_t ldc, sc;
+  __device__ __forceinline__ void operator()(int member, int m, int n, float v) const {
+    C[(int64_t)member * sc + (int64_t)m * ldc + n] = v;
+  }
+};
+
+struct EpiStoreBF16 {
+  bf16_t* C;
+  int64_t ldc, sc;
+  __device__ __forceinline__ void operator()(int member, int m, int n, float v) const {
+    C[(int64_t)member * sc + (int64_t)m * ldc + n] = f2bf(v);
+  }
+};
+
+// Forward layer: z = acc + b[n]; stores z (for the backward pass, may be null) and act(z), both bf16.
+struct EpiBiasAct {
+  const float* bias;  // + member * sbias + n
+  int64_t sbias;
+  bf16_t* Z;
+  bf16_t* Aout;
+  int64_t ld, so;
+  int act;
+  __device__ __forceinline__ void operator()(int member, int m, int n, float v) const {
+    const float z = v + bias[(int64_t)member * sbias + n];
+    const int64_t o = (int64_t)member * so + (int64_t)m * ld + n;
+    if (Z) Z[o] = f2bf(z);
+    Aout[o] = f2bf(act_fwd(z, act));
+  }
+};
+
+// Input gradient: dz_prev = acc * act'(z_prev), bf16.
+struct EpiDgradAct {
+  const bf16_t* Zprev;
+  bf16_t* dZ;
+  int64_t ld, so;
+  int act;
+  __device__ __forceinline__ void operator()(int member, int m, int n, float v) const {
+    const int64_t o = (int64_t)member * so + (int64_t)m * ld + n;
+    dZ[o] = f2bf(v * act_bwd(bf2f(Zprev[o]), act));
+  }
+};
+
+// Host-side launcher: picks the tile shape from the layout flags.  Returns hipSuccess or the
+// launch error.  Caller guarantees 16-byte alignment of pitches / strides / bases.
+template <class Epilogue>
+hipError_t launch_gemm_bf16(const bf16_t* A, int64_t lda, int64_t sa, bool a_m_contig, const bf16_t* B, int64_t ldb,
+                            int64_t sb, bool b_k_contig, int M, int N, int K, int batch, const Epilogue& epi,
+                            hipStream_t stream) {
+  constexpr int BM = 128, BN = 128;
+  GemmArgs g;
+  g.A = A; g.lda = lda; g.sa = sa;
+  g.B = B; g.ldb = ldb; g.sb = sb;
+  g.M = M; g.N = N; g.K = K; g.batch = batch;
+  g.tiles_m = (M + BM - 1) / BM;
+  g.tiles_n = (N + BN - 1) / BN;
+  const int64_t total = (int64_t)g.tiles_m * g.tiles_n * batch;
+  if (total <= 0 || total > 0x7fffffff) return hipErrorInvalidValue;
+  dim3 grid((unsigned)total), block(GEMM_THREADS);
+  if (!a_m_contig && !b_k_contig)
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, 2, 2, false, false, Epilogue>), grid, block, 0, stream, g, epi);
+  else if (!a_m_contig && b_k_contig)
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, 2, 2, false, true, Epilogue>), grid, block, 0, stream, g, epi);
+  else if (a_m_contig && !b_k_contig)
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, 2, 2, true, false, Epilogue>), grid, block, 0, stream, g, epi);
+  else
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, 2, 2, true, true, Epilogue>), grid, block, 0, stream, g, epi);
+  return hipGetLastError();
+}
+
+}  // namespace pbt

@@ -1,0 +1,96 @@
+// Host-callable launchers of the population-step kernels.  Every launcher only enqueues on
+// `stream` and returns the launch status; none allocates or synchronises.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pbt {
+
+typedef uint16_t bf16_t;
+
+// ---- gemm.hip: population-batched bf16 MFMA GEMM with fused epilogues ------------------------
+struct GemmOperands {
+  const bf16_t* A; int64_t lda, sa; bool a_m_contig;
+  const bf16_t* B; int64_t ldb, sb; bool b_k_contig;
+  int M, N, K, batch;
+};
+hipError_t gemm_store_f32(const GemmOperands& o, float* C, int64_t ldc, int64_t sc, hipStream_t s);
+hipError_t gemm_store_bf16(const GemmOperands& o, bf16_t* C, int64_t ldc, int64_t sc, hipStream_t s);
+// z = acc + bias; Z (may be null) <- z, Aout <- act(z); both [batch][M][ld] bf16 with batch stride so
+hipError_t gemm_bias_act(const GemmOperands& o, const float* bias, int64_t sbias, bf16_t* Z, bf16_t* Aout, int64_t ld,
+                         int64_t so, int act, hipStream_t s);
+// dZ <- acc * act'(Zprev)
+hipError_t gemm_dgrad_act(const GemmOperands& o, const bf16_t* Zprev, bf16_t* dZ, int64_t ld, int64_t so, int act,
+                          hipStream_t s);
+
+// ---- kernels.hip ----------------------------------------------------------------------------
+hipError_t fill_u32(uint32_t* p, uint32_t v, int64_t n, hipStream_t s);
+hipError_t iota_i32(int32_t* p, int n, hipStream_t s);
+hipError_t f32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t s);
+
+// Mini-batch fetch: row r of member i at step `step` is data row floor(x * n_train / 2^32),
+// x = word 0 of Philox(step, i, DOMAIN_BATCH, r).  Writes X[P][B][d] (bf16 or float) and Y[P][B];
+// also t[i] += 1 (the update count used by this step's optimiser pass).
+hipError_t gather_batch(const float* train_x, const int32_t* train_y, int n_train, int d, int P, int B, uint32_t step,
+                        uint64_t seed, bf16_t* X16, float* X32, int32_t* Y, int32_t* t, hipStream_t s);
+
+// Output layer + softmax cross-entropy.  logits = A W + b with A [P][rows][K] (bf16, batch stride
+// sa; sa = 0 shares A), W bf16 [K][C] at W16 + member*sw, b float at bias + member*sbias.
+// Writes rowloss[P][rows] and, when dlogits != null, dlogits[P][rows][C] = (softmax - onehot) * gscale.
+// labels are [rows] shared (sy = 0) or per member (sy = rows).
+hipError_t head_fwd_loss(const bf16_t* A, int64_t sa, const bf16_t* W16, int64_t sw, const float* bias, int64_t sbias,
+                         const int32_t* labels, int64_t sy, int P, int rows, int K, int C, float gscale,
+                         float* dlogits, float* rowloss, int64_t srowloss, hipStream_t s);
+// dW[K][C] = A^T dlogits, db[C] = column sums of dlogits (floats into G at the given offsets).
+hipError_t head_wgrad(const bf16_t* A, int64_t sa, const float* dlogits, int P, int rows, int K, int C, float* dW,
+                      float* db, int64_t sg, hipStream_t s);
+// dZprev[P][rows][K] = (dlogits W^T) * act'(Zprev)
+hipError_t head_dgrad(const float* dlogits, const bf16_t* W16, int64_t sw, const bf16_t* Zprev, bf16_t* dZprev, int P,
+                      int rows, int K, int C, int act, hipStream_t s);
+// db[n] = sum over rows of dZ[P][rows][N]
+hipError_t bias_grad(const bf16_t* dZ, int P, int rows, int N, float* db, int64_t sg, hipStream_t s);
+// out[i] = scale * sum_r rowval[i][r]   (one wavefront per member, fixed order)
+hipError_t row_reduce(const float* rowval, int64_t srow, int P, int rows, float scale, float* out, hipStream_t s);
+
+struct OptArgs {
+  float* W32; float* S0; float* S1; bf16_t* W16; const float* G;
+  const float* H; const int32_t* t;
+  int64_t stride; int P; int n_hyper;
+  int optimizer;
+  int col_lr, col_beta1, col_wd;  // column of H with that role, or -1
+  float c0, c1, c2, c3;           // opt_const
+};
+hipError_t optimizer_step(const OptArgs& a, hipStream_t s);
+
+struct ExploitArgs {
+  float* score; const float* score_override; float* H; int32_t* t; int32_t* order; int32_t* donor; int32_t* parent;
+  int32_t* recip;
+  int P, n_trunc, n_hyper;
+  float f_lo, f_hi;
+  float h_max[8];
+  uint32_t round; uint64_t seed;
+};
+hipError_t rank_select_explore(const ExploitArgs& a, hipStream_t s);
+struct CopyArrays {
+  void* base[4]; int64_t row_bytes[4]; int n;
+};
+hipError_t gather_copy(const CopyArrays& arrs, const int32_t* recip, const int32_t* donor, int n_trunc, hipStream_t s);
+
+// fused_small.hip: whole step of a small fp32 MLP classifier, one workgroup per member, the
+// member's weights, optimiser state and activations resident in LDS across n_steps steps.
+struct FusedSmallArgs {
+  float* W32; float* S0; float* S1; float* G; const float* H; int32_t* t; float* loss; float* score;
+  const float* x; const int32_t* y;          // training set (step) or held-out set (eval)
+  int64_t stride; int P, B, n_rows, n_layers; int dims[16]; int w_off[16], b_off[16];
+  int act, optimizer, n_hyper, col_lr, col_beta1, col_wd; float c0, c1, c2, c3;
+  uint32_t step0; int n_steps; uint64_t seed;
+  // LDS carve-up in floats, filled by fused_small_plan()
+  int lds_w, lds_s0, lds_s1, lds_a[16], lds_z[16], lds_dz[2], lds_rowloss, lds_y, lds_total;
+};
+// Fills the lds_* fields; returns the dynamic LDS bytes needed (for_eval: no state, no gradients).
+size_t fused_small_plan(FusedSmallArgs& a, bool for_eval);
+constexpr size_t FUSED_SMALL_MAX_LDS = 160 * 1024;
+hipError_t fused_small_step(const FusedSmallArgs& a, hipStream_t s);
+hipError_t fused_small_eval(const FusedSmallArgs& a, hipStream_t s);
+
+}  // namespace pbt

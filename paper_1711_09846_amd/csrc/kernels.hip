@@ -1,0 +1,411 @@
+// Memory-bound and small kernels of the population step: mini-batch fetch, output layer with
+// softmax cross-entropy, bias gradients, per-member reductions, the fused per-member optimiser
+// and the on-device exploit/explore pass (rank, truncation selection, gather-copy, perturb).
+#include "common.h"
+#include "internal.h"
+#include "philox.h"
+
+namespace pbt {
+
+// ---- fills and conversions -------------------------------------------------------------------
+
+__global__ void fill_u32_kernel(uint32_t* p, uint32_t v, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+}
+hipError_t fill_u32(uint32_t* p, uint32_t v, int64_t n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  const int blocks = (int)((n + 1023) / 1024 > 8192 ? 8192 : (n + 1023) / 1024);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks), dim3(256), 0, s, p, v, n);
+  return hipGetLastError();
+}
+
+__global__ void iota_i32_kernel(int32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = i;
+}
+hipError_t iota_i32(int32_t* p, int n, hipStream_t s) {
+  hipLaunchKernelGGL(iota_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, n);
+  return hipGetLastError();
+}
+
+__global__ void f32_to_bf16_kernel(const float* __restrict__ src, bf16_t* __restrict__ dst, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+    dst[i] = f2bf(src[i]);
+}
+hipError_t f32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  const int blocks = (int)((n + 1023) / 1024 > 16384 ? 16384 : (n + 1023) / 1024);
+  hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(blocks), dim3(256), 0, s, src, dst, n);
+  return hipGetLastError();
+}
+
+// ---- mini-batch fetch ------------------------------------------------------------------------
+// grid (B, P); one workgroup copies one data row.
+
+__global__ __launch_bounds__(64) void gather_batch_kernel(const float* __restrict__ train_x,
+                                                          const int32_t* __restrict__ train_y, int n_train, int d, int B,
+                                                          uint32_t step, uint32_t k0, uint32_t k1,
+                                                          bf16_t* __restrict__ X16, float* __restrict__ X32,
+                                                          int32_t* __restrict__ Y, int32_t* __restrict__ t) {
+  const int r = blockIdx.x, i = blockIdx.y;
+  const uint32_t x = philox4x32_10(step, (uint32_t)i, DOMAIN_BATCH, (uint32_t)r, k0, k1).x;
+  const int64_t src = (int64_t)philox_bounded(x, (uint32_t)n_train);
+  const int64_t dst = ((int64_t)i * B + r) * d;
+  const float* __restrict__ row = train_x + src * d;
+  if (X16) {
+    for (int c = threadIdx.x; c < d; c += 64) X16[dst + c] = f2bf(row[c]);
+  } else {
+    for (int c = threadIdx.x; c < d; c += 64) X32[dst + c] = row[c];
+  }
+  if (threadIdx.x == 0) {
+    Y[(int64_t)i * B + r] = train_y[src];
+    if (r == 0) t[i] += 1;
+  }
+}
+hipError_t gather_batch(const float* train_x, const int32_t* train_y, int n_train, int d, int P, int B, uint32_t step,
+                        uint64_t seed, bf16_t* X16, float* X32, int32_t* Y, int32_t* t, hipStream_t s) {
+  hipLaunchKernelGGL(gather_batch_kernel, dim3(B, P), dim3(64), 0, s, train_x, train_y, n_train, d, B, step,
+                     (uint32_t)seed, (uint32_t)(seed >> 32), X16, X32, Y, t);
+  return hipGetLastError();
+}
+
+// ---- output layer + softmax cross-entropy ----------------------------------------------------
+// One wavefront per row: lanes stride over K, C (<= 32) running sums per lane, butterfly
+// reduction, then every lane holds all logits and evaluates the softmax redundantly.
+
+constexpr int HEAD_CMAX = 32;
+constexpr int HEAD_ROWS_PER_WG = 8;  // 4 wavefronts x 2 rows
+
+__global__ __launch_bounds__(256) void head_fwd_loss_kernel(const bf16_t* __restrict__ A, int64_t sa,
+                                                            const bf16_t* __restrict__ W16, int64_t sw,
+                                                            const float* __restrict__ bias, int64_t sbias,
+                                                            const int32_t* __restrict__ labels, int64_t sy, int rows,
+                                                            int K, int C, float gscale, float* __restrict__ dlogits,
+                                                            float* __restrict__ rowloss, int64_t srowloss) {
+  const int i = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const bf16_t* __restrict__ W = W16 + (int64_t)i * sw;
+  const float* __restrict__ b = bias + (int64_t)i * sbias;
+  for (int rr = wave; rr < HEAD_ROWS_PER_WG; rr += 4) {
+    const int r = blockIdx.x * HEAD_ROWS_PER_WG + rr;
+    if (r >= rows) break;
+    const bf16_t* __restrict__ a = A + (int64_t)i * sa + (int64_t)r * K;
+    float acc[HEAD_CMAX];
+#pragma unroll
+    for (int c = 0; c < HEAD_CMAX; ++c) acc[c] = 0.f;
+    for (int k = lane; k < K; k += 64) {
+      const float av = bf2f(a[k]);
+      const bf16_t* __restrict__ wr = W + (int64_t)k * C;
+#pragma unroll
+      for (int c = 0; c < HEAD_CMAX; ++c)
+        if (c < C) acc[c] = fmaf(av, bf2f(wr[c]), acc[c]);
+    }
+    float mx = -INFINITY;
+    int cm = 0;
+#pragma unroll
+    for (int c = 0; c < HEAD_CMAX; ++c)
+      if (c < C) {
+        acc[c] = wave_sum(acc[c]) + b[c];
+        if (acc[c] > mx) { mx = acc[c]; cm = c; }
+      }
+    // log-sum-exp with the largest term split off: lse = mx + log1p(sum of the others)
+    float rest = 0.f;
+#pragma unroll
+    for (int c = 0; c < HEAD_CMAX; ++c)
+      if (c < C && c != cm) rest += expf(acc[c] - mx);
+    const float l1p = log1pf(rest), inv = 1.f / (1.f + rest);
+    const int y = labels[(int64_t)i * sy + r];
+    // softmax_y - 1 = -(sum of the other classes' terms) / S: no cancellation when softmax_y -> 1
+    float ly = 0.f, others = (y == cm) ? 0.f : 1.f;
+#pragma unroll
+    for (int c = 0; c < HEAD_CMAX; ++c)
+      if (c < C) {
+        if (c == y) ly = acc[c];
+        else if (c != cm) others += expf(acc[c] - mx);
+      }
+#pragma unroll
+    for (int c = 0; c < HEAD_CMAX; ++c)
+      if (c < C && dlogits && lane == c)
+        dlogits[((int64_t)i * rows + r) * C + c] = (c == y ? -others * inv : expf(acc[c] - mx) * inv) * gscale;
+    if (lane == 0) rowloss[(int64_t)i * srowloss + r] = l1p + (mx - ly);
+  }
+}
+hipError_t head_fwd_loss(const bf16_t* A, int64_t sa, const bf16_t* W16, int64_t sw, const float* bias, int64_t sbias,
+                         const int32_t* labels, int64_t sy, int P, int rows, int K, int C, float gscale,
+                         float* dlogits, float* rowloss, int64_t srowloss, hipStream_t s) {
+  if (C > HEAD_CMAX) return hipErrorInvalidValue;
+  dim3 grid((rows + HEAD_ROWS_PER_WG - 1) / HEAD_ROWS_PER_WG, P);
+  hipLaunchKernelGGL(head_fwd_loss_kernel, grid, dim3(256), 0, s, A, sa, W16, sw, bias, sbias, labels, sy, rows, K, C,
+                     gscale, dlogits, rowloss, srowloss);
+  return hipGetLastError();
+}
+
+// dW[k][c] = sum_r A[r][k] dlogits[r][c]: one thread per k, rows in order; block 0 also sums db.
+__global__ __launch_bounds__(256) void head_wgrad_kernel(const bf16_t* __restrict__ A, int64_t sa,
+                                                         const float* __restrict__ dlogits, int rows, int K, int C,
+                                                         float* __restrict__ dW, float* __restrict__ db, int64_t sg) {
+  const int i = blockIdx.y;
+  const int k = blockIdx.x * 256 + threadIdx.x;
+  const float* __restrict__ dl = dlogits + (int64_t)i * rows * C;
+  if (k < K) {
+    const bf16_t* __restrict__ a = A + (int64_t)i * sa + k;
+    float acc[HEAD_CMAX];
+#pragma unroll
+    for (int c = 0; c < HEAD_CMAX; ++c) acc[c] = 0.f;
+    for (int r = 0; r < rows; ++r) {
+      const float av = bf2f(a[(int64_t)r * K]);
+#pragma unroll
+      for (int c = 0; c < HEAD_CMAX; ++c)
+        if (c < C) acc[c] = fmaf(av, dl[r * C + c], acc[c]);
+    }
+    float* __restrict__ o = dW + (int64_t)i * sg + (int64_t)k * C;
+#pragma unroll
+    for (int c = 0; c < HEAD_CMAX; ++c)
+      if (c < C) o[c] = acc[c];
+  }
+  if (blockIdx.x == 0 && threadIdx.x < C) {
+    float sacc = 0.f;
+    for (int r = 0; r < rows; ++r) sacc += dl[r * C + threadIdx.x];
+    db[(int64_t)i * sg + threadIdx.x] = sacc;
+  }
+}
+hipError_t head_wgrad(const bf16_t* A, int64_t sa, const float* dlogits, int P, int rows, int K, int C, float* dW,
+                      float* db, int64_t sg, hipStream_t s) {
+  if (C > HEAD_CMAX) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(head_wgrad_kernel, dim3((K + 255) / 256, P), dim3(256), 0, s, A, sa, dlogits, rows, K, C, dW, db, sg);
+  return hipGetLastError();
+}
+
+// dZprev[r][k] = (sum_c dlogits[r][c] W[k][c]) * act'(Zprev[r][k]); one thread per (r, k).
+__global__ __launch_bounds__(256) void head_dgrad_kernel(const float* __restrict__ dlogits,
+                                                         const bf16_t* __restrict__ W16, int64_t sw,
+                                                         const bf16_t* __restrict__ Zprev, bf16_t* __restrict__ dZprev,
+                                                         int rows, int K, int C, int act) {
+  const int i = blockIdx.z, r = blockIdx.y;
+  const int k = blockIdx.x * 256 + threadIdx.x;
+  if (k >= K) return;
+  const float* __restrict__ dl = dlogits + ((int64_t)i * rows + r) * C;
+  const bf16_t* __restrict__ w = W16 + (int64_t)i * sw + (int64_t)k * C;
+  float acc = 0.f;
+  for (int c = 0; c < C; ++c) acc = fmaf(dl[c], bf2f(w[c]), acc);
+  const int64_t o = ((int64_t)i * rows + r) * K + k;
+  dZprev[o] = f2bf(acc * act_bwd(bf2f(Zprev[o]), act));
+}
+hipError_t head_dgrad(const float* dlogits, const bf16_t* W16, int64_t sw, const bf16_t* Zprev, bf16_t* dZprev, int P,
+                      int rows, int K, int C, int act, hipStream_t s) {
+  hipLaunchKernelGGL(head_dgrad_kernel, dim3((K + 255) / 256, rows, P), dim3(256), 0, s, dlogits, W16, sw, Zprev, dZprev,
+                     rows, K, C, act);
+  return hipGetLastError();
+}
+
+// db[n] = sum_r dZ[r][n]; one thread per column, rows in order.
+__global__ __launch_bounds__(256) void bias_grad_kernel(const bf16_t* __restrict__ dZ, int rows, int N,
+                                                        float* __restrict__ db, int64_t sg) {
+  const int i = blockIdx.y;
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  const bf16_t* __restrict__ p = dZ + (int64_t)i * rows * N + n;
+  float acc = 0.f;
+  for (int r = 0; r < rows; ++r) acc += bf2f(p[(int64_t)r * N]);
+  db[(int64_t)i * sg + n] = acc;
+}
+hipError_t bias_grad(const bf16_t* dZ, int P, int rows, int N, float* db, int64_t sg, hipStream_t s) {
+  hipLaunchKernelGGL(bias_grad_kernel, dim3((N + 255) / 256, P), dim3(256), 0, s, dZ, rows, N, db, sg);
+  return hipGetLastError();
+}
+
+// Per-member reduction of per-row values with wavefront shuffles: lane l adds rows l, l+64, ...
+// in order, then a butterfly over the 64 lanes.
+__global__ __launch_bounds__(64) void row_reduce_kernel(const float* __restrict__ rowval, int64_t srow, int rows,
+                                                        float scale, float* __restrict__ out) {
+  const int i = blockIdx.x;
+  const float* __restrict__ p = rowval + (int64_t)i * srow;
+  float acc = 0.f;
+  for (int r = threadIdx.x; r < rows; r += 64) acc += p[r];
+  acc = wave_sum(acc);
+  if (threadIdx.x == 0) out[i] = acc * scale;
+}
+hipError_t row_reduce(const float* rowval, int64_t srow, int P, int rows, float scale, float* out, hipStream_t s) {
+  hipLaunchKernelGGL(row_reduce_kernel, dim3(P), dim3(64), 0, s, rowval, srow, rows, scale, out);
+  return hipGetLastError();
+}
+
+// ---- fused per-member optimiser --------------------------------------------------------------
+// Streams a member's parameters once: reads theta, gradient and state, writes theta, state and
+// the bf16 shadow.  lr / beta1 / weight decay come from the member's row of H on the device, so
+// an explore pass changes the very next update without host involvement.
+//   SGD-momentum  v <- mu v + g;  theta <- theta - lr v
+//   Adam          m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2
+//                 theta <- theta - lr ( (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps) + wd theta )
+//   RMSProp       s <- rho s + (1-rho) g^2;  theta <- theta - lr g / sqrt(s + eps)
+
+constexpr int OPT_VEC_PER_THREAD = 2;  // float4 vectors per thread
+
+template <int OPT>
+__global__ __launch_bounds__(256) void optimizer_kernel(OptArgs a) {
+  const int i = blockIdx.y;
+  const float* __restrict__ h = a.H + (int64_t)i * a.n_hyper;
+  const float lr = h[a.col_lr];
+  float b1 = a.c0, wd = a.c3, inv_bc1 = 1.f, inv_bc2 = 1.f;
+  if (OPT == 1) {
+    if (a.col_beta1 >= 0) b1 = h[a.col_beta1];
+    if (a.col_wd >= 0) wd = h[a.col_wd];
+    const float tt = (float)a.t[i];
+    inv_bc1 = 1.f / (1.f - powf(b1, tt));
+    inv_bc2 = 1.f / (1.f - powf(a.c1, tt));
+  }
+  const int64_t base = (int64_t)i * a.stride;
+  const int64_t nvec = a.stride / 4;
+#pragma unroll
+  for (int u = 0; u < OPT_VEC_PER_THREAD; ++u) {
+    const int64_t v = ((int64_t)blockIdx.x * OPT_VEC_PER_THREAD + u) * 256 + threadIdx.x;
+    if (v >= nvec) break;
+    const int64_t o = base + v * 4;
+    float4 w = *reinterpret_cast<const float4*>(a.W32 + o);
+    const float4 g = *reinterpret_cast<const float4*>(a.G + o);
+    float4 s0 = *reinterpret_cast<const float4*>(a.S0 + o);
+    float* wp = reinterpret_cast<float*>(&w);
+    const float* gp = reinterpret_cast<const float*>(&g);
+    float* s0p = reinterpret_cast<float*>(&s0);
+    if (OPT == 0) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        s0p[e] = a.c0 * s0p[e] + gp[e];
+        wp[e] = wp[e] - lr * s0p[e];
+      }
+    } else if (OPT == 1) {
+      float4 s1 = *reinterpret_cast<const float4*>(a.S1 + o);
+      float* s1p = reinterpret_cast<float*>(&s1);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        s0p[e] = b1 * s0p[e] + (1.f - b1) * gp[e];
+        s1p[e] = a.c1 * s1p[e] + (1.f - a.c1) * gp[e] * gp[e];
+        const float mh = s0p[e] * inv_bc1;
+        const float vh = s1p[e] * inv_bc2;
+        wp[e] = wp[e] - lr * (mh / (sqrtf(vh) + a.c2) + wd * wp[e]);
+      }
+      *reinterpret_cast<float4*>(a.S1 + o) = s1;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        s0p[e] = a.c0 * s0p[e] + (1.f - a.c0) * gp[e] * gp[e];
+        wp[e] = wp[e] - lr * gp[e] / sqrtf(s0p[e] + a.c1);
+      }
+    }
+    *reinterpret_cast<float4*>(a.W32 + o) = w;
+    *reinterpret_cast<float4*>(a.S0 + o) = s0;
+    if (a.W16) {
+      uint2 pk;
+      pk.x = f2bf(wp[0]) | ((uint32_t)f2bf(wp[1]) << 16);
+      pk.y = f2bf(wp[2]) | ((uint32_t)f2bf(wp[3]) << 16);
+      *reinterpret_cast<uint2*>(a.W16 + o) = pk;
+    }
+  }
+}
+hipError_t optimizer_step(const OptArgs& a, hipStream_t s) {
+  const int64_t nvec = a.stride / 4;
+  const int per_block = 256 * OPT_VEC_PER_THREAD;
+  dim3 grid((unsigned)((nvec + per_block - 1) / per_block), a.P);
+  if (a.optimizer == 0)
+    hipLaunchKernelGGL(optimizer_kernel<0>, grid, dim3(256), 0, s, a);
+  else if (a.optimizer == 1)
+    hipLaunchKernelGGL(optimizer_kernel<1>, grid, dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL(optimizer_kernel<2>, grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+// ---- exploit / explore -----------------------------------------------------------------------
+// One workgroup ranks the population by counting: member i's position is the number of members
+// that rank above it under the total order (score descending; equal scores: lower index first;
+// -inf below every finite score; NaN below -inf).  The bottom n_trunc members then pick a donor
+// from the top n_trunc with one Philox word each and perturb the donor's hyperparameters.
+
+__device__ __forceinline__ bool ranks_above(float sj, int j, float si, int i) {
+  const bool nj = sj != sj, ni = si != si;
+  if (nj != ni) return ni;
+  if (!nj && sj != si) return sj > si;
+  return j < i;
+}
+
+__global__ __launch_bounds__(1024) void rank_select_explore_kernel(ExploitArgs a) {
+  __shared__ float sc[1024];
+  __shared__ int ord[1024];
+  const int i = threadIdx.x;
+  const float* __restrict__ src = a.score_override ? a.score_override : a.score;
+  if (i < a.P) sc[i] = src[i];
+  __syncthreads();
+  int pos = 0;
+  if (i < a.P) {
+    const float si = sc[i];
+    for (int j = 0; j < a.P; ++j) pos += (j != i && ranks_above(sc[j], j, si, i)) ? 1 : 0;
+    ord[pos] = i;
+  }
+  __syncthreads();
+  if (i >= a.P) return;
+  a.order[i] = ord[i];
+  const int first_bottom = a.P - a.n_trunc;
+  if (a.n_trunc > 0 && pos >= first_bottom) {
+    const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
+    const uint32_t x = philox4x32_10(a.round, (uint32_t)i, DOMAIN_DONOR, 0u, k0, k1).x;
+    const int d = ord[philox_bounded(x, (uint32_t)a.n_trunc)];
+    a.donor[i] = d;
+    a.recip[pos - first_bottom] = i;
+    a.parent[i] = d;
+    a.t[i] = a.t[d];
+    a.score[i] = sc[d];
+    for (int k = 0; k < a.n_hyper; ++k) {
+      const uint32_t bit = philox4x32_10(a.round, (uint32_t)i, DOMAIN_EXPLORE, (uint32_t)k, k0, k1).x & 1u;
+      // one IEEE float multiply (no contraction possible: nothing is added)
+      const float v = __fmul_rn(a.H[d * a.n_hyper + k], bit ? a.f_hi : a.f_lo);
+      a.H[i * a.n_hyper + k] = v > a.h_max[k] ? a.h_max[k] : v;
+    }
+  } else {
+    a.donor[i] = -1;
+    if (a.score_override) a.score[i] = sc[i];
+  }
+}
+hipError_t rank_select_explore(const ExploitArgs& a, hipStream_t s) {
+  if (a.P > 1024) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(rank_select_explore_kernel, dim3(1), dim3(1024), 0, s, a);
+  return hipGetLastError();
+}
+
+// Gather-copy: recipient recip[y] receives a byte copy of row donor[recip[y]] of every array.
+// grid (chunks, n_trunc, arrays); 16-byte vectors, four in flight per thread.
+constexpr int COPY_UNROLL = 4;
+__global__ __launch_bounds__(256) void gather_copy_kernel(CopyArrays arrs, const int32_t* __restrict__ recip,
+                                                          const int32_t* __restrict__ donor) {
+  const int r = recip[blockIdx.y];
+  const int d = donor[r];
+  const int64_t rb = arrs.row_bytes[blockIdx.z];
+  const uint4* __restrict__ src = reinterpret_cast<const uint4*>(static_cast<const char*>(arrs.base[blockIdx.z]) + (int64_t)d * rb);
+  uint4* __restrict__ dst = reinterpret_cast<uint4*>(static_cast<char*>(arrs.base[blockIdx.z]) + (int64_t)r * rb);
+  const int64_t nvec = rb / 16;
+  const int64_t span = (int64_t)gridDim.x * 256;
+  for (int64_t v0 = (int64_t)blockIdx.x * 256 + threadIdx.x; v0 < nvec; v0 += span * COPY_UNROLL) {
+    uint4 tmp[COPY_UNROLL];
+#pragma unroll
+    for (int u = 0; u < COPY_UNROLL; ++u) {
+      const int64_t v = v0 + u * span;
+      if (v < nvec) tmp[u] = src[v];
+    }
+#pragma unroll
+    for (int u = 0; u < COPY_UNROLL; ++u) {
+      const int64_t v = v0 + u * span;
+      if (v < nvec) dst[v] = tmp[u];
+    }
+  }
+}
+hipError_t gather_copy(const CopyArrays& arrs, const int32_t* recip, const int32_t* donor, int n_trunc, hipStream_t s) {
+  if (n_trunc <= 0 || arrs.n <= 0) return hipSuccess;
+  int64_t maxvec = 0;
+  for (int k = 0; k < arrs.n; ++k) maxvec = arrs.row_bytes[k] / 16 > maxvec ? arrs.row_bytes[k] / 16 : maxvec;
+  int64_t chunks = (maxvec + 256 * COPY_UNROLL - 1) / (256 * COPY_UNROLL);
+  if (chunks > 2048) chunks = 2048;
+  if (chunks < 1) chunks = 1;
+  hipLaunchKernelGGL(gather_copy_kernel, dim3((unsigned)chunks, n_trunc, arrs.n), dim3(256), 0, s, arrs, recip, donor);
+  return hipGetLastError();
+}
+
+}  // namespace pbt

@@ -121,3 +121,29 @@ def test_against_torch_autograd(kind, tkind):
     for (W, b), (gW, gb) in zip(tp, grads):
         assert np.allclose(W.grad.numpy(), gW, atol=1e-12)
         assert np.allclose(b.grad.numpy(), gb, atol=1e-12)
+
+
+def test_round_bf16_against_library_and_by_hand():
+    rng = np.random.default_rng(23)
+    x = np.concatenate([rng.standard_normal(5000) * 10.0 ** rng.integers(-6, 6, 5000), [0.0, -0.0, 1.0, -1.0]])
+    x32 = x.astype(np.float32)          # exactly representable inputs, so one rounding on both sides
+    ref = torch.from_numpy(x32).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(nets.round_bf16(x32.astype(np.float64)), ref)
+    # spacing at 1.0 is 2**-7: ties go to the even neighbour
+    assert nets.round_bf16(np.array([1.0 + 2.0 ** -8]))[0] == 1.0
+    assert nets.round_bf16(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6
+    assert nets.round_bf16(np.array([1.0 + 2.0 ** -8 + 2.0 ** -30]))[0] == 1.0 + 2.0 ** -7
+    assert nets.round_bf16(np.array([-3.14159]))[0] == -3.140625
+
+
+def test_bf16_storage_is_a_small_perturbation_of_the_exact_gradient():
+    rng = np.random.default_rng(29)
+    params = _rand_params([16, 32, 24, 5], rng)
+    x = rng.standard_normal((20, 16))
+    y = rng.integers(0, 5, size=20)
+    l0, g0 = nets.classifier_loss_and_grads(params, x, y, nets.ACT_GELU)
+    l1, g1 = nets.classifier_loss_and_grads(params, x, y, nets.ACT_GELU, q=nets.round_bf16)
+    assert 0 < abs(l1 - l0) < 2e-2 * abs(l0)
+    for (a, b), (c, d) in zip(g0, g1):
+        assert 0 < np.linalg.norm(a - c) < 2e-2 * np.linalg.norm(a)
+        assert np.linalg.norm(b - d) < 2e-2 * np.linalg.norm(b)
