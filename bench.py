@@ -1,0 +1,149 @@
+"""Benchmark of the population step on one MI355X.
+
+A "step" is one pass of the whole hot path over one mini-batch per member: fetch, forward, loss,
+backward, optimiser update for all P members, plus `eval` and exploit/explore at the workload's
+cadence (every `ready_interval` steps).  Workload: the wide bf16 MLP population (P = 64,
+256-1024-1024-10, batch 128, Adam).  All inputs are synthetic and resident in HBM before the
+timed region.  Prints one JSON line."""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def cpu_baseline(wl, data, seed, budget_s=15.0):
+    """The oracle as it stands, timed on the host cores over a bounded sample of the workload."""
+    import numpy as np
+    from oracle import classifier as oc
+    from paper_1711_09846_amd import workloads
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from tests.harness import oracle_spec
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    (tx, ty), _ = data
+    spec = oracle_spec(wl, seed)
+    weights = workloads.initial_mlp_weights(wl.dims, wl.P, 5)
+    H = workloads.initial_hypers(wl, 6)
+    pop = [oc.new_member(spec, weights[i], H[i], i) for i in range(wl.P)]
+    done, t0 = 0, time.perf_counter()
+    s = 0
+    while True:
+        for i, m in enumerate(pop):
+            oc.step(spec, m, i, s, tx, ty)
+            done += 1
+        s += 1
+        if time.perf_counter() - t0 >= budget_s or s >= 32:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": done / dt, "unit": "member-steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": "%d population steps (%d member-steps) of %s, step only, numpy float64" % (s, done, wl.name)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--kernel", default="optimizer", help="kernel class whose roofline is reported")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1711_09846_amd import binding, workloads
+
+    wl = workloads.MLP_WIDE
+    seed = workloads.POPULATION_SEED
+    data = workloads.classifier_data(wl)
+    (tx, ty), (ex, ey) = data
+    cfg = binding.make_config(wl, seed)
+    pop = binding.Population(cfg)
+    pop.set_members(workloads.initial_mlp_weights(wl.dims, wl.P, 5), workloads.initial_hypers(wl, 6))
+    dev = pop.device
+    d_train = [torch.from_numpy(tx).to(dev), torch.from_numpy(ty).to(dev)]
+    d_eval = [torch.from_numpy(ex).to(dev), torch.from_numpy(ey).to(dev)]
+
+    klass = {"optimizer": binding.K_OPTIMIZER, "gemm_fwd": binding.K_GEMM_FWD, "gemm_wgrad": binding.K_GEMM_WGRAD,
+             "gemm_dgrad": binding.K_GEMM_DGRAD, "copy": binding.K_COPY, "head": binding.K_HEAD,
+             "fetch": binding.K_FETCH, "bias_grad": binding.K_BIAS_GRAD}[args.kernel]
+
+    def run(first, n, rnd):
+        for s in range(first, first + n):
+            pop.step(d_train, s)
+            if (s + 1) % wl.ready_interval == 0:
+                pop.eval(d_eval)
+                pop.exploit_explore(rnd)
+                rnd += 1
+        return rnd
+
+    rnd = run(0, args.warmup, 0)
+    # the warm-up also exercises eval + exploit once so that nothing is first-touched in the timed region
+    pop.eval(d_eval)
+    pop.exploit_explore(1 << 20)
+    torch.cuda.synchronize()
+    pop.timing_enable(klass, 8 * args.steps + 64)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    # step indices continue from the warm-up so that the cadence (eval + exploit every
+    # ready_interval steps) falls inside the timed region as it does in a real run
+    run(args.warmup, args.steps, rnd)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    k_ms, k_n = pop.timing_read()
+    pop.timing_enable(binding.K_NONE, 0)
+    n_rounds = (args.warmup + args.steps) // wl.ready_interval - args.warmup // wl.ready_interval
+
+    n = pop.layout.n_params
+    L = len(wl.dims) - 1
+    flops_fwd = sum(2.0 * wl.batch * wl.dims[l] * wl.dims[l + 1] for l in range(L - 1)) * wl.P
+    per_launch = {
+        # Adam: read theta, g, m, v (16 B), write theta, m, v (12 B) and the bf16 shadow (2 B) per parameter
+        "optimizer": ("hbm", 30.0 * n * wl.P),
+        # read + write of every array of the n_trunc copied members: fp32 theta, m, v and the bf16 shadow
+        "copy": ("hbm", 2.0 * 14.0 * n * wl.n_trunc),
+        "gemm_fwd": ("mfma", flops_fwd / (L - 1)),
+        "gemm_wgrad": ("mfma", flops_fwd / (L - 1)),
+        "gemm_dgrad": ("mfma", 2.0 * wl.batch * wl.dims[1] * wl.dims[2] * wl.P),
+    }.get(args.kernel)
+    roofline = None
+    if per_launch and k_n:
+        bound, work = per_launch
+        avg_s = k_ms / k_n * 1e-3
+        if bound == "hbm":
+            ach, peak, unit = work / avg_s / 1e9, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, peak, unit = work / avg_s / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
+        roofline = {"kernel": args.kernel, "bound": bound, "achieved": ach, "peak": peak, "unit": unit,
+                    "frac": ach / peak, "traffic": None, "avg_launch_us": avg_s * 1e6, "launches": k_n,
+                    "work_per_launch": work}
+
+    out = {
+        "metric": "population member-steps/sec at 1 MI355X", "value": wl.P * args.steps / dt, "unit": "member-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "P": wl.P, "dims": wl.dims, "batch": wl.batch, "optimizer": "adam",
+                   "ready_interval": wl.ready_interval, "n_trunc": wl.n_trunc, "eval_rows": wl.n_eval,
+                   "exploit_rounds_in_timed_region": n_rounds},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, data, seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -191,6 +191,32 @@ pbt_status pbt_batched_gemm_bf16(const void* d_a, int64_t lda, int64_t stride_a,
                                  int64_t stride_c, int32_t c_is_bf16, int32_t M, int32_t N, int32_t K, int32_t batch,
                                  void* hip_stream);
 
+/* Kernel classes for pbt_timing_enable. */
+enum {
+  PBT_K_NONE = -1,
+  PBT_K_FETCH = 0,      /* mini-batch fetch                                  */
+  PBT_K_GEMM_FWD = 1,   /* forward GEMMs (bias + activation fused)           */
+  PBT_K_HEAD = 2,       /* output layer + loss + its backward kernels        */
+  PBT_K_GEMM_WGRAD = 3, /* weight-gradient GEMMs                             */
+  PBT_K_GEMM_DGRAD = 4, /* input-gradient GEMMs                              */
+  PBT_K_BIAS_GRAD = 5,  /* bias-gradient column sums                         */
+  PBT_K_OPTIMIZER = 6,  /* fused per-member optimiser                        */
+  PBT_K_RANK = 7,       /* rank + truncation select + perturb                */
+  PBT_K_COPY = 8,       /* exploit gather-copy                               */
+  PBT_K_FUSED_STEP = 9, /* LDS-resident fp32 step (small networks)           */
+  PBT_K_COUNT = 10
+};
+
+/* Measurement aid (for benchmarks; not part of the method): brackets every launch of one kernel
+ * class with a pair of HIP events on the stream it is launched on.  max_launches event pairs are
+ * created here, on the host; launches beyond that are not recorded.  kernel_class = PBT_K_NONE
+ * switches timing off and destroys the events.  Off by default. */
+pbt_status pbt_timing_enable(pbt_handle* h, int32_t kernel_class, int32_t max_launches);
+
+/* Synchronises the recorded events, returns the summed device time in milliseconds and the
+ * number of recorded launches since the last read, and rearms the event pool. */
+pbt_status pbt_timing_read(pbt_handle* h, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,10 @@ _ARR_DTYPE = {ARR_W32: np.float32, ARR_OPT0: np.float32, ARR_OPT1: np.float32, A
               ARR_T: np.int32, ARR_ORDER: np.int32, ARR_DONOR: np.int32, ARR_PARENT: np.int32}
 
 EXPORTS = ["pbt_query_sizes", "pbt_init", "pbt_step", "pbt_eval", "pbt_exploit_explore", "pbt_get_state",
-           "pbt_set_state", "pbt_state_ptr", "pbt_destroy", "pbt_last_error", "pbt_batched_gemm_bf16"]
+           "pbt_set_state", "pbt_state_ptr", "pbt_destroy", "pbt_last_error", "pbt_batched_gemm_bf16",
+           "pbt_timing_enable", "pbt_timing_read"]
+(K_NONE, K_FETCH, K_GEMM_FWD, K_HEAD, K_GEMM_WGRAD, K_GEMM_DGRAD, K_BIAS_GRAD, K_OPTIMIZER, K_RANK, K_COPY,
+ K_FUSED_STEP) = range(-1, 10)
 
 
 class PbtConfig(C.Structure):
@@ -68,6 +71,8 @@ def lib():
         L.pbt_last_error.argtypes = [vp]
         L.pbt_last_error.restype = C.c_char_p
         L.pbt_batched_gemm_bf16.argtypes = [vp, i64, i64, i32, vp, i64, i64, i32, vp, i64, i64, i32, i32, i32, i32, i32, vp]
+        L.pbt_timing_enable.argtypes = [vp, i32, i32]
+        L.pbt_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
         for name in EXPORTS:
             if name != "pbt_last_error":
                 getattr(L, name).restype = C.c_int
@@ -171,6 +176,14 @@ class Population:
     def exploit_explore(self, round_index, scores_override=None):
         p = None if scores_override is None else C.c_void_p(scores_override.data_ptr())
         self._check(lib().pbt_exploit_explore(self._h, round_index, p, self._stream()))
+
+    def timing_enable(self, kernel_class, max_launches=1):
+        self._check(lib().pbt_timing_enable(self._h, kernel_class, max_launches))
+
+    def timing_read(self):
+        ms, n = C.c_double(), C.c_int64()
+        self._check(lib().pbt_timing_read(self._h, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
 
     def _shape(self, which):
         P = self.cfg.P

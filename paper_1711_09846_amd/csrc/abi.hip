@@ -56,6 +56,10 @@ struct pbt_handle {
   char* state;
   char* scratch;
   std::string err;
+  // optional event timing of one kernel class
+  int timed_class = PBT_K_NONE;
+  std::vector<hipEvent_t> ev_start, ev_stop;
+  size_t ev_used = 0;
   template <class T> T* st(size_t off) const { return reinterpret_cast<T*>(state + off); }
   template <class T> T* sc(size_t off) const { return reinterpret_cast<T*>(scratch + off); }
 };
@@ -77,6 +81,19 @@ pbt_status fail(pbt_handle* h, pbt_status code, const char* fmt, ...) {
   do {                                                                                          \
     hipError_t e_ = (call);                                                                     \
     if (e_ != hipSuccess) return fail(h, PBT_EDEVICE, "%s failed: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+// Runs `call` (a launcher returning hipError_t); when its class is the timed one, brackets it
+// with an event pair on the same stream.
+#define PBT_LAUNCH(h, klass, s, call)                                                           \
+  do {                                                                                          \
+    const bool timed_ = (h)->timed_class == (klass) && (h)->ev_used < (h)->ev_start.size();     \
+    if (timed_) PBT_HIP(h, hipEventRecord((h)->ev_start[(h)->ev_used], s));                     \
+    PBT_HIP(h, call);                                                                           \
+    if (timed_) {                                                                               \
+      PBT_HIP(h, hipEventRecord((h)->ev_stop[(h)->ev_used], s));                                \
+      ++(h)->ev_used;                                                                           \
+    }                                                                                           \
   } while (0)
 
 pbt_status check_config(const pbt_config* c, Plan* pl) {
@@ -260,40 +277,43 @@ pbt_status step_bf16(pbt_handle* h, const float* train_x, const int32_t* train_y
   float* dlogits = h->sc<float>(p.o_dlogits);
   float* rowloss = h->sc<float>(p.o_rowloss);
 
-  PBT_HIP(h, gather_batch(train_x, train_y, c.n_train, c.dims[0], P, B, step, c.seed, h->sc<bf16_t>(p.o_act[0]), nullptr,
-                          Y, h->st<int32_t>(p.o_t), s));
+  PBT_LAUNCH(h, PBT_K_FETCH, s, gather_batch(train_x, train_y, c.n_train, c.dims[0], P, B, step, c.seed,
+                                             h->sc<bf16_t>(p.o_act[0]), nullptr, Y, h->st<int32_t>(p.o_t), s));
   for (int l = 0; l < L - 1; ++l) {
     GemmOperands o{h->sc<bf16_t>(p.o_act[l]), c.dims[l], (int64_t)B * c.dims[l], false,
                    W16 + p.lay.w_off[l], c.dims[l + 1], S, false, B, c.dims[l + 1], c.dims[l], P};
-    PBT_HIP(h, gemm_bias_act(o, W32 + p.lay.b_off[l], S, h->sc<bf16_t>(p.o_z[l]), h->sc<bf16_t>(p.o_act[l + 1]),
-                             c.dims[l + 1], (int64_t)B * c.dims[l + 1], c.act, s));
+    PBT_LAUNCH(h, PBT_K_GEMM_FWD, s, gemm_bias_act(o, W32 + p.lay.b_off[l], S, h->sc<bf16_t>(p.o_z[l]),
+                                                   h->sc<bf16_t>(p.o_act[l + 1]), c.dims[l + 1],
+                                                   (int64_t)B * c.dims[l + 1], c.act, s));
   }
   const int Kh = c.dims[L - 1], C = c.dims[L];
-  PBT_HIP(h, head_fwd_loss(h->sc<bf16_t>(p.o_act[L - 1]), (int64_t)B * Kh, W16 + p.lay.w_off[L - 1], S,
-                           W32 + p.lay.b_off[L - 1], S, Y, B, P, B, Kh, C, 1.f / (float)B, dlogits, rowloss, B, s));
-  PBT_HIP(h, row_reduce(rowloss, B, P, B, 1.f / (float)B, h->st<float>(p.o_loss), s));
-  PBT_HIP(h, head_wgrad(h->sc<bf16_t>(p.o_act[L - 1]), (int64_t)B * Kh, dlogits, P, B, Kh, C, G + p.lay.w_off[L - 1],
-                        G + p.lay.b_off[L - 1], S, s));
+  PBT_LAUNCH(h, PBT_K_HEAD, s, head_fwd_loss(h->sc<bf16_t>(p.o_act[L - 1]), (int64_t)B * Kh, W16 + p.lay.w_off[L - 1], S,
+                                             W32 + p.lay.b_off[L - 1], S, Y, B, P, B, Kh, C, 1.f / (float)B, dlogits,
+                                             rowloss, B, s));
+  PBT_LAUNCH(h, PBT_K_HEAD, s, row_reduce(rowloss, B, P, B, 1.f / (float)B, h->st<float>(p.o_loss), s));
+  PBT_LAUNCH(h, PBT_K_HEAD, s, head_wgrad(h->sc<bf16_t>(p.o_act[L - 1]), (int64_t)B * Kh, dlogits, P, B, Kh, C,
+                                          G + p.lay.w_off[L - 1], G + p.lay.b_off[L - 1], S, s));
   if (L >= 2)
-    PBT_HIP(h, head_dgrad(dlogits, W16 + p.lay.w_off[L - 1], S, h->sc<bf16_t>(p.o_z[L - 2]), h->sc<bf16_t>(p.o_dz[L - 2]),
-                          P, B, Kh, C, c.act, s));
+    PBT_LAUNCH(h, PBT_K_HEAD, s, head_dgrad(dlogits, W16 + p.lay.w_off[L - 1], S, h->sc<bf16_t>(p.o_z[L - 2]),
+                                            h->sc<bf16_t>(p.o_dz[L - 2]), P, B, Kh, C, c.act, s));
   for (int l = L - 2; l >= 0; --l) {
     const int K = c.dims[l], N = c.dims[l + 1];
     // dW_l[K][N] = X_l^T dZ_l (contraction over the B rows)
     GemmOperands wg{h->sc<bf16_t>(p.o_act[l]), K, (int64_t)B * K, true, h->sc<bf16_t>(p.o_dz[l]), N, (int64_t)B * N, false,
                     K, N, B, P};
-    PBT_HIP(h, gemm_store_f32(wg, G + p.lay.w_off[l], N, S, s));
-    PBT_HIP(h, bias_grad(h->sc<bf16_t>(p.o_dz[l]), P, B, N, G + p.lay.b_off[l], S, s));
+    PBT_LAUNCH(h, PBT_K_GEMM_WGRAD, s, gemm_store_f32(wg, G + p.lay.w_off[l], N, S, s));
+    PBT_LAUNCH(h, PBT_K_BIAS_GRAD, s, bias_grad(h->sc<bf16_t>(p.o_dz[l]), P, B, N, G + p.lay.b_off[l], S, s));
     if (l > 0) {
       // dZ_{l-1}[B][K] = (dZ_l W_l^T) * act'(Z_{l-1})
       GemmOperands dg{h->sc<bf16_t>(p.o_dz[l]), N, (int64_t)B * N, false, W16 + p.lay.w_off[l], N, S, true, B, K, N, P};
-      PBT_HIP(h, gemm_dgrad_act(dg, h->sc<bf16_t>(p.o_z[l - 1]), h->sc<bf16_t>(p.o_dz[l - 1]), K, (int64_t)B * K, c.act, s));
+      PBT_LAUNCH(h, PBT_K_GEMM_DGRAD, s, gemm_dgrad_act(dg, h->sc<bf16_t>(p.o_z[l - 1]), h->sc<bf16_t>(p.o_dz[l - 1]), K,
+                                                        (int64_t)B * K, c.act, s));
     }
   }
   OptArgs oa{W32, h->st<float>(p.o_opt0), c.optimizer == PBT_OPT_ADAM ? h->st<float>(p.o_opt1) : nullptr, W16, G,
              h->st<float>(p.o_hyper), h->st<int32_t>(p.o_t), S, P, c.n_hyper, c.optimizer, p.col_lr, p.col_beta1, p.col_wd,
              c.opt_const[0], c.opt_const[1], c.opt_const[2], c.opt_const[3]};
-  PBT_HIP(h, optimizer_step(oa, s));
+  PBT_LAUNCH(h, PBT_K_OPTIMIZER, s, optimizer_step(oa, s));
   return PBT_OK;
 }
 
@@ -389,7 +409,7 @@ pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs
     fa.x = x; fa.y = y; fa.n_rows = h->cfg.n_train;
     fa.step0 = (uint32_t)step_index; fa.n_steps = n_steps;
     fused_small_plan(fa, false);
-    PBT_HIP(h, fused_small_step(fa, s));
+    PBT_LAUNCH(h, PBT_K_FUSED_STEP, s, fused_small_step(fa, s));
     return PBT_OK;
   }
   for (int k = 0; k < n_steps; ++k) {
@@ -436,7 +456,7 @@ pbt_status pbt_exploit_explore(pbt_handle* h, int64_t round_index, const float* 
   a.f_lo = c.perturb_lo; a.f_hi = c.perturb_hi;
   for (int k = 0; k < 8; ++k) a.h_max[k] = k < c.n_hyper ? c.hyper_max[k] : INFINITY;
   a.round = (uint32_t)round_index; a.seed = c.seed;
-  PBT_HIP(h, rank_select_explore(a, s));
+  PBT_LAUNCH(h, PBT_K_RANK, s, rank_select_explore(a, s));
   CopyArrays ca;
   ca.n = 0;
   const int64_t S = p.lay.stride;
@@ -444,7 +464,7 @@ pbt_status pbt_exploit_explore(pbt_handle* h, int64_t round_index, const float* 
   ca.base[ca.n] = h->st<char>(p.o_opt0); ca.row_bytes[ca.n++] = S * 4;
   if (c.optimizer == PBT_OPT_ADAM) { ca.base[ca.n] = h->st<char>(p.o_opt1); ca.row_bytes[ca.n++] = S * 4; }
   if (c.compute_dtype == PBT_DTYPE_BF16) { ca.base[ca.n] = h->st<char>(p.o_w16); ca.row_bytes[ca.n++] = S * 2; }
-  PBT_HIP(h, gather_copy(ca, a.recip, a.donor, c.n_trunc, s));
+  PBT_LAUNCH(h, PBT_K_COPY, s, gather_copy(ca, a.recip, a.donor, c.n_trunc, s));
   return PBT_OK;
 }
 
@@ -494,7 +514,49 @@ pbt_status pbt_state_ptr(pbt_handle* h, int32_t which, void** d_ptr, size_t* byt
   return PBT_OK;
 }
 
+static void drop_events(pbt_handle* h) {
+  for (hipEvent_t e : h->ev_start) (void)hipEventDestroy(e);
+  for (hipEvent_t e : h->ev_stop) (void)hipEventDestroy(e);
+  h->ev_start.clear();
+  h->ev_stop.clear();
+  h->ev_used = 0;
+  h->timed_class = PBT_K_NONE;
+}
+
+pbt_status pbt_timing_enable(pbt_handle* h, int32_t kernel_class, int32_t max_launches) {
+  if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  if (kernel_class < PBT_K_NONE || kernel_class >= PBT_K_COUNT) return fail(h, PBT_EINVAL, "unknown kernel class %d", kernel_class);
+  drop_events(h);
+  if (kernel_class == PBT_K_NONE) return PBT_OK;
+  if (max_launches < 1 || max_launches > (1 << 20)) return fail(h, PBT_EINVAL, "max_launches outside 1..2^20");
+  for (int k = 0; k < max_launches; ++k) {
+    hipEvent_t a, b;
+    PBT_HIP(h, hipEventCreate(&a));
+    h->ev_start.push_back(a);
+    PBT_HIP(h, hipEventCreate(&b));
+    h->ev_stop.push_back(b);
+  }
+  h->timed_class = kernel_class;
+  return PBT_OK;
+}
+
+pbt_status pbt_timing_read(pbt_handle* h, double* total_ms, int64_t* launches) {
+  if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  double sum = 0.0;
+  for (size_t k = 0; k < h->ev_used; ++k) {
+    PBT_HIP(h, hipEventSynchronize(h->ev_stop[k]));
+    float ms = 0.f;
+    PBT_HIP(h, hipEventElapsedTime(&ms, h->ev_start[k], h->ev_stop[k]));
+    sum += ms;
+  }
+  if (total_ms) *total_ms = sum;
+  if (launches) *launches = (int64_t)h->ev_used;
+  h->ev_used = 0;
+  return PBT_OK;
+}
+
 pbt_status pbt_destroy(pbt_handle* h) {
+  if (h) drop_events(h);
   delete h;
   return PBT_OK;
 }
