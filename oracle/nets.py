@@ -85,17 +85,16 @@ def mlp_forward(params, x, hidden_act, out_act=ACT_NONE, q=identity):
 
 def mlp_backward(params, cache, d_out, hidden_act, out_act=ACT_NONE, q=identity):
     """Given dLoss/d(output), returns ([(dW, db), ...], dLoss/d(input)).
-    With a storage rounding q, the gradient with respect to every hidden
-    pre-activation is rounded before it enters the next contractions."""
+    With a storage rounding q, the gradient with respect to every layer's
+    pre-activation (the logits included) is rounded before it enters the
+    contractions that produce weight, bias and input gradients."""
     ins, zs = cache
     L = len(params)
     grads = [None] * L
     da = d_out
     for l in range(L - 1, -1, -1):
         W, _ = params[l]
-        dz = da * act_grad(zs[l], hidden_act if l < L - 1 else out_act)
-        if l < L - 1:
-            dz = q(dz)
+        dz = q(da * act_grad(zs[l], hidden_act if l < L - 1 else out_act))
         grads[l] = (ins[l].T @ dz, dz.sum(axis=0))
         da = dz @ q(W).T
     return grads, da

@@ -184,7 +184,7 @@ pbt_status make_plan(const pbt_config* c, Plan* pl) {
     }
     if (L >= 2 && c->dims[L - 1] % 8) return fail(nullptr, PBT_EUNSUPPORTED, "last hidden width must be a multiple of 8");
     pl->o_y = w.take(P * B * 4);
-    pl->o_dlogits = w.take((size_t)P * B * c->dims[L] * 4);
+    pl->o_dlogits = w.take((size_t)P * B * 32 * 2);  // bf16, row pitch 32
     pl->o_rowloss = w.take(P * B * 4);
     for (int l = 0; l < L; ++l) {
       pl->o_act[l] = w.take((size_t)P * B * c->dims[l] * 2);       // input of layer l
@@ -274,7 +274,7 @@ pbt_status step_bf16(pbt_handle* h, const float* train_x, const int32_t* train_y
   bf16_t* W16 = h->st<bf16_t>(p.o_w16);
   float* G = h->sc<float>(p.o_grad);
   int32_t* Y = h->sc<int32_t>(p.o_y);
-  float* dlogits = h->sc<float>(p.o_dlogits);
+  bf16_t* dlogits = h->sc<bf16_t>(p.o_dlogits);
   float* rowloss = h->sc<float>(p.o_rowloss);
 
   PBT_LAUNCH(h, PBT_K_FETCH, s, gather_batch(train_x, train_y, c.n_train, c.dims[0], P, B, step, c.seed,
@@ -291,8 +291,13 @@ pbt_status step_bf16(pbt_handle* h, const float* train_x, const int32_t* train_y
                                              W32 + p.lay.b_off[L - 1], S, Y, B, P, B, Kh, C, 1.f / (float)B, dlogits,
                                              rowloss, B, s));
   PBT_LAUNCH(h, PBT_K_HEAD, s, row_reduce(rowloss, B, P, B, 1.f / (float)B, h->st<float>(p.o_loss), s));
-  PBT_LAUNCH(h, PBT_K_HEAD, s, head_wgrad(h->sc<bf16_t>(p.o_act[L - 1]), (int64_t)B * Kh, dlogits, P, B, Kh, C,
-                                          G + p.lay.w_off[L - 1], G + p.lay.b_off[L - 1], S, s));
+  {
+    // dW_head[Kh][C] = X^T dlogits (contraction over the B rows), db_head = column sums
+    GemmOperands wg{h->sc<bf16_t>(p.o_act[L - 1]), Kh, (int64_t)B * Kh, true, dlogits, 32, (int64_t)B * 32, false,
+                    Kh, C, B, P};
+    PBT_LAUNCH(h, PBT_K_HEAD, s, gemm_store_f32(wg, G + p.lay.w_off[L - 1], C, S, s));
+    PBT_LAUNCH(h, PBT_K_HEAD, s, bias_grad(dlogits, P, B, C, 32, G + p.lay.b_off[L - 1], S, s));
+  }
   if (L >= 2)
     PBT_LAUNCH(h, PBT_K_HEAD, s, head_dgrad(dlogits, W16 + p.lay.w_off[L - 1], S, h->sc<bf16_t>(p.o_z[L - 2]),
                                             h->sc<bf16_t>(p.o_dz[L - 2]), P, B, Kh, C, c.act, s));
@@ -302,7 +307,7 @@ pbt_status step_bf16(pbt_handle* h, const float* train_x, const int32_t* train_y
     GemmOperands wg{h->sc<bf16_t>(p.o_act[l]), K, (int64_t)B * K, true, h->sc<bf16_t>(p.o_dz[l]), N, (int64_t)B * N, false,
                     K, N, B, P};
     PBT_LAUNCH(h, PBT_K_GEMM_WGRAD, s, gemm_store_f32(wg, G + p.lay.w_off[l], N, S, s));
-    PBT_LAUNCH(h, PBT_K_BIAS_GRAD, s, bias_grad(h->sc<bf16_t>(p.o_dz[l]), P, B, N, G + p.lay.b_off[l], S, s));
+    PBT_LAUNCH(h, PBT_K_BIAS_GRAD, s, bias_grad(h->sc<bf16_t>(p.o_dz[l]), P, B, N, N, G + p.lay.b_off[l], S, s));
     if (l > 0) {
       // dZ_{l-1}[B][K] = (dZ_l W_l^T) * act'(Z_{l-1})
       GemmOperands dg{h->sc<bf16_t>(p.o_dz[l]), N, (int64_t)B * N, false, W16 + p.lay.w_off[l], N, S, true, B, K, N, P};

@@ -1,0 +1,176 @@
+// Output layer of the classifier networks on the matrix cores: a "skinny" contraction whose
+// output width C (classes) is at most 32.
+//
+//   forward   logits[rows][C] = A[rows][K] W[K][C] + b, fused with softmax cross-entropy and its
+//             gradient with respect to the logits (rounded to bf16, row pitch 32, zero padded);
+//   backward  dZprev[rows][K] = (dlogits[rows][32] W^T) * act'(Zprev).
+//
+// One wavefront owns 32 rows.  The A operand of v_mfma_f32_32x32x16_bf16 (row = lane % 32, eight
+// consecutive k per lane) is exactly a 16-byte global load of a K-contiguous row, so the large
+// operand never passes through LDS; only the small weight matrix is staged there (transposed to
+// K-contiguous, which is what the B operand needs).
+#include "common.h"
+#include "internal.h"
+
+namespace pbt {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+constexpr int HEAD_NP = 32;         // padded class count = MFMA tile width
+constexpr int HEAD_ROWS = 128;      // rows per workgroup (4 wavefronts x 32)
+
+__device__ __forceinline__ bf16x8_t load_frag(const bf16_t* p, bool valid) {
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (valid) v = *reinterpret_cast<const uint4*>(p);
+  return *reinterpret_cast<bf16x8_t*>(&v);
+}
+
+// grid (ceil(rows / 128), P); dynamic LDS = 32 * (K + 8) bf16 + 128 * 33 floats
+__global__ __launch_bounds__(256) void head_fwd_loss_kernel(const bf16_t* __restrict__ A, int64_t sa,
+                                                            const bf16_t* __restrict__ W16, int64_t sw,
+                                                            const float* __restrict__ bias, int64_t sbias,
+                                                            const int32_t* __restrict__ labels, int64_t sy, int rows,
+                                                            int K, int C, float gscale, bf16_t* __restrict__ dlogits,
+                                                            float* __restrict__ rowloss, int64_t srowloss) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int pitch = K + 8;
+  bf16_t* Wt = reinterpret_cast<bf16_t*>(smem);                                  // [32][K + 8], rows >= C unused
+  float* Lg = reinterpret_cast<float*>(smem + (size_t)HEAD_NP * pitch * 2);      // [128][33]
+  const int i = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const bf16_t* __restrict__ W = W16 + (int64_t)i * sw;
+  for (int e = threadIdx.x; e < K * C; e += 256) {
+    const int k = e / C, c = e - k * C;
+    Wt[c * pitch + k] = W[e];
+  }
+  // zero the padded class rows once so that unused accumulator columns stay finite
+  for (int e = threadIdx.x; e < (HEAD_NP - C) * K; e += 256) {
+    const int c = C + e / K, k = e % K;
+    Wt[c * pitch + k] = 0;
+  }
+  __syncthreads();
+
+  const int r_lane = blockIdx.x * HEAD_ROWS + wave * 32 + (lane & 31);
+  const int kq = (lane >> 5) * 8;
+  const bf16_t* __restrict__ arow = A + (int64_t)i * sa + (int64_t)r_lane * K + kq;
+  const bf16_t* brow = Wt + (lane & 31) * pitch + kq;
+  const bool row_ok = r_lane < rows;
+  f32x16_t acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+#pragma unroll 4
+  for (int k0 = 0; k0 < K; k0 += 16) {
+    const bool k_ok = k0 + kq + 8 <= K;
+    const bf16x8_t af = load_frag(arow + k0, row_ok && k_ok);
+    const bf16x8_t bfr = load_frag(brow + k0, k_ok);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfr, acc, 0, 0, 0);
+  }
+#pragma unroll
+  for (int e = 0; e < 16; ++e)
+    Lg[(wave * 32 + 8 * (e / 4) + 4 * (lane >> 5) + (e % 4)) * 33 + (lane & 31)] = acc[e];
+  __syncthreads();
+
+  if (threadIdx.x < HEAD_ROWS) {
+    const int r = blockIdx.x * HEAD_ROWS + threadIdx.x;
+    if (r < rows) {
+      const float* __restrict__ b = bias + (int64_t)i * sbias;
+      float* lg = Lg + threadIdx.x * 33;
+      float mx = -INFINITY;
+      int cm = 0;
+      for (int c = 0; c < C; ++c) {
+        lg[c] += b[c];
+        if (lg[c] > mx) { mx = lg[c]; cm = c; }
+      }
+      // log-sum-exp with the largest term split off: lse = mx + log1p(sum of the others)
+      const int y = labels[(int64_t)i * sy + r];
+      float rest = 0.f, others = (y == cm) ? 0.f : 1.f;
+      for (int c = 0; c < C; ++c) {
+        if (c == cm) continue;
+        const float ex = expf(lg[c] - mx);
+        rest += ex;
+        if (c != y) others += ex;
+      }
+      rowloss[(int64_t)i * srowloss + r] = log1pf(rest) + (mx - lg[y]);
+      if (dlogits) {
+        // softmax_y - 1 = -(sum of the other classes' terms) / S: no cancellation as softmax_y -> 1
+        const float inv = 1.f / (1.f + rest);
+        bf16_t* __restrict__ d = dlogits + ((int64_t)i * rows + r) * HEAD_NP;
+        for (int c = 0; c < HEAD_NP; ++c) {
+          float v = 0.f;
+          if (c < C) v = (c == y ? -others * inv : expf(lg[c] - mx) * inv) * gscale;
+          d[c] = f2bf(v);
+        }
+      }
+    }
+  }
+}
+
+hipError_t head_fwd_loss(const bf16_t* A, int64_t sa, const bf16_t* W16, int64_t sw, const float* bias, int64_t sbias,
+                         const int32_t* labels, int64_t sy, int P, int rows, int K, int C, float gscale,
+                         bf16_t* dlogits, float* rowloss, int64_t srowloss, hipStream_t s) {
+  if (C > HEAD_NP || C < 1 || K % 8) return hipErrorInvalidValue;
+  const size_t lds = (size_t)HEAD_NP * (K + 8) * 2 + (size_t)HEAD_ROWS * 33 * 4;
+  if (lds > 160 * 1024) return hipErrorInvalidValue;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_fwd_loss_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  dim3 grid((rows + HEAD_ROWS - 1) / HEAD_ROWS, P);
+  hipLaunchKernelGGL(head_fwd_loss_kernel, grid, dim3(256), lds, s, A, sa, W16, sw, bias, sbias, labels, sy, rows, K, C,
+                     gscale, dlogits, rowloss, srowloss);
+  return hipGetLastError();
+}
+
+// grid (ceil(K / 64), ceil(rows / 128), P).  The contraction runs over the 32 padded classes, i.e.
+// two MFMAs per 32x32 output block (one when C <= 16).
+constexpr int DG_COLS = 64;
+__global__ __launch_bounds__(256) void head_dgrad_kernel(const bf16_t* __restrict__ dlogits,
+                                                         const bf16_t* __restrict__ W16, int64_t sw,
+                                                         const bf16_t* __restrict__ Zprev, bf16_t* __restrict__ dZprev,
+                                                         int rows, int K, int C, int act) {
+  __shared__ __attribute__((aligned(16))) bf16_t Ws[DG_COLS * 40];   // [64 columns k][32 classes + 8]
+  const int i = blockIdx.z;
+  const int k_base = blockIdx.x * DG_COLS;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const bf16_t* __restrict__ W = W16 + (int64_t)i * sw;
+  for (int e = threadIdx.x; e < DG_COLS * HEAD_NP; e += 256) {
+    const int kk = e / HEAD_NP, c = e % HEAD_NP;
+    const int k = k_base + kk;
+    Ws[kk * 40 + c] = (k < K && c < C) ? W[(int64_t)k * C + c] : (bf16_t)0;
+  }
+  __syncthreads();
+  const int r_lane = blockIdx.y * HEAD_ROWS + wave * 32 + (lane & 31);
+  const int cq = (lane >> 5) * 8;
+  const bf16_t* __restrict__ drow = dlogits + ((int64_t)i * rows + r_lane) * HEAD_NP + cq;
+  const bool row_ok = r_lane < rows;
+  const bf16x8_t a0 = load_frag(drow, row_ok);
+  const bf16x8_t a1 = load_frag(drow + 16, row_ok && C > 16);
+#pragma unroll
+  for (int j = 0; j < DG_COLS / 32; ++j) {
+    f32x16_t acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    const bf16_t* brow = Ws + (j * 32 + (lane & 31)) * 40 + cq;
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, load_frag(brow, true), acc, 0, 0, 0);
+    if (C > 16) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, load_frag(brow + 16, true), acc, 0, 0, 0);
+    const int k = k_base + j * 32 + (lane & 31);
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int r = blockIdx.y * HEAD_ROWS + wave * 32 + 8 * (e / 4) + 4 * (lane >> 5) + (e % 4);
+      if (r < rows && k < K) {
+        const int64_t o = ((int64_t)i * rows + r) * K + k;
+        dZprev[o] = f2bf(acc[e] * act_bwd(bf2f(Zprev[o]), act));
+      }
+    }
+  }
+}
+
+hipError_t head_dgrad(const bf16_t* dlogits, const bf16_t* W16, int64_t sw, const bf16_t* Zprev, bf16_t* dZprev, int P,
+                      int rows, int K, int C, int act, hipStream_t s) {
+  if (C > HEAD_NP || C < 1) return hipErrorInvalidValue;
+  dim3 grid((K + DG_COLS - 1) / DG_COLS, (rows + HEAD_ROWS - 1) / HEAD_ROWS, P);
+  hipLaunchKernelGGL(head_dgrad_kernel, grid, dim3(256), 0, s, dlogits, W16, sw, Zprev, dZprev, rows, K, C, act);
+  return hipGetLastError();
+}
+
+}  // namespace pbt

@@ -34,21 +34,19 @@ hipError_t f32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t s);
 hipError_t gather_batch(const float* train_x, const int32_t* train_y, int n_train, int d, int P, int B, uint32_t step,
                         uint64_t seed, bf16_t* X16, float* X32, int32_t* Y, int32_t* t, hipStream_t s);
 
-// Output layer + softmax cross-entropy.  logits = A W + b with A [P][rows][K] (bf16, batch stride
-// sa; sa = 0 shares A), W bf16 [K][C] at W16 + member*sw, b float at bias + member*sbias.
-// Writes rowloss[P][rows] and, when dlogits != null, dlogits[P][rows][C] = (softmax - onehot) * gscale.
+// head.hip -- output layer (C <= 32 classes) + softmax cross-entropy on the matrix cores.
+// logits = A W + b with A [P][rows][K] (bf16, batch stride sa; sa = 0 shares A), W bf16 [K][C] at
+// W16 + member*sw, b float at bias + member*sbias.  Writes rowloss[member*srowloss + r] and, when
+// dlogits != null, dlogits[P][rows][32] (bf16, zero padded) = (softmax - onehot) * gscale.
 // labels are [rows] shared (sy = 0) or per member (sy = rows).
 hipError_t head_fwd_loss(const bf16_t* A, int64_t sa, const bf16_t* W16, int64_t sw, const float* bias, int64_t sbias,
                          const int32_t* labels, int64_t sy, int P, int rows, int K, int C, float gscale,
-                         float* dlogits, float* rowloss, int64_t srowloss, hipStream_t s);
-// dW[K][C] = A^T dlogits, db[C] = column sums of dlogits (floats into G at the given offsets).
-hipError_t head_wgrad(const bf16_t* A, int64_t sa, const float* dlogits, int P, int rows, int K, int C, float* dW,
-                      float* db, int64_t sg, hipStream_t s);
+                         bf16_t* dlogits, float* rowloss, int64_t srowloss, hipStream_t s);
 // dZprev[P][rows][K] = (dlogits W^T) * act'(Zprev)
-hipError_t head_dgrad(const float* dlogits, const bf16_t* W16, int64_t sw, const bf16_t* Zprev, bf16_t* dZprev, int P,
+hipError_t head_dgrad(const bf16_t* dlogits, const bf16_t* W16, int64_t sw, const bf16_t* Zprev, bf16_t* dZprev, int P,
                       int rows, int K, int C, int act, hipStream_t s);
-// db[n] = sum over rows of dZ[P][rows][N]
-hipError_t bias_grad(const bf16_t* dZ, int P, int rows, int N, float* db, int64_t sg, hipStream_t s);
+// db[n] = sum over rows of dZ[P][rows][ld], first N columns
+hipError_t bias_grad(const bf16_t* dZ, int P, int rows, int N, int64_t ld, float* db, int64_t sg, hipStream_t s);
 // out[i] = scale * sum_r rowval[i][r]   (one wavefront per member, fixed order)
 hipError_t row_reduce(const float* rowval, int64_t srow, int P, int rows, float scale, float* out, hipStream_t s);
 

@@ -69,148 +69,45 @@ hipError_t gather_batch(const float* train_x, const int32_t* train_y, int n_trai
   return hipGetLastError();
 }
 
-// ---- output layer + softmax cross-entropy ----------------------------------------------------
-// One wavefront per row: lanes stride over K, C (<= 32) running sums per lane, butterfly
-// reduction, then every lane holds all logits and evaluates the softmax redundantly.
-
-constexpr int HEAD_CMAX = 32;
-constexpr int HEAD_ROWS_PER_WG = 8;  // 4 wavefronts x 2 rows
-
-__global__ __launch_bounds__(256) void head_fwd_loss_kernel(const bf16_t* __restrict__ A, int64_t sa,
-                                                            const bf16_t* __restrict__ W16, int64_t sw,
-                                                            const float* __restrict__ bias, int64_t sbias,
-                                                            const int32_t* __restrict__ labels, int64_t sy, int rows,
-                                                            int K, int C, float gscale, float* __restrict__ dlogits,
-                                                            float* __restrict__ rowloss, int64_t srowloss) {
-  const int i = blockIdx.y;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const bf16_t* __restrict__ W = W16 + (int64_t)i * sw;
-  const float* __restrict__ b = bias + (int64_t)i * sbias;
-  for (int rr = wave; rr < HEAD_ROWS_PER_WG; rr += 4) {
-    const int r = blockIdx.x * HEAD_ROWS_PER_WG + rr;
-    if (r >= rows) break;
-    const bf16_t* __restrict__ a = A + (int64_t)i * sa + (int64_t)r * K;
-    float acc[HEAD_CMAX];
-#pragma unroll
-    for (int c = 0; c < HEAD_CMAX; ++c) acc[c] = 0.f;
-    for (int k = lane; k < K; k += 64) {
-      const float av = bf2f(a[k]);
-      const bf16_t* __restrict__ wr = W + (int64_t)k * C;
-#pragma unroll
-      for (int c = 0; c < HEAD_CMAX; ++c)
-        if (c < C) acc[c] = fmaf(av, bf2f(wr[c]), acc[c]);
-    }
-    float mx = -INFINITY;
-    int cm = 0;
-#pragma unroll
-    for (int c = 0; c < HEAD_CMAX; ++c)
-      if (c < C) {
-        acc[c] = wave_sum(acc[c]) + b[c];
-        if (acc[c] > mx) { mx = acc[c]; cm = c; }
-      }
-    // log-sum-exp with the largest term split off: lse = mx + log1p(sum of the others)
-    float rest = 0.f;
-#pragma unroll
-    for (int c = 0; c < HEAD_CMAX; ++c)
-      if (c < C && c != cm) rest += expf(acc[c] - mx);
-    const float l1p = log1pf(rest), inv = 1.f / (1.f + rest);
-    const int y = labels[(int64_t)i * sy + r];
-    // softmax_y - 1 = -(sum of the other classes' terms) / S: no cancellation when softmax_y -> 1
-    float ly = 0.f, others = (y == cm) ? 0.f : 1.f;
-#pragma unroll
-    for (int c = 0; c < HEAD_CMAX; ++c)
-      if (c < C) {
-        if (c == y) ly = acc[c];
-        else if (c != cm) others += expf(acc[c] - mx);
-      }
-#pragma unroll
-    for (int c = 0; c < HEAD_CMAX; ++c)
-      if (c < C && dlogits && lane == c)
-        dlogits[((int64_t)i * rows + r) * C + c] = (c == y ? -others * inv : expf(acc[c] - mx) * inv) * gscale;
-    if (lane == 0) rowloss[(int64_t)i * srowloss + r] = l1p + (mx - ly);
-  }
-}
-hipError_t head_fwd_loss(const bf16_t* A, int64_t sa, const bf16_t* W16, int64_t sw, const float* bias, int64_t sbias,
-                         const int32_t* labels, int64_t sy, int P, int rows, int K, int C, float gscale,
-                         float* dlogits, float* rowloss, int64_t srowloss, hipStream_t s) {
-  if (C > HEAD_CMAX) return hipErrorInvalidValue;
-  dim3 grid((rows + HEAD_ROWS_PER_WG - 1) / HEAD_ROWS_PER_WG, P);
-  hipLaunchKernelGGL(head_fwd_loss_kernel, grid, dim3(256), 0, s, A, sa, W16, sw, bias, sbias, labels, sy, rows, K, C,
-                     gscale, dlogits, rowloss, srowloss);
-  return hipGetLastError();
-}
-
-// dW[k][c] = sum_r A[r][k] dlogits[r][c]: one thread per k, rows in order; block 0 also sums db.
-__global__ __launch_bounds__(256) void head_wgrad_kernel(const bf16_t* __restrict__ A, int64_t sa,
-                                                         const float* __restrict__ dlogits, int rows, int K, int C,
-                                                         float* __restrict__ dW, float* __restrict__ db, int64_t sg) {
-  const int i = blockIdx.y;
-  const int k = blockIdx.x * 256 + threadIdx.x;
-  const float* __restrict__ dl = dlogits + (int64_t)i * rows * C;
-  if (k < K) {
-    const bf16_t* __restrict__ a = A + (int64_t)i * sa + k;
-    float acc[HEAD_CMAX];
-#pragma unroll
-    for (int c = 0; c < HEAD_CMAX; ++c) acc[c] = 0.f;
-    for (int r = 0; r < rows; ++r) {
-      const float av = bf2f(a[(int64_t)r * K]);
-#pragma unroll
-      for (int c = 0; c < HEAD_CMAX; ++c)
-        if (c < C) acc[c] = fmaf(av, dl[r * C + c], acc[c]);
-    }
-    float* __restrict__ o = dW + (int64_t)i * sg + (int64_t)k * C;
-#pragma unroll
-    for (int c = 0; c < HEAD_CMAX; ++c)
-      if (c < C) o[c] = acc[c];
-  }
-  if (blockIdx.x == 0 && threadIdx.x < C) {
-    float sacc = 0.f;
-    for (int r = 0; r < rows; ++r) sacc += dl[r * C + threadIdx.x];
-    db[(int64_t)i * sg + threadIdx.x] = sacc;
-  }
-}
-hipError_t head_wgrad(const bf16_t* A, int64_t sa, const float* dlogits, int P, int rows, int K, int C, float* dW,
-                      float* db, int64_t sg, hipStream_t s) {
-  if (C > HEAD_CMAX) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(head_wgrad_kernel, dim3((K + 255) / 256, P), dim3(256), 0, s, A, sa, dlogits, rows, K, C, dW, db, sg);
-  return hipGetLastError();
-}
-
-// dZprev[r][k] = (sum_c dlogits[r][c] W[k][c]) * act'(Zprev[r][k]); one thread per (r, k).
-__global__ __launch_bounds__(256) void head_dgrad_kernel(const float* __restrict__ dlogits,
-                                                         const bf16_t* __restrict__ W16, int64_t sw,
-                                                         const bf16_t* __restrict__ Zprev, bf16_t* __restrict__ dZprev,
-                                                         int rows, int K, int C, int act) {
-  const int i = blockIdx.z, r = blockIdx.y;
-  const int k = blockIdx.x * 256 + threadIdx.x;
-  if (k >= K) return;
-  const float* __restrict__ dl = dlogits + ((int64_t)i * rows + r) * C;
-  const bf16_t* __restrict__ w = W16 + (int64_t)i * sw + (int64_t)k * C;
-  float acc = 0.f;
-  for (int c = 0; c < C; ++c) acc = fmaf(dl[c], bf2f(w[c]), acc);
-  const int64_t o = ((int64_t)i * rows + r) * K + k;
-  dZprev[o] = f2bf(acc * act_bwd(bf2f(Zprev[o]), act));
-}
-hipError_t head_dgrad(const float* dlogits, const bf16_t* W16, int64_t sw, const bf16_t* Zprev, bf16_t* dZprev, int P,
-                      int rows, int K, int C, int act, hipStream_t s) {
-  hipLaunchKernelGGL(head_dgrad_kernel, dim3((K + 255) / 256, rows, P), dim3(256), 0, s, dlogits, W16, sw, Zprev, dZprev,
-                     rows, K, C, act);
-  return hipGetLastError();
-}
-
-// db[n] = sum_r dZ[r][n]; one thread per column, rows in order.
-__global__ __launch_bounds__(256) void bias_grad_kernel(const bf16_t* __restrict__ dZ, int rows, int N,
+// db[n] = sum_r dZ[r][n].  A workgroup covers 512 columns: 64 threads x 8 columns (one 16-byte load
+// per row) times 4 row groups; the four partial sums are combined through LDS in fixed order.
+__global__ __launch_bounds__(256) void bias_grad_kernel(const bf16_t* __restrict__ dZ, int rows, int N, int64_t ld,
                                                         float* __restrict__ db, int64_t sg) {
+  __shared__ float part[4][512];
   const int i = blockIdx.y;
-  const int n = blockIdx.x * 256 + threadIdx.x;
-  if (n >= N) return;
-  const bf16_t* __restrict__ p = dZ + (int64_t)i * rows * N + n;
-  float acc = 0.f;
-  for (int r = 0; r < rows; ++r) acc += bf2f(p[(int64_t)r * N]);
-  db[(int64_t)i * sg + n] = acc;
+  const int cg = threadIdx.x & 63, rg = threadIdx.x >> 6;
+  const int n0 = blockIdx.x * 512 + cg * 8;
+  float acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+  if (n0 < N) {
+    const bf16_t* __restrict__ p = dZ + (int64_t)i * rows * ld + n0;
+    const bool full = n0 + 8 <= N;
+    for (int r = rg; r < rows; r += 4) {
+      if (full) {
+        const uint4 v = *reinterpret_cast<const uint4*>(p + (int64_t)r * ld);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          acc[2 * q] += __uint_as_float(w[q] << 16);
+          acc[2 * q + 1] += __uint_as_float(w[q] & 0xffff0000u);
+        }
+      } else {
+        for (int e = 0; e < N - n0; ++e) acc[e] += bf2f(p[(int64_t)r * ld + e]);
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) part[rg][cg * 8 + e] = acc[e];
+  __syncthreads();
+  for (int c = threadIdx.x; c < 512; c += 256) {
+    const int n = blockIdx.x * 512 + c;
+    if (n < N) db[(int64_t)i * sg + n] = ((part[0][c] + part[1][c]) + part[2][c]) + part[3][c];
+  }
 }
-hipError_t bias_grad(const bf16_t* dZ, int P, int rows, int N, float* db, int64_t sg, hipStream_t s) {
-  hipLaunchKernelGGL(bias_grad_kernel, dim3((N + 255) / 256, P), dim3(256), 0, s, dZ, rows, N, db, sg);
+hipError_t bias_grad(const bf16_t* dZ, int P, int rows, int N, int64_t ld, float* db, int64_t sg, hipStream_t s) {
+  if (ld % 8) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(bias_grad_kernel, dim3((N + 511) / 512, P), dim3(256), 0, s, dZ, rows, N, ld, db, sg);
   return hipGetLastError();
 }
 
@@ -239,7 +136,19 @@ hipError_t row_reduce(const float* rowval, int64_t srow, int P, int rows, float 
 //                 theta <- theta - lr ( (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps) + wd theta )
 //   RMSProp       s <- rho s + (1-rho) g^2;  theta <- theta - lr g / sqrt(s + eps)
 
-constexpr int OPT_VEC_PER_THREAD = 2;  // float4 vectors per thread
+constexpr int OPT_VEC_PER_THREAD = 1;  // float4 vectors per thread
+
+// theta, gradient and optimiser state are touched once per step: stream them past the caches
+// (nontemporal), so that the bf16 shadow, which the next step's GEMMs read, is what stays resident.
+typedef float vf4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 stream_load(const float* p) {
+  const vf4_t v = __builtin_nontemporal_load(reinterpret_cast<const vf4_t*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void stream_store(float4 x, float* p) {
+  const vf4_t v = {x.x, x.y, x.z, x.w};
+  __builtin_nontemporal_store(v, reinterpret_cast<vf4_t*>(p));
+}
 
 template <int OPT>
 __global__ __launch_bounds__(256) void optimizer_kernel(OptArgs a) {
@@ -261,9 +170,9 @@ __global__ __launch_bounds__(256) void optimizer_kernel(OptArgs a) {
     const int64_t v = ((int64_t)blockIdx.x * OPT_VEC_PER_THREAD + u) * 256 + threadIdx.x;
     if (v >= nvec) break;
     const int64_t o = base + v * 4;
-    float4 w = *reinterpret_cast<const float4*>(a.W32 + o);
-    const float4 g = *reinterpret_cast<const float4*>(a.G + o);
-    float4 s0 = *reinterpret_cast<const float4*>(a.S0 + o);
+    float4 w = stream_load(a.W32 + o);
+    const float4 g = stream_load(a.G + o);
+    float4 s0 = stream_load(a.S0 + o);
     float* wp = reinterpret_cast<float*>(&w);
     const float* gp = reinterpret_cast<const float*>(&g);
     float* s0p = reinterpret_cast<float*>(&s0);
@@ -274,7 +183,7 @@ __global__ __launch_bounds__(256) void optimizer_kernel(OptArgs a) {
         wp[e] = wp[e] - lr * s0p[e];
       }
     } else if (OPT == 1) {
-      float4 s1 = *reinterpret_cast<const float4*>(a.S1 + o);
+      float4 s1 = stream_load(a.S1 + o);
       float* s1p = reinterpret_cast<float*>(&s1);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -284,7 +193,7 @@ __global__ __launch_bounds__(256) void optimizer_kernel(OptArgs a) {
         const float vh = s1p[e] * inv_bc2;
         wp[e] = wp[e] - lr * (mh / (sqrtf(vh) + a.c2) + wd * wp[e]);
       }
-      *reinterpret_cast<float4*>(a.S1 + o) = s1;
+      stream_store(s1, a.S1 + o);
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -292,8 +201,8 @@ __global__ __launch_bounds__(256) void optimizer_kernel(OptArgs a) {
         wp[e] = wp[e] - lr * gp[e] / sqrtf(s0p[e] + a.c1);
       }
     }
-    *reinterpret_cast<float4*>(a.W32 + o) = w;
-    *reinterpret_cast<float4*>(a.S0 + o) = s0;
+    stream_store(w, a.W32 + o);
+    stream_store(s0, a.S0 + o);
     if (a.W16) {
       uint2 pk;
       pk.x = f2bf(wp[0]) | ((uint32_t)f2bf(wp[1]) << 16);
