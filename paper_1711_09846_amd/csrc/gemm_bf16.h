@@ -268,18 +268,12 @@ struct EpiDgradAct {
 
 // Host-side launcher: picks the tile shape from the layout flags.  Returns hipSuccess or the
 // launch error.  Caller guarantees 16-byte alignment of pitches / strides / bases.
-template <class Epilogue>
-hipError_t launch_gemm_bf16(const bf16_t* A, int64_t lda, int64_t sa, bool a_m_contig, const bf16_t* B, int64_t ldb,
-                            int64_t sb, bool b_k_contig, int M, int N, int K, int batch, const Epilogue& epi,
-                            hipStream_t stream) {
-  constexpr int BM = 128, BN = 128;
-  GemmArgs g;
-  g.A = A; g.lda = lda; g.sa = sa;
-  g.B = B; g.ldb = ldb; g.sb = sb;
-  g.M = M; g.N = N; g.K = K; g.batch = batch;
-  g.tiles_m = (M + BM - 1) / BM;
-  g.tiles_n = (N + BN - 1) / BN;
-  const int64_t total = (int64_t)g.tiles_m * g.tiles_n * batch;
+template <int BM, int BN, class Epilogue>
+hipError_t launch_gemm_tile(const GemmArgs& g0, bool a_m_contig, bool b_k_contig, const Epilogue& epi, hipStream_t stream) {
+  GemmArgs g = g0;
+  g.tiles_m = (g.M + BM - 1) / BM;
+  g.tiles_n = (g.N + BN - 1) / BN;
+  const int64_t total = (int64_t)g.tiles_m * g.tiles_n * g.batch;
   if (total <= 0 || total > 0x7fffffff) return hipErrorInvalidValue;
   dim3 grid((unsigned)total), block(GEMM_THREADS);
   if (!a_m_contig && !b_k_contig)
@@ -291,6 +285,23 @@ hipError_t launch_gemm_bf16(const bf16_t* A, int64_t lda, int64_t sa, bool a_m_c
   else
     hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, 2, 2, true, true, Epilogue>), grid, block, 0, stream, g, epi);
   return hipGetLastError();
+}
+
+// Host-side launcher: picks the tile shape.  128x128 tiles unless that leaves the 256 compute units
+// with fewer than four workgroups each to hide memory latency with; then 128x64.  Caller guarantees
+// 16-byte alignment of pitches / strides / bases.
+template <class Epilogue>
+hipError_t launch_gemm_bf16(const bf16_t* A, int64_t lda, int64_t sa, bool a_m_contig, const bf16_t* B, int64_t ldb,
+                            int64_t sb, bool b_k_contig, int M, int N, int K, int batch, const Epilogue& epi,
+                            hipStream_t stream) {
+  GemmArgs g;
+  g.A = A; g.lda = lda; g.sa = sa;
+  g.B = B; g.ldb = ldb; g.sb = sb;
+  g.M = M; g.N = N; g.K = K; g.batch = batch;
+  g.tiles_m = g.tiles_n = 0;
+  const int64_t wide = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
+  if (wide < 4 * 256 && N > 64) return launch_gemm_tile<128, 64, Epilogue>(g, a_m_contig, b_k_contig, epi, stream);
+  return launch_gemm_tile<128, 128, Epilogue>(g, a_m_contig, b_k_contig, epi, stream);
 }
 
 }  // namespace pbt

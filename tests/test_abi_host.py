@@ -1,0 +1,77 @@
+"""Host-side checks of the C-ABI library (no GPU needed): it loads, exports every symbol the header
+declares, lays parameters out as documented and rejects bad configurations before touching a device."""
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1711_09846_amd import binding, workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_1711_09846_amd import build
+        build.build_library(verbose=False)
+
+
+def test_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "pbt.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(pbt_[a-z0-9_]+)\s*\(", header))
+    assert {"pbt_init", "pbt_step", "pbt_eval", "pbt_exploit_explore", "pbt_get_state"} <= declared
+    lib = binding.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(binding.EXPORTS)
+
+
+def test_layout_and_sizes():
+    for key, n_params in ((1, 2372), (2, 1323018)):
+        wl = workloads.WORKLOADS[key]
+        cfg = binding.make_config(wl, 1)
+        state, scratch, lay = binding.query_sizes(cfg)
+        assert lay.n_params == n_params and lay.stride % 256 == 0 and lay.stride >= n_params
+        off = 0
+        for l, (fi, fo) in enumerate(zip(wl.dims[:-1], wl.dims[1:])):
+            assert lay.w_off[l] % 64 == 0 and lay.b_off[l] % 64 == 0
+            assert lay.w_off[l] >= off and lay.b_off[l] >= lay.w_off[l] + fi * fo
+            off = lay.b_off[l] + fo
+        n_arrays = {1: 2, 2: 3}[key]
+        assert state >= wl.P * lay.stride * 4 * n_arrays and scratch >= wl.P * lay.stride * 4
+
+
+def test_pack_unpack_roundtrip():
+    wl = workloads.MLP_SMALL
+    _, _, lay = binding.query_sizes(binding.make_config(wl, 1))
+    layers = workloads.initial_mlp_weights(wl.dims, 1, 0)[0]
+    flat = binding.pack_params(lay, layers)
+    assert flat.shape == (lay.stride,) and np.count_nonzero(flat) <= lay.n_params
+    for (W, b), (W2, b2) in zip(layers, binding.unpack_params(lay, wl.dims, flat)):
+        assert np.array_equal(W, W2) and np.array_equal(b, b2)
+
+
+@pytest.mark.parametrize("change,status", [
+    (dict(P=0), -1), (dict(P=2000), -1), (dict(n_trunc=5), -1), (dict(batch=0), -1),
+    (dict(roles=[workloads.ROLE_BETA1]), -1),                     # no learning-rate column
+    (dict(kind=7), -5),                                           # workload family not built
+    (dict(dims=[32, 64, 40]), -5),                                # more than 32 classes
+    (dict(dims=[32, 4096, 4096, 4]), -5),                         # fp32 network that does not fit LDS
+])
+def test_bad_configurations_are_rejected(change, status):
+    wl = workloads.MLP_SMALL.replace(**change)
+    if "roles" in change:
+        wl = wl.replace(priors=[("uniform", 0.8, 0.9)], h_max=[math.inf], optimizer=workloads.OPT_ADAM,
+                        opt_const=dict())
+    with pytest.raises(binding.PbtError) as e:
+        binding.query_sizes(binding.make_config(wl, 1))
+    assert e.value.status == status and len(str(e.value)) > 20
+
+
+def test_trunc_count_rule():
+    assert [workloads.trunc_count(P, pc) for P, pc in ((8, 25), (64, 20), (32, 20), (16, 20), (128, 20), (3, 20))] == \
+        [2, 12, 6, 3, 25, 1]
