@@ -127,6 +127,22 @@ pbt_status pbt_query_sizes(const pbt_config* cfg, size_t* state_bytes, size_t* s
 pbt_status pbt_init(const pbt_config* cfg, void* d_state, size_t state_bytes, void* d_scratch, size_t scratch_bytes,
                     void* hip_stream, pbt_handle** out);
 
+/* A prior over one hyperparameter column: uniform on [lo, hi] or log-uniform (exp of a uniform
+ * draw on [ln lo, ln hi]; needs 0 < lo). */
+typedef struct {
+  int32_t kind; /* 0 = uniform, 1 = log-uniform */
+  double lo, hi;
+} pbt_prior;
+
+/* Figure 1(c) / Algorithm 1, initial population drawn on the device: every member gets independent
+ * random weights (uniform in +-1/sqrt(fan_in) per layer, biases included) and hyperparameters drawn
+ * from priors[0..n_hyper-1] (HOST array).  Random words: Philox counter (0, member, domain 4,
+ * position / 4) word position % 4 for the value at `position` of the member's flat parameter vector;
+ * counter (0, member, domain 5, column) word 0 for a hyperparameter; u = (x + 0.5) / 2^32, evaluated
+ * in double precision and rounded once to float.  Optimiser state, t and scores are reset as in
+ * pbt_init.  Enqueues on hip_stream; no synchronisation. */
+pbt_status pbt_init_population(pbt_handle* h, const pbt_prior* priors, void* hip_stream);
+
 /* Section 3, Eq. 2: theta_i <- step(theta_i | h_i) for every member i, n_steps
  * times (step indices step_index .. step_index + n_steps - 1).  One step:
  * draw the member's mini-batch rows (Philox domain 1), forward, loss,

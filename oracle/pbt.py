@@ -48,6 +48,43 @@ class Member:
         self.hist = None                          # optional score history
 
 
+def init_hyperparameters(seed, P, priors):
+    """Initial h (Figure 1c: hyperparameters are sampled at random to start with): column k of
+    member i is drawn from priors[k] = (kind, lo, hi), kind "uniform" or "log" (log-uniform:
+    exp of a uniform draw between ln lo and ln hi), using u = (x + 0.5) / 2**32 with x word 0 of
+    Philox counter (0, i, DOMAIN_INIT_H, k).  Returned as float32 [P][n_h]."""
+    H = np.empty((P, len(priors)), dtype=np.float32)
+    for k, (kind, lo, hi) in enumerate(priors):
+        x = philox.words(seed, 0, np.arange(P), philox.DOMAIN_INIT_H, k)[:, 0]
+        u = philox.unit_open(x)
+        if kind == "log":
+            H[:, k] = np.exp(math.log(lo) + u * (math.log(hi) - math.log(lo)))
+        elif kind == "uniform":
+            H[:, k] = lo + u * (hi - lo)
+        else:
+            raise ValueError(kind)
+    return H
+
+
+def init_weights(seed, member, dims, offsets):
+    """Initial theta of one member (Figure 1c: random weight initialisations): every weight and
+    bias of a layer with fan-in f is uniform in (-1/sqrt f, 1/sqrt f).  The value at position p
+    of the member's flat parameter vector uses word p % 4 of Philox counter
+    (0, member, DOMAIN_INIT_W, p // 4); offsets[l] = (start of W_l, start of b_l) in that vector.
+    Returns [(W, b), ...] rounded to float32."""
+    layers = []
+    for l, (fi, fo) in enumerate(zip(dims[:-1], dims[1:])):
+        out = []
+        for start, count in ((offsets[l][0], fi * fo), (offsets[l][1], fo)):
+            pos = start + np.arange(count)
+            w = philox.words(seed, 0, member, philox.DOMAIN_INIT_W, pos // 4)
+            x = w[np.arange(count), pos % 4]
+            u = philox.unit_open(x)
+            out.append(((2.0 * u - 1.0) / math.sqrt(fi)).astype(np.float32))
+        layers.append((out[0].reshape(fi, fo), out[1]))
+    return layers
+
+
 def rank_order(scores):
     """Member indices from best to worst."""
     s = np.asarray(scores, dtype=np.float32)

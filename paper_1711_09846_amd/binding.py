@@ -23,7 +23,7 @@ _ARR_DTYPE = {ARR_W32: np.float32, ARR_OPT0: np.float32, ARR_OPT1: np.float32, A
 
 EXPORTS = ["pbt_query_sizes", "pbt_init", "pbt_step", "pbt_eval", "pbt_exploit_explore", "pbt_get_state",
            "pbt_set_state", "pbt_state_ptr", "pbt_destroy", "pbt_last_error", "pbt_batched_gemm_bf16",
-           "pbt_timing_enable", "pbt_timing_read"]
+           "pbt_timing_enable", "pbt_timing_read", "pbt_init_population"]
 (K_NONE, K_FETCH, K_GEMM_FWD, K_HEAD, K_GEMM_WGRAD, K_GEMM_DGRAD, K_BIAS_GRAD, K_OPTIMIZER, K_RANK, K_COPY,
  K_FUSED_STEP) = range(-1, 10)
 
@@ -40,6 +40,10 @@ class PbtConfig(C.Structure):
 class PbtLayout(C.Structure):
     _fields_ = [("stride", C.c_int64), ("n_params", C.c_int64), ("w_off", C.c_int64 * PBT_MAX_DIMS),
                 ("b_off", C.c_int64 * PBT_MAX_DIMS)]
+
+
+class PbtPrior(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("lo", C.c_double), ("hi", C.c_double)]
 
 
 class PbtError(RuntimeError):
@@ -71,6 +75,7 @@ def lib():
         L.pbt_last_error.argtypes = [vp]
         L.pbt_last_error.restype = C.c_char_p
         L.pbt_batched_gemm_bf16.argtypes = [vp, i64, i64, i32, vp, i64, i64, i32, vp, i64, i64, i32, i32, i32, i32, i32, vp]
+        L.pbt_init_population.argtypes = [vp, C.POINTER(PbtPrior), vp]
         L.pbt_timing_enable.argtypes = [vp, i32, i32]
         L.pbt_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
         for name in EXPORTS:
@@ -176,6 +181,11 @@ class Population:
     def exploit_explore(self, round_index, scores_override=None):
         p = None if scores_override is None else C.c_void_p(scores_override.data_ptr())
         self._check(lib().pbt_exploit_explore(self._h, round_index, p, self._stream()))
+
+    def init_population(self, priors):
+        """priors: [("uniform" | "log", lo, hi), ...], one per hyperparameter column."""
+        arr = (PbtPrior * len(priors))(*[PbtPrior(1 if k == "log" else 0, lo, hi) for k, lo, hi in priors])
+        self._check(lib().pbt_init_population(self._h, arr, self._stream()))
 
     def timing_enable(self, kernel_class, max_launches=1):
         self._check(lib().pbt_timing_enable(self._h, kernel_class, max_launches))

@@ -354,6 +354,8 @@ pbt_status eval_bf16(pbt_handle* h, const float* eval_x, const int32_t* eval_y, 
 
 }  // namespace
 
+static hipError_t reset_store(pbt_handle* h, hipStream_t s);
+
 extern "C" {
 
 pbt_status pbt_query_sizes(const pbt_config* cfg, size_t* state_bytes, size_t* scratch_bytes, pbt_layout* layout) {
@@ -384,17 +386,53 @@ pbt_status pbt_init(const pbt_config* cfg, void* d_state, size_t state_bytes, vo
   h->state = static_cast<char*>(d_state);
   h->scratch = static_cast<char*>(d_scratch);
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  hipError_t e = fill_u32(h->st<uint32_t>(0), 0u, (int64_t)(pl.state_bytes / 4), s);
-  if (e == hipSuccess) e = fill_u32(h->sc<uint32_t>(pl.o_grad), 0u, (int64_t)cfg->P * pl.lay.stride, s);
-  if (e == hipSuccess) e = fill_u32(h->st<uint32_t>(pl.o_score), 0xff800000u, cfg->P, s);  // -inf
-  if (e == hipSuccess) e = fill_u32(h->st<uint32_t>(pl.o_donor), 0xffffffffu, cfg->P, s);  // -1
-  if (e == hipSuccess) e = iota_i32(h->st<int32_t>(pl.o_parent), cfg->P, s);
-  if (e == hipSuccess) e = iota_i32(h->st<int32_t>(pl.o_order), cfg->P, s);
+  hipError_t e = reset_store(h, s);
   if (e != hipSuccess) {
     delete h;
     return fail(nullptr, PBT_EDEVICE, "initialising the population store failed: %s", hipGetErrorString(e));
   }
   *out = h;
+  return PBT_OK;
+}
+
+static hipError_t reset_store(pbt_handle* h, hipStream_t s) {
+  const Plan& pl = h->plan;
+  const int P = h->cfg.P;
+  hipError_t e = fill_u32(h->st<uint32_t>(0), 0u, (int64_t)(pl.state_bytes / 4), s);
+  if (e == hipSuccess) e = fill_u32(h->sc<uint32_t>(pl.o_grad), 0u, (int64_t)P * pl.lay.stride, s);
+  if (e == hipSuccess) e = fill_u32(h->st<uint32_t>(pl.o_score), 0xff800000u, P, s);  // -inf
+  if (e == hipSuccess) e = fill_u32(h->st<uint32_t>(pl.o_donor), 0xffffffffu, P, s);  // -1
+  if (e == hipSuccess) e = iota_i32(h->st<int32_t>(pl.o_parent), P, s);
+  if (e == hipSuccess) e = iota_i32(h->st<int32_t>(pl.o_order), P, s);
+  return e;
+}
+
+pbt_status pbt_init_population(pbt_handle* h, const pbt_prior* priors, void* hip_stream) {
+  if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  if (!priors) return fail(h, PBT_EINVAL, "priors is NULL");
+  const pbt_config& c = h->cfg;
+  const Plan& p = h->plan;
+  InitArgs a;
+  std::memset(&a, 0, sizeof a);
+  for (int k = 0; k < c.n_hyper; ++k) {
+    const pbt_prior& pr = priors[k];
+    if (pr.kind != 0 && pr.kind != 1) return fail(h, PBT_EINVAL, "prior %d: kind must be 0 (uniform) or 1 (log-uniform)", k);
+    if (!(pr.lo <= pr.hi) || !std::isfinite(pr.lo) || !std::isfinite(pr.hi)) return fail(h, PBT_EINVAL, "prior %d: need finite lo <= hi", k);
+    if (pr.kind == 1 && !(pr.lo > 0.0)) return fail(h, PBT_EINVAL, "prior %d: log-uniform needs lo > 0", k);
+    a.prior_kind[k] = pr.kind;
+    a.prior_a[k] = pr.kind == 1 ? std::log(pr.lo) : pr.lo;
+    a.prior_b[k] = pr.kind == 1 ? std::log(pr.hi) : pr.hi;
+  }
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  PBT_HIP(h, reset_store(h, s));
+  a.W32 = h->st<float>(p.o_w32);
+  a.W16 = c.compute_dtype == PBT_DTYPE_BF16 ? h->st<bf16_t>(p.o_w16) : nullptr;
+  a.H = h->st<float>(p.o_hyper);
+  a.stride = p.lay.stride; a.P = c.P; a.n_layers = c.n_layers; a.n_hyper = c.n_hyper;
+  for (int l = 0; l <= c.n_layers; ++l) a.dims[l] = c.dims[l];
+  for (int l = 0; l < c.n_layers; ++l) { a.w_off[l] = p.lay.w_off[l]; a.b_off[l] = p.lay.b_off[l]; }
+  a.seed = c.seed;
+  PBT_HIP(h, init_population(a, s));
   return PBT_OK;
 }
 

@@ -50,6 +50,17 @@ hipError_t bias_grad(const bf16_t* dZ, int P, int rows, int N, int64_t ld, float
 // out[i] = scale * sum_r rowval[i][r]   (one wavefront per member, fixed order)
 hipError_t row_reduce(const float* rowval, int64_t srow, int P, int rows, float scale, float* out, hipStream_t s);
 
+// Initial population: uniform +-1/sqrt(fan_in) weights (positions outside any layer are zero) and
+// hyperparameters from the priors; all in double, rounded once to float.
+struct InitArgs {
+  float* W32; bf16_t* W16; float* H;
+  int64_t stride; int P, n_layers, n_hyper;
+  int dims[16]; int64_t w_off[16], b_off[16];
+  int prior_kind[8]; double prior_a[8], prior_b[8];  // uniform: a + u (b - a); log: exp(a + u (b - a)), a = ln lo
+  uint64_t seed;
+};
+hipError_t init_population(const InitArgs& a, hipStream_t s);
+
 struct OptArgs {
   float* W32; float* S0; float* S1; bf16_t* W16; const float* G;
   const float* H; const int32_t* t;

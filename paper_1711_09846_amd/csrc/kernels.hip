@@ -39,6 +39,39 @@ hipError_t f32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t s) 
   return hipGetLastError();
 }
 
+// ---- initial population ----------------------------------------------------------------------
+// grid (ceil(stride / 256), P): one thread per position of the flat parameter vector.
+__global__ __launch_bounds__(256) void init_population_kernel(InitArgs a) {
+  const int i = blockIdx.y;
+  const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
+  if (p < a.stride) {
+    int fan_in = 0;
+    for (int l = 0; l < a.n_layers; ++l) {
+      const int64_t nw = (int64_t)a.dims[l] * a.dims[l + 1];
+      if ((p >= a.w_off[l] && p < a.w_off[l] + nw) || (p >= a.b_off[l] && p < a.b_off[l] + a.dims[l + 1])) fan_in = a.dims[l];
+    }
+    float v = 0.f;
+    if (fan_in > 0) {
+      const u32x4 w = philox4x32_10(0u, (uint32_t)i, DOMAIN_INIT_W, (uint32_t)(p >> 2), k0, k1);
+      const uint32_t x = (p & 3) == 0 ? w.x : (p & 3) == 1 ? w.y : (p & 3) == 2 ? w.z : w.w;
+      v = (float)((2.0 * philox_unit(x) - 1.0) / sqrt((double)fan_in));
+    }
+    a.W32[(int64_t)i * a.stride + p] = v;
+    if (a.W16) a.W16[(int64_t)i * a.stride + p] = f2bf(v);
+  }
+  if (blockIdx.x == 0 && threadIdx.x < a.n_hyper) {
+    const int k = threadIdx.x;
+    const double u = philox_unit(philox4x32_10(0u, (uint32_t)i, DOMAIN_INIT_H, (uint32_t)k, k0, k1).x);
+    const double lin = a.prior_a[k] + u * (a.prior_b[k] - a.prior_a[k]);
+    a.H[i * a.n_hyper + k] = (float)(a.prior_kind[k] == 1 ? exp(lin) : lin);
+  }
+}
+hipError_t init_population(const InitArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(init_population_kernel, dim3((unsigned)((a.stride + 255) / 256), a.P), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
 // ---- mini-batch fetch ------------------------------------------------------------------------
 // grid (B, P); one workgroup copies one data row.
 

@@ -12,6 +12,8 @@ enum {
   DOMAIN_BATCH = 1,
   DOMAIN_DONOR = 2,
   DOMAIN_EXPLORE = 3,
+  DOMAIN_INIT_W = 4,
+  DOMAIN_INIT_H = 5,
 };
 
 struct u32x4 { uint32_t x, y, z, w; };
@@ -38,5 +40,8 @@ __host__ __device__ inline u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_
 __host__ __device__ inline uint32_t philox_bounded(uint32_t x, uint32_t n) {
   return (uint32_t)(((uint64_t)x * (uint64_t)n) >> 32);
 }
+
+// (x + 0.5) / 2^32: a double in the open interval (0, 1).
+__host__ __device__ inline double philox_unit(uint32_t x) { return ((double)x + 0.5) * (1.0 / 4294967296.0); }
 
 }  // namespace pbt

@@ -1,0 +1,42 @@
+"""Device-side initial population against the oracle's."""
+import numpy as np
+import pytest
+
+from oracle import pbt as opbt
+from paper_1711_09846_amd import binding, workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("key", [1, 2])
+def test_init_population_matches_oracle(key):
+    wl = workloads.WORKLOADS[key].replace(P=6, n_trunc=1)
+    seed = 0x1234567_89abcdef
+    pop = binding.Population(binding.make_config(wl, seed))
+    pop.set(binding.ARR_T, np.full(wl.P, 9, dtype=np.int32))       # must be reset by the init
+    pop.init_population(wl.priors)
+    lay = pop.layout
+    offsets = [(lay.w_off[l], lay.b_off[l]) for l in range(len(wl.dims) - 1)]
+    W = pop.get(binding.ARR_W32)
+    for i in range(wl.P):
+        ref = binding.pack_params(lay, opbt.init_weights(seed, i, wl.dims, offsets))
+        assert W[i].tobytes() == ref.tobytes()                    # division and sqrt are correctly rounded on both sides
+    H, Href = pop.get(binding.ARR_HYPER), opbt.init_hyperparameters(seed, wl.P, wl.priors)
+    # exp() may differ by an ulp of double between the two math libraries; after rounding to float
+    # that can at most move the result to the neighbouring float
+    assert np.all(np.abs(H.view(np.int32) - Href.view(np.int32)) <= 1)
+    assert np.array_equal(H[:, 1:], Href[:, 1:]) or key == 2
+    assert np.all(pop.get(binding.ARR_T) == 0) and np.all(pop.get(binding.ARR_OPT0) == 0)
+    assert np.array_equal(pop.get(binding.ARR_PARENT), np.arange(wl.P))
+    if wl.dtype == workloads.DTYPE_BF16:
+        import torch
+        w16 = torch.from_numpy(W).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(pop.get(binding.ARR_W16), w16)
+
+
+def test_init_population_rejects_bad_priors():
+    pop = binding.Population(binding.make_config(workloads.MLP_SMALL, 1))
+    with pytest.raises(binding.PbtError):
+        pop.init_population([("log", 0.0, 1.0)])
+    with pytest.raises(binding.PbtError):
+        pop.init_population([("uniform", 2.0, 1.0)])

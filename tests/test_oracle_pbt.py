@@ -230,3 +230,39 @@ def test_training_reduces_loss_and_batch_rows():
     rows = classifier.batch_rows(42, 5, 1, 4, 256)
     ref = [(int(philox.philox4x32_10([5, 1, philox.DOMAIN_BATCH, j], [42, 0])[0]) * 256) >> 32 for j in range(4)]
     assert list(rows) == ref
+
+
+def test_init_hyperparameters_priors():
+    # Prior ranges as in the paper's appendix tables (e.g. learning rate log-uniform, Section A.3)
+    priors = [("log", 1e-4, 1e-2), ("uniform", 0.8, 0.95)]
+    H = pbt.init_hyperparameters(7, 4000, priors)
+    assert H.dtype == np.float32 and H.shape == (4000, 2)
+    assert H[:, 0].min() >= 1e-4 * (1 - 1e-6) and H[:, 0].max() <= 1e-2 * (1 + 1e-6)
+    assert H[:, 1].min() >= 0.8 and H[:, 1].max() <= 0.95
+    # log-uniform: ln h is uniform, so its quartiles sit at the quarter points of [ln lo, ln hi]
+    q = np.quantile(np.log(H[:, 0].astype(np.float64)), [0.25, 0.5, 0.75])
+    ref = math.log(1e-4) + np.array([0.25, 0.5, 0.75]) * (math.log(1e-2) - math.log(1e-4))
+    assert np.all(np.abs(q - ref) < 0.12)
+    assert abs(H[:, 1].mean() - 0.875) < 0.003
+    # one entry by hand from the definition
+    x = int(philox.philox4x32_10([0, 5, philox.DOMAIN_INIT_H, 0], [7, 0])[0])
+    u = (x + 0.5) / 2.0 ** 32
+    assert H[5, 0] == np.float32(math.exp(math.log(1e-4) + u * (math.log(1e-2) - math.log(1e-4))))
+
+
+def test_init_weights_distribution_and_formula():
+    dims = [40, 30, 3]
+    offsets = [(0, 1216), (1280, 1408)]                      # as a 64-aligned layout would place them
+    layers = pbt.init_weights(11, 2, dims, offsets)
+    assert [W.shape for W, _ in layers] == [(40, 30), (30, 3)] and layers[0][0].dtype == np.float32
+    for (W, b), fi in zip(layers, dims[:-1]):
+        bound = 1.0 / math.sqrt(fi)
+        assert np.abs(W).max() < bound and np.abs(b).max() < bound
+    W0 = layers[0][0].astype(np.float64)
+    assert abs(W0.mean()) < 0.01 and abs(W0.var() - (1.0 / 40) / 3.0) < 0.002      # var of U(-a, a) = a^2 / 3
+    # position p = 1280 + 7 is element 7 of W_1 (row 2, column 1): word 3 of counter (0, 2, INIT_W, 321)
+    p = 1280 + 7
+    x = int(philox.philox4x32_10([0, 2, philox.DOMAIN_INIT_W, p // 4], [11, 0])[p % 4])
+    assert layers[1][0][2, 1] == np.float32((2.0 * (x + 0.5) / 2.0 ** 32 - 1.0) / math.sqrt(30))
+    other = pbt.init_weights(11, 3, dims, offsets)
+    assert not np.array_equal(other[0][0], layers[0][0])
