@@ -78,7 +78,9 @@ def mlp_forward(params, x, hidden_act, out_act=ACT_NONE, q=identity):
             zs.append(q(z))
             a = q(act(z, hidden_act))
         else:
-            zs.append(z)
+            # the last pre-activation is kept for the backward pass only when an output
+            # non-linearity follows (a generator's tanh); plain logits are not stored
+            zs.append(q(z) if out_act != ACT_NONE else z)
             a = act(z, out_act)
     return a, (ins, zs)
 
@@ -117,6 +119,26 @@ def softmax_xent(logits, labels, smoothing=0.0):
     loss = -(q * lsm).sum() / n
     dlogits = (np.exp(lsm) - q) / n
     return loss, dlogits
+
+
+def softplus(x):
+    """log(1 + e^x), evaluated without overflow."""
+    return np.maximum(x, 0.0) + np.log1p(np.exp(-np.abs(x)))
+
+
+def sigmoid(x):
+    return np.where(x >= 0, 1.0 / (1.0 + np.exp(-np.abs(x))), np.exp(-np.abs(x)) / (1.0 + np.exp(-np.abs(x))))
+
+
+def logistic_loss(logits, targets):
+    """Mean binary cross-entropy of sigmoid(logits) against targets in {0, 1}:
+    -[t log s + (1 - t) log(1 - s)] = softplus(-l) for t = 1, softplus(l) for t = 0.
+    Returns (loss, dLoss/dlogits); logits has shape (n, 1) or (n,)."""
+    l = np.asarray(logits, dtype=np.float64).reshape(-1)
+    t = np.asarray(targets, dtype=np.float64).reshape(-1)
+    loss = np.mean(np.where(t > 0.5, softplus(-l), softplus(l)))
+    d = (sigmoid(l) - t) / len(l)
+    return loss, d.reshape(np.shape(logits))
 
 
 def classifier_loss_and_grads(params, x, labels, hidden_act, q=identity):
