@@ -62,11 +62,12 @@ typedef enum {
   PBT_EUNSUPPORTED = -5  /* valid request that this build has no kernel for */
 } pbt_status;
 
-enum { PBT_WL_CLASSIFIER = 1 };                       /* workload families */
+enum { PBT_WL_CLASSIFIER = 1, PBT_WL_GAN = 3 };       /* workload families */
 enum { PBT_ACT_NONE = 0, PBT_ACT_RELU = 1, PBT_ACT_GELU = 2, PBT_ACT_LEAKY_RELU = 3, PBT_ACT_TANH = 4 };
 enum { PBT_OPT_SGD_MOMENTUM = 0, PBT_OPT_ADAM = 1, PBT_OPT_RMSPROP = 2 };
 enum { PBT_DTYPE_FP32 = 0, PBT_DTYPE_BF16 = 1 };      /* BF16 = bf16 operands, fp32 accumulate, fp32 master weights */
-enum { PBT_ROLE_LR = 0, PBT_ROLE_BETA1 = 1, PBT_ROLE_WD = 2 }; /* meaning of a hyperparameter column */
+enum { PBT_ROLE_LR = 0, PBT_ROLE_BETA1 = 1, PBT_ROLE_WD = 2, /* meaning of a hyperparameter column */
+       PBT_ROLE_LR_G = 3, PBT_ROLE_LR_D = 4 };                /* GAN: generator / discriminator learning rate */
 
 /* Arrays of the population store that pbt_get_state / pbt_set_state address. */
 enum {
@@ -77,7 +78,7 @@ enum {
   PBT_ARR_GRAD = 4,   /* float  [P][stride]  gradient of the last step (scratch)      */
   PBT_ARR_HYPER = 5,  /* float  [P][n_hyper] hyperparameters h                        */
   PBT_ARR_SCORE = 6,  /* float  [P]          p, written by pbt_eval                   */
-  PBT_ARR_LOSS = 7,   /* float  [P]          training loss of the last step           */
+  PBT_ARR_LOSS = 7,   /* float  [P][n_loss]  training loss(es) of the last step; n_loss = 1, GAN: 2 = {L_D, L_G} */
   PBT_ARR_T = 8,      /* int32  [P]          optimiser updates applied (travels with theta) */
   PBT_ARR_ORDER = 9,  /* int32  [P]          members from best to worst, last exploit */
   PBT_ARR_DONOR = 10, /* int32  [P]          donor of the last exploit, -1 = kept     */
@@ -101,6 +102,13 @@ typedef struct {
   float perturb_lo, perturb_hi;     /* explore factors, 0.8f and 1.2f in the paper's RL and translation runs */
   float opt_const[4];               /* SGD: {momentum}.  Adam: {beta1, beta2, eps, weight decay} (beta1 / decay are
                                        defaults for when no column has that role).  RMSProp: {rho, eps}. */
+  /* PBT_WL_GAN only: dims/n_layers/act describe the generator (latent -> data), the fields below
+     the discriminator (data -> 1 logit).  Both networks live in one flat parameter vector per
+     member, generator layers first, so an exploit copies both (Section 4.3.1). */
+  int32_t act_out;                  /* generator output activation (PBT_ACT_TANH) */
+  int32_t n_layers2;                /* discriminator layers; dims2[0] = dims[n_layers], dims2[n_layers2] = 1 */
+  int32_t dims2[PBT_MAX_DIMS];
+  int32_t act2;                     /* discriminator hidden activation */
   int32_t n_train, n_eval;          /* rows of the training and of the held-out set */
   int32_t eval_chunk;               /* rows of the held-out set scored per pass (bounds scratch); 0 = library picks */
   uint64_t seed;                    /* Philox key */
@@ -155,7 +163,10 @@ pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs
 
 /* Section 3, Eq. 1: p_i <- eval(theta_i) for every member; writes score[P].
  * PBT_WL_CLASSIFIER: minus the mean cross-entropy over the held-out set,
- * d_inputs = {eval_x float[n_eval][dims[0]], eval_y int32[n_eval]}. */
+ * d_inputs = {eval_x float[n_eval][dims[0]], eval_y int32[n_eval]}.
+ * PBT_WL_GAN: minus the biased squared maximum mean discrepancy, RBF kernel exp(-|a-b|^2 / (2 d)),
+ * d = dims2[0], between n_eval generated rows (latents: Philox domain 6 + 2, step index 0) and the
+ * n_eval held-out rows; d_inputs = {eval_x float[n_eval][dims2[0]]}. */
 pbt_status pbt_eval(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, void* hip_stream);
 
 /* Section 4.1.1, Exploit (b) + Explore (a), for the whole population at once

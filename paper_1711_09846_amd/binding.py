@@ -33,7 +33,8 @@ class PbtConfig(C.Structure):
                 ("dims", C.c_int32 * PBT_MAX_DIMS), ("act", C.c_int32), ("optimizer", C.c_int32),
                 ("compute_dtype", C.c_int32), ("n_hyper", C.c_int32), ("hyper_role", C.c_int32 * PBT_MAX_HYPER),
                 ("hyper_max", C.c_float * PBT_MAX_HYPER), ("n_trunc", C.c_int32), ("perturb_lo", C.c_float),
-                ("perturb_hi", C.c_float), ("opt_const", C.c_float * 4), ("n_train", C.c_int32),
+                ("perturb_hi", C.c_float), ("opt_const", C.c_float * 4), ("act_out", C.c_int32),
+                ("n_layers2", C.c_int32), ("dims2", C.c_int32 * PBT_MAX_DIMS), ("act2", C.c_int32), ("n_train", C.c_int32),
                 ("n_eval", C.c_int32), ("eval_chunk", C.c_int32), ("seed", C.c_uint64)]
 
 
@@ -110,6 +111,10 @@ def make_config(wl, seed, P=None, n_trunc=None, eval_chunk=0):
         vals = [oc.get("rho", 0.99), oc.get("eps", 1e-5), 0, 0]
     for k, v in enumerate(vals):
         c.opt_const[k] = v
+    if getattr(wl, "dims2", None):                      # two-network workloads (GAN): generator, then discriminator
+        c.act_out, c.act2, c.n_layers2 = wl.act_out, wl.act2, len(wl.dims2) - 1
+        for k, d in enumerate(wl.dims2):
+            c.dims2[k] = d
     c.n_train, c.n_eval, c.eval_chunk = wl.n_train, wl.n_eval, eval_chunk
     c.seed = seed
     return c
@@ -133,8 +138,10 @@ def pack_params(lay, layers):
 
 
 def unpack_params(lay, dims, flat):
+    """dims: widths of one MLP, or a list of (fan_in, fan_out) pairs in layout order."""
+    shapes = dims if dims and isinstance(dims[0], tuple) else list(zip(dims[:-1], dims[1:]))
     out = []
-    for l, (fi, fo) in enumerate(zip(dims[:-1], dims[1:])):
+    for l, (fi, fo) in enumerate(shapes):
         W = np.array(flat[lay.w_off[l]:lay.w_off[l] + fi * fo]).reshape(fi, fo)
         b = np.array(flat[lay.b_off[l]:lay.b_off[l] + fo])
         out.append((W, b))
@@ -159,6 +166,12 @@ class Population:
         if rc != 0:
             raise PbtError(rc, lib().pbt_last_error(None).decode())
         self.dims = [cfg.dims[k] for k in range(cfg.n_layers + 1)]
+        self.n_loss = 2 if cfg.workload == 3 else 1
+        # (fan_in, fan_out) of every dense layer in layout order
+        self.layer_shapes = list(zip(self.dims[:-1], self.dims[1:]))
+        if cfg.n_layers2:
+            d2 = [cfg.dims2[k] for k in range(cfg.n_layers2 + 1)]
+            self.layer_shapes += list(zip(d2[:-1], d2[1:]))
 
     def _stream(self):
         return C.c_void_p(self.torch.cuda.current_stream(self.device).cuda_stream)
@@ -201,6 +214,8 @@ class Population:
             return (P, self.layout.stride)
         if which == ARR_HYPER:
             return (P, self.cfg.n_hyper)
+        if which == ARR_LOSS and self.n_loss > 1:
+            return (P, self.n_loss)
         return (P,)
 
     def get(self, which, member=-1):
@@ -231,7 +246,7 @@ class Population:
         self.set(ARR_HYPER, np.asarray(H, dtype=np.float32))
 
     def member_params(self, member, which=ARR_W32):
-        return unpack_params(self.layout, self.dims, self.get(which, member))
+        return unpack_params(self.layout, self.layer_shapes, self.get(which, member))
 
     def close(self):
         if self._h:

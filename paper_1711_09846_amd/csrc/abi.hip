@@ -1,6 +1,6 @@
 // C ABI of the population step: configuration checks, carving of the caller's device buffers,
 // and the kernel sequences behind pbt_step / pbt_eval / pbt_exploit_explore.
-#include "../../include/pbt.h"
+#include "handle.h"
 
 #include <cmath>
 #include <cstdarg>
@@ -10,62 +10,13 @@
 #include <string>
 #include <vector>
 
-#include "internal.h"
-
 using namespace pbt;
 
 namespace {
-
 thread_local std::string g_last_error = "";
+}
 
-constexpr int64_t SEG_ALIGN = 64;      // elements: start of every W_l and b_l
-constexpr int64_t STRIDE_ALIGN = 256;  // elements: per-member stride
-constexpr size_t BUF_ALIGN = 256;      // bytes: every carved array
-
-int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
-
-struct Carver {
-  size_t off = 0;
-  size_t take(size_t bytes) {
-    const size_t o = off;
-    off += (bytes + BUF_ALIGN - 1) / BUF_ALIGN * BUF_ALIGN;
-    return o;
-  }
-};
-
-struct Plan {
-  pbt_layout lay;
-  // offsets in bytes inside d_state
-  size_t o_w32, o_opt0, o_opt1, o_w16, o_hyper, o_score, o_loss, o_t, o_order, o_donor, o_parent, o_recip;
-  size_t state_bytes;
-  // offsets in bytes inside d_scratch
-  size_t o_grad, o_y, o_dlogits, o_rowloss, o_x32;
-  size_t o_act[PBT_MAX_DIMS], o_z[PBT_MAX_DIMS], o_dz[PBT_MAX_DIMS];
-  size_t o_evalx, o_evala[2], o_evalrow;
-  size_t scratch_bytes;
-  int eval_chunk;
-  bool fused_small;  // fp32: the whole step runs in one LDS-resident kernel
-  int col_lr, col_beta1, col_wd;
-};
-
-}  // namespace
-
-struct pbt_handle {
-  pbt_config cfg;
-  Plan plan;
-  char* state;
-  char* scratch;
-  std::string err;
-  // optional event timing of one kernel class
-  int timed_class = PBT_K_NONE;
-  std::vector<hipEvent_t> ev_start, ev_stop;
-  size_t ev_used = 0;
-  template <class T> T* st(size_t off) const { return reinterpret_cast<T*>(state + off); }
-  template <class T> T* sc(size_t off) const { return reinterpret_cast<T*>(scratch + off); }
-};
-
-namespace {
-
+namespace pbt {
 pbt_status fail(pbt_handle* h, pbt_status code, const char* fmt, ...) {
   char buf[512];
   va_list ap;
@@ -76,29 +27,15 @@ pbt_status fail(pbt_handle* h, pbt_status code, const char* fmt, ...) {
   g_last_error = buf;
   return code;
 }
+}  // namespace pbt
 
-#define PBT_HIP(h, call)                                                                        \
-  do {                                                                                          \
-    hipError_t e_ = (call);                                                                     \
-    if (e_ != hipSuccess) return fail(h, PBT_EDEVICE, "%s failed: %s", #call, hipGetErrorString(e_)); \
-  } while (0)
-
-// Runs `call` (a launcher returning hipError_t); when its class is the timed one, brackets it
-// with an event pair on the same stream.
-#define PBT_LAUNCH(h, klass, s, call)                                                           \
-  do {                                                                                          \
-    const bool timed_ = (h)->timed_class == (klass) && (h)->ev_used < (h)->ev_start.size();     \
-    if (timed_) PBT_HIP(h, hipEventRecord((h)->ev_start[(h)->ev_used], s));                     \
-    PBT_HIP(h, call);                                                                           \
-    if (timed_) {                                                                               \
-      PBT_HIP(h, hipEventRecord((h)->ev_stop[(h)->ev_used], s));                                \
-      ++(h)->ev_used;                                                                           \
-    }                                                                                           \
-  } while (0)
+namespace {
 
 pbt_status check_config(const pbt_config* c, Plan* pl) {
   if (!c) return fail(nullptr, PBT_EINVAL, "config is NULL");
-  if (c->workload != PBT_WL_CLASSIFIER) return fail(nullptr, PBT_EUNSUPPORTED, "workload %d not built", c->workload);
+  if (c->workload != PBT_WL_CLASSIFIER && c->workload != PBT_WL_GAN)
+    return fail(nullptr, PBT_EUNSUPPORTED, "workload %d not built", c->workload);
+  const bool gan = c->workload == PBT_WL_GAN;
   if (c->P < 1 || c->P > PBT_MAX_P) return fail(nullptr, PBT_EINVAL, "P = %d outside 1..%d", c->P, PBT_MAX_P);
   if (c->batch < 1) return fail(nullptr, PBT_EINVAL, "batch must be positive");
   if (c->n_layers < 1 || c->n_layers >= PBT_MAX_DIMS) return fail(nullptr, PBT_EINVAL, "n_layers = %d outside 1..%d", c->n_layers, PBT_MAX_DIMS - 1);
@@ -110,15 +47,23 @@ pbt_status check_config(const pbt_config* c, Plan* pl) {
   if (c->n_hyper < 1 || c->n_hyper > PBT_MAX_HYPER) return fail(nullptr, PBT_EINVAL, "n_hyper = %d outside 1..%d", c->n_hyper, PBT_MAX_HYPER);
   if (c->n_trunc < 0 || 2 * (int64_t)c->n_trunc > c->P) return fail(nullptr, PBT_EINVAL, "need 0 <= 2*n_trunc <= P (top and bottom sets must not overlap)");
   if (c->n_train < 1 || c->n_eval < 1) return fail(nullptr, PBT_EINVAL, "n_train and n_eval must be positive");
-  if (c->dims[c->n_layers] > 32) return fail(nullptr, PBT_EUNSUPPORTED, "more than 32 classes");
+  if (!gan && c->dims[c->n_layers] > 32) return fail(nullptr, PBT_EUNSUPPORTED, "more than 32 classes");
   pl->col_lr = pl->col_beta1 = pl->col_wd = -1;
+  pl->gan.col_lr_g = pl->gan.col_lr_d = -1;
   for (int k = 0; k < c->n_hyper; ++k) {
     if (c->hyper_role[k] == PBT_ROLE_LR) pl->col_lr = k;
     else if (c->hyper_role[k] == PBT_ROLE_BETA1) pl->col_beta1 = k;
     else if (c->hyper_role[k] == PBT_ROLE_WD) pl->col_wd = k;
+    else if (c->hyper_role[k] == PBT_ROLE_LR_G) pl->gan.col_lr_g = k;
+    else if (c->hyper_role[k] == PBT_ROLE_LR_D) pl->gan.col_lr_d = k;
     else return fail(nullptr, PBT_EINVAL, "unknown hyper_role[%d] = %d", k, c->hyper_role[k]);
     if (std::isnan(c->hyper_max[k])) return fail(nullptr, PBT_EINVAL, "hyper_max[%d] is NaN", k);
   }
+  if (gan) {
+    if (pl->gan.col_lr_g < 0 || pl->gan.col_lr_d < 0) return fail(nullptr, PBT_EINVAL, "the GAN workload needs a generator and a discriminator learning-rate column");
+    return PBT_OK;
+  }
+  if (pl->gan.col_lr_g >= 0 || pl->gan.col_lr_d >= 0) return fail(nullptr, PBT_EINVAL, "generator / discriminator learning-rate columns need the GAN workload");
   if (pl->col_lr < 0) return fail(nullptr, PBT_EINVAL, "no hyperparameter column has the learning-rate role");
   if (c->optimizer != PBT_OPT_ADAM && (pl->col_beta1 >= 0 || pl->col_wd >= 0))
     return fail(nullptr, PBT_EINVAL, "beta1 / weight-decay columns need the Adam optimizer");
@@ -130,16 +75,25 @@ pbt_status make_plan(const pbt_config* c, Plan* pl) {
   if (st != PBT_OK) return st;
   const int L = c->n_layers;
   const int64_t P = c->P, B = c->batch;
-  // parameter layout
+  const bool gan = c->workload == PBT_WL_GAN;
+  // parameter layout (GAN: generator layers, then discriminator layers)
   pbt_layout& lay = pl->lay;
   std::memset(&lay, 0, sizeof lay);
   int64_t off = 0, n_params = 0;
-  for (int l = 0; l < L; ++l) {
+  int n_all = 0;
+  int all_dims[2 * PBT_MAX_DIMS][2];
+  for (int l = 0; l < L; ++l) { all_dims[n_all][0] = c->dims[l]; all_dims[n_all++][1] = c->dims[l + 1]; }
+  if (gan) {
+    if (c->n_layers2 < 1 || L + c->n_layers2 >= PBT_MAX_DIMS) return fail(nullptr, PBT_EINVAL, "generator + discriminator layers must number 2..%d", PBT_MAX_DIMS - 1);
+    for (int l = 0; l < c->n_layers2; ++l) { all_dims[n_all][0] = c->dims2[l]; all_dims[n_all++][1] = c->dims2[l + 1]; }
+  }
+  for (int l = 0; l < n_all; ++l) {
     lay.w_off[l] = off;
-    off = round_up(off + (int64_t)c->dims[l] * c->dims[l + 1], SEG_ALIGN);
+    off = round_up(off + (int64_t)all_dims[l][0] * all_dims[l][1], SEG_ALIGN);
     lay.b_off[l] = off;
-    off = round_up(off + c->dims[l + 1], SEG_ALIGN);
-    n_params += (int64_t)c->dims[l] * c->dims[l + 1] + c->dims[l + 1];
+    off = round_up(off + all_dims[l][1], SEG_ALIGN);
+    n_params += (int64_t)all_dims[l][0] * all_dims[l][1] + all_dims[l][1];
+    if (gan && l == L - 1) pl->gan.g_count = off;
   }
   lay.stride = round_up(off, STRIDE_ALIGN);
   lay.n_params = n_params;
@@ -154,7 +108,8 @@ pbt_status make_plan(const pbt_config* c, Plan* pl) {
   pl->o_w16 = bf16 ? s.take(pw * 2) : 0;
   pl->o_hyper = s.take((size_t)P * c->n_hyper * 4);
   pl->o_score = s.take(P * 4);
-  pl->o_loss = s.take(P * 4);
+  pl->n_loss = gan ? 2 : 1;
+  pl->o_loss = s.take(P * 4 * pl->n_loss);
   pl->o_t = s.take(P * 4);
   pl->o_order = s.take(P * 4);
   pl->o_donor = s.take(P * 4);
@@ -166,7 +121,13 @@ pbt_status make_plan(const pbt_config* c, Plan* pl) {
   pl->o_grad = w.take(pw * 4);
   pl->fused_small = false;
   pl->eval_chunk = 0;
-  if (!bf16) {
+  if (gan) {
+    if (!bf16 || !adam) return fail(nullptr, PBT_EUNSUPPORTED, "the GAN workload is built for bf16 compute with Adam");
+    pl->gan.d_begin = pl->gan.g_count;
+    pl->gan.d_count = lay.stride - pl->gan.g_count;
+    pbt_status gst = gan_check_and_plan(c, pl, &w);
+    if (gst != PBT_OK) return gst;
+  } else if (!bf16) {
     FusedSmallArgs fa;
     std::memset(&fa, 0, sizeof fa);
     fa.stride = lay.stride; fa.B = (int)B; fa.n_layers = L; fa.optimizer = c->optimizer;
@@ -233,7 +194,7 @@ pbt_status arr_info(pbt_handle* h, int which, ArrInfo* ai) {
     case PBT_ARR_GRAD: *ai = {p.o_grad, 4, S, true}; return PBT_OK;
     case PBT_ARR_HYPER: *ai = {p.o_hyper, 4, c.n_hyper, false}; return PBT_OK;
     case PBT_ARR_SCORE: *ai = {p.o_score, 4, 1, false}; return PBT_OK;
-    case PBT_ARR_LOSS: *ai = {p.o_loss, 4, 1, false}; return PBT_OK;
+    case PBT_ARR_LOSS: *ai = {p.o_loss, 4, p.n_loss, false}; return PBT_OK;
     case PBT_ARR_T: *ai = {p.o_t, 4, 1, false}; return PBT_OK;
     case PBT_ARR_ORDER: *ai = {p.o_order, 4, 1, false}; return PBT_OK;
     case PBT_ARR_DONOR: *ai = {p.o_donor, 4, 1, false}; return PBT_OK;
@@ -288,9 +249,9 @@ pbt_status step_bf16(pbt_handle* h, const float* train_x, const int32_t* train_y
   }
   const int Kh = c.dims[L - 1], C = c.dims[L];
   PBT_LAUNCH(h, PBT_K_HEAD, s, head_fwd_loss(h->sc<bf16_t>(p.o_act[L - 1]), (int64_t)B * Kh, W16 + p.lay.w_off[L - 1], S,
-                                             W32 + p.lay.b_off[L - 1], S, Y, B, P, B, Kh, C, 1.f / (float)B, dlogits,
+                                             W32 + p.lay.b_off[L - 1], S, Y, B, P, B, Kh, C, 1.f / (float)B, -1, dlogits,
                                              rowloss, B, s));
-  PBT_LAUNCH(h, PBT_K_HEAD, s, row_reduce(rowloss, B, P, B, 1.f / (float)B, h->st<float>(p.o_loss), s));
+  PBT_LAUNCH(h, PBT_K_HEAD, s, row_reduce(rowloss, B, P, B, 1.f / (float)B, h->st<float>(p.o_loss), 1, s));
   {
     // dW_head[Kh][C] = X^T dlogits (contraction over the B rows), db_head = column sums
     GemmOperands wg{h->sc<bf16_t>(p.o_act[L - 1]), Kh, (int64_t)B * Kh, true, dlogits, 32, (int64_t)B * 32, false,
@@ -316,7 +277,7 @@ pbt_status step_bf16(pbt_handle* h, const float* train_x, const int32_t* train_y
     }
   }
   OptArgs oa{W32, h->st<float>(p.o_opt0), c.optimizer == PBT_OPT_ADAM ? h->st<float>(p.o_opt1) : nullptr, W16, G,
-             h->st<float>(p.o_hyper), h->st<int32_t>(p.o_t), S, P, c.n_hyper, c.optimizer, p.col_lr, p.col_beta1, p.col_wd,
+             0, S, h->st<float>(p.o_hyper), h->st<int32_t>(p.o_t), S, P, c.n_hyper, c.optimizer, p.col_lr, p.col_beta1, p.col_wd,
              c.opt_const[0], c.opt_const[1], c.opt_const[2], c.opt_const[3]};
   PBT_LAUNCH(h, PBT_K_OPTIMIZER, s, optimizer_step(oa, s));
   return PBT_OK;
@@ -346,9 +307,9 @@ pbt_status eval_bf16(pbt_handle* h, const float* eval_x, const int32_t* eval_y, 
       in_stride = (int64_t)rows * c.dims[l + 1];
     }
     PBT_HIP(h, head_fwd_loss(in, in_stride, W16 + p.lay.w_off[L - 1], S, W32 + p.lay.b_off[L - 1], S, eval_y + r0, 0, P,
-                             rows, c.dims[L - 1], c.dims[L], 0.f, nullptr, rowloss + r0, c.n_eval, s));
+                             rows, c.dims[L - 1], c.dims[L], 0.f, -1, nullptr, rowloss + r0, c.n_eval, s));
   }
-  PBT_HIP(h, row_reduce(rowloss, c.n_eval, P, c.n_eval, -1.f / (float)c.n_eval, h->st<float>(p.o_score), s));
+  PBT_HIP(h, row_reduce(rowloss, c.n_eval, P, c.n_eval, -1.f / (float)c.n_eval, h->st<float>(p.o_score), 1, s));
   return PBT_OK;
 }
 
@@ -428,9 +389,14 @@ pbt_status pbt_init_population(pbt_handle* h, const pbt_prior* priors, void* hip
   a.W32 = h->st<float>(p.o_w32);
   a.W16 = c.compute_dtype == PBT_DTYPE_BF16 ? h->st<bf16_t>(p.o_w16) : nullptr;
   a.H = h->st<float>(p.o_hyper);
-  a.stride = p.lay.stride; a.P = c.P; a.n_layers = c.n_layers; a.n_hyper = c.n_hyper;
-  for (int l = 0; l <= c.n_layers; ++l) a.dims[l] = c.dims[l];
-  for (int l = 0; l < c.n_layers; ++l) { a.w_off[l] = p.lay.w_off[l]; a.b_off[l] = p.lay.b_off[l]; }
+  a.stride = p.lay.stride; a.P = c.P; a.n_hyper = c.n_hyper;
+  a.n_layers = c.n_layers + (c.workload == PBT_WL_GAN ? c.n_layers2 : 0);
+  for (int l = 0; l < a.n_layers; ++l) {
+    a.fan_in[l] = l < c.n_layers ? c.dims[l] : c.dims2[l - c.n_layers];
+    a.fan_out[l] = l < c.n_layers ? c.dims[l + 1] : c.dims2[l - c.n_layers + 1];
+    a.w_off[l] = p.lay.w_off[l];
+    a.b_off[l] = p.lay.b_off[l];
+  }
   a.seed = c.seed;
   PBT_HIP(h, init_population(a, s));
   return PBT_OK;
@@ -439,6 +405,15 @@ pbt_status pbt_init_population(pbt_handle* h, const pbt_prior* priors, void* hip
 pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, int64_t step_index, int32_t n_steps,
                     void* hip_stream) {
   if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  if (h->cfg.workload == PBT_WL_GAN) {
+    if (!d_inputs || n_inputs != 1 || !d_inputs[0]) return fail(h, PBT_EINVAL, "GAN step needs 1 input: train_x");
+    if (n_steps < 0 || step_index < 0 || step_index + n_steps > 0xffffffffLL) return fail(h, PBT_EINVAL, "step range outside 0..2^32-1");
+    for (int k = 0; k < n_steps; ++k) {
+      pbt_status st = gan_step(h, static_cast<const float*>(d_inputs[0]), (uint32_t)(step_index + k), static_cast<hipStream_t>(hip_stream));
+      if (st != PBT_OK) return st;
+    }
+    return PBT_OK;
+  }
   if (!d_inputs || n_inputs != 2 || !d_inputs[0] || !d_inputs[1])
     return fail(h, PBT_EINVAL, "classifier step needs 2 inputs: train_x, train_y");
   if (n_steps < 0 || step_index < 0 || step_index + n_steps > 0xffffffffLL) return fail(h, PBT_EINVAL, "step range outside 0..2^32-1");
@@ -464,6 +439,10 @@ pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs
 
 pbt_status pbt_eval(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, void* hip_stream) {
   if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  if (h->cfg.workload == PBT_WL_GAN) {
+    if (!d_inputs || n_inputs != 1 || !d_inputs[0]) return fail(h, PBT_EINVAL, "GAN eval needs 1 input: eval_x");
+    return gan_eval(h, static_cast<const float*>(d_inputs[0]), static_cast<hipStream_t>(hip_stream));
+  }
   if (!d_inputs || n_inputs != 2 || !d_inputs[0] || !d_inputs[1])
     return fail(h, PBT_EINVAL, "classifier eval needs 2 inputs: eval_x, eval_y");
   hipStream_t s = static_cast<hipStream_t>(hip_stream);

@@ -1,0 +1,245 @@
+// The GAN workload (Section 4.3.1 of the PBT paper: generator and discriminator trained with Adam,
+// each with its own learning rate per member, both copied on exploit, scored by a sample-quality
+// metric that is not the training loss).  Host side: checks, scratch carve-up and the kernel
+// sequences of one population step (discriminator update, then generator update through the updated
+// discriminator) and of the MMD score.
+#include <cstring>
+
+#include "handle.h"
+
+namespace pbt {
+
+namespace {
+
+struct Net {  // a view of one of the two MLPs inside the member's flat parameter vector
+  int L;
+  const int32_t* dims;
+  int first;  // index of its first layer in the layout
+  int hidden_act, out_act;
+};
+
+Net gen_net(const pbt_config& c) { return Net{c.n_layers, c.dims, 0, c.act, c.act_out}; }
+Net dis_net(const pbt_config& c) { return Net{c.n_layers2, c.dims2, c.n_layers, c.act2, PBT_ACT_NONE}; }
+
+// Dense layers 0 .. n_dense-1 of `net` on `rows` rows per member: in[l+1] = act(in[l] W_l + b_l).
+// A[l] (inputs), Z[l] (pre-activations, may be null when no backward pass follows) are bf16
+// [P][rows][width]; the output of the last dense layer goes to `last_out` with batch stride
+// `last_stride` (so that it can land inside another network's input buffer).
+pbt_status forward(pbt_handle* h, const Net& net, int n_dense, int rows, bf16_t* const* A, bf16_t* const* Z, bf16_t* last_out,
+                   int64_t last_stride, hipStream_t s) {
+  const pbt_config& c = h->cfg;
+  const Plan& p = h->plan;
+  const int64_t S = p.lay.stride;
+  const float* W32 = h->st<float>(p.o_w32);
+  const bf16_t* W16 = h->st<bf16_t>(p.o_w16);
+  for (int l = 0; l < n_dense; ++l) {
+    const int K = net.dims[l], N = net.dims[l + 1];
+    const bool last = l == n_dense - 1;
+    const int act = (l == net.L - 1) ? net.out_act : net.hidden_act;
+    GemmOperands o{A[l], K, (int64_t)rows * K, false, W16 + p.lay.w_off[net.first + l], N, S, false, rows, N, K, c.P};
+    bf16_t* out = last && last_out ? last_out : A[l + 1];
+    const int64_t so = last && last_out ? last_stride : (int64_t)rows * N;
+    PBT_LAUNCH(h, PBT_K_GEMM_FWD, s, gemm_bias_act(o, W32 + p.lay.b_off[net.first + l], S, Z ? Z[l] : nullptr, out, N, so, act, s));
+  }
+  return PBT_OK;
+}
+
+// Backward through dense layers n_dense-1 .. 0 given dZ[n_dense-1]: weight / bias gradients into G
+// (when want_wgrad) and dZ[l-1] = (dZ[l] W_l^T) * act'(Z[l-1]).  For l = 0 the input gradient is
+// produced only when in_z != null: dIn = (dZ[0] W_0^T) * act'(in_z) with activation in_act.
+pbt_status backward(pbt_handle* h, const Net& net, int n_dense, int rows, bf16_t* const* A, bf16_t* const* Z, bf16_t* const* dZ,
+                    bool want_wgrad, const bf16_t* in_z, bf16_t* in_dz, int in_act, hipStream_t s) {
+  const pbt_config& c = h->cfg;
+  const Plan& p = h->plan;
+  const int64_t S = p.lay.stride;
+  const bf16_t* W16 = h->st<bf16_t>(p.o_w16);
+  float* G = h->sc<float>(p.o_grad);
+  for (int l = n_dense - 1; l >= 0; --l) {
+    const int K = net.dims[l], N = net.dims[l + 1];
+    if (want_wgrad) {
+      GemmOperands wg{A[l], K, (int64_t)rows * K, true, dZ[l], N, (int64_t)rows * N, false, K, N, rows, c.P};
+      PBT_LAUNCH(h, PBT_K_GEMM_WGRAD, s, gemm_store_f32(wg, G + p.lay.w_off[net.first + l], N, S, s));
+      PBT_LAUNCH(h, PBT_K_BIAS_GRAD, s, bias_grad(dZ[l], c.P, rows, N, N, G + p.lay.b_off[net.first + l], S, s));
+    }
+    const bf16_t* zprev = l > 0 ? Z[l - 1] : in_z;
+    bf16_t* dzprev = l > 0 ? dZ[l - 1] : in_dz;
+    if (zprev) {
+      GemmOperands dg{dZ[l], N, (int64_t)rows * N, false, W16 + p.lay.w_off[net.first + l], N, S, true, rows, K, N, c.P};
+      PBT_LAUNCH(h, PBT_K_GEMM_DGRAD, s, gemm_dgrad_act(dg, zprev, dzprev, K, (int64_t)rows * K, l > 0 ? net.hidden_act : in_act, s));
+    }
+  }
+  return PBT_OK;
+}
+
+struct Bufs {
+  bf16_t* gA[PBT_MAX_DIMS]; bf16_t* gZ[PBT_MAX_DIMS]; bf16_t* gdZ[PBT_MAX_DIMS];
+  bf16_t* dA[PBT_MAX_DIMS]; bf16_t* dZ[PBT_MAX_DIMS]; bf16_t* ddZ[PBT_MAX_DIMS];
+};
+
+Bufs bufs_of(pbt_handle* h) {
+  const pbt_config& c = h->cfg;
+  const GanPlan& g = h->plan.gan;
+  Bufs b;
+  std::memset(&b, 0, sizeof b);
+  b.gA[0] = h->sc<bf16_t>(g.o_zin);
+  for (int l = 0; l < c.n_layers; ++l) {
+    b.gA[l + 1] = h->sc<bf16_t>(g.o_ga[l]);
+    b.gZ[l] = h->sc<bf16_t>(g.o_gz[l]);
+    b.gdZ[l] = h->sc<bf16_t>(g.o_gdz[l]);
+  }
+  b.dA[0] = h->sc<bf16_t>(g.o_dx);
+  for (int l = 0; l < c.n_layers2 - 1; ++l) {
+    b.dA[l + 1] = h->sc<bf16_t>(g.o_da[l]);
+    b.dZ[l] = h->sc<bf16_t>(g.o_dz[l]);
+    b.ddZ[l] = h->sc<bf16_t>(g.o_ddz[l]);
+  }
+  return b;
+}
+
+pbt_status adam_range(pbt_handle* h, int64_t begin, int64_t count, int col_lr, hipStream_t s) {
+  const pbt_config& c = h->cfg;
+  const Plan& p = h->plan;
+  OptArgs oa{h->st<float>(p.o_w32), h->st<float>(p.o_opt0), h->st<float>(p.o_opt1), h->st<bf16_t>(p.o_w16), h->sc<float>(p.o_grad),
+             begin, count, h->st<float>(p.o_hyper), h->st<int32_t>(p.o_t), p.lay.stride, c.P, c.n_hyper, PBT_OPT_ADAM, col_lr, -1, -1,
+             c.opt_const[0], c.opt_const[1], c.opt_const[2], c.opt_const[3]};
+  PBT_LAUNCH(h, PBT_K_OPTIMIZER, s, optimizer_step(oa, s));
+  return PBT_OK;
+}
+
+}  // namespace
+
+pbt_status gan_check_and_plan(const pbt_config* c, Plan* pl, Carver* w) {
+  GanPlan& g = pl->gan;
+  const int Lg = c->n_layers, Ld = c->n_layers2;
+  if (Ld < 2) return fail(nullptr, PBT_EUNSUPPORTED, "the discriminator needs at least one hidden layer");
+  if (c->dims2[0] != c->dims[Lg]) return fail(nullptr, PBT_EINVAL, "discriminator input width must equal generator output width");
+  if (c->dims2[Ld] != 1) return fail(nullptr, PBT_EINVAL, "the discriminator must end in one logit");
+  for (int l = 0; l <= Lg; ++l)
+    if (c->dims[l] % 8) return fail(nullptr, PBT_EUNSUPPORTED, "generator widths must be multiples of 8");
+  for (int l = 0; l < Ld; ++l)
+    if (c->dims2[l] < 1 || c->dims2[l] % 8) return fail(nullptr, PBT_EUNSUPPORTED, "discriminator widths must be multiples of 8");
+  if (c->act_out < PBT_ACT_NONE || c->act_out > PBT_ACT_TANH || c->act2 < PBT_ACT_NONE || c->act2 > PBT_ACT_TANH)
+    return fail(nullptr, PBT_EINVAL, "unknown activation");
+  g.n_g = Lg;
+  g.n_d = Ld;
+  g.eval_rows = c->n_eval;
+  const int64_t P = c->P, B = c->batch, R = 2 * B, E = c->n_eval, D = c->dims2[0];
+  g.o_zin = w->take((size_t)P * B * c->dims[0] * 2);
+  for (int l = 0; l < Lg; ++l) {
+    g.o_ga[l] = w->take((size_t)P * B * c->dims[l + 1] * 2);
+    g.o_gz[l] = w->take((size_t)P * B * c->dims[l + 1] * 2);
+    g.o_gdz[l] = w->take((size_t)P * B * c->dims[l + 1] * 2);
+  }
+  g.o_dx = w->take((size_t)P * R * D * 2);
+  for (int l = 0; l < Ld - 1; ++l) {
+    g.o_da[l] = w->take((size_t)P * R * c->dims2[l + 1] * 2);
+    g.o_dz[l] = w->take((size_t)P * R * c->dims2[l + 1] * 2);
+    g.o_ddz[l] = w->take((size_t)P * R * c->dims2[l + 1] * 2);
+  }
+  g.o_dlogits = w->take((size_t)P * R * 32 * 2);
+  g.o_rowloss = w->take((size_t)P * R * 4);
+  // eval: latents, two ping-pong hidden buffers, generated rows, held-out rows (bf16), norms, partial sums
+  int64_t maxh = 8;
+  for (int l = 1; l < Lg; ++l) maxh = c->dims[l] > maxh ? c->dims[l] : maxh;
+  g.o_ez = w->take((size_t)P * E * c->dims[0] * 2);
+  g.o_ea[0] = w->take((size_t)P * E * maxh * 2);
+  g.o_ea[1] = w->take((size_t)P * E * maxh * 2);
+  g.o_ex = w->take((size_t)P * E * D * 2);
+  g.o_ey = w->take((size_t)E * D * 2);
+  g.o_nx = w->take((size_t)P * E * 4);
+  g.o_ny = w->take((size_t)E * 4);
+  g.o_pxx = w->take((size_t)gemm_rbf_tiles((int)E, (int)E, (int)P) * P * 4);
+  g.o_pyy = w->take((size_t)gemm_rbf_tiles((int)E, (int)E, 1) * 4);
+  g.o_pxy = w->take((size_t)gemm_rbf_tiles((int)E, (int)E, (int)P) * P * 4);
+  return PBT_OK;
+}
+
+pbt_status gan_step(pbt_handle* h, const float* train_x, uint32_t step, hipStream_t s) {
+  const pbt_config& c = h->cfg;
+  const Plan& p = h->plan;
+  const GanPlan& g = p.gan;
+  const int P = c.P, B = c.batch, R = 2 * B, D = c.dims2[0];
+  const int64_t S = p.lay.stride;
+  const Net gnet = gen_net(c), dnet = dis_net(c);
+  Bufs b = bufs_of(h);
+  const float* W32 = h->st<float>(p.o_w32);
+  const bf16_t* W16 = h->st<bf16_t>(p.o_w16);
+  float* G = h->sc<float>(p.o_grad);
+  bf16_t* dlogits = h->sc<bf16_t>(g.o_dlogits);
+  float* rowloss = h->sc<float>(g.o_rowloss);
+  float* loss = h->st<float>(p.o_loss);
+  const int Ld = c.n_layers2, Kh = c.dims2[Ld - 1];
+  const int head = c.n_layers + Ld - 1;  // layout index of the discriminator's output layer
+  pbt_status st;
+
+  // ---- discriminator update: B real rows (0..B-1) and B generated rows (B..2B-1), generator fixed
+  PBT_LAUNCH(h, PBT_K_FETCH, s, gather_rows(train_x, c.n_train, D, P, B, (int64_t)R * D, step, c.seed, b.dA[0], h->st<int32_t>(p.o_t), s));
+  PBT_LAUNCH(h, PBT_K_FETCH, s, latent_normal(b.gA[0], P, B, c.dims[0], step, 0, c.seed, s));
+  if ((st = forward(h, gnet, gnet.L, B, b.gA, nullptr, b.dA[0] + (int64_t)B * D, (int64_t)R * D, s)) != PBT_OK) return st;
+  if ((st = forward(h, dnet, Ld - 1, R, b.dA, b.dZ, nullptr, 0, s)) != PBT_OK) return st;
+  PBT_LAUNCH(h, PBT_K_HEAD, s, head_fwd_loss(b.dA[Ld - 1], (int64_t)R * Kh, W16 + p.lay.w_off[head], S, W32 + p.lay.b_off[head], S,
+                                             nullptr, 0, P, R, Kh, 1, 1.f / (float)B, B, dlogits, rowloss, R, s));
+  PBT_LAUNCH(h, PBT_K_HEAD, s, row_reduce(rowloss, R, P, R, 1.f / (float)B, loss, 2, s));
+  {
+    GemmOperands wg{b.dA[Ld - 1], Kh, (int64_t)R * Kh, true, dlogits, 32, (int64_t)R * 32, false, Kh, 1, R, P};
+    PBT_LAUNCH(h, PBT_K_HEAD, s, gemm_store_f32(wg, G + p.lay.w_off[head], 1, S, s));
+    PBT_LAUNCH(h, PBT_K_HEAD, s, bias_grad(dlogits, P, R, 1, 32, G + p.lay.b_off[head], S, s));
+  }
+  PBT_LAUNCH(h, PBT_K_HEAD, s, head_dgrad(dlogits, W16 + p.lay.w_off[head], S, b.dZ[Ld - 2], b.ddZ[Ld - 2], P, R, Kh, 1, dnet.hidden_act, s));
+  if ((st = backward(h, dnet, Ld - 1, R, b.dA, b.dZ, b.ddZ, true, nullptr, nullptr, 0, s)) != PBT_OK) return st;
+  if ((st = adam_range(h, g.d_begin, g.d_count, g.col_lr_d, s)) != PBT_OK) return st;
+
+  // ---- generator update: B fresh generated rows through the updated discriminator
+  PBT_LAUNCH(h, PBT_K_FETCH, s, latent_normal(b.gA[0], P, B, c.dims[0], step, 1, c.seed, s));
+  if ((st = forward(h, gnet, gnet.L, B, b.gA, b.gZ, nullptr, 0, s)) != PBT_OK) return st;
+  {
+    bf16_t* dA[PBT_MAX_DIMS];
+    std::memcpy(dA, b.dA, sizeof dA);
+    dA[0] = b.gA[gnet.L];  // the discriminator reads the generator's output directly
+    if ((st = forward(h, dnet, Ld - 1, B, dA, b.dZ, nullptr, 0, s)) != PBT_OK) return st;
+    PBT_LAUNCH(h, PBT_K_HEAD, s, head_fwd_loss(dA[Ld - 1], (int64_t)B * Kh, W16 + p.lay.w_off[head], S, W32 + p.lay.b_off[head], S,
+                                               nullptr, 0, P, B, Kh, 1, 1.f / (float)B, B, dlogits, rowloss, B, s));
+    PBT_LAUNCH(h, PBT_K_HEAD, s, row_reduce(rowloss, B, P, B, 1.f / (float)B, loss + 1, 2, s));
+    PBT_LAUNCH(h, PBT_K_HEAD, s, head_dgrad(dlogits, W16 + p.lay.w_off[head], S, b.dZ[Ld - 2], b.ddZ[Ld - 2], P, B, Kh, 1, dnet.hidden_act, s));
+    // through the discriminator down to its input, no weight gradients; the input gradient is
+    // multiplied by the derivative of the generator's output activation on the way
+    if ((st = backward(h, dnet, Ld - 1, B, dA, b.dZ, b.ddZ, false, b.gZ[gnet.L - 1], b.gdZ[gnet.L - 1], gnet.out_act, s)) != PBT_OK) return st;
+  }
+  if ((st = backward(h, gnet, gnet.L, B, b.gA, b.gZ, b.gdZ, true, nullptr, nullptr, 0, s)) != PBT_OK) return st;
+  return adam_range(h, 0, g.g_count, g.col_lr_g, s);
+}
+
+pbt_status gan_eval(pbt_handle* h, const float* eval_x, hipStream_t s) {
+  const pbt_config& c = h->cfg;
+  const Plan& p = h->plan;
+  const GanPlan& g = p.gan;
+  const int P = c.P, E = c.n_eval, D = c.dims2[0];
+  const Net gnet = gen_net(c);
+  bf16_t* X = h->sc<bf16_t>(g.o_ex);
+  bf16_t* Y = h->sc<bf16_t>(g.o_ey);
+  float* nx = h->sc<float>(g.o_nx);
+  float* ny = h->sc<float>(g.o_ny);
+  // generated rows: latents (sub-stream 2, step index 0) through the generator
+  bf16_t* A[PBT_MAX_DIMS];
+  A[0] = h->sc<bf16_t>(g.o_ez);
+  for (int l = 0; l < gnet.L; ++l) A[l + 1] = h->sc<bf16_t>(g.o_ea[l & 1]);
+  PBT_LAUNCH(h, PBT_K_FETCH, s, latent_normal(A[0], P, E, c.dims[0], 0u, 2, c.seed, s));
+  pbt_status st = forward(h, gnet, gnet.L, E, A, nullptr, X, (int64_t)E * D, s);
+  if (st != PBT_OK) return st;
+  PBT_HIP(h, f32_to_bf16(eval_x, Y, (int64_t)E * D, s));
+  PBT_HIP(h, row_sqnorm(X, P, E, D, nx, s));
+  PBT_HIP(h, row_sqnorm(Y, 1, E, D, ny, s));
+  const float inv2d = 1.f / (2.f * (float)D);
+  int txx = 0, tyy = 0, txy = 0;
+  GemmOperands xx{X, D, (int64_t)E * D, false, X, D, (int64_t)E * D, true, E, E, D, P};
+  PBT_HIP(h, gemm_rbf_sum(xx, nx, E, nx, E, inv2d, h->sc<float>(g.o_pxx), &txx, s));
+  GemmOperands yy{Y, D, 0, false, Y, D, 0, true, E, E, D, 1};
+  PBT_HIP(h, gemm_rbf_sum(yy, ny, 0, ny, 0, inv2d, h->sc<float>(g.o_pyy), &tyy, s));
+  GemmOperands xy{X, D, (int64_t)E * D, false, Y, D, 0, true, E, E, D, P};
+  PBT_HIP(h, gemm_rbf_sum(xy, nx, E, ny, 0, inv2d, h->sc<float>(g.o_pxy), &txy, s));
+  PBT_HIP(h, mmd_combine(h->sc<float>(g.o_pxx), txx, h->sc<float>(g.o_pyy), tyy, h->sc<float>(g.o_pxy), txy, P,
+                         1.f / ((float)E * (float)E), h->st<float>(p.o_score), s));
+  return PBT_OK;
+}
+
+}  // namespace pbt

@@ -24,4 +24,16 @@ hipError_t gemm_dgrad_act(const GemmOperands& o, const bf16_t* Zprev, bf16_t* dZ
   return run(o, EpiDgradAct{Zprev, dZ, ld, so, act}, s);
 }
 
+hipError_t gemm_rbf_sum(const GemmOperands& o, const float* na, int64_t sna, const float* nb, int64_t snb, float inv2d,
+                        float* partial, int* tiles, hipStream_t s) {
+  // tile count as launch_gemm_bf16 will choose it (the caller sizes `partial` with gemm_rbf_tiles)
+  *tiles = gemm_rbf_tiles(o.M, o.N, o.batch);
+  return run(o, EpiRbfSum{na, sna, nb, snb, inv2d, partial, 0.f}, s);
+}
+int gemm_rbf_tiles(int M, int N, int batch) {
+  const int64_t wide = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
+  const int bn = (wide < 4 * 256 && N > 64) ? 64 : 128;
+  return ((M + 127) / 128) * ((N + bn - 1) / bn);
+}
+
 }  // namespace pbt

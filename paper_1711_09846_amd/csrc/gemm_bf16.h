@@ -218,11 +218,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs g, Epi
         if (m < g.M && n < g.N) epi(member, m, n, acc[i][j][e]);
       }
     }
+  if constexpr (Epilogue::HAS_FINISH) epi.finish(member, tm * g.tiles_n + tn, g.tiles_m * g.tiles_n);
 }
 
 // ---- epilogues ------------------------------------------------------------------------------
 
 struct EpiStoreF32 {
+  static constexpr bool HAS_FINISH = false;
   float* C;
   int64_t ldc, sc;
   __device__ __forceinline__ void operator()(int member, int m, int n, float v) const {
@@ -231,6 +233,7 @@ struct EpiStoreF32 {
 };
 
 struct EpiStoreBF16 {
+  static constexpr bool HAS_FINISH = false;
   bf16_t* C;
   int64_t ldc, sc;
   __device__ __forceinline__ void operator()(int member, int m, int n, float v) const {
@@ -240,6 +243,7 @@ struct EpiStoreBF16 {
 
 // Forward layer: z = acc + b[n]; stores z (for the backward pass, may be null) and act(z), both bf16.
 struct EpiBiasAct {
+  static constexpr bool HAS_FINISH = false;
   const float* bias;  // + member * sbias + n
   int64_t sbias;
   bf16_t* Z;
@@ -256,6 +260,7 @@ struct EpiBiasAct {
 
 // Input gradient: dz_prev = acc * act'(z_prev), bf16.
 struct EpiDgradAct {
+  static constexpr bool HAS_FINISH = false;
   const bf16_t* Zprev;
   bf16_t* dZ;
   int64_t ld, so;
@@ -286,6 +291,33 @@ hipError_t launch_gemm_tile(const GemmArgs& g0, bool a_m_contig, bool b_k_contig
     hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, 2, 2, true, true, Epilogue>), grid, block, 0, stream, g, epi);
   return hipGetLastError();
 }
+
+// Sum over the tile of exp(-(|a_m|^2 + |b_n|^2 - 2 a_m.b_n) / (2 d)): the RBF kernel of the MMD
+// score evaluated on the Gram tile while it is still in the accumulators.  Every thread adds its
+// elements in a fixed order, the wavefront and then the four wavefronts are combined in a fixed
+// order, and the tile's sum goes to partial[member][tile]; a later pass adds the tiles.
+struct EpiRbfSum {
+  static constexpr bool HAS_FINISH = true;
+  const float* na;  // squared norms of the A rows, + member * sna
+  int64_t sna;
+  const float* nb;
+  int64_t snb;
+  float inv2d;
+  float* partial;
+  float sum;
+  __device__ __forceinline__ void operator()(int member, int m, int n, float v) {
+    const float sq = na[(int64_t)member * sna + m] + nb[(int64_t)member * snb + n] - 2.f * v;
+    sum += expf(-sq * inv2d);
+  }
+  __device__ __forceinline__ void finish(int member, int tile, int tiles) {
+    __shared__ float wsum[4];
+    const float w = wave_sum(sum);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = w;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[(int64_t)member * tiles + tile] = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
+  }
+};
 
 // Host-side launcher: picks the tile shape.  128x128 tiles unless that leaves the 256 compute units
 // with fewer than four workgroups each to hide memory latency with; then 128x64.  Caller guarantees

@@ -1,0 +1,104 @@
+// Host-side state behind a pbt_handle: the validated configuration, the carve-up of the caller's
+// two device buffers, error reporting and the launch macros shared by the workload files.
+#pragma once
+#include "../../include/pbt.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "internal.h"
+
+namespace pbt {
+
+constexpr int64_t SEG_ALIGN = 64;      // elements: start of every W_l and b_l
+constexpr int64_t STRIDE_ALIGN = 256;  // elements: per-member stride
+constexpr size_t BUF_ALIGN = 256;      // bytes: every carved array
+
+inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+struct Carver {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    const size_t o = off;
+    off += (bytes + BUF_ALIGN - 1) / BUF_ALIGN * BUF_ALIGN;
+    return o;
+  }
+};
+
+struct GanPlan {
+  int n_g, n_d;                       // layers of generator / discriminator; layer l of D is layout index n_g + l
+  int64_t g_count, d_begin, d_count;  // ranges of the flat parameter vector
+  int col_lr_g, col_lr_d;
+  int eval_rows;
+  // scratch offsets (bytes)
+  size_t o_zin, o_ga[PBT_MAX_DIMS], o_gz[PBT_MAX_DIMS], o_gdz[PBT_MAX_DIMS];
+  size_t o_dx, o_da[PBT_MAX_DIMS], o_dz[PBT_MAX_DIMS], o_ddz[PBT_MAX_DIMS];
+  size_t o_dlogits, o_rowloss;
+  size_t o_ez, o_ea[2], o_ex, o_ey, o_nx, o_ny, o_pxx, o_pyy, o_pxy;
+};
+
+struct Plan {
+  pbt_layout lay;
+  int n_loss;
+  // offsets in bytes inside d_state
+  size_t o_w32, o_opt0, o_opt1, o_w16, o_hyper, o_score, o_loss, o_t, o_order, o_donor, o_parent, o_recip;
+  size_t state_bytes;
+  // offsets in bytes inside d_scratch
+  size_t o_grad, o_y, o_dlogits, o_rowloss, o_x32;
+  size_t o_act[PBT_MAX_DIMS], o_z[PBT_MAX_DIMS], o_dz[PBT_MAX_DIMS];
+  size_t o_evalx, o_evala[2], o_evalrow;
+  size_t scratch_bytes;
+  int eval_chunk;
+  bool fused_small;  // fp32: the whole step runs in one LDS-resident kernel
+  int col_lr, col_beta1, col_wd;
+  GanPlan gan;
+};
+
+}  // namespace pbt
+
+struct pbt_handle {
+  pbt_config cfg;
+  pbt::Plan plan;
+  char* state;
+  char* scratch;
+  std::string err;
+  // optional event timing of one kernel class
+  int timed_class = PBT_K_NONE;
+  std::vector<hipEvent_t> ev_start, ev_stop;
+  size_t ev_used = 0;
+  template <class T> T* st(size_t off) const { return reinterpret_cast<T*>(state + off); }
+  template <class T> T* sc(size_t off) const { return reinterpret_cast<T*>(scratch + off); }
+};
+
+namespace pbt {
+
+// Records the message on the handle (when there is one) and per thread; returns `code`.
+pbt_status fail(pbt_handle* h, pbt_status code, const char* fmt, ...);
+
+#define PBT_HIP(h, call)                                                                        \
+  do {                                                                                          \
+    hipError_t e_ = (call);                                                                     \
+    if (e_ != hipSuccess) return pbt::fail(h, PBT_EDEVICE, "%s failed: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+// Runs `call` (a launcher returning hipError_t); when its class is the timed one, brackets it
+// with an event pair on the same stream.
+#define PBT_LAUNCH(h, klass, s, call)                                                           \
+  do {                                                                                          \
+    const bool timed_ = (h)->timed_class == (klass) && (h)->ev_used < (h)->ev_start.size();     \
+    if (timed_) PBT_HIP(h, hipEventRecord((h)->ev_start[(h)->ev_used], s));                     \
+    PBT_HIP(h, call);                                                                           \
+    if (timed_) {                                                                               \
+      PBT_HIP(h, hipEventRecord((h)->ev_stop[(h)->ev_used], s));                                \
+      ++(h)->ev_used;                                                                           \
+    }                                                                                           \
+  } while (0)
+
+// gan_host.hip: the GAN workload (Section 4.3.1)
+pbt_status gan_check_and_plan(const pbt_config* c, Plan* pl, Carver* scratch);
+pbt_status gan_step(pbt_handle* h, const float* train_x, uint32_t step, hipStream_t s);
+pbt_status gan_eval(pbt_handle* h, const float* eval_x, hipStream_t s);
+
+}  // namespace pbt

@@ -31,7 +31,8 @@ __global__ __launch_bounds__(256) void head_fwd_loss_kernel(const bf16_t* __rest
                                                             const bf16_t* __restrict__ W16, int64_t sw,
                                                             const float* __restrict__ bias, int64_t sbias,
                                                             const int32_t* __restrict__ labels, int64_t sy, int rows,
-                                                            int K, int C, float gscale, bf16_t* __restrict__ dlogits,
+                                                            int K, int C, float gscale, int n_pos,
+                                                            bf16_t* __restrict__ dlogits,
                                                             float* __restrict__ rowloss, int64_t srowloss) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int pitch = K + 8;
@@ -76,30 +77,46 @@ __global__ __launch_bounds__(256) void head_fwd_loss_kernel(const bf16_t* __rest
     if (r < rows) {
       const float* __restrict__ b = bias + (int64_t)i * sbias;
       float* lg = Lg + threadIdx.x * 33;
-      float mx = -INFINITY;
-      int cm = 0;
-      for (int c = 0; c < C; ++c) {
-        lg[c] += b[c];
-        if (lg[c] > mx) { mx = lg[c]; cm = c; }
-      }
-      // log-sum-exp with the largest term split off: lse = mx + log1p(sum of the others)
-      const int y = labels[(int64_t)i * sy + r];
-      float rest = 0.f, others = (y == cm) ? 0.f : 1.f;
-      for (int c = 0; c < C; ++c) {
-        if (c == cm) continue;
-        const float ex = expf(lg[c] - mx);
-        rest += ex;
-        if (c != y) others += ex;
-      }
-      rowloss[(int64_t)i * srowloss + r] = log1pf(rest) + (mx - lg[y]);
-      if (dlogits) {
-        // softmax_y - 1 = -(sum of the other classes' terms) / S: no cancellation as softmax_y -> 1
-        const float inv = 1.f / (1.f + rest);
-        bf16_t* __restrict__ d = dlogits + ((int64_t)i * rows + r) * HEAD_NP;
-        for (int c = 0; c < HEAD_NP; ++c) {
-          float v = 0.f;
-          if (c < C) v = (c == y ? -others * inv : expf(lg[c] - mx) * inv) * gscale;
-          d[c] = f2bf(v);
+      if (n_pos >= 0) {
+        // logistic loss on one logit: target 1 for rows < n_pos, else 0.
+        // loss = softplus(-l) or softplus(l) = max(x, 0) + log1p(exp(-|x|)); dl = sigmoid(l) - target
+        const float l = lg[0] + b[0];
+        const float target = r < n_pos ? 1.f : 0.f;
+        const float x = r < n_pos ? -l : l;
+        const float en = expf(-fabsf(l));
+        rowloss[(int64_t)i * srowloss + r] = fmaxf(x, 0.f) + log1pf(en);
+        if (dlogits) {
+          const float sig = l >= 0.f ? 1.f / (1.f + en) : en / (1.f + en);
+          bf16_t* __restrict__ d = dlogits + ((int64_t)i * rows + r) * HEAD_NP;
+          d[0] = f2bf((sig - target) * gscale);
+          for (int c = 1; c < HEAD_NP; ++c) d[c] = 0;
+        }
+      } else {
+        float mx = -INFINITY;
+        int cm = 0;
+        for (int c = 0; c < C; ++c) {
+          lg[c] += b[c];
+          if (lg[c] > mx) { mx = lg[c]; cm = c; }
+        }
+        // log-sum-exp with the largest term split off: lse = mx + log1p(sum of the others)
+        const int y = labels[(int64_t)i * sy + r];
+        float rest = 0.f, others = (y == cm) ? 0.f : 1.f;
+        for (int c = 0; c < C; ++c) {
+          if (c == cm) continue;
+          const float ex = expf(lg[c] - mx);
+          rest += ex;
+          if (c != y) others += ex;
+        }
+        rowloss[(int64_t)i * srowloss + r] = log1pf(rest) + (mx - lg[y]);
+        if (dlogits) {
+          // softmax_y - 1 = -(sum of the other classes' terms) / S: no cancellation as softmax_y -> 1
+          const float inv = 1.f / (1.f + rest);
+          bf16_t* __restrict__ d = dlogits + ((int64_t)i * rows + r) * HEAD_NP;
+          for (int c = 0; c < HEAD_NP; ++c) {
+            float v = 0.f;
+            if (c < C) v = (c == y ? -others * inv : expf(lg[c] - mx) * inv) * gscale;
+            d[c] = f2bf(v);
+          }
         }
       }
     }
@@ -107,9 +124,9 @@ __global__ __launch_bounds__(256) void head_fwd_loss_kernel(const bf16_t* __rest
 }
 
 hipError_t head_fwd_loss(const bf16_t* A, int64_t sa, const bf16_t* W16, int64_t sw, const float* bias, int64_t sbias,
-                         const int32_t* labels, int64_t sy, int P, int rows, int K, int C, float gscale,
+                         const int32_t* labels, int64_t sy, int P, int rows, int K, int C, float gscale, int n_pos,
                          bf16_t* dlogits, float* rowloss, int64_t srowloss, hipStream_t s) {
-  if (C > HEAD_NP || C < 1 || K % 8) return hipErrorInvalidValue;
+  if (C > HEAD_NP || C < 1 || K % 8 || (n_pos >= 0 && C != 1)) return hipErrorInvalidValue;
   const size_t lds = (size_t)HEAD_NP * (K + 8) * 2 + (size_t)HEAD_ROWS * 33 * 4;
   if (lds > 160 * 1024) return hipErrorInvalidValue;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(head_fwd_loss_kernel),
@@ -117,7 +134,7 @@ hipError_t head_fwd_loss(const bf16_t* A, int64_t sa, const bf16_t* W16, int64_t
   if (e != hipSuccess) return e;
   dim3 grid((rows + HEAD_ROWS - 1) / HEAD_ROWS, P);
   hipLaunchKernelGGL(head_fwd_loss_kernel, grid, dim3(256), lds, s, A, sa, W16, sw, bias, sbias, labels, sy, rows, K, C,
-                     gscale, dlogits, rowloss, srowloss);
+                     gscale, n_pos, dlogits, rowloss, srowloss);
   return hipGetLastError();
 }
 

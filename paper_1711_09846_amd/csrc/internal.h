@@ -23,6 +23,12 @@ hipError_t gemm_bias_act(const GemmOperands& o, const float* bias, int64_t sbias
 hipError_t gemm_dgrad_act(const GemmOperands& o, const bf16_t* Zprev, bf16_t* dZ, int64_t ld, int64_t so, int act,
                           hipStream_t s);
 
+// Per-member sum over the whole M x N Gram matrix of exp(-(na[m] + nb[n] - 2 a_m.b_n) * inv2d), as
+// per-tile partial sums partial[batch][tiles] (tiles = gemm_rbf_tiles(M, N, batch)).
+int gemm_rbf_tiles(int M, int N, int batch);
+hipError_t gemm_rbf_sum(const GemmOperands& o, const float* na, int64_t sna, const float* nb, int64_t snb, float inv2d,
+                        float* partial, int* tiles, hipStream_t s);
+
 // ---- kernels.hip ----------------------------------------------------------------------------
 hipError_t fill_u32(uint32_t* p, uint32_t v, int64_t n, hipStream_t s);
 hipError_t iota_i32(int32_t* p, int n, hipStream_t s);
@@ -39,23 +45,26 @@ hipError_t gather_batch(const float* train_x, const int32_t* train_y, int n_trai
 // W16 + member*sw, b float at bias + member*sbias.  Writes rowloss[member*srowloss + r] and, when
 // dlogits != null, dlogits[P][rows][32] (bf16, zero padded) = (softmax - onehot) * gscale.
 // labels are [rows] shared (sy = 0) or per member (sy = rows).
+// n_pos < 0: softmax cross-entropy against `labels`.  n_pos >= 0 (needs C = 1): logistic loss, rows
+// r < n_pos have target 1, the others target 0 (labels unused).
 hipError_t head_fwd_loss(const bf16_t* A, int64_t sa, const bf16_t* W16, int64_t sw, const float* bias, int64_t sbias,
-                         const int32_t* labels, int64_t sy, int P, int rows, int K, int C, float gscale,
+                         const int32_t* labels, int64_t sy, int P, int rows, int K, int C, float gscale, int n_pos,
                          bf16_t* dlogits, float* rowloss, int64_t srowloss, hipStream_t s);
 // dZprev[P][rows][K] = (dlogits W^T) * act'(Zprev)
 hipError_t head_dgrad(const bf16_t* dlogits, const bf16_t* W16, int64_t sw, const bf16_t* Zprev, bf16_t* dZprev, int P,
                       int rows, int K, int C, int act, hipStream_t s);
 // db[n] = sum over rows of dZ[P][rows][ld], first N columns
 hipError_t bias_grad(const bf16_t* dZ, int P, int rows, int N, int64_t ld, float* db, int64_t sg, hipStream_t s);
-// out[i] = scale * sum_r rowval[i][r]   (one wavefront per member, fixed order)
-hipError_t row_reduce(const float* rowval, int64_t srow, int P, int rows, float scale, float* out, hipStream_t s);
+// out[i * out_stride] = scale * sum_r rowval[i][r]   (one wavefront per member, fixed order)
+hipError_t row_reduce(const float* rowval, int64_t srow, int P, int rows, float scale, float* out, int out_stride,
+                      hipStream_t s);
 
 // Initial population: uniform +-1/sqrt(fan_in) weights (positions outside any layer are zero) and
 // hyperparameters from the priors; all in double, rounded once to float.
 struct InitArgs {
   float* W32; bf16_t* W16; float* H;
   int64_t stride; int P, n_layers, n_hyper;
-  int dims[16]; int64_t w_off[16], b_off[16];
+  int fan_in[16], fan_out[16]; int64_t w_off[16], b_off[16];
   int prior_kind[8]; double prior_a[8], prior_b[8];  // uniform: a + u (b - a); log: exp(a + u (b - a)), a = ln lo
   uint64_t seed;
 };
@@ -63,6 +72,7 @@ hipError_t init_population(const InitArgs& a, hipStream_t s);
 
 struct OptArgs {
   float* W32; float* S0; float* S1; bf16_t* W16; const float* G;
+  int64_t begin, count;  // range of the member's flat vector to update (multiples of 4)
   const float* H; const int32_t* t;
   int64_t stride; int P; int n_hyper;
   int optimizer;
@@ -70,6 +80,19 @@ struct OptArgs {
   float c0, c1, c2, c3;           // opt_const
 };
 hipError_t optimizer_step(const OptArgs& a, hipStream_t s);
+
+// out[P][rows][d] (bf16) = standard normal latents: element e uses Philox counter
+// (c0, member, DOMAIN_LATENT + substream, e / 4); words (0,1) and (2,3) are one Box-Muller pair each
+// (cosine branch for even e, sine for odd), evaluated in double.
+hipError_t latent_normal(bf16_t* out, int P, int rows, int d, uint32_t c0, int substream, uint64_t seed, hipStream_t s);
+// out[batch][rows] = sum_k X[batch][rows][d]^2 (float)
+hipError_t row_sqnorm(const bf16_t* X, int batch, int rows, int d, float* out, hipStream_t s);
+// gathers rows of a float data set into bf16 X[P][ld_rows][d] rows 0..B-1 (Philox domain 1), t[i] += 1
+hipError_t gather_rows(const float* train_x, int n_train, int d, int P, int B, int64_t member_stride, uint32_t step,
+                       uint64_t seed, bf16_t* X16, int32_t* t, hipStream_t s);
+// score[i] = -( sxx[i] + syy[0] - 2 sxy[i] ) * inv_n2 where each s is the sum of `tiles` partials
+hipError_t mmd_combine(const float* pxx, int txx, const float* pyy, int tyy, const float* pxy, int txy, int P, float inv_n2,
+                       float* score, hipStream_t s);
 
 struct ExploitArgs {
   float* score; const float* score_override; float* H; int32_t* t; int32_t* order; int32_t* donor; int32_t* parent;

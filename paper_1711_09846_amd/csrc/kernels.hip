@@ -48,8 +48,8 @@ __global__ __launch_bounds__(256) void init_population_kernel(InitArgs a) {
   if (p < a.stride) {
     int fan_in = 0;
     for (int l = 0; l < a.n_layers; ++l) {
-      const int64_t nw = (int64_t)a.dims[l] * a.dims[l + 1];
-      if ((p >= a.w_off[l] && p < a.w_off[l] + nw) || (p >= a.b_off[l] && p < a.b_off[l] + a.dims[l + 1])) fan_in = a.dims[l];
+      const int64_t nw = (int64_t)a.fan_in[l] * a.fan_out[l];
+      if ((p >= a.w_off[l] && p < a.w_off[l] + nw) || (p >= a.b_off[l] && p < a.b_off[l] + a.fan_out[l])) fan_in = a.fan_in[l];
     }
     float v = 0.f;
     if (fan_in > 0) {
@@ -147,16 +147,17 @@ hipError_t bias_grad(const bf16_t* dZ, int P, int rows, int N, int64_t ld, float
 // Per-member reduction of per-row values with wavefront shuffles: lane l adds rows l, l+64, ...
 // in order, then a butterfly over the 64 lanes.
 __global__ __launch_bounds__(64) void row_reduce_kernel(const float* __restrict__ rowval, int64_t srow, int rows,
-                                                        float scale, float* __restrict__ out) {
+                                                        float scale, float* __restrict__ out, int out_stride) {
   const int i = blockIdx.x;
   const float* __restrict__ p = rowval + (int64_t)i * srow;
   float acc = 0.f;
   for (int r = threadIdx.x; r < rows; r += 64) acc += p[r];
   acc = wave_sum(acc);
-  if (threadIdx.x == 0) out[i] = acc * scale;
+  if (threadIdx.x == 0) out[(int64_t)i * out_stride] = acc * scale;
 }
-hipError_t row_reduce(const float* rowval, int64_t srow, int P, int rows, float scale, float* out, hipStream_t s) {
-  hipLaunchKernelGGL(row_reduce_kernel, dim3(P), dim3(64), 0, s, rowval, srow, rows, scale, out);
+hipError_t row_reduce(const float* rowval, int64_t srow, int P, int rows, float scale, float* out, int out_stride,
+                      hipStream_t s) {
+  hipLaunchKernelGGL(row_reduce_kernel, dim3(P), dim3(64), 0, s, rowval, srow, rows, scale, out, out_stride);
   return hipGetLastError();
 }
 
@@ -196,8 +197,8 @@ __global__ __launch_bounds__(256) void optimizer_kernel(OptArgs a) {
     inv_bc1 = 1.f / (1.f - powf(b1, tt));
     inv_bc2 = 1.f / (1.f - powf(a.c1, tt));
   }
-  const int64_t base = (int64_t)i * a.stride;
-  const int64_t nvec = a.stride / 4;
+  const int64_t base = (int64_t)i * a.stride + a.begin;
+  const int64_t nvec = a.count / 4;
 #pragma unroll
   for (int u = 0; u < OPT_VEC_PER_THREAD; ++u) {
     const int64_t v = ((int64_t)blockIdx.x * OPT_VEC_PER_THREAD + u) * 256 + threadIdx.x;
@@ -245,7 +246,8 @@ __global__ __launch_bounds__(256) void optimizer_kernel(OptArgs a) {
   }
 }
 hipError_t optimizer_step(const OptArgs& a, hipStream_t s) {
-  const int64_t nvec = a.stride / 4;
+  if (a.begin % 4 || a.count % 4 || a.count <= 0 || a.begin + a.count > a.stride) return hipErrorInvalidValue;
+  const int64_t nvec = a.count / 4;
   const int per_block = 256 * OPT_VEC_PER_THREAD;
   dim3 grid((unsigned)((nvec + per_block - 1) / per_block), a.P);
   if (a.optimizer == 0)
@@ -254,6 +256,88 @@ hipError_t optimizer_step(const OptArgs& a, hipStream_t s) {
     hipLaunchKernelGGL(optimizer_kernel<1>, grid, dim3(256), 0, s, a);
   else
     hipLaunchKernelGGL(optimizer_kernel<2>, grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+// ---- GAN workload: latents, real-row gather, squared norms, MMD combination -------------------
+
+__global__ __launch_bounds__(256) void latent_normal_kernel(bf16_t* __restrict__ out, int64_t per_member, uint32_t c0,
+                                                            uint32_t domain, uint32_t k0, uint32_t k1) {
+  const int i = blockIdx.y;
+  const int64_t blk = (int64_t)blockIdx.x * 256 + threadIdx.x;  // block of 4 elements
+  if (blk * 4 >= per_member) return;
+  const u32x4 w = philox4x32_10(c0, (uint32_t)i, domain, (uint32_t)blk, k0, k1);
+  const double r1 = sqrt(-2.0 * log(philox_unit(w.x))), a1 = 6.283185307179586476925 * philox_unit(w.y);
+  const double r2 = sqrt(-2.0 * log(philox_unit(w.z))), a2 = 6.283185307179586476925 * philox_unit(w.w);
+  const double v[4] = {r1 * cos(a1), r1 * sin(a1), r2 * cos(a2), r2 * sin(a2)};
+  bf16_t* __restrict__ o = out + (int64_t)i * per_member + blk * 4;
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    if (blk * 4 + e < per_member) o[e] = f2bf((float)v[e]);
+}
+hipError_t latent_normal(bf16_t* out, int P, int rows, int d, uint32_t c0, int substream, uint64_t seed, hipStream_t s) {
+  const int64_t per_member = (int64_t)rows * d;
+  const int64_t blocks4 = (per_member + 3) / 4;
+  hipLaunchKernelGGL(latent_normal_kernel, dim3((unsigned)((blocks4 + 255) / 256), P), dim3(256), 0, s, out, per_member, c0,
+                     (uint32_t)(DOMAIN_LATENT + substream), (uint32_t)seed, (uint32_t)(seed >> 32));
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(64) void gather_rows_kernel(const float* __restrict__ train_x, int n_train, int d,
+                                                         int64_t member_stride, uint32_t step, uint32_t k0, uint32_t k1,
+                                                         bf16_t* __restrict__ X16, int32_t* __restrict__ t) {
+  const int r = blockIdx.x, i = blockIdx.y;
+  const uint32_t x = philox4x32_10(step, (uint32_t)i, DOMAIN_BATCH, (uint32_t)r, k0, k1).x;
+  const float* __restrict__ row = train_x + (int64_t)philox_bounded(x, (uint32_t)n_train) * d;
+  bf16_t* __restrict__ o = X16 + (int64_t)i * member_stride + (int64_t)r * d;
+  for (int c = threadIdx.x; c < d; c += 64) o[c] = f2bf(row[c]);
+  if (threadIdx.x == 0 && r == 0) t[i] += 1;
+}
+hipError_t gather_rows(const float* train_x, int n_train, int d, int P, int B, int64_t member_stride, uint32_t step,
+                       uint64_t seed, bf16_t* X16, int32_t* t, hipStream_t s) {
+  hipLaunchKernelGGL(gather_rows_kernel, dim3(B, P), dim3(64), 0, s, train_x, n_train, d, member_stride, step,
+                     (uint32_t)seed, (uint32_t)(seed >> 32), X16, t);
+  return hipGetLastError();
+}
+
+// one wavefront per row: lanes stride over the row, butterfly sum
+__global__ __launch_bounds__(256) void row_sqnorm_kernel(const bf16_t* __restrict__ X, int64_t n_rows, int d,
+                                                         float* __restrict__ out) {
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= n_rows) return;
+  const bf16_t* __restrict__ p = X + r * d;
+  float acc = 0.f;
+  for (int c = threadIdx.x & 63; c < d; c += 64) {
+    const float v = bf2f(p[c]);
+    acc = fmaf(v, v, acc);
+  }
+  acc = wave_sum(acc);
+  if ((threadIdx.x & 63) == 0) out[r] = acc;
+}
+hipError_t row_sqnorm(const bf16_t* X, int batch, int rows, int d, float* out, hipStream_t s) {
+  const int64_t n_rows = (int64_t)batch * rows;
+  hipLaunchKernelGGL(row_sqnorm_kernel, dim3((unsigned)((n_rows + 3) / 4)), dim3(256), 0, s, X, n_rows, d, out);
+  return hipGetLastError();
+}
+
+// one wavefront per member; tiles added in a fixed order (lane-strided, then butterfly)
+__global__ __launch_bounds__(64) void mmd_combine_kernel(const float* __restrict__ pxx, int txx,
+                                                         const float* __restrict__ pyy, int tyy,
+                                                         const float* __restrict__ pxy, int txy, float inv_n2,
+                                                         float* __restrict__ score) {
+  const int i = blockIdx.x;
+  float sxx = 0.f, syy = 0.f, sxy = 0.f;
+  for (int k = threadIdx.x; k < txx; k += 64) sxx += pxx[(int64_t)i * txx + k];
+  for (int k = threadIdx.x; k < tyy; k += 64) syy += pyy[k];
+  for (int k = threadIdx.x; k < txy; k += 64) sxy += pxy[(int64_t)i * txy + k];
+  sxx = wave_sum(sxx);
+  syy = wave_sum(syy);
+  sxy = wave_sum(sxy);
+  if (threadIdx.x == 0) score[i] = -((sxx * inv_n2 + syy * inv_n2) - 2.f * (sxy * inv_n2));
+}
+hipError_t mmd_combine(const float* pxx, int txx, const float* pyy, int tyy, const float* pxy, int txy, int P, float inv_n2,
+                       float* score, hipStream_t s) {
+  hipLaunchKernelGGL(mmd_combine_kernel, dim3(P), dim3(64), 0, s, pxx, txx, pyy, tyy, pxy, txy, inv_n2, score);
   return hipGetLastError();
 }
 

@@ -14,6 +14,7 @@ enum {
   DOMAIN_EXPLORE = 3,
   DOMAIN_INIT_W = 4,
   DOMAIN_INIT_H = 5,
+  DOMAIN_LATENT = 6,
 };
 
 struct u32x4 { uint32_t x, y, z, w; };

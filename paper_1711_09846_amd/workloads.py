@@ -18,8 +18,8 @@ import numpy as np
 ACT_NONE, ACT_RELU, ACT_GELU, ACT_LEAKY_RELU, ACT_TANH = 0, 1, 2, 3, 4
 OPT_SGD_MOMENTUM, OPT_ADAM, OPT_RMSPROP = 0, 1, 2
 DTYPE_FP32, DTYPE_BF16 = 0, 1
-ROLE_LR, ROLE_BETA1, ROLE_WD = 0, 1, 2
-WL_CLASSIFIER = 1
+ROLE_LR, ROLE_BETA1, ROLE_WD, ROLE_LR_G, ROLE_LR_D = 0, 1, 2, 3, 4
+WL_CLASSIFIER, WL_GAN = 1, 3
 
 POPULATION_SEED = 2017          # Philox key of the population
 
@@ -57,7 +57,17 @@ MLP_WIDE = Workload(
     ready_interval=200, n_trunc=trunc_count(64, 20), total_steps=10000,
     opt_const=dict(beta2=0.999, eps=1e-8), data_seed=1002, perturb=(0.8, 1.2))
 
-WORKLOADS = {1: MLP_SMALL, 2: MLP_WIDE}
+# MLP GAN pairs: generator latent -> data (tanh), discriminator data -> logit (LeakyReLU 0.2); Adam with
+# beta1 0.5 (the paper's GAN appendix), separate generator / discriminator learning rates per member.
+GAN_MLP = Workload(
+    name="gan_mlp_bf16", kind=WL_GAN, P=32, dims=[128, 512, 512, 784], act=ACT_RELU, act_out=ACT_TANH,
+    dims2=[784, 512, 512, 1], act2=ACT_LEAKY_RELU, dtype=DTYPE_BF16, optimizer=OPT_ADAM, batch=64,
+    n_train=65536, n_eval=2048, roles=[ROLE_LR_G, ROLE_LR_D], priors=[("log", 1e-5, 1e-3), ("log", 1e-5, 1e-3)],
+    h_max=[math.inf, math.inf], ready_interval=500, n_trunc=trunc_count(32, 20), total_steps=20000,
+    opt_const=dict(beta1=0.5, beta2=0.999, eps=1e-8), data_seed=1003, perturb=(0.8, 1.2),
+    n_modes=16, rank=32)
+
+WORKLOADS = {1: MLP_SMALL, 2: MLP_WIDE, 3: GAN_MLP}
 
 
 def gaussian_mixture(n_classes, dim, n_train, n_eval, seed):
@@ -74,6 +84,32 @@ def gaussian_mixture(n_classes, dim, n_train, n_eval, seed):
 
 def classifier_data(wl):
     return gaussian_mixture(wl.n_classes, wl.dims[0], wl.n_train, wl.n_eval, wl.data_seed)
+
+
+def low_rank_mixture(n_modes, dim, rank, n_train, n_eval, seed):
+    """x = mu_k + A_k e with k uniform over the modes, e ~ N(0, I_rank), A_k ~ N(0, 1) * 0.25 / sqrt(rank),
+    mu_k ~ N(0, 0.25^2 I): a mixture of low-rank Gaussians that fits the range of a tanh output."""
+    rng = np.random.default_rng(seed)
+    mu = rng.standard_normal((n_modes, dim)) * 0.25
+    A = rng.standard_normal((n_modes, dim, rank)) * (0.25 / math.sqrt(rank))
+    out = []
+    for n in (n_train, n_eval):
+        k = rng.integers(0, n_modes, size=n)
+        e = rng.standard_normal((n, rank))
+        x = mu[k] + np.einsum("ndr,nr->nd", A[k], e)
+        out.append(x.astype(np.float32))
+    return out[0], out[1]
+
+
+def gan_data(wl):
+    return low_rank_mixture(wl.n_modes, wl.dims2[0], wl.rank, wl.n_train, wl.n_eval, wl.data_seed)
+
+
+def initial_gan_weights(wl, P, seed):
+    """Per member: (generator layers, discriminator layers)."""
+    g = initial_mlp_weights(wl.dims, P, seed)
+    d = initial_mlp_weights(wl.dims2, P, seed + 1000)
+    return [(g[i], d[i]) for i in range(P)]
 
 
 def initial_hypers(wl, seed):

@@ -116,3 +116,72 @@ class Pair:
         """max |gpu - ref| / max(|ref|, floor) over members (losses, scores)."""
         gpu, ref = np.asarray(gpu, dtype=np.float64), np.asarray(ref, dtype=np.float64)
         return float(np.max(np.abs(gpu - ref) / np.maximum(np.abs(ref), floor)))
+
+
+class GanPair:
+    """A GAN population on the GPU and its oracle twin (all members or a sample)."""
+
+    def __init__(self, wl, seed=workloads.POPULATION_SEED, init_seed=5, ref_members=None):
+        import torch
+        from oracle import gan as og
+        self.og, self.wl, self.seed = og, wl, seed
+        self.train_x, self.eval_x = workloads.gan_data(wl)
+        self.cfg = binding.make_config(wl, seed)
+        self.gpu = binding.Population(self.cfg)
+        weights = workloads.initial_gan_weights(wl, wl.P, init_seed)
+        H = workloads.initial_hypers(wl, init_seed + 1)
+        self.gpu.set_members([list(g) + list(d) for g, d in weights], H)
+        oc_ = {k: float(np.float32(v)) for k, v in wl.opt_const.items()}
+        self.spec = og.GanSpec(wl.dims, wl.dims2, wl.batch, seed, roles=wl.roles, g_hidden=wl.act, g_out=wl.act_out,
+                               d_hidden=wl.act2, beta1=oc_["beta1"], beta2=oc_["beta2"], eps=oc_["eps"],
+                               bf16_storage=wl.dtype == workloads.DTYPE_BF16)
+        self.ref_ids = list(range(wl.P)) if ref_members is None else list(ref_members)
+        self.ref = {i: og.new_member(self.spec, weights[i][0], weights[i][1], H[i], i) for i in self.ref_ids}
+        dev = self.gpu.device
+        self.d_train = [torch.from_numpy(self.train_x).to(dev)]
+        self.d_eval = [torch.from_numpy(self.eval_x).to(dev)]
+
+    def step_ref(self, s):
+        return np.array([self.og.step(self.spec, self.ref[i], i, s, self.train_x) for i in self.ref_ids])
+
+    def eval_ref(self):
+        return np.array([self.og.evaluate(self.spec, self.ref[i], i, self.eval_x) for i in self.ref_ids])
+
+    def ref_flat(self, i, what):
+        m = self.ref[i]
+        arrs = m.theta if what == "theta" else m.opt[what]
+        lay = self.gpu.layout
+        flat = np.zeros(lay.stride)
+        for l in range(len(arrs) // 2):
+            W, b = arrs[2 * l], arrs[2 * l + 1]
+            flat[lay.w_off[l]:lay.w_off[l] + W.size] = W.ravel()
+            flat[lay.b_off[l]:lay.b_off[l] + b.size] = b.ravel()
+        return flat
+
+    def sync_ref_from_gpu(self, i):
+        m = self.ref[i]
+        lay, shapes = self.gpu.layout, self.gpu.layer_shapes
+        for what, which in (("theta", binding.ARR_W32), ("s0", binding.ARR_OPT0), ("s1", binding.ARR_OPT1)):
+            flat = self.gpu.get(which, i).astype(np.float64)
+            arrs = m.theta if what == "theta" else m.opt[what]
+            for l, (fi, fo) in enumerate(shapes):
+                arrs[2 * l] = flat[lay.w_off[l]:lay.w_off[l] + fi * fo].reshape(fi, fo).copy()
+                arrs[2 * l + 1] = flat[lay.b_off[l]:lay.b_off[l] + fo].copy()
+        m.t = int(self.gpu.get(binding.ARR_T, i)[0])
+        m.h = self.gpu.get(binding.ARR_HYPER, i).copy()
+
+    def member_errors(self, i, which, what):
+        """(worst per-array, whole-vector) relative L2 distance of member i's array."""
+        g = self.gpu.get(which, i).astype(np.float64)
+        r = self.ref_flat(i, what)
+        lay = self.gpu.layout
+        worst = 0.0
+        for l, (fi, fo) in enumerate(self.gpu.layer_shapes):
+            for off, n in ((lay.w_off[l], fi * fo), (lay.b_off[l], fo)):
+                worst = max(worst, np.linalg.norm(g[off:off + n] - r[off:off + n]) / max(np.linalg.norm(r[off:off + n]), 1e-12))
+        return worst, np.linalg.norm(g - r) / max(np.linalg.norm(r), 1e-12)
+
+    def exploit_ref(self, rnd, scores):
+        wl = self.wl
+        pop = [self.ref[i] for i in range(wl.P)]
+        return opbt.exploit_explore(pop, rnd, self.seed, wl.n_trunc, wl.perturb[0], wl.perturb[1], wl.h_max, scores=scores)
