@@ -62,12 +62,13 @@ typedef enum {
   PBT_EUNSUPPORTED = -5  /* valid request that this build has no kernel for */
 } pbt_status;
 
-enum { PBT_WL_CLASSIFIER = 1, PBT_WL_GAN = 3 };       /* workload families */
+enum { PBT_WL_CLASSIFIER = 1, PBT_WL_GAN = 3, PBT_WL_A2C = 5 }; /* workload families */
 enum { PBT_ACT_NONE = 0, PBT_ACT_RELU = 1, PBT_ACT_GELU = 2, PBT_ACT_LEAKY_RELU = 3, PBT_ACT_TANH = 4 };
 enum { PBT_OPT_SGD_MOMENTUM = 0, PBT_OPT_ADAM = 1, PBT_OPT_RMSPROP = 2 };
 enum { PBT_DTYPE_FP32 = 0, PBT_DTYPE_BF16 = 1 };      /* BF16 = bf16 operands, fp32 accumulate, fp32 master weights */
 enum { PBT_ROLE_LR = 0, PBT_ROLE_BETA1 = 1, PBT_ROLE_WD = 2, /* meaning of a hyperparameter column */
-       PBT_ROLE_LR_G = 3, PBT_ROLE_LR_D = 4 };                /* GAN: generator / discriminator learning rate */
+       PBT_ROLE_LR_G = 3, PBT_ROLE_LR_D = 4,                  /* GAN: generator / discriminator learning rate */
+       PBT_ROLE_ENTROPY_COST = 5 };                           /* actor-critic: weight of the entropy bonus */
 
 /* Arrays of the population store that pbt_get_state / pbt_set_state address. */
 enum {
@@ -83,7 +84,9 @@ enum {
   PBT_ARR_ORDER = 9,  /* int32  [P]          members from best to worst, last exploit */
   PBT_ARR_DONOR = 10, /* int32  [P]          donor of the last exploit, -1 = kept     */
   PBT_ARR_PARENT = 11,/* int32  [P]          member last copied from (initially self) */
-  PBT_ARR_COUNT = 12
+  PBT_ARR_HIST = 12,  /* float  [P][12]      actor-critic: ring of the last 10 unroll returns, slot 10 = number of
+                                             unrolls so far (int32 bits), slot 11 unused; travels with theta */
+  PBT_ARR_COUNT = 13
 };
 
 typedef struct {
@@ -109,7 +112,11 @@ typedef struct {
   int32_t n_layers2;                /* discriminator layers; dims2[0] = dims[n_layers], dims2[n_layers2] = 1 */
   int32_t dims2[PBT_MAX_DIMS];
   int32_t act2;                     /* discriminator hidden activation */
-  int32_t n_train, n_eval;          /* rows of the training and of the held-out set */
+  /* PBT_WL_A2C only: dims describe torso + one head of dims[n_layers] = n_actions + 1 outputs
+     (policy logits, then the value); `batch` trajectories of `unroll` transitions per step. */
+  int32_t unroll;
+  float gamma, value_cost;          /* discount; weight of the squared value error (0.5) */
+  int32_t n_train, n_eval;          /* rows (classifier, GAN) or trajectories (actor-critic) of the training set; rows of the held-out set */
   int32_t eval_chunk;               /* rows of the held-out set scored per pass (bounds scratch); 0 = library picks */
   uint64_t seed;                    /* Philox key */
 } pbt_config;
@@ -166,7 +173,9 @@ pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs
  * d_inputs = {eval_x float[n_eval][dims[0]], eval_y int32[n_eval]}.
  * PBT_WL_GAN: minus the biased squared maximum mean discrepancy, RBF kernel exp(-|a-b|^2 / (2 d)),
  * d = dims2[0], between n_eval generated rows (latents: Philox domain 6 + 2, step index 0) and the
- * n_eval held-out rows; d_inputs = {eval_x float[n_eval][dims2[0]]}. */
+ * n_eval held-out rows; d_inputs = {eval_x float[n_eval][dims2[0]]}.
+ * PBT_WL_A2C (Section 4.1.1, Eval): the mean of the member's last (up to) 10 unroll returns, -inf
+ * before the first step; n_inputs = 0. */
 pbt_status pbt_eval(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, void* hip_stream);
 
 /* Section 4.1.1, Exploit (b) + Explore (a), for the whole population at once

@@ -16,10 +16,10 @@ LIB_PATH = os.path.join(_HERE, "libpbt.so")
 
 PBT_MAX_DIMS, PBT_MAX_HYPER = 16, 8
 (ARR_W32, ARR_OPT0, ARR_OPT1, ARR_W16, ARR_GRAD, ARR_HYPER, ARR_SCORE, ARR_LOSS, ARR_T, ARR_ORDER, ARR_DONOR,
- ARR_PARENT) = range(12)
+ ARR_PARENT, ARR_HIST) = range(13)
 _ARR_DTYPE = {ARR_W32: np.float32, ARR_OPT0: np.float32, ARR_OPT1: np.float32, ARR_W16: np.uint16,
               ARR_GRAD: np.float32, ARR_HYPER: np.float32, ARR_SCORE: np.float32, ARR_LOSS: np.float32,
-              ARR_T: np.int32, ARR_ORDER: np.int32, ARR_DONOR: np.int32, ARR_PARENT: np.int32}
+              ARR_T: np.int32, ARR_ORDER: np.int32, ARR_DONOR: np.int32, ARR_PARENT: np.int32, ARR_HIST: np.float32}
 
 EXPORTS = ["pbt_query_sizes", "pbt_init", "pbt_step", "pbt_eval", "pbt_exploit_explore", "pbt_get_state",
            "pbt_set_state", "pbt_state_ptr", "pbt_destroy", "pbt_last_error", "pbt_batched_gemm_bf16",
@@ -34,7 +34,8 @@ class PbtConfig(C.Structure):
                 ("compute_dtype", C.c_int32), ("n_hyper", C.c_int32), ("hyper_role", C.c_int32 * PBT_MAX_HYPER),
                 ("hyper_max", C.c_float * PBT_MAX_HYPER), ("n_trunc", C.c_int32), ("perturb_lo", C.c_float),
                 ("perturb_hi", C.c_float), ("opt_const", C.c_float * 4), ("act_out", C.c_int32),
-                ("n_layers2", C.c_int32), ("dims2", C.c_int32 * PBT_MAX_DIMS), ("act2", C.c_int32), ("n_train", C.c_int32),
+                ("n_layers2", C.c_int32), ("dims2", C.c_int32 * PBT_MAX_DIMS), ("act2", C.c_int32), ("unroll", C.c_int32),
+                ("gamma", C.c_float), ("value_cost", C.c_float), ("n_train", C.c_int32),
                 ("n_eval", C.c_int32), ("eval_chunk", C.c_int32), ("seed", C.c_uint64)]
 
 
@@ -115,6 +116,8 @@ def make_config(wl, seed, P=None, n_trunc=None, eval_chunk=0):
         c.act_out, c.act2, c.n_layers2 = wl.act_out, wl.act2, len(wl.dims2) - 1
         for k, d in enumerate(wl.dims2):
             c.dims2[k] = d
+    if getattr(wl, "unroll", None):                     # actor-critic
+        c.unroll, c.gamma, c.value_cost = wl.unroll, wl.gamma, wl.value_cost
     c.n_train, c.n_eval, c.eval_chunk = wl.n_train, wl.n_eval, eval_chunk
     c.seed = seed
     return c
@@ -188,8 +191,19 @@ class Population:
     def step(self, inputs, step_index, n_steps=1):
         self._check(lib().pbt_step(self._h, self._ptrs(inputs), len(inputs), step_index, n_steps, self._stream()))
 
-    def eval(self, inputs):
-        self._check(lib().pbt_eval(self._h, self._ptrs(inputs), len(inputs), self._stream()))
+    def eval(self, inputs=()):
+        ptrs = self._ptrs(inputs) if len(inputs) else None
+        self._check(lib().pbt_eval(self._h, ptrs, len(inputs), self._stream()))
+
+    def history(self):
+        """Actor-critic: per member the unroll returns still in the ring, oldest first."""
+        raw = self.get(ARR_HIST)
+        out = []
+        for row in raw:
+            n = int(row[10:11].view(np.int32)[0])
+            m = min(n, 10)
+            out.append([row[(n - m + k) % 10] for k in range(m)])
+        return out
 
     def exploit_explore(self, round_index, scores_override=None):
         p = None if scores_override is None else C.c_void_p(scores_override.data_ptr())
@@ -214,6 +228,8 @@ class Population:
             return (P, self.layout.stride)
         if which == ARR_HYPER:
             return (P, self.cfg.n_hyper)
+        if which == ARR_HIST:
+            return (P, 12)
         if which == ARR_LOSS and self.n_loss > 1:
             return (P, self.n_loss)
         return (P,)

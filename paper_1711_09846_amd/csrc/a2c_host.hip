@@ -1,0 +1,194 @@
+// The actor-critic workload (Section 4.1.1 of the PBT paper: A3C-style agents trained with RMSProp,
+// learning rate and entropy cost adapted per member, evaluated by the last 10 episodic returns).
+// Device kernels for the trajectory bookkeeping and the loss, and the host-side kernel sequence.
+#include <cstring>
+
+#include "common.h"
+#include "dense_host.h"
+#include "philox.h"
+
+namespace pbt {
+
+constexpr int HIST_SLOTS = 10, HIST_PITCH = 12;  // ring of returns, slot 10 = count (int bits), slot 11 unused
+
+// Per member: copies actions and rewards of the B drawn trajectories (the same Philox draws as the
+// observation gather) and pushes the unroll's return (mean over trajectories of the summed
+// rewards, accumulated in double in a fixed order) into the member's history ring.
+__global__ __launch_bounds__(64) void a2c_fetch_aux_kernel(const int32_t* __restrict__ pool_act,
+                                                           const float* __restrict__ pool_rew, int n_traj, int B, int T,
+                                                           uint32_t step, uint32_t k0, uint32_t k1,
+                                                           int32_t* __restrict__ act, float* __restrict__ rew,
+                                                           float* __restrict__ hist) {
+  const int i = blockIdx.x;
+  __shared__ double tsum[64];
+  double mean = 0.0;
+  for (int r0 = 0; r0 < B; r0 += 64) {
+    const int r = r0 + threadIdx.x;
+    double sacc = 0.0;
+    if (r < B) {
+      const uint32_t x = philox4x32_10(step, (uint32_t)i, DOMAIN_BATCH, (uint32_t)r, k0, k1).x;
+      const int64_t src = (int64_t)philox_bounded(x, (uint32_t)n_traj) * T;
+      const int64_t dst = ((int64_t)i * B + r) * T;
+      for (int t = 0; t < T; ++t) {
+        act[dst + t] = pool_act[src + t];
+        const float rv = pool_rew[src + t];
+        rew[dst + t] = rv;
+        sacc += (double)rv;
+      }
+    }
+    tsum[threadIdx.x] = sacc;
+    __syncthreads();
+    if (threadIdx.x == 0)
+      for (int k = 0; k < 64 && r0 + k < B; ++k) mean += tsum[k];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    float* hrow = hist + (int64_t)i * HIST_PITCH;
+    const int n = __float_as_int(hrow[HIST_SLOTS]);
+    hrow[n % HIST_SLOTS] = (float)(mean / (double)B);
+    hrow[HIST_SLOTS] = __int_as_float(n + 1);
+  }
+}
+
+// Loss and its gradient with respect to the head outputs.  One thread per trajectory walks it
+// backwards: R_T = V(s_T), R_t = r_t + gamma R_{t+1}; A_t = R_t - V_t (both constants);
+//   loss_t = -A_t log pi(a_t) + value_cost (R_t - V_t)^2 - entropy_cost H_t
+//   dlogit_c = ( -A_t (1[c = a_t] - pi_c) + entropy_cost pi_c (log pi_c + H_t) ) / n
+//   dV_t = 2 value_cost (V_t - R_t) / n,   n = B T;  the bootstrap row gets zeros.
+// out: head outputs float [P][B][T+1][32] (n_act logits, then the value).
+__global__ __launch_bounds__(64) void a2c_loss_kernel(const float* __restrict__ out, const int32_t* __restrict__ act,
+                                                      const float* __restrict__ rew, const float* __restrict__ H,
+                                                      int n_hyper, int col_ent, int B, int T, int n_act, float gamma,
+                                                      float value_cost, bf16_t* __restrict__ dout, float* __restrict__ loss) {
+  const int i = blockIdx.x;
+  const float ent_cost = H[i * n_hyper + col_ent];
+  const float inv_n = 1.f / (float)(B * T);
+  float lacc = 0.f;
+  for (int r = threadIdx.x; r < B; r += 64) {
+    const float* __restrict__ o = out + ((int64_t)i * B + r) * (T + 1) * 32;
+    bf16_t* __restrict__ d = dout + ((int64_t)i * B + r) * (T + 1) * 32;
+    float R = o[T * 32 + n_act];
+    for (int c = 0; c < 32; ++c) d[T * 32 + c] = 0;
+    for (int t = T - 1; t >= 0; --t) {
+      const float* lg = o + t * 32;
+      const float v = lg[n_act];
+      R = rew[((int64_t)i * B + r) * T + t] + gamma * R;
+      const float adv = R - v;
+      float mx = lg[0];
+      for (int c = 1; c < n_act; ++c) mx = fmaxf(mx, lg[c]);
+      float se = 0.f;
+      for (int c = 0; c < n_act; ++c) se += expf(lg[c] - mx);
+      const float lse = mx + logf(se);
+      float ent = 0.f;
+      for (int c = 0; c < n_act; ++c) {
+        const float lp = lg[c] - lse;
+        ent -= expf(lp) * lp;
+      }
+      const int a = act[((int64_t)i * B + r) * T + t];
+      lacc += -adv * (lg[a] - lse) + value_cost * adv * adv - ent_cost * ent;
+      for (int c = 0; c < n_act; ++c) {
+        const float lp = lg[c] - lse, pi = expf(lp);
+        d[t * 32 + c] = f2bf((-adv * ((c == a ? 1.f : 0.f) - pi) + ent_cost * pi * (lp + ent)) * inv_n);
+      }
+      d[t * 32 + n_act] = f2bf(2.f * value_cost * (v - R) * inv_n);
+      for (int c = n_act + 1; c < 32; ++c) d[t * 32 + c] = 0;
+    }
+  }
+  lacc = wave_sum(lacc);
+  if (threadIdx.x == 0) loss[i] = lacc * inv_n;
+}
+
+// score = mean of the last min(count, 10) returns (double accumulation), -inf when there are none
+__global__ void a2c_score_kernel(const float* __restrict__ hist, int P, float* __restrict__ score) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= P) return;
+  const float* hrow = hist + (int64_t)i * HIST_PITCH;
+  const int n = __float_as_int(hrow[HIST_SLOTS]);
+  const int m = n < HIST_SLOTS ? n : HIST_SLOTS;
+  if (m == 0) { score[i] = -INFINITY; return; }
+  // oldest first, as a list that keeps the most recent entries would hold them
+  double acc = 0.0;
+  for (int k = 0; k < m; ++k) acc += (double)hrow[(n - m + k) % HIST_SLOTS];
+  score[i] = (float)(acc / (double)m);
+}
+
+pbt_status a2c_check_and_plan(const pbt_config* c, Plan* pl, Carver* w) {
+  A2CPlan& a = pl->a2c;
+  const int L = c->n_layers;
+  if (L < 2) return fail(nullptr, PBT_EUNSUPPORTED, "the actor-critic network needs at least one torso layer before its head");
+  if (c->unroll < 1) return fail(nullptr, PBT_EINVAL, "unroll must be positive");
+  if (c->dims[L] < 2 || c->dims[L] > 32) return fail(nullptr, PBT_EUNSUPPORTED, "head width (actions + value) must be 2..32");
+  for (int l = 0; l < L; ++l)
+    if (c->dims[l] % 8) return fail(nullptr, PBT_EUNSUPPORTED, "torso widths must be multiples of 8");
+  if (!(c->gamma >= 0.f && c->gamma <= 1.f)) return fail(nullptr, PBT_EINVAL, "gamma outside [0, 1]");
+  const int64_t P = c->P, R = (int64_t)c->batch * (c->unroll + 1);
+  a.rows = (int)R;
+  for (int l = 0; l < L; ++l) {
+    a.o_a[l] = w->take((size_t)P * R * c->dims[l] * 2);
+    if (l < L - 1) {
+      a.o_z[l] = w->take((size_t)P * R * c->dims[l + 1] * 2);
+      a.o_dz[l] = w->take((size_t)P * R * c->dims[l + 1] * 2);
+    }
+  }
+  a.o_out = w->take((size_t)P * R * 32 * 4);
+  a.o_dout = w->take((size_t)P * R * 32 * 2);
+  a.o_act = w->take((size_t)P * c->batch * c->unroll * 4);
+  a.o_rew = w->take((size_t)P * c->batch * c->unroll * 4);
+  return PBT_OK;
+}
+
+pbt_status a2c_step(pbt_handle* h, const float* obs, const int32_t* actions, const float* rewards, uint32_t step, hipStream_t s) {
+  const pbt_config& c = h->cfg;
+  const Plan& p = h->plan;
+  const A2CPlan& a = p.a2c;
+  const int P = c.P, B = c.batch, T = c.unroll, L = c.n_layers, R = a.rows;
+  const int Kh = c.dims[L - 1], C = c.dims[L];
+  const int64_t S = p.lay.stride;
+  const Net net{L, c.dims, 0, c.act, PBT_ACT_NONE};
+  bf16_t* A[PBT_MAX_DIMS]; bf16_t* Z[PBT_MAX_DIMS]; bf16_t* dZ[PBT_MAX_DIMS];
+  for (int l = 0; l < L; ++l) { A[l] = h->sc<bf16_t>(a.o_a[l]); Z[l] = l < L - 1 ? h->sc<bf16_t>(a.o_z[l]) : nullptr; dZ[l] = l < L - 1 ? h->sc<bf16_t>(a.o_dz[l]) : nullptr; }
+  const float* W32 = h->st<float>(p.o_w32);
+  const bf16_t* W16 = h->st<bf16_t>(p.o_w16);
+  float* G = h->sc<float>(p.o_grad);
+  float* out = h->sc<float>(a.o_out);
+  bf16_t* dout = h->sc<bf16_t>(a.o_dout);
+  int32_t* act = h->sc<int32_t>(a.o_act);
+  float* rew = h->sc<float>(a.o_rew);
+  pbt_status st;
+  // a trajectory is one "row" of (T+1) * d observations; B of them are drawn per member
+  PBT_LAUNCH(h, PBT_K_FETCH, s, gather_rows(obs, c.n_train, (T + 1) * c.dims[0], P, B, (int64_t)R * c.dims[0], step, c.seed, A[0],
+                                            h->st<int32_t>(p.o_t), s));
+  {
+    const bool timed = false; (void)timed;
+    hipLaunchKernelGGL(a2c_fetch_aux_kernel, dim3(P), dim3(64), 0, s, actions, rewards, c.n_train, B, T, step, (uint32_t)c.seed,
+                       (uint32_t)(c.seed >> 32), act, rew, h->st<float>(p.o_hist));
+    PBT_HIP(h, hipGetLastError());
+  }
+  if ((st = forward(h, net, L - 1, R, A, Z, nullptr, 0, s)) != PBT_OK) return st;
+  PBT_LAUNCH(h, PBT_K_HEAD, s, head_fwd_loss(A[L - 1], (int64_t)R * Kh, W16 + p.lay.w_off[L - 1], S, W32 + p.lay.b_off[L - 1], S, nullptr,
+                                             0, P, R, Kh, C, 0.f, -2, nullptr, out, 0, s));
+  hipLaunchKernelGGL(a2c_loss_kernel, dim3(P), dim3(64), 0, s, out, act, rew, h->st<float>(p.o_hyper), c.n_hyper, a.col_ent, B, T,
+                     C - 1, c.gamma, c.value_cost, dout, h->st<float>(p.o_loss));
+  PBT_HIP(h, hipGetLastError());
+  {
+    GemmOperands wg{A[L - 1], Kh, (int64_t)R * Kh, true, dout, 32, (int64_t)R * 32, false, Kh, C, R, P};
+    PBT_LAUNCH(h, PBT_K_HEAD, s, gemm_store_f32(wg, G + p.lay.w_off[L - 1], C, S, s));
+    PBT_LAUNCH(h, PBT_K_HEAD, s, bias_grad(dout, P, R, C, 32, G + p.lay.b_off[L - 1], S, s));
+  }
+  PBT_LAUNCH(h, PBT_K_HEAD, s, head_dgrad(dout, W16 + p.lay.w_off[L - 1], S, Z[L - 2], dZ[L - 2], P, R, Kh, C, c.act, s));
+  if ((st = backward(h, net, L - 1, R, A, Z, dZ, true, nullptr, nullptr, 0, s)) != PBT_OK) return st;
+  OptArgs oa{h->st<float>(p.o_w32), h->st<float>(p.o_opt0), nullptr, h->st<bf16_t>(p.o_w16), G, 0, S, h->st<float>(p.o_hyper),
+             h->st<int32_t>(p.o_t), S, P, c.n_hyper, c.optimizer, p.col_lr, -1, -1, c.opt_const[0], c.opt_const[1], c.opt_const[2],
+             c.opt_const[3]};
+  PBT_LAUNCH(h, PBT_K_OPTIMIZER, s, optimizer_step(oa, s));
+  return PBT_OK;
+}
+
+pbt_status a2c_eval(pbt_handle* h, hipStream_t s) {
+  const int P = h->cfg.P;
+  hipLaunchKernelGGL(a2c_score_kernel, dim3((P + 63) / 64), dim3(64), 0, s, h->st<float>(h->plan.o_hist), P, h->st<float>(h->plan.o_score));
+  PBT_HIP(h, hipGetLastError());
+  return PBT_OK;
+}
+
+}  // namespace pbt

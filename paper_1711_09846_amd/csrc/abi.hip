@@ -33,9 +33,10 @@ namespace {
 
 pbt_status check_config(const pbt_config* c, Plan* pl) {
   if (!c) return fail(nullptr, PBT_EINVAL, "config is NULL");
-  if (c->workload != PBT_WL_CLASSIFIER && c->workload != PBT_WL_GAN)
+  if (c->workload != PBT_WL_CLASSIFIER && c->workload != PBT_WL_GAN && c->workload != PBT_WL_A2C)
     return fail(nullptr, PBT_EUNSUPPORTED, "workload %d not built", c->workload);
   const bool gan = c->workload == PBT_WL_GAN;
+  const bool a2c = c->workload == PBT_WL_A2C;
   if (c->P < 1 || c->P > PBT_MAX_P) return fail(nullptr, PBT_EINVAL, "P = %d outside 1..%d", c->P, PBT_MAX_P);
   if (c->batch < 1) return fail(nullptr, PBT_EINVAL, "batch must be positive");
   if (c->n_layers < 1 || c->n_layers >= PBT_MAX_DIMS) return fail(nullptr, PBT_EINVAL, "n_layers = %d outside 1..%d", c->n_layers, PBT_MAX_DIMS - 1);
@@ -47,7 +48,8 @@ pbt_status check_config(const pbt_config* c, Plan* pl) {
   if (c->n_hyper < 1 || c->n_hyper > PBT_MAX_HYPER) return fail(nullptr, PBT_EINVAL, "n_hyper = %d outside 1..%d", c->n_hyper, PBT_MAX_HYPER);
   if (c->n_trunc < 0 || 2 * (int64_t)c->n_trunc > c->P) return fail(nullptr, PBT_EINVAL, "need 0 <= 2*n_trunc <= P (top and bottom sets must not overlap)");
   if (c->n_train < 1 || c->n_eval < 1) return fail(nullptr, PBT_EINVAL, "n_train and n_eval must be positive");
-  if (!gan && c->dims[c->n_layers] > 32) return fail(nullptr, PBT_EUNSUPPORTED, "more than 32 classes");
+  if (!gan && c->dims[c->n_layers] > 32) return fail(nullptr, PBT_EUNSUPPORTED, "more than 32 outputs in the last layer");
+  pl->a2c.col_ent = -1;
   pl->col_lr = pl->col_beta1 = pl->col_wd = -1;
   pl->gan.col_lr_g = pl->gan.col_lr_d = -1;
   for (int k = 0; k < c->n_hyper; ++k) {
@@ -56,6 +58,7 @@ pbt_status check_config(const pbt_config* c, Plan* pl) {
     else if (c->hyper_role[k] == PBT_ROLE_WD) pl->col_wd = k;
     else if (c->hyper_role[k] == PBT_ROLE_LR_G) pl->gan.col_lr_g = k;
     else if (c->hyper_role[k] == PBT_ROLE_LR_D) pl->gan.col_lr_d = k;
+    else if (c->hyper_role[k] == PBT_ROLE_ENTROPY_COST) pl->a2c.col_ent = k;
     else return fail(nullptr, PBT_EINVAL, "unknown hyper_role[%d] = %d", k, c->hyper_role[k]);
     if (std::isnan(c->hyper_max[k])) return fail(nullptr, PBT_EINVAL, "hyper_max[%d] is NaN", k);
   }
@@ -65,6 +68,7 @@ pbt_status check_config(const pbt_config* c, Plan* pl) {
   }
   if (pl->gan.col_lr_g >= 0 || pl->gan.col_lr_d >= 0) return fail(nullptr, PBT_EINVAL, "generator / discriminator learning-rate columns need the GAN workload");
   if (pl->col_lr < 0) return fail(nullptr, PBT_EINVAL, "no hyperparameter column has the learning-rate role");
+  if (a2c != (pl->a2c.col_ent >= 0)) return fail(nullptr, PBT_EINVAL, "an entropy-cost column goes with the actor-critic workload, and only with it");
   if (c->optimizer != PBT_OPT_ADAM && (pl->col_beta1 >= 0 || pl->col_wd >= 0))
     return fail(nullptr, PBT_EINVAL, "beta1 / weight-decay columns need the Adam optimizer");
   return PBT_OK;
@@ -115,6 +119,7 @@ pbt_status make_plan(const pbt_config* c, Plan* pl) {
   pl->o_donor = s.take(P * 4);
   pl->o_parent = s.take(P * 4);
   pl->o_recip = s.take(P * 4);
+  pl->o_hist = c->workload == PBT_WL_A2C ? s.take(P * 12 * 4) : 0;
   pl->state_bytes = s.off;
 
   Carver w;
@@ -127,6 +132,10 @@ pbt_status make_plan(const pbt_config* c, Plan* pl) {
     pl->gan.d_count = lay.stride - pl->gan.g_count;
     pbt_status gst = gan_check_and_plan(c, pl, &w);
     if (gst != PBT_OK) return gst;
+  } else if (c->workload == PBT_WL_A2C) {
+    if (!bf16) return fail(nullptr, PBT_EUNSUPPORTED, "the actor-critic workload is built for bf16 compute");
+    pbt_status ast = a2c_check_and_plan(c, pl, &w);
+    if (ast != PBT_OK) return ast;
   } else if (!bf16) {
     FusedSmallArgs fa;
     std::memset(&fa, 0, sizeof fa);
@@ -199,6 +208,9 @@ pbt_status arr_info(pbt_handle* h, int which, ArrInfo* ai) {
     case PBT_ARR_ORDER: *ai = {p.o_order, 4, 1, false}; return PBT_OK;
     case PBT_ARR_DONOR: *ai = {p.o_donor, 4, 1, false}; return PBT_OK;
     case PBT_ARR_PARENT: *ai = {p.o_parent, 4, 1, false}; return PBT_OK;
+    case PBT_ARR_HIST:
+      if (c.workload != PBT_WL_A2C) return fail(h, PBT_EINVAL, "HIST exists only in the actor-critic workload");
+      *ai = {p.o_hist, 4, 12, false}; return PBT_OK;
     default: return fail(h, PBT_EINVAL, "unknown array id %d", which);
   }
 }
@@ -405,6 +417,17 @@ pbt_status pbt_init_population(pbt_handle* h, const pbt_prior* priors, void* hip
 pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, int64_t step_index, int32_t n_steps,
                     void* hip_stream) {
   if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  if (h->cfg.workload == PBT_WL_A2C) {
+    if (!d_inputs || n_inputs != 3 || !d_inputs[0] || !d_inputs[1] || !d_inputs[2])
+      return fail(h, PBT_EINVAL, "actor-critic step needs 3 inputs: observations, actions, rewards");
+    if (n_steps < 0 || step_index < 0 || step_index + n_steps > 0xffffffffLL) return fail(h, PBT_EINVAL, "step range outside 0..2^32-1");
+    for (int k = 0; k < n_steps; ++k) {
+      pbt_status st = a2c_step(h, static_cast<const float*>(d_inputs[0]), static_cast<const int32_t*>(d_inputs[1]),
+                               static_cast<const float*>(d_inputs[2]), (uint32_t)(step_index + k), static_cast<hipStream_t>(hip_stream));
+      if (st != PBT_OK) return st;
+    }
+    return PBT_OK;
+  }
   if (h->cfg.workload == PBT_WL_GAN) {
     if (!d_inputs || n_inputs != 1 || !d_inputs[0]) return fail(h, PBT_EINVAL, "GAN step needs 1 input: train_x");
     if (n_steps < 0 || step_index < 0 || step_index + n_steps > 0xffffffffLL) return fail(h, PBT_EINVAL, "step range outside 0..2^32-1");
@@ -439,6 +462,7 @@ pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs
 
 pbt_status pbt_eval(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, void* hip_stream) {
   if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  if (h->cfg.workload == PBT_WL_A2C) return a2c_eval(h, static_cast<hipStream_t>(hip_stream));
   if (h->cfg.workload == PBT_WL_GAN) {
     if (!d_inputs || n_inputs != 1 || !d_inputs[0]) return fail(h, PBT_EINVAL, "GAN eval needs 1 input: eval_x");
     return gan_eval(h, static_cast<const float*>(d_inputs[0]), static_cast<hipStream_t>(hip_stream));
@@ -486,6 +510,7 @@ pbt_status pbt_exploit_explore(pbt_handle* h, int64_t round_index, const float* 
   ca.base[ca.n] = h->st<char>(p.o_opt0); ca.row_bytes[ca.n++] = S * 4;
   if (c.optimizer == PBT_OPT_ADAM) { ca.base[ca.n] = h->st<char>(p.o_opt1); ca.row_bytes[ca.n++] = S * 4; }
   if (c.compute_dtype == PBT_DTYPE_BF16) { ca.base[ca.n] = h->st<char>(p.o_w16); ca.row_bytes[ca.n++] = S * 2; }
+  if (c.workload == PBT_WL_A2C) { ca.base[ca.n] = h->st<char>(p.o_hist); ca.row_bytes[ca.n++] = 12 * 4; }
   PBT_LAUNCH(h, PBT_K_COPY, s, gather_copy(ca, a.recip, a.donor, c.n_trunc, s));
   return PBT_OK;
 }

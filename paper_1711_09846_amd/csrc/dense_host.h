@@ -1,0 +1,67 @@
+// Host-side helpers shared by the workload files: forward and backward passes of a stack of dense
+// layers as sequences of population-batched GEMM launches.
+#pragma once
+#include "handle.h"
+
+namespace pbt {
+
+struct Net {  // a view of one of the two MLPs inside the member's flat parameter vector
+  int L;
+  const int32_t* dims;
+  int first;  // index of its first layer in the layout
+  int hidden_act, out_act;
+};
+
+
+// Dense layers 0 .. n_dense-1 of `net` on `rows` rows per member: in[l+1] = act(in[l] W_l + b_l).
+// A[l] (inputs), Z[l] (pre-activations, may be null when no backward pass follows) are bf16
+// [P][rows][width]; the output of the last dense layer goes to `last_out` with batch stride
+// `last_stride` (so that it can land inside another network's input buffer).
+inline pbt_status forward(pbt_handle* h, const Net& net, int n_dense, int rows, bf16_t* const* A, bf16_t* const* Z, bf16_t* last_out,
+                   int64_t last_stride, hipStream_t s) {
+  const pbt_config& c = h->cfg;
+  const Plan& p = h->plan;
+  const int64_t S = p.lay.stride;
+  const float* W32 = h->st<float>(p.o_w32);
+  const bf16_t* W16 = h->st<bf16_t>(p.o_w16);
+  for (int l = 0; l < n_dense; ++l) {
+    const int K = net.dims[l], N = net.dims[l + 1];
+    const bool last = l == n_dense - 1;
+    const int act = (l == net.L - 1) ? net.out_act : net.hidden_act;
+    GemmOperands o{A[l], K, (int64_t)rows * K, false, W16 + p.lay.w_off[net.first + l], N, S, false, rows, N, K, c.P};
+    bf16_t* out = last && last_out ? last_out : A[l + 1];
+    const int64_t so = last && last_out ? last_stride : (int64_t)rows * N;
+    PBT_LAUNCH(h, PBT_K_GEMM_FWD, s, gemm_bias_act(o, W32 + p.lay.b_off[net.first + l], S, Z ? Z[l] : nullptr, out, N, so, act, s));
+  }
+  return PBT_OK;
+}
+
+// Backward through dense layers n_dense-1 .. 0 given dZ[n_dense-1]: weight / bias gradients into G
+// (when want_wgrad) and dZ[l-1] = (dZ[l] W_l^T) * act'(Z[l-1]).  For l = 0 the input gradient is
+// produced only when in_z != null: dIn = (dZ[0] W_0^T) * act'(in_z) with activation in_act.
+inline pbt_status backward(pbt_handle* h, const Net& net, int n_dense, int rows, bf16_t* const* A, bf16_t* const* Z, bf16_t* const* dZ,
+                    bool want_wgrad, const bf16_t* in_z, bf16_t* in_dz, int in_act, hipStream_t s) {
+  const pbt_config& c = h->cfg;
+  const Plan& p = h->plan;
+  const int64_t S = p.lay.stride;
+  const bf16_t* W16 = h->st<bf16_t>(p.o_w16);
+  float* G = h->sc<float>(p.o_grad);
+  for (int l = n_dense - 1; l >= 0; --l) {
+    const int K = net.dims[l], N = net.dims[l + 1];
+    if (want_wgrad) {
+      GemmOperands wg{A[l], K, (int64_t)rows * K, true, dZ[l], N, (int64_t)rows * N, false, K, N, rows, c.P};
+      PBT_LAUNCH(h, PBT_K_GEMM_WGRAD, s, gemm_store_f32(wg, G + p.lay.w_off[net.first + l], N, S, s));
+      PBT_LAUNCH(h, PBT_K_BIAS_GRAD, s, bias_grad(dZ[l], c.P, rows, N, N, G + p.lay.b_off[net.first + l], S, s));
+    }
+    const bf16_t* zprev = l > 0 ? Z[l - 1] : in_z;
+    bf16_t* dzprev = l > 0 ? dZ[l - 1] : in_dz;
+    if (zprev) {
+      GemmOperands dg{dZ[l], N, (int64_t)rows * N, false, W16 + p.lay.w_off[net.first + l], N, S, true, rows, K, N, c.P};
+      PBT_LAUNCH(h, PBT_K_GEMM_DGRAD, s, gemm_dgrad_act(dg, zprev, dzprev, K, (int64_t)rows * K, l > 0 ? net.hidden_act : in_act, s));
+    }
+  }
+  return PBT_OK;
+}
+
+
+}  // namespace pbt

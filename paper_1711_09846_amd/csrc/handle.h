@@ -39,11 +39,16 @@ struct GanPlan {
   size_t o_ez, o_ea[2], o_ex, o_ey, o_nx, o_ny, o_pxx, o_pyy, o_pxy;
 };
 
+struct A2CPlan {
+  int rows, col_ent;
+  size_t o_a[PBT_MAX_DIMS], o_z[PBT_MAX_DIMS], o_dz[PBT_MAX_DIMS], o_out, o_dout, o_act, o_rew;
+};
+
 struct Plan {
   pbt_layout lay;
   int n_loss;
   // offsets in bytes inside d_state
-  size_t o_w32, o_opt0, o_opt1, o_w16, o_hyper, o_score, o_loss, o_t, o_order, o_donor, o_parent, o_recip;
+  size_t o_w32, o_opt0, o_opt1, o_w16, o_hyper, o_score, o_loss, o_t, o_order, o_donor, o_parent, o_recip, o_hist;
   size_t state_bytes;
   // offsets in bytes inside d_scratch
   size_t o_grad, o_y, o_dlogits, o_rowloss, o_x32;
@@ -54,6 +59,7 @@ struct Plan {
   bool fused_small;  // fp32: the whole step runs in one LDS-resident kernel
   int col_lr, col_beta1, col_wd;
   GanPlan gan;
+  A2CPlan a2c;
 };
 
 }  // namespace pbt
@@ -100,5 +106,10 @@ pbt_status fail(pbt_handle* h, pbt_status code, const char* fmt, ...);
 pbt_status gan_check_and_plan(const pbt_config* c, Plan* pl, Carver* scratch);
 pbt_status gan_step(pbt_handle* h, const float* train_x, uint32_t step, hipStream_t s);
 pbt_status gan_eval(pbt_handle* h, const float* eval_x, hipStream_t s);
+
+// a2c_host.hip: the actor-critic workload (Section 4.1.1)
+pbt_status a2c_check_and_plan(const pbt_config* c, Plan* pl, Carver* scratch);
+pbt_status a2c_step(pbt_handle* h, const float* obs, const int32_t* actions, const float* rewards, uint32_t step, hipStream_t s);
+pbt_status a2c_eval(pbt_handle* h, hipStream_t s);
 
 }  // namespace pbt

@@ -77,7 +77,11 @@ __global__ __launch_bounds__(256) void head_fwd_loss_kernel(const bf16_t* __rest
     if (r < rows) {
       const float* __restrict__ b = bias + (int64_t)i * sbias;
       float* lg = Lg + threadIdx.x * 33;
-      if (n_pos >= 0) {
+      if (n_pos == -2) {
+        // no loss here: hand the head outputs (bias added, zero padded to 32) to the caller's loss kernel
+        float* __restrict__ o = rowloss + ((int64_t)i * rows + r) * HEAD_NP;
+        for (int c = 0; c < HEAD_NP; ++c) o[c] = c < C ? lg[c] + b[c] : 0.f;
+      } else if (n_pos >= 0) {
         // logistic loss on one logit: target 1 for rows < n_pos, else 0.
         // loss = softplus(-l) or softplus(l) = max(x, 0) + log1p(exp(-|x|)); dl = sigmoid(l) - target
         const float l = lg[0] + b[0];

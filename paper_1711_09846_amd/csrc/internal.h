@@ -46,7 +46,8 @@ hipError_t gather_batch(const float* train_x, const int32_t* train_y, int n_trai
 // dlogits != null, dlogits[P][rows][32] (bf16, zero padded) = (softmax - onehot) * gscale.
 // labels are [rows] shared (sy = 0) or per member (sy = rows).
 // n_pos < 0: softmax cross-entropy against `labels`.  n_pos >= 0 (needs C = 1): logistic loss, rows
-// r < n_pos have target 1, the others target 0 (labels unused).
+// r < n_pos have target 1, the others target 0 (labels unused).  n_pos = -2: no loss; rowloss then
+// receives the head outputs as float [P][rows][32] (bias added, zero padded).
 hipError_t head_fwd_loss(const bf16_t* A, int64_t sa, const bf16_t* W16, int64_t sw, const float* bias, int64_t sbias,
                          const int32_t* labels, int64_t sy, int P, int rows, int K, int C, float gscale, int n_pos,
                          bf16_t* dlogits, float* rowloss, int64_t srowloss, hipStream_t s);
@@ -104,7 +105,7 @@ struct ExploitArgs {
 };
 hipError_t rank_select_explore(const ExploitArgs& a, hipStream_t s);
 struct CopyArrays {
-  void* base[4]; int64_t row_bytes[4]; int n;
+  void* base[6]; int64_t row_bytes[6]; int n;
 };
 hipError_t gather_copy(const CopyArrays& arrs, const int32_t* recip, const int32_t* donor, int n_trunc, hipStream_t s);
 

@@ -18,8 +18,8 @@ import numpy as np
 ACT_NONE, ACT_RELU, ACT_GELU, ACT_LEAKY_RELU, ACT_TANH = 0, 1, 2, 3, 4
 OPT_SGD_MOMENTUM, OPT_ADAM, OPT_RMSPROP = 0, 1, 2
 DTYPE_FP32, DTYPE_BF16 = 0, 1
-ROLE_LR, ROLE_BETA1, ROLE_WD, ROLE_LR_G, ROLE_LR_D = 0, 1, 2, 3, 4
-WL_CLASSIFIER, WL_GAN = 1, 3
+ROLE_LR, ROLE_BETA1, ROLE_WD, ROLE_LR_G, ROLE_LR_D, ROLE_ENTROPY_COST = 0, 1, 2, 3, 4, 5
+WL_CLASSIFIER, WL_GAN, WL_A2C = 1, 3, 5
 
 POPULATION_SEED = 2017          # Philox key of the population
 
@@ -67,7 +67,17 @@ GAN_MLP = Workload(
     opt_const=dict(beta1=0.5, beta2=0.999, eps=1e-8), data_seed=1003, perturb=(0.8, 1.2),
     n_modes=16, rank=32)
 
-WORKLOADS = {1: MLP_SMALL, 2: MLP_WIDE, 3: GAN_MLP}
+# Actor-critic MLP agents on pre-recorded synthetic trajectories: torso 512-256-256 (ReLU), one head with 18
+# policy logits + 1 value; RMSProp; learning rate and entropy cost per member; 32 trajectories of 20
+# transitions per step; score = mean of the last 10 unroll returns.
+A2C_MLP = Workload(
+    name="a2c_mlp_bf16", kind=WL_A2C, P=128, dims=[512, 256, 256, 19], act=ACT_RELU, dtype=DTYPE_BF16,
+    optimizer=OPT_RMSPROP, batch=32, unroll=20, gamma=0.99, value_cost=0.5, n_actions=18, latent=16,
+    n_train=4096, n_eval=1, roles=[ROLE_LR, ROLE_ENTROPY_COST], priors=[("log", 1e-5, 1e-3), ("log", 1e-4, 1e-2)],
+    h_max=[math.inf, math.inf], ready_interval=100, n_trunc=trunc_count(128, 20), total_steps=2000,
+    opt_const=dict(rho=0.99, eps=1e-5), data_seed=1005, perturb=(0.8, 1.2))
+
+WORKLOADS = {1: MLP_SMALL, 2: MLP_WIDE, 3: GAN_MLP, 5: A2C_MLP}
 
 
 def gaussian_mixture(n_classes, dim, n_train, n_eval, seed):
@@ -110,6 +120,29 @@ def initial_gan_weights(wl, P, seed):
     g = initial_mlp_weights(wl.dims, P, seed)
     d = initial_mlp_weights(wl.dims2, P, seed + 1000)
     return [(g[i], d[i]) for i in range(P)]
+
+
+def trajectory_pool(wl):
+    """Pre-recorded trajectories from a linear-Gaussian latent system with uniformly random actions:
+    z' = A z + B e(a) + 0.1 xi (A = 0.9 x random orthogonal, B ~ N(0, 0.3^2)), observation = C z + N(0, I)
+    (C ~ N(0, 1) / 4), reward = w.z + 0.1 noise.  Returns (obs [n][T+1][d], actions [n][T], rewards [n][T])."""
+    rng = np.random.default_rng(wl.data_seed)
+    nz, d, T, n = wl.latent, wl.dims[0], wl.unroll, wl.n_train
+    Q, _ = np.linalg.qr(rng.standard_normal((nz, nz)))
+    A = 0.9 * Q
+    Bm = rng.standard_normal((nz, wl.n_actions)) * 0.3
+    C = rng.standard_normal((d, nz)) / 4.0
+    w = rng.standard_normal(nz)
+    z = rng.standard_normal((n, nz))
+    obs = np.empty((n, T + 1, d), dtype=np.float32)
+    actions = rng.integers(0, wl.n_actions, size=(n, T)).astype(np.int32)
+    rewards = np.empty((n, T), dtype=np.float32)
+    for t in range(T + 1):
+        obs[:, t] = z @ C.T + rng.standard_normal((n, d))
+        if t < T:
+            rewards[:, t] = z @ w + 0.1 * rng.standard_normal(n)
+            z = z @ A.T + Bm[:, actions[:, t]].T + 0.1 * rng.standard_normal((n, nz))
+    return obs, actions, rewards
 
 
 def initial_hypers(wl, seed):

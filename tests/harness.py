@@ -185,3 +185,55 @@ class GanPair:
         wl = self.wl
         pop = [self.ref[i] for i in range(wl.P)]
         return opbt.exploit_explore(pop, rnd, self.seed, wl.n_trunc, wl.perturb[0], wl.perturb[1], wl.h_max, scores=scores)
+
+
+class A2CPair:
+    """An actor-critic population on the GPU and its oracle twin (all members or a sample)."""
+
+    def __init__(self, wl, seed=workloads.POPULATION_SEED, init_seed=5, ref_members=None):
+        import torch
+        from oracle import a2c as oa
+        self.oa, self.wl, self.seed = oa, wl, seed
+        self.obs, self.actions, self.rewards = workloads.trajectory_pool(wl)
+        self.cfg = binding.make_config(wl, seed)
+        self.gpu = binding.Population(self.cfg)
+        weights = workloads.initial_mlp_weights(wl.dims, wl.P, init_seed)
+        H = workloads.initial_hypers(wl, init_seed + 1)
+        self.gpu.set_members(weights, H)
+        oc_ = {k: float(np.float32(v)) for k, v in wl.opt_const.items()}
+        self.spec = oa.A2CSpec(wl.dims[:-1], wl.n_actions, wl.batch, wl.unroll, seed, roles=wl.roles,
+                               gamma=float(np.float32(wl.gamma)), value_cost=float(np.float32(wl.value_cost)),
+                               rho=oc_["rho"], rms_eps=oc_["eps"], hidden_act=wl.act,
+                               bf16_storage=wl.dtype == workloads.DTYPE_BF16)
+        self.ref_ids = list(range(wl.P)) if ref_members is None else list(ref_members)
+        self.ref = {i: oa.new_member(self.spec, weights[i], H[i], i) for i in self.ref_ids}
+        dev = self.gpu.device
+        self.d_pool = [torch.from_numpy(self.obs).to(dev), torch.from_numpy(self.actions).to(dev),
+                       torch.from_numpy(self.rewards).to(dev)]
+
+    def step_ref(self, s):
+        return np.array([self.oa.step(self.spec, self.ref[i], i, s, self.obs, self.actions, self.rewards) for i in self.ref_ids])
+
+    def eval_ref(self):
+        return np.array([self.oa.evaluate(self.spec, self.ref[i]) for i in self.ref_ids], dtype=np.float32)
+
+    ref_flat = GanPair.ref_flat
+    member_errors = GanPair.member_errors
+
+    def sync_ref_from_gpu(self, i):
+        m = self.ref[i]
+        lay, shapes = self.gpu.layout, self.gpu.layer_shapes
+        for what, which in (("theta", binding.ARR_W32), ("s0", binding.ARR_OPT0)):
+            flat = self.gpu.get(which, i).astype(np.float64)
+            arrs = m.theta if what == "theta" else m.opt[what]
+            for l, (fi, fo) in enumerate(shapes):
+                arrs[2 * l] = flat[lay.w_off[l]:lay.w_off[l] + fi * fo].reshape(fi, fo).copy()
+                arrs[2 * l + 1] = flat[lay.b_off[l]:lay.b_off[l] + fo].copy()
+        m.t = int(self.gpu.get(binding.ARR_T, i)[0])
+        m.h = self.gpu.get(binding.ARR_HYPER, i).copy()
+        m.hist = [np.float32(v) for v in self.gpu.history()[i]]
+
+    def exploit_ref(self, rnd, scores):
+        wl = self.wl
+        pop = [self.ref[i] for i in range(wl.P)]
+        return opbt.exploit_explore(pop, rnd, self.seed, wl.n_trunc, wl.perturb[0], wl.perturb[1], wl.h_max, scores=scores)

@@ -1,0 +1,100 @@
+"""The actor-critic workload on the GPU against the oracle: A2C loss and update with RMSProp, the
+return history behind the score, and exploit/explore carrying the history along."""
+import numpy as np
+import pytest
+
+from paper_1711_09846_amd import binding, workloads
+from tests.harness import A2CPair
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 1e-2
+FLOOR = 1.0     # the loss mixes O(1) log-probabilities, squared value errors and entropies
+
+
+def _reduced(P=6):
+    return workloads.A2C_MLP.replace(P=P, dims=[24, 72, 40, 19], batch=5, unroll=6, n_train=50, n_trunc=1, latent=4,
+                                     priors=[("log", 1e-4, 2e-3), ("log", 1e-4, 1e-2)])
+
+
+def _hist_equal(pair, members):
+    got = pair.gpu.history()
+    for i in members:
+        ref = [float(v) for v in pair.ref[i].hist]
+        assert len(got[i]) == len(ref) and np.allclose(got[i], ref, rtol=2e-7, atol=1e-7), (i, got[i], ref)
+
+
+def test_a2c_reduced_free_running_window():
+    pair = A2CPair(_reduced())
+    g, P = pair.gpu, pair.wl.P
+    assert np.all(np.isneginf(_eval(g)))                              # no unroll yet
+    worst = dict(w=0.0, s0=0.0, loss=0.0, score=0.0)
+    rnd = 0
+    for s in range(26):
+        g.step(pair.d_pool, s)
+        loss_ref = pair.step_ref(s)
+        loss = g.get(binding.ARR_LOSS)
+        worst["loss"] = max(worst["loss"], float(np.max(np.abs(loss - loss_ref) / np.maximum(np.abs(loss_ref), FLOOR))))
+        for i in range(P):
+            worst["w"] = max(worst["w"], pair.member_errors(i, binding.ARR_W32, "theta")[0])
+            worst["s0"] = max(worst["s0"], pair.member_errors(i, binding.ARR_OPT0, "s0")[1])
+        assert worst["w"] <= TOL_BF16 and worst["loss"] <= TOL_BF16, (s, worst)
+        _hist_equal(pair, range(P))
+        if (s + 1) % 4 == 0:
+            sc = _eval(g)
+            sc_ref = pair.eval_ref()
+            worst["score"] = max(worst["score"], float(np.max(np.abs(sc - sc_ref) / np.maximum(np.abs(sc_ref), FLOOR))))
+            assert worst["score"] <= 1e-6
+            g.exploit_explore(rnd)
+            order, donor = pair.exploit_ref(rnd, sc)
+            assert list(g.get(binding.ARR_ORDER)) == order and np.array_equal(g.get(binding.ARR_DONOR), donor)
+            assert g.get(binding.ARR_HYPER).tobytes() == np.stack([pair.ref[i].h for i in range(P)]).tobytes()
+            _hist_equal(pair, range(P))                               # the history travelled with the weights
+            rnd += 1
+    print("a2c reduced:", {k: float("%.3g" % v) for k, v in worst.items()}, flush=True)
+
+
+def _eval(g):
+    g.eval()
+    return g.get(binding.ARR_SCORE)
+
+
+def test_a2c_full_size_steps_score_and_copy():
+    """P = 128, torso 512-256-256, head 18 + 1, 32 trajectories x 20 transitions (672 rows per member).
+    Four sampled members are followed by the oracle, re-synchronised before every step."""
+    from oracle import pbt as opbt
+    wl = workloads.A2C_MLP
+    H0 = workloads.initial_hypers(wl, 6)
+    sample = sorted({int(np.argmax(H0[:, 0])), int(np.argmax(H0[:, 1])), 3, 77})
+    pair = A2CPair(wl, ref_members=sample)
+    g = pair.gpu
+    worst = dict(step=0.0, s0=0.0, loss=0.0, score=0.0)
+    for s in range(12):
+        for i in sample:
+            pair.sync_ref_from_gpu(i)
+        g.step(pair.d_pool, s)
+        loss_ref = pair.step_ref(s)
+        loss = g.get(binding.ARR_LOSS)[sample]
+        worst["loss"] = max(worst["loss"], float(np.max(np.abs(loss - loss_ref) / np.maximum(np.abs(loss_ref), FLOOR))))
+        for i in sample:
+            worst["step"] = max(worst["step"], pair.member_errors(i, binding.ARR_W32, "theta")[0])
+            worst["s0"] = max(worst["s0"], pair.member_errors(i, binding.ARR_OPT0, "s0")[1])
+        assert worst["step"] <= TOL_BF16 and worst["loss"] <= TOL_BF16, (s, worst)
+        _hist_equal(pair, sample)
+    sc = _eval(g)
+    worst["score"] = float(np.max(np.abs(sc[sample] - pair.eval_ref())))
+    assert worst["score"] <= 1e-6
+    before = {w: g.get(w) for w in (binding.ARR_W32, binding.ARR_OPT0, binding.ARR_W16, binding.ARR_HIST, binding.ARR_HYPER)}
+    g.exploit_explore(0)
+    order, donor = opbt.truncation_select(sc, wl.n_trunc, 0, pair.seed)
+    assert list(g.get(binding.ARR_ORDER)) == order and np.array_equal(g.get(binding.ARR_DONOR), donor)
+    assert (donor >= 0).sum() == 25
+    after = {w: g.get(w) for w in before}
+    for r in range(wl.P):
+        src = donor[r] if donor[r] >= 0 else r
+        for w in (binding.ARR_W32, binding.ARR_OPT0, binding.ARR_W16, binding.ARR_HIST):
+            assert after[w][r].tobytes() == before[w][src].tobytes()
+        href = before[binding.ARR_HYPER][r] if donor[r] < 0 else opbt.perturb(
+            before[binding.ARR_HYPER][src], 0, r, pair.seed, wl.perturb[0], wl.perturb[1], wl.h_max)
+        assert after[binding.ARR_HYPER][r].tobytes() == href.tobytes()
+    print("a2c full size:", {k: float("%.3g" % v) for k, v in worst.items()}, flush=True)
