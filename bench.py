@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--kernel", default="optimizer", help="kernel class whose roofline is reported")
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 5],
+                    help="2 = wide bf16 MLP classifiers (default, the headline workload), 3 = MLP GAN pairs, 5 = actor-critic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -71,16 +73,26 @@ def main():
     import torch
     from paper_1711_09846_amd import binding, workloads
 
-    wl = workloads.MLP_WIDE
+    wl = workloads.WORKLOADS[args.workload]
     seed = workloads.POPULATION_SEED
-    data = workloads.classifier_data(wl)
-    (tx, ty), (ex, ey) = data
     cfg = binding.make_config(wl, seed)
     pop = binding.Population(cfg)
-    pop.set_members(workloads.initial_mlp_weights(wl.dims, wl.P, 5), workloads.initial_hypers(wl, 6))
     dev = pop.device
-    d_train = [torch.from_numpy(tx).to(dev), torch.from_numpy(ty).to(dev)]
-    d_eval = [torch.from_numpy(ex).to(dev), torch.from_numpy(ey).to(dev)]
+    data = None
+    if args.workload == 2:
+        data = workloads.classifier_data(wl)
+        (tx, ty), (ex, ey) = data
+        pop.set_members(workloads.initial_mlp_weights(wl.dims, wl.P, 5), workloads.initial_hypers(wl, 6))
+        d_train = [torch.from_numpy(tx).to(dev), torch.from_numpy(ty).to(dev)]
+        d_eval = [torch.from_numpy(ex).to(dev), torch.from_numpy(ey).to(dev)]
+    elif args.workload == 3:
+        tx, ex = workloads.gan_data(wl)
+        pop.set_members([list(g) + list(d) for g, d in workloads.initial_gan_weights(wl, wl.P, 5)], workloads.initial_hypers(wl, 6))
+        d_train, d_eval = [torch.from_numpy(tx).to(dev)], [torch.from_numpy(ex).to(dev)]
+    else:
+        obs, act, rew = workloads.trajectory_pool(wl)
+        pop.set_members(workloads.initial_mlp_weights(wl.dims, wl.P, 5), workloads.initial_hypers(wl, 6))
+        d_train, d_eval = [torch.from_numpy(obs).to(dev), torch.from_numpy(act).to(dev), torch.from_numpy(rew).to(dev)], []
 
     klass = {"optimizer": binding.K_OPTIMIZER, "gemm_fwd": binding.K_GEMM_FWD, "gemm_wgrad": binding.K_GEMM_WGRAD,
              "gemm_dgrad": binding.K_GEMM_DGRAD, "copy": binding.K_COPY, "head": binding.K_HEAD,
@@ -115,14 +127,15 @@ def main():
     n = pop.layout.n_params
     L = len(wl.dims) - 1
     flops_fwd = sum(2.0 * wl.batch * wl.dims[l] * wl.dims[l + 1] for l in range(L - 1)) * wl.P
+    state_bytes = {2: 14.0, 3: 14.0, 5: 10.0}[args.workload]      # fp32 theta + optimiser state (+ bf16 shadow) per parameter
     per_launch = {
         # Adam: read theta, g, m, v (16 B), write theta, m, v (12 B) and the bf16 shadow (2 B) per parameter
-        "optimizer": ("hbm", 30.0 * n * wl.P),
-        # read + write of every array of the n_trunc copied members: fp32 theta, m, v and the bf16 shadow
-        "copy": ("hbm", 2.0 * 14.0 * n * wl.n_trunc),
-        "gemm_fwd": ("mfma", flops_fwd / (L - 1)),
-        "gemm_wgrad": ("mfma", flops_fwd / (L - 1)),
-        "gemm_dgrad": ("mfma", 2.0 * wl.batch * wl.dims[1] * wl.dims[2] * wl.P),
+        "optimizer": ("hbm", 30.0 * n * wl.P) if args.workload == 2 else None,
+        # read + write of every array of the n_trunc copied members: fp32 theta, optimiser state, bf16 shadow
+        "copy": ("hbm", 2.0 * state_bytes * n * wl.n_trunc),
+        "gemm_fwd": ("mfma", flops_fwd / (L - 1)) if args.workload == 2 else None,
+        "gemm_wgrad": ("mfma", flops_fwd / (L - 1)) if args.workload == 2 else None,
+        "gemm_dgrad": ("mfma", 2.0 * wl.batch * wl.dims[1] * wl.dims[2] * wl.P) if args.workload == 2 else None,
     }.get(args.kernel)
     roofline = None
     if per_launch and k_n:
@@ -133,19 +146,20 @@ def main():
         else:
             ach, peak, unit = work / avg_s / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
         roofline = {"kernel": args.kernel, "bound": bound, "achieved": ach, "peak": peak, "unit": unit,
-                    "frac": ach / peak, "traffic": MEASURED_TRAFFIC_BYTES.get(args.kernel), "avg_launch_us": avg_s * 1e6, "launches": k_n,
+                    "frac": ach / peak, "traffic": MEASURED_TRAFFIC_BYTES.get(args.kernel) if args.workload == 2 else None, "avg_launch_us": avg_s * 1e6, "launches": k_n,
                     "work_per_launch": work}
 
     out = {
         "metric": "population member-steps/sec at 1 MI355X", "value": wl.P * args.steps / dt, "unit": "member-steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "P": wl.P, "dims": wl.dims, "batch": wl.batch, "optimizer": "adam",
+        "config": {"workload": wl.name, "P": wl.P, "dims": wl.dims, "batch": wl.batch,
+                   "optimizer": {0: "sgd_momentum", 1: "adam", 2: "rmsprop"}[wl.optimizer],
                    "ready_interval": wl.ready_interval, "n_trunc": wl.n_trunc, "eval_rows": wl.n_eval,
                    "exploit_rounds_in_timed_region": n_rounds},
         "roofline": roofline,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.workload == 2:
         out["cpu_baseline"] = cpu_baseline(wl, data, seed)
     print(json.dumps(out))
 

@@ -8,7 +8,7 @@
 // Tiling (wave64): a workgroup of 256 threads = 4 wavefronts owns a BM x BN
 // tile of C; each wavefront owns a (BM/WM) x (BN/WN) sub-tile made of 32x32
 // accumulator blocks fed by v_mfma_f32_32x32x16_bf16.  The K loop moves
-// BK = 64 wide slabs of A and B from HBM into registers (16-byte loads), then
+// BK wide slabs of A and B from HBM into registers (16-byte loads), then
 // into LDS in a "K-contiguous" layout, so that every MFMA operand is one
 // 16-byte LDS read.  Operands whose memory layout is contiguous along M or N
 // instead of K (W in the forward pass, X and dY in the weight gradient) are
@@ -35,16 +35,26 @@ struct GemmArgs {
 };
 
 constexpr int GEMM_THREADS = 256;
-constexpr int GEMM_BK = 64;
-constexpr int GEMM_PITCH = GEMM_BK + 8;  // LDS row pitch in elements (144 B: keeps 16-byte alignment, skews banks)
+// LDS row pitch in elements for a slab width BK: +8 keeps 16-byte alignment and skews the banks
+constexpr int gemm_pitch(int bk) { return bk + 8; }
+// Within an LDS row the 16-byte slots (8 k values each) are permuted by the row's group of eight:
+// slot' = slot ^ ((row / 8) & mask).  Readers (32 consecutive rows, one slot) are unaffected, and
+// the transposing writers (lanes 8 rows apart, same slot), which would otherwise all hit one bank
+// because 8 row pitches are a multiple of the bank period, are spread over the banks.
+template <int BK>
+__device__ __forceinline__ int lds_offset(int row, int k) {
+  constexpr int MASK = (BK / 8 < 8 ? BK / 8 : 8) - 1;
+  return row * gemm_pitch(BK) + ((((k >> 3) ^ ((row >> 3) & MASK)) << 3) | (k & 7));
+}
 
 // ---- global -> register staging -------------------------------------------------------------
 // Operand tile of ROWS x BK (ROWS along M or N).  KCONTIG: memory is [row][k].
 // Otherwise memory is [k][row] and a thread fetches a KB x 8 block (KB k-rows of
 // 8 consecutive rows each) that it transposes before the LDS write.
 
-template <int ROWS, bool KCONTIG>
+template <int ROWS, int GEMM_BK, bool KCONTIG>
 struct TileLoader {
+  static constexpr int GEMM_PITCH = gemm_pitch(GEMM_BK);
   static constexpr int CHUNKS = ROWS * GEMM_BK / 8;            // 16-byte pieces per tile
   static constexpr int PER_THREAD = CHUNKS / GEMM_THREADS;     // pieces per thread
   static constexpr int KB = PER_THREAD;                        // k-rows per thread in the transposed case
@@ -74,6 +84,24 @@ struct TileLoader {
     }
   }
 
+  // The same tile when it lies wholly inside the operand: straight 16-byte loads, no guards.
+  __device__ __forceinline__ void load_interior(const bf16_t* __restrict__ base, int64_t ld, int row0, int k0) {
+    const int t = threadIdx.x;
+    if constexpr (KCONTIG) {
+#pragma unroll
+      for (int j = 0; j < PER_THREAD; ++j) {
+        const int c = t + GEMM_THREADS * j;
+        r[j] = *reinterpret_cast<const uint4*>(base + (int64_t)(row0 + c / (GEMM_BK / 8)) * ld + k0 + (c % (GEMM_BK / 8)) * 8);
+      }
+    } else {
+      const int rb = t % (ROWS / 8);
+      const int kb = t / (ROWS / 8);
+#pragma unroll
+      for (int j = 0; j < KB; ++j)
+        r[j] = *reinterpret_cast<const uint4*>(base + (int64_t)(k0 + kb * KB + j) * ld + row0 + rb * 8);
+    }
+  }
+
   // 8 consecutive elements starting at base[off]; `valid` false or `left` <= 0 gives zeros,
   // 0 < left < 8 loads only the first `left` elements.
   static __device__ __forceinline__ uint4 fetch8(const bf16_t* __restrict__ base, int64_t off, bool valid, int left) {
@@ -100,7 +128,7 @@ struct TileLoader {
         const int c = t + GEMM_THREADS * j;
         const int row = c / (GEMM_BK / 8);
         const int k = (c % (GEMM_BK / 8)) * 8;
-        *reinterpret_cast<uint4*>(lds + row * GEMM_PITCH + k) = r[j];
+        *reinterpret_cast<uint4*>(lds + lds_offset<GEMM_BK>(row, k)) = r[j];
       }
     } else {
       const int rb = t % (ROWS / 8);
@@ -116,7 +144,7 @@ struct TileLoader {
           lo[j / 2] = (a & 0xffffu) | (b << 16);          // row 2q:   k = j, j+1
           hi[j / 2] = (a >> 16) | (b & 0xffff0000u);      // row 2q+1: k = j, j+1
         }
-        bf16_t* p0 = lds + (rb * 8 + 2 * q) * GEMM_PITCH + kb * KB;
+        bf16_t* p0 = lds + lds_offset<GEMM_BK>(rb * 8 + 2 * q, kb * KB);      // both rows are in the same group of eight
         bf16_t* p1 = p0 + GEMM_PITCH;
         if constexpr (KB == 2) {
           *reinterpret_cast<uint32_t*>(p0) = lo[0];
@@ -144,10 +172,11 @@ __device__ __forceinline__ int xcd_remap(int id, int total) {
   return (id % XCDS) * per + id / XCDS;
 }
 
-template <int BM, int BN, int WM, int WN, bool A_MCONTIG, bool B_KCONTIG, class Epilogue>
+template <int BM, int BN, int GEMM_BK, int WM, int WN, bool A_MCONTIG, bool B_KCONTIG, class Epilogue>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs g, Epilogue epi) {
   static_assert(WM * WN == 4, "four wavefronts per workgroup");
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int GEMM_PITCH = gemm_pitch(GEMM_BK);
   __shared__ __attribute__((aligned(16))) bf16_t As[BM * GEMM_PITCH];
   __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * GEMM_PITCH];
 
@@ -162,8 +191,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs g, Epi
   const bf16_t* __restrict__ A = g.A + (int64_t)member * g.sa;
   const bf16_t* __restrict__ B = g.B + (int64_t)member * g.sb;
 
-  TileLoader<BM, !A_MCONTIG> la;
-  TileLoader<BN, B_KCONTIG> lb;
+  TileLoader<BM, GEMM_BK, !A_MCONTIG> la;
+  TileLoader<BN, GEMM_BK, B_KCONTIG> lb;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WN, wn = wave % WN;
@@ -177,27 +206,30 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs g, Epi
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  la.load(A, g.lda, m0, 0, g.M, g.K);
-  lb.load(B, g.ldb, n0, 0, g.N, g.K);
+  // tiles wholly inside the operands (the common case) take the unguarded loads
+  const bool a_inside = m0 + BM <= g.M, b_inside = n0 + BN <= g.N;
+  auto fetch_slab = [&](int k) {
+    const bool k_inside = k + GEMM_BK <= g.K;
+    if (a_inside && k_inside) la.load_interior(A, g.lda, m0, k); else la.load(A, g.lda, m0, k, g.M, g.K);
+    if (b_inside && k_inside) lb.load_interior(B, g.ldb, n0, k); else lb.load(B, g.ldb, n0, k, g.N, g.K);
+  };
+  fetch_slab(0);
 
   for (int k0 = 0; k0 < g.K; k0 += GEMM_BK) {
     __syncthreads();  // previous slab fully consumed
     la.store(As);
     lb.store(Bs);
     __syncthreads();
-    if (k0 + GEMM_BK < g.K) {
-      la.load(A, g.lda, m0, k0 + GEMM_BK, g.M, g.K);
-      lb.load(B, g.ldb, n0, k0 + GEMM_BK, g.N, g.K);
-    }
+    if (k0 + GEMM_BK < g.K) fetch_slab(k0 + GEMM_BK);
 #pragma unroll
     for (int kk = 0; kk < GEMM_BK; kk += 16) {
       bf16x8_t af[TM], bfr[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        af[i] = *reinterpret_cast<const bf16x8_t*>(As + (wm * (BM / WM) + i * 32 + frag_row) * GEMM_PITCH + kk + frag_k);
+        af[i] = *reinterpret_cast<const bf16x8_t*>(As + lds_offset<GEMM_BK>(wm * (BM / WM) + i * 32 + frag_row, kk + frag_k));
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8_t*>(Bs + (wn * (BN / WN) + j * 32 + frag_row) * GEMM_PITCH + kk + frag_k);
+        bfr[j] = *reinterpret_cast<const bf16x8_t*>(Bs + lds_offset<GEMM_BK>(wn * (BN / WN) + j * 32 + frag_row, kk + frag_k));
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -273,7 +305,7 @@ struct EpiDgradAct {
 
 // Host-side launcher: picks the tile shape from the layout flags.  Returns hipSuccess or the
 // launch error.  Caller guarantees 16-byte alignment of pitches / strides / bases.
-template <int BM, int BN, class Epilogue>
+template <int BM, int BN, int BK, class Epilogue>
 hipError_t launch_gemm_tile(const GemmArgs& g0, bool a_m_contig, bool b_k_contig, const Epilogue& epi, hipStream_t stream) {
   GemmArgs g = g0;
   g.tiles_m = (g.M + BM - 1) / BM;
@@ -282,13 +314,13 @@ hipError_t launch_gemm_tile(const GemmArgs& g0, bool a_m_contig, bool b_k_contig
   if (total <= 0 || total > 0x7fffffff) return hipErrorInvalidValue;
   dim3 grid((unsigned)total), block(GEMM_THREADS);
   if (!a_m_contig && !b_k_contig)
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, 2, 2, false, false, Epilogue>), grid, block, 0, stream, g, epi);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, BK, 2, 2, false, false, Epilogue>), grid, block, 0, stream, g, epi);
   else if (!a_m_contig && b_k_contig)
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, 2, 2, false, true, Epilogue>), grid, block, 0, stream, g, epi);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, BK, 2, 2, false, true, Epilogue>), grid, block, 0, stream, g, epi);
   else if (a_m_contig && !b_k_contig)
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, 2, 2, true, false, Epilogue>), grid, block, 0, stream, g, epi);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, BK, 2, 2, true, false, Epilogue>), grid, block, 0, stream, g, epi);
   else
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, 2, 2, true, true, Epilogue>), grid, block, 0, stream, g, epi);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, BK, 2, 2, true, true, Epilogue>), grid, block, 0, stream, g, epi);
   return hipGetLastError();
 }
 
@@ -332,8 +364,8 @@ hipError_t launch_gemm_bf16(const bf16_t* A, int64_t lda, int64_t sa, bool a_m_c
   g.M = M; g.N = N; g.K = K; g.batch = batch;
   g.tiles_m = g.tiles_n = 0;
   const int64_t wide = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
-  if (wide < 4 * 256 && N > 64) return launch_gemm_tile<128, 64, Epilogue>(g, a_m_contig, b_k_contig, epi, stream);
-  return launch_gemm_tile<128, 128, Epilogue>(g, a_m_contig, b_k_contig, epi, stream);
+  if (wide < 4 * 256 && N > 64) return launch_gemm_tile<128, 64, 64, Epilogue>(g, a_m_contig, b_k_contig, epi, stream);
+  return launch_gemm_tile<128, 128, 64, Epilogue>(g, a_m_contig, b_k_contig, epi, stream);
 }
 
 }  // namespace pbt
