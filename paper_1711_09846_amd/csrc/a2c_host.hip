@@ -50,52 +50,68 @@ __global__ __launch_bounds__(64) void a2c_fetch_aux_kernel(const int32_t* __rest
   }
 }
 
-// Loss and its gradient with respect to the head outputs.  One thread per trajectory walks it
-// backwards: R_T = V(s_T), R_t = r_t + gamma R_{t+1}; A_t = R_t - V_t (both constants);
+// Loss and its gradient with respect to the head outputs, one workgroup per member.
+// Phase 1 (one thread per trajectory) walks each trajectory backwards for the bootstrapped returns
+//   R_T = V(s_T), R_t = r_t + gamma R_{t+1}      into LDS.
+// Phase 2 (one thread per transition) evaluates, with A_t = R_t - V_t and R_t constants,
 //   loss_t = -A_t log pi(a_t) + value_cost (R_t - V_t)^2 - entropy_cost H_t
 //   dlogit_c = ( -A_t (1[c = a_t] - pi_c) + entropy_cost pi_c (log pi_c + H_t) ) / n
-//   dV_t = 2 value_cost (V_t - R_t) / n,   n = B T;  the bootstrap row gets zeros.
-// out: head outputs float [P][B][T+1][32] (n_act logits, then the value).
-__global__ __launch_bounds__(64) void a2c_loss_kernel(const float* __restrict__ out, const int32_t* __restrict__ act,
-                                                      const float* __restrict__ rew, const float* __restrict__ H,
-                                                      int n_hyper, int col_ent, int B, int T, int n_act, float gamma,
-                                                      float value_cost, bf16_t* __restrict__ dout, float* __restrict__ loss) {
+//   dV_t = 2 value_cost (V_t - R_t) / n,   n = B T;  the bootstrap rows get zeros.
+// out: head outputs float [P][B][T+1][32] (n_act logits, then the value).  The per-thread losses
+// are combined in a fixed order (lane butterfly, then the four wavefronts).
+__global__ __launch_bounds__(256) void a2c_loss_kernel(const float* __restrict__ out, const int32_t* __restrict__ act,
+                                                       const float* __restrict__ rew, const float* __restrict__ H,
+                                                       int n_hyper, int col_ent, int B, int T, int n_act, float gamma,
+                                                       float value_cost, bf16_t* __restrict__ dout, float* __restrict__ loss) {
+  extern __shared__ float Rl[];  // [B][T]
+  __shared__ float wsum[4];
   const int i = blockIdx.x;
   const float ent_cost = H[i * n_hyper + col_ent];
   const float inv_n = 1.f / (float)(B * T);
-  float lacc = 0.f;
-  for (int r = threadIdx.x; r < B; r += 64) {
+  for (int r = threadIdx.x; r < B; r += 256) {
     const float* __restrict__ o = out + ((int64_t)i * B + r) * (T + 1) * 32;
-    bf16_t* __restrict__ d = dout + ((int64_t)i * B + r) * (T + 1) * 32;
     float R = o[T * 32 + n_act];
-    for (int c = 0; c < 32; ++c) d[T * 32 + c] = 0;
     for (int t = T - 1; t >= 0; --t) {
-      const float* lg = o + t * 32;
-      const float v = lg[n_act];
       R = rew[((int64_t)i * B + r) * T + t] + gamma * R;
-      const float adv = R - v;
-      float mx = lg[0];
-      for (int c = 1; c < n_act; ++c) mx = fmaxf(mx, lg[c]);
-      float se = 0.f;
-      for (int c = 0; c < n_act; ++c) se += expf(lg[c] - mx);
-      const float lse = mx + logf(se);
-      float ent = 0.f;
-      for (int c = 0; c < n_act; ++c) {
-        const float lp = lg[c] - lse;
-        ent -= expf(lp) * lp;
-      }
-      const int a = act[((int64_t)i * B + r) * T + t];
-      lacc += -adv * (lg[a] - lse) + value_cost * adv * adv - ent_cost * ent;
-      for (int c = 0; c < n_act; ++c) {
-        const float lp = lg[c] - lse, pi = expf(lp);
-        d[t * 32 + c] = f2bf((-adv * ((c == a ? 1.f : 0.f) - pi) + ent_cost * pi * (lp + ent)) * inv_n);
-      }
-      d[t * 32 + n_act] = f2bf(2.f * value_cost * (v - R) * inv_n);
-      for (int c = n_act + 1; c < 32; ++c) d[t * 32 + c] = 0;
+      Rl[r * T + t] = R;
     }
   }
+  __syncthreads();
+  float lacc = 0.f;
+  for (int idx = threadIdx.x; idx < B * (T + 1); idx += 256) {
+    const int r = idx / (T + 1), t = idx - r * (T + 1);
+    const float* lg = out + ((int64_t)i * B * (T + 1) + idx) * 32;
+    bf16_t* __restrict__ d = dout + ((int64_t)i * B * (T + 1) + idx) * 32;
+    if (t == T) {
+      for (int c = 0; c < 32; ++c) d[c] = 0;
+      continue;
+    }
+    const float R = Rl[r * T + t];
+    const float v = lg[n_act];
+    const float adv = R - v;
+    float mx = lg[0];
+    for (int c = 1; c < n_act; ++c) mx = fmaxf(mx, lg[c]);
+    float se = 0.f;
+    for (int c = 0; c < n_act; ++c) se += expf(lg[c] - mx);
+    const float lse = mx + logf(se);
+    float ent = 0.f;
+    for (int c = 0; c < n_act; ++c) {
+      const float lp = lg[c] - lse;
+      ent -= expf(lp) * lp;
+    }
+    const int a = act[((int64_t)i * B + r) * T + t];
+    lacc += -adv * (lg[a] - lse) + value_cost * adv * adv - ent_cost * ent;
+    for (int c = 0; c < n_act; ++c) {
+      const float lp = lg[c] - lse, pi = expf(lp);
+      d[c] = f2bf((-adv * ((c == a ? 1.f : 0.f) - pi) + ent_cost * pi * (lp + ent)) * inv_n);
+    }
+    d[n_act] = f2bf(2.f * value_cost * (v - R) * inv_n);
+    for (int c = n_act + 1; c < 32; ++c) d[c] = 0;
+  }
   lacc = wave_sum(lacc);
-  if (threadIdx.x == 0) loss[i] = lacc * inv_n;
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = lacc;
+  __syncthreads();
+  if (threadIdx.x == 0) loss[i] = (((wsum[0] + wsum[1]) + wsum[2]) + wsum[3]) * inv_n;
 }
 
 // score = mean of the last min(count, 10) returns (double accumulation), -inf when there are none
@@ -117,6 +133,7 @@ pbt_status a2c_check_and_plan(const pbt_config* c, Plan* pl, Carver* w) {
   const int L = c->n_layers;
   if (L < 2) return fail(nullptr, PBT_EUNSUPPORTED, "the actor-critic network needs at least one torso layer before its head");
   if (c->unroll < 1) return fail(nullptr, PBT_EINVAL, "unroll must be positive");
+  if ((int64_t)c->batch * c->unroll * 4 > 48 * 1024) return fail(nullptr, PBT_EUNSUPPORTED, "batch x unroll above 12288 transitions per member");
   if (c->dims[L] < 2 || c->dims[L] > 32) return fail(nullptr, PBT_EUNSUPPORTED, "head width (actions + value) must be 2..32");
   for (int l = 0; l < L; ++l)
     if (c->dims[l] % 8) return fail(nullptr, PBT_EUNSUPPORTED, "torso widths must be multiples of 8");
@@ -167,7 +184,7 @@ pbt_status a2c_step(pbt_handle* h, const float* obs, const int32_t* actions, con
   if ((st = forward(h, net, L - 1, R, A, Z, nullptr, 0, s)) != PBT_OK) return st;
   PBT_LAUNCH(h, PBT_K_HEAD, s, head_fwd_loss(A[L - 1], (int64_t)R * Kh, W16 + p.lay.w_off[L - 1], S, W32 + p.lay.b_off[L - 1], S, nullptr,
                                              0, P, R, Kh, C, 0.f, -2, nullptr, out, 0, s));
-  hipLaunchKernelGGL(a2c_loss_kernel, dim3(P), dim3(64), 0, s, out, act, rew, h->st<float>(p.o_hyper), c.n_hyper, a.col_ent, B, T,
+  hipLaunchKernelGGL(a2c_loss_kernel, dim3(P), dim3(256), (size_t)B * T * sizeof(float), s, out, act, rew, h->st<float>(p.o_hyper), c.n_hyper, a.col_ent, B, T,
                      C - 1, c.gamma, c.value_cost, dout, h->st<float>(p.o_loss));
   PBT_HIP(h, hipGetLastError());
   {

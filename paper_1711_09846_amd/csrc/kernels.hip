@@ -102,21 +102,21 @@ hipError_t gather_batch(const float* train_x, const int32_t* train_y, int n_trai
   return hipGetLastError();
 }
 
-// db[n] = sum_r dZ[r][n].  A workgroup covers 512 columns: 64 threads x 8 columns (one 16-byte load
-// per row) times 4 row groups; the four partial sums are combined through LDS in fixed order.
+// db[n] = sum_r dZ[r][n].  A workgroup covers 64 columns: 8 threads x 8 columns (one 16-byte load per
+// row) times 32 row groups; the 32 partial sums are combined through LDS in fixed order.
 __global__ __launch_bounds__(256) void bias_grad_kernel(const bf16_t* __restrict__ dZ, int rows, int N, int64_t ld,
                                                         float* __restrict__ db, int64_t sg) {
-  __shared__ float part[4][512];
+  __shared__ float part[32][65];
   const int i = blockIdx.y;
-  const int cg = threadIdx.x & 63, rg = threadIdx.x >> 6;
-  const int n0 = blockIdx.x * 512 + cg * 8;
+  const int cg = threadIdx.x & 7, rg = threadIdx.x >> 3;
+  const int n0 = blockIdx.x * 64 + cg * 8;
   float acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
   if (n0 < N) {
     const bf16_t* __restrict__ p = dZ + (int64_t)i * rows * ld + n0;
     const bool full = n0 + 8 <= N;
-    for (int r = rg; r < rows; r += 4) {
+    for (int r = rg; r < rows; r += 32) {
       if (full) {
         const uint4 v = *reinterpret_cast<const uint4*>(p + (int64_t)r * ld);
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -133,14 +133,17 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const bf16_t* __restrict
 #pragma unroll
   for (int e = 0; e < 8; ++e) part[rg][cg * 8 + e] = acc[e];
   __syncthreads();
-  for (int c = threadIdx.x; c < 512; c += 256) {
-    const int n = blockIdx.x * 512 + c;
-    if (n < N) db[(int64_t)i * sg + n] = ((part[0][c] + part[1][c]) + part[2][c]) + part[3][c];
+  if (threadIdx.x < 64) {
+    const int n = blockIdx.x * 64 + threadIdx.x;
+    float sum = 0.f;
+#pragma unroll
+    for (int g = 0; g < 32; ++g) sum += part[g][threadIdx.x];
+    if (n < N) db[(int64_t)i * sg + n] = sum;
   }
 }
 hipError_t bias_grad(const bf16_t* dZ, int P, int rows, int N, int64_t ld, float* db, int64_t sg, hipStream_t s) {
   if (ld % 8) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(bias_grad_kernel, dim3((N + 511) / 512, P), dim3(256), 0, s, dZ, rows, N, ld, db, sg);
+  hipLaunchKernelGGL(bias_grad_kernel, dim3((N + 63) / 64, P), dim3(256), 0, s, dZ, rows, N, ld, db, sg);
   return hipGetLastError();
 }
 
@@ -283,19 +286,30 @@ hipError_t latent_normal(bf16_t* out, int P, int rows, int d, uint32_t c0, int s
   return hipGetLastError();
 }
 
-__global__ __launch_bounds__(64) void gather_rows_kernel(const float* __restrict__ train_x, int n_train, int d,
-                                                         int64_t member_stride, uint32_t step, uint32_t k0, uint32_t k1,
-                                                         bf16_t* __restrict__ X16, int32_t* __restrict__ t) {
+__global__ __launch_bounds__(256) void gather_rows_kernel(const float* __restrict__ train_x, int n_train, int d,
+                                                          int64_t member_stride, uint32_t step, uint32_t k0, uint32_t k1,
+                                                          bf16_t* __restrict__ X16, int32_t* __restrict__ t) {
   const int r = blockIdx.x, i = blockIdx.y;
   const uint32_t x = philox4x32_10(step, (uint32_t)i, DOMAIN_BATCH, (uint32_t)r, k0, k1).x;
   const float* __restrict__ row = train_x + (int64_t)philox_bounded(x, (uint32_t)n_train) * d;
   bf16_t* __restrict__ o = X16 + (int64_t)i * member_stride + (int64_t)r * d;
-  for (int c = threadIdx.x; c < d; c += 64) o[c] = f2bf(row[c]);
+  if ((d & 3) == 0) {  // rows are 16-byte aligned: four floats in, four bf16 out per access
+    for (int c = threadIdx.x * 4; c < d; c += 1024) {
+      const float4 v = *reinterpret_cast<const float4*>(row + c);
+      uint2 pk;
+      pk.x = f2bf(v.x) | ((uint32_t)f2bf(v.y) << 16);
+      pk.y = f2bf(v.z) | ((uint32_t)f2bf(v.w) << 16);
+      *reinterpret_cast<uint2*>(o + c) = pk;
+    }
+  } else {
+    for (int c = threadIdx.x; c < d; c += 256) o[c] = f2bf(row[c]);
+  }
   if (threadIdx.x == 0 && r == 0) t[i] += 1;
 }
 hipError_t gather_rows(const float* train_x, int n_train, int d, int P, int B, int64_t member_stride, uint32_t step,
                        uint64_t seed, bf16_t* X16, int32_t* t, hipStream_t s) {
-  hipLaunchKernelGGL(gather_rows_kernel, dim3(B, P), dim3(64), 0, s, train_x, n_train, d, member_stride, step,
+  if ((d & 3) == 0 && (member_stride & 3)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gather_rows_kernel, dim3(B, P), dim3(256), 0, s, train_x, n_train, d, member_stride, step,
                      (uint32_t)seed, (uint32_t)(seed >> 32), X16, t);
   return hipGetLastError();
 }
