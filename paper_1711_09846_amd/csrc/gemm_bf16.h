@@ -177,8 +177,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs g, Epi
   static_assert(WM * WN == 4, "four wavefronts per workgroup");
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int GEMM_PITCH = gemm_pitch(GEMM_BK);
-  __shared__ __attribute__((aligned(16))) bf16_t As[BM * GEMM_PITCH];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[BN * GEMM_PITCH];
+  // one LDS block: the A and B slabs during the K loop, then (reused) a strip of the C tile
+  __shared__ __attribute__((aligned(16))) bf16_t smem[(BM + BN) * GEMM_PITCH];
+  bf16_t* const As = smem;
+  bf16_t* const Bs = smem + BM * GEMM_PITCH;
 
   const int total = g.tiles_m * g.tiles_n * g.batch;
   int id = xcd_remap(blockIdx.x, total);
@@ -237,30 +239,86 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs g, Epi
     }
   }
 
-  // Accumulator layout of the 32x32 block: lane -> column (lane % 32); register e -> row
-  // 8*(e/4) + 4*(lane/32) + e%4.
+  // Epilogue.  Accumulator layout of a 32x32 block: lane -> column (lane % 32); register e -> row
+  // 8*(e/4) + 4*(lane/32) + e%4, i.e. a lane holds single elements of many rows.  To reach memory
+  // with 16-byte accesses the tile is passed through LDS in strips of BM/WM rows (the rows of one
+  // wavefront row): accumulators -> LDS (float), then every thread takes runs of 8 consecutive
+  // columns of one row and hands them to the epilogue functor.
+  constexpr int STRIP = BM / WM, CPITCH = BN + 4;
+  static_assert(STRIP * CPITCH * 4 <= (BM + BN) * GEMM_PITCH * 2, "C strip must fit the slab LDS");
+  float* const Cs = reinterpret_cast<float*>(smem);
+#pragma unroll 1
+  for (int strip = 0; strip < WM; ++strip) {
+    __syncthreads();  // slabs (or the previous strip) fully consumed
+    if (wm == strip) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = n0 + wn * (BN / WN) + j * 32 + (lane & 31);
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int m = m0 + wm * (BM / WM) + i * 32 + 8 * (e / 4) + 4 * (lane >> 5) + (e % 4);
-        if (m < g.M && n < g.N) epi(member, m, n, acc[i][j][e]);
+          for (int e = 0; e < 16; ++e)
+            Cs[(i * 32 + 8 * (e / 4) + 4 * (lane >> 5) + (e % 4)) * CPITCH + wn * (BN / WN) + j * 32 + (lane & 31)] = acc[i][j][e];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < STRIP * BN / 8 / GEMM_THREADS; ++q) {
+      const int c = threadIdx.x + GEMM_THREADS * q;
+      const int row = c / (BN / 8), col = (c % (BN / 8)) * 8;
+      const int m = m0 + strip * STRIP + row, n = n0 + col;
+      if (m < g.M && n < g.N) {
+        const float4 lo = *reinterpret_cast<const float4*>(Cs + row * CPITCH + col);
+        const float4 hi = *reinterpret_cast<const float4*>(Cs + row * CPITCH + col + 4);
+        const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        epi.apply8(member, m, n, v, g.N - n < 8 ? g.N - n : 8);
       }
     }
+  }
   if constexpr (Epilogue::HAS_FINISH) epi.finish(member, tm * g.tiles_n + tn, g.tiles_m * g.tiles_n);
 }
 
 // ---- epilogues ------------------------------------------------------------------------------
 
+// Every epilogue receives runs of up to 8 consecutive columns of one row: v[0..count-1] are the
+// accumulator values of C[m][n .. n+count-1].  Full, 16-byte aligned runs use vector accesses.
+
+__device__ __forceinline__ uint4 pack_bf16x8(const float* v) {
+  uint4 p;
+  p.x = f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
+  p.y = f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+  p.z = f2bf(v[4]) | ((uint32_t)f2bf(v[5]) << 16);
+  p.w = f2bf(v[6]) | ((uint32_t)f2bf(v[7]) << 16);
+  return p;
+}
+__device__ __forceinline__ void unpack_bf16x8(uint4 p, float* v) {
+  const uint32_t w[4] = {p.x, p.y, p.z, p.w};
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    v[2 * q] = __uint_as_float(w[q] << 16);
+    v[2 * q + 1] = __uint_as_float(w[q] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+__device__ __forceinline__ void store_bf16_run(bf16_t* dst, const float* v, int count) {
+  if (count == 8 && aligned16(dst)) {
+    *reinterpret_cast<uint4*>(dst) = pack_bf16x8(v);
+  } else {
+    for (int e = 0; e < count; ++e) dst[e] = f2bf(v[e]);
+  }
+}
+
 struct EpiStoreF32 {
   static constexpr bool HAS_FINISH = false;
   float* C;
   int64_t ldc, sc;
-  __device__ __forceinline__ void operator()(int member, int m, int n, float v) const {
-    C[(int64_t)member * sc + (int64_t)m * ldc + n] = v;
+  __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) const {
+    float* dst = C + (int64_t)member * sc + (int64_t)m * ldc + n;
+    if (count == 8 && aligned16(dst)) {
+      *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+      *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    } else {
+      for (int e = 0; e < count; ++e) dst[e] = v[e];
+    }
   }
 };
 
@@ -268,8 +326,8 @@ struct EpiStoreBF16 {
   static constexpr bool HAS_FINISH = false;
   bf16_t* C;
   int64_t ldc, sc;
-  __device__ __forceinline__ void operator()(int member, int m, int n, float v) const {
-    C[(int64_t)member * sc + (int64_t)m * ldc + n] = f2bf(v);
+  __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) const {
+    store_bf16_run(C + (int64_t)member * sc + (int64_t)m * ldc + n, v, count);
   }
 };
 
@@ -282,11 +340,17 @@ struct EpiBiasAct {
   bf16_t* Aout;
   int64_t ld, so;
   int act;
-  __device__ __forceinline__ void operator()(int member, int m, int n, float v) const {
-    const float z = v + bias[(int64_t)member * sbias + n];
+  __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) const {
+    const float* b = bias + (int64_t)member * sbias + n;
+    float z[8], a[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      z[e] = e < count ? v[e] + b[e] : 0.f;
+      a[e] = act_fwd(z[e], act);
+    }
     const int64_t o = (int64_t)member * so + (int64_t)m * ld + n;
-    if (Z) Z[o] = f2bf(z);
-    Aout[o] = f2bf(act_fwd(z, act));
+    if (Z) store_bf16_run(Z + o, z, count);
+    store_bf16_run(Aout + o, a, count);
   }
 };
 
@@ -297,9 +361,17 @@ struct EpiDgradAct {
   bf16_t* dZ;
   int64_t ld, so;
   int act;
-  __device__ __forceinline__ void operator()(int member, int m, int n, float v) const {
+  __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) const {
     const int64_t o = (int64_t)member * so + (int64_t)m * ld + n;
-    dZ[o] = f2bf(v * act_bwd(bf2f(Zprev[o]), act));
+    float z[8], d[8];
+    if (count == 8 && aligned16(Zprev + o)) {
+      unpack_bf16x8(*reinterpret_cast<const uint4*>(Zprev + o), z);
+    } else {
+      for (int e = 0; e < 8; ++e) z[e] = e < count ? bf2f(Zprev[o + e]) : 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) d[e] = v[e] * act_bwd(z[e], act);
+    store_bf16_run(dZ + o, d, count);
   }
 };
 
@@ -337,9 +409,10 @@ struct EpiRbfSum {
   float inv2d;
   float* partial;
   float sum;
-  __device__ __forceinline__ void operator()(int member, int m, int n, float v) {
-    const float sq = na[(int64_t)member * sna + m] + nb[(int64_t)member * snb + n] - 2.f * v;
-    sum += expf(-sq * inv2d);
+  __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) {
+    const float nam = na[(int64_t)member * sna + m];
+    const float* nbn = nb + (int64_t)member * snb + n;
+    for (int e = 0; e < count; ++e) sum += expf(-(nam + nbn[e] - 2.f * v[e]) * inv2d);
   }
   __device__ __forceinline__ void finish(int member, int tile, int tiles) {
     __shared__ float wsum[4];
