@@ -20,7 +20,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counters, scaled by what the same counters read
 # for a copy of known size (profiles/population_step_mlp_wide_bf16_hbm_counters.md).  An entry is only
 # valid for the kernel as it was when the counters were taken; set it to None when the kernel changes.
-MEASURED_TRAFFIC_BYTES = {"optimizer": 2.574e9}
+MEASURED_TRAFFIC_BYTES = {"optimizer": 2.574e9, "gemm_wgrad": None}
 
 
 def cpu_baseline(wl, data, seed, budget_s=15.0):
@@ -59,7 +59,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--kernel", default="optimizer", help="kernel class whose roofline is reported")
+    ap.add_argument("--kernel", default=None, help="kernel class whose roofline is reported (default: the dominant one)")
+    ap.add_argument("--fused", type=int, default=0, choices=[0, 1],
+                    help="0 = separate streaming optimiser pass (default, the faster of the two as measured), "
+                         "1 = optimiser applied inside the weight-gradient GEMMs")
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 5],
                     help="2 = wide bf16 MLP classifiers (default, the headline workload), 3 = MLP GAN pairs, 5 = actor-critic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -75,9 +78,11 @@ def main():
 
     wl = workloads.WORKLOADS[args.workload]
     seed = workloads.POPULATION_SEED
-    cfg = binding.make_config(wl, seed)
+    cfg = binding.make_config(wl, seed, fuse_optimizer=args.fused)
     pop = binding.Population(cfg)
     dev = pop.device
+    if args.kernel is None:
+        args.kernel = "gemm_wgrad" if args.fused else "optimizer"
     data = None
     if args.workload == 2:
         data = workloads.classifier_data(wl)
@@ -134,7 +139,11 @@ def main():
         # read + write of every array of the n_trunc copied members: fp32 theta, optimiser state, bf16 shadow
         "copy": ("hbm", 2.0 * state_bytes * n * wl.n_trunc),
         "gemm_fwd": ("mfma", flops_fwd / (L - 1)) if args.workload == 2 else None,
-        "gemm_wgrad": ("mfma", flops_fwd / (L - 1)) if args.workload == 2 else None,
+        # fused: per hidden matrix read theta, m, v (12 B) and write theta, m, v and the bf16 shadow (14 B) per
+        # parameter, plus the bf16 operands X and dZ; averaged over the launches of one step (one per matrix)
+        "gemm_wgrad": (("hbm", (26.0 * sum(wl.dims[l] * wl.dims[l + 1] for l in range(L - 1))
+                                + 2.0 * wl.batch * sum(wl.dims[l] + wl.dims[l + 1] for l in range(L - 1))) * wl.P / (L - 1))
+                       if args.fused else ("mfma", flops_fwd / (L - 1))) if args.workload == 2 else None,
         "gemm_dgrad": ("mfma", 2.0 * wl.batch * wl.dims[1] * wl.dims[2] * wl.P) if args.workload == 2 else None,
     }.get(args.kernel)
     roofline = None
@@ -153,7 +162,7 @@ def main():
         "metric": "population member-steps/sec at 1 MI355X", "value": wl.P * args.steps / dt, "unit": "member-steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "P": wl.P, "dims": wl.dims, "batch": wl.batch,
+        "config": {"workload": wl.name, "fused_optimizer": bool(args.fused), "P": wl.P, "dims": wl.dims, "batch": wl.batch,
                    "optimizer": {0: "sgd_momentum", 1: "adam", 2: "rmsprop"}[wl.optimizer],
                    "ready_interval": wl.ready_interval, "n_trunc": wl.n_trunc, "eval_rows": wl.n_eval,
                    "exploit_rounds_in_timed_region": n_rounds},

@@ -118,6 +118,9 @@ typedef struct {
   float gamma, value_cost;          /* discount; weight of the squared value error (0.5) */
   int32_t n_train, n_eval;          /* rows (classifier, GAN) or trajectories (actor-critic) of the training set; rows of the held-out set */
   int32_t eval_chunk;               /* rows of the held-out set scored per pass (bounds scratch); 0 = library picks */
+  int32_t fuse_optimizer;           /* bf16 compute: 1 = apply the optimiser inside the weight-gradient GEMMs (the gradient of
+                                       those matrices is then never stored: PBT_ARR_GRAD holds only bias / output-layer
+                                       gradients); 0 = separate optimiser pass over a complete gradient */
   uint64_t seed;                    /* Philox key */
 } pbt_config;
 

@@ -36,7 +36,7 @@ class PbtConfig(C.Structure):
                 ("perturb_hi", C.c_float), ("opt_const", C.c_float * 4), ("act_out", C.c_int32),
                 ("n_layers2", C.c_int32), ("dims2", C.c_int32 * PBT_MAX_DIMS), ("act2", C.c_int32), ("unroll", C.c_int32),
                 ("gamma", C.c_float), ("value_cost", C.c_float), ("n_train", C.c_int32),
-                ("n_eval", C.c_int32), ("eval_chunk", C.c_int32), ("seed", C.c_uint64)]
+                ("n_eval", C.c_int32), ("eval_chunk", C.c_int32), ("fuse_optimizer", C.c_int32), ("seed", C.c_uint64)]
 
 
 class PbtLayout(C.Structure):
@@ -87,7 +87,7 @@ def lib():
     return _lib
 
 
-def make_config(wl, seed, P=None, n_trunc=None, eval_chunk=0):
+def make_config(wl, seed, P=None, n_trunc=None, eval_chunk=0, fuse_optimizer=0):
     """PbtConfig from a workloads.Workload description."""
     c = PbtConfig()
     c.workload = wl.kind
@@ -119,6 +119,7 @@ def make_config(wl, seed, P=None, n_trunc=None, eval_chunk=0):
     if getattr(wl, "unroll", None):                     # actor-critic
         c.unroll, c.gamma, c.value_cost = wl.unroll, wl.gamma, wl.value_cost
     c.n_train, c.n_eval, c.eval_chunk = wl.n_train, wl.n_eval, eval_chunk
+    c.fuse_optimizer = fuse_optimizer
     c.seed = seed
     return c
 

@@ -193,10 +193,12 @@ pbt_status a2c_step(pbt_handle* h, const float* obs, const int32_t* actions, con
     PBT_LAUNCH(h, PBT_K_HEAD, s, bias_grad(dout, P, R, C, 32, G + p.lay.b_off[L - 1], S, s));
   }
   PBT_LAUNCH(h, PBT_K_HEAD, s, head_dgrad(dout, W16 + p.lay.w_off[L - 1], S, Z[L - 2], dZ[L - 2], P, R, Kh, C, c.act, s));
-  if ((st = backward(h, net, L - 1, R, A, Z, dZ, true, nullptr, nullptr, 0, s)) != PBT_OK) return st;
   OptArgs oa{h->st<float>(p.o_w32), h->st<float>(p.o_opt0), nullptr, h->st<bf16_t>(p.o_w16), G, 0, S, h->st<float>(p.o_hyper),
              h->st<int32_t>(p.o_t), S, P, c.n_hyper, c.optimizer, p.col_lr, -1, -1, c.opt_const[0], c.opt_const[1], c.opt_const[2],
              c.opt_const[3]};
+  const bool fused = c.fuse_optimizer != 0;
+  if ((st = backward(h, net, L - 1, R, A, Z, dZ, true, fused ? &oa : nullptr, nullptr, nullptr, 0, s)) != PBT_OK) return st;
+  if (fused) return optimizer_rest(h, oa, 0, L, L - 1, S, s);
   PBT_LAUNCH(h, PBT_K_OPTIMIZER, s, optimizer_step(oa, s));
   return PBT_OK;
 }

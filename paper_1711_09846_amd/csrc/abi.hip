@@ -1,6 +1,6 @@
 // C ABI of the population step: configuration checks, carving of the caller's device buffers,
 // and the kernel sequences behind pbt_step / pbt_eval / pbt_exploit_explore.
-#include "handle.h"
+#include "dense_host.h"
 
 #include <cmath>
 #include <cstdarg>
@@ -274,23 +274,29 @@ pbt_status step_bf16(pbt_handle* h, const float* train_x, const int32_t* train_y
   if (L >= 2)
     PBT_LAUNCH(h, PBT_K_HEAD, s, head_dgrad(dlogits, W16 + p.lay.w_off[L - 1], S, h->sc<bf16_t>(p.o_z[L - 2]),
                                             h->sc<bf16_t>(p.o_dz[L - 2]), P, B, Kh, C, c.act, s));
+  OptArgs oa{W32, h->st<float>(p.o_opt0), c.optimizer == PBT_OPT_ADAM ? h->st<float>(p.o_opt1) : nullptr, W16, G,
+             0, S, h->st<float>(p.o_hyper), h->st<int32_t>(p.o_t), S, P, c.n_hyper, c.optimizer, p.col_lr, p.col_beta1, p.col_wd,
+             c.opt_const[0], c.opt_const[1], c.opt_const[2], c.opt_const[3]};
+  const bool fused = c.fuse_optimizer != 0;
   for (int l = L - 2; l >= 0; --l) {
     const int K = c.dims[l], N = c.dims[l + 1];
-    // dW_l[K][N] = X_l^T dZ_l (contraction over the B rows)
-    GemmOperands wg{h->sc<bf16_t>(p.o_act[l]), K, (int64_t)B * K, true, h->sc<bf16_t>(p.o_dz[l]), N, (int64_t)B * N, false,
-                    K, N, B, P};
-    PBT_LAUNCH(h, PBT_K_GEMM_WGRAD, s, gemm_store_f32(wg, G + p.lay.w_off[l], N, S, s));
-    PBT_LAUNCH(h, PBT_K_BIAS_GRAD, s, bias_grad(h->sc<bf16_t>(p.o_dz[l]), P, B, N, N, G + p.lay.b_off[l], S, s));
     if (l > 0) {
-      // dZ_{l-1}[B][K] = (dZ_l W_l^T) * act'(Z_{l-1})
+      // dZ_{l-1}[B][K] = (dZ_l W_l^T) * act'(Z_{l-1}); before the weight gradient, whose fused
+      // epilogue rewrites the bf16 weights read here
       GemmOperands dg{h->sc<bf16_t>(p.o_dz[l]), N, (int64_t)B * N, false, W16 + p.lay.w_off[l], N, S, true, B, K, N, P};
       PBT_LAUNCH(h, PBT_K_GEMM_DGRAD, s, gemm_dgrad_act(dg, h->sc<bf16_t>(p.o_z[l - 1]), h->sc<bf16_t>(p.o_dz[l - 1]), K,
                                                         (int64_t)B * K, c.act, s));
     }
+    PBT_LAUNCH(h, PBT_K_BIAS_GRAD, s, bias_grad(h->sc<bf16_t>(p.o_dz[l]), P, B, N, N, G + p.lay.b_off[l], S, s));
+    // dW_l[K][N] = X_l^T dZ_l (contraction over the B rows)
+    GemmOperands wg{h->sc<bf16_t>(p.o_act[l]), K, (int64_t)B * K, true, h->sc<bf16_t>(p.o_dz[l]), N, (int64_t)B * N, false,
+                    K, N, B, P};
+    if (fused)
+      PBT_LAUNCH(h, PBT_K_GEMM_WGRAD, s, gemm_wgrad_optimizer(wg, oa, p.lay.w_off[l], N, s));
+    else
+      PBT_LAUNCH(h, PBT_K_GEMM_WGRAD, s, gemm_store_f32(wg, G + p.lay.w_off[l], N, S, s));
   }
-  OptArgs oa{W32, h->st<float>(p.o_opt0), c.optimizer == PBT_OPT_ADAM ? h->st<float>(p.o_opt1) : nullptr, W16, G,
-             0, S, h->st<float>(p.o_hyper), h->st<int32_t>(p.o_t), S, P, c.n_hyper, c.optimizer, p.col_lr, p.col_beta1, p.col_wd,
-             c.opt_const[0], c.opt_const[1], c.opt_const[2], c.opt_const[3]};
+  if (fused) return optimizer_rest(h, oa, 0, L, L - 1, S, s);
   PBT_LAUNCH(h, PBT_K_OPTIMIZER, s, optimizer_step(oa, s));
   return PBT_OK;
 }

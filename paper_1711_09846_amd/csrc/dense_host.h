@@ -36,11 +36,15 @@ inline pbt_status forward(pbt_handle* h, const Net& net, int n_dense, int rows, 
   return PBT_OK;
 }
 
-// Backward through dense layers n_dense-1 .. 0 given dZ[n_dense-1]: weight / bias gradients into G
-// (when want_wgrad) and dZ[l-1] = (dZ[l] W_l^T) * act'(Z[l-1]).  For l = 0 the input gradient is
-// produced only when in_z != null: dIn = (dZ[0] W_0^T) * act'(in_z) with activation in_act.
+// Backward through dense layers n_dense-1 .. 0 given dZ[n_dense-1]: dZ[l-1] = (dZ[l] W_l^T) * act'(Z[l-1])
+// and, when want_wgrad, the weight / bias gradients.  With `fused` null the weight gradient goes to G;
+// otherwise the optimiser described by *fused is applied in the weight-gradient GEMM's epilogue (the
+// bias gradient still goes to G).  The input gradient of a layer is always taken BEFORE its weight
+// gradient, because the fused epilogue rewrites the bf16 weights that the input gradient reads.
+// For l = 0 the input gradient is produced only when in_z != null: dIn = (dZ[0] W_0^T) * act'(in_z)
+// with activation in_act.
 inline pbt_status backward(pbt_handle* h, const Net& net, int n_dense, int rows, bf16_t* const* A, bf16_t* const* Z, bf16_t* const* dZ,
-                    bool want_wgrad, const bf16_t* in_z, bf16_t* in_dz, int in_act, hipStream_t s) {
+                           bool want_wgrad, const OptArgs* fused, const bf16_t* in_z, bf16_t* in_dz, int in_act, hipStream_t s) {
   const pbt_config& c = h->cfg;
   const Plan& p = h->plan;
   const int64_t S = p.lay.stride;
@@ -48,20 +52,44 @@ inline pbt_status backward(pbt_handle* h, const Net& net, int n_dense, int rows,
   float* G = h->sc<float>(p.o_grad);
   for (int l = n_dense - 1; l >= 0; --l) {
     const int K = net.dims[l], N = net.dims[l + 1];
-    if (want_wgrad) {
-      GemmOperands wg{A[l], K, (int64_t)rows * K, true, dZ[l], N, (int64_t)rows * N, false, K, N, rows, c.P};
-      PBT_LAUNCH(h, PBT_K_GEMM_WGRAD, s, gemm_store_f32(wg, G + p.lay.w_off[net.first + l], N, S, s));
-      PBT_LAUNCH(h, PBT_K_BIAS_GRAD, s, bias_grad(dZ[l], c.P, rows, N, N, G + p.lay.b_off[net.first + l], S, s));
-    }
     const bf16_t* zprev = l > 0 ? Z[l - 1] : in_z;
     bf16_t* dzprev = l > 0 ? dZ[l - 1] : in_dz;
     if (zprev) {
       GemmOperands dg{dZ[l], N, (int64_t)rows * N, false, W16 + p.lay.w_off[net.first + l], N, S, true, rows, K, N, c.P};
       PBT_LAUNCH(h, PBT_K_GEMM_DGRAD, s, gemm_dgrad_act(dg, zprev, dzprev, K, (int64_t)rows * K, l > 0 ? net.hidden_act : in_act, s));
     }
+    if (want_wgrad) {
+      GemmOperands wg{A[l], K, (int64_t)rows * K, true, dZ[l], N, (int64_t)rows * N, false, K, N, rows, c.P};
+      PBT_LAUNCH(h, PBT_K_BIAS_GRAD, s, bias_grad(dZ[l], c.P, rows, N, N, G + p.lay.b_off[net.first + l], S, s));
+      if (fused)
+        PBT_LAUNCH(h, PBT_K_GEMM_WGRAD, s, gemm_wgrad_optimizer(wg, *fused, p.lay.w_off[net.first + l], N, s));
+      else
+        PBT_LAUNCH(h, PBT_K_GEMM_WGRAD, s, gemm_store_f32(wg, G + p.lay.w_off[net.first + l], N, S, s));
+    }
   }
   return PBT_OK;
 }
 
+// The streaming optimiser on what the fused weight-gradient epilogues did not cover: of layers
+// first .. first+n-1 (layout indices) the first n_fused had their matrices updated in the GEMM; this
+// updates their biases and everything of the remaining layers, up to range_end, merging
+// neighbouring ranges into one launch.
+inline pbt_status optimizer_rest(pbt_handle* h, OptArgs oa, int first, int n, int n_fused, int64_t range_end, hipStream_t s) {
+  const Plan& p = h->plan;
+  int64_t begin = -1, end = -1;
+  for (int l = first; l < first + n; ++l) {
+    const int64_t next = l + 1 < first + n ? p.lay.w_off[l + 1] : range_end;
+    const int64_t b = l < first + n_fused ? p.lay.b_off[l] : p.lay.w_off[l];
+    if (begin >= 0 && b == end) {
+      end = next;
+    } else {
+      if (begin >= 0) { oa.begin = begin; oa.count = end - begin; PBT_LAUNCH(h, PBT_K_OPTIMIZER, s, optimizer_step(oa, s)); }
+      begin = b;
+      end = next;
+    }
+  }
+  if (begin >= 0) { oa.begin = begin; oa.count = end - begin; PBT_LAUNCH(h, PBT_K_OPTIMIZER, s, optimizer_step(oa, s)); }
+  return PBT_OK;
+}
 
 }  // namespace pbt

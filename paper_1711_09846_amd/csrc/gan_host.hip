@@ -39,14 +39,12 @@ Bufs bufs_of(pbt_handle* h) {
   return b;
 }
 
-pbt_status adam_range(pbt_handle* h, int64_t begin, int64_t count, int col_lr, hipStream_t s) {
+OptArgs adam_args(pbt_handle* h, int64_t begin, int64_t count, int col_lr) {
   const pbt_config& c = h->cfg;
   const Plan& p = h->plan;
-  OptArgs oa{h->st<float>(p.o_w32), h->st<float>(p.o_opt0), h->st<float>(p.o_opt1), h->st<bf16_t>(p.o_w16), h->sc<float>(p.o_grad),
+  return OptArgs{h->st<float>(p.o_w32), h->st<float>(p.o_opt0), h->st<float>(p.o_opt1), h->st<bf16_t>(p.o_w16), h->sc<float>(p.o_grad),
              begin, count, h->st<float>(p.o_hyper), h->st<int32_t>(p.o_t), p.lay.stride, c.P, c.n_hyper, PBT_OPT_ADAM, col_lr, -1, -1,
              c.opt_const[0], c.opt_const[1], c.opt_const[2], c.opt_const[3]};
-  PBT_LAUNCH(h, PBT_K_OPTIMIZER, s, optimizer_step(oa, s));
-  return PBT_OK;
 }
 
 }  // namespace
@@ -129,8 +127,14 @@ pbt_status gan_step(pbt_handle* h, const float* train_x, uint32_t step, hipStrea
     PBT_LAUNCH(h, PBT_K_HEAD, s, bias_grad(dlogits, P, R, 1, 32, G + p.lay.b_off[head], S, s));
   }
   PBT_LAUNCH(h, PBT_K_HEAD, s, head_dgrad(dlogits, W16 + p.lay.w_off[head], S, b.dZ[Ld - 2], b.ddZ[Ld - 2], P, R, Kh, 1, dnet.hidden_act, s));
-  if ((st = backward(h, dnet, Ld - 1, R, b.dA, b.dZ, b.ddZ, true, nullptr, nullptr, 0, s)) != PBT_OK) return st;
-  if ((st = adam_range(h, g.d_begin, g.d_count, g.col_lr_d, s)) != PBT_OK) return st;
+  const bool fused = c.fuse_optimizer != 0;
+  const OptArgs oa_d = adam_args(h, g.d_begin, g.d_count, g.col_lr_d), oa_g = adam_args(h, 0, g.g_count, g.col_lr_g);
+  if ((st = backward(h, dnet, Ld - 1, R, b.dA, b.dZ, b.ddZ, true, fused ? &oa_d : nullptr, nullptr, nullptr, 0, s)) != PBT_OK) return st;
+  if (fused) {
+    if ((st = optimizer_rest(h, oa_d, c.n_layers, Ld, Ld - 1, S, s)) != PBT_OK) return st;
+  } else {
+    PBT_LAUNCH(h, PBT_K_OPTIMIZER, s, optimizer_step(oa_d, s));
+  }
 
   // ---- generator update: B fresh generated rows through the updated discriminator
   PBT_LAUNCH(h, PBT_K_FETCH, s, latent_normal(b.gA[0], P, B, c.dims[0], step, 1, c.seed, s));
@@ -146,10 +150,12 @@ pbt_status gan_step(pbt_handle* h, const float* train_x, uint32_t step, hipStrea
     PBT_LAUNCH(h, PBT_K_HEAD, s, head_dgrad(dlogits, W16 + p.lay.w_off[head], S, b.dZ[Ld - 2], b.ddZ[Ld - 2], P, B, Kh, 1, dnet.hidden_act, s));
     // through the discriminator down to its input, no weight gradients; the input gradient is
     // multiplied by the derivative of the generator's output activation on the way
-    if ((st = backward(h, dnet, Ld - 1, B, dA, b.dZ, b.ddZ, false, b.gZ[gnet.L - 1], b.gdZ[gnet.L - 1], gnet.out_act, s)) != PBT_OK) return st;
+    if ((st = backward(h, dnet, Ld - 1, B, dA, b.dZ, b.ddZ, false, nullptr, b.gZ[gnet.L - 1], b.gdZ[gnet.L - 1], gnet.out_act, s)) != PBT_OK) return st;
   }
-  if ((st = backward(h, gnet, gnet.L, B, b.gA, b.gZ, b.gdZ, true, nullptr, nullptr, 0, s)) != PBT_OK) return st;
-  return adam_range(h, 0, g.g_count, g.col_lr_g, s);
+  if ((st = backward(h, gnet, gnet.L, B, b.gA, b.gZ, b.gdZ, true, fused ? &oa_g : nullptr, nullptr, nullptr, 0, s)) != PBT_OK) return st;
+  if (fused) return optimizer_rest(h, oa_g, 0, gnet.L, gnet.L, g.g_count, s);
+  PBT_LAUNCH(h, PBT_K_OPTIMIZER, s, optimizer_step(oa_g, s));
+  return PBT_OK;
 }
 
 pbt_status gan_eval(pbt_handle* h, const float* eval_x, hipStream_t s) {

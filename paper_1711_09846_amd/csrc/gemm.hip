@@ -24,6 +24,13 @@ hipError_t gemm_dgrad_act(const GemmOperands& o, const bf16_t* Zprev, bf16_t* dZ
   return run(o, EpiDgradAct{Zprev, dZ, ld, so, act}, s);
 }
 
+hipError_t gemm_wgrad_optimizer(const GemmOperands& o, const OptArgs& a, int64_t off, int64_t ldc, hipStream_t s) {
+  const OptHyper hy{a.H, a.t, a.n_hyper, a.col_lr, a.col_beta1, a.col_wd, a.c0, a.c1, a.c2, a.c3};
+  if (a.optimizer == OPT_SGD_MOMENTUM) return run(o, EpiOptimizer<OPT_SGD_MOMENTUM>{a.W32, a.S0, a.S1, a.W16, a.stride, off, ldc, hy, {}}, s);
+  if (a.optimizer == OPT_ADAM) return run(o, EpiOptimizer<OPT_ADAM>{a.W32, a.S0, a.S1, a.W16, a.stride, off, ldc, hy, {}}, s);
+  return run(o, EpiOptimizer<OPT_RMSPROP>{a.W32, a.S0, a.S1, a.W16, a.stride, off, ldc, hy, {}}, s);
+}
+
 hipError_t gemm_rbf_sum(const GemmOperands& o, const float* na, int64_t sna, const float* nb, int64_t snb, float inv2d,
                         float* partial, int* tiles, hipStream_t s) {
   // tile count as launch_gemm_bf16 will choose it (the caller sizes `partial` with gemm_rbf_tiles)

@@ -19,6 +19,7 @@
 // bias + activation (forward) or the activation derivative (input gradient).
 #pragma once
 #include "common.h"
+#include "optim_math.h"
 
 namespace pbt {
 
@@ -247,6 +248,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs g, Epi
   constexpr int STRIP = BM / WM, CPITCH = BN + 4;
   static_assert(STRIP * CPITCH * 4 <= (BM + BN) * GEMM_PITCH * 2, "C strip must fit the slab LDS");
   float* const Cs = reinterpret_cast<float*>(smem);
+  epi.begin(member);
 #pragma unroll 1
   for (int strip = 0; strip < WM; ++strip) {
     __syncthreads();  // slabs (or the previous strip) fully consumed
@@ -309,6 +311,7 @@ __device__ __forceinline__ void store_bf16_run(bf16_t* dst, const float* v, int 
 
 struct EpiStoreF32 {
   static constexpr bool HAS_FINISH = false;
+  __device__ __forceinline__ void begin(int) {}
   float* C;
   int64_t ldc, sc;
   __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) const {
@@ -324,6 +327,7 @@ struct EpiStoreF32 {
 
 struct EpiStoreBF16 {
   static constexpr bool HAS_FINISH = false;
+  __device__ __forceinline__ void begin(int) {}
   bf16_t* C;
   int64_t ldc, sc;
   __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) const {
@@ -334,6 +338,7 @@ struct EpiStoreBF16 {
 // Forward layer: z = acc + b[n]; stores z (for the backward pass, may be null) and act(z), both bf16.
 struct EpiBiasAct {
   static constexpr bool HAS_FINISH = false;
+  __device__ __forceinline__ void begin(int) {}
   const float* bias;  // + member * sbias + n
   int64_t sbias;
   bf16_t* Z;
@@ -357,6 +362,7 @@ struct EpiBiasAct {
 // Input gradient: dz_prev = acc * act'(z_prev), bf16.
 struct EpiDgradAct {
   static constexpr bool HAS_FINISH = false;
+  __device__ __forceinline__ void begin(int) {}
   const bf16_t* Zprev;
   bf16_t* dZ;
   int64_t ld, so;
@@ -372,6 +378,60 @@ struct EpiDgradAct {
 #pragma unroll
     for (int e = 0; e < 8; ++e) d[e] = v[e] * act_bwd(z[e], act);
     store_bf16_run(dZ + o, d, count);
+  }
+};
+
+// Weight gradient with the optimiser applied in place: v = dW[m][n .. n+7] never goes to memory;
+// the run of theta, its optimiser state and the bf16 shadow is read, updated and written back
+// (16-byte streaming accesses).  Saves writing and re-reading the gradient (8 of 34 bytes per
+// parameter and step).  The layer's input-gradient GEMM must already have read the bf16 shadow.
+template <int OPT>
+struct EpiOptimizer {
+  static constexpr bool HAS_FINISH = false;
+  float* W32; float* S0; float* S1; bf16_t* W16;
+  int64_t stride, off, ldc;   // member stride, offset of the matrix in the member's vector, row pitch
+  OptHyper hy;
+  OptScalars sc;
+  __device__ __forceinline__ void begin(int member) { sc = opt_scalars<OPT>(hy, member); }
+  __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) {
+    const int64_t o = (int64_t)member * stride + off + (int64_t)m * ldc + n;
+    float w[8], s0[8], s1[8];
+    const bool vec = count == 8 && (o & 3) == 0;
+    if (vec) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const float4 a = stream_load(W32 + o + 4 * h), b = stream_load(S0 + o + 4 * h);
+        w[4 * h] = a.x; w[4 * h + 1] = a.y; w[4 * h + 2] = a.z; w[4 * h + 3] = a.w;
+        s0[4 * h] = b.x; s0[4 * h + 1] = b.y; s0[4 * h + 2] = b.z; s0[4 * h + 3] = b.w;
+        if (OPT == OPT_ADAM) {
+          const float4 c = stream_load(S1 + o + 4 * h);
+          s1[4 * h] = c.x; s1[4 * h + 1] = c.y; s1[4 * h + 2] = c.z; s1[4 * h + 3] = c.w;
+        }
+      }
+    } else {
+      for (int e = 0; e < 8; ++e) {
+        w[e] = e < count ? W32[o + e] : 0.f;
+        s0[e] = e < count ? S0[o + e] : 0.f;
+        s1[e] = (OPT == OPT_ADAM && e < count) ? S1[o + e] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) opt_update<OPT>(w[e], e < count ? v[e] : 0.f, s0[e], s1[e], sc, hy);
+    if (vec) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        stream_store(make_float4(w[4 * h], w[4 * h + 1], w[4 * h + 2], w[4 * h + 3]), W32 + o + 4 * h);
+        stream_store(make_float4(s0[4 * h], s0[4 * h + 1], s0[4 * h + 2], s0[4 * h + 3]), S0 + o + 4 * h);
+        if (OPT == OPT_ADAM) stream_store(make_float4(s1[4 * h], s1[4 * h + 1], s1[4 * h + 2], s1[4 * h + 3]), S1 + o + 4 * h);
+      }
+    } else {
+      for (int e = 0; e < count; ++e) {
+        W32[o + e] = w[e];
+        S0[o + e] = s0[e];
+        if (OPT == OPT_ADAM) S1[o + e] = s1[e];
+      }
+    }
+    if (W16) store_bf16_run(W16 + o, w, count);
   }
 };
 
@@ -402,6 +462,7 @@ hipError_t launch_gemm_tile(const GemmArgs& g0, bool a_m_contig, bool b_k_contig
 // order, and the tile's sum goes to partial[member][tile]; a later pass adds the tiles.
 struct EpiRbfSum {
   static constexpr bool HAS_FINISH = true;
+  __device__ __forceinline__ void begin(int) {}
   const float* na;  // squared norms of the A rows, + member * sna
   int64_t sna;
   const float* nb;

@@ -81,6 +81,9 @@ struct OptArgs {
   float c0, c1, c2, c3;           // opt_const
 };
 hipError_t optimizer_step(const OptArgs& a, hipStream_t s);
+// Weight-gradient GEMM (o) whose epilogue applies the optimiser to the matrix at offset `off` (row
+// pitch ldc) of every member's flat vector instead of storing the gradient; a.G, a.begin, a.count unused.
+hipError_t gemm_wgrad_optimizer(const GemmOperands& o, const OptArgs& a, int64_t off, int64_t ldc, hipStream_t s);
 
 // out[P][rows][d] (bf16) = standard normal latents: element e uses Philox counter
 // (c0, member, DOMAIN_LATENT + substream, e / 4); words (0,1) and (2,3) are one Box-Muller pair each

@@ -3,6 +3,7 @@
 // and the on-device exploit/explore pass (rank, truncation selection, gather-copy, perturb).
 #include "common.h"
 #include "internal.h"
+#include "optim_math.h"
 #include "philox.h"
 
 namespace pbt {
@@ -165,41 +166,15 @@ hipError_t row_reduce(const float* rowval, int64_t srow, int P, int rows, float 
 }
 
 // ---- fused per-member optimiser --------------------------------------------------------------
-// Streams a member's parameters once: reads theta, gradient and state, writes theta, state and
-// the bf16 shadow.  lr / beta1 / weight decay come from the member's row of H on the device, so
-// an explore pass changes the very next update without host involvement.
-//   SGD-momentum  v <- mu v + g;  theta <- theta - lr v
-//   Adam          m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2
-//                 theta <- theta - lr ( (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps) + wd theta )
-//   RMSProp       s <- rho s + (1-rho) g^2;  theta <- theta - lr g / sqrt(s + eps)
-
-constexpr int OPT_VEC_PER_THREAD = 1;  // float4 vectors per thread
-
-// theta, gradient and optimiser state are touched once per step: stream them past the caches
-// (nontemporal), so that the bf16 shadow, which the next step's GEMMs read, is what stays resident.
-typedef float vf4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ float4 stream_load(const float* p) {
-  const vf4_t v = __builtin_nontemporal_load(reinterpret_cast<const vf4_t*>(p));
-  return make_float4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ void stream_store(float4 x, float* p) {
-  const vf4_t v = {x.x, x.y, x.z, x.w};
-  __builtin_nontemporal_store(v, reinterpret_cast<vf4_t*>(p));
-}
+// Streams a range of every member's parameters once: reads theta, gradient and state, writes theta,
+// state and the bf16 shadow (update rules in optim_math.h).  One float4 per thread per array.
+constexpr int OPT_VEC_PER_THREAD = 1;
 
 template <int OPT>
 __global__ __launch_bounds__(256) void optimizer_kernel(OptArgs a) {
   const int i = blockIdx.y;
-  const float* __restrict__ h = a.H + (int64_t)i * a.n_hyper;
-  const float lr = h[a.col_lr];
-  float b1 = a.c0, wd = a.c3, inv_bc1 = 1.f, inv_bc2 = 1.f;
-  if (OPT == 1) {
-    if (a.col_beta1 >= 0) b1 = h[a.col_beta1];
-    if (a.col_wd >= 0) wd = h[a.col_wd];
-    const float tt = (float)a.t[i];
-    inv_bc1 = 1.f / (1.f - powf(b1, tt));
-    inv_bc2 = 1.f / (1.f - powf(a.c1, tt));
-  }
+  const OptHyper hy{a.H, a.t, a.n_hyper, a.col_lr, a.col_beta1, a.col_wd, a.c0, a.c1, a.c2, a.c3};
+  const OptScalars sc = opt_scalars<OPT>(hy, i);
   const int64_t base = (int64_t)i * a.stride + a.begin;
   const int64_t nvec = a.count / 4;
 #pragma unroll
@@ -210,36 +185,17 @@ __global__ __launch_bounds__(256) void optimizer_kernel(OptArgs a) {
     float4 w = stream_load(a.W32 + o);
     const float4 g = stream_load(a.G + o);
     float4 s0 = stream_load(a.S0 + o);
+    float4 s1 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (OPT == OPT_ADAM) s1 = stream_load(a.S1 + o);
     float* wp = reinterpret_cast<float*>(&w);
     const float* gp = reinterpret_cast<const float*>(&g);
     float* s0p = reinterpret_cast<float*>(&s0);
-    if (OPT == 0) {
+    float* s1p = reinterpret_cast<float*>(&s1);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        s0p[e] = a.c0 * s0p[e] + gp[e];
-        wp[e] = wp[e] - lr * s0p[e];
-      }
-    } else if (OPT == 1) {
-      float4 s1 = stream_load(a.S1 + o);
-      float* s1p = reinterpret_cast<float*>(&s1);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        s0p[e] = b1 * s0p[e] + (1.f - b1) * gp[e];
-        s1p[e] = a.c1 * s1p[e] + (1.f - a.c1) * gp[e] * gp[e];
-        const float mh = s0p[e] * inv_bc1;
-        const float vh = s1p[e] * inv_bc2;
-        wp[e] = wp[e] - lr * (mh / (sqrtf(vh) + a.c2) + wd * wp[e]);
-      }
-      stream_store(s1, a.S1 + o);
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        s0p[e] = a.c0 * s0p[e] + (1.f - a.c0) * gp[e] * gp[e];
-        wp[e] = wp[e] - lr * gp[e] / sqrtf(s0p[e] + a.c1);
-      }
-    }
+    for (int e = 0; e < 4; ++e) opt_update<OPT>(wp[e], gp[e], s0p[e], s1p[e], sc, hy);
     stream_store(w, a.W32 + o);
     stream_store(s0, a.S0 + o);
+    if (OPT == OPT_ADAM) stream_store(s1, a.S1 + o);
     if (a.W16) {
       uint2 pk;
       pk.x = f2bf(wp[0]) | ((uint32_t)f2bf(wp[1]) << 16);

@@ -20,13 +20,14 @@ def oracle_spec(wl, seed):
 class Pair:
     """One population on the GPU and its twin in the oracle."""
 
-    def __init__(self, wl, seed=workloads.POPULATION_SEED, init_seed=5, data=None, eval_chunk=0, ref_members=None):
+    def __init__(self, wl, seed=workloads.POPULATION_SEED, init_seed=5, data=None, eval_chunk=0, ref_members=None,
+                 fuse_optimizer=0):
         import torch
         self.torch = torch
         self.wl = wl
         self.seed = seed
         (self.train_x, self.train_y), (self.eval_x, self.eval_y) = data or workloads.classifier_data(wl)
-        self.cfg = binding.make_config(wl, seed, eval_chunk=eval_chunk)
+        self.cfg = binding.make_config(wl, seed, eval_chunk=eval_chunk, fuse_optimizer=fuse_optimizer)
         self.gpu = binding.Population(self.cfg)
         weights = workloads.initial_mlp_weights(wl.dims, wl.P, init_seed)
         H = workloads.initial_hypers(wl, init_seed + 1)
@@ -121,12 +122,12 @@ class Pair:
 class GanPair:
     """A GAN population on the GPU and its oracle twin (all members or a sample)."""
 
-    def __init__(self, wl, seed=workloads.POPULATION_SEED, init_seed=5, ref_members=None):
+    def __init__(self, wl, seed=workloads.POPULATION_SEED, init_seed=5, ref_members=None, fuse_optimizer=0):
         import torch
         from oracle import gan as og
         self.og, self.wl, self.seed = og, wl, seed
         self.train_x, self.eval_x = workloads.gan_data(wl)
-        self.cfg = binding.make_config(wl, seed)
+        self.cfg = binding.make_config(wl, seed, fuse_optimizer=fuse_optimizer)
         self.gpu = binding.Population(self.cfg)
         weights = workloads.initial_gan_weights(wl, wl.P, init_seed)
         H = workloads.initial_hypers(wl, init_seed + 1)
@@ -190,12 +191,12 @@ class GanPair:
 class A2CPair:
     """An actor-critic population on the GPU and its oracle twin (all members or a sample)."""
 
-    def __init__(self, wl, seed=workloads.POPULATION_SEED, init_seed=5, ref_members=None):
+    def __init__(self, wl, seed=workloads.POPULATION_SEED, init_seed=5, ref_members=None, fuse_optimizer=0):
         import torch
         from oracle import a2c as oa
         self.oa, self.wl, self.seed = oa, wl, seed
         self.obs, self.actions, self.rewards = workloads.trajectory_pool(wl)
-        self.cfg = binding.make_config(wl, seed)
+        self.cfg = binding.make_config(wl, seed, fuse_optimizer=fuse_optimizer)
         self.gpu = binding.Population(self.cfg)
         weights = workloads.initial_mlp_weights(wl.dims, wl.P, init_seed)
         H = workloads.initial_hypers(wl, init_seed + 1)
