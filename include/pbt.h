@@ -62,13 +62,14 @@ typedef enum {
   PBT_EUNSUPPORTED = -5  /* valid request that this build has no kernel for */
 } pbt_status;
 
-enum { PBT_WL_CLASSIFIER = 1, PBT_WL_GAN = 3, PBT_WL_A2C = 5 }; /* workload families */
+enum { PBT_WL_CLASSIFIER = 1, PBT_WL_GAN = 3, PBT_WL_TRANSFORMER = 4, PBT_WL_A2C = 5 }; /* workload families */
 enum { PBT_ACT_NONE = 0, PBT_ACT_RELU = 1, PBT_ACT_GELU = 2, PBT_ACT_LEAKY_RELU = 3, PBT_ACT_TANH = 4 };
 enum { PBT_OPT_SGD_MOMENTUM = 0, PBT_OPT_ADAM = 1, PBT_OPT_RMSPROP = 2 };
 enum { PBT_DTYPE_FP32 = 0, PBT_DTYPE_BF16 = 1 };      /* BF16 = bf16 operands, fp32 accumulate, fp32 master weights */
 enum { PBT_ROLE_LR = 0, PBT_ROLE_BETA1 = 1, PBT_ROLE_WD = 2, /* meaning of a hyperparameter column */
        PBT_ROLE_LR_G = 3, PBT_ROLE_LR_D = 4,                  /* GAN: generator / discriminator learning rate */
-       PBT_ROLE_ENTROPY_COST = 5 };                           /* actor-critic: weight of the entropy bonus */
+       PBT_ROLE_ENTROPY_COST = 5,                             /* actor-critic: weight of the entropy bonus */
+       PBT_ROLE_DROPOUT = 6, PBT_ROLE_LABEL_SMOOTH = 7 };     /* transformer: dropout rate, label smoothing */
 
 /* Arrays of the population store that pbt_get_state / pbt_set_state address. */
 enum {
@@ -116,6 +117,10 @@ typedef struct {
      (policy logits, then the value); `batch` trajectories of `unroll` transitions per step. */
   int32_t unroll;
   float gamma, value_cost;          /* discount; weight of the squared value error (0.5) */
+  /* PBT_WL_TRANSFORMER only: decoder-only transformer with n_layers pre-LayerNorm blocks; `batch`
+     sequences of tf_seq tokens per step (the pool rows hold tf_seq + 1 tokens: inputs and next-token
+     targets); dims[] unused. */
+  int32_t tf_vocab, tf_d_model, tf_heads, tf_d_ff, tf_seq;
   int32_t n_train, n_eval;          /* rows (classifier, GAN) or trajectories (actor-critic) of the training set; rows of the held-out set */
   int32_t eval_chunk;               /* rows of the held-out set scored per pass (bounds scratch); 0 = library picks */
   int32_t fuse_optimizer;           /* bf16 compute: 1 = apply the optimiser inside the weight-gradient GEMMs (the gradient of
@@ -125,11 +130,19 @@ typedef struct {
 } pbt_config;
 
 /* Offsets (in elements) inside one member's flat parameter vector. */
+#define PBT_MAX_SEGMENTS 96
 typedef struct {
   int64_t stride;                   /* elements per member */
   int64_t n_params;                 /* elements that are parameters (rest is padding) */
-  int64_t w_off[PBT_MAX_DIMS];      /* start of W_l */
+  int64_t w_off[PBT_MAX_DIMS];      /* start of W_l (dense-layer workloads) */
   int64_t b_off[PBT_MAX_DIMS];      /* start of b_l */
+  /* every parameter array in order of appearance (dense workloads: W_0, b_0, W_1, ...; transformer:
+     token embedding [V][d], position embedding [S][d], per block {ln1 gain, ln1 bias, Wqkv [d][3d],
+     bqkv, Wo [d][d], bo, ln2 gain, ln2 bias, W1 [d][f], b1, W2 [f][d], b2}, final gain, final bias,
+     Whead [d][V], bhead) */
+  int32_t n_seg;
+  int64_t seg_off[PBT_MAX_SEGMENTS];
+  int64_t seg_len[PBT_MAX_SEGMENTS];
 } pbt_layout;
 
 /* Sizes of the two device buffers pbt_init needs, and the parameter layout.
@@ -178,7 +191,9 @@ pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs
  * d = dims2[0], between n_eval generated rows (latents: Philox domain 6 + 2, step index 0) and the
  * n_eval held-out rows; d_inputs = {eval_x float[n_eval][dims2[0]]}.
  * PBT_WL_A2C (Section 4.1.1, Eval): the mean of the member's last (up to) 10 unroll returns, -inf
- * before the first step; n_inputs = 0. */
+ * before the first step; n_inputs = 0.
+ * PBT_WL_TRANSFORMER: minus the perplexity exp(mean next-token cross-entropy) over the n_eval
+ * held-out sequences, no dropout, no smoothing; d_inputs = {tokens int32[n_eval][tf_seq + 1]}. */
 pbt_status pbt_eval(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, void* hip_stream);
 
 /* Section 4.1.1, Exploit (b) + Explore (a), for the whole population at once

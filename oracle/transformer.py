@@ -24,7 +24,11 @@ token sequences:
 Dropout masks come from Philox: element i of site s keeps its value iff word
 i % 4 of counter (step, member, DOMAIN_DROPOUT + s, i // 4) is >= floor(p * 2^32)
 (capped at 2^32 - 1), p the float32 rate widened exactly; kept values are scaled
-by 1/(1-p).  Sites are numbered 4*layer + {0: attention probabilities [B][H][S][S],
+by the float32 number nearest to 1/(1-p) (the factor is a device-resident
+float32 like the rate it comes from; naming its precision matters because
+bf16 values times a factor like 10/7 or 4/3 often land within 1e-8 of the
+midpoint between two bf16 values, where the last bits of the factor decide
+the rounding).  Sites are numbered 4*layer + {0: attention probabilities [B][H][S][S],
 1: attention output [B*S][d], 2: feed-forward hidden [B*S][f], 3: feed-forward
 output [B*S][d]}.
 
@@ -113,7 +117,7 @@ class _Drop:
         self.spec, self.step, self.member = spec, step, member
         self.p32 = np.float32(p32)
         self.active = active and float(p32) > 0.0
-        self.scale = 1.0 / (1.0 - float(self.p32)) if self.active else 1.0
+        self.scale = float(np.float32(1.0 / (1.0 - float(self.p32)))) if self.active else 1.0
 
     def mask(self, site, shape):
         if not self.active:
@@ -229,7 +233,8 @@ def loss_and_grads(spec, m, seqs, step, member, train=True):
     return loss, [G[name] for name, _ in spec.param_shapes()]
 
 
-def step(spec, m, i, s, pool):
+def step(spec, m, i, s, pool, want_grads=False):
+    """One update of member i at step s; returns the loss (and the gradients it used, if asked)."""
     idx = philox.bounded(philox.words(spec.seed, s, i, philox.DOMAIN_BATCH, np.arange(spec.B))[..., 0], len(pool))
     loss, grads = loss_and_grads(spec, m, pool[idx], s, i)
     lr = m.h[spec.roles.index(ROLE_LR)]
@@ -237,7 +242,7 @@ def step(spec, m, i, s, pool):
     for j, g in enumerate(grads):
         m.theta[j], m.opt["s0"][j], m.opt["s1"][j] = optim.adam(
             m.theta[j], g, m.opt["s0"][j], m.opt["s1"][j], m.t, lr, spec.beta1, spec.beta2, spec.eps, 0.0)
-    return loss
+    return (loss, grads) if want_grads else loss
 
 
 def evaluate(spec, m, eval_seqs, chunk=64):

@@ -14,7 +14,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpbt.so")
 
-PBT_MAX_DIMS, PBT_MAX_HYPER = 16, 8
+PBT_MAX_DIMS, PBT_MAX_HYPER, PBT_MAX_SEGMENTS = 16, 8, 96
 (ARR_W32, ARR_OPT0, ARR_OPT1, ARR_W16, ARR_GRAD, ARR_HYPER, ARR_SCORE, ARR_LOSS, ARR_T, ARR_ORDER, ARR_DONOR,
  ARR_PARENT, ARR_HIST) = range(13)
 _ARR_DTYPE = {ARR_W32: np.float32, ARR_OPT0: np.float32, ARR_OPT1: np.float32, ARR_W16: np.uint16,
@@ -35,13 +35,15 @@ class PbtConfig(C.Structure):
                 ("hyper_max", C.c_float * PBT_MAX_HYPER), ("n_trunc", C.c_int32), ("perturb_lo", C.c_float),
                 ("perturb_hi", C.c_float), ("opt_const", C.c_float * 4), ("act_out", C.c_int32),
                 ("n_layers2", C.c_int32), ("dims2", C.c_int32 * PBT_MAX_DIMS), ("act2", C.c_int32), ("unroll", C.c_int32),
-                ("gamma", C.c_float), ("value_cost", C.c_float), ("n_train", C.c_int32),
+                ("gamma", C.c_float), ("value_cost", C.c_float), ("tf_vocab", C.c_int32), ("tf_d_model", C.c_int32),
+                ("tf_heads", C.c_int32), ("tf_d_ff", C.c_int32), ("tf_seq", C.c_int32), ("n_train", C.c_int32),
                 ("n_eval", C.c_int32), ("eval_chunk", C.c_int32), ("fuse_optimizer", C.c_int32), ("seed", C.c_uint64)]
 
 
 class PbtLayout(C.Structure):
     _fields_ = [("stride", C.c_int64), ("n_params", C.c_int64), ("w_off", C.c_int64 * PBT_MAX_DIMS),
-                ("b_off", C.c_int64 * PBT_MAX_DIMS)]
+                ("b_off", C.c_int64 * PBT_MAX_DIMS), ("n_seg", C.c_int32), ("seg_off", C.c_int64 * PBT_MAX_SEGMENTS),
+                ("seg_len", C.c_int64 * PBT_MAX_SEGMENTS)]
 
 
 class PbtPrior(C.Structure):
@@ -93,9 +95,13 @@ def make_config(wl, seed, P=None, n_trunc=None, eval_chunk=0, fuse_optimizer=0):
     c.workload = wl.kind
     c.P = wl.P if P is None else P
     c.batch = wl.batch
-    c.n_layers = len(wl.dims) - 1
-    for k, d in enumerate(wl.dims):
-        c.dims[k] = d
+    if wl.kind == 4:                                    # transformer: n_layers counts blocks
+        c.n_layers = wl.n_blocks
+        c.tf_vocab, c.tf_d_model, c.tf_heads, c.tf_d_ff, c.tf_seq = wl.vocab, wl.d_model, wl.heads, wl.d_ff, wl.seq
+    else:
+        c.n_layers = len(wl.dims) - 1
+        for k, d in enumerate(wl.dims):
+            c.dims[k] = d
     c.act, c.optimizer, c.compute_dtype = wl.act, wl.optimizer, wl.dtype
     c.n_hyper = len(wl.roles)
     for k, r in enumerate(wl.roles):
@@ -139,6 +145,21 @@ def pack_params(lay, layers):
         flat[lay.w_off[l]:lay.w_off[l] + W.size] = np.asarray(W, dtype=np.float32).ravel()
         flat[lay.b_off[l]:lay.b_off[l] + b.size] = np.asarray(b, dtype=np.float32).ravel()
     return flat
+
+
+def pack_segments(lay, arrays):
+    """Parameter arrays in layout order -> flat float32 vector of one member (padding = 0)."""
+    assert len(arrays) == lay.n_seg
+    flat = np.zeros(lay.stride, dtype=np.float32)
+    for j, a in enumerate(arrays):
+        assert a.size == lay.seg_len[j]
+        flat[lay.seg_off[j]:lay.seg_off[j] + a.size] = np.asarray(a, dtype=np.float32).ravel()
+    return flat
+
+
+def unpack_segments(lay, shapes, flat):
+    """Inverse of pack_segments; shapes in layout order."""
+    return [np.array(flat[lay.seg_off[j]:lay.seg_off[j] + int(np.prod(sh))]).reshape(sh) for j, sh in enumerate(shapes)]
 
 
 def unpack_params(lay, dims, flat):

@@ -11,7 +11,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpbt.so")
-SOURCES = ["abi.hip", "gemm.hip", "kernels.hip", "fused_small.hip", "head.hip", "gan_host.hip", "a2c_host.hip"]
+SOURCES = ["abi.hip", "gemm.hip", "kernels.hip", "fused_small.hip", "head.hip", "gan_host.hip", "a2c_host.hip", "transformer_kernels.hip", "transformer_host.hip"]
 # -packed-fp32-ops off: scalar float code must not be turned into packed FP32 instructions.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -35,7 +35,7 @@ def _compile(src):
 
 
 def build_library(verbose=True):
-    with ThreadPoolExecutor(max_workers=7) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         results = list(ex.map(_compile, SOURCES))
     for obj, err in results:
         if verbose and err.strip():

@@ -33,14 +33,15 @@ namespace {
 
 pbt_status check_config(const pbt_config* c, Plan* pl) {
   if (!c) return fail(nullptr, PBT_EINVAL, "config is NULL");
-  if (c->workload != PBT_WL_CLASSIFIER && c->workload != PBT_WL_GAN && c->workload != PBT_WL_A2C)
+  if (c->workload != PBT_WL_CLASSIFIER && c->workload != PBT_WL_GAN && c->workload != PBT_WL_A2C && c->workload != PBT_WL_TRANSFORMER)
     return fail(nullptr, PBT_EUNSUPPORTED, "workload %d not built", c->workload);
   const bool gan = c->workload == PBT_WL_GAN;
+  const bool tf = c->workload == PBT_WL_TRANSFORMER;
   const bool a2c = c->workload == PBT_WL_A2C;
   if (c->P < 1 || c->P > PBT_MAX_P) return fail(nullptr, PBT_EINVAL, "P = %d outside 1..%d", c->P, PBT_MAX_P);
   if (c->batch < 1) return fail(nullptr, PBT_EINVAL, "batch must be positive");
   if (c->n_layers < 1 || c->n_layers >= PBT_MAX_DIMS) return fail(nullptr, PBT_EINVAL, "n_layers = %d outside 1..%d", c->n_layers, PBT_MAX_DIMS - 1);
-  for (int l = 0; l <= c->n_layers; ++l)
+  for (int l = 0; l <= c->n_layers && !tf; ++l)
     if (c->dims[l] < 1) return fail(nullptr, PBT_EINVAL, "dims[%d] must be positive", l);
   if (c->act < PBT_ACT_NONE || c->act > PBT_ACT_TANH) return fail(nullptr, PBT_EINVAL, "unknown activation %d", c->act);
   if (c->optimizer < PBT_OPT_SGD_MOMENTUM || c->optimizer > PBT_OPT_RMSPROP) return fail(nullptr, PBT_EINVAL, "unknown optimizer %d", c->optimizer);
@@ -48,8 +49,9 @@ pbt_status check_config(const pbt_config* c, Plan* pl) {
   if (c->n_hyper < 1 || c->n_hyper > PBT_MAX_HYPER) return fail(nullptr, PBT_EINVAL, "n_hyper = %d outside 1..%d", c->n_hyper, PBT_MAX_HYPER);
   if (c->n_trunc < 0 || 2 * (int64_t)c->n_trunc > c->P) return fail(nullptr, PBT_EINVAL, "need 0 <= 2*n_trunc <= P (top and bottom sets must not overlap)");
   if (c->n_train < 1 || c->n_eval < 1) return fail(nullptr, PBT_EINVAL, "n_train and n_eval must be positive");
-  if (!gan && c->dims[c->n_layers] > 32) return fail(nullptr, PBT_EUNSUPPORTED, "more than 32 outputs in the last layer");
+  if (!gan && !tf && c->dims[c->n_layers] > 32) return fail(nullptr, PBT_EUNSUPPORTED, "more than 32 outputs in the last layer");
   pl->a2c.col_ent = -1;
+  pl->tf.col_drop = pl->tf.col_ls = -1;
   pl->col_lr = pl->col_beta1 = pl->col_wd = -1;
   pl->gan.col_lr_g = pl->gan.col_lr_d = -1;
   for (int k = 0; k < c->n_hyper; ++k) {
@@ -59,6 +61,8 @@ pbt_status check_config(const pbt_config* c, Plan* pl) {
     else if (c->hyper_role[k] == PBT_ROLE_LR_G) pl->gan.col_lr_g = k;
     else if (c->hyper_role[k] == PBT_ROLE_LR_D) pl->gan.col_lr_d = k;
     else if (c->hyper_role[k] == PBT_ROLE_ENTROPY_COST) pl->a2c.col_ent = k;
+    else if (c->hyper_role[k] == PBT_ROLE_DROPOUT) pl->tf.col_drop = k;
+    else if (c->hyper_role[k] == PBT_ROLE_LABEL_SMOOTH) pl->tf.col_ls = k;
     else return fail(nullptr, PBT_EINVAL, "unknown hyper_role[%d] = %d", k, c->hyper_role[k]);
     if (std::isnan(c->hyper_max[k])) return fail(nullptr, PBT_EINVAL, "hyper_max[%d] is NaN", k);
   }
@@ -68,6 +72,12 @@ pbt_status check_config(const pbt_config* c, Plan* pl) {
   }
   if (pl->gan.col_lr_g >= 0 || pl->gan.col_lr_d >= 0) return fail(nullptr, PBT_EINVAL, "generator / discriminator learning-rate columns need the GAN workload");
   if (pl->col_lr < 0) return fail(nullptr, PBT_EINVAL, "no hyperparameter column has the learning-rate role");
+  if (!tf && (pl->tf.col_drop >= 0 || pl->tf.col_ls >= 0)) return fail(nullptr, PBT_EINVAL, "dropout / label-smoothing columns need the transformer workload");
+  if (tf) {
+    // a rate of 1 would drop everything and divide by zero; explore clamps at hyper_max
+    if (pl->tf.col_drop >= 0 && !(c->hyper_max[pl->tf.col_drop] < 1.f)) return fail(nullptr, PBT_EINVAL, "hyper_max of the dropout column must be below 1");
+    if (pl->tf.col_ls >= 0 && !(c->hyper_max[pl->tf.col_ls] < 1.f)) return fail(nullptr, PBT_EINVAL, "hyper_max of the label-smoothing column must be below 1");
+  }
   if (a2c != (pl->a2c.col_ent >= 0)) return fail(nullptr, PBT_EINVAL, "an entropy-cost column goes with the actor-critic workload, and only with it");
   if (c->optimizer != PBT_OPT_ADAM && (pl->col_beta1 >= 0 || pl->col_wd >= 0))
     return fail(nullptr, PBT_EINVAL, "beta1 / weight-decay columns need the Adam optimizer");
@@ -80,6 +90,7 @@ pbt_status make_plan(const pbt_config* c, Plan* pl) {
   const int L = c->n_layers;
   const int64_t P = c->P, B = c->batch;
   const bool gan = c->workload == PBT_WL_GAN;
+  const bool tf = c->workload == PBT_WL_TRANSFORMER;
   // parameter layout (GAN: generator layers, then discriminator layers)
   pbt_layout& lay = pl->lay;
   std::memset(&lay, 0, sizeof lay);
@@ -91,16 +102,25 @@ pbt_status make_plan(const pbt_config* c, Plan* pl) {
     if (c->n_layers2 < 1 || L + c->n_layers2 >= PBT_MAX_DIMS) return fail(nullptr, PBT_EINVAL, "generator + discriminator layers must number 2..%d", PBT_MAX_DIMS - 1);
     for (int l = 0; l < c->n_layers2; ++l) { all_dims[n_all][0] = c->dims2[l]; all_dims[n_all++][1] = c->dims2[l + 1]; }
   }
+  if (tf) n_all = 0;
   for (int l = 0; l < n_all; ++l) {
     lay.w_off[l] = off;
+    lay.seg_off[lay.n_seg] = off;
+    lay.seg_len[lay.n_seg++] = (int64_t)all_dims[l][0] * all_dims[l][1];
     off = round_up(off + (int64_t)all_dims[l][0] * all_dims[l][1], SEG_ALIGN);
     lay.b_off[l] = off;
+    lay.seg_off[lay.n_seg] = off;
+    lay.seg_len[lay.n_seg++] = all_dims[l][1];
     off = round_up(off + all_dims[l][1], SEG_ALIGN);
     n_params += (int64_t)all_dims[l][0] * all_dims[l][1] + all_dims[l][1];
     if (gan && l == L - 1) pl->gan.g_count = off;
   }
   lay.stride = round_up(off, STRIDE_ALIGN);
   lay.n_params = n_params;
+  if (tf) {
+    pbt_status tst = tf_layout(c, pl);
+    if (tst != PBT_OK) return tst;
+  }
   const bool bf16 = c->compute_dtype == PBT_DTYPE_BF16;
   const bool adam = c->optimizer == PBT_OPT_ADAM;
 
@@ -132,6 +152,11 @@ pbt_status make_plan(const pbt_config* c, Plan* pl) {
     pl->gan.d_count = lay.stride - pl->gan.g_count;
     pbt_status gst = gan_check_and_plan(c, pl, &w);
     if (gst != PBT_OK) return gst;
+  } else if (tf) {
+    if (!bf16 || !adam) return fail(nullptr, PBT_EUNSUPPORTED, "the transformer workload is built for bf16 compute with Adam");
+    if (c->n_eval % c->batch) return fail(nullptr, PBT_EUNSUPPORTED, "the transformer workload needs n_eval to be a multiple of batch");
+    pbt_status tst = tf_check_and_plan(c, pl, &w);
+    if (tst != PBT_OK) return tst;
   } else if (c->workload == PBT_WL_A2C) {
     if (!bf16) return fail(nullptr, PBT_EUNSUPPORTED, "the actor-critic workload is built for bf16 compute");
     pbt_status ast = a2c_check_and_plan(c, pl, &w);
@@ -391,6 +416,8 @@ pbt_status pbt_init_population(pbt_handle* h, const pbt_prior* priors, void* hip
   if (!priors) return fail(h, PBT_EINVAL, "priors is NULL");
   const pbt_config& c = h->cfg;
   const Plan& p = h->plan;
+  if (c.workload == PBT_WL_TRANSFORMER)
+    return fail(h, PBT_EUNSUPPORTED, "device-side initialisation is not built for the transformer workload; use pbt_set_state");
   InitArgs a;
   std::memset(&a, 0, sizeof a);
   for (int k = 0; k < c.n_hyper; ++k) {
@@ -434,6 +461,15 @@ pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs
     }
     return PBT_OK;
   }
+  if (h->cfg.workload == PBT_WL_TRANSFORMER) {
+    if (!d_inputs || n_inputs != 1 || !d_inputs[0]) return fail(h, PBT_EINVAL, "transformer step needs 1 input: the token pool");
+    if (n_steps < 0 || step_index < 0 || step_index + n_steps > 0xffffffffLL) return fail(h, PBT_EINVAL, "step range outside 0..2^32-1");
+    for (int k = 0; k < n_steps; ++k) {
+      pbt_status st = tf_step(h, static_cast<const int32_t*>(d_inputs[0]), (uint32_t)(step_index + k), static_cast<hipStream_t>(hip_stream));
+      if (st != PBT_OK) return st;
+    }
+    return PBT_OK;
+  }
   if (h->cfg.workload == PBT_WL_GAN) {
     if (!d_inputs || n_inputs != 1 || !d_inputs[0]) return fail(h, PBT_EINVAL, "GAN step needs 1 input: train_x");
     if (n_steps < 0 || step_index < 0 || step_index + n_steps > 0xffffffffLL) return fail(h, PBT_EINVAL, "step range outside 0..2^32-1");
@@ -469,6 +505,10 @@ pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs
 pbt_status pbt_eval(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, void* hip_stream) {
   if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
   if (h->cfg.workload == PBT_WL_A2C) return a2c_eval(h, static_cast<hipStream_t>(hip_stream));
+  if (h->cfg.workload == PBT_WL_TRANSFORMER) {
+    if (!d_inputs || n_inputs != 1 || !d_inputs[0]) return fail(h, PBT_EINVAL, "transformer eval needs 1 input: the held-out tokens");
+    return tf_eval(h, static_cast<const int32_t*>(d_inputs[0]), static_cast<hipStream_t>(hip_stream));
+  }
   if (h->cfg.workload == PBT_WL_GAN) {
     if (!d_inputs || n_inputs != 1 || !d_inputs[0]) return fail(h, PBT_EINVAL, "GAN eval needs 1 input: eval_x");
     return gan_eval(h, static_cast<const float*>(d_inputs[0]), static_cast<hipStream_t>(hip_stream));

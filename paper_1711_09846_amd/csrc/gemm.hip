@@ -6,7 +6,8 @@ namespace pbt {
 
 template <class E>
 static hipError_t run(const GemmOperands& o, const E& e, hipStream_t s) {
-  return launch_gemm_bf16<E>(o.A, o.lda, o.sa, o.a_m_contig, o.B, o.ldb, o.sb, o.b_k_contig, o.M, o.N, o.K, o.batch, e, s);
+  return launch_gemm_bf16<E>(o.A, o.lda, o.sa, o.a_m_contig, o.B, o.ldb, o.sb, o.b_k_contig, o.M, o.N, o.K, o.batch, e, s, o.inner,
+                             o.sa_in, o.sb_in);
 }
 
 hipError_t gemm_store_f32(const GemmOperands& o, float* C, int64_t ldc, int64_t sc, hipStream_t s) {
@@ -14,6 +15,12 @@ hipError_t gemm_store_f32(const GemmOperands& o, float* C, int64_t ldc, int64_t 
 }
 hipError_t gemm_store_bf16(const GemmOperands& o, bf16_t* C, int64_t ldc, int64_t sc, hipStream_t s) {
   return run(o, EpiStoreBF16{C, ldc, sc}, s);
+}
+hipError_t gemm_store_bf16_heads(const GemmOperands& o, bf16_t* C, int64_t ldc, int64_t sc, int64_t sc_in, hipStream_t s) {
+  return run(o, EpiStoreBF16{C, ldc, sc, o.inner, sc_in}, s);
+}
+hipError_t gemm_bias_f32(const GemmOperands& o, const float* bias, int64_t sbias, float* C, int64_t ldc, int64_t sc, hipStream_t s) {
+  return run(o, EpiBiasF32{bias, sbias, C, ldc, sc}, s);
 }
 hipError_t gemm_bias_act(const GemmOperands& o, const float* bias, int64_t sbias, bf16_t* Z, bf16_t* Aout, int64_t ld,
                          int64_t so, int act, hipStream_t s) {
@@ -39,7 +46,7 @@ hipError_t gemm_rbf_sum(const GemmOperands& o, const float* na, int64_t sna, con
 }
 int gemm_rbf_tiles(int M, int N, int batch) {
   const int64_t wide = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
-  const int bn = (wide < 4 * 256 && N > 64) ? 64 : 128;
+  const int bn = ((wide < 4 * 256 && N > 64) || (N <= 64 && N > 32)) ? 64 : 128;
   return ((M + 127) / 128) * ((N + bn - 1) / bn);
 }
 

@@ -33,6 +33,10 @@ struct GemmArgs {
   int64_t ldb, sb;
   int M, N, K, batch;
   int tiles_m, tiles_n;
+  // two-level batch index (attention: outer = sequence, inner = head): the operand of batch element b
+  // starts at (b / inner) * s? + (b % inner) * s?_in
+  int inner;
+  int64_t sa_in, sb_in;
 };
 
 constexpr int GEMM_THREADS = 256;
@@ -191,8 +195,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs g, Epi
   const int member = id / g.tiles_m;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  const bf16_t* __restrict__ A = g.A + (int64_t)member * g.sa;
-  const bf16_t* __restrict__ B = g.B + (int64_t)member * g.sb;
+  const bf16_t* __restrict__ A = g.A + (int64_t)(member / g.inner) * g.sa + (int64_t)(member % g.inner) * g.sa_in;
+  const bf16_t* __restrict__ B = g.B + (int64_t)(member / g.inner) * g.sb + (int64_t)(member % g.inner) * g.sb_in;
 
   TileLoader<BM, GEMM_BK, !A_MCONTIG> la;
   TileLoader<BN, GEMM_BK, B_KCONTIG> lb;
@@ -330,8 +334,30 @@ struct EpiStoreBF16 {
   __device__ __forceinline__ void begin(int) {}
   bf16_t* C;
   int64_t ldc, sc;
+  int inner = 1;       // two-level batch index as in GemmArgs
+  int64_t sc_in = 0;
   __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) const {
-    store_bf16_run(C + (int64_t)member * sc + (int64_t)m * ldc + n, v, count);
+    store_bf16_run(C + (int64_t)(member / inner) * sc + (int64_t)(member % inner) * sc_in + (int64_t)m * ldc + n, v, count);
+  }
+};
+
+// Output layer over a large vocabulary: logits = acc + b[n], kept in float.
+struct EpiBiasF32 {
+  static constexpr bool HAS_FINISH = false;
+  __device__ __forceinline__ void begin(int) {}
+  const float* bias;
+  int64_t sbias;
+  float* C;
+  int64_t ldc, sc;
+  __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) const {
+    const float* b = bias + (int64_t)member * sbias + n;
+    float* dst = C + (int64_t)member * sc + (int64_t)m * ldc + n;
+    if (count == 8 && aligned16(dst)) {
+      *reinterpret_cast<float4*>(dst) = make_float4(v[0] + b[0], v[1] + b[1], v[2] + b[2], v[3] + b[3]);
+      *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4] + b[4], v[5] + b[5], v[6] + b[6], v[7] + b[7]);
+    } else {
+      for (int e = 0; e < count; ++e) dst[e] = v[e] + b[e];
+    }
   }
 };
 
@@ -491,14 +517,15 @@ struct EpiRbfSum {
 template <class Epilogue>
 hipError_t launch_gemm_bf16(const bf16_t* A, int64_t lda, int64_t sa, bool a_m_contig, const bf16_t* B, int64_t ldb,
                             int64_t sb, bool b_k_contig, int M, int N, int K, int batch, const Epilogue& epi,
-                            hipStream_t stream) {
+                            hipStream_t stream, int inner = 1, int64_t sa_in = 0, int64_t sb_in = 0) {
   GemmArgs g;
   g.A = A; g.lda = lda; g.sa = sa;
   g.B = B; g.ldb = ldb; g.sb = sb;
   g.M = M; g.N = N; g.K = K; g.batch = batch;
   g.tiles_m = g.tiles_n = 0;
+  g.inner = inner < 1 ? 1 : inner; g.sa_in = sa_in; g.sb_in = sb_in;
   const int64_t wide = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
-  if (wide < 4 * 256 && N > 64) return launch_gemm_tile<128, 64, 64, Epilogue>(g, a_m_contig, b_k_contig, epi, stream);
+  if ((wide < 4 * 256 && N > 64) || (N <= 64 && N > 32)) return launch_gemm_tile<128, 64, 64, Epilogue>(g, a_m_contig, b_k_contig, epi, stream);
   return launch_gemm_tile<128, 128, 64, Epilogue>(g, a_m_contig, b_k_contig, epi, stream);
 }
 

@@ -44,6 +44,19 @@ struct A2CPlan {
   size_t o_a[PBT_MAX_DIMS], o_z[PBT_MAX_DIMS], o_dz[PBT_MAX_DIMS], o_out, o_dout, o_act, o_rew;
 };
 
+struct TfBlockOff { int64_t ln1g, ln1b, wqkv, bqkv, wo, bo, ln2g, ln2b, w1, b1, w2, b2; };
+struct TfPlan {
+  int col_drop, col_ls;
+  int64_t tok, pos, lnfg, lnfb, whead, bhead;   // parameter offsets (elements)
+  TfBlockOff blk[PBT_MAX_DIMS];
+  // scratch offsets (bytes); activations are [P][batch*seq][width]
+  size_t o_tokens, o_targets, o_h[PBT_MAX_DIMS + 1], o_hmid[PBT_MAX_DIMS];
+  size_t o_mean1[PBT_MAX_DIMS], o_rstd1[PBT_MAX_DIMS], o_mean2[PBT_MAX_DIMS], o_rstd2[PBT_MAX_DIMS], o_meanf, o_rstdf;
+  size_t o_u[PBT_MAX_DIMS], o_qkv[PBT_MAX_DIMS], o_pq[PBT_MAX_DIMS], o_pd[PBT_MAX_DIMS], o_o[PBT_MAX_DIMS];
+  size_t o_u2[PBT_MAX_DIMS], o_z1[PBT_MAX_DIMS], o_fd[PBT_MAX_DIMS];
+  size_t o_score, o_tmp_d[3], o_tmp_f[2], o_dqkv, o_uf, o_logits, o_dlogits, o_rowloss, o_evalrow;
+};
+
 struct Plan {
   pbt_layout lay;
   int n_loss;
@@ -60,6 +73,7 @@ struct Plan {
   int col_lr, col_beta1, col_wd;
   GanPlan gan;
   A2CPlan a2c;
+  TfPlan tf;
 };
 
 }  // namespace pbt
@@ -111,5 +125,11 @@ pbt_status gan_eval(pbt_handle* h, const float* eval_x, hipStream_t s);
 pbt_status a2c_check_and_plan(const pbt_config* c, Plan* pl, Carver* scratch);
 pbt_status a2c_step(pbt_handle* h, const float* obs, const int32_t* actions, const float* rewards, uint32_t step, hipStream_t s);
 pbt_status a2c_eval(pbt_handle* h, hipStream_t s);
+
+// transformer_host.hip: the language-model workload (Section 4.2.1)
+pbt_status tf_layout(const pbt_config* c, Plan* pl);
+pbt_status tf_check_and_plan(const pbt_config* c, Plan* pl, Carver* scratch);
+pbt_status tf_step(pbt_handle* h, const int32_t* pool, uint32_t step, hipStream_t s);
+pbt_status tf_eval(pbt_handle* h, const int32_t* eval_tokens, hipStream_t s);
 
 }  // namespace pbt

@@ -13,9 +13,15 @@ struct GemmOperands {
   const bf16_t* A; int64_t lda, sa; bool a_m_contig;
   const bf16_t* B; int64_t ldb, sb; bool b_k_contig;
   int M, N, K, batch;
+  int inner = 1;                 // two-level batch index: element b reads A at (b / inner) * sa + (b % inner) * sa_in
+  int64_t sa_in = 0, sb_in = 0;
 };
 hipError_t gemm_store_f32(const GemmOperands& o, float* C, int64_t ldc, int64_t sc, hipStream_t s);
 hipError_t gemm_store_bf16(const GemmOperands& o, bf16_t* C, int64_t ldc, int64_t sc, hipStream_t s);
+// as gemm_store_bf16 with C of batch element b at (b / o.inner) * sc + (b % o.inner) * sc_in
+hipError_t gemm_store_bf16_heads(const GemmOperands& o, bf16_t* C, int64_t ldc, int64_t sc, int64_t sc_in, hipStream_t s);
+// C (float) = acc + bias
+hipError_t gemm_bias_f32(const GemmOperands& o, const float* bias, int64_t sbias, float* C, int64_t ldc, int64_t sc, hipStream_t s);
 // z = acc + bias; Z (may be null) <- z, Aout <- act(z); both [batch][M][ld] bf16 with batch stride so
 hipError_t gemm_bias_act(const GemmOperands& o, const float* bias, int64_t sbias, bf16_t* Z, bf16_t* Aout, int64_t ld,
                          int64_t so, int act, hipStream_t s);
@@ -97,6 +103,34 @@ hipError_t gather_rows(const float* train_x, int n_train, int d, int P, int B, i
 // score[i] = -( sxx[i] + syy[0] - 2 sxy[i] ) * inv_n2 where each s is the sum of `tiles` partials
 hipError_t mmd_combine(const float* pxx, int txx, const float* pyy, int tyy, const float* pxy, int txy, int P, float inv_n2,
                        float* score, hipStream_t s);
+
+// ---- transformer_kernels.hip ------------------------------------------------------------------
+struct DropArgs {  // where a kernel finds the member's dropout rate and the Philox counter base
+  const float* H; int n_hyper; int col;  // column of H holding the rate, -1 = no dropout
+  int active;                            // 0 = eval: keep everything
+  uint32_t c0; uint64_t seed;            // step index, Philox key
+};
+hipError_t embed_fwd(const int32_t* pool, int n_pool, int S, int B, int d, int V, int P, const bf16_t* W16, int64_t stride,
+                     int64_t tok_off, int64_t pos_off, uint32_t c0, uint64_t seed, int draw, bf16_t* h, int32_t* tokens,
+                     int32_t* targets, int32_t* t, hipStream_t s);
+hipError_t embed_bwd(const bf16_t* dh, const int32_t* tokens, int B, int S, int d, int V, int P, float* G, int64_t stride,
+                     int64_t tok_off, int64_t pos_off, hipStream_t s);
+hipError_t layernorm_fwd(const bf16_t* x, int P, int rows, int d, const float* W32, int64_t stride, int64_t g_off, int64_t b_off,
+                         bf16_t* y, float* mean, float* rstd, hipStream_t s);
+hipError_t layernorm_bwd(const bf16_t* dy, const bf16_t* x, const float* mean, const float* rstd, int P, int rows, int d,
+                         const float* W32, int64_t stride, int64_t g_off, const bf16_t* res, bf16_t* out, hipStream_t s);
+hipError_t layernorm_param_grad(const bf16_t* dy, const bf16_t* x, const float* mean, const float* rstd, int P, int rows, int d,
+                                float* G, int64_t stride, int64_t g_off, int64_t b_off, hipStream_t s);
+hipError_t softmax_fwd(const bf16_t* sc, int P, int64_t rows, int S, float scale, const DropArgs& d, int site, bf16_t* pq,
+                       bf16_t* pd, hipStream_t s);
+hipError_t softmax_bwd(const bf16_t* pq, bf16_t* dpd, int P, int64_t rows, int S, float scale, const DropArgs& d, int site,
+                       hipStream_t s);
+hipError_t dropout_apply(const bf16_t* x, const bf16_t* res, int P, int64_t per_member, const DropArgs& d, int site, bf16_t* out,
+                         hipStream_t s);
+hipError_t xent_rows(const float* logits, const int32_t* targets, int P, int rows, int V, const float* H, int n_hyper, int col_ls,
+                     int use_ls, float gscale, bf16_t* dlogits, float* rowloss, hipStream_t s);
+hipError_t perplexity_score(const float* rowloss, int P, int rows, float* score, hipStream_t s);
+hipError_t tf_scatter_rows(const float* src, int P, int rows, float* dst, int64_t dst_stride, int64_t offset, hipStream_t s);
 
 struct ExploitArgs {
   float* score; const float* score_override; float* H; int32_t* t; int32_t* order; int32_t* donor; int32_t* parent;

@@ -15,6 +15,7 @@ enum {
   DOMAIN_INIT_W = 4,
   DOMAIN_INIT_H = 5,
   DOMAIN_LATENT = 6,
+  DOMAIN_DROPOUT = 16,
 };
 
 struct u32x4 { uint32_t x, y, z, w; };

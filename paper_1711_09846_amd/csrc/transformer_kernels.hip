@@ -1,0 +1,393 @@
+// Row-wise and element-wise kernels of the transformer workload: embedding gather and its gradient,
+// LayerNorm forward / backward, causal softmax with dropout forward / backward, dropout and
+// residual updates with counter-based (Philox) masks, and the label-smoothed cross-entropy over a
+// large vocabulary.  All activations are bf16 in memory; arithmetic is fp32.
+//
+// Dropout: element e of site s (member i, step c0) keeps its value iff word e % 4 of the Philox
+// counter (c0, i, DOMAIN_DROPOUT + s, e / 4) is >= floor(p * 2^32) (capped at 2^32 - 1); kept values
+// are scaled by the float nearest to 1 / (1 - p).  p is the member's own rate, read from H on the
+// device.  Where a bf16 value times that factor (plus a bf16 residual) is rounded to bf16 again, the
+// arithmetic is done in double and rounded once: with round rates such as 0.25 or 0.3 a seventh or
+// so of such products are dyadic and a good share of the sums lie within 1e-8 (relative) of the
+// midpoint of two bf16 values, closer than fp32 can resolve.
+#include "common.h"
+#include "internal.h"
+#include "philox.h"
+
+namespace pbt {
+
+struct DropRate { uint32_t thr; float scale; };
+
+__device__ __forceinline__ DropRate drop_rate(const float* H, int n_hyper, int col, int member, int active) {
+  DropRate r{0u, 1.f};
+  if (active && col >= 0) {
+    const float p = H[(int64_t)member * n_hyper + col];
+    if (p > 0.f) {
+      const double t = floor((double)p * 4294967296.0);
+      r.thr = t >= 4294967295.0 ? 4294967295u : (uint32_t)t;
+      r.scale = (float)(1.0 / (1.0 - (double)p));
+    }
+  }
+  return r;
+}
+
+// double -> bf16 with a single round-to-nearest-even: first to float with round-to-odd (truncate
+// toward zero, then set the last bit if anything was lost), which the final rounding cannot mistake.
+__device__ __forceinline__ bf16_t d2bf(double v) {
+  float f = (float)v;
+  const double back = (double)f;
+  if (back != v) {
+    uint32_t b = __float_as_uint(f);
+    if (fabs(back) > fabs(v)) b -= 1u;  // step toward zero (f is finite and non-zero here)
+    f = __uint_as_float(b | 1u);
+  }
+  return f2bf(f);
+}
+
+// keep factors (0 or scale) of the four elements 4*blk .. 4*blk+3 of a site
+__device__ __forceinline__ void drop_factors4(const DropArgs& d, const DropRate& r, int member, int site, uint32_t blk, float* f) {
+  if (r.thr == 0u) { f[0] = f[1] = f[2] = f[3] = r.scale; return; }
+  const u32x4 w = philox4x32_10(d.c0, (uint32_t)member, (uint32_t)(DOMAIN_DROPOUT + site), blk, (uint32_t)d.seed, (uint32_t)(d.seed >> 32));
+  f[0] = w.x >= r.thr ? r.scale : 0.f;
+  f[1] = w.y >= r.thr ? r.scale : 0.f;
+  f[2] = w.z >= r.thr ? r.scale : 0.f;
+  f[3] = w.w >= r.thr ? r.scale : 0.f;
+}
+
+// tokens outside the vocabulary are mapped to its ends so that no table read leaves its array
+__device__ __forceinline__ int32_t clamp_token(int32_t tok, int V) { return tok < 0 ? 0 : tok >= V ? V - 1 : tok; }
+
+// ---- embeddings ------------------------------------------------------------------------------
+// h[i][b][s][:] = tok[token] + pos[s]; tokens are drawn here: sequence b of member i is pool row
+// floor(x * n_pool / 2^32), x from Philox domain 1; also copies the targets and bumps t.
+__global__ __launch_bounds__(64) void embed_fwd_kernel(const int32_t* __restrict__ pool, int n_pool, int S, int B, int d, int V,
+                                                       const bf16_t* __restrict__ W16, int64_t stride, int64_t tok_off,
+                                                       int64_t pos_off, uint32_t c0, uint32_t k0, uint32_t k1, int draw,
+                                                       bf16_t* __restrict__ h, int32_t* __restrict__ tokens,
+                                                       int32_t* __restrict__ targets, int32_t* __restrict__ t) {
+  const int s = blockIdx.x, b = blockIdx.y, i = blockIdx.z;
+  int64_t row = b;
+  if (draw) row = philox_bounded(philox4x32_10(c0, (uint32_t)i, DOMAIN_BATCH, (uint32_t)b, k0, k1).x, (uint32_t)n_pool);
+  const int32_t tok = clamp_token(pool[row * (S + 1) + s], V);
+  const int64_t r = ((int64_t)i * B + b) * S + s;
+  const bf16_t* __restrict__ te = W16 + (int64_t)i * stride + tok_off + (int64_t)tok * d;
+  const bf16_t* __restrict__ pe = W16 + (int64_t)i * stride + pos_off + (int64_t)s * d;
+  for (int c = threadIdx.x; c < d; c += 64) h[r * d + c] = f2bf(bf2f(te[c]) + bf2f(pe[c]));
+  if (threadIdx.x == 0) {
+    tokens[r] = tok;
+    targets[r] = clamp_token(pool[row * (S + 1) + s + 1], V);
+    if (draw && s == 0 && b == 0) t[i] += 1;
+  }
+}
+hipError_t embed_fwd(const int32_t* pool, int n_pool, int S, int B, int d, int V, int P, const bf16_t* W16, int64_t stride,
+                     int64_t tok_off, int64_t pos_off, uint32_t c0, uint64_t seed, int draw, bf16_t* h, int32_t* tokens,
+                     int32_t* targets, int32_t* t, hipStream_t s) {
+  hipLaunchKernelGGL(embed_fwd_kernel, dim3(S, B, P), dim3(64), 0, s, pool, n_pool, S, B, d, V, W16, stride, tok_off, pos_off, c0,
+                     (uint32_t)seed, (uint32_t)(seed >> 32), draw, h, tokens, targets, t);
+  return hipGetLastError();
+}
+
+// dPos[s][:] = sum_b dh[b][s][:] and dTok[v][:] = sum over positions holding token v, both in a
+// fixed order (no atomics): one workgroup per (row of the table, member) scans the positions.
+__global__ __launch_bounds__(256) void embed_bwd_kernel(const bf16_t* __restrict__ dh, const int32_t* __restrict__ tokens,
+                                                        int B, int S, int d, int V, float* __restrict__ G, int64_t stride,
+                                                        int64_t tok_off, int64_t pos_off) {
+  const int i = blockIdx.y;
+  const int row = blockIdx.x;  // 0..V-1: token rows; V..V+S-1: position rows
+  const int n = B * S;
+  const bf16_t* __restrict__ g = dh + (int64_t)i * n * d;
+  const int32_t* __restrict__ tk = tokens + (int64_t)i * n;
+  for (int c0 = threadIdx.x; c0 < d; c0 += 256) {
+    float acc = 0.f;
+    if (row < V) {
+      for (int r = 0; r < n; ++r)
+        if (tk[r] == row) acc += bf2f(g[(int64_t)r * d + c0]);
+      G[(int64_t)i * stride + tok_off + (int64_t)row * d + c0] = acc;
+    } else {
+      const int s = row - V;
+      for (int b = 0; b < B; ++b) acc += bf2f(g[((int64_t)b * S + s) * d + c0]);
+      G[(int64_t)i * stride + pos_off + (int64_t)s * d + c0] = acc;
+    }
+  }
+}
+hipError_t embed_bwd(const bf16_t* dh, const int32_t* tokens, int B, int S, int d, int V, int P, float* G, int64_t stride,
+                     int64_t tok_off, int64_t pos_off, hipStream_t s) {
+  hipLaunchKernelGGL(embed_bwd_kernel, dim3(V + S, P), dim3(256), 0, s, dh, tokens, B, S, d, V, G, stride, tok_off, pos_off);
+  return hipGetLastError();
+}
+
+// ---- LayerNorm -------------------------------------------------------------------------------
+// One wavefront per row.  y = (x - mean) * rstd * g + b, eps = 1e-5; mean and rstd are kept.
+constexpr float LN_EPS = 1e-5f;
+__global__ __launch_bounds__(256) void layernorm_fwd_kernel(const bf16_t* __restrict__ x, int rows_per_member, int d,
+                                                            const float* __restrict__ W32, int64_t stride, int64_t g_off,
+                                                            int64_t b_off, bf16_t* __restrict__ y, float* __restrict__ mean,
+                                                            float* __restrict__ rstd) {
+  const int i = blockIdx.y;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (r >= rows_per_member) return;
+  const int64_t row = (int64_t)i * rows_per_member + r;
+  const bf16_t* __restrict__ xr = x + row * d;
+  float s = 0.f;
+  for (int c = lane; c < d; c += 64) s += bf2f(xr[c]);
+  const float mu = wave_sum(s) / (float)d;
+  float v = 0.f;
+  for (int c = lane; c < d; c += 64) { const float t = bf2f(xr[c]) - mu; v = fmaf(t, t, v); }
+  const float rs = rsqrtf(wave_sum(v) / (float)d + LN_EPS);
+  const float* __restrict__ g = W32 + (int64_t)i * stride + g_off;
+  const float* __restrict__ b = W32 + (int64_t)i * stride + b_off;
+  for (int c = lane; c < d; c += 64) y[row * d + c] = f2bf((bf2f(xr[c]) - mu) * rs * g[c] + b[c]);
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+}
+hipError_t layernorm_fwd(const bf16_t* x, int P, int rows, int d, const float* W32, int64_t stride, int64_t g_off, int64_t b_off,
+                         bf16_t* y, float* mean, float* rstd, hipStream_t s) {
+  hipLaunchKernelGGL(layernorm_fwd_kernel, dim3((rows + 3) / 4, P), dim3(256), 0, s, x, rows, d, W32, stride, g_off, b_off, y, mean, rstd);
+  return hipGetLastError();
+}
+
+// dx = rstd (dy g - mean(dy g) - xhat mean(dy g xhat)); out = dx (+ res when res != null), bf16.
+__global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x,
+                                                            const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                            int rows_per_member, int d, const float* __restrict__ W32,
+                                                            int64_t stride, int64_t g_off, const bf16_t* __restrict__ res,
+                                                            bf16_t* __restrict__ out) {
+  const int i = blockIdx.y;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (r >= rows_per_member) return;
+  const int64_t row = (int64_t)i * rows_per_member + r;
+  const float mu = mean[row], rs = rstd[row];
+  const float* __restrict__ g = W32 + (int64_t)i * stride + g_off;
+  float a = 0.f, b = 0.f;
+  for (int c = lane; c < d; c += 64) {
+    const float dyg = bf2f(dy[row * d + c]) * g[c];
+    a += dyg;
+    b = fmaf(dyg, (bf2f(x[row * d + c]) - mu) * rs, b);
+  }
+  a = wave_sum(a) / (float)d;
+  b = wave_sum(b) / (float)d;
+  for (int c = lane; c < d; c += 64) {
+    const float xh = (bf2f(x[row * d + c]) - mu) * rs;
+    float v = rs * (bf2f(dy[row * d + c]) * g[c] - a - xh * b);
+    if (res) v += bf2f(res[row * d + c]);
+    out[row * d + c] = f2bf(v);
+  }
+}
+hipError_t layernorm_bwd(const bf16_t* dy, const bf16_t* x, const float* mean, const float* rstd, int P, int rows, int d,
+                         const float* W32, int64_t stride, int64_t g_off, const bf16_t* res, bf16_t* out, hipStream_t s) {
+  hipLaunchKernelGGL(layernorm_bwd_kernel, dim3((rows + 3) / 4, P), dim3(256), 0, s, dy, x, mean, rstd, rows, d, W32, stride, g_off, res, out);
+  return hipGetLastError();
+}
+
+// dg[c] = sum_r dy[r][c] xhat[r][c], db[c] = sum_r dy[r][c]; 64 columns per workgroup, 4 row groups of
+// 64 threads, partial sums combined through LDS in a fixed order.
+__global__ __launch_bounds__(256) void layernorm_param_grad_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x,
+                                                                   const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                                   int rows_per_member, int d, float* __restrict__ G, int64_t stride,
+                                                                   int64_t g_off, int64_t b_off) {
+  __shared__ float pg[4][64], pb[4][64];
+  const int i = blockIdx.y;
+  const int cl = threadIdx.x & 63, rg = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
+  float ag = 0.f, ab = 0.f;
+  if (c < d) {
+    for (int r = rg; r < rows_per_member; r += 4) {
+      const int64_t row = (int64_t)i * rows_per_member + r;
+      const float v = bf2f(dy[row * d + c]);
+      ab += v;
+      ag = fmaf(v, (bf2f(x[row * d + c]) - mean[row]) * rstd[row], ag);
+    }
+  }
+  pg[rg][cl] = ag;
+  pb[rg][cl] = ab;
+  __syncthreads();
+  if (rg == 0 && c < d) {
+    G[(int64_t)i * stride + g_off + c] = ((pg[0][cl] + pg[1][cl]) + pg[2][cl]) + pg[3][cl];
+    G[(int64_t)i * stride + b_off + c] = ((pb[0][cl] + pb[1][cl]) + pb[2][cl]) + pb[3][cl];
+  }
+}
+hipError_t layernorm_param_grad(const bf16_t* dy, const bf16_t* x, const float* mean, const float* rstd, int P, int rows, int d,
+                                float* G, int64_t stride, int64_t g_off, int64_t b_off, hipStream_t s) {
+  hipLaunchKernelGGL(layernorm_param_grad_kernel, dim3((d + 63) / 64, P), dim3(256), 0, s, dy, x, mean, rstd, rows, d, G, stride, g_off, b_off);
+  return hipGetLastError();
+}
+
+// ---- causal softmax with dropout -------------------------------------------------------------
+// One wavefront per row of the [P][B][H][S][S] score array.  p = softmax over positions <= t of
+// score * scale; writes p (kept for the backward pass) and p * keep (the operand of P V).
+__global__ __launch_bounds__(256) void softmax_fwd_kernel(const bf16_t* __restrict__ sc, int64_t rows_per_member, int S, float scale,
+                                                          DropArgs d, int site, bf16_t* __restrict__ pq, bf16_t* __restrict__ pd) {
+  const int i = blockIdx.y;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (r >= rows_per_member) return;
+  const int t = (int)(r % S);  // query position: attends to keys 0..t
+  const int64_t base = ((int64_t)i * rows_per_member + r) * S;
+  const DropRate dr = drop_rate(d.H, d.n_hyper, d.col, i, d.active);
+  float mx = -INFINITY;
+  for (int c = lane; c <= t; c += 64) mx = fmaxf(mx, bf2f(sc[base + c]) * scale);
+  mx = wave_max(mx);
+  float se = 0.f;
+  for (int c = lane; c <= t; c += 64) se += expf(bf2f(sc[base + c]) * scale - mx);
+  const float inv = 1.f / wave_sum(se);
+  for (int c = lane; c < S; c += 64) {
+    float p = 0.f;
+    if (c <= t) p = expf(bf2f(sc[base + c]) * scale - mx) * inv;
+    float keep = dr.scale;
+    if (dr.thr) {
+      const uint64_t e = (uint64_t)r * S + c;  // element index inside the member's site array
+      float f[4];
+      drop_factors4(d, dr, i, site, (uint32_t)(e >> 2), f);
+      keep = f[e & 3];
+    }
+    pq[base + c] = f2bf(p);
+    pd[base + c] = f2bf(p * keep);
+  }
+}
+hipError_t softmax_fwd(const bf16_t* sc, int P, int64_t rows, int S, float scale, const DropArgs& d, int site, bf16_t* pq,
+                       bf16_t* pd, hipStream_t s) {
+  hipLaunchKernelGGL(softmax_fwd_kernel, dim3((unsigned)((rows + 3) / 4), P), dim3(256), 0, s, sc, rows, S, scale, d, site, pq, pd);
+  return hipGetLastError();
+}
+
+// ds = p (dp - sum_c dp p) * scale with dp = dpd * keep; in place over dpd.
+__global__ __launch_bounds__(256) void softmax_bwd_kernel(const bf16_t* __restrict__ pq, bf16_t* __restrict__ dpd, int64_t rows_per_member,
+                                                          int S, float scale, DropArgs d, int site) {
+  const int i = blockIdx.y;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (r >= rows_per_member) return;
+  const int64_t base = ((int64_t)i * rows_per_member + r) * S;
+  const DropRate dr = drop_rate(d.H, d.n_hyper, d.col, i, d.active);
+  float dot = 0.f;
+  for (int c = lane; c < S; c += 64) {
+    float keep = dr.scale;
+    if (dr.thr) {
+      const uint64_t e = (uint64_t)r * S + c;
+      float f[4];
+      drop_factors4(d, dr, i, site, (uint32_t)(e >> 2), f);
+      keep = f[e & 3];
+    }
+    dot = fmaf(bf2f(dpd[base + c]) * keep, bf2f(pq[base + c]), dot);
+  }
+  dot = wave_sum(dot);
+  for (int c = lane; c < S; c += 64) {
+    float keep = dr.scale;
+    if (dr.thr) {
+      const uint64_t e = (uint64_t)r * S + c;
+      float f[4];
+      drop_factors4(d, dr, i, site, (uint32_t)(e >> 2), f);
+      keep = f[e & 3];
+    }
+    const float p = bf2f(pq[base + c]);
+    dpd[base + c] = f2bf(p * (bf2f(dpd[base + c]) * keep - dot) * scale);
+  }
+}
+hipError_t softmax_bwd(const bf16_t* pq, bf16_t* dpd, int P, int64_t rows, int S, float scale, const DropArgs& d, int site,
+                       hipStream_t s) {
+  hipLaunchKernelGGL(softmax_bwd_kernel, dim3((unsigned)((rows + 3) / 4), P), dim3(256), 0, s, pq, dpd, rows, S, scale, d, site);
+  return hipGetLastError();
+}
+
+// ---- dropout / residual ----------------------------------------------------------------------
+// out = x * keep (+ res when res != null); four elements per thread (one Philox call).
+__global__ __launch_bounds__(256) void dropout_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ res,
+                                                      int64_t per_member, DropArgs d, int site, bf16_t* __restrict__ out) {
+  const int i = blockIdx.y;
+  const int64_t blk = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (blk * 4 >= per_member) return;
+  const DropRate dr = drop_rate(d.H, d.n_hyper, d.col, i, d.active);
+  float f[4];
+  drop_factors4(d, dr, i, site, (uint32_t)blk, f);
+  const int64_t o = (int64_t)i * per_member + blk * 4;
+  const uint2 xv = *reinterpret_cast<const uint2*>(x + o);
+  // bf16 x float products are exact in double
+  double v[4] = {(double)__uint_as_float(xv.x << 16) * (double)f[0], (double)__uint_as_float(xv.x & 0xffff0000u) * (double)f[1],
+                 (double)__uint_as_float(xv.y << 16) * (double)f[2], (double)__uint_as_float(xv.y & 0xffff0000u) * (double)f[3]};
+  if (res) {
+    const uint2 rv = *reinterpret_cast<const uint2*>(res + o);
+    v[0] = (double)__uint_as_float(rv.x << 16) + v[0]; v[1] = (double)__uint_as_float(rv.x & 0xffff0000u) + v[1];
+    v[2] = (double)__uint_as_float(rv.y << 16) + v[2]; v[3] = (double)__uint_as_float(rv.y & 0xffff0000u) + v[3];
+  }
+  uint2 pk;
+  pk.x = d2bf(v[0]) | ((uint32_t)d2bf(v[1]) << 16);
+  pk.y = d2bf(v[2]) | ((uint32_t)d2bf(v[3]) << 16);
+  *reinterpret_cast<uint2*>(out + o) = pk;
+}
+hipError_t dropout_apply(const bf16_t* x, const bf16_t* res, int P, int64_t per_member, const DropArgs& d, int site, bf16_t* out,
+                         hipStream_t s) {
+  if (per_member % 4) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(dropout_kernel, dim3((unsigned)((per_member / 4 + 255) / 256), P), dim3(256), 0, s, x, res, per_member, d, site, out);
+  return hipGetLastError();
+}
+
+// ---- label-smoothed cross-entropy over the vocabulary -----------------------------------------
+// One workgroup per row of float logits[rows][V].  loss = lse - (1-e) l_y - (e/V) sum l;
+// dlogits = (softmax - ((1-e) onehot + e/V)) * gscale as bf16 (when dlogits != null).
+__global__ __launch_bounds__(256) void xent_kernel(const float* __restrict__ logits, const int32_t* __restrict__ targets, int rows_per_member,
+                                                   int V, const float* __restrict__ H, int n_hyper, int col_ls, int use_ls, float gscale,
+                                                   bf16_t* __restrict__ dlogits, float* __restrict__ rowloss) {
+  __shared__ float red[4];
+  const int i = blockIdx.y;
+  const int64_t row = (int64_t)i * rows_per_member + blockIdx.x;
+  const float* __restrict__ l = logits + row * V;
+  const float eps = (use_ls && col_ls >= 0) ? H[(int64_t)i * n_hyper + col_ls] : 0.f;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float mx = -INFINITY;
+  for (int c = threadIdx.x; c < V; c += 256) mx = fmaxf(mx, l[c]);
+  mx = wave_max(mx);
+  if (lane == 0) red[wave] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float se = 0.f, sl = 0.f;
+  for (int c = threadIdx.x; c < V; c += 256) { se += expf(l[c] - mx); sl += l[c]; }
+  se = wave_sum(se);
+  if (lane == 0) red[wave] = se;
+  __syncthreads();
+  se = ((red[0] + red[1]) + red[2]) + red[3];
+  __syncthreads();
+  sl = wave_sum(sl);
+  if (lane == 0) red[wave] = sl;
+  __syncthreads();
+  sl = ((red[0] + red[1]) + red[2]) + red[3];
+  const float lse = mx + logf(se);
+  const int y = targets[row];
+  if (threadIdx.x == 0) rowloss[row] = lse - (1.f - eps) * l[y] - eps * (sl / (float)V);
+  if (dlogits) {
+    const float inv = 1.f / se, u = eps / (float)V;
+    bf16_t* __restrict__ dl = dlogits + row * V;
+    for (int c = threadIdx.x; c < V; c += 256)
+      dl[c] = f2bf((expf(l[c] - mx) * inv - u - (c == y ? 1.f - eps : 0.f)) * gscale);
+  }
+}
+hipError_t xent_rows(const float* logits, const int32_t* targets, int P, int rows, int V, const float* H, int n_hyper, int col_ls,
+                     int use_ls, float gscale, bf16_t* dlogits, float* rowloss, hipStream_t s) {
+  hipLaunchKernelGGL(xent_kernel, dim3(rows, P), dim3(256), 0, s, logits, targets, rows, V, H, n_hyper, col_ls, use_ls, gscale, dlogits, rowloss);
+  return hipGetLastError();
+}
+
+// dst[i][offset + r] = src[i][r]: collects the per-row losses of one eval chunk
+__global__ void scatter_rows_kernel(const float* __restrict__ src, int rows, float* __restrict__ dst, int64_t dst_stride, int64_t offset) {
+  const int i = blockIdx.y;
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r < rows) dst[(int64_t)i * dst_stride + offset + r] = src[(int64_t)i * rows + r];
+}
+hipError_t tf_scatter_rows(const float* src, int P, int rows, float* dst, int64_t dst_stride, int64_t offset, hipStream_t s) {
+  hipLaunchKernelGGL(scatter_rows_kernel, dim3((rows + 255) / 256, P), dim3(256), 0, s, src, rows, dst, dst_stride, offset);
+  return hipGetLastError();
+}
+
+// score[i] = -exp(mean of rowloss[i][:])   (perplexity, negated), one wavefront per member
+__global__ __launch_bounds__(64) void perplexity_kernel(const float* __restrict__ rowloss, int rows, float* __restrict__ score) {
+  const int i = blockIdx.x;
+  float acc = 0.f;
+  for (int r = threadIdx.x; r < rows; r += 64) acc += rowloss[(int64_t)i * rows + r];
+  acc = wave_sum(acc);
+  if (threadIdx.x == 0) score[i] = -expf(acc / (float)rows);
+}
+hipError_t perplexity_score(const float* rowloss, int P, int rows, float* score, hipStream_t s) {
+  hipLaunchKernelGGL(perplexity_kernel, dim3(P), dim3(64), 0, s, rowloss, rows, score);
+  return hipGetLastError();
+}
+
+}  // namespace pbt

@@ -18,8 +18,8 @@ import numpy as np
 ACT_NONE, ACT_RELU, ACT_GELU, ACT_LEAKY_RELU, ACT_TANH = 0, 1, 2, 3, 4
 OPT_SGD_MOMENTUM, OPT_ADAM, OPT_RMSPROP = 0, 1, 2
 DTYPE_FP32, DTYPE_BF16 = 0, 1
-ROLE_LR, ROLE_BETA1, ROLE_WD, ROLE_LR_G, ROLE_LR_D, ROLE_ENTROPY_COST = 0, 1, 2, 3, 4, 5
-WL_CLASSIFIER, WL_GAN, WL_A2C = 1, 3, 5
+ROLE_LR, ROLE_BETA1, ROLE_WD, ROLE_LR_G, ROLE_LR_D, ROLE_ENTROPY_COST, ROLE_DROPOUT, ROLE_LABEL_SMOOTH = 0, 1, 2, 3, 4, 5, 6, 7
+WL_CLASSIFIER, WL_GAN, WL_TRANSFORMER, WL_A2C = 1, 3, 4, 5
 
 POPULATION_SEED = 2017          # Philox key of the population
 
@@ -77,7 +77,69 @@ A2C_MLP = Workload(
     h_max=[math.inf, math.inf], ready_interval=100, n_trunc=trunc_count(128, 20), total_steps=2000,
     opt_const=dict(rho=0.99, eps=1e-5), data_seed=1005, perturb=(0.8, 1.2))
 
-WORKLOADS = {1: MLP_SMALL, 2: MLP_WIDE, 3: GAN_MLP, 5: A2C_MLP}
+# Decoder-only transformers (pre-LayerNorm blocks, learned positions, untied head) on synthetic token
+# sequences; Adam; learning rate, one dropout rate and the label smoothing per member; score = minus the
+# held-out perplexity.
+TRANSFORMER = Workload(
+    name="transformer_bf16", kind=WL_TRANSFORMER, P=16, vocab=8192, d_model=512, heads=8, d_ff=2048, n_blocks=4,
+    seq=128, batch=32, dtype=DTYPE_BF16, optimizer=OPT_ADAM, act=ACT_RELU, dims=[], n_train=8192, n_eval=256,
+    roles=[ROLE_LR, ROLE_DROPOUT, ROLE_LABEL_SMOOTH],
+    priors=[("log", 1e-4, 1e-3), ("uniform", 0.0, 0.3), ("uniform", 0.0, 0.2)], h_max=[math.inf, 0.9, 0.9],
+    ready_interval=200, n_trunc=trunc_count(16, 20), total_steps=2000,
+    opt_const=dict(beta1=0.9, beta2=0.999, eps=1e-8), data_seed=1004, perturb=(0.8, 1.2), zipf_s=1.1)
+
+WORKLOADS = {1: MLP_SMALL, 2: MLP_WIDE, 3: GAN_MLP, 4: TRANSFORMER, 5: A2C_MLP}
+
+
+def transformer_shapes(wl):
+    """Shapes of the parameter arrays of one transformer, in the order of the flat parameter vector."""
+    d, f, V, S = wl.d_model, wl.d_ff, wl.vocab, wl.seq
+    out = [(V, d), (S, d)]
+    for _ in range(wl.n_blocks):
+        out += [(d,), (d,), (d, 3 * d), (3 * d,), (d, d), (d,), (d,), (d,), (d, f), (f,), (f, d), (d,)]
+    return out + [(d,), (d,), (d, V), (V,)]
+
+
+def initial_transformer_weights(wl, P, seed):
+    """Per member the parameter arrays in layout order: embeddings ~ N(0, 0.1^2), matrices uniform in
+    +-1/sqrt(fan_in), LayerNorm gains 1, every bias 0."""
+    rng = np.random.default_rng(seed)
+    shapes = transformer_shapes(wl)
+    gains = {2 + 12 * l + k for l in range(wl.n_blocks) for k in (0, 6)} | {len(shapes) - 4}
+    members = []
+    for _ in range(P):
+        arrays = []
+        for j, sh in enumerate(shapes):
+            if j < 2:
+                arrays.append((0.1 * rng.standard_normal(sh)).astype(np.float32))
+            elif len(sh) == 2:
+                lim = 1.0 / math.sqrt(sh[0])
+                arrays.append(rng.uniform(-lim, lim, size=sh).astype(np.float32))
+            else:
+                arrays.append(np.full(sh, 1.0 if j in gains else 0.0, dtype=np.float32))
+        members.append(arrays)
+    return members
+
+
+def zipf_bigram_sequences(wl):
+    """(train [n_train][seq+1], eval [n_eval][seq+1]) int32 token sequences.  Ranks z_t are i.i.d. from a
+    Zipf(s) law truncated to the vocabulary (inverse-CDF lookup); with a fixed random permutation pi of
+    the vocabulary, x_0 = z_0 - 1 and x_t = (pi[x_{t-1}] + z_t - 1) mod V, so the next token is
+    predictable from the current one up to the entropy of the Zipf law."""
+    rng = np.random.default_rng(wl.data_seed)
+    V, T = wl.vocab, wl.seq + 1
+    pmf = 1.0 / np.arange(1, V + 1) ** wl.zipf_s
+    cdf = np.cumsum(pmf / pmf.sum())
+    pi = rng.permutation(V)
+    out = []
+    for n in (wl.n_train, wl.n_eval):
+        z = np.minimum(np.searchsorted(cdf, rng.random((n, T))), V - 1)      # rank - 1
+        x = np.empty((n, T), dtype=np.int64)
+        x[:, 0] = z[:, 0]
+        for t in range(1, T):
+            x[:, t] = (pi[x[:, t - 1]] + z[:, t]) % V
+        out.append(x.astype(np.int32))
+    return out[0], out[1]
 
 
 def gaussian_mixture(n_classes, dim, n_train, n_eval, seed):

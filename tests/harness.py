@@ -238,3 +238,76 @@ class A2CPair:
         wl = self.wl
         pop = [self.ref[i] for i in range(wl.P)]
         return opbt.exploit_explore(pop, rnd, self.seed, wl.n_trunc, wl.perturb[0], wl.perturb[1], wl.h_max, scores=scores)
+
+
+class TransformerPair:
+    """A transformer population on the GPU and its oracle twin (all members or a sample)."""
+
+    def __init__(self, wl, seed=workloads.POPULATION_SEED, init_seed=5, ref_members=None, H=None):
+        import torch
+        from oracle import transformer as ot
+        self.ot, self.wl, self.seed = ot, wl, seed
+        self.pool, self.eval_seqs = workloads.zipf_bigram_sequences(wl)
+        self.cfg = binding.make_config(wl, seed)
+        self.gpu = binding.Population(self.cfg)
+        self.shapes = workloads.transformer_shapes(wl)
+        weights = workloads.initial_transformer_weights(wl, wl.P, init_seed)
+        H = workloads.initial_hypers(wl, init_seed + 1) if H is None else np.asarray(H, dtype=np.float32)
+        self.gpu.set(binding.ARR_W32, np.stack([binding.pack_segments(self.gpu.layout, a) for a in weights]))
+        self.gpu.set(binding.ARR_HYPER, H)
+        oc_ = {k: float(np.float32(v)) for k, v in wl.opt_const.items()}
+        self.spec = ot.TransformerSpec(wl.vocab, wl.d_model, wl.heads, wl.d_ff, wl.n_blocks, wl.seq, wl.batch, seed,
+                                       roles=wl.roles, beta1=oc_["beta1"], beta2=oc_["beta2"], eps=oc_["eps"],
+                                       bf16_storage=True)
+        assert [s for _, s in self.spec.param_shapes()] == self.shapes
+        self.ref_ids = list(range(wl.P)) if ref_members is None else list(ref_members)
+        self.ref = {i: ot.new_member(self.spec, weights[i], H[i], i) for i in self.ref_ids}
+        dev = self.gpu.device
+        self.d_pool = [torch.from_numpy(self.pool).to(dev)]
+        self.d_eval = [torch.from_numpy(self.eval_seqs).to(dev)]
+
+    def step_ref(self, s):
+        return np.array([self.ot.step(self.spec, self.ref[i], i, s, self.pool) for i in self.ref_ids])
+
+    def eval_ref(self):
+        return np.array([self.ot.evaluate(self.spec, self.ref[i], self.eval_seqs, chunk=self.wl.batch) for i in self.ref_ids])
+
+    def ref_arrays(self, i, what):
+        m = self.ref[i]
+        return m.theta if what == "theta" else m.opt[what]
+
+    def gpu_arrays(self, i, which):
+        return binding.unpack_segments(self.gpu.layout, self.shapes, self.gpu.get(which, i).astype(np.float64))
+
+    def array_errors(self, i, which, ref_arrays, rms_floor=0.0, skip_key_bias=False):
+        """Per parameter array: relative L2 distance between the GPU's and the given reference arrays.
+
+        skip_key_bias leaves the key third of every bqkv out.  Adding a constant to all keys shifts each
+        row of scores by a constant, which the softmax removes: the network does not depend on the key
+        bias and its exact gradient is zero.  What reaches Adam is rounding noise, which Adam's
+        normalisation turns into steps of the full learning rate with random signs, so the value of
+        that bias (and its moment estimates) is not a reproducible quantity."""
+        d = self.wl.d_model
+        out = []
+        for (name, _), g, r in zip(self.spec.param_shapes(), self.gpu_arrays(i, which), ref_arrays):
+            if skip_key_bias and name.startswith("bqkv"):
+                g, r = np.delete(g, np.s_[d:2 * d]), np.delete(r, np.s_[d:2 * d])
+            den = max(np.linalg.norm(r), rms_floor * np.sqrt(r.size), 1e-30)
+            out.append(np.linalg.norm(g - r) / den)
+        return np.array(out)
+
+    def sync_ref_from_gpu(self, i):
+        m = self.ref[i]
+        for what, which in (("theta", binding.ARR_W32), ("s0", binding.ARR_OPT0), ("s1", binding.ARR_OPT1)):
+            arrs = self.gpu_arrays(i, which)
+            if what == "theta":
+                m.theta = arrs
+            else:
+                m.opt[what] = arrs
+        m.t = int(self.gpu.get(binding.ARR_T, i)[0])
+        m.h = self.gpu.get(binding.ARR_HYPER, i).copy()
+
+    def exploit_ref(self, rnd, scores):
+        wl = self.wl
+        pop = [self.ref[i] for i in range(wl.P)]
+        return opbt.exploit_explore(pop, rnd, self.seed, wl.n_trunc, wl.perturb[0], wl.perturb[1], wl.h_max, scores=scores)

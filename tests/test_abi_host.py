@@ -75,3 +75,40 @@ def test_bad_configurations_are_rejected(change, status):
 def test_trunc_count_rule():
     assert [workloads.trunc_count(P, pc) for P, pc in ((8, 25), (64, 20), (32, 20), (16, 20), (128, 20), (3, 20))] == \
         [2, 12, 6, 3, 25, 1]
+
+
+def test_transformer_layout_lists_every_parameter_array_in_order():
+    wl = workloads.TRANSFORMER
+    state, scratch, lay = binding.query_sizes(binding.make_config(wl, 1))
+    shapes = workloads.transformer_shapes(wl)
+    assert lay.n_seg == len(shapes) == 2 + 12 * wl.n_blocks + 4
+    sizes = [int(np.prod(s)) for s in shapes]
+    assert [lay.seg_len[j] for j in range(lay.n_seg)] == sizes and lay.n_params == sum(sizes)
+    end = 0
+    for j in range(lay.n_seg):
+        assert lay.seg_off[j] >= end and lay.seg_off[j] % 8 == 0      # no overlap, 16-byte aligned as bf16
+        end = lay.seg_off[j] + lay.seg_len[j]
+    assert end <= lay.stride
+    assert state >= wl.P * lay.stride * (4 * 3 + 2) and scratch > wl.P * lay.stride * 4
+    arrays = workloads.initial_transformer_weights(wl.replace(vocab=64, d_model=16, heads=2, d_ff=32, seq=8, n_blocks=1), 1, 3)[0]
+    small = binding.query_sizes(binding.make_config(wl.replace(vocab=64, d_model=16, heads=2, d_ff=32, seq=8, n_blocks=1), 1))[2]
+    flat = binding.pack_segments(small, arrays)
+    back = binding.unpack_segments(small, [a.shape for a in arrays], flat)
+    assert all(np.array_equal(a, b) for a, b in zip(arrays, back))
+
+
+@pytest.mark.parametrize("change", [dict(d_model=500), dict(heads=3), dict(seq=100), dict(n_eval=250), dict(h_max=[math.inf, 1.0, 0.9]),
+                                    dict(optimizer=workloads.OPT_RMSPROP, opt_const=dict(rho=0.9, eps=1e-5))])
+def test_transformer_bad_configurations_are_rejected(change):
+    cfg = binding.make_config(workloads.TRANSFORMER.replace(**change), 1)
+    with pytest.raises(binding.PbtError):
+        binding.query_sizes(cfg)
+
+
+def test_dense_workload_segments_mirror_layer_offsets():
+    _, _, lay = binding.query_sizes(binding.make_config(workloads.MLP_WIDE, 1))
+    dims = workloads.MLP_WIDE.dims
+    assert lay.n_seg == 2 * (len(dims) - 1)
+    for l in range(len(dims) - 1):
+        assert (lay.seg_off[2 * l], lay.seg_len[2 * l]) == (lay.w_off[l], dims[l] * dims[l + 1])
+        assert (lay.seg_off[2 * l + 1], lay.seg_len[2 * l + 1]) == (lay.b_off[l], dims[l + 1])
