@@ -57,20 +57,26 @@ def cpu_baseline(wl, data, seed, budget_s=15.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=None, help="default 400 (30 for the transformer workload)")
+    ap.add_argument("--warmup", type=int, default=None, help="default 20 (3 for the transformer workload)")
     ap.add_argument("--kernel", default=None, help="kernel class whose roofline is reported (default: the dominant one)")
     ap.add_argument("--fused", type=int, default=0, choices=[0, 1],
                     help="0 = separate streaming optimiser pass (default, the faster of the two as measured), "
                          "1 = optimiser applied inside the weight-gradient GEMMs")
-    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 5],
-                    help="2 = wide bf16 MLP classifiers (default, the headline workload), 3 = MLP GAN pairs, 5 = actor-critic")
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5],
+                    help="2 = wide bf16 MLP classifiers (default, the headline workload), 3 = MLP GAN pairs, "
+                         "4 = decoder-only transformers, 5 = actor-critic")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); --gpus %d is not supported"
               % args.gpus, file=sys.stderr)
         sys.exit(2)
+
+    if args.steps is None:
+        args.steps = 30 if args.workload == 4 else 400
+    if args.warmup is None:
+        args.warmup = 3 if args.workload == 4 else 20
 
     import numpy as np
     import torch
@@ -82,7 +88,7 @@ def main():
     pop = binding.Population(cfg)
     dev = pop.device
     if args.kernel is None:
-        args.kernel = "gemm_wgrad" if args.fused else "optimizer"
+        args.kernel = "gemm_fwd" if args.workload == 4 else "gemm_wgrad" if args.fused else "optimizer"
     data = None
     if args.workload == 2:
         data = workloads.classifier_data(wl)
@@ -94,6 +100,12 @@ def main():
         tx, ex = workloads.gan_data(wl)
         pop.set_members([list(g) + list(d) for g, d in workloads.initial_gan_weights(wl, wl.P, 5)], workloads.initial_hypers(wl, 6))
         d_train, d_eval = [torch.from_numpy(tx).to(dev)], [torch.from_numpy(ex).to(dev)]
+    elif args.workload == 4:
+        pool, held_out = workloads.zipf_bigram_sequences(wl)
+        weights = workloads.initial_transformer_weights(wl, wl.P, 5)
+        pop.set(binding.ARR_W32, np.stack([binding.pack_segments(pop.layout, a) for a in weights]))
+        pop.set(binding.ARR_HYPER, workloads.initial_hypers(wl, 6))
+        d_train, d_eval = [torch.from_numpy(pool).to(dev)], [torch.from_numpy(held_out).to(dev)]
     else:
         obs, act, rew = workloads.trajectory_pool(wl)
         pop.set_members(workloads.initial_mlp_weights(wl.dims, wl.P, 5), workloads.initial_hypers(wl, 6))
@@ -132,8 +144,17 @@ def main():
     n = pop.layout.n_params
     L = len(wl.dims) - 1
     flops_fwd = sum(2.0 * wl.batch * wl.dims[l] * wl.dims[l + 1] for l in range(L - 1)) * wl.P
-    state_bytes = {2: 14.0, 3: 14.0, 5: 10.0}[args.workload]      # fp32 theta + optimiser state (+ bf16 shadow) per parameter
-    per_launch = {
+    state_bytes = {2: 14.0, 3: 14.0, 4: 14.0, 5: 10.0}[args.workload]      # fp32 theta + optimiser state (+ bf16 shadow) per parameter
+    if args.workload == 4:
+        # dense layers of one forward pass: per block QKV, attention output, two feed-forward matrices; the vocabulary head
+        rows, d, f = wl.batch * wl.seq, wl.d_model, wl.d_ff
+        dense = 2.0 * rows * (wl.n_blocks * (3 * d * d + d * d + 2 * d * f) + d * wl.vocab) * wl.P
+        n_dense = 4 * wl.n_blocks + 1
+        per_launch = {"optimizer": ("hbm", 30.0 * n * wl.P), "copy": ("hbm", 2.0 * state_bytes * n * wl.n_trunc),
+                      "gemm_fwd": ("mfma", dense / n_dense), "gemm_wgrad": ("mfma", dense / n_dense),
+                      "gemm_dgrad": ("mfma", dense / n_dense)}.get(args.kernel)
+    else:
+      per_launch = {
         # Adam: read theta, g, m, v (16 B), write theta, m, v (12 B) and the bf16 shadow (2 B) per parameter
         "optimizer": ("hbm", 30.0 * n * wl.P) if args.workload == 2 else None,
         # read + write of every array of the n_trunc copied members: fp32 theta, optimiser state, bf16 shadow
@@ -145,7 +166,7 @@ def main():
                                 + 2.0 * wl.batch * sum(wl.dims[l] + wl.dims[l + 1] for l in range(L - 1))) * wl.P / (L - 1))
                        if args.fused else ("mfma", flops_fwd / (L - 1))) if args.workload == 2 else None,
         "gemm_dgrad": ("mfma", 2.0 * wl.batch * wl.dims[1] * wl.dims[2] * wl.P) if args.workload == 2 else None,
-    }.get(args.kernel)
+      }.get(args.kernel)
     roofline = None
     if per_launch and k_n:
         bound, work = per_launch
@@ -162,7 +183,9 @@ def main():
         "metric": "population member-steps/sec at 1 MI355X", "value": wl.P * args.steps / dt, "unit": "member-steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "fused_optimizer": bool(args.fused), "P": wl.P, "dims": wl.dims, "batch": wl.batch,
+        "config": {"workload": wl.name, "fused_optimizer": bool(args.fused), "P": wl.P,
+                   "dims": wl.dims or {"blocks": wl.n_blocks, "d_model": wl.d_model, "heads": wl.heads, "d_ff": wl.d_ff, "seq": wl.seq, "vocab": wl.vocab},
+                   "batch": wl.batch,
                    "optimizer": {0: "sgd_momentum", 1: "adam", 2: "rmsprop"}[wl.optimizer],
                    "ready_interval": wl.ready_interval, "n_trunc": wl.n_trunc, "eval_rows": wl.n_eval,
                    "exploit_rounds_in_timed_region": n_rounds},

@@ -114,13 +114,14 @@ hipError_t embed_fwd(const int32_t* pool, int n_pool, int S, int B, int d, int V
                      int64_t tok_off, int64_t pos_off, uint32_t c0, uint64_t seed, int draw, bf16_t* h, int32_t* tokens,
                      int32_t* targets, int32_t* t, hipStream_t s);
 hipError_t embed_bwd(const bf16_t* dh, const int32_t* tokens, int B, int S, int d, int V, int P, float* G, int64_t stride,
-                     int64_t tok_off, int64_t pos_off, hipStream_t s);
+                     int64_t tok_off, int64_t pos_off, int32_t* start, int32_t* cursor, int32_t* order, hipStream_t s);
 hipError_t layernorm_fwd(const bf16_t* x, int P, int rows, int d, const float* W32, int64_t stride, int64_t g_off, int64_t b_off,
                          bf16_t* y, float* mean, float* rstd, hipStream_t s);
 hipError_t layernorm_bwd(const bf16_t* dy, const bf16_t* x, const float* mean, const float* rstd, int P, int rows, int d,
                          const float* W32, int64_t stride, int64_t g_off, const bf16_t* res, bf16_t* out, hipStream_t s);
+constexpr int LN_MAX_SLABS = 64;  // row slabs whose partial sums layernorm_param_grad combines
 hipError_t layernorm_param_grad(const bf16_t* dy, const bf16_t* x, const float* mean, const float* rstd, int P, int rows, int d,
-                                float* G, int64_t stride, int64_t g_off, int64_t b_off, hipStream_t s);
+                                float* G, int64_t stride, int64_t g_off, int64_t b_off, float* part, hipStream_t s);
 hipError_t softmax_fwd(const bf16_t* sc, int P, int64_t rows, int S, float scale, const DropArgs& d, int site, bf16_t* pq,
                        bf16_t* pd, hipStream_t s);
 hipError_t softmax_bwd(const bf16_t* pq, bf16_t* dpd, int P, int64_t rows, int S, float scale, const DropArgs& d, int site,

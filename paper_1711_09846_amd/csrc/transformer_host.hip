@@ -169,6 +169,10 @@ pbt_status tf_check_and_plan(const pbt_config* c, Plan* pl, Carver* w) {
   t.o_dlogits = w->take(P * n * D.V * 2);
   t.o_rowloss = w->take(P * n * 4);
   t.o_evalrow = w->take(P * (size_t)c->n_eval * D.S * 4);
+  t.o_tokstart = w->take(P * ((size_t)D.V + 1) * 4);
+  t.o_tokcursor = w->take(P * (size_t)D.V * 4);
+  t.o_tokorder = w->take(P * n * 4);
+  t.o_lnpart = w->take(P * (size_t)LN_MAX_SLABS * 2 * D.d * 4);
   return PBT_OK;
 }
 
@@ -200,7 +204,7 @@ pbt_status tf_step(pbt_handle* h, const int32_t* pool, uint32_t step, hipStream_
   // head and final LayerNorm
   TF_TRY(wgrad(x, x.sc<bf16_t>(t.o_uf), D.d, dl, D.V, t.whead, t.bhead));
   TF_TRY(dgrad(x, dl, D.V, D.d, t.whead, nullptr, 0, dd));
-  PBT_HIP(h, layernorm_param_grad(dd, x.sc<bf16_t>(t.o_h[D.L]), x.sc<float>(t.o_meanf), x.sc<float>(t.o_rstdf), x.P, x.n, D.d, x.G, x.S_, t.lnfg, t.lnfb, s));
+  PBT_HIP(h, layernorm_param_grad(dd, x.sc<bf16_t>(t.o_h[D.L]), x.sc<float>(t.o_meanf), x.sc<float>(t.o_rstdf), x.P, x.n, D.d, x.G, x.S_, t.lnfg, t.lnfb, x.sc<float>(t.o_lnpart), s));
   PBT_HIP(h, layernorm_bwd(dd, x.sc<bf16_t>(t.o_h[D.L]), x.sc<float>(t.o_meanf), x.sc<float>(t.o_rstdf), x.P, x.n, D.d, x.W32, x.S_, t.lnfg, nullptr, dh, s));
   for (int l = D.L - 1; l >= 0; --l) {
     const TfBlockOff& b = t.blk[l];
@@ -212,7 +216,7 @@ pbt_status tf_step(pbt_handle* h, const int32_t* pool, uint32_t step, hipStream_
     PBT_HIP(h, dropout_apply(df0, nullptr, x.P, per_f, dr, 4 * l + 2, df1, s));
     TF_TRY(wgrad(x, x.sc<bf16_t>(t.o_u2[l]), D.d, df1, D.f, b.w1, b.b1));
     TF_TRY(dgrad(x, df1, D.f, D.d, b.w1, nullptr, 0, du));
-    PBT_HIP(h, layernorm_param_grad(du, x.sc<bf16_t>(t.o_hmid[l]), x.sc<float>(t.o_mean2[l]), x.sc<float>(t.o_rstd2[l]), x.P, x.n, D.d, x.G, x.S_, b.ln2g, b.ln2b, s));
+    PBT_HIP(h, layernorm_param_grad(du, x.sc<bf16_t>(t.o_hmid[l]), x.sc<float>(t.o_mean2[l]), x.sc<float>(t.o_rstd2[l]), x.P, x.n, D.d, x.G, x.S_, b.ln2g, b.ln2b, x.sc<float>(t.o_lnpart), s));
     PBT_HIP(h, layernorm_bwd(du, x.sc<bf16_t>(t.o_hmid[l]), x.sc<float>(t.o_mean2[l]), x.sc<float>(t.o_rstd2[l]), x.P, x.n, D.d, x.W32, x.S_, b.ln2g, dh, dh2, s));
     // attention branch
     PBT_HIP(h, dropout_apply(dh2, nullptr, x.P, per_d, dr, 4 * l + 1, dd, s));
@@ -226,10 +230,11 @@ pbt_status tf_step(pbt_handle* h, const int32_t* pool, uint32_t step, hipStream_
     TF_TRY(attn_gemm(x, in_scores(dscore, D), true, in_rows(qkv, 0, 3 * D.d, D), false, in_rows(dqkv, D.d, 3 * D.d, D), D.S, D.dh, D.S));        // dK = dS^T Q
     TF_TRY(wgrad(x, x.sc<bf16_t>(t.o_u[l]), D.d, dqkv, 3 * D.d, b.wqkv, b.bqkv));
     TF_TRY(dgrad(x, dqkv, 3 * D.d, D.d, b.wqkv, nullptr, 0, du));
-    PBT_HIP(h, layernorm_param_grad(du, x.sc<bf16_t>(t.o_h[l]), x.sc<float>(t.o_mean1[l]), x.sc<float>(t.o_rstd1[l]), x.P, x.n, D.d, x.G, x.S_, b.ln1g, b.ln1b, s));
+    PBT_HIP(h, layernorm_param_grad(du, x.sc<bf16_t>(t.o_h[l]), x.sc<float>(t.o_mean1[l]), x.sc<float>(t.o_rstd1[l]), x.P, x.n, D.d, x.G, x.S_, b.ln1g, b.ln1b, x.sc<float>(t.o_lnpart), s));
     PBT_HIP(h, layernorm_bwd(du, x.sc<bf16_t>(t.o_h[l]), x.sc<float>(t.o_mean1[l]), x.sc<float>(t.o_rstd1[l]), x.P, x.n, D.d, x.W32, x.S_, b.ln1g, dh2, dh, s));
   }
-  PBT_HIP(h, embed_bwd(dh, x.sc<int32_t>(t.o_tokens), x.Bc, D.S, D.d, D.V, x.P, x.G, x.S_, t.tok, t.pos, s));
+  PBT_HIP(h, embed_bwd(dh, x.sc<int32_t>(t.o_tokens), x.Bc, D.S, D.d, D.V, x.P, x.G, x.S_, t.tok, t.pos, x.sc<int32_t>(t.o_tokstart),
+                       x.sc<int32_t>(t.o_tokcursor), x.sc<int32_t>(t.o_tokorder), s));
   OptArgs oa{h->st<float>(p.o_w32), h->st<float>(p.o_opt0), h->st<float>(p.o_opt1), h->st<bf16_t>(p.o_w16), x.G, 0, x.S_,
              h->st<float>(p.o_hyper), h->st<int32_t>(p.o_t), x.S_, x.P, c.n_hyper, PBT_OPT_ADAM, p.col_lr, -1, -1,
              c.opt_const[0], c.opt_const[1], c.opt_const[2], c.opt_const[3]};

@@ -87,32 +87,106 @@ hipError_t embed_fwd(const int32_t* pool, int n_pool, int S, int B, int d, int V
   return hipGetLastError();
 }
 
-// dPos[s][:] = sum_b dh[b][s][:] and dTok[v][:] = sum over positions holding token v, both in a
-// fixed order (no atomics): one workgroup per (row of the table, member) scans the positions.
-__global__ __launch_bounds__(256) void embed_bwd_kernel(const bf16_t* __restrict__ dh, const int32_t* __restrict__ tokens,
-                                                        int B, int S, int d, int V, float* __restrict__ G, int64_t stride,
-                                                        int64_t tok_off, int64_t pos_off) {
+// Gradient of the embedding tables, in a fixed summation order (no floating-point atomics):
+//   1. count the positions of every token (integer atomics), 2. one workgroup per member turns the
+//   counts into list starts and files every position under its token, positions ascending,
+//   3. one workgroup per (token, member) adds up the rows of its list; tokens that do not occur get
+//   zeros.  The position table's gradient sums the B rows that share a position.
+__global__ __launch_bounds__(256) void tok_count_kernel(const int32_t* __restrict__ tokens, int n, int V, int32_t* __restrict__ start) {
   const int i = blockIdx.y;
-  const int row = blockIdx.x;  // 0..V-1: token rows; V..V+S-1: position rows
-  const int n = B * S;
-  const bf16_t* __restrict__ g = dh + (int64_t)i * n * d;
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r < n) atomicAdd(&start[(int64_t)i * (V + 1) + tokens[(int64_t)i * n + r]], 1);
+}
+
+__global__ __launch_bounds__(256) void tok_place_kernel(const int32_t* __restrict__ tokens, int n, int V, int32_t* __restrict__ start,
+                                                        int32_t* __restrict__ cursor, int32_t* __restrict__ order) {
+  __shared__ int32_t part[256];
+  __shared__ int32_t s_tok[256];
+  const int i = blockIdx.x, tid = threadIdx.x;
+  int32_t* __restrict__ st = start + (int64_t)i * (V + 1);
+  int32_t* cur = cursor + (int64_t)i * V;
   const int32_t* __restrict__ tk = tokens + (int64_t)i * n;
-  for (int c0 = threadIdx.x; c0 < d; c0 += 256) {
-    float acc = 0.f;
-    if (row < V) {
-      for (int r = 0; r < n; ++r)
-        if (tk[r] == row) acc += bf2f(g[(int64_t)r * d + c0]);
-      G[(int64_t)i * stride + tok_off + (int64_t)row * d + c0] = acc;
-    } else {
-      const int s = row - V;
-      for (int b = 0; b < B; ++b) acc += bf2f(g[((int64_t)b * S + s) * d + c0]);
-      G[(int64_t)i * stride + pos_off + (int64_t)s * d + c0] = acc;
+  int32_t* __restrict__ ord = order + (int64_t)i * n;
+  // exclusive prefix sum of the counts: a span of consecutive tokens per thread
+  const int span = (V + 255) / 256;
+  const int v0 = tid * span, v1 = min(V, v0 + span);
+  int32_t sum = 0;
+  for (int v = v0; v < v1; ++v) sum += st[v];
+  part[tid] = sum;
+  __syncthreads();
+  if (tid == 0) {
+    int32_t run = 0;
+    for (int k = 0; k < 256; ++k) { const int32_t c = part[k]; part[k] = run; run += c; }
+  }
+  __syncthreads();
+  int32_t run = part[tid];
+  for (int v = v0; v < v1; ++v) { const int32_t c = st[v]; st[v] = run; cur[v] = run; run += c; }
+  if (tid == 255) st[V] = n;
+  __syncthreads();
+  // file the positions, 256 at a time; inside a batch a position's place among equal tokens is the
+  // number of earlier positions of the batch with the same token
+  for (int base = 0; base < n; base += 256) {
+    const int r = base + tid;
+    const int32_t tok = r < n ? tk[r] : -1;
+    s_tok[tid] = tok;
+    __syncthreads();
+    int rank = 0, later = 0;
+    for (int j = 0; j < 256; ++j) {
+      const bool same = s_tok[j] == tok;
+      rank += (same && j < tid) ? 1 : 0;
+      later += (same && j > tid) ? 1 : 0;
     }
+    if (tok >= 0) ord[cur[tok] + rank] = r;
+    __syncthreads();
+    if (tok >= 0 && later == 0) cur[tok] += rank + 1;
+    __syncthreads();
   }
 }
+
+__global__ __launch_bounds__(128) void tok_sum_kernel(const bf16_t* __restrict__ dh, const int32_t* __restrict__ start,
+                                                      const int32_t* __restrict__ order, int n, int d, int V, float* __restrict__ G,
+                                                      int64_t stride, int64_t tok_off) {
+  const int v = blockIdx.x, i = blockIdx.y;
+  const int32_t b = start[(int64_t)i * (V + 1) + v], e = start[(int64_t)i * (V + 1) + v + 1];
+  const int32_t* __restrict__ ord = order + (int64_t)i * n;
+  const bf16_t* __restrict__ g = dh + (int64_t)i * n * d;
+  for (int c0 = threadIdx.x * 4; c0 < d; c0 += 512) {
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    for (int k = b; k < e; ++k) {
+      const uint2 x = *reinterpret_cast<const uint2*>(g + (int64_t)ord[k] * d + c0);
+      a0 += __uint_as_float(x.x << 16); a1 += __uint_as_float(x.x & 0xffff0000u);
+      a2 += __uint_as_float(x.y << 16); a3 += __uint_as_float(x.y & 0xffff0000u);
+    }
+    *reinterpret_cast<float4*>(G + (int64_t)i * stride + tok_off + (int64_t)v * d + c0) = make_float4(a0, a1, a2, a3);
+  }
+}
+
+__global__ __launch_bounds__(128) void pos_sum_kernel(const bf16_t* __restrict__ dh, int B, int S, int d, float* __restrict__ G,
+                                                      int64_t stride, int64_t pos_off) {
+  const int sp = blockIdx.x, i = blockIdx.y;
+  const bf16_t* __restrict__ g = dh + (int64_t)i * B * S * d;
+  for (int c0 = threadIdx.x * 4; c0 < d; c0 += 512) {
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    for (int b = 0; b < B; ++b) {
+      const uint2 x = *reinterpret_cast<const uint2*>(g + ((int64_t)b * S + sp) * d + c0);
+      a0 += __uint_as_float(x.x << 16); a1 += __uint_as_float(x.x & 0xffff0000u);
+      a2 += __uint_as_float(x.y << 16); a3 += __uint_as_float(x.y & 0xffff0000u);
+    }
+    *reinterpret_cast<float4*>(G + (int64_t)i * stride + pos_off + (int64_t)sp * d + c0) = make_float4(a0, a1, a2, a3);
+  }
+}
+
+// start: int32 [P][V + 1], cursor: int32 [P][V], order: int32 [P][B * S] (scratch)
 hipError_t embed_bwd(const bf16_t* dh, const int32_t* tokens, int B, int S, int d, int V, int P, float* G, int64_t stride,
-                     int64_t tok_off, int64_t pos_off, hipStream_t s) {
-  hipLaunchKernelGGL(embed_bwd_kernel, dim3(V + S, P), dim3(256), 0, s, dh, tokens, B, S, d, V, G, stride, tok_off, pos_off);
+                     int64_t tok_off, int64_t pos_off, int32_t* start, int32_t* cursor, int32_t* order, hipStream_t s) {
+  const int n = B * S;
+  if (d % 4) return hipErrorInvalidValue;
+  hipError_t e = fill_u32(reinterpret_cast<uint32_t*>(start), 0u, (int64_t)P * (V + 1), s);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(tok_count_kernel, dim3((n + 255) / 256, P), dim3(256), 0, s, tokens, n, V, start);
+  hipLaunchKernelGGL(tok_place_kernel, dim3(P), dim3(256), 0, s, tokens, n, V, start, cursor, order);
+  hipLaunchKernelGGL(tok_sum_kernel, dim3(V, P), dim3(128), 0, s, dh, start, order, n, d, V, G, stride, tok_off);
+  hipLaunchKernelGGL(pos_sum_kernel, dim3(S, P), dim3(128), 0, s, dh, B, S, d, G, stride, pos_off);
   return hipGetLastError();
 }
 
@@ -178,19 +252,21 @@ hipError_t layernorm_bwd(const bf16_t* dy, const bf16_t* x, const float* mean, c
   return hipGetLastError();
 }
 
-// dg[c] = sum_r dy[r][c] xhat[r][c], db[c] = sum_r dy[r][c]; 64 columns per workgroup, 4 row groups of
-// 64 threads, partial sums combined through LDS in a fixed order.
+// dg[c] = sum_r dy[r][c] xhat[r][c], db[c] = sum_r dy[r][c].  Two passes with a fixed summation order:
+// a workgroup covers 64 columns of one slab of rows (4 row groups of 64 threads, combined through
+// LDS) and writes a partial sum; a second kernel adds the slabs' partial sums in slab order.
 __global__ __launch_bounds__(256) void layernorm_param_grad_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x,
                                                                    const float* __restrict__ mean, const float* __restrict__ rstd,
-                                                                   int rows_per_member, int d, float* __restrict__ G, int64_t stride,
-                                                                   int64_t g_off, int64_t b_off) {
+                                                                   int rows_per_member, int d, int rows_per_slab,
+                                                                   float* __restrict__ part) {
   __shared__ float pg[4][64], pb[4][64];
-  const int i = blockIdx.y;
+  const int i = blockIdx.z, slab = blockIdx.y, n_slabs = gridDim.y;
   const int cl = threadIdx.x & 63, rg = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + cl;
+  const int r_end = min(rows_per_member, (slab + 1) * rows_per_slab);
   float ag = 0.f, ab = 0.f;
   if (c < d) {
-    for (int r = rg; r < rows_per_member; r += 4) {
+    for (int r = slab * rows_per_slab + rg; r < r_end; r += 4) {
       const int64_t row = (int64_t)i * rows_per_member + r;
       const float v = bf2f(dy[row * d + c]);
       ab += v;
@@ -201,91 +277,156 @@ __global__ __launch_bounds__(256) void layernorm_param_grad_kernel(const bf16_t*
   pb[rg][cl] = ab;
   __syncthreads();
   if (rg == 0 && c < d) {
-    G[(int64_t)i * stride + g_off + c] = ((pg[0][cl] + pg[1][cl]) + pg[2][cl]) + pg[3][cl];
-    G[(int64_t)i * stride + b_off + c] = ((pb[0][cl] + pb[1][cl]) + pb[2][cl]) + pb[3][cl];
+    float* __restrict__ out = part + ((int64_t)i * n_slabs + slab) * 2 * d;
+    out[c] = ((pg[0][cl] + pg[1][cl]) + pg[2][cl]) + pg[3][cl];
+    out[d + c] = ((pb[0][cl] + pb[1][cl]) + pb[2][cl]) + pb[3][cl];
   }
 }
+__global__ __launch_bounds__(256) void layernorm_param_combine_kernel(const float* __restrict__ part, int n_slabs, int d,
+                                                                      float* __restrict__ G, int64_t stride, int64_t g_off, int64_t b_off) {
+  const int i = blockIdx.y;
+  const int c = blockIdx.x * 256 + threadIdx.x;  // 0..2d-1: gains, then biases
+  if (c >= 2 * d) return;
+  float acc = 0.f;
+  for (int k = 0; k < n_slabs; ++k) acc += part[((int64_t)i * n_slabs + k) * 2 * d + c];
+  G[(int64_t)i * stride + (c < d ? g_off + c : b_off + c - d)] = acc;
+}
+// part: float [P][LN_MAX_SLABS][2][d] (scratch)
 hipError_t layernorm_param_grad(const bf16_t* dy, const bf16_t* x, const float* mean, const float* rstd, int P, int rows, int d,
-                                float* G, int64_t stride, int64_t g_off, int64_t b_off, hipStream_t s) {
-  hipLaunchKernelGGL(layernorm_param_grad_kernel, dim3((d + 63) / 64, P), dim3(256), 0, s, dy, x, mean, rstd, rows, d, G, stride, g_off, b_off);
+                                float* G, int64_t stride, int64_t g_off, int64_t b_off, float* part, hipStream_t s) {
+  int n_slabs = (rows + 127) / 128;
+  if (n_slabs > LN_MAX_SLABS) n_slabs = LN_MAX_SLABS;
+  const int rows_per_slab = (rows + n_slabs - 1) / n_slabs;
+  hipLaunchKernelGGL(layernorm_param_grad_kernel, dim3((d + 63) / 64, n_slabs, P), dim3(256), 0, s, dy, x, mean, rstd, rows, d,
+                     rows_per_slab, part);
+  hipLaunchKernelGGL(layernorm_param_combine_kernel, dim3((2 * d + 255) / 256, P), dim3(256), 0, s, part, n_slabs, d, G, stride, g_off, b_off);
   return hipGetLastError();
 }
 
 // ---- causal softmax with dropout -------------------------------------------------------------
-// One wavefront per row of the [P][B][H][S][S] score array.  p = softmax over positions <= t of
-// score * scale; writes p (kept for the backward pass) and p * keep (the operand of P V).
+// Rows of the [P][B][H][S][S] score array; LPR lanes share a row (64 / LPR rows per wavefront) and each
+// lane owns runs of four consecutive keys, i.e. one Philox counter and 8-byte accesses.
+// p = softmax over positions <= t of score * scale; writes p (kept for the backward pass) and
+// p * keep (the operand of P V).
+template <int LPR> __device__ __forceinline__ float group_max(float v) {
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+template <int LPR> __device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ __forceinline__ void unpack4(uint2 x, float* v) {
+  v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xffff0000u);
+  v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xffff0000u);
+}
+__device__ __forceinline__ uint2 pack4(const float* v) {
+  return make_uint2(f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16), f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16));
+}
+
+template <int LPR>
 __global__ __launch_bounds__(256) void softmax_fwd_kernel(const bf16_t* __restrict__ sc, int64_t rows_per_member, int S, float scale,
                                                           DropArgs d, int site, bf16_t* __restrict__ pq, bf16_t* __restrict__ pd) {
+  constexpr int RPW = 64 / LPR;
   const int i = blockIdx.y;
-  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
+  const int lane = threadIdx.x & 63, l = lane % LPR;
+  const int64_t r = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / LPR;
   if (r >= rows_per_member) return;
   const int t = (int)(r % S);  // query position: attends to keys 0..t
   const int64_t base = ((int64_t)i * rows_per_member + r) * S;
   const DropRate dr = drop_rate(d.H, d.n_hyper, d.col, i, d.active);
   float mx = -INFINITY;
-  for (int c = lane; c <= t; c += 64) mx = fmaxf(mx, bf2f(sc[base + c]) * scale);
-  mx = wave_max(mx);
-  float se = 0.f;
-  for (int c = lane; c <= t; c += 64) se += expf(bf2f(sc[base + c]) * scale - mx);
-  const float inv = 1.f / wave_sum(se);
-  for (int c = lane; c < S; c += 64) {
-    float p = 0.f;
-    if (c <= t) p = expf(bf2f(sc[base + c]) * scale - mx) * inv;
-    float keep = dr.scale;
-    if (dr.thr) {
-      const uint64_t e = (uint64_t)r * S + c;  // element index inside the member's site array
-      float f[4];
-      drop_factors4(d, dr, i, site, (uint32_t)(e >> 2), f);
-      keep = f[e & 3];
-    }
-    pq[base + c] = f2bf(p);
-    pd[base + c] = f2bf(p * keep);
+  for (int c = l * 4; c <= t; c += LPR * 4) {
+    float v[4];
+    unpack4(*reinterpret_cast<const uint2*>(sc + base + c), v);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) if (c + k <= t) mx = fmaxf(mx, v[k] * scale);
   }
-}
-hipError_t softmax_fwd(const bf16_t* sc, int P, int64_t rows, int S, float scale, const DropArgs& d, int site, bf16_t* pq,
-                       bf16_t* pd, hipStream_t s) {
-  hipLaunchKernelGGL(softmax_fwd_kernel, dim3((unsigned)((rows + 3) / 4), P), dim3(256), 0, s, sc, rows, S, scale, d, site, pq, pd);
-  return hipGetLastError();
+  mx = group_max<LPR>(mx);
+  float se = 0.f;
+  for (int c = l * 4; c <= t; c += LPR * 4) {
+    float v[4];
+    unpack4(*reinterpret_cast<const uint2*>(sc + base + c), v);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) if (c + k <= t) se += expf(v[k] * scale - mx);
+  }
+  const float inv = 1.f / group_sum<LPR>(se);
+  for (int c = l * 4; c < S; c += LPR * 4) {
+    float p[4] = {0.f, 0.f, 0.f, 0.f}, f[4];
+    if (c <= t) {
+      float v[4];
+      unpack4(*reinterpret_cast<const uint2*>(sc + base + c), v);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) if (c + k <= t) p[k] = expf(v[k] * scale - mx) * inv;
+    }
+    drop_factors4(d, dr, i, site, (uint32_t)(((uint64_t)r * S + c) >> 2), f);
+    *reinterpret_cast<uint2*>(pq + base + c) = pack4(p);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) p[k] *= f[k];
+    *reinterpret_cast<uint2*>(pd + base + c) = pack4(p);
+  }
 }
 
 // ds = p (dp - sum_c dp p) * scale with dp = dpd * keep; in place over dpd.
+template <int LPR>
 __global__ __launch_bounds__(256) void softmax_bwd_kernel(const bf16_t* __restrict__ pq, bf16_t* __restrict__ dpd, int64_t rows_per_member,
                                                           int S, float scale, DropArgs d, int site) {
+  constexpr int RPW = 64 / LPR;
   const int i = blockIdx.y;
-  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
+  const int lane = threadIdx.x & 63, l = lane % LPR;
+  const int64_t r = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / LPR;
   if (r >= rows_per_member) return;
+  const int t = (int)(r % S);
   const int64_t base = ((int64_t)i * rows_per_member + r) * S;
   const DropRate dr = drop_rate(d.H, d.n_hyper, d.col, i, d.active);
+  // p is zero beyond the diagonal, so the dot product and the non-zero results stop there
   float dot = 0.f;
-  for (int c = lane; c < S; c += 64) {
-    float keep = dr.scale;
-    if (dr.thr) {
-      const uint64_t e = (uint64_t)r * S + c;
-      float f[4];
-      drop_factors4(d, dr, i, site, (uint32_t)(e >> 2), f);
-      keep = f[e & 3];
-    }
-    dot = fmaf(bf2f(dpd[base + c]) * keep, bf2f(pq[base + c]), dot);
+  for (int c = l * 4; c <= t; c += LPR * 4) {
+    float p[4], g[4], f[4];
+    unpack4(*reinterpret_cast<const uint2*>(pq + base + c), p);
+    unpack4(*reinterpret_cast<const uint2*>(dpd + base + c), g);
+    drop_factors4(d, dr, i, site, (uint32_t)(((uint64_t)r * S + c) >> 2), f);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) dot = fmaf(g[k] * f[k], p[k], dot);
   }
-  dot = wave_sum(dot);
-  for (int c = lane; c < S; c += 64) {
-    float keep = dr.scale;
-    if (dr.thr) {
-      const uint64_t e = (uint64_t)r * S + c;
-      float f[4];
-      drop_factors4(d, dr, i, site, (uint32_t)(e >> 2), f);
-      keep = f[e & 3];
+  dot = group_sum<LPR>(dot);
+  for (int c = l * 4; c < S; c += LPR * 4) {
+    float o[4] = {0.f, 0.f, 0.f, 0.f};
+    if (c <= t) {
+      float p[4], g[4], f[4];
+      unpack4(*reinterpret_cast<const uint2*>(pq + base + c), p);
+      unpack4(*reinterpret_cast<const uint2*>(dpd + base + c), g);
+      drop_factors4(d, dr, i, site, (uint32_t)(((uint64_t)r * S + c) >> 2), f);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) o[k] = p[k] * (g[k] * f[k] - dot) * scale;
     }
-    const float p = bf2f(pq[base + c]);
-    dpd[base + c] = f2bf(p * (bf2f(dpd[base + c]) * keep - dot) * scale);
+    *reinterpret_cast<uint2*>(dpd + base + c) = pack4(o);
   }
+}
+
+template <int LPR>
+static void launch_softmax(bool fwd, const bf16_t* a, bf16_t* b, bf16_t* c, int P, int64_t rows, int S, float scale, const DropArgs& d, int site, hipStream_t s) {
+  const int64_t rows_per_block = 4 * (64 / LPR);
+  const dim3 grid((unsigned)((rows + rows_per_block - 1) / rows_per_block), P);
+  if (fwd) hipLaunchKernelGGL(softmax_fwd_kernel<LPR>, grid, dim3(256), 0, s, a, rows, S, scale, d, site, b, c);
+  else hipLaunchKernelGGL(softmax_bwd_kernel<LPR>, grid, dim3(256), 0, s, a, b, rows, S, scale, d, site);
+}
+static hipError_t softmax_dispatch(bool fwd, const bf16_t* a, bf16_t* b, bf16_t* c, int P, int64_t rows, int S, float scale, const DropArgs& d, int site, hipStream_t s) {
+  if (S % 4) return hipErrorInvalidValue;
+  if (S <= 64) launch_softmax<16>(fwd, a, b, c, P, rows, S, scale, d, site, s);
+  else if (S <= 128) launch_softmax<32>(fwd, a, b, c, P, rows, S, scale, d, site, s);
+  else launch_softmax<64>(fwd, a, b, c, P, rows, S, scale, d, site, s);
+  return hipGetLastError();
+}
+hipError_t softmax_fwd(const bf16_t* sc, int P, int64_t rows, int S, float scale, const DropArgs& d, int site, bf16_t* pq,
+                       bf16_t* pd, hipStream_t s) {
+  return softmax_dispatch(true, sc, pq, pd, P, rows, S, scale, d, site, s);
 }
 hipError_t softmax_bwd(const bf16_t* pq, bf16_t* dpd, int P, int64_t rows, int S, float scale, const DropArgs& d, int site,
                        hipStream_t s) {
-  hipLaunchKernelGGL(softmax_bwd_kernel, dim3((unsigned)((rows + 3) / 4), P), dim3(256), 0, s, pq, dpd, rows, S, scale, d, site);
-  return hipGetLastError();
+  return softmax_dispatch(false, pq, dpd, nullptr, P, rows, S, scale, d, site, s);
 }
 
 // ---- dropout / residual ----------------------------------------------------------------------
@@ -360,9 +501,86 @@ __global__ __launch_bounds__(256) void xent_kernel(const float* __restrict__ log
       dl[c] = f2bf((expf(l[c] - mx) * inv - u - (c == y ? 1.f - eps : 0.f)) * gscale);
   }
 }
+// The same with the whole row held in registers (V <= 2048 G, V a multiple of 8): every thread owns G
+// runs of 8 consecutive logits, so the row is read once with 16-byte loads and the gradient leaves in
+// 16-byte stores.
+template <int G>
+__global__ __launch_bounds__(256) void xent_rowreg_kernel(const float* __restrict__ logits, const int32_t* __restrict__ targets, int rows_per_member,
+                                                          int V, const float* __restrict__ H, int n_hyper, int col_ls, int use_ls, float gscale,
+                                                          bf16_t* __restrict__ dlogits, float* __restrict__ rowloss) {
+  __shared__ float red[4];
+  const int i = blockIdx.y;
+  const int64_t row = (int64_t)i * rows_per_member + blockIdx.x;
+  const float* __restrict__ l = logits + row * V;
+  const float eps = (use_ls && col_ls >= 0) ? H[(int64_t)i * n_hyper + col_ls] : 0.f;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float v[G][8];
+  float mx = -INFINITY, sl = 0.f;
+#pragma unroll
+  for (int j = 0; j < G; ++j) {
+    const int c0 = (j * 256 + threadIdx.x) * 8;
+    if (c0 < V) {
+      const float4 a = *reinterpret_cast<const float4*>(l + c0), b = *reinterpret_cast<const float4*>(l + c0 + 4);
+      v[j][0] = a.x; v[j][1] = a.y; v[j][2] = a.z; v[j][3] = a.w; v[j][4] = b.x; v[j][5] = b.y; v[j][6] = b.z; v[j][7] = b.w;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { mx = fmaxf(mx, v[j][k]); sl += v[j][k]; }
+    }
+  }
+  mx = wave_max(mx);
+  if (lane == 0) red[wave] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float se = 0.f;
+#pragma unroll
+  for (int j = 0; j < G; ++j) {
+    if ((j * 256 + threadIdx.x) * 8 < V) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { v[j][k] = expf(v[j][k] - mx); se += v[j][k]; }
+    }
+  }
+  se = wave_sum(se);
+  if (lane == 0) red[wave] = se;
+  __syncthreads();
+  se = ((red[0] + red[1]) + red[2]) + red[3];
+  __syncthreads();
+  sl = wave_sum(sl);
+  if (lane == 0) red[wave] = sl;
+  __syncthreads();
+  sl = ((red[0] + red[1]) + red[2]) + red[3];
+  const int y = targets[row];
+  if (threadIdx.x == 0) rowloss[row] = mx + logf(se) - (1.f - eps) * l[y] - eps * (sl / (float)V);
+  if (dlogits) {
+    const float inv = 1.f / se, u = eps / (float)V;
+    bf16_t* __restrict__ dl = dlogits + row * V;
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const int c0 = (j * 256 + threadIdx.x) * 8;
+      if (c0 < V) {
+        uint32_t w[4];
+#pragma unroll
+        for (int k = 0; k < 8; k += 2) {
+          const float g0 = (v[j][k] * inv - u - (c0 + k == y ? 1.f - eps : 0.f)) * gscale;
+          const float g1 = (v[j][k + 1] * inv - u - (c0 + k + 1 == y ? 1.f - eps : 0.f)) * gscale;
+          w[k / 2] = f2bf(g0) | ((uint32_t)f2bf(g1) << 16);
+        }
+        *reinterpret_cast<uint4*>(dl + c0) = make_uint4(w[0], w[1], w[2], w[3]);
+      }
+    }
+  }
+}
+
 hipError_t xent_rows(const float* logits, const int32_t* targets, int P, int rows, int V, const float* H, int n_hyper, int col_ls,
                      int use_ls, float gscale, bf16_t* dlogits, float* rowloss, hipStream_t s) {
-  hipLaunchKernelGGL(xent_kernel, dim3(rows, P), dim3(256), 0, s, logits, targets, rows, V, H, n_hyper, col_ls, use_ls, gscale, dlogits, rowloss);
+  const dim3 grid(rows, P), block(256);
+  if (V % 8 == 0 && V <= 2048)
+    hipLaunchKernelGGL(xent_rowreg_kernel<1>, grid, block, 0, s, logits, targets, rows, V, H, n_hyper, col_ls, use_ls, gscale, dlogits, rowloss);
+  else if (V % 8 == 0 && V <= 4096)
+    hipLaunchKernelGGL(xent_rowreg_kernel<2>, grid, block, 0, s, logits, targets, rows, V, H, n_hyper, col_ls, use_ls, gscale, dlogits, rowloss);
+  else if (V % 8 == 0 && V <= 8192)
+    hipLaunchKernelGGL(xent_rowreg_kernel<4>, grid, block, 0, s, logits, targets, rows, V, H, n_hyper, col_ls, use_ls, gscale, dlogits, rowloss);
+  else
+    hipLaunchKernelGGL(xent_kernel, grid, block, 0, s, logits, targets, rows, V, H, n_hyper, col_ls, use_ls, gscale, dlogits, rowloss);
   return hipGetLastError();
 }
 
