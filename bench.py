@@ -18,9 +18,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 
 # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counters, scaled by what the same counters read
-# for a copy of known size (profiles/population_step_mlp_wide_bf16_hbm_counters.md).  An entry is only
-# valid for the kernel as it was when the counters were taken; set it to None when the kernel changes.
-MEASURED_TRAFFIC_BYTES = {"optimizer": 2.574e9, "gemm_wgrad": None}
+# for a copy of known size (profiles/population_step_<workload>_hbm_counters.md), by (workload, kernel
+# class).  An entry is only valid for the kernel as it was when the counters were taken; remove it when
+# the kernel changes.
+MEASURED_TRAFFIC_BYTES = {(2, "optimizer"): 2.541e9, (4, "optimizer"): 10.115e9}
 
 
 def cpu_baseline(wl, data, seed, budget_s=15.0):
@@ -176,7 +177,7 @@ def main():
         else:
             ach, peak, unit = work / avg_s / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
         roofline = {"kernel": args.kernel, "bound": bound, "achieved": ach, "peak": peak, "unit": unit,
-                    "frac": ach / peak, "traffic": MEASURED_TRAFFIC_BYTES.get(args.kernel) if args.workload == 2 else None, "avg_launch_us": avg_s * 1e6, "launches": k_n,
+                    "frac": ach / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.kernel)), "avg_launch_us": avg_s * 1e6, "launches": k_n,
                     "work_per_launch": work}
 
     out = {
