@@ -40,14 +40,13 @@ hipError_t gemm_wgrad_optimizer(const GemmOperands& o, const OptArgs& a, int64_t
 
 hipError_t gemm_rbf_sum(const GemmOperands& o, const float* na, int64_t sna, const float* nb, int64_t snb, float inv2d,
                         float* partial, int* tiles, hipStream_t s) {
-  // tile count as launch_gemm_bf16 will choose it (the caller sizes `partial` with gemm_rbf_tiles)
-  *tiles = gemm_rbf_tiles(o.M, o.N, o.batch);
+  // tile count as launch_gemm_bf16 will choose it (the caller sizes `partial` with gemm_rbf_tiles, an upper bound)
+  const TileShape t = tile_shape(choose_tile(o.M, o.N, o.K, o.batch));
+  *tiles = ((o.M + t.bm - 1) / t.bm) * ((o.N + t.bn - 1) / t.bn);
   return run(o, EpiRbfSum{na, sna, nb, snb, inv2d, partial, 0.f}, s);
 }
-int gemm_rbf_tiles(int M, int N, int batch) {
-  const int64_t wide = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
-  const int bn = ((wide < 4 * 256 && N > 64) || (N <= 64 && N > 32)) ? 64 : 128;
-  return ((M + 127) / 128) * ((N + bn - 1) / bn);
+int gemm_rbf_tiles(int M, int N, int) {
+  return ((M + 127) / 128) * ((N + 63) / 64);  // the smallest tile gives the most partial sums
 }
 
 }  // namespace pbt

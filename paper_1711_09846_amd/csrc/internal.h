@@ -30,7 +30,7 @@ hipError_t gemm_dgrad_act(const GemmOperands& o, const bf16_t* Zprev, bf16_t* dZ
                           hipStream_t s);
 
 // Per-member sum over the whole M x N Gram matrix of exp(-(na[m] + nb[n] - 2 a_m.b_n) * inv2d), as
-// per-tile partial sums partial[batch][tiles] (tiles = gemm_rbf_tiles(M, N, batch)).
+// per-tile partial sums partial[batch][*tiles]; gemm_rbf_tiles(M, N, batch) is an upper bound of *tiles for sizing `partial`.
 int gemm_rbf_tiles(int M, int N, int batch);
 hipError_t gemm_rbf_sum(const GemmOperands& o, const float* na, int64_t sna, const float* nb, int64_t snb, float inv2d,
                         float* partial, int* tiles, hipStream_t s);
