@@ -8,11 +8,15 @@ namespace pbt {
 typedef uint16_t bf16_t;  // raw bfloat16 bits
 
 // Round-to-nearest-even float -> bfloat16 (NaN kept quiet).
-__device__ __forceinline__ bf16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+// float -> bf16, round to nearest even: the matrix-core generation has a conversion instruction
+// (v_cvt_pk_bf16_f32), which the compiler emits for these casts
+__device__ __forceinline__ bf16_t f2bf(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+// two at once: lo in bits 0..15, hi in bits 16..31
+__device__ __forceinline__ uint32_t f2bf_pair(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 

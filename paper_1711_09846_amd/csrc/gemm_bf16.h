@@ -337,12 +337,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
 // accumulator values of C[m][n .. n+count-1].  Full, 16-byte aligned runs use vector accesses.
 
 __device__ __forceinline__ uint4 pack_bf16x8(const float* v) {
-  uint4 p;
-  p.x = f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
-  p.y = f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
-  p.z = f2bf(v[4]) | ((uint32_t)f2bf(v[5]) << 16);
-  p.w = f2bf(v[6]) | ((uint32_t)f2bf(v[7]) << 16);
-  return p;
+  return make_uint4(f2bf_pair(v[0], v[1]), f2bf_pair(v[2], v[3]), f2bf_pair(v[4], v[5]), f2bf_pair(v[6], v[7]));
 }
 __device__ __forceinline__ void unpack_bf16x8(uint4 p, float* v) {
   const uint32_t w[4] = {p.x, p.y, p.z, p.w};
@@ -362,13 +357,15 @@ __device__ __forceinline__ void store_bf16_run(bf16_t* dst, const float* v, int 
   }
 }
 
+// Every functor's begin(member) moves its pointers to the member's arrays once, so that apply8 is
+// left with m * pitch + n.
 struct EpiStoreF32 {
   static constexpr bool HAS_FINISH = false;
-  __device__ __forceinline__ void begin(int) {}
   float* C;
   int64_t ldc, sc;
-  __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) const {
-    float* dst = C + (int64_t)member * sc + (int64_t)m * ldc + n;
+  __device__ __forceinline__ void begin(int member) { C += (int64_t)member * sc; }
+  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count) const {
+    float* dst = C + (int64_t)m * ldc + n;
     if (count == 8 && aligned16(dst)) {
       *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
       *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
@@ -380,27 +377,27 @@ struct EpiStoreF32 {
 
 struct EpiStoreBF16 {
   static constexpr bool HAS_FINISH = false;
-  __device__ __forceinline__ void begin(int) {}
   bf16_t* C;
   int64_t ldc, sc;
   int inner = 1;       // two-level batch index as in GemmArgs
   int64_t sc_in = 0;
-  __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) const {
-    store_bf16_run(C + (int64_t)(member / inner) * sc + (int64_t)(member % inner) * sc_in + (int64_t)m * ldc + n, v, count);
+  __device__ __forceinline__ void begin(int member) { C += (int64_t)(member / inner) * sc + (int64_t)(member % inner) * sc_in; }
+  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count) const {
+    store_bf16_run(C + (int64_t)m * ldc + n, v, count);
   }
 };
 
 // Output layer over a large vocabulary: logits = acc + b[n], kept in float.
 struct EpiBiasF32 {
   static constexpr bool HAS_FINISH = false;
-  __device__ __forceinline__ void begin(int) {}
   const float* bias;
   int64_t sbias;
   float* C;
   int64_t ldc, sc;
-  __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) const {
-    const float* b = bias + (int64_t)member * sbias + n;
-    float* dst = C + (int64_t)member * sc + (int64_t)m * ldc + n;
+  __device__ __forceinline__ void begin(int member) { bias += (int64_t)member * sbias; C += (int64_t)member * sc; }
+  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count) const {
+    const float* b = bias + n;
+    float* dst = C + (int64_t)m * ldc + n;
     if (count == 8 && aligned16(dst)) {
       *reinterpret_cast<float4*>(dst) = make_float4(v[0] + b[0], v[1] + b[1], v[2] + b[2], v[3] + b[3]);
       *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4] + b[4], v[5] + b[5], v[6] + b[6], v[7] + b[7]);
@@ -413,22 +410,26 @@ struct EpiBiasF32 {
 // Forward layer: z = acc + b[n]; stores z (for the backward pass, may be null) and act(z), both bf16.
 struct EpiBiasAct {
   static constexpr bool HAS_FINISH = false;
-  __device__ __forceinline__ void begin(int) {}
   const float* bias;  // + member * sbias + n
   int64_t sbias;
   bf16_t* Z;
   bf16_t* Aout;
   int64_t ld, so;
   int act;
-  __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) const {
-    const float* b = bias + (int64_t)member * sbias + n;
+  __device__ __forceinline__ void begin(int member) {
+    bias += (int64_t)member * sbias;
+    if (Z) Z += (int64_t)member * so;
+    Aout += (int64_t)member * so;
+  }
+  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count) const {
+    const float* b = bias + n;
     float z[8], a[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       z[e] = e < count ? v[e] + b[e] : 0.f;
       a[e] = act_fwd(z[e], act);
     }
-    const int64_t o = (int64_t)member * so + (int64_t)m * ld + n;
+    const int64_t o = (int64_t)m * ld + n;
     if (Z) store_bf16_run(Z + o, z, count);
     store_bf16_run(Aout + o, a, count);
   }
@@ -437,13 +438,13 @@ struct EpiBiasAct {
 // Input gradient: dz_prev = acc * act'(z_prev), bf16.
 struct EpiDgradAct {
   static constexpr bool HAS_FINISH = false;
-  __device__ __forceinline__ void begin(int) {}
   const bf16_t* Zprev;
   bf16_t* dZ;
   int64_t ld, so;
   int act;
-  __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) const {
-    const int64_t o = (int64_t)member * so + (int64_t)m * ld + n;
+  __device__ __forceinline__ void begin(int member) { Zprev += (int64_t)member * so; dZ += (int64_t)member * so; }
+  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count) const {
+    const int64_t o = (int64_t)m * ld + n;
     float z[8], d[8];
     if (count == 8 && aligned16(Zprev + o)) {
       unpack_bf16x8(*reinterpret_cast<const uint4*>(Zprev + o), z);
@@ -467,9 +468,9 @@ struct EpiOptimizer {
   int64_t stride, off, ldc;   // member stride, offset of the matrix in the member's vector, row pitch
   OptHyper hy;
   OptScalars sc;
-  __device__ __forceinline__ void begin(int member) { sc = opt_scalars<OPT>(hy, member); }
-  __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) {
-    const int64_t o = (int64_t)member * stride + off + (int64_t)m * ldc + n;
+  __device__ __forceinline__ void begin(int member) { sc = opt_scalars<OPT>(hy, member); off += (int64_t)member * stride; }
+  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count) {
+    const int64_t o = off + (int64_t)m * ldc + n;
     float w[8], s0[8], s1[8];
     const bool vec = count == 8 && (o & 3) == 0;
     if (vec) {
@@ -567,7 +568,7 @@ hipError_t launch_gemm_tile(const GemmArgs& g0, bool a_m_contig, bool b_k_contig
 // order, and the tile's sum goes to partial[member][tile]; a later pass adds the tiles.
 struct EpiRbfSum {
   static constexpr bool HAS_FINISH = true;
-  __device__ __forceinline__ void begin(int) {}
+  __device__ __forceinline__ void begin(int member) { na += (int64_t)member * sna; nb += (int64_t)member * snb; }
   const float* na;  // squared norms of the A rows, + member * sna
   int64_t sna;
   const float* nb;
@@ -576,8 +577,8 @@ struct EpiRbfSum {
   float* partial;
   float sum;
   __device__ __forceinline__ void apply8(int member, int m, int n, const float* v, int count) {
-    const float nam = na[(int64_t)member * sna + m];
-    const float* nbn = nb + (int64_t)member * snb + n;
+    const float nam = na[m];
+    const float* nbn = nb + n;
     for (int e = 0; e < count; ++e) sum += expf(-(nam + nbn[e] - 2.f * v[e]) * inv2d);
   }
   __device__ __forceinline__ void finish(int member, int tile, int tiles) {

@@ -198,8 +198,8 @@ __global__ __launch_bounds__(256) void optimizer_kernel(OptArgs a) {
     if (OPT == OPT_ADAM) stream_store(s1, a.S1 + o);
     if (a.W16) {
       uint2 pk;
-      pk.x = f2bf(wp[0]) | ((uint32_t)f2bf(wp[1]) << 16);
-      pk.y = f2bf(wp[2]) | ((uint32_t)f2bf(wp[3]) << 16);
+      pk.x = f2bf_pair(wp[0], wp[1]);
+      pk.y = f2bf_pair(wp[2], wp[3]);
       *reinterpret_cast<uint2*>(a.W16 + o) = pk;
     }
   }
@@ -253,8 +253,8 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const float* __restric
     for (int c = threadIdx.x * 4; c < d; c += 1024) {
       const float4 v = *reinterpret_cast<const float4*>(row + c);
       uint2 pk;
-      pk.x = f2bf(v.x) | ((uint32_t)f2bf(v.y) << 16);
-      pk.y = f2bf(v.z) | ((uint32_t)f2bf(v.w) << 16);
+      pk.x = f2bf_pair(v.x, v.y);
+      pk.y = f2bf_pair(v.z, v.w);
       *reinterpret_cast<uint2*>(o + c) = pk;
     }
   } else {

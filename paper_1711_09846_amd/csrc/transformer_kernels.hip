@@ -323,7 +323,7 @@ __device__ __forceinline__ void unpack4(uint2 x, float* v) {
   v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xffff0000u);
 }
 __device__ __forceinline__ uint2 pack4(const float* v) {
-  return make_uint2(f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16), f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16));
+  return make_uint2(f2bf_pair(v[0], v[1]), f2bf_pair(v[2], v[3]));
 }
 
 template <int LPR>
@@ -562,7 +562,7 @@ __global__ __launch_bounds__(256) void xent_rowreg_kernel(const float* __restric
         for (int k = 0; k < 8; k += 2) {
           const float g0 = (v[j][k] * inv - u - (c0 + k == y ? 1.f - eps : 0.f)) * gscale;
           const float g1 = (v[j][k + 1] * inv - u - (c0 + k + 1 == y ? 1.f - eps : 0.f)) * gscale;
-          w[k / 2] = f2bf(g0) | ((uint32_t)f2bf(g1) << 16);
+          w[k / 2] = f2bf_pair(g0, g1);
         }
         *reinterpret_cast<uint4*>(dl + c0) = make_uint4(w[0], w[1], w[2], w[3]);
       }
