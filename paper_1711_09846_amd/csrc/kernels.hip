@@ -103,12 +103,15 @@ hipError_t gather_batch(const float* train_x, const int32_t* train_y, int n_trai
   return hipGetLastError();
 }
 
-// db[n] = sum_r dZ[r][n].  A workgroup covers 64 columns: 8 threads x 8 columns (one 16-byte load per
-// row) times 32 row groups; the 32 partial sums are combined through LDS in fixed order.
+// db[n] = sum_r dZ[r][n].  A workgroup covers 64 columns of one slab of rows: 8 threads x 8 columns (one
+// 16-byte load per row) times 32 row groups; the 32 partial sums are combined through LDS in fixed
+// order.  With one slab the result goes straight to db; with several (tall inputs, so that the grid
+// fills the chip) to slab_out[member][slab][n], which bias_combine_kernel adds up in slab order.
 __global__ __launch_bounds__(256) void bias_grad_kernel(const bf16_t* __restrict__ dZ, int rows, int N, int64_t ld,
-                                                        float* __restrict__ db, int64_t sg) {
+                                                        float* __restrict__ db, int64_t sg, int rows_per_slab) {
   __shared__ float part[32][65];
-  const int i = blockIdx.y;
+  const int i = blockIdx.z, slab = blockIdx.y;
+  const int r_end = min(rows, (slab + 1) * rows_per_slab);
   const int cg = threadIdx.x & 7, rg = threadIdx.x >> 3;
   const int n0 = blockIdx.x * 64 + cg * 8;
   float acc[8];
@@ -117,7 +120,7 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const bf16_t* __restrict
   if (n0 < N) {
     const bf16_t* __restrict__ p = dZ + (int64_t)i * rows * ld + n0;
     const bool full = n0 + 8 <= N;
-    for (int r = rg; r < rows; r += 32) {
+    for (int r = slab * rows_per_slab + rg; r < r_end; r += 32) {
       if (full) {
         const uint4 v = *reinterpret_cast<const uint4*>(p + (int64_t)r * ld);
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -139,12 +142,33 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const bf16_t* __restrict
     float sum = 0.f;
 #pragma unroll
     for (int g = 0; g < 32; ++g) sum += part[g][threadIdx.x];
-    if (n < N) db[(int64_t)i * sg + n] = sum;
+    if (n < N) db[((int64_t)i * gridDim.y + slab) * sg + n] = sum;
   }
 }
-hipError_t bias_grad(const bf16_t* dZ, int P, int rows, int N, int64_t ld, float* db, int64_t sg, hipStream_t s) {
+__global__ __launch_bounds__(256) void bias_combine_kernel(const float* __restrict__ part, int slabs, int N, float* __restrict__ db, int64_t sg) {
+  const int i = blockIdx.y;
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  float sum = 0.f;
+  for (int k = 0; k < slabs; ++k) sum += part[((int64_t)i * slabs + k) * N + n];
+  db[(int64_t)i * sg + n] = sum;
+}
+// part: optional scratch of P * BIAS_GRAD_MAX_SLABS * N floats; without it every member's rows are one slab
+hipError_t bias_grad(const bf16_t* dZ, int P, int rows, int N, int64_t ld, float* db, int64_t sg, hipStream_t s, float* part) {
   if (ld % 8) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(bias_grad_kernel, dim3((N + 63) / 64, P), dim3(256), 0, s, dZ, rows, N, ld, db, sg);
+  int slabs = 1;
+  if (part && (int64_t)((N + 63) / 64) * P < 2048) {
+    slabs = rows / 256;
+    if (slabs > BIAS_GRAD_MAX_SLABS) slabs = BIAS_GRAD_MAX_SLABS;
+    if (slabs < 1) slabs = 1;
+  }
+  const int rows_per_slab = (rows + slabs - 1) / slabs;
+  if (slabs == 1) {
+    hipLaunchKernelGGL(bias_grad_kernel, dim3((N + 63) / 64, 1, P), dim3(256), 0, s, dZ, rows, N, ld, db, sg, rows_per_slab);
+  } else {
+    hipLaunchKernelGGL(bias_grad_kernel, dim3((N + 63) / 64, slabs, P), dim3(256), 0, s, dZ, rows, N, ld, part, (int64_t)N, rows_per_slab);
+    hipLaunchKernelGGL(bias_combine_kernel, dim3((N + 255) / 256, P), dim3(256), 0, s, part, slabs, N, db, sg);
+  }
   return hipGetLastError();
 }
 

@@ -32,7 +32,7 @@ pbt_status dense(const Ctx& x, const bf16_t* in, int K, int N, int64_t w, int64_
 pbt_status wgrad(const Ctx& x, const bf16_t* in, int K, const bf16_t* dout, int N, int64_t w, int64_t b) {
   GemmOperands o{in, K, (int64_t)x.n * K, true, dout, N, (int64_t)x.n * N, false, K, N, x.n, x.P};
   PBT_LAUNCH(x.h, PBT_K_GEMM_WGRAD, x.s, gemm_store_f32(o, x.G + w, N, x.S_, x.s));
-  PBT_LAUNCH(x.h, PBT_K_BIAS_GRAD, x.s, bias_grad(dout, x.P, x.n, N, N, x.G + b, x.S_, x.s));
+  PBT_LAUNCH(x.h, PBT_K_BIAS_GRAD, x.s, bias_grad(dout, x.P, x.n, N, N, x.G + b, x.S_, x.s, x.sc<float>(x.h->plan.tf.o_biaspart)));
   return PBT_OK;
 }
 // din[P][n][K] = dout[P][n][N] W^T   (optionally times act'(zprev))
@@ -91,8 +91,9 @@ pbt_status forward(const Ctx& x, const int32_t* pool, int n_pool, uint32_t c0, i
     PBT_HIP(h, dropout_apply(tmp_d, hin, x.P, per_d, dr, 4 * l + 1, hmid, x.s));
     bf16_t* u2 = x.sc<bf16_t>(t.o_u2[l]);
     PBT_HIP(h, layernorm_fwd(hmid, x.P, x.n, D.d, x.W32, x.S_, b.ln2g, b.ln2b, u2, x.sc<float>(t.o_mean2[l]), x.sc<float>(t.o_rstd2[l]), x.s));
-    TF_TRY(dense(x, u2, D.d, D.f, b.w1, b.b1, x.sc<bf16_t>(t.o_z1[l]), tmp_f, PBT_ACT_RELU));
-    PBT_HIP(h, dropout_apply(tmp_f, nullptr, x.P, per_f, dr, 4 * l + 2, x.sc<bf16_t>(t.o_fd[l]), x.s));
+    // only relu(z) is kept: it is positive exactly where z is, which is all the backward pass needs
+    TF_TRY(dense(x, u2, D.d, D.f, b.w1, b.b1, nullptr, x.sc<bf16_t>(t.o_z1[l]), PBT_ACT_RELU));
+    PBT_HIP(h, dropout_apply(x.sc<bf16_t>(t.o_z1[l]), nullptr, x.P, per_f, dr, 4 * l + 2, x.sc<bf16_t>(t.o_fd[l]), x.s));
     TF_TRY(dense(x, x.sc<bf16_t>(t.o_fd[l]), D.f, D.d, b.w2, b.b2, nullptr, tmp_d, PBT_ACT_NONE));
     PBT_HIP(h, dropout_apply(tmp_d, hmid, x.P, per_d, dr, 4 * l + 3, hout, x.s));
   }
@@ -173,6 +174,11 @@ pbt_status tf_check_and_plan(const pbt_config* c, Plan* pl, Carver* w) {
   t.o_tokcursor = w->take(P * (size_t)D.V * 4);
   t.o_tokorder = w->take(P * n * 4);
   t.o_lnpart = w->take(P * (size_t)LN_MAX_SLABS * 2 * D.d * 4);
+  {
+    size_t widest = D.V > D.f ? D.V : D.f;
+    if (widest < 3 * (size_t)D.d) widest = 3 * (size_t)D.d;
+    t.o_biaspart = w->take(P * (size_t)BIAS_GRAD_MAX_SLABS * widest * 4);
+  }
   return PBT_OK;
 }
 

@@ -191,8 +191,24 @@ hipError_t embed_bwd(const bf16_t* dh, const int32_t* tokens, int B, int S, int 
 }
 
 // ---- LayerNorm -------------------------------------------------------------------------------
-// One wavefront per row.  y = (x - mean) * rstd * g + b, eps = 1e-5; mean and rstd are kept.
+// One wavefront per row, eight consecutive elements (one 16-byte access) per lane and pass; a row
+// is at most a few KB, so the second and third pass over it are served by the caches.
+// y = (x - mean) * rstd * g + b, eps = 1e-5; mean and rstd are kept.
 constexpr float LN_EPS = 1e-5f;
+__device__ __forceinline__ void load8(const bf16_t* p, float* v) {
+  const uint4 u = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+  for (int q = 0; q < 4; ++q) { v[2 * q] = __uint_as_float(w[q] << 16); v[2 * q + 1] = __uint_as_float(w[q] & 0xffff0000u); }
+}
+__device__ __forceinline__ void load8(const float* p, float* v) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void store8(bf16_t* p, const float* v) {
+  *reinterpret_cast<uint4*>(p) = make_uint4(f2bf_pair(v[0], v[1]), f2bf_pair(v[2], v[3]), f2bf_pair(v[4], v[5]), f2bf_pair(v[6], v[7]));
+}
+
 __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const bf16_t* __restrict__ x, int rows_per_member, int d,
                                                             const float* __restrict__ W32, int64_t stride, int64_t g_off,
                                                             int64_t b_off, bf16_t* __restrict__ y, float* __restrict__ mean,
@@ -203,18 +219,37 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const bf16_t* __rest
   const int64_t row = (int64_t)i * rows_per_member + r;
   const bf16_t* __restrict__ xr = x + row * d;
   float s = 0.f;
-  for (int c = lane; c < d; c += 64) s += bf2f(xr[c]);
+  for (int c = lane * 8; c < d; c += 512) {
+    float v[8];
+    load8(xr + c, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += v[e];
+  }
   const float mu = wave_sum(s) / (float)d;
-  float v = 0.f;
-  for (int c = lane; c < d; c += 64) { const float t = bf2f(xr[c]) - mu; v = fmaf(t, t, v); }
-  const float rs = rsqrtf(wave_sum(v) / (float)d + LN_EPS);
+  float var = 0.f;
+  for (int c = lane * 8; c < d; c += 512) {
+    float v[8];
+    load8(xr + c, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { const float t = v[e] - mu; var = fmaf(t, t, var); }
+  }
+  const float rs = rsqrtf(wave_sum(var) / (float)d + LN_EPS);
   const float* __restrict__ g = W32 + (int64_t)i * stride + g_off;
   const float* __restrict__ b = W32 + (int64_t)i * stride + b_off;
-  for (int c = lane; c < d; c += 64) y[row * d + c] = f2bf((bf2f(xr[c]) - mu) * rs * g[c] + b[c]);
+  for (int c = lane * 8; c < d; c += 512) {
+    float v[8], gv[8], bv[8];
+    load8(xr + c, v);
+    load8(g + c, gv);
+    load8(b + c, bv);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (v[e] - mu) * rs * gv[e] + bv[e];
+    store8(y + row * d + c, v);
+  }
   if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
 }
 hipError_t layernorm_fwd(const bf16_t* x, int P, int rows, int d, const float* W32, int64_t stride, int64_t g_off, int64_t b_off,
                          bf16_t* y, float* mean, float* rstd, hipStream_t s) {
+  if (d % 8 || g_off % 4 || b_off % 4 || stride % 4) return hipErrorInvalidValue;
   hipLaunchKernelGGL(layernorm_fwd_kernel, dim3((rows + 3) / 4, P), dim3(256), 0, s, x, rows, d, W32, stride, g_off, b_off, y, mean, rstd);
   return hipGetLastError();
 }
@@ -232,22 +267,42 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
   const float mu = mean[row], rs = rstd[row];
   const float* __restrict__ g = W32 + (int64_t)i * stride + g_off;
   float a = 0.f, b = 0.f;
-  for (int c = lane; c < d; c += 64) {
-    const float dyg = bf2f(dy[row * d + c]) * g[c];
-    a += dyg;
-    b = fmaf(dyg, (bf2f(x[row * d + c]) - mu) * rs, b);
+  for (int c = lane * 8; c < d; c += 512) {
+    float dv[8], xv[8], gv[8];
+    load8(dy + row * d + c, dv);
+    load8(x + row * d + c, xv);
+    load8(g + c, gv);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float dyg = dv[e] * gv[e];
+      a += dyg;
+      b = fmaf(dyg, (xv[e] - mu) * rs, b);
+    }
   }
   a = wave_sum(a) / (float)d;
   b = wave_sum(b) / (float)d;
-  for (int c = lane; c < d; c += 64) {
-    const float xh = (bf2f(x[row * d + c]) - mu) * rs;
-    float v = rs * (bf2f(dy[row * d + c]) * g[c] - a - xh * b);
-    if (res) v += bf2f(res[row * d + c]);
-    out[row * d + c] = f2bf(v);
+  for (int c = lane * 8; c < d; c += 512) {
+    float dv[8], xv[8], gv[8], o[8];
+    load8(dy + row * d + c, dv);
+    load8(x + row * d + c, xv);
+    load8(g + c, gv);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float xh = (xv[e] - mu) * rs;
+      o[e] = rs * (dv[e] * gv[e] - a - xh * b);
+    }
+    if (res) {
+      float rv[8];
+      load8(res + row * d + c, rv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] += rv[e];
+    }
+    store8(out + row * d + c, o);
   }
 }
 hipError_t layernorm_bwd(const bf16_t* dy, const bf16_t* x, const float* mean, const float* rstd, int P, int rows, int d,
                          const float* W32, int64_t stride, int64_t g_off, const bf16_t* res, bf16_t* out, hipStream_t s) {
+  if (d % 8 || g_off % 4 || stride % 4) return hipErrorInvalidValue;
   hipLaunchKernelGGL(layernorm_bwd_kernel, dim3((rows + 3) / 4, P), dim3(256), 0, s, dy, x, mean, rstd, rows, d, W32, stride, g_off, res, out);
   return hipGetLastError();
 }
