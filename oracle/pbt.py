@@ -5,7 +5,7 @@ Follows Algorithm 1 of the paper (Section 3) executed with the partial
 synchrony of Appendix A.1: every member is advanced by `step` for a fixed
 number of iterations, then `eval` scores every member and the
 exploit-and-explore procedure runs over the whole population, and the cycle
-repeats.  `exploit` is truncation selection (Section 4.1.1, Exploit (b)): rank
+repeats.  `exploit` is truncation selection by default (Section 4.1.1, Exploit (b)): rank
 all members by score; each member of the bottom set samples a donor uniformly
 from the top set and takes over its weights and hyperparameters.  `explore` is
 perturb (Section 4.1.1, Explore (a)): every hyperparameter of a member that was
@@ -114,6 +114,54 @@ def truncation_select(scores, n_trunc, round_index, seed):
     return order, donor
 
 
+def binary_tournament(scores, round_index, seed):
+    """Section 4.3.1, Exploit (b): every member draws ONE other member uniformly at random and copies
+    it if the other member's score is better.  "Better" is the total order of rank_order (so NaN and
+    -inf members always lose, ties go to the lower index).  Opponent of member i: j = floor(x (P-1) /
+    2^32) from word 0 of Philox counter (round, i, DOMAIN_DONOR, 0), then j += 1 if j >= i (uniform
+    over the P-1 others).  All members decide on the scores as they were before the pass.
+    Returns (order, donor): donor[i] = member i copies from, or -1."""
+    P = len(scores)
+    order = rank_order(scores)
+    place = np.empty(P, dtype=np.int64)
+    place[order] = np.arange(P)
+    donor = np.full(P, -1, dtype=np.int32)
+    if P < 2:
+        return order, donor
+    for i in range(P):
+        x = philox.words(seed, round_index, i, philox.DOMAIN_DONOR, 0)[0]
+        j = int(philox.bounded(x, P - 1))
+        j += 1 if j >= i else 0
+        if place[j] < place[i]:
+            donor[i] = j
+    return order, donor
+
+
+def resample(h_src, round_index, r, seed, prob, priors, h_max=None):
+    """Explore (b) of Section 4.1.1 for recipient r: every hyperparameter is, independently and with
+    probability `prob`, drawn afresh from its prior (kind, lo, hi); otherwise the copied value is kept.
+    Hyperparameter k uses Philox counter (round, r, DOMAIN_EXPLORE, k): resample iff word 1 <
+    floor(prob 2^32) (prob >= 1: always), new value = prior map of u = (word 2 + 0.5) / 2^32, computed
+    in double and rounded to float32 as for the initial population."""
+    h_src = np.asarray(h_src, dtype=np.float32)
+    out = h_src.copy()
+    thr = int(math.floor(float(np.float32(prob)) * 4294967296.0))
+    for k, (kind, lo, hi) in enumerate(priors):
+        w = philox.words(seed, round_index, r, philox.DOMAIN_EXPLORE, k)
+        if prob >= 1.0 or int(w[1]) < thr:
+            u = float(philox.unit_open(w[2]))
+            if kind == "log":
+                v = np.float32(math.exp(math.log(lo) + u * (math.log(hi) - math.log(lo))))
+            elif kind == "uniform":
+                v = np.float32(lo + u * (hi - lo))
+            else:
+                raise ValueError(kind)
+            out[k] = v
+        if h_max is not None and out[k] > np.float32(h_max[k]):
+            out[k] = np.float32(h_max[k])
+    return out
+
+
 def perturb(h_src, round_index, r, seed, factor_lo, factor_hi, h_max=None):
     """Explore for recipient r: float32 multiply of every hyperparameter of the
     source vector by factor_lo or factor_hi."""
@@ -134,31 +182,55 @@ def perturb(h_src, round_index, r, seed, factor_lo, factor_hi, h_max=None):
 
 
 def exploit_explore(pop, round_index, seed, n_trunc, factor_lo=0.8, factor_hi=1.2, h_max=None,
-                    scores=None, explore_fn=None):
+                    scores=None, explore_fn=None, mode="truncation", copy_weights=True, copy_hypers=True,
+                    explore="perturb", resample_prob=0.0, priors=None):
     """One exploit-and-explore pass over the population, in place.
     `scores` overrides the members' stored p (float32).  `explore_fn(h, round,
-    r)` replaces the perturb rule (used by the toy example).  Returns (order, donor)."""
+    r)` replaces the explore rule (used by the toy example).  Returns (order, donor).
+
+    mode: "truncation" (Section 4.1.1 Exploit (b)) or "tournament" (Section 4.3.1 Exploit (b)).  In a
+    tournament a member can be donor and recipient in the same pass; every recipient receives its
+    donor's state as it was BEFORE the pass (all members act on the same snapshot).
+    copy_weights / copy_hypers: the subsets of Section 4.4 ("PBT targets"): without copy_weights the
+    recipient keeps its own weights, optimiser state, update count, score and history and only takes
+    (explored) hyperparameters; without copy_hypers it takes the weights and keeps its own
+    hyperparameters, which are then neither copied nor explored.
+    explore: "perturb" (Section 4.1.1 Explore (a)) or "resample" (Explore (b), needs priors)."""
     if scores is None:
         scores = np.array([m.p for m in pop], dtype=np.float32)
     else:
         scores = np.asarray(scores, dtype=np.float32)
         for m, s in zip(pop, scores):
             m.p = np.float32(s)
-    order, donor = truncation_select(scores, n_trunc, round_index, seed)
+    if mode == "truncation":
+        order, donor = truncation_select(scores, n_trunc, round_index, seed)
+    elif mode == "tournament":
+        order, donor = binary_tournament(scores, round_index, seed)
+    else:
+        raise ValueError(mode)
+    # assignments below replace attributes and never change the old objects, so these references are a snapshot
+    before = [(m.theta, m.opt, m.t, m.p, m.hist, m.h) for m in pop]
     for r in range(len(pop)):
         d = int(donor[r])
         if d < 0:
             continue
-        src, dst = pop[d], pop[r]
-        dst.theta = copy.deepcopy(src.theta)
-        dst.opt = copy.deepcopy(src.opt)
-        dst.t = src.t
-        dst.p = src.p
-        dst.hist = copy.deepcopy(src.hist)
-        if explore_fn is None:
-            dst.h = perturb(src.h, round_index, r, seed, factor_lo, factor_hi, h_max)
-        else:
-            dst.h = np.asarray(explore_fn(src.h, round_index, r), dtype=np.float32)
+        theta, opt, t, p, hist, h = before[d]
+        dst = pop[r]
+        if copy_weights:
+            dst.theta = copy.deepcopy(theta)
+            dst.opt = copy.deepcopy(opt)
+            dst.t = t
+            dst.p = p
+            dst.hist = copy.deepcopy(hist)
+        if copy_hypers:
+            if explore_fn is not None:
+                dst.h = np.asarray(explore_fn(h, round_index, r), dtype=np.float32)
+            elif explore == "perturb":
+                dst.h = perturb(h, round_index, r, seed, factor_lo, factor_hi, h_max)
+            elif explore == "resample":
+                dst.h = resample(h, round_index, r, seed, resample_prob, priors, h_max)
+            else:
+                raise ValueError(explore)
         dst.parent = d
     return order, donor
 

@@ -266,3 +266,100 @@ def test_init_weights_distribution_and_formula():
     assert layers[1][0][2, 1] == np.float32((2.0 * (x + 0.5) / 2.0 ** 32 - 1.0) / math.sqrt(30))
     other = pbt.init_weights(11, 3, dims, offsets)
     assert not np.array_equal(other[0][0], layers[0][0])
+
+
+# ---- binary tournament, PBT targets, resample explore (Sections 4.3.1, 4.4, 4.1.1 Explore (b)) --------
+
+def _tiny_pop(P, rng):
+    pop = []
+    for i in range(P):
+        m = pbt.Member([rng.standard_normal(3)], rng.uniform(0.1, 1.0, 2), {"s0": [rng.standard_normal(3)]}, i)
+        m.t = 10 + i
+        m.hist = [float(i)]
+        pop.append(m)
+    return pop
+
+
+def test_binary_tournament_exhaustive_small():
+    """Every member copies only from a member that ranks above it, the opponent is uniform over the
+    others, and the best member never copies."""
+    seen = np.zeros((6, 6), dtype=np.int64)
+    for rnd in range(400):
+        scores = np.array([0.3, 0.9, -1.0, 0.9, np.nan, 0.1], dtype=np.float32)
+        order, donor = pbt.binary_tournament(scores, rnd, 77)
+        assert order == pbt.rank_order(scores)
+        place = {m: k for k, m in enumerate(order)}
+        for i in range(6):
+            x = philox.words(77, rnd, i, philox.DOMAIN_DONOR, 0)[0]
+            j = (int(x) * 5) >> 32
+            j += 1 if j >= i else 0
+            assert j != i
+            seen[i, j] += 1
+            assert donor[i] == (j if place[j] < place[i] else -1)
+        assert donor[4] != -1                                     # the NaN member loses against anyone
+        assert donor[1] == -1                                     # best (tie broken by index) never copies
+    off = seen[~np.eye(6, dtype=bool)]
+    assert off.min() > 40 and seen.trace() == 0                   # 400 / 5 = 80 expected per pair
+
+
+def test_tournament_copies_use_the_state_before_the_pass():
+    """Chain 2 <- 1 <- 0: member 2 must receive member 1's OLD weights, not the ones 1 got from 0."""
+    rng = np.random.default_rng(5)
+    for rnd in range(300):
+        pop = _tiny_pop(3, rng)
+        scores = np.array([3.0, 2.0, 1.0], dtype=np.float32)
+        _, donor = pbt.binary_tournament(scores, rnd, 5)
+        if donor[1] == 0 and donor[2] == 1:
+            old1, old0 = pop[1].theta[0].copy(), pop[0].theta[0].copy()
+            old_h1 = pop[1].h.copy()
+            pbt.exploit_explore(pop, rnd, 5, 0, scores=scores, mode="tournament")
+            assert np.array_equal(pop[1].theta[0], old0) and np.array_equal(pop[2].theta[0], old1)
+            assert pop[2].t == 11 and pop[1].t == 10 and pop[2].hist == [1.0]
+            assert pop[2].h.tobytes() == pbt.perturb(old_h1, rnd, 2, 5, 0.8, 1.2).tobytes()
+            return
+    raise AssertionError("no chain drawn")
+
+
+def test_pbt_targets_subsets():
+    rng = np.random.default_rng(6)
+    scores = np.array([5, 4, 3, 2, 1, 0], dtype=np.float32)
+    for cw, ch in ((True, False), (False, True)):
+        pop = _tiny_pop(6, rng)
+        ref = [(m.theta[0].copy(), m.h.copy(), m.t, m.opt["s0"][0].copy()) for m in pop]
+        _, donor = pbt.exploit_explore(pop, 0, 9, 2, scores=scores, copy_weights=cw, copy_hypers=ch)
+        for r in range(6):
+            d = int(donor[r])
+            if d < 0:
+                assert np.array_equal(pop[r].theta[0], ref[r][0]) and pop[r].h.tobytes() == ref[r][1].tobytes()
+                continue
+            if cw:
+                assert np.array_equal(pop[r].theta[0], ref[d][0]) and pop[r].t == ref[d][2] and np.array_equal(pop[r].opt["s0"][0], ref[d][3])
+                assert pop[r].p == scores[d]
+            else:
+                assert np.array_equal(pop[r].theta[0], ref[r][0]) and pop[r].t == ref[r][2] and pop[r].p == scores[r]
+            if ch:
+                assert pop[r].h.tobytes() == pbt.perturb(ref[d][1], 0, r, 9, 0.8, 1.2).tobytes()
+            else:
+                assert pop[r].h.tobytes() == ref[r][1].tobytes()              # neither copied nor explored
+
+
+def test_resample_explore_frequency_range_and_passthrough():
+    priors = [("log", 1e-4, 1e-2), ("uniform", 0.8, 0.95)]
+    h = np.array([0.5, 0.5], dtype=np.float32)                                # outside both priors: a resample is visible
+    hits = np.zeros(2)
+    for r in range(2000):
+        out = pbt.resample(h, 3, r, 11, 0.25, priors)
+        for k, (kind, lo, hi) in enumerate(priors):
+            if out[k] != h[k]:
+                hits[k] += 1
+                assert np.float32(lo) <= out[k] <= np.float32(hi)
+                w = philox.words(11, 3, r, philox.DOMAIN_EXPLORE, k)
+                assert int(w[1]) < 2 ** 30
+                u = (int(w[2]) + 0.5) / 2.0 ** 32
+                want = math.exp(math.log(lo) + u * (math.log(hi) - math.log(lo))) if kind == "log" else lo + u * (hi - lo)
+                assert out[k] == np.float32(want)
+    assert np.all(np.abs(hits / 2000 - 0.25) < 0.04)
+    assert pbt.resample(h, 3, 0, 11, 0.0, priors).tobytes() == h.tobytes()
+    always = pbt.resample(h, 3, 0, 11, 1.0, priors)
+    assert always[0] != h[0] and always[1] != h[1]
+    assert pbt.resample(h, 3, 0, 11, 1.0, priors, h_max=[1e-3, 0.9])[0] <= np.float32(1e-3)
