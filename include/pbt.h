@@ -62,6 +62,8 @@ typedef enum {
   PBT_EUNSUPPORTED = -5  /* valid request that this build has no kernel for */
 } pbt_status;
 
+enum { PBT_EXPLOIT_TRUNCATION = 0, PBT_EXPLOIT_TOURNAMENT = 1 };
+enum { PBT_EXPLORE_PERTURB = 0, PBT_EXPLORE_RESAMPLE = 1 };
 enum { PBT_WL_CLASSIFIER = 1, PBT_WL_GAN = 3, PBT_WL_TRANSFORMER = 4, PBT_WL_A2C = 5 }; /* workload families */
 enum { PBT_ACT_NONE = 0, PBT_ACT_RELU = 1, PBT_ACT_GELU = 2, PBT_ACT_LEAKY_RELU = 3, PBT_ACT_TANH = 4 };
 enum { PBT_OPT_SGD_MOMENTUM = 0, PBT_OPT_ADAM = 1, PBT_OPT_RMSPROP = 2 };
@@ -126,6 +128,21 @@ typedef struct {
   int32_t fuse_optimizer;           /* bf16 compute: 1 = apply the optimiser inside the weight-gradient GEMMs (the gradient of
                                        those matrices is then never stored: PBT_ARR_GRAD holds only bias / output-layer
                                        gradients); 0 = separate optimiser pass over a complete gradient */
+  /* Variants of exploit and explore (all 0 = truncation selection + perturb on weights and hyperparameters).
+     exploit_mode 1: binary tournament (Section 4.3.1, Exploit (b)): every member draws one other member
+     uniformly (j = floor(x (P-1) / 2^32) from Philox counter (round, i, domain 2, 0), j += 1 if j >= i) and
+     copies it if that member ranks above it; n_trunc is ignored; every recipient receives its donor's state
+     as it was before the pass.
+     explore_mode 1: resample (Section 4.1.1, Explore (b)): hyperparameter k of an overwritten member is drawn
+     afresh from its prior (pbt_set_priors) iff word 1 of Philox counter (round, i, domain 3, k) is below
+     floor(resample_prob 2^32) (always when resample_prob >= 1), from u = (word 2 + 0.5) / 2^32; otherwise the
+     copied value stays; the upper clamp hyper_max applies.
+     keep_weights / keep_hypers: the subsets of Section 4.4 ("PBT targets"): keep_weights = 1 copies (and
+     explores) hyperparameters only, the recipient keeps its weights, optimiser state, update count, score
+     and history; keep_hypers = 1 copies the weights and leaves the recipient's hyperparameters untouched. */
+  int32_t exploit_mode, explore_mode;
+  float resample_prob;
+  int32_t keep_weights, keep_hypers;
   uint64_t seed;                    /* Philox key */
 } pbt_config;
 
@@ -173,6 +190,11 @@ typedef struct {
  * in double precision and rounded once to float.  Optimiser state, t and scores are reset as in
  * pbt_init.  Enqueues on hip_stream; no synchronisation. */
 pbt_status pbt_init_population(pbt_handle* h, const pbt_prior* priors, void* hip_stream);
+
+/* Section 4.1.1, Explore (b): the priors that resample-explore draws from (HOST array of n_hyper
+ * entries, copied into the handle; pbt_init_population stores its priors the same way).  Host-only call.
+ * PBT_EINVAL for a bad prior (as in pbt_init_population). */
+pbt_status pbt_set_priors(pbt_handle* h, const pbt_prior* priors);
 
 /* Section 3, Eq. 2: theta_i <- step(theta_i | h_i) for every member i, n_steps
  * times (step indices step_index .. step_index + n_steps - 1).  One step:

@@ -23,7 +23,7 @@ _ARR_DTYPE = {ARR_W32: np.float32, ARR_OPT0: np.float32, ARR_OPT1: np.float32, A
 
 EXPORTS = ["pbt_query_sizes", "pbt_init", "pbt_step", "pbt_eval", "pbt_exploit_explore", "pbt_get_state",
            "pbt_set_state", "pbt_state_ptr", "pbt_destroy", "pbt_last_error", "pbt_batched_gemm_bf16",
-           "pbt_timing_enable", "pbt_timing_read", "pbt_init_population"]
+           "pbt_timing_enable", "pbt_timing_read", "pbt_init_population", "pbt_set_priors"]
 (K_NONE, K_FETCH, K_GEMM_FWD, K_HEAD, K_GEMM_WGRAD, K_GEMM_DGRAD, K_BIAS_GRAD, K_OPTIMIZER, K_RANK, K_COPY,
  K_FUSED_STEP) = range(-1, 10)
 
@@ -37,7 +37,9 @@ class PbtConfig(C.Structure):
                 ("n_layers2", C.c_int32), ("dims2", C.c_int32 * PBT_MAX_DIMS), ("act2", C.c_int32), ("unroll", C.c_int32),
                 ("gamma", C.c_float), ("value_cost", C.c_float), ("tf_vocab", C.c_int32), ("tf_d_model", C.c_int32),
                 ("tf_heads", C.c_int32), ("tf_d_ff", C.c_int32), ("tf_seq", C.c_int32), ("n_train", C.c_int32),
-                ("n_eval", C.c_int32), ("eval_chunk", C.c_int32), ("fuse_optimizer", C.c_int32), ("seed", C.c_uint64)]
+                ("n_eval", C.c_int32), ("eval_chunk", C.c_int32), ("fuse_optimizer", C.c_int32), ("exploit_mode", C.c_int32),
+                ("explore_mode", C.c_int32), ("resample_prob", C.c_float), ("keep_weights", C.c_int32), ("keep_hypers", C.c_int32),
+                ("seed", C.c_uint64)]
 
 
 class PbtLayout(C.Structure):
@@ -80,6 +82,7 @@ def lib():
         L.pbt_last_error.restype = C.c_char_p
         L.pbt_batched_gemm_bf16.argtypes = [vp, i64, i64, i32, vp, i64, i64, i32, vp, i64, i64, i32, i32, i32, i32, i32, vp]
         L.pbt_init_population.argtypes = [vp, C.POINTER(PbtPrior), vp]
+        L.pbt_set_priors.argtypes = [vp, C.POINTER(PbtPrior)]
         L.pbt_timing_enable.argtypes = [vp, i32, i32]
         L.pbt_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
         for name in EXPORTS:
@@ -126,6 +129,12 @@ def make_config(wl, seed, P=None, n_trunc=None, eval_chunk=0, fuse_optimizer=0):
         c.unroll, c.gamma, c.value_cost = wl.unroll, wl.gamma, wl.value_cost
     c.n_train, c.n_eval, c.eval_chunk = wl.n_train, wl.n_eval, eval_chunk
     c.fuse_optimizer = fuse_optimizer
+    # variants of exploit / explore (Sections 4.3.1, 4.4, 4.1.1 Explore (b)); all default to 0
+    c.exploit_mode = getattr(wl, "exploit_mode", 0)
+    c.explore_mode = getattr(wl, "explore_mode", 0)
+    c.resample_prob = getattr(wl, "resample_prob", 0.0)
+    c.keep_weights = getattr(wl, "keep_weights", 0)
+    c.keep_hypers = getattr(wl, "keep_hypers", 0)
     c.seed = seed
     return c
 
@@ -235,6 +244,11 @@ class Population:
         """priors: [("uniform" | "log", lo, hi), ...], one per hyperparameter column."""
         arr = (PbtPrior * len(priors))(*[PbtPrior(1 if k == "log" else 0, lo, hi) for k, lo, hi in priors])
         self._check(lib().pbt_init_population(self._h, arr, self._stream()))
+
+    def set_priors(self, priors):
+        """priors as in init_population; used by resample explore."""
+        arr = (PbtPrior * len(priors))(*[PbtPrior(1 if k == "log" else 0, lo, hi) for k, lo, hi in priors])
+        self._check(lib().pbt_set_priors(self._h, arr))
 
     def timing_enable(self, kernel_class, max_launches=1):
         self._check(lib().pbt_timing_enable(self._h, kernel_class, max_launches))

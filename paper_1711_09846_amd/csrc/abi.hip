@@ -49,6 +49,11 @@ pbt_status check_config(const pbt_config* c, Plan* pl) {
   if (c->n_hyper < 1 || c->n_hyper > PBT_MAX_HYPER) return fail(nullptr, PBT_EINVAL, "n_hyper = %d outside 1..%d", c->n_hyper, PBT_MAX_HYPER);
   if (c->n_trunc < 0 || 2 * (int64_t)c->n_trunc > c->P) return fail(nullptr, PBT_EINVAL, "need 0 <= 2*n_trunc <= P (top and bottom sets must not overlap)");
   if (c->n_train < 1 || c->n_eval < 1) return fail(nullptr, PBT_EINVAL, "n_train and n_eval must be positive");
+  if (c->exploit_mode != PBT_EXPLOIT_TRUNCATION && c->exploit_mode != PBT_EXPLOIT_TOURNAMENT) return fail(nullptr, PBT_EINVAL, "unknown exploit_mode %d", c->exploit_mode);
+  if (c->explore_mode != PBT_EXPLORE_PERTURB && c->explore_mode != PBT_EXPLORE_RESAMPLE) return fail(nullptr, PBT_EINVAL, "unknown explore_mode %d", c->explore_mode);
+  if (!(c->resample_prob >= 0.f)) return fail(nullptr, PBT_EINVAL, "resample_prob must be >= 0");
+  if ((c->keep_weights != 0 && c->keep_weights != 1) || (c->keep_hypers != 0 && c->keep_hypers != 1)) return fail(nullptr, PBT_EINVAL, "keep_weights / keep_hypers are 0 or 1");
+  if (c->keep_weights && c->keep_hypers) return fail(nullptr, PBT_EINVAL, "keep_weights and keep_hypers together leave exploit nothing to do");
   if (!gan && !tf && c->dims[c->n_layers] > 32) return fail(nullptr, PBT_EUNSUPPORTED, "more than 32 outputs in the last layer");
   pl->a2c.col_ent = -1;
   pl->tf.col_drop = pl->tf.col_ls = -1;
@@ -139,11 +144,22 @@ pbt_status make_plan(const pbt_config* c, Plan* pl) {
   pl->o_donor = s.take(P * 4);
   pl->o_parent = s.take(P * 4);
   pl->o_recip = s.take(P * 4);
+  pl->o_nrecip = s.take(4);
   pl->o_hist = c->workload == PBT_WL_A2C ? s.take(P * 12 * 4) : 0;
   pl->state_bytes = s.off;
 
   Carver w;
   pl->o_grad = w.take(pw * 4);
+  for (int k = 0; k < 6; ++k) pl->o_stage[k] = 0;
+  if (c->exploit_mode == PBT_EXPLOIT_TOURNAMENT && !c->keep_weights) {
+    // a member can be donor and recipient: donor rows pass through these staging rows (same order as in pbt_exploit_explore)
+    int k = 0;
+    pl->o_stage[k++] = w.take(pw * 4);
+    pl->o_stage[k++] = w.take(pw * 4);
+    if (adam) pl->o_stage[k++] = w.take(pw * 4);
+    if (bf16) pl->o_stage[k++] = w.take(pw * 2);
+    if (c->workload == PBT_WL_A2C) pl->o_stage[k++] = w.take(P * 12 * 4);
+  }
   pl->fused_small = false;
   pl->eval_chunk = 0;
   if (gan) {
@@ -411,6 +427,26 @@ static hipError_t reset_store(pbt_handle* h, hipStream_t s) {
   return e;
 }
 
+static pbt_status check_priors(pbt_handle* h, const pbt_prior* priors) {
+  if (!priors) return fail(h, PBT_EINVAL, "priors is NULL");
+  for (int k = 0; k < h->cfg.n_hyper; ++k) {
+    const pbt_prior& pr = priors[k];
+    if (pr.kind != 0 && pr.kind != 1) return fail(h, PBT_EINVAL, "prior %d: kind must be 0 (uniform) or 1 (log-uniform)", k);
+    if (!(pr.lo <= pr.hi) || !std::isfinite(pr.lo) || !std::isfinite(pr.hi)) return fail(h, PBT_EINVAL, "prior %d: need finite lo <= hi", k);
+    if (pr.kind == 1 && !(pr.lo > 0.0)) return fail(h, PBT_EINVAL, "prior %d: log-uniform needs lo > 0", k);
+  }
+  return PBT_OK;
+}
+
+pbt_status pbt_set_priors(pbt_handle* h, const pbt_prior* priors) {
+  if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  pbt_status st = check_priors(h, priors);
+  if (st != PBT_OK) return st;
+  for (int k = 0; k < h->cfg.n_hyper; ++k) h->priors[k] = priors[k];
+  h->have_priors = true;
+  return PBT_OK;
+}
+
 pbt_status pbt_init_population(pbt_handle* h, const pbt_prior* priors, void* hip_stream) {
   if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
   if (!priors) return fail(h, PBT_EINVAL, "priors is NULL");
@@ -429,6 +465,8 @@ pbt_status pbt_init_population(pbt_handle* h, const pbt_prior* priors, void* hip
     a.prior_a[k] = pr.kind == 1 ? std::log(pr.lo) : pr.lo;
     a.prior_b[k] = pr.kind == 1 ? std::log(pr.hi) : pr.hi;
   }
+  for (int k = 0; k < c.n_hyper; ++k) h->priors[k] = priors[k];
+  h->have_priors = true;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   PBT_HIP(h, reset_store(h, s));
   a.W32 = h->st<float>(p.o_w32);
@@ -544,20 +582,38 @@ pbt_status pbt_exploit_explore(pbt_handle* h, int64_t round_index, const float* 
   a.donor = h->st<int32_t>(p.o_donor);
   a.parent = h->st<int32_t>(p.o_parent);
   a.recip = h->st<int32_t>(p.o_recip);
+  a.n_recip = h->st<int32_t>(p.o_nrecip);
+  a.tournament = c.exploit_mode == PBT_EXPLOIT_TOURNAMENT;
+  a.resample = c.explore_mode == PBT_EXPLORE_RESAMPLE;
+  a.keep_weights = c.keep_weights; a.keep_hypers = c.keep_hypers;
+  a.resample_always = c.resample_prob >= 1.f;
+  a.resample_thr = a.resample_always ? 0xffffffffu : (uint32_t)std::floor((double)c.resample_prob * 4294967296.0);
+  for (int k = 0; k < 8; ++k) { a.prior_kind[k] = 0; a.prior_a[k] = a.prior_b[k] = 0.0; }
+  if (a.resample && !c.keep_hypers) {
+    if (!h->have_priors) return fail(h, PBT_ESTATE, "resample explore needs priors: call pbt_set_priors or pbt_init_population first");
+    for (int k = 0; k < c.n_hyper; ++k) {
+      const pbt_prior& pr = h->priors[k];
+      a.prior_kind[k] = pr.kind;
+      a.prior_a[k] = pr.kind == 1 ? std::log(pr.lo) : pr.lo;
+      a.prior_b[k] = pr.kind == 1 ? std::log(pr.hi) : pr.hi;
+    }
+  }
   a.P = c.P; a.n_trunc = c.n_trunc; a.n_hyper = c.n_hyper;
   a.f_lo = c.perturb_lo; a.f_hi = c.perturb_hi;
   for (int k = 0; k < 8; ++k) a.h_max[k] = k < c.n_hyper ? c.hyper_max[k] : INFINITY;
   a.round = (uint32_t)round_index; a.seed = c.seed;
   PBT_LAUNCH(h, PBT_K_RANK, s, rank_select_explore(a, s));
+  if (c.keep_weights) return PBT_OK;  // hyperparameters only: nothing to copy
   CopyArrays ca;
   ca.n = 0;
+  for (int k = 0; k < 6; ++k) ca.stage[k] = a.tournament ? h->sc<char>(p.o_stage[k]) : nullptr;
   const int64_t S = p.lay.stride;
   ca.base[ca.n] = h->st<char>(p.o_w32); ca.row_bytes[ca.n++] = S * 4;
   ca.base[ca.n] = h->st<char>(p.o_opt0); ca.row_bytes[ca.n++] = S * 4;
   if (c.optimizer == PBT_OPT_ADAM) { ca.base[ca.n] = h->st<char>(p.o_opt1); ca.row_bytes[ca.n++] = S * 4; }
   if (c.compute_dtype == PBT_DTYPE_BF16) { ca.base[ca.n] = h->st<char>(p.o_w16); ca.row_bytes[ca.n++] = S * 2; }
   if (c.workload == PBT_WL_A2C) { ca.base[ca.n] = h->st<char>(p.o_hist); ca.row_bytes[ca.n++] = 12 * 4; }
-  PBT_LAUNCH(h, PBT_K_COPY, s, gather_copy(ca, a.recip, a.donor, c.n_trunc, s));
+  PBT_LAUNCH(h, PBT_K_COPY, s, gather_copy(ca, a.recip, a.donor, a.tournament ? c.P : c.n_trunc, a.n_recip, a.tournament, s));
   return PBT_OK;
 }
 

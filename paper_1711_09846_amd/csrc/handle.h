@@ -61,12 +61,13 @@ struct Plan {
   pbt_layout lay;
   int n_loss;
   // offsets in bytes inside d_state
-  size_t o_w32, o_opt0, o_opt1, o_w16, o_hyper, o_score, o_loss, o_t, o_order, o_donor, o_parent, o_recip, o_hist;
+  size_t o_w32, o_opt0, o_opt1, o_w16, o_hyper, o_score, o_loss, o_t, o_order, o_donor, o_parent, o_recip, o_nrecip, o_hist;
   size_t state_bytes;
   // offsets in bytes inside d_scratch
   size_t o_grad, o_y, o_dlogits, o_rowloss, o_x32;
   size_t o_act[PBT_MAX_DIMS], o_z[PBT_MAX_DIMS], o_dz[PBT_MAX_DIMS];
   size_t o_evalx, o_evala[2], o_evalrow;
+  size_t o_stage[6];  // tournament exploit: staging rows of the copied arrays
   size_t scratch_bytes;
   int eval_chunk;
   bool fused_small;  // fp32: the whole step runs in one LDS-resident kernel
@@ -84,6 +85,8 @@ struct pbt_handle {
   char* state;
   char* scratch;
   std::string err;
+  pbt_prior priors[PBT_MAX_HYPER];  // for resample explore (pbt_set_priors / pbt_init_population)
+  bool have_priors = false;
   // optional event timing of one kernel class
   int timed_class = PBT_K_NONE;
   std::vector<hipEvent_t> ev_start, ev_stop;

@@ -136,17 +136,24 @@ hipError_t tf_scatter_rows(const float* src, int P, int rows, float* dst, int64_
 
 struct ExploitArgs {
   float* score; const float* score_override; float* H; int32_t* t; int32_t* order; int32_t* donor; int32_t* parent;
-  int32_t* recip;
+  int32_t* recip; int32_t* n_recip;  // recipients (member indices) and their number
   int P, n_trunc, n_hyper;
   float f_lo, f_hi;
   float h_max[8];
   uint32_t round; uint64_t seed;
+  int tournament, resample, keep_weights, keep_hypers;
+  uint32_t resample_thr; int resample_always;     // resample iff word < thr, or always
+  int prior_kind[8]; double prior_a[8], prior_b[8];  // as in InitArgs
 };
 hipError_t rank_select_explore(const ExploitArgs& a, hipStream_t s);
 struct CopyArrays {
   void* base[6]; int64_t row_bytes[6]; int n;
+  void* stage[6];  // optional staging rows [max_rows][row_bytes] per array (donors that are recipients too)
 };
-hipError_t gather_copy(const CopyArrays& arrs, const int32_t* recip, const int32_t* donor, int n_trunc, hipStream_t s);
+// Row recip[y] of every array <- row donor[recip[y]], y < *n_recip (at most max_rows).  staged: every donor
+// row is first gathered into arrs.stage and then scattered, so that a member can be donor and recipient.
+hipError_t gather_copy(const CopyArrays& arrs, const int32_t* recip, const int32_t* donor, int max_rows, const int32_t* n_recip,
+                       bool staged, hipStream_t s);
 
 // fused_small.hip: whole step of a small fp32 MLP classifier, one workgroup per member, the
 // member's weights, optimiser state and activations resident in LDS across n_steps steps.

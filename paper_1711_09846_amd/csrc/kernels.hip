@@ -351,38 +351,85 @@ __device__ __forceinline__ bool ranks_above(float sj, int j, float si, int i) {
 __global__ __launch_bounds__(1024) void rank_select_explore_kernel(ExploitArgs a) {
   __shared__ float sc[1024];
   __shared__ int ord[1024];
+  __shared__ int place[1024];
+  __shared__ int is_rec[1024];
   const int i = threadIdx.x;
+  const bool live = i < a.P;
   const float* __restrict__ src = a.score_override ? a.score_override : a.score;
-  if (i < a.P) sc[i] = src[i];
+  if (live) sc[i] = src[i];
   __syncthreads();
   int pos = 0;
-  if (i < a.P) {
+  if (live) {
     const float si = sc[i];
     for (int j = 0; j < a.P; ++j) pos += (j != i && ranks_above(sc[j], j, si, i)) ? 1 : 0;
     ord[pos] = i;
+    place[i] = pos;
   }
   __syncthreads();
-  if (i >= a.P) return;
-  a.order[i] = ord[i];
+  // exploit: who copies from whom (decided on the scores before the pass)
+  const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
   const int first_bottom = a.P - a.n_trunc;
-  if (a.n_trunc > 0 && pos >= first_bottom) {
-    const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
+  int d = -1;
+  if (live) {
     const uint32_t x = philox4x32_10(a.round, (uint32_t)i, DOMAIN_DONOR, 0u, k0, k1).x;
-    const int d = ord[philox_bounded(x, (uint32_t)a.n_trunc)];
-    a.donor[i] = d;
-    a.recip[pos - first_bottom] = i;
-    a.parent[i] = d;
-    a.t[i] = a.t[d];
-    a.score[i] = sc[d];
-    for (int k = 0; k < a.n_hyper; ++k) {
-      const uint32_t bit = philox4x32_10(a.round, (uint32_t)i, DOMAIN_EXPLORE, (uint32_t)k, k0, k1).x & 1u;
-      // one IEEE float multiply (no contraction possible: nothing is added)
-      const float v = __fmul_rn(a.H[d * a.n_hyper + k], bit ? a.f_hi : a.f_lo);
-      a.H[i * a.n_hyper + k] = v > a.h_max[k] ? a.h_max[k] : v;
+    if (a.tournament) {
+      if (a.P > 1) {
+        int j = (int)philox_bounded(x, (uint32_t)(a.P - 1));
+        j += j >= i ? 1 : 0;
+        if (place[j] < pos) d = j;
+      }
+    } else if (a.n_trunc > 0 && pos >= first_bottom) {
+      d = ord[philox_bounded(x, (uint32_t)a.n_trunc)];
     }
-  } else {
-    a.donor[i] = -1;
+    is_rec[i] = d >= 0;
+  }
+  // the donor's values as they are before anybody writes (a donor can be a recipient in a tournament)
+  int t_d = 0;
+  float h_d[8];
+  if (d >= 0) {
+    t_d = a.t[d];
+    for (int k = 0; k < a.n_hyper; ++k) h_d[k] = a.H[d * a.n_hyper + k];
+  }
+  __syncthreads();
+  if (!live) return;
+  a.order[i] = ord[i];
+  if (i == 0) {
+    int n = 0;
+    for (int j = 0; j < a.P; ++j) n += is_rec[j];
+    a.n_recip[0] = n;
+  }
+  a.donor[i] = d;
+  if (d < 0) {
     if (a.score_override) a.score[i] = sc[i];
+    return;
+  }
+  int slot = pos - first_bottom;  // truncation: bottom set in rank order
+  if (a.tournament) {
+    slot = 0;
+    for (int j = 0; j < i; ++j) slot += is_rec[j];
+  }
+  a.recip[slot] = i;
+  a.parent[i] = d;
+  if (!a.keep_weights) {
+    a.t[i] = t_d;
+    a.score[i] = sc[d];
+  } else if (a.score_override) {
+    a.score[i] = sc[i];
+  }
+  if (a.keep_hypers) return;
+  for (int k = 0; k < a.n_hyper; ++k) {
+    const u32x4 w = philox4x32_10(a.round, (uint32_t)i, DOMAIN_EXPLORE, (uint32_t)k, k0, k1);
+    float v = h_d[k];
+    if (a.resample) {
+      if (a.resample_always || w.y < a.resample_thr) {
+        const double lin = a.prior_a[k] + philox_unit(w.z) * (a.prior_b[k] - a.prior_a[k]);
+        v = (float)(a.prior_kind[k] == 1 ? exp(lin) : lin);
+      }
+    } else {
+      // one IEEE float multiply (no contraction possible: nothing is added)
+      v = __fmul_rn(v, (w.x & 1u) ? a.f_hi : a.f_lo);
+    }
+    a.H[i * a.n_hyper + k] = v > a.h_max[k] ? a.h_max[k] : v;
   }
 }
 hipError_t rank_select_explore(const ExploitArgs& a, hipStream_t s) {
@@ -392,15 +439,20 @@ hipError_t rank_select_explore(const ExploitArgs& a, hipStream_t s) {
 }
 
 // Gather-copy: recipient recip[y] receives a byte copy of row donor[recip[y]] of every array.
-// grid (chunks, n_trunc, arrays); 16-byte vectors, four in flight per thread.
+// grid (chunks, rows, arrays); 16-byte vectors, four in flight per thread.  pass 0: row to row;
+// pass 1: donor row -> staging row y; pass 2: staging row y -> recipient row.
 constexpr int COPY_UNROLL = 4;
 __global__ __launch_bounds__(256) void gather_copy_kernel(CopyArrays arrs, const int32_t* __restrict__ recip,
-                                                          const int32_t* __restrict__ donor) {
+                                                          const int32_t* __restrict__ donor, const int32_t* __restrict__ n_recip,
+                                                          int pass) {
+  if ((int)blockIdx.y >= n_recip[0]) return;
   const int r = recip[blockIdx.y];
   const int d = donor[r];
   const int64_t rb = arrs.row_bytes[blockIdx.z];
-  const uint4* __restrict__ src = reinterpret_cast<const uint4*>(static_cast<const char*>(arrs.base[blockIdx.z]) + (int64_t)d * rb);
-  uint4* __restrict__ dst = reinterpret_cast<uint4*>(static_cast<char*>(arrs.base[blockIdx.z]) + (int64_t)r * rb);
+  char* const base = static_cast<char*>(arrs.base[blockIdx.z]);
+  char* const stage = static_cast<char*>(arrs.stage[blockIdx.z]) + (int64_t)blockIdx.y * rb;
+  const uint4* __restrict__ src = reinterpret_cast<const uint4*>(pass == 2 ? stage : base + (int64_t)d * rb);
+  uint4* __restrict__ dst = reinterpret_cast<uint4*>(pass == 1 ? stage : base + (int64_t)r * rb);
   const int64_t nvec = rb / 16;
   const int64_t span = (int64_t)gridDim.x * 256;
   for (int64_t v0 = (int64_t)blockIdx.x * 256 + threadIdx.x; v0 < nvec; v0 += span * COPY_UNROLL) {
@@ -417,14 +469,21 @@ __global__ __launch_bounds__(256) void gather_copy_kernel(CopyArrays arrs, const
     }
   }
 }
-hipError_t gather_copy(const CopyArrays& arrs, const int32_t* recip, const int32_t* donor, int n_trunc, hipStream_t s) {
-  if (n_trunc <= 0 || arrs.n <= 0) return hipSuccess;
+hipError_t gather_copy(const CopyArrays& arrs, const int32_t* recip, const int32_t* donor, int max_rows, const int32_t* n_recip,
+                       bool staged, hipStream_t s) {
+  if (max_rows <= 0 || arrs.n <= 0) return hipSuccess;
   int64_t maxvec = 0;
   for (int k = 0; k < arrs.n; ++k) maxvec = arrs.row_bytes[k] / 16 > maxvec ? arrs.row_bytes[k] / 16 : maxvec;
   int64_t chunks = (maxvec + 256 * COPY_UNROLL - 1) / (256 * COPY_UNROLL);
   if (chunks > 2048) chunks = 2048;
   if (chunks < 1) chunks = 1;
-  hipLaunchKernelGGL(gather_copy_kernel, dim3((unsigned)chunks, n_trunc, arrs.n), dim3(256), 0, s, arrs, recip, donor);
+  const dim3 grid((unsigned)chunks, max_rows, arrs.n);
+  if (!staged) {
+    hipLaunchKernelGGL(gather_copy_kernel, grid, dim3(256), 0, s, arrs, recip, donor, n_recip, 0);
+  } else {
+    hipLaunchKernelGGL(gather_copy_kernel, grid, dim3(256), 0, s, arrs, recip, donor, n_recip, 1);
+    hipLaunchKernelGGL(gather_copy_kernel, grid, dim3(256), 0, s, arrs, recip, donor, n_recip, 2);
+  }
   return hipGetLastError();
 }
 

@@ -7,6 +7,14 @@ from oracle import classifier as oc, pbt as opbt, nets as onets
 from paper_1711_09846_amd import binding, workloads
 
 
+def exploit_variant(wl):
+    """The oracle's keyword arguments for the exploit / explore variant a workload description selects."""
+    return dict(mode="tournament" if getattr(wl, "exploit_mode", 0) else "truncation",
+                copy_weights=not getattr(wl, "keep_weights", 0), copy_hypers=not getattr(wl, "keep_hypers", 0),
+                explore="resample" if getattr(wl, "explore_mode", 0) else "perturb",
+                resample_prob=float(np.float32(getattr(wl, "resample_prob", 0.0))), priors=wl.priors)
+
+
 def oracle_spec(wl, seed):
     # optimiser constants cross the C ABI as float32; the oracle widens those exact values
     oc_ = {k: float(np.float32(v)) for k, v in wl.opt_const.items()}
@@ -84,7 +92,7 @@ class Pair:
     def exploit_ref(self, rnd, scores):
         wl = self.wl
         return opbt.exploit_explore(self.ref, rnd, self.seed, wl.n_trunc, wl.perturb[0], wl.perturb[1], wl.h_max,
-                                    scores=scores)
+                                    scores=scores, **exploit_variant(wl))
 
     # -- distances -----------------------------------------------------------------------------
     def ref_flat(self, member, what):
@@ -185,7 +193,8 @@ class GanPair:
     def exploit_ref(self, rnd, scores):
         wl = self.wl
         pop = [self.ref[i] for i in range(wl.P)]
-        return opbt.exploit_explore(pop, rnd, self.seed, wl.n_trunc, wl.perturb[0], wl.perturb[1], wl.h_max, scores=scores)
+        return opbt.exploit_explore(pop, rnd, self.seed, wl.n_trunc, wl.perturb[0], wl.perturb[1], wl.h_max, scores=scores,
+                                    **exploit_variant(wl))
 
 
 class A2CPair:
@@ -237,7 +246,8 @@ class A2CPair:
     def exploit_ref(self, rnd, scores):
         wl = self.wl
         pop = [self.ref[i] for i in range(wl.P)]
-        return opbt.exploit_explore(pop, rnd, self.seed, wl.n_trunc, wl.perturb[0], wl.perturb[1], wl.h_max, scores=scores)
+        return opbt.exploit_explore(pop, rnd, self.seed, wl.n_trunc, wl.perturb[0], wl.perturb[1], wl.h_max, scores=scores,
+                                    **exploit_variant(wl))
 
 
 class TransformerPair:
@@ -310,4 +320,5 @@ class TransformerPair:
     def exploit_ref(self, rnd, scores):
         wl = self.wl
         pop = [self.ref[i] for i in range(wl.P)]
-        return opbt.exploit_explore(pop, rnd, self.seed, wl.n_trunc, wl.perturb[0], wl.perturb[1], wl.h_max, scores=scores)
+        return opbt.exploit_explore(pop, rnd, self.seed, wl.n_trunc, wl.perturb[0], wl.perturb[1], wl.h_max, scores=scores,
+                                    **exploit_variant(wl))
