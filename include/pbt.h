@@ -62,7 +62,7 @@ typedef enum {
   PBT_EUNSUPPORTED = -5  /* valid request that this build has no kernel for */
 } pbt_status;
 
-enum { PBT_EXPLOIT_TRUNCATION = 0, PBT_EXPLOIT_TOURNAMENT = 1 };
+enum { PBT_EXPLOIT_TRUNCATION = 0, PBT_EXPLOIT_TOURNAMENT = 1, PBT_EXPLOIT_TTEST = 2 };
 enum { PBT_EXPLORE_PERTURB = 0, PBT_EXPLORE_RESAMPLE = 1 };
 enum { PBT_WL_CLASSIFIER = 1, PBT_WL_GAN = 3, PBT_WL_TRANSFORMER = 4, PBT_WL_A2C = 5 }; /* workload families */
 enum { PBT_ACT_NONE = 0, PBT_ACT_RELU = 1, PBT_ACT_GELU = 2, PBT_ACT_LEAKY_RELU = 3, PBT_ACT_TANH = 4 };
@@ -133,6 +133,11 @@ typedef struct {
      uniformly (j = floor(x (P-1) / 2^32) from Philox counter (round, i, domain 2, 0), j += 1 if j >= i) and
      copies it if that member ranks above it; n_trunc is ignored; every recipient receives its donor's state
      as it was before the pass.
+     exploit_mode 2: t-test selection (Section 4.1.1, Exploit (a); actor-critic workload only): the opponent is
+     drawn as in the tournament; the member copies it if the opponent's score history (the last up to 10 unroll
+     returns) has the higher mean and Welch's one-sided test gives p < ttest_alpha (Student t with the
+     Welch-Satterthwaite degrees of freedom, evaluated in double; zero variance on both sides counts as
+     significant); histories with fewer than two entries neither copy nor are copied.
      explore_mode 1: resample (Section 4.1.1, Explore (b)): hyperparameter k of an overwritten member is drawn
      afresh from its prior (pbt_set_priors) iff word 1 of Philox counter (round, i, domain 3, k) is below
      floor(resample_prob 2^32) (always when resample_prob >= 1), from u = (word 2 + 0.5) / 2^32; otherwise the
@@ -143,6 +148,7 @@ typedef struct {
   int32_t exploit_mode, explore_mode;
   float resample_prob;
   int32_t keep_weights, keep_hypers;
+  float ttest_alpha;                /* exploit_mode 2: significance level, 0 < alpha <= 1 */
   uint64_t seed;                    /* Philox key */
 } pbt_config;
 

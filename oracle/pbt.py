@@ -137,6 +137,54 @@ def binary_tournament(scores, round_index, seed):
     return order, donor
 
 
+def student_sf(t, nu):
+    """P(T > t) for Student's t distribution with nu degrees of freedom, t >= 0:
+    half the regularised incomplete beta function I_x(nu/2, 1/2) at x = nu / (nu + t^2)."""
+    from scipy.special import betainc
+    return 0.5 * float(betainc(0.5 * nu, 0.5, nu / (nu + t * t)))
+
+
+def welch(a, b):
+    """Welch's unequal-variance statistic for "mean(b) > mean(a)": returns (t, nu, mean_a, mean_b) with
+    t = (mean_b - mean_a) / sqrt(va + vb), v = s^2 / n (s^2 the unbiased sample variance), and the
+    Welch-Satterthwaite degrees of freedom nu = (va + vb)^2 / (va^2/(na-1) + vb^2/(nb-1)).
+    t = nu = inf when both variances are zero."""
+    a, b = np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64)
+    na, nb = len(a), len(b)
+    ma, mb = a.sum() / na, b.sum() / nb
+    va = ((a - ma) ** 2).sum() / (na - 1) / na
+    vb = ((b - mb) ** 2).sum() / (nb - 1) / nb
+    if va + vb == 0.0:
+        return math.inf, math.inf, ma, mb
+    t = (mb - ma) / math.sqrt(va + vb)
+    nu = (va + vb) ** 2 / (va * va / (na - 1) + vb * vb / (nb - 1))
+    return t, nu, ma, mb
+
+
+def ttest_select(scores, hists, round_index, seed, alpha):
+    """Section 4.1.1, Exploit (a): every member draws one other member uniformly (as in the binary
+    tournament) and copies it if that member's recent scores (hists[j], oldest first, the last up to
+    10 evaluations) have a higher mean than its own AND Welch's t-test rejects equality of the means in
+    that direction at level alpha (one-sided p < alpha; zero variance on both sides counts as
+    rejected).  Members with fewer than two recorded scores neither copy nor get copied.
+    Returns (order, donor)."""
+    P = len(scores)
+    order = rank_order(scores)
+    donor = np.full(P, -1, dtype=np.int32)
+    if P < 2:
+        return order, donor
+    for i in range(P):
+        x = philox.words(seed, round_index, i, philox.DOMAIN_DONOR, 0)[0]
+        j = int(philox.bounded(x, P - 1))
+        j += 1 if j >= i else 0
+        if hists[i] is None or hists[j] is None or len(hists[i]) < 2 or len(hists[j]) < 2:
+            continue
+        t, nu, mi, mj = welch(hists[i], hists[j])
+        if mj > mi and (math.isinf(t) or student_sf(t, nu) < alpha):
+            donor[i] = j
+    return order, donor
+
+
 def resample(h_src, round_index, r, seed, prob, priors, h_max=None):
     """Explore (b) of Section 4.1.1 for recipient r: every hyperparameter is, independently and with
     probability `prob`, drawn afresh from its prior (kind, lo, hi); otherwise the copied value is kept.
@@ -183,13 +231,14 @@ def perturb(h_src, round_index, r, seed, factor_lo, factor_hi, h_max=None):
 
 def exploit_explore(pop, round_index, seed, n_trunc, factor_lo=0.8, factor_hi=1.2, h_max=None,
                     scores=None, explore_fn=None, mode="truncation", copy_weights=True, copy_hypers=True,
-                    explore="perturb", resample_prob=0.0, priors=None):
+                    explore="perturb", resample_prob=0.0, priors=None, ttest_alpha=0.05):
     """One exploit-and-explore pass over the population, in place.
     `scores` overrides the members' stored p (float32).  `explore_fn(h, round,
     r)` replaces the explore rule (used by the toy example).  Returns (order, donor).
 
-    mode: "truncation" (Section 4.1.1 Exploit (b)) or "tournament" (Section 4.3.1 Exploit (b)).  In a
-    tournament a member can be donor and recipient in the same pass; every recipient receives its
+    mode: "truncation" (Section 4.1.1 Exploit (b)), "tournament" (Section 4.3.1 Exploit (b)) or "ttest"
+    (Section 4.1.1 Exploit (a), on the members' score histories).  In the last two a member can be donor
+    and recipient in the same pass; every recipient receives its
     donor's state as it was BEFORE the pass (all members act on the same snapshot).
     copy_weights / copy_hypers: the subsets of Section 4.4 ("PBT targets"): without copy_weights the
     recipient keeps its own weights, optimiser state, update count, score and history and only takes
@@ -206,6 +255,8 @@ def exploit_explore(pop, round_index, seed, n_trunc, factor_lo=0.8, factor_hi=1.
         order, donor = truncation_select(scores, n_trunc, round_index, seed)
     elif mode == "tournament":
         order, donor = binary_tournament(scores, round_index, seed)
+    elif mode == "ttest":
+        order, donor = ttest_select(scores, [m.hist for m in pop], round_index, seed, ttest_alpha)
     else:
         raise ValueError(mode)
     # assignments below replace attributes and never change the old objects, so these references are a snapshot

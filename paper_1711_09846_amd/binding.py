@@ -39,6 +39,7 @@ class PbtConfig(C.Structure):
                 ("tf_heads", C.c_int32), ("tf_d_ff", C.c_int32), ("tf_seq", C.c_int32), ("n_train", C.c_int32),
                 ("n_eval", C.c_int32), ("eval_chunk", C.c_int32), ("fuse_optimizer", C.c_int32), ("exploit_mode", C.c_int32),
                 ("explore_mode", C.c_int32), ("resample_prob", C.c_float), ("keep_weights", C.c_int32), ("keep_hypers", C.c_int32),
+                ("ttest_alpha", C.c_float),
                 ("seed", C.c_uint64)]
 
 
@@ -135,6 +136,7 @@ def make_config(wl, seed, P=None, n_trunc=None, eval_chunk=0, fuse_optimizer=0):
     c.resample_prob = getattr(wl, "resample_prob", 0.0)
     c.keep_weights = getattr(wl, "keep_weights", 0)
     c.keep_hypers = getattr(wl, "keep_hypers", 0)
+    c.ttest_alpha = getattr(wl, "ttest_alpha", 0.0)
     c.seed = seed
     return c
 

@@ -49,7 +49,11 @@ pbt_status check_config(const pbt_config* c, Plan* pl) {
   if (c->n_hyper < 1 || c->n_hyper > PBT_MAX_HYPER) return fail(nullptr, PBT_EINVAL, "n_hyper = %d outside 1..%d", c->n_hyper, PBT_MAX_HYPER);
   if (c->n_trunc < 0 || 2 * (int64_t)c->n_trunc > c->P) return fail(nullptr, PBT_EINVAL, "need 0 <= 2*n_trunc <= P (top and bottom sets must not overlap)");
   if (c->n_train < 1 || c->n_eval < 1) return fail(nullptr, PBT_EINVAL, "n_train and n_eval must be positive");
-  if (c->exploit_mode != PBT_EXPLOIT_TRUNCATION && c->exploit_mode != PBT_EXPLOIT_TOURNAMENT) return fail(nullptr, PBT_EINVAL, "unknown exploit_mode %d", c->exploit_mode);
+  if (c->exploit_mode < PBT_EXPLOIT_TRUNCATION || c->exploit_mode > PBT_EXPLOIT_TTEST) return fail(nullptr, PBT_EINVAL, "unknown exploit_mode %d", c->exploit_mode);
+  if (c->exploit_mode == PBT_EXPLOIT_TTEST) {
+    if (!a2c) return fail(nullptr, PBT_EINVAL, "t-test selection needs the score history of the actor-critic workload");
+    if (!(c->ttest_alpha > 0.f && c->ttest_alpha <= 1.f)) return fail(nullptr, PBT_EINVAL, "ttest_alpha must be in (0, 1]");
+  }
   if (c->explore_mode != PBT_EXPLORE_PERTURB && c->explore_mode != PBT_EXPLORE_RESAMPLE) return fail(nullptr, PBT_EINVAL, "unknown explore_mode %d", c->explore_mode);
   if (!(c->resample_prob >= 0.f)) return fail(nullptr, PBT_EINVAL, "resample_prob must be >= 0");
   if ((c->keep_weights != 0 && c->keep_weights != 1) || (c->keep_hypers != 0 && c->keep_hypers != 1)) return fail(nullptr, PBT_EINVAL, "keep_weights / keep_hypers are 0 or 1");
@@ -151,7 +155,7 @@ pbt_status make_plan(const pbt_config* c, Plan* pl) {
   Carver w;
   pl->o_grad = w.take(pw * 4);
   for (int k = 0; k < 6; ++k) pl->o_stage[k] = 0;
-  if (c->exploit_mode == PBT_EXPLOIT_TOURNAMENT && !c->keep_weights) {
+  if (c->exploit_mode != PBT_EXPLOIT_TRUNCATION && !c->keep_weights) {
     // a member can be donor and recipient: donor rows pass through these staging rows (same order as in pbt_exploit_explore)
     int k = 0;
     pl->o_stage[k++] = w.take(pw * 4);
@@ -583,7 +587,10 @@ pbt_status pbt_exploit_explore(pbt_handle* h, int64_t round_index, const float* 
   a.parent = h->st<int32_t>(p.o_parent);
   a.recip = h->st<int32_t>(p.o_recip);
   a.n_recip = h->st<int32_t>(p.o_nrecip);
-  a.tournament = c.exploit_mode == PBT_EXPLOIT_TOURNAMENT;
+  a.tournament = c.exploit_mode != PBT_EXPLOIT_TRUNCATION;
+  a.ttest = c.exploit_mode == PBT_EXPLOIT_TTEST;
+  a.ttest_alpha = (double)c.ttest_alpha;
+  a.hist = a.ttest ? h->st<float>(p.o_hist) : nullptr;
   a.resample = c.explore_mode == PBT_EXPLORE_RESAMPLE;
   a.keep_weights = c.keep_weights; a.keep_hypers = c.keep_hypers;
   a.resample_always = c.resample_prob >= 1.f;

@@ -141,7 +141,8 @@ struct ExploitArgs {
   float f_lo, f_hi;
   float h_max[8];
   uint32_t round; uint64_t seed;
-  int tournament, resample, keep_weights, keep_hypers;
+  int tournament, resample, keep_weights, keep_hypers;  // tournament: opponent drawn from the whole population
+  int ttest; double ttest_alpha; const float* hist;     // t-test selection on the score histories [P][12]
   uint32_t resample_thr; int resample_always;     // resample iff word < thr, or always
   int prior_kind[8]; double prior_a[8], prior_b[8];  // as in InitArgs
 };

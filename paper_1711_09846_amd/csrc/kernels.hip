@@ -348,6 +348,57 @@ __device__ __forceinline__ bool ranks_above(float sj, int j, float si, int i) {
   return j < i;
 }
 
+// ---- Welch's t-test (Section 4.1.1, Exploit (a)) in double -----------------------------------
+// Continued fraction of the incomplete beta function, evaluated with the modified Lentz scheme.
+__device__ double beta_cf(double a, double b, double x) {
+  const double tiny = 1e-300;
+  double c = 1.0, d = 1.0 - (a + b) * x / (a + 1.0);
+  if (fabs(d) < tiny) d = tiny;
+  d = 1.0 / d;
+  double h = d;
+  for (int m = 1; m <= 400; ++m) {
+    const double m2 = 2.0 * m;
+    double num = m * (b - m) * x / ((a + m2 - 1.0) * (a + m2));
+    d = 1.0 + num * d; if (fabs(d) < tiny) d = tiny;
+    c = 1.0 + num / c; if (fabs(c) < tiny) c = tiny;
+    d = 1.0 / d;
+    h *= d * c;
+    num = -(a + m) * (a + b + m) * x / ((a + m2) * (a + m2 + 1.0));
+    d = 1.0 + num * d; if (fabs(d) < tiny) d = tiny;
+    c = 1.0 + num / c; if (fabs(c) < tiny) c = tiny;
+    d = 1.0 / d;
+    const double del = d * c;
+    h *= del;
+    if (fabs(del - 1.0) < 1e-16) break;
+  }
+  return h;
+}
+// regularised incomplete beta function I_x(a, b)
+__device__ double beta_inc(double a, double b, double x) {
+  if (x <= 0.0) return 0.0;
+  if (x >= 1.0) return 1.0;
+  const double front = exp(lgamma(a + b) - lgamma(a) - lgamma(b) + a * log(x) + b * log1p(-x));
+  if (x < (a + 1.0) / (a + b + 2.0)) return front * beta_cf(a, b, x) / a;
+  return 1.0 - front * beta_cf(b, a, 1.0 - x) / b;
+}
+// P(T_nu > t), t >= 0
+__device__ double student_sf(double t, double nu) { return 0.5 * beta_inc(0.5 * nu, 0.5, nu / (nu + t * t)); }
+
+// mean and variance-of-the-mean (s^2 / n, s^2 unbiased) of a member's recorded scores, oldest first
+__device__ int hist_stats(const float* __restrict__ hrow, double* mean, double* vmean) {
+  const int n = __float_as_int(hrow[10]);
+  const int m = n < 10 ? n : 10;
+  if (m < 2) return m;
+  double acc = 0.0;
+  for (int k = 0; k < m; ++k) acc += (double)hrow[(n - m + k) % 10];
+  const double mu = acc / (double)m;
+  double ss = 0.0;
+  for (int k = 0; k < m; ++k) { const double dv = (double)hrow[(n - m + k) % 10] - mu; ss += dv * dv; }
+  *mean = mu;
+  *vmean = ss / (double)(m - 1) / (double)m;
+  return m;
+}
+
 __global__ __launch_bounds__(1024) void rank_select_explore_kernel(ExploitArgs a) {
   __shared__ float sc[1024];
   __shared__ int ord[1024];
@@ -376,7 +427,21 @@ __global__ __launch_bounds__(1024) void rank_select_explore_kernel(ExploitArgs a
       if (a.P > 1) {
         int j = (int)philox_bounded(x, (uint32_t)(a.P - 1));
         j += j >= i ? 1 : 0;
-        if (place[j] < pos) d = j;
+        if (!a.ttest) {
+          if (place[j] < pos) d = j;
+        } else {
+          double mi, vi, mj, vj;
+          const int ni = hist_stats(a.hist + (int64_t)i * 12, &mi, &vi), nj = hist_stats(a.hist + (int64_t)j * 12, &mj, &vj);
+          if (ni >= 2 && nj >= 2 && mj > mi) {
+            if (vi + vj == 0.0) {
+              d = j;
+            } else {
+              const double t = (mj - mi) / sqrt(vi + vj);
+              const double nu = (vi + vj) * (vi + vj) / (vi * vi / (double)(ni - 1) + vj * vj / (double)(nj - 1));
+              if (student_sf(t, nu) < a.ttest_alpha) d = j;
+            }
+          }
+        }
       }
     } else if (a.n_trunc > 0 && pos >= first_bottom) {
       d = ord[philox_bounded(x, (uint32_t)a.n_trunc)];

@@ -9,7 +9,8 @@ from paper_1711_09846_amd import binding, workloads
 
 def exploit_variant(wl):
     """The oracle's keyword arguments for the exploit / explore variant a workload description selects."""
-    return dict(mode="tournament" if getattr(wl, "exploit_mode", 0) else "truncation",
+    return dict(mode=("truncation", "tournament", "ttest")[getattr(wl, "exploit_mode", 0)],
+                ttest_alpha=float(np.float32(getattr(wl, "ttest_alpha", 0.05))),
                 copy_weights=not getattr(wl, "keep_weights", 0), copy_hypers=not getattr(wl, "keep_hypers", 0),
                 explore="resample" if getattr(wl, "explore_mode", 0) else "perturb",
                 resample_prob=float(np.float32(getattr(wl, "resample_prob", 0.0))), priors=wl.priors)

@@ -112,3 +112,22 @@ def test_dense_workload_segments_mirror_layer_offsets():
     for l in range(len(dims) - 1):
         assert (lay.seg_off[2 * l], lay.seg_len[2 * l]) == (lay.w_off[l], dims[l] * dims[l + 1])
         assert (lay.seg_off[2 * l + 1], lay.seg_len[2 * l + 1]) == (lay.b_off[l], dims[l + 1])
+
+
+@pytest.mark.parametrize("bad", [dict(exploit_mode=3), dict(explore_mode=5), dict(resample_prob=-0.5), dict(keep_weights=1, keep_hypers=1),
+                                 dict(exploit_mode=2, ttest_alpha=0.05)])
+def test_exploit_variant_configurations_are_checked(bad):
+    """The last case: t-test selection needs the actor-critic workload's score history."""
+    with pytest.raises(binding.PbtError):
+        binding.query_sizes(binding.make_config(workloads.MLP_WIDE.replace(**bad), 1))
+
+
+def test_exploit_variants_size_their_staging_rows():
+    base = binding.query_sizes(binding.make_config(workloads.MLP_WIDE, 1))
+    tour = binding.query_sizes(binding.make_config(workloads.MLP_WIDE.replace(exploit_mode=1), 1))
+    assert tour[0] == base[0] and tour[1] >= base[1] + workloads.MLP_WIDE.P * base[2].stride * 14
+    ok = binding.query_sizes(binding.make_config(workloads.A2C_MLP.replace(exploit_mode=2, ttest_alpha=0.05), 1))
+    assert ok[1] > binding.query_sizes(binding.make_config(workloads.A2C_MLP, 1))[1]
+    for alpha in (0.0, 1.5):
+        with pytest.raises(binding.PbtError):
+            binding.query_sizes(binding.make_config(workloads.A2C_MLP.replace(exploit_mode=2, ttest_alpha=alpha), 1))

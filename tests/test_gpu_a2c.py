@@ -98,3 +98,39 @@ def test_a2c_full_size_steps_score_and_copy():
             before[binding.ARR_HYPER][src], 0, r, pair.seed, wl.perturb[0], wl.perturb[1], wl.h_max)
         assert after[binding.ARR_HYPER][r].tobytes() == href.tobytes()
     print("a2c full size:", {k: float("%.3g" % v) for k, v in worst.items()}, flush=True)
+
+
+@pytest.mark.parametrize("alpha", [0.05, 0.5, 1.0])
+def test_a2c_ttest_selection_bit_exact(alpha):
+    """Section 4.1.1 Exploit (a): opponent drawn uniformly, Welch's test on the last 10 unroll returns.
+    Both sides decide from the same float32 histories in double precision."""
+    wl = _reduced(P=12).replace(exploit_mode=2, ttest_alpha=alpha)
+    pair = A2CPair(wl)
+    g, P = pair.gpu, wl.P
+    n_copy = n_chain = 0
+    rnd = 0
+    for s in range(16):
+        g.step(pair.d_pool, s)
+        if s == 0:                                                    # one entry only: nobody may copy
+            g.exploit_explore(99)
+            assert np.all(g.get(binding.ARR_DONOR) == -1)
+        if s >= 3 and s % 4 == 3:
+            for i in range(P):
+                pair.sync_ref_from_gpu(i)
+            sc = _eval(g)
+            before = {w: g.get(w).copy() for w in (binding.ARR_W32, binding.ARR_OPT0, binding.ARR_W16, binding.ARR_HIST, binding.ARR_HYPER)}
+            g.exploit_explore(rnd)
+            order, donor = pair.exploit_ref(rnd, sc)
+            assert list(g.get(binding.ARR_ORDER)) == order and np.array_equal(g.get(binding.ARR_DONOR), donor), (s, donor)
+            n_copy += int((donor >= 0).sum())
+            n_chain += sum(1 for i in range(P) if donor[i] >= 0 and donor[donor[i]] >= 0)
+            after = {w: g.get(w) for w in before}
+            for i in range(P):
+                src = donor[i] if donor[i] >= 0 else i
+                for w in (binding.ARR_W32, binding.ARR_OPT0, binding.ARR_W16, binding.ARR_HIST):
+                    assert after[w][i].tobytes() == before[w][src].tobytes()
+            assert after[binding.ARR_HYPER].tobytes() == np.stack([pair.ref[i].h for i in range(P)]).tobytes()
+            _hist_equal(pair, range(P))
+            rnd += 1
+    assert n_copy > 0
+    print("t-test selection alpha %.2f: %d copies, %d of them from a member that was itself overwritten" % (alpha, n_copy, n_chain), flush=True)

@@ -363,3 +363,69 @@ def test_resample_explore_frequency_range_and_passthrough():
     always = pbt.resample(h, 3, 0, 11, 1.0, priors)
     assert always[0] != h[0] and always[1] != h[1]
     assert pbt.resample(h, 3, 0, 11, 1.0, priors, h_max=[1e-3, 0.9])[0] <= np.float32(1e-3)
+
+
+# ---- t-test selection (Section 4.1.1, Exploit (a)) ---------------------------------------------------
+
+def test_student_sf_closed_forms_and_quadrature():
+    for t in (0.0, 0.3, 1.0, 2.5, 7.0):
+        assert abs(pbt.student_sf(t, 1.0) - (0.5 - math.atan(t) / math.pi)) < 1e-13          # Cauchy
+        assert abs(pbt.student_sf(t, 2.0) - (0.5 - t / (2.0 * math.sqrt(2.0 + t * t)))) < 1e-13
+    # nu = 7.3: integrate the density numerically
+    nu = 7.3
+    c = math.exp(math.lgamma((nu + 1) / 2) - math.lgamma(nu / 2)) / math.sqrt(nu * math.pi)
+    xs = np.linspace(1.7, 400.0, 2_000_001)
+    dens = c * (1.0 + xs * xs / nu) ** (-(nu + 1) / 2)
+    integral = float(((dens[:-1] + dens[1:]) * 0.5 * np.diff(xs)).sum())
+    assert abs(pbt.student_sf(1.7, nu) - integral) < 1e-7
+    assert abs(pbt.student_sf(3.0, 1e9) - 0.5 * math.erfc(3.0 / math.sqrt(2.0))) < 1e-9     # normal limit
+
+
+def test_welch_statistic_by_hand_and_against_library():
+    a, b = [1.0, 2.0, 3.0, 4.0], [2.0, 4.0, 6.0]
+    t, nu, ma, mb = pbt.welch(a, b)
+    # hand: var(a) = 5/3, var(b) = 4; va = 5/12, vb = 4/3; t = (4 - 2.5)/sqrt(7/4); nu = (7/4)^2 / ((5/12)^2/3 + (4/3)^2/2)
+    assert (ma, mb) == (2.5, 4.0)
+    assert abs(t - 1.5 / math.sqrt(1.75)) < 1e-15 and abs(nu - 1.75 ** 2 / ((5 / 12) ** 2 / 3 + (4 / 3) ** 2 / 2)) < 1e-13
+    from scipy import stats
+    rng = np.random.default_rng(0)
+    for _ in range(20):
+        x, y = rng.standard_normal(rng.integers(2, 11)), rng.standard_normal(rng.integers(2, 11)) + 0.5
+        t, nu, _, _ = pbt.welch(x, y)
+        ref = stats.ttest_ind(y, x, equal_var=False, alternative="greater")
+        assert abs(t - ref.statistic) < 1e-12
+        if t > 0:
+            assert abs(pbt.student_sf(t, nu) - ref.pvalue) < 1e-12
+    assert pbt.welch([1.0, 1.0], [2.0, 2.0])[0] == math.inf
+
+
+def test_ttest_select_rules():
+    rng = np.random.default_rng(1)
+    P = 7
+    hists = [list(rng.standard_normal(10) * 0.1 + m) for m in (0.0, 1.0, 0.05, 2.0, 0.0, 1.0)] + [[5.0]]   # last: one score only
+    scores = np.array([np.mean(h) for h in hists], dtype=np.float32)
+    n_copy = 0
+    for rnd in range(200):
+        order, donor = pbt.ttest_select(scores, hists, rnd, 3, 0.05)
+        assert order == pbt.rank_order(scores)
+        for i in range(P):
+            x = philox.words(3, rnd, i, philox.DOMAIN_DONOR, 0)[0]
+            j = (int(x) * (P - 1)) >> 32
+            j += 1 if j >= i else 0
+            if i == 6 or j == 6:
+                assert donor[i] == -1                                    # too short a history on either side
+                continue
+            better = np.mean(hists[j]) > np.mean(hists[i])
+            clear = abs(np.mean(hists[j]) - np.mean(hists[i])) > 0.5     # 0.1 noise: a gap of 1 is significant, 0.05 is not
+            if better and clear:
+                assert donor[i] == j
+                n_copy += 1
+            elif not better:
+                assert donor[i] == -1
+            elif {i, j} == {0, 2} or {i, j} == {2, 4} or {i, j} == {0, 4} or {i, j} == {1, 5}:
+                assert donor[i] == -1 or pbt.student_sf(*pbt.welch(hists[i], hists[j])[:2]) < 0.05
+    assert n_copy > 100
+    # alpha = 1 turns the test into "higher mean wins"; alpha = 0 never copies
+    _, d1 = pbt.ttest_select(scores, hists, 0, 3, 1.0)
+    _, d0 = pbt.ttest_select(scores, hists, 0, 3, 0.0)
+    assert np.all(d0 == -1) and (d1 >= 0).sum() >= (pbt.ttest_select(scores, hists, 0, 3, 0.05)[1] >= 0).sum()
