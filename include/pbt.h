@@ -189,8 +189,9 @@ typedef struct {
 } pbt_prior;
 
 /* Figure 1(c) / Algorithm 1, initial population drawn on the device: every member gets independent
- * random weights (uniform in +-1/sqrt(fan_in) per layer, biases included) and hyperparameters drawn
- * from priors[0..n_hyper-1] (HOST array).  Random words: Philox counter (0, member, domain 4,
+ * random weights (dense layers: uniform in +-1/sqrt(fan_in), biases included; transformer: tables and
+ * matrices uniform in +-1/sqrt(fan_in) with fan_in = d_model for the two tables, LayerNorm gains 1,
+ * biases 0) and hyperparameters drawn from priors[0..n_hyper-1] (HOST array).  Random words: Philox counter (0, member, domain 4,
  * position / 4) word position % 4 for the value at `position` of the member's flat parameter vector;
  * counter (0, member, domain 5, column) word 0 for a hyperparameter; u = (x + 0.5) / 2^32, evaluated
  * in double precision and rounded once to float.  Optimiser state, t and scores are reset as in

@@ -85,6 +85,24 @@ def init_weights(seed, member, dims, offsets):
     return layers
 
 
+def init_segments(seed, member, segments):
+    """Initial values of arbitrary parameter arrays of one member: segments = [(start, shape, fan,
+    const), ...] in positions of the member's flat vector; fan > 0: uniform in (-1/sqrt fan, 1/sqrt fan)
+    from the same Philox words as init_weights (word p % 4 of counter (0, member, DOMAIN_INIT_W,
+    p // 4) for position p); fan == 0: the constant.  Returns float32 arrays."""
+    out = []
+    for start, shape, fan, const in segments:
+        count = int(np.prod(shape))
+        if fan > 0:
+            pos = start + np.arange(count)
+            w = philox.words(seed, 0, member, philox.DOMAIN_INIT_W, pos // 4)
+            u = philox.unit_open(w[np.arange(count), pos % 4])
+            out.append(((2.0 * u - 1.0) / math.sqrt(fan)).astype(np.float32).reshape(shape))
+        else:
+            out.append(np.full(shape, const, dtype=np.float32))
+    return out
+
+
 def rank_order(scores):
     """Member indices from best to worst."""
     s = np.asarray(scores, dtype=np.float32)

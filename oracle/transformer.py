@@ -67,6 +67,21 @@ class TransformerSpec:
         return out
 
 
+def init_arrays(spec, seed, member, starts):
+    """Initial parameter arrays of one member (Figure 1c: random weight initialisations): token and
+    position tables and all matrices uniform in +-1/sqrt(fan_in) (fan_in = d_model for the tables),
+    LayerNorm gains 1, every bias 0; starts[j] = position of array j in the member's flat vector."""
+    segs = []
+    for (name, shape), start in zip(spec.param_shapes(), starts):
+        if name in ("tok_emb", "pos_emb"):
+            segs.append((start, shape, spec.d, 0.0))
+        elif len(shape) == 2:
+            segs.append((start, shape, shape[0], 0.0))
+        else:
+            segs.append((start, shape, 0, 1.0 if "_g" in name else 0.0))
+    return pbt.init_segments(seed, member, segs)
+
+
 def new_member(spec, arrays, h, index):
     flat = [np.array(a, dtype=np.float64) for a in arrays]
     assert [a.shape for a in flat] == [s for _, s in spec.param_shapes()]

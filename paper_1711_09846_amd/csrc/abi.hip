@@ -456,8 +456,6 @@ pbt_status pbt_init_population(pbt_handle* h, const pbt_prior* priors, void* hip
   if (!priors) return fail(h, PBT_EINVAL, "priors is NULL");
   const pbt_config& c = h->cfg;
   const Plan& p = h->plan;
-  if (c.workload == PBT_WL_TRANSFORMER)
-    return fail(h, PBT_EUNSUPPORTED, "device-side initialisation is not built for the transformer workload; use pbt_set_state");
   InitArgs a;
   std::memset(&a, 0, sizeof a);
   for (int k = 0; k < c.n_hyper; ++k) {
@@ -477,12 +475,22 @@ pbt_status pbt_init_population(pbt_handle* h, const pbt_prior* priors, void* hip
   a.W16 = c.compute_dtype == PBT_DTYPE_BF16 ? h->st<bf16_t>(p.o_w16) : nullptr;
   a.H = h->st<float>(p.o_hyper);
   a.stride = p.lay.stride; a.P = c.P; a.n_hyper = c.n_hyper;
-  a.n_layers = c.n_layers + (c.workload == PBT_WL_GAN ? c.n_layers2 : 0);
-  for (int l = 0; l < a.n_layers; ++l) {
-    a.fan_in[l] = l < c.n_layers ? c.dims[l] : c.dims2[l - c.n_layers];
-    a.fan_out[l] = l < c.n_layers ? c.dims[l + 1] : c.dims2[l - c.n_layers + 1];
-    a.w_off[l] = p.lay.w_off[l];
-    a.b_off[l] = p.lay.b_off[l];
+  a.n_seg = p.lay.n_seg;
+  for (int k = 0; k < a.n_seg; ++k) { a.seg_off[k] = p.lay.seg_off[k]; a.seg_len[k] = p.lay.seg_len[k]; a.seg_fan[k] = 0; a.seg_const[k] = 0.f; }
+  if (c.workload == PBT_WL_TRANSFORMER) {
+    // embeddings and matrices uniform in +-1/sqrt(fan_in) (fan_in = d_model for the two tables), LayerNorm gains 1, every bias 0
+    const int d = c.tf_d_model, f = c.tf_d_ff;
+    a.seg_fan[0] = a.seg_fan[1] = d;
+    for (int l = 0; l < c.n_layers; ++l) {
+      const int b0 = 2 + 12 * l;
+      a.seg_const[b0 + 0] = 1.f; a.seg_fan[b0 + 2] = d; a.seg_fan[b0 + 4] = d;
+      a.seg_const[b0 + 6] = 1.f; a.seg_fan[b0 + 8] = d; a.seg_fan[b0 + 10] = f;
+    }
+    a.seg_const[a.n_seg - 4] = 1.f; a.seg_fan[a.n_seg - 2] = d;
+  } else {
+    // dense layers: weights and biases of a layer uniform in +-1/sqrt(fan_in)
+    const int n_layers = c.n_layers + (c.workload == PBT_WL_GAN ? c.n_layers2 : 0);
+    for (int l = 0; l < n_layers; ++l) a.seg_fan[2 * l] = a.seg_fan[2 * l + 1] = l < c.n_layers ? c.dims[l] : c.dims2[l - c.n_layers];
   }
   a.seed = c.seed;
   PBT_HIP(h, init_population(a, s));

@@ -1,6 +1,7 @@
 // Host-callable launchers of the population-step kernels.  Every launcher only enqueues on
 // `stream` and returns the launch status; none allocates or synchronises.
 #pragma once
+#include "../../include/pbt.h"
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -71,8 +72,9 @@ hipError_t row_reduce(const float* rowval, int64_t srow, int P, int rows, float 
 // hyperparameters from the priors; all in double, rounded once to float.
 struct InitArgs {
   float* W32; bf16_t* W16; float* H;
-  int64_t stride; int P, n_layers, n_hyper;
-  int fan_in[16], fan_out[16]; int64_t w_off[16], b_off[16];
+  int64_t stride; int P, n_seg, n_hyper;
+  // parameter arrays of one member: fan > 0: uniform in +-1/sqrt(fan); fan == 0: the constant
+  int64_t seg_off[PBT_MAX_SEGMENTS], seg_len[PBT_MAX_SEGMENTS]; int seg_fan[PBT_MAX_SEGMENTS]; float seg_const[PBT_MAX_SEGMENTS];
   int prior_kind[8]; double prior_a[8], prior_b[8];  // uniform: a + u (b - a); log: exp(a + u (b - a)), a = ln lo
   uint64_t seed;
 };

@@ -41,27 +41,25 @@ hipError_t f32_to_bf16(const float* src, bf16_t* dst, int64_t n, hipStream_t s) 
 }
 
 // ---- initial population ----------------------------------------------------------------------
-// grid (ceil(stride / 256), P): one thread per position of the flat parameter vector.
+// grid (chunks, parameter arrays, P): one thread per element of one parameter array.  The value at
+// position p of the member's flat vector depends on p alone (word p % 4 of Philox counter
+// (0, member, DOMAIN_INIT_W, p / 4)), not on how the grid is cut.
 __global__ __launch_bounds__(256) void init_population_kernel(InitArgs a) {
-  const int i = blockIdx.y;
-  const int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int i = blockIdx.z, seg = blockIdx.y;
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
-  if (p < a.stride) {
-    int fan_in = 0;
-    for (int l = 0; l < a.n_layers; ++l) {
-      const int64_t nw = (int64_t)a.fan_in[l] * a.fan_out[l];
-      if ((p >= a.w_off[l] && p < a.w_off[l] + nw) || (p >= a.b_off[l] && p < a.b_off[l] + a.fan_out[l])) fan_in = a.fan_in[l];
-    }
-    float v = 0.f;
-    if (fan_in > 0) {
+  if (e < a.seg_len[seg]) {
+    const int64_t p = a.seg_off[seg] + e;
+    float v = a.seg_const[seg];
+    if (a.seg_fan[seg] > 0) {
       const u32x4 w = philox4x32_10(0u, (uint32_t)i, DOMAIN_INIT_W, (uint32_t)(p >> 2), k0, k1);
       const uint32_t x = (p & 3) == 0 ? w.x : (p & 3) == 1 ? w.y : (p & 3) == 2 ? w.z : w.w;
-      v = (float)((2.0 * philox_unit(x) - 1.0) / sqrt((double)fan_in));
+      v = (float)((2.0 * philox_unit(x) - 1.0) / sqrt((double)a.seg_fan[seg]));
     }
     a.W32[(int64_t)i * a.stride + p] = v;
     if (a.W16) a.W16[(int64_t)i * a.stride + p] = f2bf(v);
   }
-  if (blockIdx.x == 0 && threadIdx.x < a.n_hyper) {
+  if (blockIdx.x == 0 && seg == 0 && threadIdx.x < a.n_hyper) {
     const int k = threadIdx.x;
     const double u = philox_unit(philox4x32_10(0u, (uint32_t)i, DOMAIN_INIT_H, (uint32_t)k, k0, k1).x);
     const double lin = a.prior_a[k] + u * (a.prior_b[k] - a.prior_a[k]);
@@ -69,7 +67,9 @@ __global__ __launch_bounds__(256) void init_population_kernel(InitArgs a) {
   }
 }
 hipError_t init_population(const InitArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(init_population_kernel, dim3((unsigned)((a.stride + 255) / 256), a.P), dim3(256), 0, s, a);
+  int64_t longest = 1;
+  for (int k = 0; k < a.n_seg; ++k) longest = a.seg_len[k] > longest ? a.seg_len[k] : longest;
+  hipLaunchKernelGGL(init_population_kernel, dim3((unsigned)((longest + 255) / 256), a.n_seg, a.P), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -40,3 +40,32 @@ def test_init_population_rejects_bad_priors():
         pop.init_population([("log", 0.0, 1.0)])
     with pytest.raises(binding.PbtError):
         pop.init_population([("uniform", 2.0, 1.0)])
+
+
+def test_init_population_transformer_matches_oracle():
+    from oracle import transformer as ot
+    wl = workloads.TRANSFORMER.replace(P=3, vocab=64, d_model=32, heads=2, d_ff=64, n_blocks=2, seq=16, batch=4, n_train=64, n_eval=8, n_trunc=1)
+    seed = 0x51
+    pop = binding.Population(binding.make_config(wl, seed))
+    pop.init_population(wl.priors)
+    lay = pop.layout
+    spec = ot.TransformerSpec(wl.vocab, wl.d_model, wl.heads, wl.d_ff, wl.n_blocks, wl.seq, wl.batch, seed, roles=wl.roles)
+    shapes = workloads.transformer_shapes(wl)
+    W, W16 = pop.get(binding.ARR_W32), pop.get(binding.ARR_W16)
+    for i in range(wl.P):
+        ref = binding.pack_segments(lay, ot.init_arrays(spec, seed, i, [lay.seg_off[j] for j in range(lay.n_seg)]))
+        assert W[i].tobytes() == ref.tobytes()
+        got = binding.unpack_segments(lay, shapes, W[i])
+        assert np.all(got[2] == 1.0) and np.all(got[3] == 0.0) and np.all(got[-1] == 0.0)     # gain, bias, head bias
+    import torch
+    assert np.array_equal(W16, torch.from_numpy(W).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+    H, Href = pop.get(binding.ARR_HYPER), opbt.init_hyperparameters(seed, wl.P, wl.priors)
+    assert np.all(np.abs(H.view(np.int32) - Href.view(np.int32)) <= 1)
+    # and the initialised population trains
+    pair_pool, _ = workloads.zipf_bigram_sequences(wl)
+    d_pool = [torch.from_numpy(pair_pool).cuda()]
+    pop.step(d_pool, 0)
+    l0 = pop.get(binding.ARR_LOSS).copy()
+    for s in range(1, 40):
+        pop.step(d_pool, s)
+    assert np.all(np.isfinite(l0)) and np.all(pop.get(binding.ARR_LOSS) < l0)

@@ -429,3 +429,13 @@ def test_ttest_select_rules():
     _, d1 = pbt.ttest_select(scores, hists, 0, 3, 1.0)
     _, d0 = pbt.ttest_select(scores, hists, 0, 3, 0.0)
     assert np.all(d0 == -1) and (d1 >= 0).sum() >= (pbt.ttest_select(scores, hists, 0, 3, 0.05)[1] >= 0).sum()
+
+
+def test_init_segments_matches_init_weights_and_constants():
+    dims, offsets = [5, 7, 3], [(0, 64), (128, 192)]
+    layers = pbt.init_weights(11, 2, dims, offsets)
+    segs = pbt.init_segments(11, 2, [(0, (5, 7), 5, 0.0), (64, (7,), 5, 0.0), (128, (7, 3), 7, 0.0), (192, (3,), 7, 0.0), (256, (4,), 0, 1.0)])
+    for (W, b), k in zip(layers, (0, 2)):
+        assert W.tobytes() == segs[k].tobytes() and b.tobytes() == segs[k + 1].tobytes()
+    assert np.all(segs[4] == 1.0)
+    assert np.all(np.abs(segs[0]) < 1 / math.sqrt(5)) and abs(float(segs[2].mean())) < 0.2

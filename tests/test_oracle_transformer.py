@@ -155,3 +155,21 @@ def test_step_trains_and_bf16_storage_is_close():
     for nm in ("whead", "w10", "wqkv0", "tok_emb"):
         j = names.index(nm)
         assert np.linalg.norm(ga[j] - gb[j]) < 0.35 * np.linalg.norm(ga[j])   # many rounding points, width-8 layers
+
+
+def test_init_arrays_rule():
+    spec = _spec()
+    starts, pos = [], 0
+    for _, shape in spec.param_shapes():
+        starts.append(pos)
+        pos += -(-int(np.prod(shape)) // 64) * 64
+    arrays = tf.init_arrays(spec, 5, 1, starts)
+    for (name, shape), a in zip(spec.param_shapes(), arrays):
+        assert a.shape == shape and a.dtype == np.float32
+        if len(shape) == 2:
+            fan = spec.d if name.endswith("_emb") else shape[0]
+            assert np.all(np.abs(a) < 1 / math.sqrt(fan)) and a.std() > 0.3 / math.sqrt(fan)
+        else:
+            assert np.all(a == (1.0 if "_g" in name else 0.0))
+    again = tf.init_arrays(spec, 5, 2, starts)
+    assert not np.array_equal(arrays[0], again[0])                       # members are initialised independently
