@@ -24,35 +24,60 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 MEASURED_TRAFFIC_BYTES = {(2, "optimizer"): 2.541e9, (4, "optimizer"): 10.115e9}
 
 
-def cpu_baseline(wl, data, seed, budget_s=15.0):
-    """The oracle as it stands, timed on the host cores over a bounded sample of the workload."""
+def cpu_baseline(workload, wl, seed, budget_s=15.0):
+    """The oracle as it stands, timed on the host cores over a bounded sample of the workload:
+    member-steps of the first population step(s), member after member, until the budget is used."""
     import numpy as np
-    from oracle import classifier as oc
     from paper_1711_09846_amd import workloads
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from tests.harness import oracle_spec
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count()
-    (tx, ty), _ = data
-    spec = oracle_spec(wl, seed)
-    weights = workloads.initial_mlp_weights(wl.dims, wl.P, 5)
     H = workloads.initial_hypers(wl, 6)
-    pop = [oc.new_member(spec, weights[i], H[i], i) for i in range(wl.P)]
-    done, t0 = 0, time.perf_counter()
-    s = 0
-    while True:
+    oc = {k: float(np.float32(v)) for k, v in wl.opt_const.items()}
+    if workload == 2:
+        from oracle import classifier as o
+        from tests.harness import oracle_spec
+        (tx, ty), _ = workloads.classifier_data(wl)
+        spec = oracle_spec(wl, seed)
+        weights = workloads.initial_mlp_weights(wl.dims, wl.P, 5)
+        pop = [o.new_member(spec, weights[i], H[i], i) for i in range(wl.P)]
+        step = lambda m, i, s: o.step(spec, m, i, s, tx, ty)
+    elif workload == 3:
+        from oracle import gan as o
+        tx, _ = workloads.gan_data(wl)
+        spec = o.GanSpec(wl.dims, wl.dims2, wl.batch, seed, roles=wl.roles, beta1=oc["beta1"], beta2=oc["beta2"], eps=oc["eps"], bf16_storage=True)
+        weights = workloads.initial_gan_weights(wl, wl.P, 5)
+        pop = [o.new_member(spec, weights[i][0], weights[i][1], H[i], i) for i in range(wl.P)]
+        step = lambda m, i, s: o.step(spec, m, i, s, tx)
+    elif workload == 4:
+        from oracle import transformer as o
+        pool, _ = workloads.zipf_bigram_sequences(wl)
+        spec = o.TransformerSpec(wl.vocab, wl.d_model, wl.heads, wl.d_ff, wl.n_blocks, wl.seq, wl.batch, seed, roles=wl.roles,
+                                 beta1=oc["beta1"], beta2=oc["beta2"], eps=oc["eps"], bf16_storage=True)
+        weights = workloads.initial_transformer_weights(wl, 2, 5)
+        pop = [o.new_member(spec, weights[i], H[i], i) for i in range(2)]
+        step = lambda m, i, s: o.step(spec, m, i, s, pool)
+    else:
+        from oracle import a2c as o
+        obs, act, rew = workloads.trajectory_pool(wl)
+        spec = o.A2CSpec(wl.dims[:-1], wl.n_actions, wl.batch, wl.unroll, seed, roles=wl.roles, gamma=float(np.float32(wl.gamma)),
+                         value_cost=float(np.float32(wl.value_cost)), rho=oc["rho"], rms_eps=oc["eps"], hidden_act=wl.act, bf16_storage=True)
+        weights = workloads.initial_mlp_weights(wl.dims, wl.P, 5)
+        pop = [o.new_member(spec, weights[i], H[i], i) for i in range(wl.P)]
+        step = lambda m, i, s: o.step(spec, m, i, s, obs, act, rew)
+    done, s, t0 = 0, 0, time.perf_counter()
+    while time.perf_counter() - t0 < budget_s and s < 32:
         for i, m in enumerate(pop):
-            oc.step(spec, m, i, s, tx, ty)
+            step(m, i, s)
             done += 1
+            if time.perf_counter() - t0 >= budget_s:
+                break
         s += 1
-        if time.perf_counter() - t0 >= budget_s or s >= 32:
-            break
     dt = time.perf_counter() - t0
     return {"value": done / dt, "unit": "member-steps/s", "cores": int(cores), "kind": "oracle",
-            "sample": "%d population steps (%d member-steps) of %s, step only, numpy float64" % (s, done, wl.name)}
+            "sample": "%d member-steps of %s (step only, numpy float64 with bf16 storage rounding where the workload has it)" % (done, wl.name)}
 
 
 def main():
@@ -192,8 +217,8 @@ def main():
                    "exploit_rounds_in_timed_region": n_rounds},
         "roofline": roofline,
     }
-    if not args.no_cpu_baseline and args.workload == 2:
-        out["cpu_baseline"] = cpu_baseline(wl, data, seed)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.workload, wl, seed)
     print(json.dumps(out))
 
 
