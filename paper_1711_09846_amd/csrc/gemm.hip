@@ -1,11 +1,22 @@
 // Instantiations of the population-batched bf16 MFMA GEMM for the epilogues the step uses.
 #include "gemm_bf16.h"
+#include "gemm_nt_lds.h"
 #include "internal.h"
 
 namespace pbt {
 
 template <class E>
 static hipError_t run(const GemmOperands& o, const E& e, hipStream_t s) {
+  // long contractions of two K-contiguous operands (input gradients) take the direct-to-LDS kernel
+  if constexpr (std::is_same_v<E, EpiStoreBF16> || std::is_same_v<E, EpiDgradAct>) {
+    GemmArgs g;
+    g.A = o.A; g.lda = o.lda; g.sa = o.sa;
+    g.B = o.B; g.ldb = o.ldb; g.sb = o.sb;
+    g.M = o.M; g.N = o.N; g.K = o.K; g.batch = o.batch;
+    g.tiles_m = g.tiles_n = 0;
+    g.inner = o.inner < 1 ? 1 : o.inner; g.sa_in = o.sa_in; g.sb_in = o.sb_in;
+    if (nt_lds_applies(g, o.a_m_contig, o.b_k_contig)) return launch_gemm_nt_lds(g, e, s);
+  }
   return launch_gemm_bf16<E>(o.A, o.lda, o.sa, o.a_m_contig, o.B, o.ldb, o.sb, o.b_k_contig, o.M, o.N, o.K, o.batch, e, s, o.inner,
                              o.sa_in, o.sb_in);
 }
