@@ -21,7 +21,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 # for a copy of known size (profiles/population_step_<workload>_hbm_counters.md), by (workload, kernel
 # class).  An entry is only valid for the kernel as it was when the counters were taken; remove it when
 # the kernel changes.
-MEASURED_TRAFFIC_BYTES = {(2, "optimizer"): 2.541e9, (4, "optimizer"): 10.115e9}
+MEASURED_TRAFFIC_BYTES = {(2, "optimizer"): 2.541e9, (2, "gemm_wgrad_fused"): 1.1184e9, (4, "optimizer"): 10.115e9}
 
 
 def cpu_baseline(workload, wl, seed, budget_s=15.0):
@@ -86,9 +86,9 @@ def main():
     ap.add_argument("--steps", type=int, default=None, help="default 400 (30 for the transformer workload)")
     ap.add_argument("--warmup", type=int, default=None, help="default 20 (3 for the transformer workload)")
     ap.add_argument("--kernel", default=None, help="kernel class whose roofline is reported (default: the dominant one)")
-    ap.add_argument("--fused", type=int, default=0, choices=[0, 1],
-                    help="0 = separate streaming optimiser pass (default, the faster of the two as measured), "
-                         "1 = optimiser applied inside the weight-gradient GEMMs")
+    ap.add_argument("--fused", type=int, default=None, choices=[0, 1],
+                    help="1 = optimiser applied inside the weight-gradient GEMMs (default for workload 2, where it is "
+                         "the faster of the two as measured), 0 = separate streaming optimiser pass (default otherwise)")
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5],
                     help="2 = wide bf16 MLP classifiers (default, the headline workload), 3 = MLP GAN pairs, "
                          "4 = decoder-only transformers, 5 = actor-critic")
@@ -99,6 +99,8 @@ def main():
               % args.gpus, file=sys.stderr)
         sys.exit(2)
 
+    if args.fused is None:
+        args.fused = 1 if args.workload == 2 else 0
     if args.steps is None:
         args.steps = 30 if args.workload == 4 else 400
     if args.warmup is None:
@@ -202,7 +204,7 @@ def main():
         else:
             ach, peak, unit = work / avg_s / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
         roofline = {"kernel": args.kernel, "bound": bound, "achieved": ach, "peak": peak, "unit": unit,
-                    "frac": ach / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.kernel)), "avg_launch_us": avg_s * 1e6, "launches": k_n,
+                    "frac": ach / peak, "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.kernel + ("_fused" if args.fused and args.kernel == "gemm_wgrad" else ""))), "avg_launch_us": avg_s * 1e6, "launches": k_n,
                     "work_per_launch": work}
 
     out = {

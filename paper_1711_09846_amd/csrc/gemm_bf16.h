@@ -225,6 +225,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+  // A functor that reads what it updates (the optimiser) takes runs of 4 columns, consecutive lanes side
+  // by side (whole 256-byte row segments per access, which streaming loads need: nothing keeps the other
+  // half of a line).  The runs of the first 32-row strip are requested right after the K loop, each later
+  // strip's while the one before it is applied.
+  constexpr int WCOLS = BN / WN, RUNS4 = WCOLS / 4, NQ4 = 32 * RUNS4 / 64;
+  epi.begin(member);
+
   // One K loop per kind of tile: tiles wholly inside the operands (the common case) use straight
   // 16-byte loads, the others the guarded ones; keeping the two apart keeps the guards' branches out of
   // the common loop.
@@ -296,13 +303,23 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
   // 32x32 blocks at a time, through a private LDS region (16-byte writes, no conflicts at a pitch of
   // 4 mod 64 floats) and reads them back as runs of 8 consecutive columns for the functor.  LDS
   // operations of one wavefront execute in order, so no workgroup barrier is needed between strips.
-  constexpr int WCOLS = BN / WN, CPITCH = WCOLS + 4, RUNS = WCOLS / 8;
+  constexpr int CPITCH = WCOLS + 4, RUNS = WCOLS / 8;
   static_assert(WM * WN * 32 * CPITCH * 4 <= SLAB * 2, "C strips must fit the slab LDS");
   float* const Cw = reinterpret_cast<float*>(smem) + wave * 32 * CPITCH;
-  epi.begin(member);
+  typename Epilogue::Fetched pre[NQ4];
+  if constexpr (Epilogue::PREFETCH) {
+#pragma unroll
+    for (int q = 0; q < NQ4; ++q) {
+      const int run = q * 64 + lane;
+      const int m = m0 + wm * (BM / WM) + run / RUNS4, n = n0 + wn * WCOLS + (run % RUNS4) * 4;
+      if (m < g.M && n < g.N) pre[q] = epi.fetch(m, n, g.N - n < 4 ? g.N - n : 4);
+    }
+  }
   __syncthreads();  // every wavefront is done with the slabs
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
+    // a functor that reads what it updates asks for all of a strip's runs first, so that their
+    // latencies overlap each other and the staging below
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -312,16 +329,32 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if constexpr (Epilogue::PREFETCH) {
 #pragma unroll
-    for (int q = 0; q < 32 * RUNS / 64; ++q) {
-      const int run = q * 64 + lane;
-      const int row = run / RUNS, col = (run % RUNS) * 8;
-      const int m = m0 + wm * (BM / WM) + i * 32 + row, n = n0 + wn * WCOLS + col;
-      const float4 lo = *reinterpret_cast<const float4*>(Cw + row * CPITCH + col);
-      const float4 hi = *reinterpret_cast<const float4*>(Cw + row * CPITCH + col + 4);
-      if (m < g.M && n < g.N) {
-        const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-        epi.apply8(member, m, n, v, g.N - n < 8 ? g.N - n : 8);
+      for (int q = 0; q < NQ4; ++q) {
+        const int run = q * 64 + lane;
+        const int row = run / RUNS4, col = (run % RUNS4) * 4;
+        const int m = m0 + wm * (BM / WM) + i * 32 + row, n = n0 + wn * WCOLS + col;
+        const float4 x = *reinterpret_cast<const float4*>(Cw + row * CPITCH + col);
+        if (m < g.M && n < g.N) {
+          const float v[4] = {x.x, x.y, x.z, x.w};
+          epi.apply4_fetched(pre[q], m, n, v, g.N - n < 4 ? g.N - n : 4);
+        }
+        // the registers of this run are free again: the same run of the next strip goes into them
+        if (i + 1 < TM && m + 32 < g.M && n < g.N) pre[q] = epi.fetch(m + 32, n, g.N - n < 4 ? g.N - n : 4);
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < 32 * RUNS / 64; ++q) {
+        const int run = q * 64 + lane;
+        const int row = run / RUNS, col = (run % RUNS) * 8;
+        const int m = m0 + wm * (BM / WM) + i * 32 + row, n = n0 + wn * WCOLS + col;
+        const float4 lo = *reinterpret_cast<const float4*>(Cw + row * CPITCH + col);
+        const float4 hi = *reinterpret_cast<const float4*>(Cw + row * CPITCH + col + 4);
+        if (m < g.M && n < g.N) {
+          const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+          epi.apply8(member, m, n, v, g.N - n < 8 ? g.N - n : 8);
+        }
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -353,7 +386,9 @@ __device__ __forceinline__ void store_bf16_run(bf16_t* dst, const float* v, int 
   if (count == 8 && aligned16(dst)) {
     *reinterpret_cast<uint4*>(dst) = pack_bf16x8(v);
   } else {
-    for (int e = 0; e < count; ++e) dst[e] = f2bf(v[e]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (e < count) dst[e] = f2bf(v[e]);
   }
 }
 
@@ -361,6 +396,8 @@ __device__ __forceinline__ void store_bf16_run(bf16_t* dst, const float* v, int 
 // left with m * pitch + n.
 struct EpiStoreF32 {
   static constexpr bool HAS_FINISH = false;
+  static constexpr bool PREFETCH = false;
+  struct Fetched {};
   float* C;
   int64_t ldc, sc;
   __device__ __forceinline__ void begin(int member) { C += (int64_t)member * sc; }
@@ -377,6 +414,8 @@ struct EpiStoreF32 {
 
 struct EpiStoreBF16 {
   static constexpr bool HAS_FINISH = false;
+  static constexpr bool PREFETCH = false;
+  struct Fetched {};
   bf16_t* C;
   int64_t ldc, sc;
   int inner = 1;       // two-level batch index as in GemmArgs
@@ -390,6 +429,8 @@ struct EpiStoreBF16 {
 // Output layer over a large vocabulary: logits = acc + b[n], kept in float.
 struct EpiBiasF32 {
   static constexpr bool HAS_FINISH = false;
+  static constexpr bool PREFETCH = false;
+  struct Fetched {};
   const float* bias;
   int64_t sbias;
   float* C;
@@ -410,6 +451,8 @@ struct EpiBiasF32 {
 // Forward layer: z = acc + b[n]; stores z (for the backward pass, may be null) and act(z), both bf16.
 struct EpiBiasAct {
   static constexpr bool HAS_FINISH = false;
+  static constexpr bool PREFETCH = false;
+  struct Fetched {};
   const float* bias;  // + member * sbias + n
   int64_t sbias;
   bf16_t* Z;
@@ -438,6 +481,8 @@ struct EpiBiasAct {
 // Input gradient: dz_prev = acc * act'(z_prev), bf16.
 struct EpiDgradAct {
   static constexpr bool HAS_FINISH = false;
+  static constexpr bool PREFETCH = false;
+  struct Fetched {};
   const bf16_t* Zprev;
   bf16_t* dZ;
   int64_t ld, so;
@@ -457,57 +502,60 @@ struct EpiDgradAct {
   }
 };
 
-// Weight gradient with the optimiser applied in place: v = dW[m][n .. n+7] never goes to memory;
+// Weight gradient with the optimiser applied in place: v = dW[m][n .. n+3] never goes to memory;
 // the run of theta, its optimiser state and the bf16 shadow is read, updated and written back
 // (16-byte streaming accesses).  Saves writing and re-reading the gradient (8 of 34 bytes per
 // parameter and step).  The layer's input-gradient GEMM must already have read the bf16 shadow.
 template <int OPT>
 struct EpiOptimizer {
   static constexpr bool HAS_FINISH = false;
+  static constexpr bool PREFETCH = true;
+  struct Fetched { float w[4], s0[4], s1[4]; };  // one run of theta and its state, read ahead of use
   float* W32; float* S0; float* S1; bf16_t* W16;
   int64_t stride, off, ldc;   // member stride, offset of the matrix in the member's vector, row pitch
   OptHyper hy;
   OptScalars sc;
   __device__ __forceinline__ void begin(int member) { sc = opt_scalars<OPT>(hy, member); off += (int64_t)member * stride; }
-  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count) {
+  __device__ __forceinline__ Fetched fetch(int m, int n, int count) const {
+    Fetched f;
     const int64_t o = off + (int64_t)m * ldc + n;
-    float w[8], s0[8], s1[8];
-    const bool vec = count == 8 && (o & 3) == 0;
-    if (vec) {
+    if (count == 4 && (o & 3) == 0) {
+      const float4 a = stream_load(W32 + o), b = stream_load(S0 + o);
+      f.w[0] = a.x; f.w[1] = a.y; f.w[2] = a.z; f.w[3] = a.w;
+      f.s0[0] = b.x; f.s0[1] = b.y; f.s0[2] = b.z; f.s0[3] = b.w;
+      if (OPT == OPT_ADAM) {
+        const float4 c = stream_load(S1 + o);
+        f.s1[0] = c.x; f.s1[1] = c.y; f.s1[2] = c.z; f.s1[3] = c.w;
+      }
+    } else {
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const float4 a = stream_load(W32 + o + 4 * h), b = stream_load(S0 + o + 4 * h);
-        w[4 * h] = a.x; w[4 * h + 1] = a.y; w[4 * h + 2] = a.z; w[4 * h + 3] = a.w;
-        s0[4 * h] = b.x; s0[4 * h + 1] = b.y; s0[4 * h + 2] = b.z; s0[4 * h + 3] = b.w;
-        if (OPT == OPT_ADAM) {
-          const float4 c = stream_load(S1 + o + 4 * h);
-          s1[4 * h] = c.x; s1[4 * h + 1] = c.y; s1[4 * h + 2] = c.z; s1[4 * h + 3] = c.w;
+      for (int e = 0; e < 4; ++e) {
+        f.w[e] = e < count ? W32[o + e] : 0.f;
+        f.s0[e] = e < count ? S0[o + e] : 0.f;
+        f.s1[e] = (OPT == OPT_ADAM && e < count) ? S1[o + e] : 0.f;
+      }
+    }
+    return f;
+  }
+  __device__ __forceinline__ void apply4_fetched(Fetched& f, int m, int n, const float* v, int count) const {
+    const int64_t o = off + (int64_t)m * ldc + n;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) opt_update<OPT>(f.w[e], e < count ? v[e] : 0.f, f.s0[e], f.s1[e], sc, hy);
+    if (count == 4 && (o & 3) == 0) {
+      stream_store(make_float4(f.w[0], f.w[1], f.w[2], f.w[3]), W32 + o);
+      stream_store(make_float4(f.s0[0], f.s0[1], f.s0[2], f.s0[3]), S0 + o);
+      if (OPT == OPT_ADAM) stream_store(make_float4(f.s1[0], f.s1[1], f.s1[2], f.s1[3]), S1 + o);
+      if (W16) *reinterpret_cast<uint2*>(W16 + o) = make_uint2(f2bf_pair(f.w[0], f.w[1]), f2bf_pair(f.w[2], f.w[3]));
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (e < count) {
+          W32[o + e] = f.w[e];
+          S0[o + e] = f.s0[e];
+          if (OPT == OPT_ADAM) S1[o + e] = f.s1[e];
+          if (W16) W16[o + e] = f2bf(f.w[e]);
         }
-      }
-    } else {
-      for (int e = 0; e < 8; ++e) {
-        w[e] = e < count ? W32[o + e] : 0.f;
-        s0[e] = e < count ? S0[o + e] : 0.f;
-        s1[e] = (OPT == OPT_ADAM && e < count) ? S1[o + e] : 0.f;
-      }
     }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) opt_update<OPT>(w[e], e < count ? v[e] : 0.f, s0[e], s1[e], sc, hy);
-    if (vec) {
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        stream_store(make_float4(w[4 * h], w[4 * h + 1], w[4 * h + 2], w[4 * h + 3]), W32 + o + 4 * h);
-        stream_store(make_float4(s0[4 * h], s0[4 * h + 1], s0[4 * h + 2], s0[4 * h + 3]), S0 + o + 4 * h);
-        if (OPT == OPT_ADAM) stream_store(make_float4(s1[4 * h], s1[4 * h + 1], s1[4 * h + 2], s1[4 * h + 3]), S1 + o + 4 * h);
-      }
-    } else {
-      for (int e = 0; e < count; ++e) {
-        W32[o + e] = w[e];
-        S0[o + e] = s0[e];
-        if (OPT == OPT_ADAM) S1[o + e] = s1[e];
-      }
-    }
-    if (W16) store_bf16_run(W16 + o, w, count);
   }
 };
 
@@ -568,6 +616,8 @@ hipError_t launch_gemm_tile(const GemmArgs& g0, bool a_m_contig, bool b_k_contig
 // order, and the tile's sum goes to partial[member][tile]; a later pass adds the tiles.
 struct EpiRbfSum {
   static constexpr bool HAS_FINISH = true;
+  static constexpr bool PREFETCH = false;
+  struct Fetched {};
   __device__ __forceinline__ void begin(int member) { na += (int64_t)member * sna; nb += (int64_t)member * snb; }
   const float* na;  // squared norms of the A rows, + member * sna
   int64_t sna;
