@@ -232,6 +232,23 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
   constexpr int WCOLS = BN / WN, RUNS4 = WCOLS / 4, NQ4 = 32 * RUNS4 / 64;
   epi.begin(member);
 
+  // (half of the first strip goes out ahead of the K loop so that memory is never left idle while the
+  // workgroups of a compute unit are all busy with their operands; all of it would cost an occupancy step)
+  typename Epilogue::Fetched pre[NQ4];
+  constexpr int EARLY_RUNS = NQ4 / 2;
+  auto fetch_first_strip = [&](int q0, int q1) {
+    if constexpr (Epilogue::PREFETCH) {
+#pragma unroll
+      for (int q = 0; q < NQ4; ++q) {
+        if (q < q0 || q >= q1) continue;
+        const int run = q * 64 + lane;
+        const int m = m0 + wm * (BM / WM) + run / RUNS4, n = n0 + wn * WCOLS + (run % RUNS4) * 4;
+        if (m < g.M && n < g.N) pre[q] = epi.fetch(m, n, g.N - n < 4 ? g.N - n : 4);
+      }
+    }
+  };
+  fetch_first_strip(0, EARLY_RUNS);
+
   // One K loop per kind of tile: tiles wholly inside the operands (the common case) use straight
   // 16-byte loads, the others the guarded ones; keeping the two apart keeps the guards' branches out of
   // the common loop.
@@ -306,15 +323,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
   constexpr int CPITCH = WCOLS + 4, RUNS = WCOLS / 8;
   static_assert(WM * WN * 32 * CPITCH * 4 <= SLAB * 2, "C strips must fit the slab LDS");
   float* const Cw = reinterpret_cast<float*>(smem) + wave * 32 * CPITCH;
-  typename Epilogue::Fetched pre[NQ4];
-  if constexpr (Epilogue::PREFETCH) {
-#pragma unroll
-    for (int q = 0; q < NQ4; ++q) {
-      const int run = q * 64 + lane;
-      const int m = m0 + wm * (BM / WM) + run / RUNS4, n = n0 + wn * WCOLS + (run % RUNS4) * 4;
-      if (m < g.M && n < g.N) pre[q] = epi.fetch(m, n, g.N - n < 4 ? g.N - n : 4);
-    }
-  }
+  fetch_first_strip(EARLY_RUNS, NQ4);
   __syncthreads();  // every wavefront is done with the slabs
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
