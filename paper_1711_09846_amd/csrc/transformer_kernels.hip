@@ -485,34 +485,65 @@ hipError_t softmax_bwd(const bf16_t* pq, bf16_t* dpd, int P, int64_t rows, int S
 }
 
 // ---- dropout / residual ----------------------------------------------------------------------
-// out = x * keep (+ res when res != null); four elements per thread (one Philox call).
-__global__ __launch_bounds__(256) void dropout_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ res,
-                                                      int64_t per_member, DropArgs d, int site, bf16_t* __restrict__ out) {
-  const int i = blockIdx.y;
-  const int64_t blk = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (blk * 4 >= per_member) return;
-  const DropRate dr = drop_rate(d.H, d.n_hyper, d.col, i, d.active);
-  float f[4];
-  drop_factors4(d, dr, i, site, (uint32_t)blk, f);
-  const int64_t o = (int64_t)i * per_member + blk * 4;
-  const uint2 xv = *reinterpret_cast<const uint2*>(x + o);
+// out = x * keep (+ res when res != null).  A thread takes DROP_GROUPS consecutive groups of four
+// elements (one Philox call each): 32-byte runs per thread and a quarter of the wavefronts that one
+// group per thread would launch (at one group the launch rate of wavefronts, not memory, set the time).
+constexpr int DROP_GROUPS = 4;
+__device__ __forceinline__ void dropout_group(uint2 xv, bool has_res, uint2 rv, const float* f, uint2* out) {
   // bf16 x float products are exact in double
   double v[4] = {(double)__uint_as_float(xv.x << 16) * (double)f[0], (double)__uint_as_float(xv.x & 0xffff0000u) * (double)f[1],
                  (double)__uint_as_float(xv.y << 16) * (double)f[2], (double)__uint_as_float(xv.y & 0xffff0000u) * (double)f[3]};
-  if (res) {
-    const uint2 rv = *reinterpret_cast<const uint2*>(res + o);
+  if (has_res) {
     v[0] = (double)__uint_as_float(rv.x << 16) + v[0]; v[1] = (double)__uint_as_float(rv.x & 0xffff0000u) + v[1];
     v[2] = (double)__uint_as_float(rv.y << 16) + v[2]; v[3] = (double)__uint_as_float(rv.y & 0xffff0000u) + v[3];
   }
-  uint2 pk;
-  pk.x = d2bf(v[0]) | ((uint32_t)d2bf(v[1]) << 16);
-  pk.y = d2bf(v[2]) | ((uint32_t)d2bf(v[3]) << 16);
-  *reinterpret_cast<uint2*>(out + o) = pk;
+  out->x = d2bf(v[0]) | ((uint32_t)d2bf(v[1]) << 16);
+  out->y = d2bf(v[2]) | ((uint32_t)d2bf(v[3]) << 16);
+}
+__global__ __launch_bounds__(256) void dropout_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ res,
+                                                      int64_t per_member, DropArgs d, int site, bf16_t* __restrict__ out) {
+  const int i = blockIdx.y;
+  const int64_t first = ((int64_t)blockIdx.x * 256 + threadIdx.x) * DROP_GROUPS;   // first group of this thread
+  const int64_t groups = per_member / 4;
+  if (first >= groups) return;
+  const DropRate dr = drop_rate(d.H, d.n_hyper, d.col, i, d.active);
+  const int64_t o = (int64_t)i * per_member + first * 4;
+  if (first + DROP_GROUPS <= groups && ((reinterpret_cast<uintptr_t>(x + o) | reinterpret_cast<uintptr_t>(out + o) |
+                                         (res ? reinterpret_cast<uintptr_t>(res + o) : 0)) & 15) == 0) {
+    uint4 xv[DROP_GROUPS / 2], rv[DROP_GROUPS / 2], ov[DROP_GROUPS / 2];
+#pragma unroll
+    for (int h = 0; h < DROP_GROUPS / 2; ++h) {
+      xv[h] = *reinterpret_cast<const uint4*>(x + o + 8 * h);
+      rv[h] = res ? *reinterpret_cast<const uint4*>(res + o + 8 * h) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int h = 0; h < DROP_GROUPS / 2; ++h) {
+      float f[4];
+      uint2 lo, hi;
+      drop_factors4(d, dr, i, site, (uint32_t)(first + 2 * h), f);
+      dropout_group(make_uint2(xv[h].x, xv[h].y), res != nullptr, make_uint2(rv[h].x, rv[h].y), f, &lo);
+      drop_factors4(d, dr, i, site, (uint32_t)(first + 2 * h + 1), f);
+      dropout_group(make_uint2(xv[h].z, xv[h].w), res != nullptr, make_uint2(rv[h].z, rv[h].w), f, &hi);
+      ov[h] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    }
+#pragma unroll
+    for (int h = 0; h < DROP_GROUPS / 2; ++h) *reinterpret_cast<uint4*>(out + o + 8 * h) = ov[h];
+  } else {
+    for (int g = 0; g < DROP_GROUPS && first + g < groups; ++g) {
+      float f[4];
+      uint2 pk;
+      drop_factors4(d, dr, i, site, (uint32_t)(first + g), f);
+      const uint2 rv = res ? *reinterpret_cast<const uint2*>(res + o + 4 * g) : make_uint2(0, 0);
+      dropout_group(*reinterpret_cast<const uint2*>(x + o + 4 * g), res != nullptr, rv, f, &pk);
+      *reinterpret_cast<uint2*>(out + o + 4 * g) = pk;
+    }
+  }
 }
 hipError_t dropout_apply(const bf16_t* x, const bf16_t* res, int P, int64_t per_member, const DropArgs& d, int site, bf16_t* out,
                          hipStream_t s) {
   if (per_member % 4) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(dropout_kernel, dim3((unsigned)((per_member / 4 + 255) / 256), P), dim3(256), 0, s, x, res, per_member, d, site, out);
+  const int64_t threads = (per_member / 4 + DROP_GROUPS - 1) / DROP_GROUPS;
+  hipLaunchKernelGGL(dropout_kernel, dim3((unsigned)((threads + 255) / 256), P), dim3(256), 0, s, x, res, per_member, d, site, out);
   return hipGetLastError();
 }
 
