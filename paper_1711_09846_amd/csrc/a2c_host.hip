@@ -51,67 +51,94 @@ __global__ __launch_bounds__(64) void a2c_fetch_aux_kernel(const int32_t* __rest
 }
 
 // Loss and its gradient with respect to the head outputs, one workgroup per member.
-// Phase 1 (one thread per trajectory) walks each trajectory backwards for the bootstrapped returns
-//   R_T = V(s_T), R_t = r_t + gamma R_{t+1}      into LDS.
+// Phase 1: the rewards of the member's trajectories are brought into LDS by all threads, then one
+//   thread per trajectory walks it backwards in place for the bootstrapped returns
+//   R_T = V(s_T), R_t = r_t + gamma R_{t+1}.
 // Phase 2 (one thread per transition) evaluates, with A_t = R_t - V_t and R_t constants,
 //   loss_t = -A_t log pi(a_t) + value_cost (R_t - V_t)^2 - entropy_cost H_t
 //   dlogit_c = ( -A_t (1[c = a_t] - pi_c) + entropy_cost pi_c (log pi_c + H_t) ) / n
 //   dV_t = 2 value_cost (V_t - R_t) / n,   n = B T;  the bootstrap rows get zeros.
-// out: head outputs float [P][B][T+1][32] (n_act logits, then the value).  The per-thread losses
-// are combined in a fixed order (lane butterfly, then the four wavefronts).
-__global__ __launch_bounds__(256) void a2c_loss_kernel(const float* __restrict__ out, const int32_t* __restrict__ act,
-                                                       const float* __restrict__ rew, const float* __restrict__ H,
-                                                       int n_hyper, int col_ent, int B, int T, int n_act, float gamma,
-                                                       float value_cost, bf16_t* __restrict__ dout, float* __restrict__ loss) {
+// out: head outputs float [P][B][T+1][32] (n_act logits, then the value).  The exponentials of a row
+// are evaluated once and kept in registers.  The per-thread losses are combined in a fixed order
+// (lane butterfly, then the wavefronts in order).
+__global__ __launch_bounds__(1024) void a2c_loss_kernel(const float* __restrict__ out, const int32_t* __restrict__ act,
+                                                        const float* __restrict__ rew, const float* __restrict__ H,
+                                                        int n_hyper, int col_ent, int B, int T, int n_act, float gamma,
+                                                        float value_cost, bf16_t* __restrict__ dout, float* __restrict__ loss) {
   extern __shared__ float Rl[];  // [B][T]
-  __shared__ float wsum[4];
+  __shared__ float wsum[16];
   const int i = blockIdx.x;
+  const int threads = blockDim.x;
   const float ent_cost = H[i * n_hyper + col_ent];
   const float inv_n = 1.f / (float)(B * T);
-  for (int r = threadIdx.x; r < B; r += 256) {
-    const float* __restrict__ o = out + ((int64_t)i * B + r) * (T + 1) * 32;
-    float R = o[T * 32 + n_act];
+  for (int e = threadIdx.x; e < B * T; e += threads) Rl[e] = rew[(int64_t)i * B * T + e];
+  __syncthreads();
+  for (int r = threadIdx.x; r < B; r += threads) {
+    float R = out[(((int64_t)i * B + r) * (T + 1) + T) * 32 + n_act];
     for (int t = T - 1; t >= 0; --t) {
-      R = rew[((int64_t)i * B + r) * T + t] + gamma * R;
+      R = Rl[r * T + t] + gamma * R;
       Rl[r * T + t] = R;
     }
   }
   __syncthreads();
   float lacc = 0.f;
-  for (int idx = threadIdx.x; idx < B * (T + 1); idx += 256) {
+  for (int idx = threadIdx.x; idx < B * (T + 1); idx += threads) {
     const int r = idx / (T + 1), t = idx - r * (T + 1);
-    const float* lg = out + ((int64_t)i * B * (T + 1) + idx) * 32;
-    bf16_t* __restrict__ d = dout + ((int64_t)i * B * (T + 1) + idx) * 32;
+    const float4* __restrict__ lg4 = reinterpret_cast<const float4*>(out + ((int64_t)i * B * (T + 1) + idx) * 32);
+    uint4* __restrict__ d4 = reinterpret_cast<uint4*>(dout + ((int64_t)i * B * (T + 1) + idx) * 32);
     if (t == T) {
-      for (int c = 0; c < 32; ++c) d[c] = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) d4[q] = make_uint4(0, 0, 0, 0);
       continue;
     }
-    const float R = Rl[r * T + t];
-    const float v = lg[n_act];
-    const float adv = R - v;
-    float mx = lg[0];
-    for (int c = 1; c < n_act; ++c) mx = fmaxf(mx, lg[c]);
-    float se = 0.f;
-    for (int c = 0; c < n_act; ++c) se += expf(lg[c] - mx);
-    const float lse = mx + logf(se);
-    float ent = 0.f;
-    for (int c = 0; c < n_act; ++c) {
-      const float lp = lg[c] - lse;
-      ent -= expf(lp) * lp;
+    float lg[32];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const float4 x = lg4[q];
+      lg[4 * q] = x.x; lg[4 * q + 1] = x.y; lg[4 * q + 2] = x.z; lg[4 * q + 3] = x.w;
     }
     const int a = act[((int64_t)i * B + r) * T + t];
-    lacc += -adv * (lg[a] - lse) + value_cost * adv * adv - ent_cost * ent;
-    for (int c = 0; c < n_act; ++c) {
-      const float lp = lg[c] - lse, pi = expf(lp);
-      d[c] = f2bf((-adv * ((c == a ? 1.f : 0.f) - pi) + ent_cost * pi * (lp + ent)) * inv_n);
+    const float R = Rl[r * T + t];
+    float v = 0.f, la = 0.f, mx = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < 32; ++c) {
+      if (c < n_act) mx = fmaxf(mx, lg[c]);
+      if (c == n_act) v = lg[c];
+      if (c == a) la = lg[c];
     }
-    d[n_act] = f2bf(2.f * value_cost * (v - R) * inv_n);
-    for (int c = n_act + 1; c < 32; ++c) d[c] = 0;
+    const float adv = R - v;
+    float ex[32], se = 0.f;
+#pragma unroll
+    for (int c = 0; c < 32; ++c) {
+      ex[c] = c < n_act ? expf(lg[c] - mx) : 0.f;
+      se += ex[c];
+    }
+    const float lse = mx + logf(se), inv_se = 1.f / se;
+    float ent = 0.f;
+#pragma unroll
+    for (int c = 0; c < 32; ++c)
+      if (c < n_act) ent -= ex[c] * inv_se * (lg[c] - lse);
+    lacc += -adv * (la - lse) + value_cost * adv * adv - ent_cost * ent;
+    float dv[32];
+#pragma unroll
+    for (int c = 0; c < 32; ++c) {
+      const float pi = ex[c] * inv_se, lp = lg[c] - lse;
+      dv[c] = c < n_act ? (-adv * ((c == a ? 1.f : 0.f) - pi) + ent_cost * pi * (lp + ent)) * inv_n
+              : c == n_act ? 2.f * value_cost * (v - R) * inv_n : 0.f;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      d4[q] = make_uint4(f2bf_pair(dv[8 * q], dv[8 * q + 1]), f2bf_pair(dv[8 * q + 2], dv[8 * q + 3]),
+                         f2bf_pair(dv[8 * q + 4], dv[8 * q + 5]), f2bf_pair(dv[8 * q + 6], dv[8 * q + 7]));
   }
   lacc = wave_sum(lacc);
   if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = lacc;
   __syncthreads();
-  if (threadIdx.x == 0) loss[i] = (((wsum[0] + wsum[1]) + wsum[2]) + wsum[3]) * inv_n;
+  if (threadIdx.x == 0) {
+    float total = 0.f;
+    for (int w = 0; w < threads / 64; ++w) total += wsum[w];
+    loss[i] = total * inv_n;
+  }
 }
 
 // score = mean of the last min(count, 10) returns (double accumulation), -inf when there are none
@@ -184,7 +211,7 @@ pbt_status a2c_step(pbt_handle* h, const float* obs, const int32_t* actions, con
   if ((st = forward(h, net, L - 1, R, A, Z, nullptr, 0, s)) != PBT_OK) return st;
   PBT_LAUNCH(h, PBT_K_HEAD, s, head_fwd_loss(A[L - 1], (int64_t)R * Kh, W16 + p.lay.w_off[L - 1], S, W32 + p.lay.b_off[L - 1], S, nullptr,
                                              0, P, R, Kh, C, 0.f, -2, nullptr, out, 0, s));
-  hipLaunchKernelGGL(a2c_loss_kernel, dim3(P), dim3(256), (size_t)B * T * sizeof(float), s, out, act, rew, h->st<float>(p.o_hyper), c.n_hyper, a.col_ent, B, T,
+  hipLaunchKernelGGL(a2c_loss_kernel, dim3(P), dim3(B * (T + 1) > 512 ? 1024 : B * (T + 1) > 256 ? 512 : 256), (size_t)B * T * sizeof(float), s, out, act, rew, h->st<float>(p.o_hyper), c.n_hyper, a.col_ent, B, T,
                      C - 1, c.gamma, c.value_cost, dout, h->st<float>(p.o_loss));
   PBT_HIP(h, hipGetLastError());
   {
