@@ -92,21 +92,26 @@ struct TileLoader {
     }
   }
 
-  // The same tile when it lies wholly inside the operand: straight 16-byte loads, no guards.
-  __device__ __forceinline__ void load_interior(const bf16_t* __restrict__ base, int64_t ld, int row0, int k0) {
+  // The same tile when its K range lies wholly inside the operand: straight 16-byte loads, no guards.
+  // Rows past the operand's last row (a ragged last tile in M or N) read the last row (K-contiguous
+  // operand) or the last whole group of eight rows (the other layout; the launcher checks that the row
+  // count is a multiple of 8 then): always in bounds, and the epilogue drops those rows' results.
+  __device__ __forceinline__ void load_interior(const bf16_t* __restrict__ base, int64_t ld, int row0, int k0, int nrows) {
     const int t = threadIdx.x;
     if constexpr (KCONTIG) {
 #pragma unroll
       for (int j = 0; j < PER_THREAD; ++j) {
         const int c = t + THREADS * j;
-        r[j] = *reinterpret_cast<const uint4*>(base + (int64_t)(row0 + c / (GEMM_BK / 8)) * ld + k0 + (c % (GEMM_BK / 8)) * 8);
+        const int row = min(row0 + c / (GEMM_BK / 8), nrows - 1);
+        r[j] = *reinterpret_cast<const uint4*>(base + (int64_t)row * ld + k0 + (c % (GEMM_BK / 8)) * 8);
       }
     } else {
       const int rb = t % (ROWS / 8);
       const int kb = t / (ROWS / 8);
+      const int row = min(row0 + rb * 8, nrows - 8);
 #pragma unroll
       for (int j = 0; j < KB; ++j)
-        r[j] = *reinterpret_cast<const uint4*>(base + (int64_t)(k0 + kb * KB + j) * ld + row0 + rb * 8);
+        r[j] = *reinterpret_cast<const uint4*>(base + (int64_t)(k0 + kb * KB + j) * ld + row);
     }
   }
 
@@ -249,15 +254,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
   };
   fetch_first_strip(0, EARLY_RUNS);
 
-  // One K loop per kind of tile: tiles wholly inside the operands (the common case) use straight
-  // 16-byte loads, the others the guarded ones; keeping the two apart keeps the guards' branches out of
-  // the common loop.
+  // One K loop per kind of launch: straight 16-byte loads when K is a multiple of the slab depth (ragged
+  // last tiles in M or N read clamped rows), the guarded loads otherwise; keeping the two apart keeps the
+  // guards' branches out of the common loop.
   auto k_loop = [&](auto interior_tag) {
     constexpr bool INTERIOR = decltype(interior_tag)::value;
     auto fetch_slab = [&](int k) {
       if constexpr (INTERIOR) {
-        la.load_interior(A, g.lda, m0, k);
-        lb.load_interior(B, g.ldb, n0, k);
+        la.load_interior(A, g.lda, m0, k, g.M);
+        lb.load_interior(B, g.ldb, n0, k, g.N);
       } else {
         la.load(A, g.lda, m0, k, g.M, g.K);
         lb.load(B, g.ldb, n0, k, g.N, g.K);
@@ -310,7 +315,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
       }
     }
   };
-  if (m0 + BM <= g.M && n0 + BN <= g.N && g.K % GEMM_BK == 0) k_loop(std::true_type{});
+  // (uniform over the launch: a ragged K needs the zero fill of the guarded loads; ragged M or N only
+  // needs in-bounds addresses, unless the operand is stored eight rows per 16 bytes and does not end on one)
+  const bool a_rows_ok = A_MCONTIG ? (g.M % 8 == 0 && g.M >= 8) : true;
+  const bool b_rows_ok = B_KCONTIG ? true : (g.N % 8 == 0 && g.N >= 8);
+  if (g.K % GEMM_BK == 0 && a_rows_ok && b_rows_ok) k_loop(std::true_type{});
   else k_loop(std::false_type{});
 
   // Epilogue.  The MFMAs above take the B fragment as their first operand, so an accumulator block
