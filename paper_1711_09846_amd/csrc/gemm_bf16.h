@@ -596,7 +596,8 @@ inline TileShape tile_shape(GemmTile t) {
 inline int64_t tile_count(int M, int N, int batch, int bm, int bn) { return (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn) * batch; }
 inline GemmTile choose_tile(int M, int N, int K, int batch) {
   constexpr int CUS = 256;
-  if (K >= 1024 && M > 128 && N > 128 && tile_count(M, N, batch, 256, 256) >= CUS) return TILE_256x256;
+  // (three quarters of the compute units busy with 256x256 tiles still beat all of them on smaller ones)
+  if (K >= 1024 && M > 128 && N > 128 && tile_count(M, N, batch, 256, 256) >= CUS * 3 / 4) return TILE_256x256;
   if ((tile_count(M, N, batch, 128, 128) < 4 * CUS && N > 64) || (N <= 64 && N > 32)) return TILE_128x64;
   return TILE_128x128;
 }
