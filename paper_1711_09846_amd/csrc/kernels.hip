@@ -120,7 +120,25 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const bf16_t* __restrict
   if (n0 < N) {
     const bf16_t* __restrict__ p = dZ + (int64_t)i * rows * ld + n0;
     const bool full = n0 + 8 <= N;
-    for (int r = slab * rows_per_slab + rg; r < r_end; r += 32) {
+    int r = slab * rows_per_slab + rg;
+    if (full) {
+      // four rows' loads go out together (the sums still run in row order)
+      for (; r + 96 < r_end; r += 128) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint4*>(p + (int64_t)(r + 32 * u) * ld);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            acc[2 * q] += __uint_as_float(w[q] << 16);
+            acc[2 * q + 1] += __uint_as_float(w[q] & 0xffff0000u);
+          }
+        }
+      }
+    }
+    for (; r < r_end; r += 32) {
       if (full) {
         const uint4 v = *reinterpret_cast<const uint4*>(p + (int64_t)r * ld);
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
