@@ -215,9 +215,10 @@ pbt_status a2c_step(pbt_handle* h, const float* obs, const int32_t* actions, con
                      C - 1, c.gamma, c.value_cost, dout, h->st<float>(p.o_loss));
   PBT_HIP(h, hipGetLastError());
   {
+    // (the bias gradient, column sums of dout, is a by-product of the same launch)
     GemmOperands wg{A[L - 1], Kh, (int64_t)R * Kh, true, dout, 32, (int64_t)R * 32, false, Kh, C, R, P};
+    wg.colsum = G + p.lay.b_off[L - 1]; wg.colsum_stride = S;
     PBT_LAUNCH(h, PBT_K_HEAD, s, gemm_store_f32(wg, G + p.lay.w_off[L - 1], C, S, s));
-    PBT_LAUNCH(h, PBT_K_HEAD, s, bias_grad(dout, P, R, C, 32, G + p.lay.b_off[L - 1], S, s));
   }
   PBT_LAUNCH(h, PBT_K_HEAD, s, head_dgrad(dout, W16 + p.lay.w_off[L - 1], S, Z[L - 2], dZ[L - 2], P, R, Kh, C, c.act, s));
   OptArgs oa{h->st<float>(p.o_w32), h->st<float>(p.o_opt0), nullptr, h->st<bf16_t>(p.o_w16), G, 0, S, h->st<float>(p.o_hyper),

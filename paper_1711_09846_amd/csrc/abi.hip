@@ -313,8 +313,8 @@ pbt_status step_bf16(pbt_handle* h, const float* train_x, const int32_t* train_y
     // dW_head[Kh][C] = X^T dlogits (contraction over the B rows), db_head = column sums
     GemmOperands wg{h->sc<bf16_t>(p.o_act[L - 1]), Kh, (int64_t)B * Kh, true, dlogits, 32, (int64_t)B * 32, false,
                     Kh, C, B, P};
+    wg.colsum = G + p.lay.b_off[L - 1]; wg.colsum_stride = S;   // db_head, a by-product of the same launch
     PBT_LAUNCH(h, PBT_K_HEAD, s, gemm_store_f32(wg, G + p.lay.w_off[L - 1], C, S, s));
-    PBT_LAUNCH(h, PBT_K_HEAD, s, bias_grad(dlogits, P, B, C, 32, G + p.lay.b_off[L - 1], S, s));
   }
   if (L >= 2)
     PBT_LAUNCH(h, PBT_K_HEAD, s, head_dgrad(dlogits, W16 + p.lay.w_off[L - 1], S, h->sc<bf16_t>(p.o_z[L - 2]),
@@ -332,10 +332,10 @@ pbt_status step_bf16(pbt_handle* h, const float* train_x, const int32_t* train_y
       PBT_LAUNCH(h, PBT_K_GEMM_DGRAD, s, gemm_dgrad_act(dg, h->sc<bf16_t>(p.o_z[l - 1]), h->sc<bf16_t>(p.o_dz[l - 1]), K,
                                                         (int64_t)B * K, c.act, s));
     }
-    PBT_LAUNCH(h, PBT_K_BIAS_GRAD, s, bias_grad(h->sc<bf16_t>(p.o_dz[l]), P, B, N, N, G + p.lay.b_off[l], S, s));
-    // dW_l[K][N] = X_l^T dZ_l (contraction over the B rows)
+    // dW_l[K][N] = X_l^T dZ_l (contraction over the B rows); db_l = column sums of dZ_l from the same launch
     GemmOperands wg{h->sc<bf16_t>(p.o_act[l]), K, (int64_t)B * K, true, h->sc<bf16_t>(p.o_dz[l]), N, (int64_t)B * N, false,
                     K, N, B, P};
+    wg.colsum = G + p.lay.b_off[l]; wg.colsum_stride = S;
     if (fused)
       PBT_LAUNCH(h, PBT_K_GEMM_WGRAD, s, gemm_wgrad_optimizer(wg, oa, p.lay.w_off[l], N, s));
     else

@@ -59,8 +59,9 @@ inline pbt_status backward(pbt_handle* h, const Net& net, int n_dense, int rows,
       PBT_LAUNCH(h, PBT_K_GEMM_DGRAD, s, gemm_dgrad_act(dg, zprev, dzprev, K, (int64_t)rows * K, l > 0 ? net.hidden_act : in_act, s));
     }
     if (want_wgrad) {
+      // (the bias gradient, column sums of dZ_l, is a by-product of the same launch)
       GemmOperands wg{A[l], K, (int64_t)rows * K, true, dZ[l], N, (int64_t)rows * N, false, K, N, rows, c.P};
-      PBT_LAUNCH(h, PBT_K_BIAS_GRAD, s, bias_grad(dZ[l], c.P, rows, N, N, G + p.lay.b_off[net.first + l], S, s));
+      wg.colsum = G + p.lay.b_off[net.first + l]; wg.colsum_stride = S;
       if (fused)
         PBT_LAUNCH(h, PBT_K_GEMM_WGRAD, s, gemm_wgrad_optimizer(wg, *fused, p.lay.w_off[net.first + l], N, s));
       else

@@ -123,8 +123,8 @@ pbt_status gan_step(pbt_handle* h, const float* train_x, uint32_t step, hipStrea
   PBT_LAUNCH(h, PBT_K_HEAD, s, row_reduce(rowloss, R, P, R, 1.f / (float)B, loss, 2, s));
   {
     GemmOperands wg{b.dA[Ld - 1], Kh, (int64_t)R * Kh, true, dlogits, 32, (int64_t)R * 32, false, Kh, 1, R, P};
+    wg.colsum = G + p.lay.b_off[head]; wg.colsum_stride = S;   // the bias gradient, a by-product of the same launch
     PBT_LAUNCH(h, PBT_K_HEAD, s, gemm_store_f32(wg, G + p.lay.w_off[head], 1, S, s));
-    PBT_LAUNCH(h, PBT_K_HEAD, s, bias_grad(dlogits, P, R, 1, 32, G + p.lay.b_off[head], S, s));
   }
   PBT_LAUNCH(h, PBT_K_HEAD, s, head_dgrad(dlogits, W16 + p.lay.w_off[head], S, b.dZ[Ld - 2], b.ddZ[Ld - 2], P, R, Kh, 1, dnet.hidden_act, s));
   const bool fused = c.fuse_optimizer != 0;

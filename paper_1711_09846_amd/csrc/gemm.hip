@@ -15,10 +15,10 @@ static hipError_t run(const GemmOperands& o, const E& e, hipStream_t s) {
     g.M = o.M; g.N = o.N; g.K = o.K; g.batch = o.batch;
     g.tiles_m = g.tiles_n = 0;
     g.inner = o.inner < 1 ? 1 : o.inner; g.sa_in = o.sa_in; g.sb_in = o.sb_in;
-    if (nt_lds_applies(g, o.a_m_contig, o.b_k_contig)) return launch_gemm_nt_lds(g, e, s);
+    if (!o.colsum && nt_lds_applies(g, o.a_m_contig, o.b_k_contig)) return launch_gemm_nt_lds(g, e, s);
   }
   return launch_gemm_bf16<E>(o.A, o.lda, o.sa, o.a_m_contig, o.B, o.ldb, o.sb, o.b_k_contig, o.M, o.N, o.K, o.batch, e, s, o.inner,
-                             o.sa_in, o.sb_in);
+                             o.sa_in, o.sb_in, o.colsum, o.colsum_stride);
 }
 
 hipError_t gemm_store_f32(const GemmOperands& o, float* C, int64_t ldc, int64_t sc, hipStream_t s) {

@@ -39,6 +39,11 @@ struct GemmArgs {
   // starts at (b / inner) * s? + (b % inner) * s?_in
   int inner;
   int64_t sa_in, sb_in;
+  // optional by-product: colsum[b * colsum_stride + n] = sum_k B[k][n] (float), written by the first tile
+  // row of every batch element from the B slabs it stages anyway (the bias gradient of a weight-gradient
+  // contraction, whose B operand is dZ); null = not wanted
+  float* colsum = nullptr;
+  int64_t colsum_stride = 0;
 };
 
 // LDS row pitch in elements for a slab width BK: +8 keeps 16-byte alignment and skews the banks
@@ -254,6 +259,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
   };
   fetch_first_strip(0, EARLY_RUNS);
 
+  // (only the weight-gradient functors carry this code: elsewhere its registers would cost an occupancy step)
+  const bool want_colsum = Epilogue::COLSUM && g.colsum != nullptr && tm == 0;
+  float csum = 0.f;
+
   // One K loop per kind of launch: straight 16-byte loads when K is a multiple of the slab depth (ragged
   // last tiles in M or N read clamped rows), the guarded loads otherwise; keeping the two apart keeps the
   // guards' branches out of the common loop.
@@ -285,6 +294,21 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
           for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
       }
     };
+    // column sums of the B slab in LDS (rows of Bs are columns n; the slot permutation only reorders k)
+    auto colsum_slab = [&](const bf16_t* Bs) {
+      if constexpr (Epilogue::COLSUM) if (want_colsum && (int)threadIdx.x < BN) {
+#pragma unroll
+        for (int ks = 0; ks < GEMM_BK; ks += 8) {
+          const uint4 v = *reinterpret_cast<const uint4*>(Bs + lds_offset<GEMM_BK>((int)threadIdx.x, ks));
+          const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            csum += __uint_as_float(w[q] << 16);
+            csum += __uint_as_float(w[q] & 0xffff0000u);
+          }
+        }
+      }
+    };
     if constexpr (DOUBLE_BUF) {
       // slab s+1 goes from registers into the other LDS buffer and slab s+2 leaves for the registers
       // before slab s is multiplied: one barrier per slab, and a load has a whole slab's MFMAs to land
@@ -301,6 +325,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
           if (k0 + 2 * GEMM_BK < g.K) fetch_slab(k0 + 2 * GEMM_BK);
         }
         multiply_slab(smem + buf * SLAB, smem + buf * SLAB + BM * GEMM_PITCH);
+        colsum_slab(smem + buf * SLAB + BM * GEMM_PITCH);
         __syncthreads();
       }
     } else {
@@ -312,6 +337,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
         __syncthreads();
         if (k0 + GEMM_BK < g.K) fetch_slab(k0 + GEMM_BK);
         multiply_slab(smem, smem + BM * GEMM_PITCH);
+        colsum_slab(smem + BM * GEMM_PITCH);
       }
     }
   };
@@ -321,6 +347,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
   const bool b_rows_ok = B_KCONTIG ? true : (g.N % 8 == 0 && g.N >= 8);
   if (g.K % GEMM_BK == 0 && a_rows_ok && b_rows_ok) k_loop(std::true_type{});
   else k_loop(std::false_type{});
+
+  if constexpr (Epilogue::COLSUM) if (want_colsum && (int)threadIdx.x < BN && n0 + (int)threadIdx.x < g.N)
+    g.colsum[(int64_t)member * g.colsum_stride + n0 + threadIdx.x] = csum;
 
   // Epilogue.  The MFMAs above take the B fragment as their first operand, so an accumulator block
   // holds the transposed product: lane -> row m (lane % 32) of C, register e -> column
@@ -415,6 +444,7 @@ __device__ __forceinline__ void store_bf16_run(bf16_t* dst, const float* v, int 
 struct EpiStoreF32 {
   static constexpr bool HAS_FINISH = false;
   static constexpr bool PREFETCH = false;
+  static constexpr bool COLSUM = true;   // weight gradients: the bias gradient can ride along
   struct Fetched {};
   float* C;
   int64_t ldc, sc;
@@ -433,6 +463,7 @@ struct EpiStoreF32 {
 struct EpiStoreBF16 {
   static constexpr bool HAS_FINISH = false;
   static constexpr bool PREFETCH = false;
+  static constexpr bool COLSUM = false;
   struct Fetched {};
   bf16_t* C;
   int64_t ldc, sc;
@@ -448,6 +479,7 @@ struct EpiStoreBF16 {
 struct EpiBiasF32 {
   static constexpr bool HAS_FINISH = false;
   static constexpr bool PREFETCH = false;
+  static constexpr bool COLSUM = false;
   struct Fetched {};
   const float* bias;
   int64_t sbias;
@@ -470,6 +502,7 @@ struct EpiBiasF32 {
 struct EpiBiasAct {
   static constexpr bool HAS_FINISH = false;
   static constexpr bool PREFETCH = false;
+  static constexpr bool COLSUM = false;
   struct Fetched {};
   const float* bias;  // + member * sbias + n
   int64_t sbias;
@@ -500,6 +533,7 @@ struct EpiBiasAct {
 struct EpiDgradAct {
   static constexpr bool HAS_FINISH = false;
   static constexpr bool PREFETCH = false;
+  static constexpr bool COLSUM = false;
   struct Fetched {};
   const bf16_t* Zprev;
   bf16_t* dZ;
@@ -528,6 +562,7 @@ template <int OPT>
 struct EpiOptimizer {
   static constexpr bool HAS_FINISH = false;
   static constexpr bool PREFETCH = true;
+  static constexpr bool COLSUM = true;
   struct Fetched { float w[4], s0[4], s1[4]; };  // one run of theta and its state, read ahead of use
   float* W32; float* S0; float* S1; bf16_t* W16;
   int64_t stride, off, ldc;   // member stride, offset of the matrix in the member's vector, row pitch
@@ -636,6 +671,7 @@ hipError_t launch_gemm_tile(const GemmArgs& g0, bool a_m_contig, bool b_k_contig
 struct EpiRbfSum {
   static constexpr bool HAS_FINISH = true;
   static constexpr bool PREFETCH = false;
+  static constexpr bool COLSUM = false;
   struct Fetched {};
   __device__ __forceinline__ void begin(int member) { na += (int64_t)member * sna; nb += (int64_t)member * snb; }
   const float* na;  // squared norms of the A rows, + member * sna
@@ -668,13 +704,15 @@ struct EpiRbfSum {
 template <class Epilogue>
 hipError_t launch_gemm_bf16(const bf16_t* A, int64_t lda, int64_t sa, bool a_m_contig, const bf16_t* B, int64_t ldb,
                             int64_t sb, bool b_k_contig, int M, int N, int K, int batch, const Epilogue& epi,
-                            hipStream_t stream, int inner = 1, int64_t sa_in = 0, int64_t sb_in = 0) {
+                            hipStream_t stream, int inner = 1, int64_t sa_in = 0, int64_t sb_in = 0, float* colsum = nullptr,
+                            int64_t colsum_stride = 0) {
   GemmArgs g;
   g.A = A; g.lda = lda; g.sa = sa;
   g.B = B; g.ldb = ldb; g.sb = sb;
   g.M = M; g.N = N; g.K = K; g.batch = batch;
   g.tiles_m = g.tiles_n = 0;
   g.inner = inner < 1 ? 1 : inner; g.sa_in = sa_in; g.sb_in = sb_in;
+  g.colsum = colsum; g.colsum_stride = colsum_stride;
   switch (choose_tile(M, N, K, batch)) {
     case TILE_256x256: return launch_gemm_tile<256, 256, 64, 2, 4, true, Epilogue>(g, a_m_contig, b_k_contig, epi, stream);
     case TILE_128x64: return launch_gemm_tile<128, 64, 64, 2, 2, false, Epilogue>(g, a_m_contig, b_k_contig, epi, stream);

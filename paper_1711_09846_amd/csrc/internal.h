@@ -16,6 +16,8 @@ struct GemmOperands {
   int M, N, K, batch;
   int inner = 1;                 // two-level batch index: element b reads A at (b / inner) * sa + (b % inner) * sa_in
   int64_t sa_in = 0, sb_in = 0;
+  float* colsum = nullptr;       // optional by-product: colsum[b * colsum_stride + n] = sum_k B[k][n]
+  int64_t colsum_stride = 0;
 };
 hipError_t gemm_store_f32(const GemmOperands& o, float* C, int64_t ldc, int64_t sc, hipStream_t s);
 hipError_t gemm_store_bf16(const GemmOperands& o, bf16_t* C, int64_t ldc, int64_t sc, hipStream_t s);

@@ -30,6 +30,8 @@ pbt_status dense(const Ctx& x, const bf16_t* in, int K, int N, int64_t w, int64_
 }
 // G[w] = in^T dout, G[b] = column sums of dout
 pbt_status wgrad(const Ctx& x, const bf16_t* in, int K, const bf16_t* dout, int N, int64_t w, int64_t b) {
+  // (with thousands of rows per member the column sums get their own launch: as a by-product of the GEMM
+  // they would be summed by the first tile row alone, which then finishes last)
   GemmOperands o{in, K, (int64_t)x.n * K, true, dout, N, (int64_t)x.n * N, false, K, N, x.n, x.P};
   PBT_LAUNCH(x.h, PBT_K_GEMM_WGRAD, x.s, gemm_store_f32(o, x.G + w, N, x.S_, x.s));
   PBT_LAUNCH(x.h, PBT_K_BIAS_GRAD, x.s, bias_grad(dout, x.P, x.n, N, N, x.G + b, x.S_, x.s, x.sc<float>(x.h->plan.tf.o_biaspart)));
