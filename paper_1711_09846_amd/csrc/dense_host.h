@@ -77,6 +77,9 @@ inline pbt_status backward(pbt_handle* h, const Net& net, int n_dense, int rows,
 // neighbouring ranges into one launch.
 inline pbt_status optimizer_rest(pbt_handle* h, OptArgs oa, int first, int n, int n_fused, int64_t range_end, hipStream_t s) {
   const Plan& p = h->plan;
+  // collect the ranges, then hand them to the kernel OPT_MAX_RANGES at a time
+  int64_t rb[PBT_MAX_DIMS + 1], rc[PBT_MAX_DIMS + 1];
+  int n_ranges = 0;
   int64_t begin = -1, end = -1;
   for (int l = first; l < first + n; ++l) {
     const int64_t next = l + 1 < first + n ? p.lay.w_off[l + 1] : range_end;
@@ -84,12 +87,19 @@ inline pbt_status optimizer_rest(pbt_handle* h, OptArgs oa, int first, int n, in
     if (begin >= 0 && b == end) {
       end = next;
     } else {
-      if (begin >= 0) { oa.begin = begin; oa.count = end - begin; PBT_LAUNCH(h, PBT_K_OPTIMIZER, s, optimizer_step(oa, s)); }
+      if (begin >= 0) { rb[n_ranges] = begin; rc[n_ranges] = end - begin; ++n_ranges; }
       begin = b;
       end = next;
     }
   }
-  if (begin >= 0) { oa.begin = begin; oa.count = end - begin; PBT_LAUNCH(h, PBT_K_OPTIMIZER, s, optimizer_step(oa, s)); }
+  if (begin >= 0) { rb[n_ranges] = begin; rc[n_ranges] = end - begin; ++n_ranges; }
+  for (int r0 = 0; r0 < n_ranges; r0 += OPT_MAX_RANGES) {
+    oa.begin = rb[r0];
+    oa.count = rc[r0];
+    oa.n_extra = n_ranges - r0 - 1 < OPT_MAX_RANGES - 1 ? n_ranges - r0 - 1 : OPT_MAX_RANGES - 1;
+    for (int x = 0; x < oa.n_extra; ++x) { oa.xbegin[x] = rb[r0 + 1 + x]; oa.xcount[x] = rc[r0 + 1 + x]; }
+    PBT_LAUNCH(h, PBT_K_OPTIMIZER, s, optimizer_step(oa, s));
+  }
   return PBT_OK;
 }
 

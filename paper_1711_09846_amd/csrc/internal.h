@@ -90,7 +90,11 @@ struct OptArgs {
   int optimizer;
   int col_lr, col_beta1, col_wd;  // column of H with that role, or -1
   float c0, c1, c2, c3;           // opt_const
+  // further ranges of the flat vector handled by the same launch (the biases between fused matrices)
+  int n_extra = 0;
+  int64_t xbegin[3] = {0, 0, 0}, xcount[3] = {0, 0, 0};
 };
+constexpr int OPT_MAX_RANGES = 4;
 hipError_t optimizer_step(const OptArgs& a, hipStream_t s);
 // Weight-gradient GEMM (o) whose epilogue applies the optimiser to the matrix at offset `off` (row
 // pitch ldc) of every member's flat vector instead of storing the gradient; a.G, a.begin, a.count unused.

@@ -217,13 +217,18 @@ __global__ __launch_bounds__(256) void optimizer_kernel(OptArgs a) {
   const int i = blockIdx.y;
   const OptHyper hy{a.H, a.t, a.n_hyper, a.col_lr, a.col_beta1, a.col_wd, a.c0, a.c1, a.c2, a.c3};
   const OptScalars sc = opt_scalars<OPT>(hy, i);
-  const int64_t base = (int64_t)i * a.stride + a.begin;
-  const int64_t nvec = a.count / 4;
 #pragma unroll
   for (int u = 0; u < OPT_VEC_PER_THREAD; ++u) {
-    const int64_t v = ((int64_t)blockIdx.x * OPT_VEC_PER_THREAD + u) * 256 + threadIdx.x;
+    // vector index over the concatenation of the ranges
+    int64_t v = ((int64_t)blockIdx.x * OPT_VEC_PER_THREAD + u) * 256 + threadIdx.x;
+    int64_t begin = a.begin, nvec = a.count / 4;
+    for (int x = 0; x < a.n_extra && v >= nvec; ++x) {
+      v -= nvec;
+      begin = a.xbegin[x];
+      nvec = a.xcount[x] / 4;
+    }
     if (v >= nvec) break;
-    const int64_t o = base + v * 4;
+    const int64_t o = (int64_t)i * a.stride + begin + v * 4;
     float4 w = stream_load(a.W32 + o);
     const float4 g = stream_load(a.G + o);
     float4 s0 = stream_load(a.S0 + o);
@@ -248,7 +253,12 @@ __global__ __launch_bounds__(256) void optimizer_kernel(OptArgs a) {
 }
 hipError_t optimizer_step(const OptArgs& a, hipStream_t s) {
   if (a.begin % 4 || a.count % 4 || a.count <= 0 || a.begin + a.count > a.stride) return hipErrorInvalidValue;
-  const int64_t nvec = a.count / 4;
+  if (a.n_extra < 0 || a.n_extra > OPT_MAX_RANGES - 1) return hipErrorInvalidValue;
+  int64_t nvec = a.count / 4;
+  for (int x = 0; x < a.n_extra; ++x) {
+    if (a.xbegin[x] % 4 || a.xcount[x] % 4 || a.xcount[x] <= 0 || a.xbegin[x] + a.xcount[x] > a.stride) return hipErrorInvalidValue;
+    nvec += a.xcount[x] / 4;
+  }
   const int per_block = 256 * OPT_VEC_PER_THREAD;
   dim3 grid((unsigned)((nvec + per_block - 1) / per_block), a.P);
   if (a.optimizer == 0)
