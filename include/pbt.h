@@ -59,7 +59,7 @@ typedef enum {
   PBT_ENOMEM = -2,       /* a caller-provided buffer is too small */
   PBT_EDEVICE = -3,      /* a HIP call or kernel launch failed */
   PBT_ESTATE = -4,       /* call not valid in the handle's current state */
-  PBT_EUNSUPPORTED = -5  /* valid request that this build has no kernel for */
+  PBT_EUNSUPPORTED = -5  /* valid request that the library has no kernel for */
 } pbt_status;
 
 enum { PBT_EXPLOIT_TRUNCATION = 0, PBT_EXPLOIT_TOURNAMENT = 1, PBT_EXPLOIT_TTEST = 2 };
