@@ -21,7 +21,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 # for a copy of known size (profiles/population_step_<workload>_hbm_counters.md), by (workload, kernel
 # class).  An entry is only valid for the kernel as it was when the counters were taken; remove it when
 # the kernel changes.
-MEASURED_TRAFFIC_BYTES = {(2, "optimizer"): 2.541e9, (2, "gemm_wgrad_fused"): 1.1184e9, (4, "optimizer"): 10.115e9}
+MEASURED_TRAFFIC_BYTES = {(2, "optimizer"): 2.541e9, (2, "gemm_wgrad_fused"): 1.1187e9, (4, "optimizer"): 10.115e9}
 
 
 def cpu_baseline(workload, wl, seed, budget_s=15.0):
