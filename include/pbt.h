@@ -296,6 +296,12 @@ enum {
  * switches timing off and destroys the events.  Off by default. */
 pbt_status pbt_timing_enable(pbt_handle* h, int32_t kernel_class, int32_t max_launches);
 
+/* Records only every stride-th launch of the timed class (stride >= 1; 1, the default, records all;
+ * pbt_timing_enable resets it to 1).  An event pair costs the stream a few microseconds around the
+ * launch it brackets, so a benchmark that also reports whole-run throughput samples the launches; an odd
+ * stride visits the launches of a step in turn when a class has two per step. */
+pbt_status pbt_timing_stride(pbt_handle* h, int32_t stride);
+
 /* Synchronises the recorded events, returns the summed device time in milliseconds and the
  * number of recorded launches since the last read, and rearms the event pool. */
 pbt_status pbt_timing_read(pbt_handle* h, double* total_ms, int64_t* launches);

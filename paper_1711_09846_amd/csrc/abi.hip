@@ -685,6 +685,8 @@ static void drop_events(pbt_handle* h) {
   h->ev_stop.clear();
   h->ev_used = 0;
   h->timed_class = PBT_K_NONE;
+  h->timed_stride = 1;
+  h->timed_seen = 0;
 }
 
 pbt_status pbt_timing_enable(pbt_handle* h, int32_t kernel_class, int32_t max_launches) {
@@ -701,6 +703,14 @@ pbt_status pbt_timing_enable(pbt_handle* h, int32_t kernel_class, int32_t max_la
     h->ev_stop.push_back(b);
   }
   h->timed_class = kernel_class;
+  return PBT_OK;
+}
+
+pbt_status pbt_timing_stride(pbt_handle* h, int32_t stride) {
+  if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  if (stride < 1) return fail(h, PBT_EINVAL, "stride must be at least 1");
+  h->timed_stride = stride;
+  h->timed_seen = 0;
   return PBT_OK;
 }
 

@@ -91,6 +91,8 @@ struct pbt_handle {
   int timed_class = PBT_K_NONE;
   std::vector<hipEvent_t> ev_start, ev_stop;
   size_t ev_used = 0;
+  int timed_stride = 1;   // every timed_stride-th launch of the class is recorded
+  size_t timed_seen = 0;  // launches of the class since timing was enabled
   template <class T> T* st(size_t off) const { return reinterpret_cast<T*>(state + off); }
   template <class T> T* sc(size_t off) const { return reinterpret_cast<T*>(scratch + off); }
 };
@@ -110,7 +112,8 @@ pbt_status fail(pbt_handle* h, pbt_status code, const char* fmt, ...);
 // with an event pair on the same stream.
 #define PBT_LAUNCH(h, klass, s, call)                                                           \
   do {                                                                                          \
-    const bool timed_ = (h)->timed_class == (klass) && (h)->ev_used < (h)->ev_start.size();     \
+    const bool timed_ = (h)->timed_class == (klass) && (h)->ev_used < (h)->ev_start.size() &&  \
+                        ((h)->timed_seen++ % (size_t)(h)->timed_stride) == 0;                   \
     if (timed_) PBT_HIP(h, hipEventRecord((h)->ev_start[(h)->ev_used], s));                     \
     PBT_HIP(h, call);                                                                           \
     if (timed_) {                                                                               \
