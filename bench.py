@@ -188,7 +188,9 @@ def main():
     else:
       per_launch = {
         # Adam: read theta, g, m, v (16 B), write theta, m, v (12 B) and the bf16 shadow (2 B) per parameter
-        "optimizer": ("hbm", 30.0 * n * wl.P) if args.workload == 2 else None,
+        # (RMSProp: theta, g, one state array read, theta, state and the shadow written: 22 B; the GAN step has two
+        # launches, one over the discriminator's and one over the generator's parameters: mean of the two)
+        "optimizer": ("hbm", {2: 30.0, 3: 15.0, 5: 22.0}[args.workload] * n * wl.P),
         # read + write of every array of the n_trunc copied members: fp32 theta, optimiser state, bf16 shadow
         "copy": ("hbm", 2.0 * state_bytes * n * wl.n_trunc),
         "gemm_fwd": ("mfma", flops_fwd / (L - 1)) if args.workload == 2 else None,
