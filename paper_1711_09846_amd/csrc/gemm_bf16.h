@@ -362,6 +362,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
   static_assert(WM * WN * 32 * CPITCH * 4 <= SLAB * 2, "C strips must fit the slab LDS");
   float* const Cw = reinterpret_cast<float*>(smem) + wave * 32 * CPITCH;
   fetch_first_strip(EARLY_RUNS, NQ4);
+  // A lane handles the same eight columns in every run, so what a functor needs per column (the bias) is
+  // read once, here: read inside the runs, after the stores of the run before, each run paid a memory
+  // latency of its own (more than half of a K = 512 tile's lifetime).  (Ahead of the K loop the eight
+  // registers would cost the 128x128 kernel its third workgroup per compute unit.)
+  static_assert(64 % RUNS == 0, "a lane's runs must share their columns");
+  float colv[8];
+  if constexpr (Epilogue::HAS_COLS) epi.load_cols(n0 + wn * WCOLS + (lane % RUNS) * 8, g.N, colv);
   __syncthreads();  // every wavefront is done with the slabs
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -400,7 +407,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
         const float4 hi = *reinterpret_cast<const float4*>(Cw + row * CPITCH + col + 4);
         if (m < g.M && n < g.N) {
           const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-          epi.apply8(member, m, n, v, g.N - n < 8 ? g.N - n : 8);
+          if constexpr (Epilogue::HAS_COLS) epi.apply8(member, m, n, v, g.N - n < 8 ? g.N - n : 8, colv);
+          else epi.apply8(member, m, n, v, g.N - n < 8 ? g.N - n : 8);
         }
       }
     }
@@ -445,6 +453,7 @@ struct EpiStoreF32 {
   static constexpr bool HAS_FINISH = false;
   static constexpr bool PREFETCH = false;
   static constexpr bool COLSUM = true;   // weight gradients: the bias gradient can ride along
+  static constexpr bool HAS_COLS = false;
   struct Fetched {};
   float* C;
   int64_t ldc, sc;
@@ -464,6 +473,7 @@ struct EpiStoreBF16 {
   static constexpr bool HAS_FINISH = false;
   static constexpr bool PREFETCH = false;
   static constexpr bool COLSUM = false;
+  static constexpr bool HAS_COLS = false;
   struct Fetched {};
   bf16_t* C;
   int64_t ldc, sc;
@@ -480,20 +490,27 @@ struct EpiBiasF32 {
   static constexpr bool HAS_FINISH = false;
   static constexpr bool PREFETCH = false;
   static constexpr bool COLSUM = false;
+  static constexpr bool HAS_COLS = true;
   struct Fetched {};
   const float* bias;
   int64_t sbias;
   float* C;
   int64_t ldc, sc;
   __device__ __forceinline__ void begin(int member) { bias += (int64_t)member * sbias; C += (int64_t)member * sc; }
-  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count) const {
-    const float* b = bias + n;
+  // the eight biases of the lane's columns (the same for every run the lane handles), zero past N
+  __device__ __forceinline__ void load_cols(int n, int N, float* b) const {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) b[e] = n + e < N ? bias[n + e] : 0.f;
+  }
+  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count, const float* b) const {
     float* dst = C + (int64_t)m * ldc + n;
     if (count == 8 && aligned16(dst)) {
       *reinterpret_cast<float4*>(dst) = make_float4(v[0] + b[0], v[1] + b[1], v[2] + b[2], v[3] + b[3]);
       *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4] + b[4], v[5] + b[5], v[6] + b[6], v[7] + b[7]);
     } else {
-      for (int e = 0; e < count; ++e) dst[e] = v[e] + b[e];
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (e < count) dst[e] = v[e] + b[e];
     }
   }
 };
@@ -503,6 +520,7 @@ struct EpiBiasAct {
   static constexpr bool HAS_FINISH = false;
   static constexpr bool PREFETCH = false;
   static constexpr bool COLSUM = false;
+  static constexpr bool HAS_COLS = true;
   struct Fetched {};
   const float* bias;  // + member * sbias + n
   int64_t sbias;
@@ -515,8 +533,12 @@ struct EpiBiasAct {
     if (Z) Z += (int64_t)member * so;
     Aout += (int64_t)member * so;
   }
-  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count) const {
-    const float* b = bias + n;
+  // the eight biases of the lane's columns (the same for every run the lane handles), zero past N
+  __device__ __forceinline__ void load_cols(int n, int N, float* b) const {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) b[e] = n + e < N ? bias[n + e] : 0.f;
+  }
+  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count, const float* b) const {
     float z[8], a[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -534,6 +556,7 @@ struct EpiDgradAct {
   static constexpr bool HAS_FINISH = false;
   static constexpr bool PREFETCH = false;
   static constexpr bool COLSUM = false;
+  static constexpr bool HAS_COLS = false;
   struct Fetched {};
   const bf16_t* Zprev;
   bf16_t* dZ;
@@ -563,6 +586,7 @@ struct EpiOptimizer {
   static constexpr bool HAS_FINISH = false;
   static constexpr bool PREFETCH = true;
   static constexpr bool COLSUM = true;
+  static constexpr bool HAS_COLS = false;
   struct Fetched { float w[4], s0[4], s1[4]; };  // one run of theta and its state, read ahead of use
   float* W32; float* S0; float* S1; bf16_t* W16;
   int64_t stride, off, ldc;   // member stride, offset of the matrix in the member's vector, row pitch
@@ -672,6 +696,7 @@ struct EpiRbfSum {
   static constexpr bool HAS_FINISH = true;
   static constexpr bool PREFETCH = false;
   static constexpr bool COLSUM = false;
+  static constexpr bool HAS_COLS = false;
   struct Fetched {};
   __device__ __forceinline__ void begin(int member) { na += (int64_t)member * sna; nb += (int64_t)member * snb; }
   const float* na;  // squared norms of the A rows, + member * sna
