@@ -398,6 +398,16 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
         if (i + 1 < TM && m + 32 < g.M && n < g.N) pre[q] = epi.fetch(m + 32, n, g.N - n < 4 ? g.N - n : 4);
       }
     } else {
+      uint4 rund[32 * RUNS / 64];
+      if constexpr (Epilogue::HAS_RUNDATA) {
+#pragma unroll
+        for (int q = 0; q < 32 * RUNS / 64; ++q) {
+          const int run = q * 64 + lane;
+          const int m = m0 + wm * (BM / WM) + i * 32 + run / RUNS, n = n0 + wn * WCOLS + (run % RUNS) * 8;
+          rund[q] = make_uint4(0, 0, 0, 0);
+          if (m < g.M && n < g.N) rund[q] = epi.load_run(m, n, g.N - n < 8 ? g.N - n : 8);
+        }
+      }
 #pragma unroll
       for (int q = 0; q < 32 * RUNS / 64; ++q) {
         const int run = q * 64 + lane;
@@ -408,6 +418,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
         if (m < g.M && n < g.N) {
           const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
           if constexpr (Epilogue::HAS_COLS) epi.apply8(member, m, n, v, g.N - n < 8 ? g.N - n : 8, colv);
+          else if constexpr (Epilogue::HAS_RUNDATA) epi.apply8(member, m, n, v, g.N - n < 8 ? g.N - n : 8, rund[q]);
           else epi.apply8(member, m, n, v, g.N - n < 8 ? g.N - n : 8);
         }
       }
@@ -454,6 +465,7 @@ struct EpiStoreF32 {
   static constexpr bool PREFETCH = false;
   static constexpr bool COLSUM = true;   // weight gradients: the bias gradient can ride along
   static constexpr bool HAS_COLS = false;
+  static constexpr bool HAS_RUNDATA = false;
   struct Fetched {};
   float* C;
   int64_t ldc, sc;
@@ -474,6 +486,7 @@ struct EpiStoreBF16 {
   static constexpr bool PREFETCH = false;
   static constexpr bool COLSUM = false;
   static constexpr bool HAS_COLS = false;
+  static constexpr bool HAS_RUNDATA = false;
   struct Fetched {};
   bf16_t* C;
   int64_t ldc, sc;
@@ -491,6 +504,7 @@ struct EpiBiasF32 {
   static constexpr bool PREFETCH = false;
   static constexpr bool COLSUM = false;
   static constexpr bool HAS_COLS = true;
+  static constexpr bool HAS_RUNDATA = false;
   struct Fetched {};
   const float* bias;
   int64_t sbias;
@@ -521,6 +535,7 @@ struct EpiBiasAct {
   static constexpr bool PREFETCH = false;
   static constexpr bool COLSUM = false;
   static constexpr bool HAS_COLS = true;
+  static constexpr bool HAS_RUNDATA = false;
   struct Fetched {};
   const float* bias;  // + member * sbias + n
   int64_t sbias;
@@ -557,20 +572,28 @@ struct EpiDgradAct {
   static constexpr bool PREFETCH = false;
   static constexpr bool COLSUM = false;
   static constexpr bool HAS_COLS = false;
+  static constexpr bool HAS_RUNDATA = true;
   struct Fetched {};
   const bf16_t* Zprev;
   bf16_t* dZ;
   int64_t ld, so;
   int act;
   __device__ __forceinline__ void begin(int member) { Zprev += (int64_t)member * so; dZ += (int64_t)member * so; }
-  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count) const {
+  // the run of z the result is scaled by: requested for all runs of a strip before the first is applied
+  // (read inside apply8, after the store of the run before, every run paid a memory latency of its own)
+  __device__ __forceinline__ uint4 load_run(int m, int n, int count) const {
+    const int64_t o = (int64_t)m * ld + n;
+    if (count == 8 && aligned16(Zprev + o)) return *reinterpret_cast<const uint4*>(Zprev + o);
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (e < count) w[e >> 1] |= (uint32_t)Zprev[o + e] << (16 * (e & 1));
+    return make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count, uint4 zrun) const {
     const int64_t o = (int64_t)m * ld + n;
     float z[8], d[8];
-    if (count == 8 && aligned16(Zprev + o)) {
-      unpack_bf16x8(*reinterpret_cast<const uint4*>(Zprev + o), z);
-    } else {
-      for (int e = 0; e < 8; ++e) z[e] = e < count ? bf2f(Zprev[o + e]) : 0.f;
-    }
+    unpack_bf16x8(zrun, z);
 #pragma unroll
     for (int e = 0; e < 8; ++e) d[e] = v[e] * act_bwd(z[e], act);
     store_bf16_run(dZ + o, d, count);
@@ -587,6 +610,7 @@ struct EpiOptimizer {
   static constexpr bool PREFETCH = true;
   static constexpr bool COLSUM = true;
   static constexpr bool HAS_COLS = false;
+  static constexpr bool HAS_RUNDATA = false;
   struct Fetched { float w[4], s0[4], s1[4]; };  // one run of theta and its state, read ahead of use
   float* W32; float* S0; float* S1; bf16_t* W16;
   int64_t stride, off, ldc;   // member stride, offset of the matrix in the member's vector, row pitch
@@ -697,6 +721,7 @@ struct EpiRbfSum {
   static constexpr bool PREFETCH = false;
   static constexpr bool COLSUM = false;
   static constexpr bool HAS_COLS = false;
+  static constexpr bool HAS_RUNDATA = false;
   struct Fetched {};
   __device__ __forceinline__ void begin(int member) { na += (int64_t)member * sna; nb += (int64_t)member * snb; }
   const float* na;  // squared norms of the A rows, + member * sna

@@ -155,6 +155,14 @@ __global__ __launch_bounds__(NTL_THREADS) void gemm_nt_lds_kernel(GemmArgs g, Ep
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    uint4 rund[32 * RUNS / 64];
+    if constexpr (Epilogue::HAS_RUNDATA) {
+#pragma unroll
+      for (int q = 0; q < 32 * RUNS / 64; ++q) {
+        const int run = q * 64 + lane;
+        rund[q] = epi.load_run(m0 + wm * (BM / WM) + i * 32 + run / RUNS, n0 + wn * WCOLS + (run % RUNS) * 8, 8);
+      }
+    }
 #pragma unroll
     for (int q = 0; q < 32 * RUNS / 64; ++q) {
       const int run = q * 64 + lane;
@@ -163,7 +171,8 @@ __global__ __launch_bounds__(NTL_THREADS) void gemm_nt_lds_kernel(GemmArgs g, Ep
       const float4 lo = *reinterpret_cast<const float4*>(Cw + row * CPITCH + col);
       const float4 hi = *reinterpret_cast<const float4*>(Cw + row * CPITCH + col + 4);
       const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-      epi.apply8(member, m, n, v, 8);
+      if constexpr (Epilogue::HAS_RUNDATA) epi.apply8(member, m, n, v, 8, rund[q]);
+      else epi.apply8(member, m, n, v, 8);
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
