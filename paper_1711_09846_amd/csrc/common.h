@@ -60,6 +60,56 @@ __device__ __forceinline__ float act_bwd(float z, int kind) {
   }
 }
 
+// The same for eight values with the choice of the activation taken once, outside the element loop (inside
+// it the compiler keeps a branch ladder per element).
+__device__ __forceinline__ void act_fwd8(const float* z, float* a, int kind) {
+  switch (kind) {
+    case ACT_RELU:
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a[e] = z[e] > 0.f ? z[e] : 0.f;
+      break;
+    case ACT_GELU:
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { float c, p; normal_cdf_pdf(z[e], c, p); a[e] = z[e] * c; }
+      break;
+    case ACT_LEAKY_RELU:
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a[e] = z[e] > 0.f ? z[e] : 0.2f * z[e];
+      break;
+    case ACT_TANH:
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a[e] = tanhf(z[e]);
+      break;
+    default:
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a[e] = z[e];
+  }
+}
+// d[e] = v[e] * act'(z[e])
+__device__ __forceinline__ void act_bwd_scale8(const float* v, const float* z, float* d, int kind) {
+  switch (kind) {
+    case ACT_RELU:
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d[e] = v[e] * (z[e] > 0.f ? 1.f : 0.f);
+      break;
+    case ACT_GELU:
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { float c, p; normal_cdf_pdf(z[e], c, p); d[e] = v[e] * fmaf(z[e], p, c); }
+      break;
+    case ACT_LEAKY_RELU:
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d[e] = v[e] * (z[e] > 0.f ? 1.f : 0.2f);
+      break;
+    case ACT_TANH:
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { const float t = tanhf(z[e]); d[e] = v[e] * (1.f - t * t); }
+      break;
+    default:
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d[e] = v[e] * 1.f;
+  }
+}
+
 // Sum over the 64 lanes of a wavefront; every lane receives the total.  The
 // butterfly order is fixed, so the result does not depend on scheduling.
 __device__ __forceinline__ float wave_sum(float v) {

@@ -513,8 +513,13 @@ struct EpiBiasF32 {
   __device__ __forceinline__ void begin(int member) { bias += (int64_t)member * sbias; C += (int64_t)member * sc; }
   // the eight biases of the lane's columns (the same for every run the lane handles), zero past N
   __device__ __forceinline__ void load_cols(int n, int N, float* b) const {
+    if (n + 8 <= N && aligned16(bias + n)) {
+      const float4 lo = *reinterpret_cast<const float4*>(bias + n), hi = *reinterpret_cast<const float4*>(bias + n + 4);
+      b[0] = lo.x; b[1] = lo.y; b[2] = lo.z; b[3] = lo.w; b[4] = hi.x; b[5] = hi.y; b[6] = hi.z; b[7] = hi.w;
+    } else {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) b[e] = n + e < N ? bias[n + e] : 0.f;
+      for (int e = 0; e < 8; ++e) b[e] = n + e < N ? bias[n + e] : 0.f;
+    }
   }
   __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count, const float* b) const {
     float* dst = C + (int64_t)m * ldc + n;
@@ -550,16 +555,19 @@ struct EpiBiasAct {
   }
   // the eight biases of the lane's columns (the same for every run the lane handles), zero past N
   __device__ __forceinline__ void load_cols(int n, int N, float* b) const {
+    if (n + 8 <= N && aligned16(bias + n)) {
+      const float4 lo = *reinterpret_cast<const float4*>(bias + n), hi = *reinterpret_cast<const float4*>(bias + n + 4);
+      b[0] = lo.x; b[1] = lo.y; b[2] = lo.z; b[3] = lo.w; b[4] = hi.x; b[5] = hi.y; b[6] = hi.z; b[7] = hi.w;
+    } else {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) b[e] = n + e < N ? bias[n + e] : 0.f;
+      for (int e = 0; e < 8; ++e) b[e] = n + e < N ? bias[n + e] : 0.f;
+    }
   }
   __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count, const float* b) const {
     float z[8], a[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      z[e] = e < count ? v[e] + b[e] : 0.f;
-      a[e] = act_fwd(z[e], act);
-    }
+    for (int e = 0; e < 8; ++e) z[e] = e < count ? v[e] + b[e] : 0.f;
+    act_fwd8(z, a, act);
     const int64_t o = (int64_t)m * ld + n;
     if (Z) store_bf16_run(Z + o, z, count);
     store_bf16_run(Aout + o, a, count);
@@ -594,8 +602,7 @@ struct EpiDgradAct {
     const int64_t o = (int64_t)m * ld + n;
     float z[8], d[8];
     unpack_bf16x8(zrun, z);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) d[e] = v[e] * act_bwd(z[e], act);
+    act_bwd_scale8(v, z, d, act);
     store_bf16_run(dZ + o, d, count);
   }
 };
