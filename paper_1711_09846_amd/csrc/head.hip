@@ -238,12 +238,15 @@ __global__ __launch_bounds__(256) void head_dgrad_kernel(const bf16_t* __restric
     if (vec && k + 8 <= K) {
       const uint4 z = *reinterpret_cast<const uint4*>(Zprev + o);
       const uint32_t zw[4] = {z.x, z.y, z.z, z.w};
-      uint32_t out[4];
+      float zf[8], d[8];
 #pragma unroll
-      for (int h = 0; h < 4; ++h)
-        out[h] = f2bf_pair(v[2 * h] * act_bwd(__uint_as_float(zw[h] << 16), act),
-                           v[2 * h + 1] * act_bwd(__uint_as_float(zw[h] & 0xffff0000u), act));
-      *reinterpret_cast<uint4*>(dZprev + o) = make_uint4(out[0], out[1], out[2], out[3]);
+      for (int h = 0; h < 4; ++h) {
+        zf[2 * h] = __uint_as_float(zw[h] << 16);
+        zf[2 * h + 1] = __uint_as_float(zw[h] & 0xffff0000u);
+      }
+      act_bwd_scale8(v, zf, d, act);
+      *reinterpret_cast<uint4*>(dZprev + o) =
+          make_uint4(f2bf_pair(d[0], d[1]), f2bf_pair(d[2], d[3]), f2bf_pair(d[4], d[5]), f2bf_pair(d[6], d[7]));
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e)
