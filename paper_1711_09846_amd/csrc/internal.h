@@ -135,8 +135,11 @@ hipError_t softmax_fwd(const bf16_t* sc, int P, int64_t rows, int S, float scale
                        bf16_t* pd, hipStream_t s);
 hipError_t softmax_bwd(const bf16_t* pq, bf16_t* dpd, int P, int64_t rows, int S, float scale, const DropArgs& d, int site,
                        hipStream_t s);
+// out = x * keep (+ res); mask_out (optional) receives the keep bits, mask_in (optional) supplies them (the
+// backward pass of a site reads what its forward pass recorded); dropout_mask_bytes sizes such a record
 hipError_t dropout_apply(const bf16_t* x, const bf16_t* res, int P, int64_t per_member, const DropArgs& d, int site, bf16_t* out,
-                         hipStream_t s);
+                         hipStream_t s, const uint16_t* mask_in = nullptr, uint16_t* mask_out = nullptr);
+size_t dropout_mask_bytes(int P, int64_t per_member);
 hipError_t xent_rows(const float* logits, const int32_t* targets, int P, int rows, int V, const float* H, int n_hyper, int col_ls,
                      int use_ls, float gscale, bf16_t* dlogits, float* rowloss, hipStream_t s);
 hipError_t perplexity_score(const float* rowloss, int P, int rows, float* score, hipStream_t s);

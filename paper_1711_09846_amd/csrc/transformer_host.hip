@@ -90,14 +90,15 @@ pbt_status forward(const Ctx& x, const int32_t* pool, int n_pool, uint32_t c0, i
     PBT_HIP(h, softmax_fwd(score, x.P, (int64_t)x.Bc * D.H * D.S, D.S, 1.f / sqrtf((float)D.dh), dr, 4 * l + 0, pq, pd, x.s));
     TF_TRY(attn_gemm(x, in_scores(pd, D), false, in_rows(qkv, 2 * D.d, 3 * D.d, D), false, in_rows(o, 0, D.d, D), D.S, D.dh, D.S));
     TF_TRY(dense(x, o, D.d, D.d, b.wo, b.bo, nullptr, tmp_d, PBT_ACT_NONE));
-    PBT_HIP(h, dropout_apply(tmp_d, hin, x.P, per_d, dr, 4 * l + 1, hmid, x.s));
+    PBT_HIP(h, dropout_apply(tmp_d, hin, x.P, per_d, dr, 4 * l + 1, hmid, x.s, nullptr, x.sc<uint16_t>(t.o_mask[l][0])));
     bf16_t* u2 = x.sc<bf16_t>(t.o_u2[l]);
     PBT_HIP(h, layernorm_fwd(hmid, x.P, x.n, D.d, x.W32, x.S_, b.ln2g, b.ln2b, u2, x.sc<float>(t.o_mean2[l]), x.sc<float>(t.o_rstd2[l]), x.s));
     // only relu(z) is kept: it is positive exactly where z is, which is all the backward pass needs
     TF_TRY(dense(x, u2, D.d, D.f, b.w1, b.b1, nullptr, x.sc<bf16_t>(t.o_z1[l]), PBT_ACT_RELU));
-    PBT_HIP(h, dropout_apply(x.sc<bf16_t>(t.o_z1[l]), nullptr, x.P, per_f, dr, 4 * l + 2, x.sc<bf16_t>(t.o_fd[l]), x.s));
+    PBT_HIP(h, dropout_apply(x.sc<bf16_t>(t.o_z1[l]), nullptr, x.P, per_f, dr, 4 * l + 2, x.sc<bf16_t>(t.o_fd[l]), x.s, nullptr,
+                             x.sc<uint16_t>(t.o_mask[l][1])));
     TF_TRY(dense(x, x.sc<bf16_t>(t.o_fd[l]), D.f, D.d, b.w2, b.b2, nullptr, tmp_d, PBT_ACT_NONE));
-    PBT_HIP(h, dropout_apply(tmp_d, hmid, x.P, per_d, dr, 4 * l + 3, hout, x.s));
+    PBT_HIP(h, dropout_apply(tmp_d, hmid, x.P, per_d, dr, 4 * l + 3, hout, x.s, nullptr, x.sc<uint16_t>(t.o_mask[l][2])));
   }
   bf16_t* uf = x.sc<bf16_t>(t.o_uf);
   PBT_HIP(h, layernorm_fwd(x.sc<bf16_t>(t.o_h[D.L]), x.P, x.n, D.d, x.W32, x.S_, t.lnfg, t.lnfb, uf, x.sc<float>(t.o_meanf), x.sc<float>(t.o_rstdf), x.s));
@@ -161,6 +162,9 @@ pbt_status tf_check_and_plan(const pbt_config* c, Plan* pl, Carver* w) {
     t.o_mean2[l] = w->take(P * n * 4); t.o_rstd2[l] = w->take(P * n * 4);
     t.o_u[l] = w->take(nd); t.o_qkv[l] = w->take(3 * nd); t.o_pq[l] = w->take(ns); t.o_pd[l] = w->take(ns); t.o_o[l] = w->take(nd);
     t.o_u2[l] = w->take(nd); t.o_z1[l] = w->take(nf); t.o_fd[l] = w->take(nf);
+    t.o_mask[l][0] = w->take(dropout_mask_bytes((int)P, (int64_t)n * D.d));
+    t.o_mask[l][1] = w->take(dropout_mask_bytes((int)P, (int64_t)n * D.f));
+    t.o_mask[l][2] = w->take(dropout_mask_bytes((int)P, (int64_t)n * D.d));
   }
   t.o_meanf = w->take(P * n * 4); t.o_rstdf = w->take(P * n * 4);
   t.o_score = w->take(ns);
@@ -218,16 +222,16 @@ pbt_status tf_step(pbt_handle* h, const int32_t* pool, uint32_t step, hipStream_
     const TfBlockOff& b = t.blk[l];
     bf16_t* qkv = x.sc<bf16_t>(t.o_qkv[l]);
     // feed-forward branch
-    PBT_HIP(h, dropout_apply(dh, nullptr, x.P, per_d, dr, 4 * l + 3, dd, s));
+    PBT_HIP(h, dropout_apply(dh, nullptr, x.P, per_d, dr, 4 * l + 3, dd, s, x.sc<uint16_t>(t.o_mask[l][2])));
     TF_TRY(wgrad(x, x.sc<bf16_t>(t.o_fd[l]), D.f, dd, D.d, b.w2, b.b2));
     TF_TRY(dgrad(x, dd, D.d, D.f, b.w2, x.sc<bf16_t>(t.o_z1[l]), PBT_ACT_RELU, df0));
-    PBT_HIP(h, dropout_apply(df0, nullptr, x.P, per_f, dr, 4 * l + 2, df1, s));
+    PBT_HIP(h, dropout_apply(df0, nullptr, x.P, per_f, dr, 4 * l + 2, df1, s, x.sc<uint16_t>(t.o_mask[l][1])));
     TF_TRY(wgrad(x, x.sc<bf16_t>(t.o_u2[l]), D.d, df1, D.f, b.w1, b.b1));
     TF_TRY(dgrad(x, df1, D.f, D.d, b.w1, nullptr, 0, du));
     PBT_HIP(h, layernorm_param_grad(du, x.sc<bf16_t>(t.o_hmid[l]), x.sc<float>(t.o_mean2[l]), x.sc<float>(t.o_rstd2[l]), x.P, x.n, D.d, x.G, x.S_, b.ln2g, b.ln2b, x.sc<float>(t.o_lnpart), s));
     PBT_HIP(h, layernorm_bwd(du, x.sc<bf16_t>(t.o_hmid[l]), x.sc<float>(t.o_mean2[l]), x.sc<float>(t.o_rstd2[l]), x.P, x.n, D.d, x.W32, x.S_, b.ln2g, dh, dh2, s));
     // attention branch
-    PBT_HIP(h, dropout_apply(dh2, nullptr, x.P, per_d, dr, 4 * l + 1, dd, s));
+    PBT_HIP(h, dropout_apply(dh2, nullptr, x.P, per_d, dr, 4 * l + 1, dd, s, x.sc<uint16_t>(t.o_mask[l][0])));
     TF_TRY(wgrad(x, x.sc<bf16_t>(t.o_o[l]), D.d, dd, D.d, b.wo, b.bo));
     TF_TRY(dgrad(x, dd, D.d, D.d, b.wo, nullptr, 0, du));  // du = gradient of the merged head outputs
     const bf16_t* pd = x.sc<bf16_t>(t.o_pd[l]);

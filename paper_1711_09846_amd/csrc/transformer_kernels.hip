@@ -500,14 +500,37 @@ __device__ __forceinline__ void dropout_group(uint2 xv, bool has_res, uint2 rv, 
   out->x = d2bf(v[0]) | ((uint32_t)d2bf(v[1]) << 16);
   out->y = d2bf(v[2]) | ((uint32_t)d2bf(v[3]) << 16);
 }
+// keep bits (bit k = element 4*blk + k kept) of one group, from the Philox words or, when the pass that made
+// them left them behind, from its record
+__device__ __forceinline__ uint32_t drop_bits4(const DropArgs& d, const DropRate& r, int member, int site, uint32_t blk) {
+  if (r.thr == 0u) return 15u;
+  const u32x4 w = philox4x32_10(d.c0, (uint32_t)member, (uint32_t)(DOMAIN_DROPOUT + site), blk, (uint32_t)d.seed, (uint32_t)(d.seed >> 32));
+  return (w.x >= r.thr ? 1u : 0u) | (w.y >= r.thr ? 2u : 0u) | (w.z >= r.thr ? 4u : 0u) | (w.w >= r.thr ? 8u : 0u);
+}
+__device__ __forceinline__ void bits_to_factors(uint32_t bits, float scale, float* f) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) f[k] = (bits >> k) & 1u ? scale : 0.f;
+}
+// mask_out (may be null): the forward pass records the keep bits, one 16-bit word per thread (four groups);
+// mask_in (may be null): the backward pass of the same site and step reads them instead of repeating the
+// Philox calls, whose 32-bit multiplies, not memory, bound this kernel.
 __global__ __launch_bounds__(256) void dropout_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ res,
-                                                      int64_t per_member, DropArgs d, int site, bf16_t* __restrict__ out) {
+                                                      int64_t per_member, DropArgs d, int site, bf16_t* __restrict__ out,
+                                                      const uint16_t* __restrict__ mask_in, uint16_t* __restrict__ mask_out) {
   const int i = blockIdx.y;
-  const int64_t first = ((int64_t)blockIdx.x * 256 + threadIdx.x) * DROP_GROUPS;   // first group of this thread
+  const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t first = tid * DROP_GROUPS;   // first group of this thread
   const int64_t groups = per_member / 4;
   if (first >= groups) return;
   const DropRate dr = drop_rate(d.H, d.n_hyper, d.col, i, d.active);
   const int64_t o = (int64_t)i * per_member + first * 4;
+  const int64_t words = (groups + DROP_GROUPS - 1) / DROP_GROUPS;   // mask words per member
+  uint32_t word = mask_in ? mask_in[(int64_t)i * words + tid] : 0u, made = 0u;
+  auto group_bits = [&](int g) {
+    const uint32_t bits = mask_in ? (word >> (4 * g)) & 15u : drop_bits4(d, dr, i, site, (uint32_t)(first + g));
+    made |= bits << (4 * g);
+    return bits;
+  };
   if (first + DROP_GROUPS <= groups && ((reinterpret_cast<uintptr_t>(x + o) | reinterpret_cast<uintptr_t>(out + o) |
                                          (res ? reinterpret_cast<uintptr_t>(res + o) : 0)) & 15) == 0) {
     uint4 xv[DROP_GROUPS / 2], rv[DROP_GROUPS / 2], ov[DROP_GROUPS / 2];
@@ -520,9 +543,9 @@ __global__ __launch_bounds__(256) void dropout_kernel(const bf16_t* __restrict__
     for (int h = 0; h < DROP_GROUPS / 2; ++h) {
       float f[4];
       uint2 lo, hi;
-      drop_factors4(d, dr, i, site, (uint32_t)(first + 2 * h), f);
+      bits_to_factors(group_bits(2 * h), dr.scale, f);
       dropout_group(make_uint2(xv[h].x, xv[h].y), res != nullptr, make_uint2(rv[h].x, rv[h].y), f, &lo);
-      drop_factors4(d, dr, i, site, (uint32_t)(first + 2 * h + 1), f);
+      bits_to_factors(group_bits(2 * h + 1), dr.scale, f);
       dropout_group(make_uint2(xv[h].z, xv[h].w), res != nullptr, make_uint2(rv[h].z, rv[h].w), f, &hi);
       ov[h] = make_uint4(lo.x, lo.y, hi.x, hi.y);
     }
@@ -532,18 +555,24 @@ __global__ __launch_bounds__(256) void dropout_kernel(const bf16_t* __restrict__
     for (int g = 0; g < DROP_GROUPS && first + g < groups; ++g) {
       float f[4];
       uint2 pk;
-      drop_factors4(d, dr, i, site, (uint32_t)(first + g), f);
+      bits_to_factors(group_bits(g), dr.scale, f);
       const uint2 rv = res ? *reinterpret_cast<const uint2*>(res + o + 4 * g) : make_uint2(0, 0);
       dropout_group(*reinterpret_cast<const uint2*>(x + o + 4 * g), res != nullptr, rv, f, &pk);
       *reinterpret_cast<uint2*>(out + o + 4 * g) = pk;
     }
   }
+  if (mask_out) mask_out[(int64_t)i * words + tid] = (uint16_t)made;
+}
+size_t dropout_mask_bytes(int P, int64_t per_member) {
+  const int64_t groups = per_member / 4;
+  return (size_t)P * (size_t)((groups + DROP_GROUPS - 1) / DROP_GROUPS) * sizeof(uint16_t);
 }
 hipError_t dropout_apply(const bf16_t* x, const bf16_t* res, int P, int64_t per_member, const DropArgs& d, int site, bf16_t* out,
-                         hipStream_t s) {
+                         hipStream_t s, const uint16_t* mask_in, uint16_t* mask_out) {
   if (per_member % 4) return hipErrorInvalidValue;
   const int64_t threads = (per_member / 4 + DROP_GROUPS - 1) / DROP_GROUPS;
-  hipLaunchKernelGGL(dropout_kernel, dim3((unsigned)((threads + 255) / 256), P), dim3(256), 0, s, x, res, per_member, d, site, out);
+  hipLaunchKernelGGL(dropout_kernel, dim3((unsigned)((threads + 255) / 256), P), dim3(256), 0, s, x, res, per_member, d, site, out,
+                     mask_in, mask_out);
   return hipGetLastError();
 }
 
