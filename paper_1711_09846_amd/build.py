@@ -28,7 +28,7 @@ def _compile(src):
     obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
     cmd = [_hipcc()] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
-    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+    err = r.stderr
     if r.returncode != 0:
         raise RuntimeError("hipcc failed on %s:\n%s" % (src, err))
     return obj, err

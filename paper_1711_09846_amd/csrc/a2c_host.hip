@@ -160,6 +160,9 @@ pbt_status a2c_check_and_plan(const pbt_config* c, Plan* pl, Carver* w) {
   const int L = c->n_layers;
   if (L < 2) return fail(nullptr, PBT_EUNSUPPORTED, "the actor-critic network needs at least one torso layer before its head");
   if (c->unroll < 1) return fail(nullptr, PBT_EINVAL, "unroll must be positive");
+  // the step passes one optimiser-state array and no beta1 / decay columns to the update kernels
+  if (c->optimizer != PBT_OPT_RMSPROP && c->optimizer != PBT_OPT_SGD_MOMENTUM)
+    return fail(nullptr, PBT_EUNSUPPORTED, "the actor-critic workload is built for RMSProp and SGD with momentum");
   if ((int64_t)c->batch * c->unroll * 4 > 48 * 1024) return fail(nullptr, PBT_EUNSUPPORTED, "batch x unroll above 12288 transitions per member");
   if (c->dims[L] < 2 || c->dims[L] > 32) return fail(nullptr, PBT_EUNSUPPORTED, "head width (actions + value) must be 2..32");
   for (int l = 0; l < L; ++l)

@@ -90,6 +90,8 @@ pbt_status check_config(const pbt_config* c, Plan* pl) {
   if (a2c != (pl->a2c.col_ent >= 0)) return fail(nullptr, PBT_EINVAL, "an entropy-cost column goes with the actor-critic workload, and only with it");
   if (c->optimizer != PBT_OPT_ADAM && (pl->col_beta1 >= 0 || pl->col_wd >= 0))
     return fail(nullptr, PBT_EINVAL, "beta1 / weight-decay columns need the Adam optimizer");
+  // explore only clamps at hyper_max: at beta1 >= 1 the bias correction 1 / (1 - beta1^t) is infinite or negative
+  if (pl->col_beta1 >= 0 && !(c->hyper_max[pl->col_beta1] < 1.f)) return fail(nullptr, PBT_EINVAL, "hyper_max of the beta1 column must be below 1");
   return PBT_OK;
 }
 

@@ -131,3 +131,22 @@ def test_exploit_variants_size_their_staging_rows():
     for alpha in (0.0, 1.5):
         with pytest.raises(binding.PbtError):
             binding.query_sizes(binding.make_config(workloads.A2C_MLP.replace(exploit_mode=2, ttest_alpha=alpha), 1))
+
+
+def test_actor_critic_rejects_optimizers_it_has_no_state_for():
+    """The actor-critic step hands one optimiser-state array to the update kernels: Adam is refused at
+    configuration time (both by the size query and, through the same check, by pbt_init)."""
+    for opt, oc in ((workloads.OPT_RMSPROP, dict(rho=0.99, eps=1e-5)), (workloads.OPT_SGD_MOMENTUM, dict(momentum=0.9))):
+        binding.query_sizes(binding.make_config(workloads.A2C_MLP.replace(optimizer=opt, opt_const=oc), 1))
+    with pytest.raises(binding.PbtError) as e:
+        binding.query_sizes(binding.make_config(workloads.A2C_MLP.replace(optimizer=workloads.OPT_ADAM, opt_const=dict()), 1))
+    assert e.value.status == -5
+
+
+def test_beta1_column_needs_an_upper_clamp_below_one():
+    """Explore only clamps at hyper_max; beta1 >= 1 would make Adam's bias correction infinite."""
+    binding.query_sizes(binding.make_config(workloads.MLP_WIDE, 1))
+    for bad in (1.0, math.inf):
+        with pytest.raises(binding.PbtError) as e:
+            binding.query_sizes(binding.make_config(workloads.MLP_WIDE.replace(h_max=[math.inf, bad, math.inf]), 1))
+        assert e.value.status == -1
