@@ -95,9 +95,9 @@ def params_of(spec, m):
 def dropout_keep(seed, step, member, site, n, p32):
     """Boolean keep mask of n elements for rate p32 (a float32 value)."""
     thr = min(int(np.floor(np.float64(p32) * 4294967296.0)), 4294967295)
-    e = np.arange(n)
-    w = philox.words(seed, step, member, philox.DOMAIN_DROPOUT + site, e // 4)
-    return w[e, e % 4].astype(np.uint64) >= np.uint64(thr)
+    # element e takes word e % 4 of counter e // 4: the words of counters 0, 1, 2, ... laid end to end
+    w = philox.words(seed, step, member, philox.DOMAIN_DROPOUT + site, np.arange((n + 3) // 4))
+    return w.reshape(-1)[:n].astype(np.uint64) >= np.uint64(thr)
 
 
 def layernorm(x, g, b):
