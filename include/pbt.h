@@ -296,7 +296,13 @@ enum {
  * switches timing off and destroys the events.  Off by default. */
 pbt_status pbt_timing_enable(pbt_handle* h, int32_t kernel_class, int32_t max_launches);
 
-/* Records only every stride-th launch of the timed class (stride >= 1; 1, the default, records all;
+/* As pbt_timing_enable for several classes at once: bit k of class_mask selects class k (0 switches timing
+ * off).  Every recorded pair remembers its class; pbt_timing_read_class sums one class without rearming,
+ * pbt_timing_read sums all of them and rearms. */
+pbt_status pbt_timing_enable_classes(pbt_handle* h, uint32_t class_mask, int32_t max_launches);
+pbt_status pbt_timing_read_class(pbt_handle* h, int32_t kernel_class, double* total_ms, int64_t* launches);
+
+/* Records only every stride-th launch of each timed class (stride >= 1; 1, the default, records all;
  * pbt_timing_enable resets it to 1).  An event pair costs the stream a few microseconds around the
  * launch it brackets, so a benchmark that also reports whole-run throughput samples the launches; an odd
  * stride visits the launches of a step in turn when a class has two per step. */

@@ -23,7 +23,8 @@ _ARR_DTYPE = {ARR_W32: np.float32, ARR_OPT0: np.float32, ARR_OPT1: np.float32, A
 
 EXPORTS = ["pbt_query_sizes", "pbt_init", "pbt_step", "pbt_eval", "pbt_exploit_explore", "pbt_get_state",
            "pbt_set_state", "pbt_state_ptr", "pbt_destroy", "pbt_last_error", "pbt_batched_gemm_bf16",
-           "pbt_timing_enable", "pbt_timing_stride", "pbt_timing_read", "pbt_init_population", "pbt_set_priors"]
+           "pbt_timing_enable", "pbt_timing_stride", "pbt_timing_read", "pbt_init_population", "pbt_set_priors",
+           "pbt_timing_enable_classes", "pbt_timing_read_class"]
 (K_NONE, K_FETCH, K_GEMM_FWD, K_HEAD, K_GEMM_WGRAD, K_GEMM_DGRAD, K_BIAS_GRAD, K_OPTIMIZER, K_RANK, K_COPY,
  K_FUSED_STEP) = range(-1, 10)
 
@@ -86,6 +87,8 @@ def lib():
         L.pbt_set_priors.argtypes = [vp, C.POINTER(PbtPrior)]
         L.pbt_timing_enable.argtypes = [vp, i32, i32]
         L.pbt_timing_stride.argtypes = [vp, i32]
+        L.pbt_timing_enable_classes.argtypes = [vp, C.c_uint32, i32]
+        L.pbt_timing_read_class.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
         L.pbt_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
         for name in EXPORTS:
             if name != "pbt_last_error":
@@ -255,6 +258,19 @@ class Population:
 
     def timing_enable(self, kernel_class, max_launches=1):
         self._check(lib().pbt_timing_enable(self._h, kernel_class, max_launches))
+
+    def timing_enable_classes(self, classes, max_launches):
+        """Brackets every launch of the listed kernel classes (K_* constants) with HIP events."""
+        mask = 0
+        for k in classes:
+            mask |= 1 << k
+        self._check(lib().pbt_timing_enable_classes(self._h, mask, max_launches))
+
+    def timing_read_class(self, kernel_class):
+        """(summed device milliseconds, recorded launches) of one class; does not rearm."""
+        ms, n = C.c_double(), C.c_int64()
+        self._check(lib().pbt_timing_read_class(self._h, kernel_class, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
 
     def timing_stride(self, stride):
         self._check(lib().pbt_timing_stride(self._h, stride))

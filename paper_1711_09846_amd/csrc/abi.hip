@@ -14,6 +14,7 @@ using namespace pbt;
 
 namespace {
 thread_local std::string g_last_error = "";
+
 }
 
 namespace pbt {
@@ -685,17 +686,18 @@ static void drop_events(pbt_handle* h) {
   for (hipEvent_t e : h->ev_stop) (void)hipEventDestroy(e);
   h->ev_start.clear();
   h->ev_stop.clear();
+  h->ev_class.clear();
   h->ev_used = 0;
-  h->timed_class = PBT_K_NONE;
+  h->timed_mask = 0;
   h->timed_stride = 1;
-  h->timed_seen = 0;
+  for (size_t& n : h->timed_seen) n = 0;
 }
 
-pbt_status pbt_timing_enable(pbt_handle* h, int32_t kernel_class, int32_t max_launches) {
+pbt_status pbt_timing_enable_classes(pbt_handle* h, uint32_t class_mask, int32_t max_launches) {
   if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
-  if (kernel_class < PBT_K_NONE || kernel_class >= PBT_K_COUNT) return fail(h, PBT_EINVAL, "unknown kernel class %d", kernel_class);
+  if (class_mask >> PBT_K_COUNT) return fail(h, PBT_EINVAL, "class mask 0x%x names a class beyond %d", class_mask, PBT_K_COUNT - 1);
   drop_events(h);
-  if (kernel_class == PBT_K_NONE) return PBT_OK;
+  if (class_mask == 0) return PBT_OK;
   if (max_launches < 1 || max_launches > (1 << 20)) return fail(h, PBT_EINVAL, "max_launches outside 1..2^20");
   for (int k = 0; k < max_launches; ++k) {
     hipEvent_t a, b;
@@ -704,31 +706,53 @@ pbt_status pbt_timing_enable(pbt_handle* h, int32_t kernel_class, int32_t max_la
     PBT_HIP(h, hipEventCreate(&b));
     h->ev_stop.push_back(b);
   }
-  h->timed_class = kernel_class;
+  h->ev_class.assign((size_t)max_launches, PBT_K_NONE);
+  h->timed_mask = class_mask;
   return PBT_OK;
+}
+
+pbt_status pbt_timing_enable(pbt_handle* h, int32_t kernel_class, int32_t max_launches) {
+  if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  if (kernel_class < PBT_K_NONE || kernel_class >= PBT_K_COUNT) return fail(h, PBT_EINVAL, "unknown kernel class %d", kernel_class);
+  return pbt_timing_enable_classes(h, kernel_class == PBT_K_NONE ? 0u : 1u << kernel_class, max_launches);
 }
 
 pbt_status pbt_timing_stride(pbt_handle* h, int32_t stride) {
   if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
   if (stride < 1) return fail(h, PBT_EINVAL, "stride must be at least 1");
   h->timed_stride = stride;
-  h->timed_seen = 0;
+  for (size_t& n : h->timed_seen) n = 0;
   return PBT_OK;
 }
 
-pbt_status pbt_timing_read(pbt_handle* h, double* total_ms, int64_t* launches) {
-  if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+// Sums the recorded pairs of one class (PBT_K_NONE: of all classes).
+static pbt_status sum_events(pbt_handle* h, int klass, double* total_ms, int64_t* launches) {
   double sum = 0.0;
+  int64_t n = 0;
   for (size_t k = 0; k < h->ev_used; ++k) {
+    if (klass != PBT_K_NONE && h->ev_class[k] != klass) continue;
     PBT_HIP(h, hipEventSynchronize(h->ev_stop[k]));
     float ms = 0.f;
     PBT_HIP(h, hipEventElapsedTime(&ms, h->ev_start[k], h->ev_stop[k]));
     sum += ms;
+    ++n;
   }
   if (total_ms) *total_ms = sum;
-  if (launches) *launches = (int64_t)h->ev_used;
-  h->ev_used = 0;
+  if (launches) *launches = n;
   return PBT_OK;
+}
+
+pbt_status pbt_timing_read_class(pbt_handle* h, int32_t kernel_class, double* total_ms, int64_t* launches) {
+  if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  if (kernel_class < 0 || kernel_class >= PBT_K_COUNT) return fail(h, PBT_EINVAL, "unknown kernel class %d", kernel_class);
+  return sum_events(h, kernel_class, total_ms, launches);
+}
+
+pbt_status pbt_timing_read(pbt_handle* h, double* total_ms, int64_t* launches) {
+  if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  pbt_status st = sum_events(h, PBT_K_NONE, total_ms, launches);
+  if (st == PBT_OK) h->ev_used = 0;
+  return st;
 }
 
 pbt_status pbt_destroy(pbt_handle* h) {

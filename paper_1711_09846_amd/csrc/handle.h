@@ -88,12 +88,13 @@ struct pbt_handle {
   std::string err;
   pbt_prior priors[PBT_MAX_HYPER];  // for resample explore (pbt_set_priors / pbt_init_population)
   bool have_priors = false;
-  // optional event timing of one kernel class
-  int timed_class = PBT_K_NONE;
+  // optional event timing of kernel classes
+  uint32_t timed_mask = 0;  // bit k set: launches of class k are bracketed
   std::vector<hipEvent_t> ev_start, ev_stop;
+  std::vector<int> ev_class;  // class of every recorded pair
   size_t ev_used = 0;
-  int timed_stride = 1;   // every timed_stride-th launch of the class is recorded
-  size_t timed_seen = 0;  // launches of the class since timing was enabled
+  int timed_stride = 1;                    // every timed_stride-th launch of a class is recorded
+  size_t timed_seen[PBT_K_COUNT] = {};     // launches of each class since timing was enabled
   template <class T> T* st(size_t off) const { return reinterpret_cast<T*>(state + off); }
   template <class T> T* sc(size_t off) const { return reinterpret_cast<T*>(scratch + off); }
 };
@@ -113,12 +114,13 @@ pbt_status fail(pbt_handle* h, pbt_status code, const char* fmt, ...);
 // with an event pair on the same stream.
 #define PBT_LAUNCH(h, klass, s, call)                                                           \
   do {                                                                                          \
-    const bool timed_ = (h)->timed_class == (klass) && (h)->ev_used < (h)->ev_start.size() &&  \
-                        ((h)->timed_seen++ % (size_t)(h)->timed_stride) == 0;                   \
+    const bool timed_ = (((h)->timed_mask >> (klass)) & 1u) && (h)->ev_used < (h)->ev_start.size() && \
+                        ((h)->timed_seen[klass]++ % (size_t)(h)->timed_stride) == 0;            \
     if (timed_) PBT_HIP(h, hipEventRecord((h)->ev_start[(h)->ev_used], s));                     \
     PBT_HIP(h, call);                                                                           \
     if (timed_) {                                                                               \
       PBT_HIP(h, hipEventRecord((h)->ev_stop[(h)->ev_used], s));                                \
+      (h)->ev_class[(h)->ev_used] = (klass);                                                    \
       ++(h)->ev_used;                                                                           \
     }                                                                                           \
   } while (0)

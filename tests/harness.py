@@ -323,3 +323,88 @@ class TransformerPair:
         pop = [self.ref[i] for i in range(wl.P)]
         return opbt.exploit_explore(pop, rnd, self.seed, wl.n_trunc, wl.perturb[0], wl.perturb[1], wl.h_max, scores=scores,
                                     **exploit_variant(wl))
+
+
+# ---- helpers shared by the window tests: any pair, any oracle member (not only pair.ref) ----------------
+
+def gpu_arrays(pair, i, which):
+    """Member i's `which` array of the population store as float64 parameter arrays in the oracle's order."""
+    if isinstance(pair, TransformerPair):
+        return pair.gpu_arrays(i, which)
+    flat = pair.gpu.get(which, i).astype(np.float64)
+    lay, out = pair.gpu.layout, []
+    for l, (fi, fo) in enumerate(pair.gpu.layer_shapes):
+        out.append(flat[lay.w_off[l]:lay.w_off[l] + fi * fo].reshape(fi, fo).copy())
+        out.append(flat[lay.b_off[l]:lay.b_off[l] + fo].copy())
+    return out
+
+
+def sync_member(pair, m, i):
+    """Oracle member m takes over GPU member i's weights, optimiser state, update count, hyperparameters
+    (and return history): float32 values widen exactly."""
+    m.theta = gpu_arrays(pair, i, binding.ARR_W32)
+    for what, which in (("s0", binding.ARR_OPT0), ("s1", binding.ARR_OPT1)):
+        if what in m.opt:
+            m.opt[what] = gpu_arrays(pair, i, which)
+    m.t = int(pair.gpu.get(binding.ARR_T, i)[0])
+    m.h = pair.gpu.get(binding.ARR_HYPER, i).copy()
+    if isinstance(pair, A2CPair):
+        m.hist = [np.float32(v) for v in pair.gpu.history()[i]]
+
+
+def oracle_step(pair, m, i, s, spec=None):
+    """One `step` of oracle member m as population member i; returns the loss(es) as a float array."""
+    spec = spec or pair.spec
+    if isinstance(pair, TransformerPair):
+        return np.array([pair.ot.step(spec, m, i, s, pair.pool)])
+    if isinstance(pair, GanPair):
+        return np.array(pair.og.step(spec, m, i, s, pair.train_x))
+    if isinstance(pair, A2CPair):
+        return np.array([pair.oa.step(spec, m, i, s, pair.obs, pair.actions, pair.rewards)])
+    return np.array([oc.step(spec, m, i, s, pair.train_x, pair.train_y)])
+
+
+def oracle_eval(pair, m, i, spec=None):
+    spec = spec or pair.spec
+    if isinstance(pair, TransformerPair):
+        return float(pair.ot.evaluate(spec, m, pair.eval_seqs, chunk=pair.wl.batch))
+    if isinstance(pair, GanPair):
+        return float(pair.og.evaluate(spec, m, i, pair.eval_x))
+    if isinstance(pair, A2CPair):
+        return float(pair.oa.evaluate(spec, m))
+    return float(oc.evaluate(spec, m, pair.eval_x, pair.eval_y))
+
+
+def train_inputs(pair):
+    return pair.d_pool if hasattr(pair, "d_pool") else pair.d_train
+
+
+def eval_inputs(pair):
+    return [] if isinstance(pair, A2CPair) else pair.d_eval
+
+
+def exact_spec(pair):
+    """The pair's oracle specification without the bf16 rounding model: plain float64 everywhere."""
+    import copy
+    spec = copy.copy(pair.spec)
+    spec.q = onets.identity
+    return spec
+
+
+def array_distances(pair, got, ref, bias_floor=0.0):
+    """(per-array relative L2 distances, whole-vector relative L2 distance) between two lists of parameter
+    arrays.  The transformer's key biases are left out (the network does not depend on them: softmax removes
+    a constant added to all keys, so their gradient is rounding noise).  bias_floor: one-dimensional arrays
+    (biases, which start at or near zero) are compared at no smaller scale than an rms of bias_floor."""
+    d = pair.wl.d_model if isinstance(pair, TransformerPair) else 0
+    names = [n for n, _ in pair.spec.param_shapes()] if d else [""] * len(ref)
+    per, num, den = [], 0.0, 0.0
+    for name, g, r in zip(names, got, ref):
+        g, r = np.asarray(g, dtype=np.float64), np.asarray(r, dtype=np.float64)
+        if name.startswith("bqkv"):
+            g, r = np.delete(g, np.s_[d:2 * d]), np.delete(r, np.s_[d:2 * d])
+        floor = bias_floor * np.sqrt(r.size) if r.ndim == 1 else 0.0
+        per.append(np.linalg.norm(g - r) / max(np.linalg.norm(r), floor, 1e-30))
+        num += float(np.sum((g - r) ** 2))
+        den += float(np.sum(r ** 2))
+    return np.array(per), float(np.sqrt(num / max(den, 1e-300)))
