@@ -16,6 +16,8 @@ keeps that structure on pre-recorded trajectories:
                 -A_t log pi(a_t|s_t) + 0.5 (R_t - V(s_t))^2 - entropy_cost * H(pi(.|s_t)),
             minimised by one RMSProp update with the member's learning rate;
             the member's entropy cost is its second hyperparameter;
+            (`step_on_policy` generates the unroll from the member's current policy instead,
+            see a2c_env.py; the update is the same);
   eval      the mean of the member's last (up to) 10 unroll returns, where an
             unroll's return is the mean over its B trajectories of the sum of
             the T rewards.  The history travels with the weights on exploit.
@@ -93,16 +95,31 @@ def loss_and_grads(spec, m, obs, actions, rewards):
     return loss, grads
 
 
-def step(spec, m, i, s, pool_obs, pool_actions, pool_rewards):
-    idx = philox.bounded(philox.words(spec.seed, s, i, philox.DOMAIN_BATCH, np.arange(spec.batch))[..., 0], len(pool_obs))
-    loss, grads = loss_and_grads(spec, m, pool_obs[idx], pool_actions[idx], pool_rewards[idx])
+def update_on_batch(spec, m, obs, actions, rewards):
+    """One RMSProp update on a given unroll; pushes the unroll's return onto the member's history."""
+    loss, grads = loss_and_grads(spec, m, obs, actions, rewards)
     lr = m.h[spec.roles.index(ROLE_LR)]
     m.t += 1
     for j, g in enumerate([a for gr in grads for a in gr]):
         m.theta[j], m.opt["s0"][j] = optim.rmsprop(m.theta[j], g, m.opt["s0"][j], lr, spec.rho, spec.rms_eps)
     # float32 like the population store keeps it
-    m.hist = (m.hist + [np.float32(np.asarray(pool_rewards[idx], dtype=np.float64).sum(axis=1).mean())])[-HIST:]
+    m.hist = (m.hist + [np.float32(np.asarray(rewards, dtype=np.float64).sum(axis=1).mean())])[-HIST:]
     return loss
+
+
+def step(spec, m, i, s, pool_obs, pool_actions, pool_rewards):
+    """`step` on pre-recorded trajectories: B draws from the pool (Philox domain 1, one per trajectory)."""
+    idx = philox.bounded(philox.words(spec.seed, s, i, philox.DOMAIN_BATCH, np.arange(spec.batch))[..., 0], len(pool_obs))
+    return update_on_batch(spec, m, pool_obs[idx], pool_actions[idx], pool_rewards[idx])
+
+
+def step_on_policy(spec, env, m, i, s, batch=None):
+    """`step` on an unroll generated from the member's current policy (a2c_env.rollout), or on a given
+    batch = (obs, actions, rewards) that such a generator produced.  Returns (loss, batch)."""
+    from . import a2c_env
+    if batch is None:
+        batch = a2c_env.rollout(spec, env, params_of(m), i, s)[:3]
+    return update_on_batch(spec, m, *batch), batch
 
 
 def evaluate(spec, m):

@@ -184,6 +184,21 @@ def initial_gan_weights(wl, P, seed):
     return [(g[i], d[i]) for i in range(P)]
 
 
+def latent_system(wl):
+    """The linear-Gaussian latent system of the actor-critic workload, from the data seed:
+    A = 0.9 x random orthogonal [n_z][n_z], B ~ N(0, 0.3^2) [n_z][n_actions], C ~ N(0, 1) / 4 [d][n_z],
+    reward direction w ~ N(0, 1) [n_z]; float64 arrays.  (The same draws, in the same order, that
+    trajectory_pool starts with.)"""
+    rng = np.random.default_rng(wl.data_seed)
+    nz, d = wl.latent, wl.dims[0]
+    Q, _ = np.linalg.qr(rng.standard_normal((nz, nz)))
+    A = 0.9 * Q
+    Bm = rng.standard_normal((nz, wl.n_actions)) * 0.3
+    C = rng.standard_normal((d, nz)) / 4.0
+    w = rng.standard_normal(nz)
+    return A, Bm, C, w
+
+
 def trajectory_pool(wl):
     """Pre-recorded trajectories from a linear-Gaussian latent system with uniformly random actions:
     z' = A z + B e(a) + 0.1 xi (A = 0.9 x random orthogonal, B ~ N(0, 0.3^2)), observation = C z + N(0, I)
