@@ -89,7 +89,13 @@ enum {
   PBT_ARR_PARENT = 11,/* int32  [P]          member last copied from (initially self) */
   PBT_ARR_HIST = 12,  /* float  [P][12]      actor-critic: ring of the last 10 unroll returns, slot 10 = number of
                                              unrolls so far (int32 bits), slot 11 unused; travels with theta */
-  PBT_ARR_COUNT = 13
+  /* actor-critic: the unroll the last step was taken on (scratch; read-only): observations as the network saw
+     them, bf16 [P][batch * (unroll + 1)][dims[0]] (trajectory-major, unroll + 1 rows per trajectory), actions
+     int32 [P][batch * unroll], rewards float [P][batch * unroll] */
+  PBT_ARR_TRAJ_OBS = 13,
+  PBT_ARR_TRAJ_ACT = 14,
+  PBT_ARR_TRAJ_REW = 15,
+  PBT_ARR_COUNT = 16
 };
 
 typedef struct {
@@ -149,6 +155,10 @@ typedef struct {
   float resample_prob;
   int32_t keep_weights, keep_hypers;
   float ttest_alpha;                /* exploit_mode 2: significance level, 0 < alpha <= 1 */
+  /* PBT_WL_A2C only.  on_policy = 1: every step first generates its unroll on the device from the member's
+     current policy in a linear-Gaussian latent system of dimension latent_dim (see pbt_step), so that the
+     score depends on the member's weights as in Section 4.1.1; 0: trajectories are drawn from a recorded pool. */
+  int32_t on_policy, latent_dim;
   uint64_t seed;                    /* Philox key */
 } pbt_config;
 
@@ -209,7 +219,22 @@ pbt_status pbt_set_priors(pbt_handle* h, const pbt_prior* priors);
  * backward, optimiser update with lr / beta1 / weight decay read from h_i on
  * the device, t_i += 1.  Writes loss[P] (mean mini-batch loss before the last
  * update).  d_inputs for PBT_WL_CLASSIFIER: {train_x float[n_train][dims[0]],
- * train_y int32[n_train]}, device pointers in a HOST array of n_inputs = 2. */
+ * train_y int32[n_train]}, device pointers in a HOST array of n_inputs = 2.
+ * PBT_WL_A2C with on_policy = 0: {observations float[n_train][unroll + 1][dims[0]], actions
+ * int32[n_train][unroll], rewards float[n_train][unroll]}; `batch` trajectories are drawn per member
+ * (Philox domain 1).  With on_policy = 1 (Section 4.1.1: agents act with their current policy and are
+ * evaluated by their last 10 episodic returns): d_inputs = {A double[nz][nz], B double[nz][n_actions],
+ * C double[dims[0]][nz], w double[nz], noise double[3] = {observation, reward, transition scale}},
+ * nz = latent_dim; the step first generates `batch` trajectories per member,
+ *   z_0 ~ N(0, I); o_t = C z_t + noise[0] xi_t (rounded to float, then to bf16); a_t ~ softmax(policy
+ *   logits of the member's network on o_t); r_t = w.z_t + noise[1] nu_t (float);
+ *   z_{t+1} = A z_t + B[:, a_t] + noise[2] zeta_t,
+ * the latent and every sum in double.  Philox counters (step, member, 32 + k, e / 4): k = 0 z_0 (element
+ * e = r nz + j), 1 xi (e = (r (unroll + 1) + t) dims[0] + j), 3 nu (e = r unroll + t), 4 zeta
+ * (e = (r unroll + t) nz + j), normals by Box-Muller from word pairs (0,1), (2,3) of a counter (cosine for
+ * even e, sine for odd e, evaluated in double); k = 2: u = (word 0 + 0.5) / 2^32 of counter element
+ * r unroll + t.  a_t = the number of actions k with cdf_k <= u (at most n_actions - 1), cdf the running
+ * sum of the softmax probabilities, evaluated in double from the float logits. */
 pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, int64_t step_index, int32_t n_steps,
                     void* hip_stream);
 

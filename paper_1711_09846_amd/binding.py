@@ -16,10 +16,11 @@ LIB_PATH = os.path.join(_HERE, "libpbt.so")
 
 PBT_MAX_DIMS, PBT_MAX_HYPER, PBT_MAX_SEGMENTS = 16, 8, 96
 (ARR_W32, ARR_OPT0, ARR_OPT1, ARR_W16, ARR_GRAD, ARR_HYPER, ARR_SCORE, ARR_LOSS, ARR_T, ARR_ORDER, ARR_DONOR,
- ARR_PARENT, ARR_HIST) = range(13)
+ ARR_PARENT, ARR_HIST, ARR_TRAJ_OBS, ARR_TRAJ_ACT, ARR_TRAJ_REW) = range(16)
 _ARR_DTYPE = {ARR_W32: np.float32, ARR_OPT0: np.float32, ARR_OPT1: np.float32, ARR_W16: np.uint16,
               ARR_GRAD: np.float32, ARR_HYPER: np.float32, ARR_SCORE: np.float32, ARR_LOSS: np.float32,
-              ARR_T: np.int32, ARR_ORDER: np.int32, ARR_DONOR: np.int32, ARR_PARENT: np.int32, ARR_HIST: np.float32}
+              ARR_T: np.int32, ARR_ORDER: np.int32, ARR_DONOR: np.int32, ARR_PARENT: np.int32, ARR_HIST: np.float32,
+              ARR_TRAJ_OBS: np.uint16, ARR_TRAJ_ACT: np.int32, ARR_TRAJ_REW: np.float32}
 
 EXPORTS = ["pbt_query_sizes", "pbt_init", "pbt_step", "pbt_eval", "pbt_exploit_explore", "pbt_get_state",
            "pbt_set_state", "pbt_state_ptr", "pbt_destroy", "pbt_last_error", "pbt_batched_gemm_bf16",
@@ -40,7 +41,7 @@ class PbtConfig(C.Structure):
                 ("tf_heads", C.c_int32), ("tf_d_ff", C.c_int32), ("tf_seq", C.c_int32), ("n_train", C.c_int32),
                 ("n_eval", C.c_int32), ("eval_chunk", C.c_int32), ("fuse_optimizer", C.c_int32), ("exploit_mode", C.c_int32),
                 ("explore_mode", C.c_int32), ("resample_prob", C.c_float), ("keep_weights", C.c_int32), ("keep_hypers", C.c_int32),
-                ("ttest_alpha", C.c_float),
+                ("ttest_alpha", C.c_float), ("on_policy", C.c_int32), ("latent_dim", C.c_int32),
                 ("seed", C.c_uint64)]
 
 
@@ -141,6 +142,8 @@ def make_config(wl, seed, P=None, n_trunc=None, eval_chunk=0, fuse_optimizer=0):
     c.keep_weights = getattr(wl, "keep_weights", 0)
     c.keep_hypers = getattr(wl, "keep_hypers", 0)
     c.ttest_alpha = getattr(wl, "ttest_alpha", 0.0)
+    c.on_policy = getattr(wl, "on_policy", 0)
+    c.latent_dim = getattr(wl, "latent", 0) if wl.kind == 5 else 0
     c.seed = seed
     return c
 
@@ -288,6 +291,10 @@ class Population:
             return (P, self.cfg.n_hyper)
         if which == ARR_HIST:
             return (P, 12)
+        if which == ARR_TRAJ_OBS:
+            return (P, self.cfg.batch * (self.cfg.unroll + 1), self.cfg.dims[0])
+        if which in (ARR_TRAJ_ACT, ARR_TRAJ_REW):
+            return (P, self.cfg.batch * self.cfg.unroll)
         if which == ARR_LOSS and self.n_loss > 1:
             return (P, self.n_loss)
         return (P,)

@@ -181,10 +181,21 @@ pbt_status a2c_check_and_plan(const pbt_config* c, Plan* pl, Carver* w) {
   a.o_dout = w->take((size_t)P * R * 32 * 2);
   a.o_act = w->take((size_t)P * c->batch * c->unroll * 4);
   a.o_rew = w->take((size_t)P * c->batch * c->unroll * 4);
+  a.o_lat = a.o_gout = 0;
+  if (c->on_policy) {
+    if (c->latent_dim < 1 || c->latent_dim > 64) return fail(nullptr, PBT_EINVAL, "latent_dim outside 1..64");
+    if ((int64_t)c->batch * c->latent_dim * 8 > 32 * 1024) return fail(nullptr, PBT_EUNSUPPORTED, "batch x latent_dim above 4096");
+    if ((int64_t)R * c->dims[0] >= (1LL << 31)) return fail(nullptr, PBT_EUNSUPPORTED, "more than 2^31 observation elements per member");
+    a.o_lat = w->take((size_t)P * c->batch * c->latent_dim * 8);
+    for (int l = 1; l < L; ++l) a.o_ga[l] = w->take((size_t)P * c->batch * c->dims[l] * 2);
+    a.o_gout = w->take((size_t)P * c->batch * 32 * 4);
+  }
   return PBT_OK;
 }
 
-pbt_status a2c_step(pbt_handle* h, const float* obs, const int32_t* actions, const float* rewards, uint32_t step, hipStream_t s) {
+// Forward, loss, backward and update on the unroll that sits in the step's input buffers (observations in
+// the first activation buffer, actions and rewards in theirs).
+static pbt_status a2c_update(pbt_handle* h, hipStream_t s) {
   const pbt_config& c = h->cfg;
   const Plan& p = h->plan;
   const A2CPlan& a = p.a2c;
@@ -202,15 +213,6 @@ pbt_status a2c_step(pbt_handle* h, const float* obs, const int32_t* actions, con
   int32_t* act = h->sc<int32_t>(a.o_act);
   float* rew = h->sc<float>(a.o_rew);
   pbt_status st;
-  // a trajectory is one "row" of (T+1) * d observations; B of them are drawn per member
-  PBT_LAUNCH(h, PBT_K_FETCH, s, gather_rows(obs, c.n_train, (T + 1) * c.dims[0], P, B, (int64_t)R * c.dims[0], step, c.seed, A[0],
-                                            h->st<int32_t>(p.o_t), s));
-  {
-    const bool timed = false; (void)timed;
-    hipLaunchKernelGGL(a2c_fetch_aux_kernel, dim3(P), dim3(64), 0, s, actions, rewards, c.n_train, B, T, step, (uint32_t)c.seed,
-                       (uint32_t)(c.seed >> 32), act, rew, h->st<float>(p.o_hist));
-    PBT_HIP(h, hipGetLastError());
-  }
   if ((st = forward(h, net, L - 1, R, A, Z, nullptr, 0, s)) != PBT_OK) return st;
   PBT_LAUNCH(h, PBT_K_HEAD, s, head_fwd_loss(A[L - 1], (int64_t)R * Kh, W16 + p.lay.w_off[L - 1], S, W32 + p.lay.b_off[L - 1], S, nullptr,
                                              0, P, R, Kh, C, 0.f, -2, nullptr, out, 0, s));
@@ -232,6 +234,165 @@ pbt_status a2c_step(pbt_handle* h, const float* obs, const int32_t* actions, con
   if (fused) return optimizer_rest(h, oa, 0, L, L - 1, S, s);
   PBT_LAUNCH(h, PBT_K_OPTIMIZER, s, optimizer_step(oa, s));
   return PBT_OK;
+}
+
+pbt_status a2c_step(pbt_handle* h, const float* obs, const int32_t* actions, const float* rewards, uint32_t step, hipStream_t s) {
+  const pbt_config& c = h->cfg;
+  const Plan& p = h->plan;
+  const A2CPlan& a = p.a2c;
+  const int P = c.P, B = c.batch, T = c.unroll, R = a.rows;
+  // a trajectory is one "row" of (T+1) * d observations; B of them are drawn per member
+  PBT_LAUNCH(h, PBT_K_FETCH, s, gather_rows(obs, c.n_train, (T + 1) * c.dims[0], P, B, (int64_t)R * c.dims[0], step, c.seed,
+                                            h->sc<bf16_t>(a.o_a[0]), h->st<int32_t>(p.o_t), s));
+  hipLaunchKernelGGL(a2c_fetch_aux_kernel, dim3(P), dim3(64), 0, s, actions, rewards, c.n_train, B, T, step, (uint32_t)c.seed,
+                     (uint32_t)(c.seed >> 32), h->sc<int32_t>(a.o_act), h->sc<float>(a.o_rew), h->st<float>(p.o_hist));
+  PBT_HIP(h, hipGetLastError());
+  return a2c_update(h, s);
+}
+
+// ---- on-policy unrolls (Section 4.1.1: agents act with their current policy) -------------------------
+
+constexpr uint32_t DOMAIN_ENV = 32;
+
+// Four standard normals from one Philox counter: Box-Muller on the word pairs (0,1) and (2,3), in double.
+__device__ __forceinline__ void env_normal4(uint32_t step, uint32_t member, uint32_t domain, uint32_t counter, uint32_t k0,
+                                            uint32_t k1, double* v) {
+  const u32x4 w = philox4x32_10(step, member, domain, counter, k0, k1);
+  const double r1 = sqrt(-2.0 * log(philox_unit(w.x))), a1 = 6.283185307179586476925 * philox_unit(w.y);
+  const double r2 = sqrt(-2.0 * log(philox_unit(w.z))), a2 = 6.283185307179586476925 * philox_unit(w.w);
+  v[0] = r1 * cos(a1); v[1] = r1 * sin(a1); v[2] = r2 * cos(a2); v[3] = r2 * sin(a2);
+}
+__device__ __forceinline__ double env_normal(uint32_t step, uint32_t member, uint32_t domain, uint32_t e, uint32_t k0, uint32_t k1) {
+  double v[4];
+  env_normal4(step, member, domain, e >> 2, k0, k1, v);
+  return v[e & 3];
+}
+
+struct EnvArgs {
+  A2CEnv env;
+  int nz, n_act, d, B, T, rows;        // rows = B (T + 1) observation rows per member
+  uint32_t step, k0, k1;
+  double* z;                           // [P][B][nz]
+  const float* head_out;               // [P][B][32]: head outputs of the policy at time t - 1
+  int32_t* act; float* rew;            // [P][B][T]
+  bf16_t* obs;                         // [P][rows][d]
+  int32_t* t_count;
+};
+
+// One time step of the unroll for all trajectories of one member (one workgroup per member).
+// t > 0: every trajectory draws a_{t-1} from the policy's head outputs, receives r_{t-1} and moves to z_t.
+// t = 0: z_0 is drawn.  Then the observation o_t of every trajectory is written where the step (and the
+// policy's next forward pass) reads it.
+__global__ __launch_bounds__(256) void a2c_env_advance_kernel(EnvArgs a, int t) {
+  extern __shared__ double zs[];  // [B][nz]
+  const int i = blockIdx.x;
+  const int nz = a.nz, B = a.B, T = a.T;
+  for (int r = threadIdx.x; r < B; r += blockDim.x) {
+    double* zr = a.z + ((int64_t)i * B + r) * nz;
+    double zn[64];
+    if (t == 0) {
+      for (int k = 0; k < nz; ++k) zn[k] = env_normal(a.step, i, DOMAIN_ENV + 0, (uint32_t)(r * nz + k), a.k0, a.k1);
+    } else {
+      const int tt = t - 1;
+      const float* lg = a.head_out + ((int64_t)i * B + r) * 32;
+      double mx = -INFINITY;
+      for (int c = 0; c < a.n_act; ++c) mx = fmax(mx, (double)lg[c]);
+      double ex[32], se = 0.0;
+      for (int c = 0; c < a.n_act; ++c) { ex[c] = exp((double)lg[c] - mx); se += ex[c]; }
+      const double u = philox_unit(philox4x32_10(a.step, i, DOMAIN_ENV + 2, (uint32_t)(r * T + tt), a.k0, a.k1).x);
+      double cdf = 0.0;
+      int action = 0;
+      for (int c = 0; c < a.n_act; ++c) { cdf += ex[c] / se; action += cdf <= u ? 1 : 0; }
+      action = action < a.n_act - 1 ? action : a.n_act - 1;
+      double rw = 0.0;
+      for (int k = 0; k < nz; ++k) rw += a.env.w[k] * zr[k];
+      rw += a.env.noise[1] * env_normal(a.step, i, DOMAIN_ENV + 3, (uint32_t)(r * T + tt), a.k0, a.k1);
+      a.act[((int64_t)i * B + r) * T + tt] = action;
+      a.rew[((int64_t)i * B + r) * T + tt] = (float)rw;
+      for (int k = 0; k < nz; ++k) {
+        double acc = 0.0;
+        for (int j = 0; j < nz; ++j) acc += a.env.A[k * nz + j] * zr[j];
+        zn[k] = acc + a.env.B[k * a.n_act + action] + a.env.noise[2] * env_normal(a.step, i, DOMAIN_ENV + 4, (uint32_t)((r * T + tt) * nz + k), a.k0, a.k1);
+      }
+    }
+    for (int k = 0; k < nz; ++k) { zr[k] = zn[k]; zs[r * nz + k] = zn[k]; }
+  }
+  if (t == 0 && threadIdx.x == 0) a.t_count[i] += 1;
+  __syncthreads();
+  const int quads = a.d / 4;
+  for (int item = threadIdx.x; item < B * quads; item += blockDim.x) {
+    const int r = item / quads, j0 = (item - r * quads) * 4;
+    const int64_t row = (int64_t)r * (T + 1) + t;
+    double v[4];
+    env_normal4(a.step, i, DOMAIN_ENV + 1, (uint32_t)((row * a.d + j0) >> 2), a.k0, a.k1, v);
+    float o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      double acc = 0.0;
+      for (int k = 0; k < nz; ++k) acc += a.env.C[(j0 + e) * nz + k] * zs[r * nz + k];
+      o[e] = (float)(acc + a.env.noise[0] * v[e]);
+    }
+    *reinterpret_cast<uint2*>(a.obs + ((int64_t)i * a.rows + row) * a.d + j0) = make_uint2(f2bf_pair(o[0], o[1]), f2bf_pair(o[2], o[3]));
+  }
+}
+
+// Pushes the unroll's return (mean over trajectories of the summed rewards, in double, trajectories in order)
+// into the member's history ring.
+__global__ __launch_bounds__(64) void a2c_push_return_kernel(const float* __restrict__ rew, int B, int T, float* __restrict__ hist) {
+  const int i = blockIdx.x;
+  __shared__ double tsum[64];
+  double mean = 0.0;
+  for (int r0 = 0; r0 < B; r0 += 64) {
+    const int r = r0 + threadIdx.x;
+    double sacc = 0.0;
+    if (r < B)
+      for (int t = 0; t < T; ++t) sacc += (double)rew[((int64_t)i * B + r) * T + t];
+    tsum[threadIdx.x] = sacc;
+    __syncthreads();
+    if (threadIdx.x == 0)
+      for (int k = 0; k < 64 && r0 + k < B; ++k) mean += tsum[k];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    float* hrow = hist + (int64_t)i * HIST_PITCH;
+    const int n = __float_as_int(hrow[HIST_SLOTS]);
+    hrow[n % HIST_SLOTS] = (float)(mean / (double)B);
+    hrow[HIST_SLOTS] = __int_as_float(n + 1);
+  }
+}
+
+pbt_status a2c_step_on_policy(pbt_handle* h, const A2CEnv& env, uint32_t step, hipStream_t s) {
+  const pbt_config& c = h->cfg;
+  const Plan& p = h->plan;
+  const A2CPlan& a = p.a2c;
+  const int P = c.P, B = c.batch, T = c.unroll, L = c.n_layers, R = a.rows, d = c.dims[0];
+  const int Kh = c.dims[L - 1], C = c.dims[L];
+  const int64_t S = p.lay.stride;
+  const float* W32 = h->st<float>(p.o_w32);
+  const bf16_t* W16 = h->st<bf16_t>(p.o_w16);
+  bf16_t* obs = h->sc<bf16_t>(a.o_a[0]);
+  float* gout = h->sc<float>(a.o_gout);
+  EnvArgs ea{env, c.latent_dim, C - 1, d, B, T, R, step, (uint32_t)c.seed, (uint32_t)(c.seed >> 32), h->sc<double>(a.o_lat), gout,
+             h->sc<int32_t>(a.o_act), h->sc<float>(a.o_rew), obs, h->st<int32_t>(p.o_t)};
+  const size_t lds = (size_t)B * c.latent_dim * sizeof(double);
+  for (int t = 0; t <= T; ++t) {
+    hipLaunchKernelGGL(a2c_env_advance_kernel, dim3(P), dim3(256), lds, s, ea, t);
+    PBT_HIP(h, hipGetLastError());
+    if (t == T) break;
+    // the policy on the B observations of time t: rows t, t + (T+1), ... of the member's observation buffer
+    for (int l = 0; l < L - 1; ++l) {
+      const int K = c.dims[l], N = c.dims[l + 1];
+      const bf16_t* in = l == 0 ? obs + (int64_t)t * d : h->sc<bf16_t>(a.o_ga[l]);
+      GemmOperands o{in, l == 0 ? (int64_t)(T + 1) * d : (int64_t)K, l == 0 ? (int64_t)R * d : (int64_t)B * K, false,
+                     W16 + p.lay.w_off[l], N, S, false, B, N, K, P};
+      PBT_LAUNCH(h, PBT_K_FETCH, s, gemm_bias_act(o, W32 + p.lay.b_off[l], S, nullptr, h->sc<bf16_t>(a.o_ga[l + 1]), N, (int64_t)B * N, c.act, s));
+    }
+    PBT_LAUNCH(h, PBT_K_FETCH, s, head_fwd_loss(h->sc<bf16_t>(a.o_ga[L - 1]), (int64_t)B * Kh, W16 + p.lay.w_off[L - 1], S, W32 + p.lay.b_off[L - 1], S,
+                                                nullptr, 0, P, B, Kh, C, 0.f, -2, nullptr, gout, 0, s));
+  }
+  hipLaunchKernelGGL(a2c_push_return_kernel, dim3(P), dim3(64), 0, s, h->sc<float>(a.o_rew), B, T, h->st<float>(p.o_hist));
+  PBT_HIP(h, hipGetLastError());
+  return a2c_update(h, s);
 }
 
 pbt_status a2c_eval(pbt_handle* h, hipStream_t s) {

@@ -51,6 +51,8 @@ pbt_status check_config(const pbt_config* c, Plan* pl) {
   if (c->n_trunc < 0 || 2 * (int64_t)c->n_trunc > c->P) return fail(nullptr, PBT_EINVAL, "need 0 <= 2*n_trunc <= P (top and bottom sets must not overlap)");
   if (c->n_train < 1 || c->n_eval < 1) return fail(nullptr, PBT_EINVAL, "n_train and n_eval must be positive");
   if (c->exploit_mode < PBT_EXPLOIT_TRUNCATION || c->exploit_mode > PBT_EXPLOIT_TTEST) return fail(nullptr, PBT_EINVAL, "unknown exploit_mode %d", c->exploit_mode);
+  if (c->on_policy != 0 && c->on_policy != 1) return fail(nullptr, PBT_EINVAL, "on_policy is 0 or 1");
+  if (c->on_policy && !a2c) return fail(nullptr, PBT_EINVAL, "on_policy needs the actor-critic workload");
   if (c->exploit_mode == PBT_EXPLOIT_TTEST) {
     if (!a2c) return fail(nullptr, PBT_EINVAL, "t-test selection needs the score history of the actor-critic workload");
     if (!(c->ttest_alpha > 0.f && c->ttest_alpha <= 1.f)) return fail(nullptr, PBT_EINVAL, "ttest_alpha must be in (0, 1]");
@@ -259,6 +261,12 @@ pbt_status arr_info(pbt_handle* h, int which, ArrInfo* ai) {
     case PBT_ARR_HIST:
       if (c.workload != PBT_WL_A2C) return fail(h, PBT_EINVAL, "HIST exists only in the actor-critic workload");
       *ai = {p.o_hist, 4, 12, false}; return PBT_OK;
+    case PBT_ARR_TRAJ_OBS: case PBT_ARR_TRAJ_ACT: case PBT_ARR_TRAJ_REW:
+      if (c.workload != PBT_WL_A2C) return fail(h, PBT_EINVAL, "the unroll arrays exist only in the actor-critic workload");
+      if (which == PBT_ARR_TRAJ_OBS) *ai = {p.a2c.o_a[0], 2, (int64_t)p.a2c.rows * c.dims[0], true};
+      else if (which == PBT_ARR_TRAJ_ACT) *ai = {p.a2c.o_act, 4, (int64_t)c.batch * c.unroll, true};
+      else *ai = {p.a2c.o_rew, 4, (int64_t)c.batch * c.unroll, true};
+      return PBT_OK;
     default: return fail(h, PBT_EINVAL, "unknown array id %d", which);
   }
 }
@@ -504,9 +512,20 @@ pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs
                     void* hip_stream) {
   if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
   if (h->cfg.workload == PBT_WL_A2C) {
+    if (n_steps < 0 || step_index < 0 || step_index + n_steps > 0xffffffffLL) return fail(h, PBT_EINVAL, "step range outside 0..2^32-1");
+    if (h->cfg.on_policy) {
+      if (!d_inputs || n_inputs != 5 || !d_inputs[0] || !d_inputs[1] || !d_inputs[2] || !d_inputs[3] || !d_inputs[4])
+        return fail(h, PBT_EINVAL, "on-policy actor-critic step needs 5 inputs: A, B, C, w, noise scales (double arrays)");
+      const A2CEnv env{static_cast<const double*>(d_inputs[0]), static_cast<const double*>(d_inputs[1]), static_cast<const double*>(d_inputs[2]),
+                       static_cast<const double*>(d_inputs[3]), static_cast<const double*>(d_inputs[4])};
+      for (int k = 0; k < n_steps; ++k) {
+        pbt_status st = a2c_step_on_policy(h, env, (uint32_t)(step_index + k), static_cast<hipStream_t>(hip_stream));
+        if (st != PBT_OK) return st;
+      }
+      return PBT_OK;
+    }
     if (!d_inputs || n_inputs != 3 || !d_inputs[0] || !d_inputs[1] || !d_inputs[2])
       return fail(h, PBT_EINVAL, "actor-critic step needs 3 inputs: observations, actions, rewards");
-    if (n_steps < 0 || step_index < 0 || step_index + n_steps > 0xffffffffLL) return fail(h, PBT_EINVAL, "step range outside 0..2^32-1");
     for (int k = 0; k < n_steps; ++k) {
       pbt_status st = a2c_step(h, static_cast<const float*>(d_inputs[0]), static_cast<const int32_t*>(d_inputs[1]),
                                static_cast<const float*>(d_inputs[2]), (uint32_t)(step_index + k), static_cast<hipStream_t>(hip_stream));
@@ -666,7 +685,8 @@ pbt_status pbt_get_state(pbt_handle* h, int32_t which, int32_t member, void* h_d
 
 pbt_status pbt_set_state(pbt_handle* h, int32_t which, int32_t member, const void* h_src, size_t src_bytes,
                          void* hip_stream) {
-  if (which == PBT_ARR_GRAD || which == PBT_ARR_ORDER || which == PBT_ARR_DONOR || which == PBT_ARR_LOSS)
+  if (which == PBT_ARR_GRAD || which == PBT_ARR_ORDER || which == PBT_ARR_DONOR || which == PBT_ARR_LOSS ||
+      which == PBT_ARR_TRAJ_OBS || which == PBT_ARR_TRAJ_ACT || which == PBT_ARR_TRAJ_REW)
     return fail(h, PBT_EINVAL, "array %d is an output and cannot be set", which);
   return xfer(h, which, member, const_cast<void*>(h_src), src_bytes, hip_stream, false);
 }

@@ -687,6 +687,9 @@ inline int64_t tile_count(int M, int N, int batch, int bm, int bn) { return (int
 inline GemmTile choose_tile(int M, int N, int K, int batch) {
   constexpr int CUS = 256;
   // (three quarters of the compute units busy with 256x256 tiles still beat all of them on smaller ones)
+  // K = 512 stays with 128x128: timed alone, 256x256 tiles are 5-20 % faster there (4096 rows x 16 members,
+  // N = 512 ... 8192), but inside the transformer step, with the fused epilogues and whatever the previous kernel
+  // left in the caches, the same launches came out 9 % slower (forward class 206 -> 225 us, step +0.6 ms).
   if (K >= 1024 && M > 128 && N > 128 && tile_count(M, N, batch, 256, 256) >= CUS * 3 / 4) return TILE_256x256;
   if ((tile_count(M, N, batch, 128, 128) < 4 * CUS && N > 64) || (N <= 64 && N > 32)) return TILE_128x64;
   return TILE_128x128;

@@ -42,6 +42,9 @@ struct GanPlan {
 struct A2CPlan {
   int rows, col_ent;
   size_t o_a[PBT_MAX_DIMS], o_z[PBT_MAX_DIMS], o_dz[PBT_MAX_DIMS], o_out, o_dout, o_act, o_rew;
+  // on-policy generation: latent states (double [P][batch][latent_dim]), the policy's hidden activations and
+  // head outputs for one time step ([P][batch][width])
+  size_t o_lat, o_ga[PBT_MAX_DIMS], o_gout;
 };
 
 struct TfBlockOff { int64_t ln1g, ln1b, wqkv, bqkv, wo, bo, ln2g, ln2b, w1, b1, w2, b2; };
@@ -133,6 +136,8 @@ pbt_status gan_eval(pbt_handle* h, const float* eval_x, hipStream_t s);
 // a2c_host.hip: the actor-critic workload (Section 4.1.1)
 pbt_status a2c_check_and_plan(const pbt_config* c, Plan* pl, Carver* scratch);
 pbt_status a2c_step(pbt_handle* h, const float* obs, const int32_t* actions, const float* rewards, uint32_t step, hipStream_t s);
+struct A2CEnv { const double *A, *B, *C, *w, *noise; };   // the latent system, device arrays
+pbt_status a2c_step_on_policy(pbt_handle* h, const A2CEnv& env, uint32_t step, hipStream_t s);
 pbt_status a2c_eval(pbt_handle* h, hipStream_t s);
 
 // transformer_host.hip: the language-model workload (Section 4.2.1)

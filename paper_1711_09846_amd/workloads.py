@@ -77,6 +77,10 @@ A2C_MLP = Workload(
     h_max=[math.inf, math.inf], ready_interval=100, n_trunc=trunc_count(128, 20), total_steps=2000,
     opt_const=dict(rho=0.99, eps=1e-5), data_seed=1005, perturb=(0.8, 1.2))
 
+# The same agents acting with their current policy: every step generates its unroll on the device in the
+# latent system of latent_system() (the score then depends on the member's weights).
+A2C_MLP_ON_POLICY = A2C_MLP.replace(on_policy=1)
+
 # Decoder-only transformers (pre-LayerNorm blocks, learned positions, untied head) on synthetic token
 # sequences; Adam; learning rate, one dropout rate and the label smoothing per member; score = minus the
 # held-out perplexity.

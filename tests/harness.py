@@ -205,7 +205,13 @@ class A2CPair:
         import torch
         from oracle import a2c as oa
         self.oa, self.wl, self.seed = oa, wl, seed
-        self.obs, self.actions, self.rewards = workloads.trajectory_pool(wl)
+        self.on_policy = bool(getattr(wl, "on_policy", 0))
+        if self.on_policy:
+            from oracle import a2c_env
+            self.env_mod = a2c_env
+            self.env = a2c_env.Environment(*workloads.latent_system(wl))
+        else:
+            self.obs, self.actions, self.rewards = workloads.trajectory_pool(wl)
         self.cfg = binding.make_config(wl, seed, fuse_optimizer=fuse_optimizer)
         self.gpu = binding.Population(self.cfg)
         weights = workloads.initial_mlp_weights(wl.dims, wl.P, init_seed)
@@ -219,10 +225,25 @@ class A2CPair:
         self.ref_ids = list(range(wl.P)) if ref_members is None else list(ref_members)
         self.ref = {i: oa.new_member(self.spec, weights[i], H[i], i) for i in self.ref_ids}
         dev = self.gpu.device
-        self.d_pool = [torch.from_numpy(self.obs).to(dev), torch.from_numpy(self.actions).to(dev),
-                       torch.from_numpy(self.rewards).to(dev)]
+        if self.on_policy:
+            e = self.env
+            noise = np.array([e.obs_noise, e.reward_noise, e.trans_noise])
+            self.d_pool = [torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64)).to(dev) for a in (e.A, e.B, e.C, e.w, noise)]
+        else:
+            self.d_pool = [torch.from_numpy(self.obs).to(dev), torch.from_numpy(self.actions).to(dev),
+                           torch.from_numpy(self.rewards).to(dev)]
+
+    def gpu_unroll(self, i):
+        """The unroll member i's last step was taken on, as the GPU holds it: (obs float64 [B][T+1][d] of bf16
+        values, actions [B][T], rewards float32 [B][T])."""
+        wl = self.wl
+        obs = (self.gpu.get(binding.ARR_TRAJ_OBS, i).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        return (obs.reshape(wl.batch, wl.unroll + 1, wl.dims[0]), self.gpu.get(binding.ARR_TRAJ_ACT, i).reshape(wl.batch, wl.unroll),
+                self.gpu.get(binding.ARR_TRAJ_REW, i).reshape(wl.batch, wl.unroll))
 
     def step_ref(self, s):
+        if self.on_policy:      # the oracle takes its step on the unroll the GPU generated
+            return np.array([self.oa.step_on_policy(self.spec, self.env, self.ref[i], i, s, batch=self.gpu_unroll(i))[0] for i in self.ref_ids])
         return np.array([self.oa.step(self.spec, self.ref[i], i, s, self.obs, self.actions, self.rewards) for i in self.ref_ids])
 
     def eval_ref(self):
@@ -360,6 +381,8 @@ def oracle_step(pair, m, i, s, spec=None):
     if isinstance(pair, GanPair):
         return np.array(pair.og.step(spec, m, i, s, pair.train_x))
     if isinstance(pair, A2CPair):
+        if pair.on_policy:
+            return np.array([pair.oa.step_on_policy(spec, pair.env, m, i, s, batch=pair.gpu_unroll(i))[0]])
         return np.array([pair.oa.step(spec, m, i, s, pair.obs, pair.actions, pair.rewards)])
     return np.array([oc.step(spec, m, i, s, pair.train_x, pair.train_y)])
 

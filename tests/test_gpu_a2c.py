@@ -134,3 +134,89 @@ def test_a2c_ttest_selection_bit_exact(alpha):
             rnd += 1
     assert n_copy > 0
     print("t-test selection alpha %.2f: %d copies, %d of them from a member that was itself overwritten" % (alpha, n_copy, n_chain), flush=True)
+
+
+def test_a2c_on_policy_unrolls_against_the_oracle():
+    """Section 4.1.1: agents act with their current policy.  Every step the GPU generates the unroll; the oracle
+    (a) replays the latent system along the GPU's actions and must reproduce observations and rewards, (b) makes
+    its own choice at every transition from its own logits: it may differ from the GPU's only where the uniform
+    draw lies within 1e-3 of an edge of the cdf (float32 against float64 logits), and on fewer than 1 % of the
+    choices, (c) takes its step on the GPU's unroll and must stay within the bf16 tolerance, free-running."""
+    from oracle import nets
+    wl = _reduced().replace(on_policy=1)
+    pair = A2CPair(wl)
+    g, P = pair.gpu, wl.P
+    n_choices = n_differ = n_obs = n_obs_differ = 0
+    worst = dict(w=0.0, loss=0.0, reward=0.0, score=0.0)
+    rnd = 0
+    for s in range(16):
+        before = {i: pair.oa.params_of(pair.ref[i]) for i in range(P)}
+        before = {i: [(W.copy(), b.copy()) for W, b in before[i]] for i in range(P)}
+        g.step(pair.d_pool, s)
+        for i in range(P):
+            obs_g, act_g, rew_g = pair.gpu_unroll(i)
+            assert act_g.min() >= 0 and act_g.max() < wl.n_actions
+            obs_o, act_o, rew_o, margin = pair.env_mod.rollout(pair.spec, pair.env, before[i], i, s, forced_actions=act_g)
+            differ = act_o != act_g
+            assert np.all(margin[differ] < 1e-3), (s, i, margin[differ])
+            n_choices += act_g.size
+            n_differ += int(differ.sum())
+            obs_o16 = nets.round_bf16(obs_o.astype(np.float64))
+            off = obs_o16 != obs_g
+            assert np.all(np.abs(obs_o16 - obs_g)[off] <= 2.0 ** -7 * np.abs(obs_g)[off]), (s, i)     # one bf16 step at most
+            n_obs += obs_g.size
+            n_obs_differ += int(off.sum())
+            worst["reward"] = max(worst["reward"], float(np.max(np.abs(rew_o.astype(np.float64) - rew_g))))
+        loss_ref = pair.step_ref(s)
+        loss = g.get(binding.ARR_LOSS)
+        worst["loss"] = max(worst["loss"], float(np.max(np.abs(loss - loss_ref) / np.maximum(np.abs(loss_ref), FLOOR))))
+        for i in range(P):
+            worst["w"] = max(worst["w"], pair.member_errors(i, binding.ARR_W32, "theta")[0])
+        assert worst["w"] <= TOL_BF16 and worst["loss"] <= TOL_BF16 and worst["reward"] <= 1e-5, (s, worst)
+        _hist_equal(pair, range(P))
+        if (s + 1) % 4 == 0:
+            sc = _eval(g)
+            worst["score"] = max(worst["score"], float(np.max(np.abs(sc - pair.eval_ref()))))
+            assert worst["score"] <= 1e-5 and len(set(sc.tolist())) == P       # every member earned its own score
+            g.exploit_explore(rnd)
+            order, donor = pair.exploit_ref(rnd, sc)
+            assert list(g.get(binding.ARR_ORDER)) == order and np.array_equal(g.get(binding.ARR_DONOR), donor)
+            assert g.get(binding.ARR_HYPER).tobytes() == np.stack([pair.ref[i].h for i in range(P)]).tobytes()
+            rnd += 1
+    assert n_differ <= 0.01 * n_choices and n_obs_differ <= 1e-3 * n_obs, (n_differ, n_choices, n_obs_differ, n_obs)
+    print("a2c on-policy: %d of %d choices differ (all next to a cdf edge), %d of %d observations round the other way;"
+          % (n_differ, n_choices, n_obs_differ, n_obs), {k: float("%.3g" % v) for k, v in worst.items()}, flush=True)
+
+
+def test_a2c_on_policy_full_size_steps():
+    """P = 128 at the full shape, a few on-policy steps: sampled members' unrolls replayed by the oracle, their
+    steps within the tolerance, and scores that differ between members."""
+    from oracle import nets
+    wl = workloads.A2C_MLP_ON_POLICY
+    sample = [3, 40, 77, 120]
+    pair = A2CPair(wl, ref_members=sample)
+    g = pair.gpu
+    worst = dict(w=0.0, loss=0.0, reward=0.0)
+    n_choices = n_differ = 0
+    for s in range(5):
+        before = {i: [(W.copy(), b.copy()) for W, b in pair.oa.params_of(pair.ref[i])] for i in sample}
+        g.step(pair.d_pool, s)
+        for i in sample:
+            obs_g, act_g, rew_g = pair.gpu_unroll(i)
+            obs_o, act_o, rew_o, margin = pair.env_mod.rollout(pair.spec, pair.env, before[i], i, s, forced_actions=act_g)
+            differ = act_o != act_g
+            assert np.all(margin[differ] < 1e-3)
+            n_choices += act_g.size
+            n_differ += int(differ.sum())
+            assert np.mean(nets.round_bf16(obs_o.astype(np.float64)) != obs_g) <= 1e-3
+            worst["reward"] = max(worst["reward"], float(np.max(np.abs(rew_o.astype(np.float64) - rew_g))))
+        loss_ref = pair.step_ref(s)
+        loss = g.get(binding.ARR_LOSS)[sample]
+        worst["loss"] = max(worst["loss"], float(np.max(np.abs(loss - loss_ref) / np.maximum(np.abs(loss_ref), FLOOR))))
+        for i in sample:
+            worst["w"] = max(worst["w"], pair.member_errors(i, binding.ARR_W32, "theta")[0])
+        assert worst["w"] <= TOL_BF16 and worst["loss"] <= TOL_BF16 and worst["reward"] <= 1e-5, (s, worst)
+        _hist_equal(pair, sample)
+    sc = _eval(g)
+    assert len(set(sc.tolist())) > 100 and n_differ <= 0.01 * n_choices
+    print("a2c on-policy full size:", {k: float("%.3g" % v) for k, v in worst.items()}, "choices differing:", n_differ, "of", n_choices, flush=True)

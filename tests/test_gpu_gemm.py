@@ -13,7 +13,7 @@ def _bf16_round(x):
 
 @pytest.mark.parametrize("M,N,K,batch", [(128, 128, 64, 2), (200, 136, 72, 3), (40, 264, 1024, 2), (1, 8, 8, 1),
                                          (300, 130, 100, 2), (300, 130, 128, 2), (672, 264, 512, 3), (512, 512, 1056, 64),
-                                         (256, 768, 1024, 86)])
+                                         (256, 768, 1024, 86), (512, 512, 600, 48)])
 @pytest.mark.parametrize("a_m_contig", [0, 1])
 @pytest.mark.parametrize("b_k_contig", [0, 1])
 @pytest.mark.parametrize("out_bf16", [False, True])
