@@ -126,3 +126,124 @@ def test_bf16_storage_perturbs_slightly():
     lb, gb = gan.g_loss_and_grads(_spec(True), b, z)
     assert 0 < abs(la - lb) < 3e-2 * abs(la)
     assert np.linalg.norm(ga[0][0] - gb[0][0]) < 5e-2 * np.linalg.norm(ga[0][0])
+
+
+# ---- WGAN-GP (Section 4.3.1: the paper's objective, 5 critic updates per generator update) -----------
+
+def _wspec(K=2, bf16=False):
+    return gan.GanSpec([3, 6, 5], [5, 7, 4, 1], batch=4, seed=9, bf16_storage=bf16, objective="wgan_gp", n_critic=K)
+
+
+def test_gradient_penalty_of_a_linear_critic_closed_form():
+    """D(x) = x.w + b: the input gradient is w for every row, penalty = gp_weight (|w| - 1)^2 and
+    d penalty / d w = 2 gp_weight (|w| - 1) w / |w|, whatever the rows are."""
+    spec = gan.GanSpec([2, 3], [3, 1], batch=4, seed=1, objective="wgan_gp")
+    w = np.array([[0.6], [-1.2], [2.0]])
+    D = [(w, np.array([0.3]))]
+    x = np.random.default_rng(0).standard_normal((5, 3))
+    out, g, _, _ = gan.critic_input_gradient(spec, D, x)
+    assert np.allclose(g, np.tile(w.T, (5, 1))) and np.allclose(out, x @ w + 0.3)
+    nw = math.sqrt(0.36 + 1.44 + 4.0)
+    pen, grads = gan.gradient_penalty_and_grads(spec, D, x)
+    assert abs(pen - 10.0 * (nw - 1.0) ** 2) < 1e-12
+    assert np.allclose(grads[0][0], 2 * 10.0 * (nw - 1.0) * w / nw) and np.all(grads[0][1] == 0.0)
+
+
+def test_critic_input_gradient_and_penalty_gradient_fd():
+    spec = _wspec()
+    rng = np.random.default_rng(2)
+    m = _member(spec, rng)
+    D = gan.d_params(spec, m)
+    x = rng.standard_normal((4, 5))
+    out, g, _, _ = gan.critic_input_gradient(spec, D, x)
+    f = lambda xx: nets.mlp_forward(D, xx, spec.d_hidden)[0].ravel()
+    for r in range(4):
+        for k in range(5):
+            e = np.zeros_like(x)
+            e[r, k] = 1e-6
+            assert abs((f(x + e)[r] - f(x - e)[r]) / 2e-6 - g[r, k]) < 1e-6
+    pen, grads = gan.gradient_penalty_and_grads(spec, D, x)
+    # the penalty written out from its definition, with the input gradient by the network's own backward pass
+    def penalty():
+        gg = gan.critic_input_gradient(spec, gan.d_params(spec, m), x)[1]
+        return 10.0 * np.mean([(math.sqrt(float(row @ row)) - 1.0) ** 2 for row in gg])
+    assert abs(pen - penalty()) < 1e-12
+    n_g = 2 * spec.n_g
+    _fd_check(penalty, m.theta[n_g:], grads, None, tol=2e-6)
+    assert all(np.all(gb == 0.0) for _, gb in grads)                 # the input gradient does not depend on the biases
+
+
+def test_wgan_gp_losses_and_gradients_fd():
+    spec = _wspec()
+    rng = np.random.default_rng(3)
+    m = _member(spec, rng)
+    real, z, eps = rng.standard_normal((4, 5)), rng.standard_normal((4, 3)), rng.random(4)
+    loss_d, gd = gan.critic_loss_and_grads(spec, m, real, z, eps)
+    n_g = 2 * spec.n_g
+    _fd_check(lambda: gan.critic_loss_and_grads(spec, m, real, z, eps)[0], m.theta[n_g:], gd, None, tol=2e-6)
+    loss_g, gg = gan.wgan_generator_loss_and_grads(spec, m, z)
+    _fd_check(lambda: gan.wgan_generator_loss_and_grads(spec, m, z)[0], m.theta[:n_g], gg, None)
+    # definitions written out
+    fake = nets.mlp_forward(gan.g_params(spec, m), z, spec.g_hidden, spec.g_out)[0]
+    D = lambda x: nets.mlp_forward(gan.d_params(spec, m), x, spec.d_hidden)[0].ravel()
+    xhat = eps[:, None] * real + (1 - eps[:, None]) * fake
+    pen = gan.gradient_penalty_and_grads(spec, gan.d_params(spec, m), xhat)[0]
+    assert abs(loss_d - (D(fake).mean() - D(real).mean() + pen)) < 1e-12
+    assert abs(loss_g + D(fake).mean()) < 1e-12
+    # eps = 1 puts the penalty on the real rows, eps = 0 on the generated ones
+    assert abs(gan.critic_loss_and_grads(spec, m, real, z, np.ones(4))[0]
+               - (D(fake).mean() - D(real).mean() + gan.gradient_penalty_and_grads(spec, gan.d_params(spec, m), real)[0])) < 1e-12
+
+
+def test_wgan_gp_step_schedule_counters_and_update_counts():
+    """K critic updates then one generator update; critic update k of step s uses batch counters k B + r,
+    latent sub-stream 3 + k and eps from domain 14; the critic's Adam has had K (t-1) + k + 1 updates."""
+    K = 3
+    spec = _wspec(K=K)
+    rng = np.random.default_rng(4)
+    train_x = rng.standard_normal((50, 5))
+    m = _member(spec, rng)
+    twin = _member(spec, np.random.default_rng(4 + 0))         # rebuilt below from m's arrays
+    twin.theta = [a.copy() for a in m.theta]
+    twin.h = m.h.copy()
+    B, n_g = spec.batch, 2 * spec.n_g
+    # eps and rows against single Philox calls
+    e = gan.gp_eps(spec.seed, 5, 2, 1, B)
+    for r in range(B):
+        w = philox.philox4x32_10([5, 2, gan.DOMAIN_GP_EPS, 1 * B + r], [spec.seed, 0])
+        assert e[r] == (int(w[0]) + 0.5) / 2 ** 32
+    # two steps by the oracle; the same two steps assembled by hand from the pieces, critic state through torch's Adam
+    d_t = [torch.tensor(a.copy(), dtype=torch.float64, requires_grad=True) for a in twin.theta[n_g:]]
+    opt_d = torch.optim.Adam(d_t, lr=float(twin.h[1]), betas=(spec.beta1, spec.beta2), eps=spec.eps)
+    g_t = [torch.tensor(a.copy(), dtype=torch.float64, requires_grad=True) for a in twin.theta[:n_g]]
+    opt_g = torch.optim.Adam(g_t, lr=float(twin.h[0]), betas=(spec.beta1, spec.beta2), eps=spec.eps)
+    for s in range(2):
+        ld, lg = gan.step(spec, m, 0, s, train_x)
+        for k in range(K):
+            rows = [int((int(philox.philox4x32_10([s, 0, philox.DOMAIN_BATCH, k * B + r], [spec.seed, 0])[0]) * 50) >> 32) for r in range(B)]
+            loss_d, gd = gan.critic_loss_and_grads(spec, twin, train_x[rows], gan.latents(spec.seed, s, 0, 3 + k, B, 3), gan.gp_eps(spec.seed, s, 0, k, B))
+            for p, g in zip(d_t, [a for gr in gd for a in gr]):
+                p.grad = torch.tensor(g)
+            opt_d.step()
+            twin.theta[n_g:] = [p.detach().numpy().copy() for p in d_t]
+        loss_g, gg = gan.wgan_generator_loss_and_grads(spec, twin, gan.latents(spec.seed, s, 0, 1, B, 3))
+        for p, g in zip(g_t, [a for gr in gg for a in gr]):
+            p.grad = torch.tensor(g)
+        opt_g.step()
+        twin.theta[:n_g] = [p.detach().numpy().copy() for p in g_t]
+        assert abs(ld - loss_d) < 1e-9 and abs(lg - loss_g) < 1e-9
+    assert m.t == 2
+    for a, b in zip(m.theta, twin.theta):
+        assert np.allclose(a, b, rtol=1e-9, atol=1e-12)
+
+
+def test_wgan_gp_bf16_model_is_a_small_perturbation():
+    spec, spec16 = _wspec(), _wspec(bf16=True)
+    rng = np.random.default_rng(5)
+    m = _member(spec, rng)
+    real, z, eps = rng.standard_normal((4, 5)), rng.standard_normal((4, 3)), rng.random(4)
+    la, ga = gan.critic_loss_and_grads(spec, m, real, z, eps)
+    lb, gb = gan.critic_loss_and_grads(spec16, m, real, z, eps)
+    assert 0 < abs(la - lb) < 5e-2 * max(1.0, abs(la))
+    for (wa, _), (wb, _) in zip(ga, gb):
+        assert np.linalg.norm(wa - wb) < 0.1 * np.linalg.norm(wa)

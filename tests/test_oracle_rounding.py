@@ -232,3 +232,36 @@ def test_actor_critic_rounding_points_in_order():
         loss, grads = a2c.loss_and_grads(spec, m, obs, actions, rewards)
         return np.concatenate([[loss]] + [a.ravel() for gr in grads for a in gr])
     _every_point_is_live(run, len(want) - 1, sign_only=[2])
+
+
+def test_wgan_gp_rounding_points_in_order():
+    B, zd = 4, 3
+    spec = gan.GanSpec([zd, 5, 6], [6, 7, 1], B, seed=1, bf16_storage=True, objective="wgan_gp", n_critic=2)
+    rng = np.random.default_rng(2)
+    g = [(rng.standard_normal((a, b)), rng.standard_normal(b)) for a, b in ((zd, 5), (5, 6))]
+    dn = [(rng.standard_normal((a, b)), rng.standard_normal(b)) for a, b in ((6, 7), (7, 1))]
+    m = gan.new_member(spec, g, dn, np.array([1e-3, 1e-3], dtype=np.float32), 0)
+    real, z, eps = rng.standard_normal((B, 6)), rng.standard_normal((B, zd)), rng.random(B)
+    rec = _Recorder()
+    spec.q = rec
+    gan.critic_loss_and_grads(spec, m, real, z, eps)
+    want = [(B, zd), (zd, 5), (B, 5), (B, 5), (5, 6), (B, 6),                   # generator forward
+            (B, 6), (B, 6),                                                      # real rows and generated rows as handed on
+            (2 * B, 6), (6, 7), (2 * B, 7), (2 * B, 7), (7, 1),                  # critic on real + generated rows
+            (2 * B, 1), (7, 1), (2 * B, 7), (6, 7),                              # its backward pass (Wasserstein terms)
+            (B, 6), (6, 7), (B, 7), (B, 7), (7, 1),                              # critic on the interpolated rows
+            (B, 1), (7, 1), (B, 7), (6, 7),                                      # input-gradient pass from d out = 1
+            (B, 6), (6, 7), (B, 7)]                                              # d penalty / d g, and its way back through W_0
+    assert rec.shapes == want
+
+    def run(q):
+        spec.q = q
+        loss, grads = gan.critic_loss_and_grads(spec, m, real, z, eps)
+        return np.concatenate([[loss]] + [a.ravel() for gr in grads for a in gr])
+    # The critic's forward pass on the interpolated rows (17-21) enters the penalty only through the LeakyReLU
+    # slopes, i.e. through signs; 2, 10 are ReLU / LeakyReLU pre-activations, 5 is kept for the generator's own
+    # backward pass, 6-8 round values that are rounded again (or are already bf16), 13 and 22 are +-1/B and 1,
+    # 16 feeds the unused gradient with respect to the critic's input.  Every other point must change the result.
+    base = run(_Recorder())
+    live = [k for k in range(len(want)) if not np.array_equal(run(_Recorder(skip=k)), base)]
+    assert set(live) >= {0, 1, 3, 4, 9, 11, 12, 14, 15, 23, 24, 25, 26, 27, 28}, live
