@@ -238,6 +238,21 @@ pbt_status pbt_set_priors(pbt_handle* h, const pbt_prior* priors);
 pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, int64_t step_index, int32_t n_steps,
                     void* hip_stream);
 
+/* For callers that cannot allocate device memory or hold a working buffer per handle (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): pbt_step with its working
+ * memory (the d_scratch of pbt_init: gradients, activations, per-row losses) taken from an array of
+ * PBT_STATIC_SCRATCH_BYTES bytes that lives inside the library, one copy per GPU, held until the process
+ * ends.  Same arguments, same kernels and bit-identical results as pbt_step; the population store stays
+ * in the caller's d_state.  Calls no hipMalloc / hipFree and nothing that allocates.  PBT_ENOMEM when the
+ * handle's configuration needs more working memory than the array holds (pbt_query_sizes reports the
+ * need).  Every call on a GPU, from any handle, shares that GPU's array: it keeps the previous call's
+ * contents (the call clears the part that must start at zero, with a fill kernel), and calls that overlap
+ * in time on one GPU race.  PBT_ARR_GRAD and the other scratch-backed arrays of the handle (which live in
+ * d_scratch) are not written. */
+#define PBT_STATIC_SCRATCH_BYTES ((size_t)8 << 20)
+pbt_status pbt_step_static(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, int64_t step_index,
+                           int32_t n_steps, void* hip_stream);
+
 /* Section 3, Eq. 1: p_i <- eval(theta_i) for every member; writes score[P].
  * PBT_WL_CLASSIFIER: minus the mean cross-entropy over the held-out set,
  * d_inputs = {eval_x float[n_eval][dims[0]], eval_y int32[n_eval]}.

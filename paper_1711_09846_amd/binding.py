@@ -25,7 +25,8 @@ _ARR_DTYPE = {ARR_W32: np.float32, ARR_OPT0: np.float32, ARR_OPT1: np.float32, A
 EXPORTS = ["pbt_query_sizes", "pbt_init", "pbt_step", "pbt_eval", "pbt_exploit_explore", "pbt_get_state",
            "pbt_set_state", "pbt_state_ptr", "pbt_destroy", "pbt_last_error", "pbt_batched_gemm_bf16",
            "pbt_timing_enable", "pbt_timing_stride", "pbt_timing_read", "pbt_init_population", "pbt_set_priors",
-           "pbt_timing_enable_classes", "pbt_timing_read_class"]
+           "pbt_step_static", "pbt_timing_enable_classes", "pbt_timing_read_class"]
+STATIC_SCRATCH_BYTES = 8 << 20
 (K_NONE, K_FETCH, K_GEMM_FWD, K_HEAD, K_GEMM_WGRAD, K_GEMM_DGRAD, K_BIAS_GRAD, K_OPTIMIZER, K_RANK, K_COPY,
  K_FUSED_STEP) = range(-1, 10)
 
@@ -75,6 +76,7 @@ def lib():
         L.pbt_query_sizes.argtypes = [C.POINTER(PbtConfig), C.POINTER(sz), C.POINTER(sz), C.POINTER(PbtLayout)]
         L.pbt_init.argtypes = [C.POINTER(PbtConfig), vp, sz, vp, sz, vp, C.POINTER(vp)]
         L.pbt_step.argtypes = [vp, C.POINTER(vp), i32, i64, i32, vp]
+        L.pbt_step_static.argtypes = [vp, C.POINTER(vp), i32, i64, i32, vp]
         L.pbt_eval.argtypes = [vp, C.POINTER(vp), i32, vp]
         L.pbt_exploit_explore.argtypes = [vp, i64, vp, vp]
         L.pbt_get_state.argtypes = [vp, i32, i32, vp, sz, vp]
@@ -230,6 +232,10 @@ class Population:
 
     def step(self, inputs, step_index, n_steps=1):
         self._check(lib().pbt_step(self._h, self._ptrs(inputs), len(inputs), step_index, n_steps, self._stream()))
+
+    def step_static(self, inputs, step_index, n_steps=1):
+        """pbt_step with the library's static working memory (no buffer of the caller's is used as scratch)."""
+        self._check(lib().pbt_step_static(self._h, self._ptrs(inputs), len(inputs), step_index, n_steps, self._stream()))
 
     def eval(self, inputs=()):
         ptrs = self._ptrs(inputs) if len(inputs) else None

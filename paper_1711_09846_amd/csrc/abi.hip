@@ -15,6 +15,30 @@ using namespace pbt;
 namespace {
 thread_local std::string g_last_error = "";
 
+// Working memory of pbt_step_static: one array per GPU inside the library's own image, so that the call
+// needs no buffer from an allocator.  In host code the array's name is only a handle for the symbol
+// lookup below; kernels are given the looked-up device address, as they are given a caller's buffer.
+constexpr size_t STATIC_SCRATCH_BYTES = PBT_STATIC_SCRATCH_BYTES;
+__device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+char* g_static_scratch[MAX_DEVICES] = {};   // device address of `scratch` on each GPU, resolved once per GPU
+
+// Device address of the current GPU's copy of the array (looked up on first use on that GPU).
+hipError_t static_scratch_ptr(char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  if (!g_static_scratch[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_static_scratch[dev] = static_cast<char*>(p);
+  }
+  *out = g_static_scratch[dev];
+  return hipSuccess;
+}
 }
 
 namespace pbt {
@@ -426,6 +450,10 @@ pbt_status pbt_init(const pbt_config* cfg, void* d_state, size_t state_bytes, vo
     delete h;
     return fail(nullptr, PBT_EDEVICE, "initialising the population store failed: %s", hipGetErrorString(e));
   }
+  // set-up is the place for the one symbol lookup pbt_step_static needs on this GPU (a failure here only
+  // surfaces if that entry point is used)
+  char* unused = nullptr;
+  (void)static_scratch_ptr(&unused);
   *out = h;
   return PBT_OK;
 }
@@ -572,6 +600,28 @@ pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs
     if (st != PBT_OK) return st;
   }
   return PBT_OK;
+}
+
+pbt_status pbt_step_static(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, int64_t step_index, int32_t n_steps,
+                           void* hip_stream) {
+  if (!h) return fail(nullptr, PBT_EINVAL, "handle is NULL");
+  if (h->plan.scratch_bytes > STATIC_SCRATCH_BYTES)
+    return fail(h, PBT_ENOMEM, "pbt_step_static: this configuration needs %zu bytes of working memory, the library's static array holds %zu; use pbt_step",
+                h->plan.scratch_bytes, (size_t)STATIC_SCRATCH_BYTES);
+  char* ptr = nullptr;
+  hipError_t e = static_scratch_ptr(&ptr);
+  if (e != hipSuccess) return fail(h, PBT_EDEVICE, "pbt_step_static: looking up the static working memory failed: %s", hipGetErrorString(e));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  char* const callers = h->scratch;
+  h->scratch = ptr;
+  // the array keeps what the last call (of any handle) left: the gradient buffer must start at zero, because
+  // its padding elements are never written and the optimiser reads them (a fill kernel, which a stream
+  // capture records faithfully)
+  e = fill_u32(h->sc<uint32_t>(h->plan.o_grad), 0u, (int64_t)h->cfg.P * h->plan.lay.stride, s);
+  pbt_status st = e == hipSuccess ? pbt_step(h, d_inputs, n_inputs, step_index, n_steps, hip_stream)
+                                  : fail(h, PBT_EDEVICE, "pbt_step_static: clearing the gradient buffer failed: %s", hipGetErrorString(e));
+  h->scratch = callers;
+  return st;
 }
 
 pbt_status pbt_eval(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, void* hip_stream) {
