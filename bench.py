@@ -32,6 +32,18 @@ TARGET = {"mfma": 0.5, "hbm": 0.7}   # the fractions aimed at for the GEMMs and 
 SUB_STEPS = {1: (1000, 100), 2: (200, 20), 3: (200, 20), 4: (10, 2), 5: (200, 20)}
 
 
+def _workload(key, variant):
+    """Workload 5 acts on-policy (unrolls generated on the device from each member's current policy); variant "pool"
+    is the same agents on pre-recorded trajectories.  Workload 3 is the logistic GAN; variant "wgan_gp" is the
+    paper's own step (5 critic updates on the WGAN-GP objective per generator update)."""
+    from paper_1711_09846_amd import workloads
+    if key == 5:
+        return workloads.A2C_MLP if variant == "pool" else workloads.A2C_MLP_ON_POLICY
+    if key == 3 and variant == "wgan_gp":
+        return workloads.GAN_MLP_WGAN_GP
+    return workloads.WORKLOADS[key]
+
+
 def _oracle_setup(key, wl, seed):
     """(members, step function) of the oracle for one workload; inputs from the seeded generators."""
     import numpy as np
@@ -51,7 +63,9 @@ def _oracle_setup(key, wl, seed):
     if key == 3:
         from oracle import gan as o
         tx, _ = workloads.gan_data(wl)
-        spec = o.GanSpec(wl.dims, wl.dims2, wl.batch, seed, roles=wl.roles, beta1=oc["beta1"], beta2=oc["beta2"], eps=oc["eps"], bf16_storage=True)
+        spec = o.GanSpec(wl.dims, wl.dims2, wl.batch, seed, roles=wl.roles, beta1=oc["beta1"], beta2=oc["beta2"], eps=oc["eps"], bf16_storage=True,
+                         objective=getattr(wl, "objective", "logistic"), n_critic=getattr(wl, "n_critic", 1),
+                         gp_weight=float(np.float32(getattr(wl, "gp_weight", 10.0))))
         weights = workloads.initial_gan_weights(wl, wl.P, 5)
         pop = [o.new_member(spec, weights[i][0], weights[i][1], H[i], i) for i in range(wl.P)]
         return pop, lambda m, i, s: o.step(spec, m, i, s, tx)
@@ -64,11 +78,17 @@ def _oracle_setup(key, wl, seed):
         pop = [o.new_member(spec, weights[i], H[i], i) for i in range(2)]
         return pop, lambda m, i, s: o.step(spec, m, i, s, pool)
     from oracle import a2c as o
-    obs, act, rew = workloads.trajectory_pool(wl)
+    if getattr(wl, "on_policy", 0):
+        from oracle import a2c_env
+        env = a2c_env.Environment(*workloads.latent_system(wl))
+    else:
+        obs, act, rew = workloads.trajectory_pool(wl)
     spec = o.A2CSpec(wl.dims[:-1], wl.n_actions, wl.batch, wl.unroll, seed, roles=wl.roles, gamma=float(np.float32(wl.gamma)),
                      value_cost=float(np.float32(wl.value_cost)), rho=oc["rho"], rms_eps=oc["eps"], hidden_act=wl.act, bf16_storage=True)
     weights = workloads.initial_mlp_weights(wl.dims, wl.P, 5)
     pop = [o.new_member(spec, weights[i], H[i], i) for i in range(wl.P)]
+    if getattr(wl, "on_policy", 0):
+        return pop, lambda m, i, s: o.step_on_policy(spec, env, m, i, s)
     return pop, lambda m, i, s: o.step(spec, m, i, s, obs, act, rew)
 
 
@@ -117,8 +137,12 @@ def _setup_gpu(key, wl, seed, fused):
         pop.set(binding.ARR_W32, np.stack([binding.pack_segments(pop.layout, a) for a in weights]))
         pop.set(binding.ARR_HYPER, H)
         return pop, [to(pool)], [to(held_out)]
-    obs, act, rew = workloads.trajectory_pool(wl)
     pop.set_members(workloads.initial_mlp_weights(wl.dims, wl.P, 5), H)
+    if getattr(wl, "on_policy", 0):
+        A, Bm, Cm, w = workloads.latent_system(wl)
+        noise = np.array([1.0, 0.1, 0.1])      # observation, reward and transition noise scales of the latent system
+        return pop, [to(np.ascontiguousarray(a, dtype=np.float64)) for a in (A, Bm, Cm, w, noise)], []
+    obs, act, rew = workloads.trajectory_pool(wl)
     return pop, [to(obs), to(act), to(rew)], []
 
 
@@ -153,18 +177,20 @@ def _work_per_step(key, wl, n, fused):
             out["gemm_wgrad"] = ("mfma", flops, len(mats))
             out["optimizer"] = ("hbm", 30.0 * n * P, 1)
     elif key == 3:
-        # Adam, two launches per step (discriminator's, then generator's parameters): 30 B per parameter in total
-        out["optimizer"] = ("hbm", 30.0 * n * P, 2)
+        # Adam, one launch per network update (discriminator's, then generator's parameters): 30 B per parameter
+        n_d = sum(a * b + b for a, b in zip(wl.dims2[:-1], wl.dims2[1:]))
+        k = getattr(wl, "n_critic", 1)
+        out["optimizer"] = ("hbm", 30.0 * (n + (k - 1) * n_d) * P, 1 + k)
     else:
         # RMSProp: theta, g and one state array read, theta, state and the bf16 shadow written: 22 B per parameter
         out["optimizer"] = ("hbm", 22.0 * n * P, 1)
     return out
 
 
-def run_workload(key, steps, warmup, fused, baseline_budget_s):
+def run_workload(key, steps, warmup, fused, baseline_budget_s, variant=None):
     import torch
     from paper_1711_09846_amd import binding, workloads
-    wl = workloads.WORKLOADS[key]
+    wl = _workload(key, variant)
     seed = workloads.POPULATION_SEED
     pop, d_train, d_eval = _setup_gpu(key, wl, seed, fused)
     K = {"gemm_fwd": binding.K_GEMM_FWD, "gemm_wgrad": binding.K_GEMM_WGRAD, "gemm_dgrad": binding.K_GEMM_DGRAD,
@@ -249,7 +275,7 @@ def run_workload(key, steps, warmup, fused, baseline_budget_s):
         "dtype": "bf16" if wl.dtype == workloads.DTYPE_BF16 else "f32", "data": "synthetic",
         "step_only": {"value": wl.P / (ms_step * 1e-3), "ms_per_step": ms_step},
         "eval_ms": dt_eval * 1e3, "exploit_explore_ms": dt_exploit * 1e3,
-        "config": {"workload": wl.name, "P": wl.P,
+        "config": {"workload": wl.name + (" (%s)" % variant if variant else ""), "P": wl.P,
                    "dims": wl.dims or {"blocks": wl.n_blocks, "d_model": wl.d_model, "heads": wl.heads, "d_ff": wl.d_ff, "seq": wl.seq, "vocab": wl.vocab},
                    "batch": wl.batch, "optimizer": {0: "sgd_momentum", 1: "adam", 2: "rmsprop"}[wl.optimizer],
                    "fused_optimizer": bool(fused), "steps_per_launch": chunk, "ready_interval": wl.ready_interval, "n_trunc": wl.n_trunc, "eval_rows": wl.n_eval,
@@ -293,6 +319,9 @@ def main():
             subs.append(run_workload(key, k_steps, k_warm, fused(key), 0 if args.no_cpu_baseline else 5.0))
         top_copy = {k: v for k, v in out.items()}
         subs.insert(3, top_copy)
+        # the same networks under the other step definitions that are built
+        subs.append(run_workload(3, 100, 10, 0, 0, variant="wgan_gp"))
+        subs.append(run_workload(5, 200, 20, 0, 0, variant="pool"))
         out["workloads"] = subs
     print(json.dumps(out))
 

@@ -159,6 +159,15 @@ typedef struct {
      current policy in a linear-Gaussian latent system of dimension latent_dim (see pbt_step), so that the
      score depends on the member's weights as in Section 4.1.1; 0: trajectories are drawn from a recorded pool. */
   int32_t on_policy, latent_dim;
+  /* PBT_WL_GAN only.  gan_objective 0: non-saturating logistic GAN, one discriminator and one generator update per
+     step.  1: the paper's own step (Section 4.3.1): n_critic updates of the discriminator, then one of the
+     generator, on the WGAN-GP objective L_D = mean D(G(z)) - mean D(x) + gp_weight mean (|grad D(xhat)| - 1)^2,
+     xhat = eps x + (1 - eps) G(z), L_G = -mean D(G(z')).  Critic update k of a step draws its rows from Philox
+     counters (step, member, 1, k batch + r), its latents from sub-stream 3 + k, eps_r = (word 0 + 0.5) / 2^32 of
+     counter (step, member, 14, k batch + r); its Adam bias correction counts n_critic (t - 1) + k + 1 updates.
+     loss[i] = {L_D of the last critic update, L_G}. */
+  int32_t gan_objective, n_critic;
+  float gp_weight;
   uint64_t seed;                    /* Philox key */
 } pbt_config;
 
@@ -247,8 +256,7 @@ pbt_status pbt_step(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs
  * handle's configuration needs more working memory than the array holds (pbt_query_sizes reports the
  * need).  Every call on a GPU, from any handle, shares that GPU's array: it keeps the previous call's
  * contents (the call clears the part that must start at zero, with a fill kernel), and calls that overlap
- * in time on one GPU race.  PBT_ARR_GRAD and the other scratch-backed arrays of the handle (which live in
- * d_scratch) are not written. */
+ * in time on one GPU race.  PBT_ARR_GRAD of the handle (which lives in d_scratch) is not written. */
 #define PBT_STATIC_SCRATCH_BYTES ((size_t)8 << 20)
 pbt_status pbt_step_static(pbt_handle* h, const void* const* d_inputs, int32_t n_inputs, int64_t step_index,
                            int32_t n_steps, void* hip_stream);

@@ -43,6 +43,7 @@ class PbtConfig(C.Structure):
                 ("n_eval", C.c_int32), ("eval_chunk", C.c_int32), ("fuse_optimizer", C.c_int32), ("exploit_mode", C.c_int32),
                 ("explore_mode", C.c_int32), ("resample_prob", C.c_float), ("keep_weights", C.c_int32), ("keep_hypers", C.c_int32),
                 ("ttest_alpha", C.c_float), ("on_policy", C.c_int32), ("latent_dim", C.c_int32),
+                ("gan_objective", C.c_int32), ("n_critic", C.c_int32), ("gp_weight", C.c_float),
                 ("seed", C.c_uint64)]
 
 
@@ -146,6 +147,9 @@ def make_config(wl, seed, P=None, n_trunc=None, eval_chunk=0, fuse_optimizer=0):
     c.ttest_alpha = getattr(wl, "ttest_alpha", 0.0)
     c.on_policy = getattr(wl, "on_policy", 0)
     c.latent_dim = getattr(wl, "latent", 0) if wl.kind == 5 else 0
+    c.gan_objective = 1 if getattr(wl, "objective", "logistic") == "wgan_gp" else 0
+    c.n_critic = getattr(wl, "n_critic", 1)
+    c.gp_weight = getattr(wl, "gp_weight", 10.0)
     c.seed = seed
     return c
 

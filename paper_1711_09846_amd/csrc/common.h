@@ -19,6 +19,19 @@ __device__ __forceinline__ uint32_t f2bf_pair(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+// double -> bf16 with a single round-to-nearest-even: first to float with round-to-odd (truncate
+// toward zero, then set the last bit if anything was lost), which the final rounding cannot mistake.
+__device__ __forceinline__ bf16_t d2bf(double v) {
+  float f = (float)v;
+  const double back = (double)f;
+  if (back != v) {
+    uint32_t b = __float_as_uint(f);
+    if (fabs(back) > fabs(v)) b -= 1u;  // step toward zero (f is finite and non-zero here)
+    f = __uint_as_float(b | 1u);
+  }
+  return f2bf(f);
+}
+
 
 enum { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2, ACT_LEAKY_RELU = 3, ACT_TANH = 4 };
 

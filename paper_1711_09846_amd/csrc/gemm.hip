@@ -18,7 +18,7 @@ static hipError_t run(const GemmOperands& o, const E& e, hipStream_t s) {
     if (!o.colsum && nt_lds_applies(g, o.a_m_contig, o.b_k_contig)) return launch_gemm_nt_lds(g, e, s);
   }
   return launch_gemm_bf16<E>(o.A, o.lda, o.sa, o.a_m_contig, o.B, o.ldb, o.sb, o.b_k_contig, o.M, o.N, o.K, o.batch, e, s, o.inner,
-                             o.sa_in, o.sb_in, o.colsum, o.colsum_stride);
+                             o.sa_in, o.sb_in, o.colsum, o.colsum_stride, o.colsum_k);
 }
 
 hipError_t gemm_store_f32(const GemmOperands& o, float* C, int64_t ldc, int64_t sc, hipStream_t s) {
@@ -43,7 +43,7 @@ hipError_t gemm_dgrad_act(const GemmOperands& o, const bf16_t* Zprev, bf16_t* dZ
 }
 
 hipError_t gemm_wgrad_optimizer(const GemmOperands& o, const OptArgs& a, int64_t off, int64_t ldc, hipStream_t s) {
-  const OptHyper hy{a.H, a.t, a.n_hyper, a.col_lr, a.col_beta1, a.col_wd, a.c0, a.c1, a.c2, a.c3};
+  const OptHyper hy{a.H, a.t, a.n_hyper, a.col_lr, a.col_beta1, a.col_wd, a.c0, a.c1, a.c2, a.c3, a.t_mul, a.t_add};
   if (a.optimizer == OPT_SGD_MOMENTUM) return run(o, EpiOptimizer<OPT_SGD_MOMENTUM>{a.W32, a.S0, a.S1, a.W16, a.stride, off, ldc, hy, {}}, s);
   if (a.optimizer == OPT_ADAM) return run(o, EpiOptimizer<OPT_ADAM>{a.W32, a.S0, a.S1, a.W16, a.stride, off, ldc, hy, {}}, s);
   return run(o, EpiOptimizer<OPT_RMSPROP>{a.W32, a.S0, a.S1, a.W16, a.stride, off, ldc, hy, {}}, s);

@@ -44,6 +44,7 @@ struct GemmArgs {
   // contraction, whose B operand is dZ); null = not wanted
   float* colsum = nullptr;
   int64_t colsum_stride = 0;
+  int colsum_k = 0;   // the column sums run over k < colsum_k (the launcher sets K when the caller gives no limit)
 };
 
 // LDS row pitch in elements for a slab width BK: +8 keeps 16-byte alignment and skews the banks
@@ -295,16 +296,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
       }
     };
     // column sums of the B slab in LDS (rows of Bs are columns n; the slot permutation only reorders k)
-    auto colsum_slab = [&](const bf16_t* Bs) {
-      if constexpr (Epilogue::COLSUM) if (want_colsum && (int)threadIdx.x < BN) {
+    auto colsum_slab = [&](const bf16_t* Bs, int k0) {
+      if constexpr (Epilogue::COLSUM) if (want_colsum && (int)threadIdx.x < BN && k0 < g.colsum_k) {
+        const bool whole = k0 + GEMM_BK <= g.colsum_k;   // (uniform: only the slab that straddles the limit masks)
 #pragma unroll
         for (int ks = 0; ks < GEMM_BK; ks += 8) {
           const uint4 v = *reinterpret_cast<const uint4*>(Bs + lds_offset<GEMM_BK>((int)threadIdx.x, ks));
           const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            csum += __uint_as_float(w[q] << 16);
-            csum += __uint_as_float(w[q] & 0xffff0000u);
+            const float lo = __uint_as_float(w[q] << 16), hi = __uint_as_float(w[q] & 0xffff0000u);
+            csum += whole || k0 + ks + 2 * q < g.colsum_k ? lo : 0.f;
+            csum += whole || k0 + ks + 2 * q + 1 < g.colsum_k ? hi : 0.f;
           }
         }
       }
@@ -325,7 +328,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
           if (k0 + 2 * GEMM_BK < g.K) fetch_slab(k0 + 2 * GEMM_BK);
         }
         multiply_slab(smem + buf * SLAB, smem + buf * SLAB + BM * GEMM_PITCH);
-        colsum_slab(smem + buf * SLAB + BM * GEMM_PITCH);
+        colsum_slab(smem + buf * SLAB + BM * GEMM_PITCH, k0);
         __syncthreads();
       }
     } else {
@@ -337,7 +340,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
         __syncthreads();
         if (k0 + GEMM_BK < g.K) fetch_slab(k0 + GEMM_BK);
         multiply_slab(smem, smem + BM * GEMM_PITCH);
-        colsum_slab(smem + BM * GEMM_PITCH);
+        colsum_slab(smem + BM * GEMM_PITCH, k0);
       }
     }
   };
@@ -765,14 +768,14 @@ template <class Epilogue>
 hipError_t launch_gemm_bf16(const bf16_t* A, int64_t lda, int64_t sa, bool a_m_contig, const bf16_t* B, int64_t ldb,
                             int64_t sb, bool b_k_contig, int M, int N, int K, int batch, const Epilogue& epi,
                             hipStream_t stream, int inner = 1, int64_t sa_in = 0, int64_t sb_in = 0, float* colsum = nullptr,
-                            int64_t colsum_stride = 0) {
+                            int64_t colsum_stride = 0, int colsum_k = -1) {
   GemmArgs g;
   g.A = A; g.lda = lda; g.sa = sa;
   g.B = B; g.ldb = ldb; g.sb = sb;
   g.M = M; g.N = N; g.K = K; g.batch = batch;
   g.tiles_m = g.tiles_n = 0;
   g.inner = inner < 1 ? 1 : inner; g.sa_in = sa_in; g.sb_in = sb_in;
-  g.colsum = colsum; g.colsum_stride = colsum_stride;
+  g.colsum = colsum; g.colsum_stride = colsum_stride; g.colsum_k = colsum_k < 0 ? K : colsum_k;
   switch (choose_tile(M, N, K, batch)) {
     case TILE_256x256: return launch_gemm_tile<256, 256, 64, 2, 4, true, Epilogue>(g, a_m_contig, b_k_contig, epi, stream);
     case TILE_128x64: return launch_gemm_tile<128, 64, 64, 2, 2, false, Epilogue>(g, a_m_contig, b_k_contig, epi, stream);

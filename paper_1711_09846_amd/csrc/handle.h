@@ -36,6 +36,7 @@ struct GanPlan {
   size_t o_zin, o_ga[PBT_MAX_DIMS], o_gz[PBT_MAX_DIMS], o_gdz[PBT_MAX_DIMS];
   size_t o_dx, o_da[PBT_MAX_DIMS], o_dz[PBT_MAX_DIMS], o_ddz[PBT_MAX_DIMS];
   size_t o_dlogits, o_rowloss;
+  size_t o_hout, o_gin;   // WGAN-GP: the critic's outputs (float [P][rows][32]) and its input gradient on the interpolated rows (float [P][batch][width])
   size_t o_ez, o_ea[2], o_ex, o_ey, o_nx, o_ny, o_pxx, o_pyy, o_pxy;
 };
 

@@ -18,6 +18,7 @@ struct GemmOperands {
   int64_t sa_in = 0, sb_in = 0;
   float* colsum = nullptr;       // optional by-product: colsum[b * colsum_stride + n] = sum_k B[k][n]
   int64_t colsum_stride = 0;
+  int colsum_k = -1;             // the column sums run over k < colsum_k only (-1: over all of K)
 };
 hipError_t gemm_store_f32(const GemmOperands& o, float* C, int64_t ldc, int64_t sc, hipStream_t s);
 hipError_t gemm_store_bf16(const GemmOperands& o, bf16_t* C, int64_t ldc, int64_t sc, hipStream_t s);
@@ -93,6 +94,8 @@ struct OptArgs {
   // further ranges of the flat vector handled by the same launch (the biases between fused matrices)
   int n_extra = 0;
   int64_t xbegin[3] = {0, 0, 0}, xcount[3] = {0, 0, 0};
+  // Adam's bias correction counts t[i] * t_mul + t_add updates (a network updated several times per step)
+  int t_mul = 1, t_add = 0;
 };
 constexpr int OPT_MAX_RANGES = 4;
 hipError_t optimizer_step(const OptArgs& a, hipStream_t s);
@@ -106,9 +109,10 @@ hipError_t gemm_wgrad_optimizer(const GemmOperands& o, const OptArgs& a, int64_t
 hipError_t latent_normal(bf16_t* out, int P, int rows, int d, uint32_t c0, int substream, uint64_t seed, hipStream_t s);
 // out[batch][rows] = sum_k X[batch][rows][d]^2 (float)
 hipError_t row_sqnorm(const bf16_t* X, int batch, int rows, int d, float* out, hipStream_t s);
-// gathers rows of a float data set into bf16 X[P][ld_rows][d] rows 0..B-1 (Philox domain 1), t[i] += 1
+// gathers rows of a float data set into bf16 X[P][ld_rows][d] rows 0..B-1 (Philox domain 1, counter element
+// counter0 + r for row r); t[i] += 1 when bump_t
 hipError_t gather_rows(const float* train_x, int n_train, int d, int P, int B, int64_t member_stride, uint32_t step,
-                       uint64_t seed, bf16_t* X16, int32_t* t, hipStream_t s);
+                       uint64_t seed, bf16_t* X16, int32_t* t, hipStream_t s, uint32_t counter0 = 0, bool bump_t = true);
 // score[i] = -( sxx[i] + syy[0] - 2 sxy[i] ) * inv_n2 where each s is the sum of `tiles` partials
 hipError_t mmd_combine(const float* pxx, int txx, const float* pyy, int tyy, const float* pxy, int txy, int P, float inv_n2,
                        float* score, hipStream_t s);

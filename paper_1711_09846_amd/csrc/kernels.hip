@@ -215,7 +215,7 @@ constexpr int OPT_VEC_PER_THREAD = 1;
 template <int OPT>
 __global__ __launch_bounds__(256) void optimizer_kernel(OptArgs a) {
   const int i = blockIdx.y;
-  const OptHyper hy{a.H, a.t, a.n_hyper, a.col_lr, a.col_beta1, a.col_wd, a.c0, a.c1, a.c2, a.c3};
+  const OptHyper hy{a.H, a.t, a.n_hyper, a.col_lr, a.col_beta1, a.col_wd, a.c0, a.c1, a.c2, a.c3, a.t_mul, a.t_add};
   const OptScalars sc = opt_scalars<OPT>(hy, i);
 #pragma unroll
   for (int u = 0; u < OPT_VEC_PER_THREAD; ++u) {
@@ -296,9 +296,9 @@ hipError_t latent_normal(bf16_t* out, int P, int rows, int d, uint32_t c0, int s
 
 __global__ __launch_bounds__(256) void gather_rows_kernel(const float* __restrict__ train_x, int n_train, int d,
                                                           int64_t member_stride, uint32_t step, uint32_t k0, uint32_t k1,
-                                                          bf16_t* __restrict__ X16, int32_t* __restrict__ t) {
+                                                          bf16_t* __restrict__ X16, int32_t* __restrict__ t, uint32_t counter0) {
   const int r = blockIdx.x, i = blockIdx.y;
-  const uint32_t x = philox4x32_10(step, (uint32_t)i, DOMAIN_BATCH, (uint32_t)r, k0, k1).x;
+  const uint32_t x = philox4x32_10(step, (uint32_t)i, DOMAIN_BATCH, counter0 + (uint32_t)r, k0, k1).x;
   const float* __restrict__ row = train_x + (int64_t)philox_bounded(x, (uint32_t)n_train) * d;
   bf16_t* __restrict__ o = X16 + (int64_t)i * member_stride + (int64_t)r * d;
   if ((d & 3) == 0) {  // rows are 16-byte aligned: four floats in, four bf16 out per access
@@ -312,13 +312,13 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const float* __restric
   } else {
     for (int c = threadIdx.x; c < d; c += 256) o[c] = f2bf(row[c]);
   }
-  if (threadIdx.x == 0 && r == 0) t[i] += 1;
+  if (t != nullptr && threadIdx.x == 0 && r == 0) t[i] += 1;
 }
 hipError_t gather_rows(const float* train_x, int n_train, int d, int P, int B, int64_t member_stride, uint32_t step,
-                       uint64_t seed, bf16_t* X16, int32_t* t, hipStream_t s) {
+                       uint64_t seed, bf16_t* X16, int32_t* t, hipStream_t s, uint32_t counter0, bool bump_t) {
   if ((d & 3) == 0 && (member_stride & 3)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(gather_rows_kernel, dim3(B, P), dim3(256), 0, s, train_x, n_train, d, member_stride, step,
-                     (uint32_t)seed, (uint32_t)(seed >> 32), X16, t);
+                     (uint32_t)seed, (uint32_t)(seed >> 32), X16, bump_t ? t : nullptr, counter0);
   return hipGetLastError();
 }
 

@@ -18,6 +18,7 @@ struct OptHyper {  // where the member's hyperparameters and constants come from
   const float* H; const int32_t* t; int n_hyper;
   int col_lr, col_beta1, col_wd;  // column of H with that role, or -1
   float c0, c1, c2, c3;           // SGD {mu}; Adam {beta1, beta2, eps, wd}; RMSProp {rho, eps}
+  int t_mul = 1, t_add = 0;       // updates counted by the bias correction: t[member] * t_mul + t_add
 };
 
 struct OptScalars { float lr, b1, wd, inv_bc1, inv_bc2; };
@@ -31,7 +32,7 @@ __device__ __forceinline__ OptScalars opt_scalars(const OptHyper& a, int member)
   if (OPT == OPT_ADAM) {
     if (a.col_beta1 >= 0) s.b1 = h[a.col_beta1];
     if (a.col_wd >= 0) s.wd = h[a.col_wd];
-    const float tt = (float)a.t[member];
+    const float tt = (float)(a.t[member] * a.t_mul + a.t_add);
     s.inv_bc1 = 1.f / (1.f - powf(s.b1, tt));
     s.inv_bc2 = 1.f / (1.f - powf(a.c1, tt));
   }

@@ -31,19 +31,6 @@ __device__ __forceinline__ DropRate drop_rate(const float* H, int n_hyper, int c
   return r;
 }
 
-// double -> bf16 with a single round-to-nearest-even: first to float with round-to-odd (truncate
-// toward zero, then set the last bit if anything was lost), which the final rounding cannot mistake.
-__device__ __forceinline__ bf16_t d2bf(double v) {
-  float f = (float)v;
-  const double back = (double)f;
-  if (back != v) {
-    uint32_t b = __float_as_uint(f);
-    if (fabs(back) > fabs(v)) b -= 1u;  // step toward zero (f is finite and non-zero here)
-    f = __uint_as_float(b | 1u);
-  }
-  return f2bf(f);
-}
-
 // keep factors (0 or scale) of the four elements 4*blk .. 4*blk+3 of a site
 __device__ __forceinline__ void drop_factors4(const DropArgs& d, const DropRate& r, int member, int site, uint32_t blk, float* f) {
   if (r.thr == 0u) { f[0] = f[1] = f[2] = f[3] = r.scale; return; }

@@ -67,6 +67,10 @@ GAN_MLP = Workload(
     opt_const=dict(beta1=0.5, beta2=0.999, eps=1e-8), data_seed=1003, perturb=(0.8, 1.2),
     n_modes=16, rank=32)
 
+# The same pairs trained as in the paper's GAN experiment (Section 4.3.1): 5 critic updates per generator update
+# on the WGAN-GP objective, perturb factors 2.0 / 0.5.
+GAN_MLP_WGAN_GP = GAN_MLP.replace(objective="wgan_gp", n_critic=5, gp_weight=10.0, perturb=(0.5, 2.0))
+
 # Actor-critic MLP agents on pre-recorded synthetic trajectories: torso 512-256-256 (ReLU), one head with 18
 # policy logits + 1 value; RMSProp; learning rate and entropy cost per member; 32 trajectories of 20
 # transitions per step; score = mean of the last 10 unroll returns.

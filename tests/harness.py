@@ -144,7 +144,8 @@ class GanPair:
         oc_ = {k: float(np.float32(v)) for k, v in wl.opt_const.items()}
         self.spec = og.GanSpec(wl.dims, wl.dims2, wl.batch, seed, roles=wl.roles, g_hidden=wl.act, g_out=wl.act_out,
                                d_hidden=wl.act2, beta1=oc_["beta1"], beta2=oc_["beta2"], eps=oc_["eps"],
-                               bf16_storage=wl.dtype == workloads.DTYPE_BF16)
+                               bf16_storage=wl.dtype == workloads.DTYPE_BF16, objective=getattr(wl, "objective", "logistic"),
+                               n_critic=getattr(wl, "n_critic", 1), gp_weight=float(np.float32(getattr(wl, "gp_weight", 10.0))))
         self.ref_ids = list(range(wl.P)) if ref_members is None else list(ref_members)
         self.ref = {i: og.new_member(self.spec, weights[i][0], weights[i][1], H[i], i) for i in self.ref_ids}
         dev = self.gpu.device
