@@ -184,7 +184,7 @@ pbt_status a2c_check_and_plan(const pbt_config* c, Plan* pl, Carver* w) {
   a.o_lat = a.o_gout = 0;
   if (c->on_policy) {
     if (c->latent_dim < 1 || c->latent_dim > 64) return fail(nullptr, PBT_EINVAL, "latent_dim outside 1..64");
-    if ((int64_t)c->batch * c->latent_dim * 8 > 32 * 1024) return fail(nullptr, PBT_EUNSUPPORTED, "batch x latent_dim above 4096");
+    if ((int64_t)c->batch * (c->latent_dim * 8 + 4) > 48 * 1024) return fail(nullptr, PBT_EUNSUPPORTED, "batch x latent_dim too large for the transition kernel's LDS");
     if ((int64_t)R * c->dims[0] >= (1LL << 31)) return fail(nullptr, PBT_EUNSUPPORTED, "more than 2^31 observation elements per member");
     a.o_lat = w->take((size_t)P * c->batch * c->latent_dim * 8);
     for (int l = 1; l < L; ++l) a.o_ga[l] = w->take((size_t)P * c->batch * c->dims[l] * 2);
@@ -258,9 +258,12 @@ constexpr uint32_t DOMAIN_ENV = 32;
 __device__ __forceinline__ void env_normal4(uint32_t step, uint32_t member, uint32_t domain, uint32_t counter, uint32_t k0,
                                             uint32_t k1, double* v) {
   const u32x4 w = philox4x32_10(step, member, domain, counter, k0, k1);
-  const double r1 = sqrt(-2.0 * log(philox_unit(w.x))), a1 = 6.283185307179586476925 * philox_unit(w.y);
-  const double r2 = sqrt(-2.0 * log(philox_unit(w.z))), a2 = 6.283185307179586476925 * philox_unit(w.w);
-  v[0] = r1 * cos(a1); v[1] = r1 * sin(a1); v[2] = r2 * cos(a2); v[3] = r2 * sin(a2);
+  // (cos and sin of 2 pi u through sincospi(2 u): no reduction of a large argument modulo pi)
+  const double r1 = sqrt(-2.0 * log(philox_unit(w.x))), r2 = sqrt(-2.0 * log(philox_unit(w.z)));
+  double s1, c1, s2, c2;
+  sincospi(2.0 * philox_unit(w.y), &s1, &c1);
+  sincospi(2.0 * philox_unit(w.w), &s2, &c2);
+  v[0] = r1 * c1; v[1] = r1 * s1; v[2] = r2 * c2; v[3] = r2 * s2;
 }
 __device__ __forceinline__ double env_normal(uint32_t step, uint32_t member, uint32_t domain, uint32_t e, uint32_t k0, uint32_t k1) {
   double v[4];
@@ -279,21 +282,20 @@ struct EnvArgs {
   int32_t* t_count;
 };
 
-// One time step of the unroll for all trajectories of one member (one workgroup per member).
-// t > 0: every trajectory draws a_{t-1} from the policy's head outputs, receives r_{t-1} and moves to z_t.
-// t = 0: z_0 is drawn.  Then the observation o_t of every trajectory is written where the step (and the
-// policy's next forward pass) reads it.
-__global__ __launch_bounds__(256) void a2c_env_advance_kernel(EnvArgs a, int t) {
-  extern __shared__ double zs[];  // [B][nz]
+// One time step of the latent system for all trajectories of one member (one workgroup per member).
+// t > 0: one thread per trajectory draws a_{t-1} from the policy's head outputs and books r_{t-1}; then one
+// thread per (trajectory, four latent components) moves the latent to z_t (four normals = one Philox counter).
+// t = 0: z_0 is drawn.
+__global__ __launch_bounds__(256) void a2c_env_transition_kernel(EnvArgs a, int t) {
+  extern __shared__ double zs[];                 // [B][nz] latent before the transition
+  int* action = reinterpret_cast<int*>(zs + (size_t)a.B * a.nz);   // [B]
   const int i = blockIdx.x;
-  const int nz = a.nz, B = a.B, T = a.T;
-  for (int r = threadIdx.x; r < B; r += blockDim.x) {
-    double* zr = a.z + ((int64_t)i * B + r) * nz;
-    double zn[64];
-    if (t == 0) {
-      for (int k = 0; k < nz; ++k) zn[k] = env_normal(a.step, i, DOMAIN_ENV + 0, (uint32_t)(r * nz + k), a.k0, a.k1);
-    } else {
-      const int tt = t - 1;
+  const int nz = a.nz, B = a.B, T = a.T, tt = t - 1;
+  double* zm = a.z + (int64_t)i * B * nz;
+  if (t > 0) {
+    for (int e = threadIdx.x; e < B * nz; e += blockDim.x) zs[e] = zm[e];
+    __syncthreads();
+    for (int r = threadIdx.x; r < B; r += blockDim.x) {
       const float* lg = a.head_out + ((int64_t)i * B + r) * 32;
       double mx = -INFINITY;
       for (int c = 0; c < a.n_act; ++c) mx = fmax(mx, (double)lg[c]);
@@ -301,35 +303,61 @@ __global__ __launch_bounds__(256) void a2c_env_advance_kernel(EnvArgs a, int t) 
       for (int c = 0; c < a.n_act; ++c) { ex[c] = exp((double)lg[c] - mx); se += ex[c]; }
       const double u = philox_unit(philox4x32_10(a.step, i, DOMAIN_ENV + 2, (uint32_t)(r * T + tt), a.k0, a.k1).x);
       double cdf = 0.0;
-      int action = 0;
-      for (int c = 0; c < a.n_act; ++c) { cdf += ex[c] / se; action += cdf <= u ? 1 : 0; }
-      action = action < a.n_act - 1 ? action : a.n_act - 1;
+      int act = 0;
+      for (int c = 0; c < a.n_act; ++c) { cdf += ex[c] / se; act += cdf <= u ? 1 : 0; }
+      act = act < a.n_act - 1 ? act : a.n_act - 1;
       double rw = 0.0;
-      for (int k = 0; k < nz; ++k) rw += a.env.w[k] * zr[k];
+      for (int k = 0; k < nz; ++k) rw += a.env.w[k] * zs[r * nz + k];
       rw += a.env.noise[1] * env_normal(a.step, i, DOMAIN_ENV + 3, (uint32_t)(r * T + tt), a.k0, a.k1);
-      a.act[((int64_t)i * B + r) * T + tt] = action;
+      a.act[((int64_t)i * B + r) * T + tt] = act;
       a.rew[((int64_t)i * B + r) * T + tt] = (float)rw;
-      for (int k = 0; k < nz; ++k) {
-        double acc = 0.0;
-        for (int j = 0; j < nz; ++j) acc += a.env.A[k * nz + j] * zr[j];
-        zn[k] = acc + a.env.B[k * a.n_act + action] + a.env.noise[2] * env_normal(a.step, i, DOMAIN_ENV + 4, (uint32_t)((r * T + tt) * nz + k), a.k0, a.k1);
-      }
+      action[r] = act;
     }
-    for (int k = 0; k < nz; ++k) { zr[k] = zn[k]; zs[r * nz + k] = zn[k]; }
+    __syncthreads();
+  }
+  // element e = (trajectory, component) of the normal stream of this time step: z_0 (t = 0) or zeta_{t-1}
+  const uint32_t domain = t == 0 ? DOMAIN_ENV + 0 : DOMAIN_ENV + 4;
+  const int quads = (nz + 3) / 4;
+  for (int item = threadIdx.x; item < B * quads; item += blockDim.x) {
+    const int r = item / quads, k0 = (item - r * quads) * 4;
+    const uint32_t e0 = (uint32_t)((t == 0 ? r : r * T + tt) * nz + k0);
+    double v[4];
+    if ((e0 & 3u) == 0) {
+      env_normal4(a.step, i, domain, e0 >> 2, a.k0, a.k1, v);
+    } else {
+      for (int q = 0; q < 4; ++q) v[q] = env_normal(a.step, i, domain, e0 + q, a.k0, a.k1);
+    }
+    for (int q = 0; q < 4 && k0 + q < nz; ++q) {
+      const int k = k0 + q;
+      double zn = v[q];
+      if (t > 0) {
+        double acc = 0.0;
+        for (int j = 0; j < nz; ++j) acc += a.env.A[k * nz + j] * zs[r * nz + j];
+        zn = acc + a.env.B[k * a.n_act + action[r]] + a.env.noise[2] * v[q];
+      }
+      zm[r * nz + k] = zn;
+    }
   }
   if (t == 0 && threadIdx.x == 0) a.t_count[i] += 1;
+}
+
+// The observation o_t of one trajectory (blockIdx.x) of one member (blockIdx.y), written where the step (and
+// the policy's next forward pass) reads it; a thread handles runs of four elements, i.e. one Philox counter.
+__global__ __launch_bounds__(128) void a2c_env_observe_kernel(EnvArgs a, int t) {
+  __shared__ double zs[64];
+  const int r = blockIdx.x, i = blockIdx.y;
+  const int nz = a.nz;
+  if ((int)threadIdx.x < nz) zs[threadIdx.x] = a.z[((int64_t)i * a.B + r) * nz + threadIdx.x];
   __syncthreads();
-  const int quads = a.d / 4;
-  for (int item = threadIdx.x; item < B * quads; item += blockDim.x) {
-    const int r = item / quads, j0 = (item - r * quads) * 4;
-    const int64_t row = (int64_t)r * (T + 1) + t;
+  const int64_t row = (int64_t)r * (a.T + 1) + t;
+  for (int j0 = threadIdx.x * 4; j0 < a.d; j0 += blockDim.x * 4) {
     double v[4];
     env_normal4(a.step, i, DOMAIN_ENV + 1, (uint32_t)((row * a.d + j0) >> 2), a.k0, a.k1, v);
     float o[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       double acc = 0.0;
-      for (int k = 0; k < nz; ++k) acc += a.env.C[(j0 + e) * nz + k] * zs[r * nz + k];
+      for (int k = 0; k < nz; ++k) acc += a.env.C[(j0 + e) * nz + k] * zs[k];
       o[e] = (float)(acc + a.env.noise[0] * v[e]);
     }
     *reinterpret_cast<uint2*>(a.obs + ((int64_t)i * a.rows + row) * a.d + j0) = make_uint2(f2bf_pair(o[0], o[1]), f2bf_pair(o[2], o[3]));
@@ -374,9 +402,10 @@ pbt_status a2c_step_on_policy(pbt_handle* h, const A2CEnv& env, uint32_t step, h
   float* gout = h->sc<float>(a.o_gout);
   EnvArgs ea{env, c.latent_dim, C - 1, d, B, T, R, step, (uint32_t)c.seed, (uint32_t)(c.seed >> 32), h->sc<double>(a.o_lat), gout,
              h->sc<int32_t>(a.o_act), h->sc<float>(a.o_rew), obs, h->st<int32_t>(p.o_t)};
-  const size_t lds = (size_t)B * c.latent_dim * sizeof(double);
   for (int t = 0; t <= T; ++t) {
-    hipLaunchKernelGGL(a2c_env_advance_kernel, dim3(P), dim3(256), lds, s, ea, t);
+    hipLaunchKernelGGL(a2c_env_transition_kernel, dim3(P), dim3(256), (size_t)B * c.latent_dim * sizeof(double) + (size_t)B * sizeof(int), s, ea, t);
+    PBT_HIP(h, hipGetLastError());
+    hipLaunchKernelGGL(a2c_env_observe_kernel, dim3(B, P), dim3(128), 0, s, ea, t);
     PBT_HIP(h, hipGetLastError());
     if (t == T) break;
     // the policy on the B observations of time t: rows t, t + (T+1), ... of the member's observation buffer

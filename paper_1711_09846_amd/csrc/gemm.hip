@@ -38,8 +38,9 @@ hipError_t gemm_bias_act(const GemmOperands& o, const float* bias, int64_t sbias
   return run(o, EpiBiasAct{bias, sbias, Z, Aout, ld, so, act}, s);
 }
 hipError_t gemm_dgrad_act(const GemmOperands& o, const bf16_t* Zprev, bf16_t* dZ, int64_t ld, int64_t so, int act,
-                          hipStream_t s) {
-  return run(o, EpiDgradAct{Zprev, dZ, ld, so, act}, s);
+                          hipStream_t s, const DropRecord& drop) {
+  if (drop.mask && (o.N % 8 || ld % 8 || so % 8)) return hipErrorInvalidValue;
+  return run(o, EpiDgradAct{Zprev, dZ, ld, so, act, drop.mask, drop.mask_stride, drop.H, drop.n_hyper, drop.col, 1.f}, s);
 }
 
 hipError_t gemm_wgrad_optimizer(const GemmOperands& o, const OptArgs& a, int64_t off, int64_t ldc, hipStream_t s) {

@@ -577,7 +577,11 @@ struct EpiBiasAct {
   }
 };
 
-// Input gradient: dz_prev = acc * act'(z_prev), bf16.
+// Input gradient: dz_prev = acc * act'(z_prev), bf16.  With a dropout record (mask != null) the result is then
+// multiplied by the keep factor of the site that followed the activation in the forward pass: the value is
+// rounded to bf16, multiplied by 0 or by the member's scale (the float nearest 1 / (1 - p), p from column col
+// of H) in double, and rounded once more.  The record holds one bit per element of the member's [rows][ld]
+// array (bit e % 8 of byte e / 8), as the forward pass of that site left it.
 struct EpiDgradAct {
   static constexpr bool HAS_FINISH = false;
   static constexpr bool PREFETCH = false;
@@ -589,7 +593,19 @@ struct EpiDgradAct {
   bf16_t* dZ;
   int64_t ld, so;
   int act;
-  __device__ __forceinline__ void begin(int member) { Zprev += (int64_t)member * so; dZ += (int64_t)member * so; }
+  const uint8_t* mask = nullptr;
+  int64_t mask_stride = 0;       // bytes of record per member
+  const float* H = nullptr;
+  int n_hyper = 0, col = -1;
+  float scale = 1.f;
+  __device__ __forceinline__ void begin(int member) {
+    Zprev += (int64_t)member * so; dZ += (int64_t)member * so;
+    if (mask) {
+      mask += (int64_t)member * mask_stride;
+      const float p = col >= 0 ? H[(int64_t)member * n_hyper + col] : 0.f;
+      scale = p > 0.f ? (float)(1.0 / (1.0 - (double)p)) : 1.f;
+    }
+  }
   // the run of z the result is scaled by: requested for all runs of a strip before the first is applied
   // (read inside apply8, after the store of the run before, every run paid a memory latency of its own)
   __device__ __forceinline__ uint4 load_run(int m, int n, int count) const {
@@ -606,6 +622,16 @@ struct EpiDgradAct {
     float z[8], d[8];
     unpack_bf16x8(zrun, z);
     act_bwd_scale8(v, z, d, act);
+    if (mask) {
+      // (the launcher only attaches a record to arrays whose rows are whole runs of eight)
+      const uint32_t bits = mask[o >> 3];
+      bf16_t out[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) out[e] = (bits >> e) & 1u ? d2bf((double)bf2f(f2bf(d[e])) * (double)scale) : (bf16_t)(f2bf(d[e]) & 0x8000u);  // x * 0 keeps the sign
+      *reinterpret_cast<uint4*>(dZ + o) = make_uint4(out[0] | ((uint32_t)out[1] << 16), out[2] | ((uint32_t)out[3] << 16),
+                                                     out[4] | ((uint32_t)out[5] << 16), out[6] | ((uint32_t)out[7] << 16));
+      return;
+    }
     store_bf16_run(dZ + o, d, count);
   }
 };
@@ -692,7 +718,8 @@ inline GemmTile choose_tile(int M, int N, int K, int batch) {
   // (three quarters of the compute units busy with 256x256 tiles still beat all of them on smaller ones)
   // K = 512 stays with 128x128: timed alone, 256x256 tiles are 5-20 % faster there (4096 rows x 16 members,
   // N = 512 ... 8192), but inside the transformer step, with the fused epilogues and whatever the previous kernel
-  // left in the caches, the same launches came out 9 % slower (forward class 206 -> 225 us, step +0.6 ms).
+  // left in the caches, the same launches came out 9 % slower (forward class 206 -> 225 us, step +0.6 ms; for the
+  // feed-forward layers alone +0.8 ms, for the vocabulary head alone +0.15 ms).
   if (K >= 1024 && M > 128 && N > 128 && tile_count(M, N, batch, 256, 256) >= CUS * 3 / 4) return TILE_256x256;
   if ((tile_count(M, N, batch, 128, 128) < 4 * CUS && N > 64) || (N <= 64 && N > 32)) return TILE_128x64;
   return TILE_128x128;

@@ -29,9 +29,11 @@ hipError_t gemm_bias_f32(const GemmOperands& o, const float* bias, int64_t sbias
 // z = acc + bias; Z (may be null) <- z, Aout <- act(z); both [batch][M][ld] bf16 with batch stride so
 hipError_t gemm_bias_act(const GemmOperands& o, const float* bias, int64_t sbias, bf16_t* Z, bf16_t* Aout, int64_t ld,
                          int64_t so, int act, hipStream_t s);
-// dZ <- acc * act'(Zprev)
+// dZ <- acc * act'(Zprev); with a dropout record (drop.mask != null; needs N and ld multiples of 8) the result is
+// rounded and then multiplied by the recorded keep factors of the member (rate in column drop.col of drop.H)
+struct DropRecord { const uint8_t* mask = nullptr; int64_t mask_stride = 0; const float* H = nullptr; int n_hyper = 0, col = -1; };
 hipError_t gemm_dgrad_act(const GemmOperands& o, const bf16_t* Zprev, bf16_t* dZ, int64_t ld, int64_t so, int act,
-                          hipStream_t s);
+                          hipStream_t s, const DropRecord& drop = DropRecord());
 
 // Per-member sum over the whole M x N Gram matrix of exp(-(na[m] + nb[n] - 2 a_m.b_n) * inv2d), as
 // per-tile partial sums partial[batch][*tiles]; gemm_rbf_tiles(M, N, batch) is an upper bound of *tiles for sizing `partial`.
@@ -135,6 +137,14 @@ hipError_t layernorm_bwd(const bf16_t* dy, const bf16_t* x, const float* mean, c
 constexpr int LN_MAX_SLABS = 64;  // row slabs whose partial sums layernorm_param_grad combines
 hipError_t layernorm_param_grad(const bf16_t* dy, const bf16_t* x, const float* mean, const float* rstd, int P, int rows, int d,
                                 float* G, int64_t stride, int64_t g_off, int64_t b_off, float* part, hipStream_t s);
+constexpr int LN_FUSED_SLABS = 64;  // row slabs of the fused LayerNorm backward
+// LayerNorm backward (as layernorm_bwd) and the gain / bias gradients (as layernorm_param_grad) in one pass; d <= 2048
+// out2 (optional): out multiplied by the recorded keep factors of a dropout site (drop as in gemm_dgrad_act), i.e.
+// the gradient that enters the branch behind that site
+hipError_t layernorm_bwd_with_param_grad(const bf16_t* dy, const bf16_t* x, const float* mean, const float* rstd, int P, int rows,
+                                         int d, const float* W32, int64_t stride, int64_t g_off, int64_t b_off, const bf16_t* res,
+                                         bf16_t* out, float* G, float* part, hipStream_t s, bf16_t* out2 = nullptr,
+                                         const DropRecord& drop = DropRecord());
 hipError_t softmax_fwd(const bf16_t* sc, int P, int64_t rows, int S, float scale, const DropArgs& d, int site, bf16_t* pq,
                        bf16_t* pd, hipStream_t s);
 hipError_t softmax_bwd(const bf16_t* pq, bf16_t* dpd, int P, int64_t rows, int S, float scale, const DropArgs& d, int site,

@@ -19,6 +19,7 @@ Dim dim_of(const pbt_config& c) { return Dim{c.tf_vocab, c.tf_d_model, c.tf_head
 struct Ctx {
   pbt_handle* h; hipStream_t s; Dim D; int P, Bc, n;  // Bc sequences per member in this pass, n = Bc * S rows
   int64_t S_; const float* W32; const bf16_t* W16; float* G;
+  bool fused_bwd;   // LayerNorm backward + its parameter gradients + the next dropout site's backward in one kernel (d_model <= 2048)
   template <class T> T* sc(size_t off) const { return h->sc<T>(off); }
 };
 
@@ -30,20 +31,36 @@ pbt_status dense(const Ctx& x, const bf16_t* in, int K, int N, int64_t w, int64_
 }
 // G[w] = in^T dout, G[b] = column sums of dout
 pbt_status wgrad(const Ctx& x, const bf16_t* in, int K, const bf16_t* dout, int N, int64_t w, int64_t b) {
-  // (with thousands of rows per member the column sums get their own launch: as a by-product of the GEMM
-  // they would be summed by the first tile row alone, which then finishes last)
+  // The column sums are a by-product of the GEMM (its first tile row adds up the dout slabs it stages anyway).
+  // That tile row finishes last and the launch takes 17 % longer (146 -> 171 us), which is still cheaper than a
+  // pass of its own over dout (41 us per layer): 16.78 -> 16.43 ms per population step.
   GemmOperands o{in, K, (int64_t)x.n * K, true, dout, N, (int64_t)x.n * N, false, K, N, x.n, x.P};
+  o.colsum = x.G + b; o.colsum_stride = x.S_;
   PBT_LAUNCH(x.h, PBT_K_GEMM_WGRAD, x.s, gemm_store_f32(o, x.G + w, N, x.S_, x.s));
-  PBT_LAUNCH(x.h, PBT_K_BIAS_GRAD, x.s, bias_grad(dout, x.P, x.n, N, N, x.G + b, x.S_, x.s, x.sc<float>(x.h->plan.tf.o_biaspart)));
   return PBT_OK;
 }
 // din[P][n][K] = dout[P][n][N] W^T   (optionally times act'(zprev))
-pbt_status dgrad(const Ctx& x, const bf16_t* dout, int N, int K, int64_t w, const bf16_t* zprev, int act, bf16_t* din) {
+pbt_status dgrad(const Ctx& x, const bf16_t* dout, int N, int K, int64_t w, const bf16_t* zprev, int act, bf16_t* din,
+                 const DropRecord& drop = DropRecord()) {
   GemmOperands o{dout, N, (int64_t)x.n * N, false, x.W16 + w, N, x.S_, true, x.n, K, N, x.P};
   if (zprev)
-    PBT_LAUNCH(x.h, PBT_K_GEMM_DGRAD, x.s, gemm_dgrad_act(o, zprev, din, K, (int64_t)x.n * K, act, x.s));
+    PBT_LAUNCH(x.h, PBT_K_GEMM_DGRAD, x.s, gemm_dgrad_act(o, zprev, din, K, (int64_t)x.n * K, act, x.s, drop));
   else
     PBT_LAUNCH(x.h, PBT_K_GEMM_DGRAD, x.s, gemm_store_bf16(o, din, K, (int64_t)x.n * K, x.s));
+  return PBT_OK;
+}
+
+// out = LayerNorm backward of dy (+ res); G[g], G[b] = gradients of gain and bias
+// out2 / drop (optional, fused path only): out times the recorded keep factors of a dropout site
+pbt_status ln_backward(const Ctx& x, const bf16_t* dy, const bf16_t* in, const float* mean, const float* rstd, int64_t g, int64_t b,
+                       const bf16_t* res, bf16_t* out, bf16_t* out2 = nullptr, const DropRecord& drop = DropRecord()) {
+  float* part = x.sc<float>(x.h->plan.tf.o_lnpart);
+  if (x.fused_bwd) {
+    PBT_HIP(x.h, layernorm_bwd_with_param_grad(dy, in, mean, rstd, x.P, x.n, x.D.d, x.W32, x.S_, g, b, res, out, x.G, part, x.s, out2, drop));
+    return PBT_OK;
+  }
+  PBT_HIP(x.h, layernorm_param_grad(dy, in, mean, rstd, x.P, x.n, x.D.d, x.G, x.S_, g, b, part, x.s));
+  PBT_HIP(x.h, layernorm_bwd(dy, in, mean, rstd, x.P, x.n, x.D.d, x.W32, x.S_, g, res, out, x.s));
   return PBT_OK;
 }
 
@@ -72,7 +89,6 @@ pbt_status forward(const Ctx& x, const int32_t* pool, int n_pool, uint32_t c0, i
                                             x.sc<bf16_t>(t.o_h[0]), x.sc<int32_t>(t.o_tokens), x.sc<int32_t>(t.o_targets),
                                             h->st<int32_t>(h->plan.o_t), x.s));
   bf16_t* tmp_d = x.sc<bf16_t>(t.o_tmp_d[0]);
-  bf16_t* tmp_f = x.sc<bf16_t>(t.o_tmp_f[0]);
   bf16_t* score = x.sc<bf16_t>(t.o_score);
   for (int l = 0; l < D.L; ++l) {
     const TfBlockOff& b = t.blk[l];
@@ -109,7 +125,8 @@ pbt_status forward(const Ctx& x, const int32_t* pool, int n_pool, uint32_t c0, i
 
 Ctx make_ctx(pbt_handle* h, int Bc, hipStream_t s) {
   const Plan& p = h->plan;
-  Ctx x{h, s, dim_of(h->cfg), h->cfg.P, Bc, Bc * h->cfg.tf_seq, p.lay.stride, h->st<float>(p.o_w32), h->st<bf16_t>(p.o_w16), h->sc<float>(p.o_grad)};
+  Ctx x{h, s, dim_of(h->cfg), h->cfg.P, Bc, Bc * h->cfg.tf_seq, p.lay.stride, h->st<float>(p.o_w32), h->st<bf16_t>(p.o_w16), h->sc<float>(p.o_grad), false};
+  x.fused_bwd = h->cfg.tf_d_model <= 2048;
   return x;
 }
 
@@ -179,12 +196,7 @@ pbt_status tf_check_and_plan(const pbt_config* c, Plan* pl, Carver* w) {
   t.o_tokstart = w->take(P * ((size_t)D.V + 1) * 4);
   t.o_tokcursor = w->take(P * (size_t)D.V * 4);
   t.o_tokorder = w->take(P * n * 4);
-  t.o_lnpart = w->take(P * (size_t)LN_MAX_SLABS * 2 * D.d * 4);
-  {
-    size_t widest = D.V > D.f ? D.V : D.f;
-    if (widest < 3 * (size_t)D.d) widest = 3 * (size_t)D.d;
-    t.o_biaspart = w->take(P * (size_t)BIAS_GRAD_MAX_SLABS * widest * 4);
-  }
+  t.o_lnpart = w->take(P * (size_t)(LN_FUSED_SLABS > LN_MAX_SLABS ? LN_FUSED_SLABS : LN_MAX_SLABS) * 2 * D.d * 4);
   return PBT_OK;
 }
 
@@ -213,25 +225,38 @@ pbt_status tf_step(pbt_handle* h, const int32_t* pool, uint32_t step, hipStream_
   bf16_t* dqkv = x.sc<bf16_t>(t.o_dqkv);
   bf16_t* dscore = x.sc<bf16_t>(t.o_score);
 
+  // The gradient of a dropout site's input is the gradient of its output times the keep factors the forward pass
+  // recorded.  On the fused path that multiply rides on the kernel that produces the gradient (the LayerNorm
+  // backward for the two residual-branch sites, the input-gradient GEMM's epilogue for the feed-forward hidden
+  // site); otherwise it is a pass of its own.
+  const float* Hh = h->st<float>(p.o_hyper);
+  auto record = [&](int l, int k, int64_t per_member) {
+    return DropRecord{x.sc<uint8_t>(t.o_mask[l][k]), (int64_t)(dropout_mask_bytes(1, per_member)), Hh, c.n_hyper, t.col_drop};
+  };
+  const bool fb = x.fused_bwd;
   // head and final LayerNorm
   TF_TRY(wgrad(x, x.sc<bf16_t>(t.o_uf), D.d, dl, D.V, t.whead, t.bhead));
-  TF_TRY(dgrad(x, dl, D.V, D.d, t.whead, nullptr, 0, dd));
-  PBT_HIP(h, layernorm_param_grad(dd, x.sc<bf16_t>(t.o_h[D.L]), x.sc<float>(t.o_meanf), x.sc<float>(t.o_rstdf), x.P, x.n, D.d, x.G, x.S_, t.lnfg, t.lnfb, x.sc<float>(t.o_lnpart), s));
-  PBT_HIP(h, layernorm_bwd(dd, x.sc<bf16_t>(t.o_h[D.L]), x.sc<float>(t.o_meanf), x.sc<float>(t.o_rstdf), x.P, x.n, D.d, x.W32, x.S_, t.lnfg, nullptr, dh, s));
+  TF_TRY(dgrad(x, dl, D.V, D.d, t.whead, nullptr, 0, du));   // (du: the final LayerNorm's output buffer, free once the head's weight gradient is taken)
+  TF_TRY(ln_backward(x, du, x.sc<bf16_t>(t.o_h[D.L]), x.sc<float>(t.o_meanf), x.sc<float>(t.o_rstdf), t.lnfg, t.lnfb, nullptr, dh,
+                     fb ? dd : nullptr, fb ? record(D.L - 1, 2, per_d) : DropRecord()));
   for (int l = D.L - 1; l >= 0; --l) {
     const TfBlockOff& b = t.blk[l];
     bf16_t* qkv = x.sc<bf16_t>(t.o_qkv[l]);
     // feed-forward branch
-    PBT_HIP(h, dropout_apply(dh, nullptr, x.P, per_d, dr, 4 * l + 3, dd, s, x.sc<uint16_t>(t.o_mask[l][2])));
+    if (!fb) PBT_HIP(h, dropout_apply(dh, nullptr, x.P, per_d, dr, 4 * l + 3, dd, s, x.sc<uint16_t>(t.o_mask[l][2])));
     TF_TRY(wgrad(x, x.sc<bf16_t>(t.o_fd[l]), D.f, dd, D.d, b.w2, b.b2));
-    TF_TRY(dgrad(x, dd, D.d, D.f, b.w2, x.sc<bf16_t>(t.o_z1[l]), PBT_ACT_RELU, df0));
-    PBT_HIP(h, dropout_apply(df0, nullptr, x.P, per_f, dr, 4 * l + 2, df1, s, x.sc<uint16_t>(t.o_mask[l][1])));
+    if (fb) {
+      TF_TRY(dgrad(x, dd, D.d, D.f, b.w2, x.sc<bf16_t>(t.o_z1[l]), PBT_ACT_RELU, df1, record(l, 1, per_f)));
+    } else {
+      TF_TRY(dgrad(x, dd, D.d, D.f, b.w2, x.sc<bf16_t>(t.o_z1[l]), PBT_ACT_RELU, df0));
+      PBT_HIP(h, dropout_apply(df0, nullptr, x.P, per_f, dr, 4 * l + 2, df1, s, x.sc<uint16_t>(t.o_mask[l][1])));
+    }
     TF_TRY(wgrad(x, x.sc<bf16_t>(t.o_u2[l]), D.d, df1, D.f, b.w1, b.b1));
     TF_TRY(dgrad(x, df1, D.f, D.d, b.w1, nullptr, 0, du));
-    PBT_HIP(h, layernorm_param_grad(du, x.sc<bf16_t>(t.o_hmid[l]), x.sc<float>(t.o_mean2[l]), x.sc<float>(t.o_rstd2[l]), x.P, x.n, D.d, x.G, x.S_, b.ln2g, b.ln2b, x.sc<float>(t.o_lnpart), s));
-    PBT_HIP(h, layernorm_bwd(du, x.sc<bf16_t>(t.o_hmid[l]), x.sc<float>(t.o_mean2[l]), x.sc<float>(t.o_rstd2[l]), x.P, x.n, D.d, x.W32, x.S_, b.ln2g, dh, dh2, s));
+    TF_TRY(ln_backward(x, du, x.sc<bf16_t>(t.o_hmid[l]), x.sc<float>(t.o_mean2[l]), x.sc<float>(t.o_rstd2[l]), b.ln2g, b.ln2b, dh, dh2,
+                       fb ? dd : nullptr, fb ? record(l, 0, per_d) : DropRecord()));
     // attention branch
-    PBT_HIP(h, dropout_apply(dh2, nullptr, x.P, per_d, dr, 4 * l + 1, dd, s, x.sc<uint16_t>(t.o_mask[l][0])));
+    if (!fb) PBT_HIP(h, dropout_apply(dh2, nullptr, x.P, per_d, dr, 4 * l + 1, dd, s, x.sc<uint16_t>(t.o_mask[l][0])));
     TF_TRY(wgrad(x, x.sc<bf16_t>(t.o_o[l]), D.d, dd, D.d, b.wo, b.bo));
     TF_TRY(dgrad(x, dd, D.d, D.d, b.wo, nullptr, 0, du));  // du = gradient of the merged head outputs
     const bf16_t* pd = x.sc<bf16_t>(t.o_pd[l]);
@@ -242,8 +267,9 @@ pbt_status tf_step(pbt_handle* h, const int32_t* pool, uint32_t step, hipStream_
     TF_TRY(attn_gemm(x, in_scores(dscore, D), true, in_rows(qkv, 0, 3 * D.d, D), false, in_rows(dqkv, D.d, 3 * D.d, D), D.S, D.dh, D.S));        // dK = dS^T Q
     TF_TRY(wgrad(x, x.sc<bf16_t>(t.o_u[l]), D.d, dqkv, 3 * D.d, b.wqkv, b.bqkv));
     TF_TRY(dgrad(x, dqkv, 3 * D.d, D.d, b.wqkv, nullptr, 0, du));
-    PBT_HIP(h, layernorm_param_grad(du, x.sc<bf16_t>(t.o_h[l]), x.sc<float>(t.o_mean1[l]), x.sc<float>(t.o_rstd1[l]), x.P, x.n, D.d, x.G, x.S_, b.ln1g, b.ln1b, x.sc<float>(t.o_lnpart), s));
-    PBT_HIP(h, layernorm_bwd(du, x.sc<bf16_t>(t.o_h[l]), x.sc<float>(t.o_mean1[l]), x.sc<float>(t.o_rstd1[l]), x.P, x.n, D.d, x.W32, x.S_, b.ln1g, dh2, dh, s));
+    const bool next = fb && l > 0;   // the block below starts with the backward of its feed-forward output site
+    TF_TRY(ln_backward(x, du, x.sc<bf16_t>(t.o_h[l]), x.sc<float>(t.o_mean1[l]), x.sc<float>(t.o_rstd1[l]), b.ln1g, b.ln1b, dh2, dh,
+                       next ? dd : nullptr, next ? record(l - 1, 2, per_d) : DropRecord()));
   }
   PBT_HIP(h, embed_bwd(dh, x.sc<int32_t>(t.o_tokens), x.Bc, D.S, D.d, D.V, x.P, x.G, x.S_, t.tok, t.pos, x.sc<int32_t>(t.o_tokstart),
                        x.sc<int32_t>(t.o_tokcursor), x.sc<int32_t>(t.o_tokorder), s));

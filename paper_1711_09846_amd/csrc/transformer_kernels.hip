@@ -345,6 +345,131 @@ hipError_t layernorm_param_grad(const bf16_t* dy, const bf16_t* x, const float* 
   return hipGetLastError();
 }
 
+// LayerNorm backward and the gradients of its gain and bias in one pass over dy and x: a workgroup takes a slab
+// of rows (wavefront w the rows w, w + 4, ... of the slab), a lane owns the same 8 J columns in every row, so the
+// gain is read once, a row is read once (it stays in registers between the two reductions and the output) and
+// the per-column sums dg += dy xhat, db += dy accumulate in registers; the four wavefronts are combined through
+// LDS in wavefront order and the slab's partial sums go to `part`, which layernorm_param_combine_kernel adds in
+// slab order.  J = ceil(d / 512).
+template <int J>
+__global__ __launch_bounds__(256) void layernorm_bwd_fused_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x,
+                                                                  const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                                  int rows_per_member, int d, int rows_per_slab,
+                                                                  const float* __restrict__ W32, int64_t stride, int64_t g_off,
+                                                                  const bf16_t* __restrict__ res, bf16_t* __restrict__ out,
+                                                                  float* __restrict__ part, bf16_t* __restrict__ out2, DropRecord drop) {
+  extern __shared__ float red[];  // [4][2][d]
+  const int i = blockIdx.y, slab = blockIdx.x, n_slabs = gridDim.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float* __restrict__ g = W32 + (int64_t)i * stride + g_off;
+  float drop_scale = 1.f;
+  if (out2) {
+    const float p = drop.col >= 0 ? drop.H[(int64_t)i * drop.n_hyper + drop.col] : 0.f;
+    drop_scale = p > 0.f ? (float)(1.0 / (1.0 - (double)p)) : 1.f;
+  }
+  float gv[J][8], ag[J][8], ab[J][8];
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int c = lane * 8 + 512 * j;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { gv[j][e] = 0.f; ag[j][e] = 0.f; ab[j][e] = 0.f; }
+    if (c < d) load8(g + c, gv[j]);
+  }
+  const int r_end = min(rows_per_member, (slab + 1) * rows_per_slab);
+  for (int r = slab * rows_per_slab + wave; r < r_end; r += 4) {
+    const int64_t row = (int64_t)i * rows_per_member + r;
+    const float mu = mean[row], rs = rstd[row];
+    float dv[J][8], xv[J][8];
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+      const int c = lane * 8 + 512 * j;
+      if (c < d) {
+        load8(dy + row * d + c, dv[j]);
+        load8(x + row * d + c, xv[j]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float dyg = dv[j][e] * gv[j][e];
+          a += dyg;
+          b = fmaf(dyg, (xv[j][e] - mu) * rs, b);
+        }
+      }
+    }
+    a = wave_sum(a) / (float)d;
+    b = wave_sum(b) / (float)d;
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+      const int c = lane * 8 + 512 * j;
+      if (c < d) {
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float xh = (xv[j][e] - mu) * rs;
+          o[e] = rs * (dv[j][e] * gv[j][e] - a - xh * b);
+          ab[j][e] += dv[j][e];
+          ag[j][e] = fmaf(dv[j][e], xh, ag[j][e]);
+        }
+        if (res) {
+          float rv[8];
+          load8(res + row * d + c, rv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] += rv[e];
+        }
+        store8(out + row * d + c, o);
+        if (out2) {
+          // the stored (bf16) value times the recorded keep factor, rounded once more
+          const uint32_t bits = drop.mask[(int64_t)i * drop.mask_stride + (((int64_t)r * d + c) >> 3)];
+          bf16_t w[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) w[e] = (bits >> e) & 1u ? d2bf((double)bf2f(f2bf(o[e])) * (double)drop_scale) : (bf16_t)(f2bf(o[e]) & 0x8000u);  // x * 0 keeps the sign
+          *reinterpret_cast<uint4*>(out2 + row * d + c) = make_uint4(w[0] | ((uint32_t)w[1] << 16), w[2] | ((uint32_t)w[3] << 16),
+                                                                      w[4] | ((uint32_t)w[5] << 16), w[6] | ((uint32_t)w[7] << 16));
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int c = lane * 8 + 512 * j;
+    if (c < d) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        red[(wave * 2 + 0) * d + c + e] = ag[j][e];
+        red[(wave * 2 + 1) * d + c + e] = ab[j][e];
+      }
+    }
+  }
+  __syncthreads();
+  float* __restrict__ po = part + ((int64_t)i * n_slabs + slab) * 2 * d;
+  for (int c = threadIdx.x; c < 2 * d; c += 256) {
+    const int which = c / d, col = c - which * d;
+    po[c] = ((red[(0 * 2 + which) * d + col] + red[(1 * 2 + which) * d + col]) + red[(2 * 2 + which) * d + col]) + red[(3 * 2 + which) * d + col];
+  }
+}
+// out = LayerNorm backward of dy (+ res), G[g_off], G[b_off] = gradients of gain and bias; part: float
+// [P][LN_FUSED_SLABS][2][d] (scratch).  d <= 2048.
+hipError_t layernorm_bwd_with_param_grad(const bf16_t* dy, const bf16_t* x, const float* mean, const float* rstd, int P, int rows,
+                                         int d, const float* W32, int64_t stride, int64_t g_off, int64_t b_off, const bf16_t* res,
+                                         bf16_t* out, float* G, float* part, hipStream_t s, bf16_t* out2, const DropRecord& drop) {
+  if (d % 8 || g_off % 4 || b_off % 4 || stride % 4 || d > 2048) return hipErrorInvalidValue;
+  if (out2 && !drop.mask) return hipErrorInvalidValue;
+  int n_slabs = (rows + 15) / 16;
+  if (n_slabs > LN_FUSED_SLABS) n_slabs = LN_FUSED_SLABS;
+  const int rows_per_slab = (rows + n_slabs - 1) / n_slabs;
+  const size_t lds = (size_t)8 * d * sizeof(float);
+  const dim3 grid(n_slabs, P);
+  if (d <= 512)
+    hipLaunchKernelGGL(layernorm_bwd_fused_kernel<1>, grid, dim3(256), lds, s, dy, x, mean, rstd, rows, d, rows_per_slab, W32, stride, g_off, res, out, part, out2, drop);
+  else if (d <= 1024)
+    hipLaunchKernelGGL(layernorm_bwd_fused_kernel<2>, grid, dim3(256), lds, s, dy, x, mean, rstd, rows, d, rows_per_slab, W32, stride, g_off, res, out, part, out2, drop);
+  else
+    hipLaunchKernelGGL(layernorm_bwd_fused_kernel<4>, grid, dim3(256), lds, s, dy, x, mean, rstd, rows, d, rows_per_slab, W32, stride, g_off, res, out, part, out2, drop);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(layernorm_param_combine_kernel, dim3((2 * d + 255) / 256, P), dim3(256), 0, s, part, n_slabs, d, G, stride, g_off, b_off);
+  return hipGetLastError();
+}
+
 // ---- causal softmax with dropout -------------------------------------------------------------
 // Rows of the [P][B][H][S][S] score array; LPR lanes share a row (64 / LPR rows per wavefront) and each
 // lane owns runs of four consecutive keys, i.e. one Philox counter and 8-byte accesses.

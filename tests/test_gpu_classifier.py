@@ -14,10 +14,10 @@ TOL_BF16 = 1e-2     # relative, bf16 compute with fp32 master weights
 # Losses and scores are compared as |gpu - ref| / max(|ref|, floor).  A loss is lse(logits) minus the
 # label's logit: its absolute error is set by the rounding of O(10) logits and does not shrink with
 # the loss, so a purely relative test is unattainable in any finite precision once training drives
-# the loss towards 0.  fp32: floor 1e-3.  bf16: logits carry 2^-9 relative rounding, floor 1 (the
-# scale of ln C and of the logits).
+# the loss towards 0.  fp32: floor 1e-3.  bf16: logits carry 2^-9 relative rounding; floor 0.1 (measured
+# absolute errors stay below 1e-4 while the logits grow past 1000).
 FLOOR_FP32 = 1e-3
-FLOOR_BF16 = 1.0
+FLOOR_BF16 = 0.1
 
 
 def _window(pair, n_steps, tol, ready_interval, check_every=1, opt1=False, verbose="", tol_scalar=None):
@@ -180,7 +180,7 @@ def test_mlp_wide_bf16_full_size_window():
             rows = oc.batch_rows(pair.seed, s, i, wl.batch, wl.n_train)
             loss_ref, grads = nets.classifier_loss_and_grads(oc.params_of(m), pair.train_x[rows], pair.train_y[rows],
                                                              wl.act, pair.spec.q)
-            worst["loss"] = max(worst["loss"], abs(loss_gpu[i] - loss_ref) / max(abs(loss_ref), 1.0))
+            worst["loss"] = max(worst["loss"], abs(loss_gpu[i] - loss_ref) / max(abs(loss_ref), FLOOR_BF16))
             # (a) gradient, while the member's loss is >= 1e-3.  Below that every softmax term
             # e^(l_c - l_y) turns the absolute fp32 rounding of the logits (which grows with their
             # size, > 1000 here for members trained into saturation) into relative error of the

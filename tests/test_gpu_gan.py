@@ -9,7 +9,11 @@ from tests.harness import GanPair
 pytestmark = pytest.mark.gpu
 
 TOL_BF16 = 1e-2
-FLOOR = 1.0     # losses are softplus of O(1) logits, the score a difference of kernel means of order 1
+FLOOR = 1e-2    # |gpu - ref| / max(|ref|, FLOOR) for losses (softplus of O(1) logits) and scores (kernel means, 1e-2 .. 0.5)
+
+# WGAN-GP losses: a difference of critic means plus 10 x a mean squared deviation of gradient norms from 1; their
+# absolute error is set by those O(1) terms and does not shrink when the terms cancel
+FLOOR_WGAN = 1.0
 
 
 def _reduced(P=5):
@@ -115,7 +119,7 @@ def test_wgan_gp_reduced_free_running_window():
         g.step(pair.d_train, s)
         loss_ref = pair.step_ref(s)
         loss = g.get(binding.ARR_LOSS)
-        worst["loss"] = max(worst["loss"], float(np.max(np.abs(loss - loss_ref) / np.maximum(np.abs(loss_ref), FLOOR))))
+        worst["loss"] = max(worst["loss"], float(np.max(np.abs(loss - loss_ref) / np.maximum(np.abs(loss_ref), FLOOR_WGAN))))
         for i in range(pair.wl.P):
             worst["w"] = max(worst["w"], pair.member_errors(i, binding.ARR_W32, "theta")[0])
             worst["m"] = max(worst["m"], pair.member_errors(i, binding.ARR_OPT0, "s0")[1])
@@ -175,7 +179,7 @@ def test_wgan_gp_full_size_steps():
         g.step(pair.d_train, s)
         loss_ref = pair.step_ref(s)
         loss = g.get(binding.ARR_LOSS)[sample]
-        worst["loss"] = max(worst["loss"], float(np.max(np.abs(loss - loss_ref) / np.maximum(np.abs(loss_ref), FLOOR))))
+        worst["loss"] = max(worst["loss"], float(np.max(np.abs(loss - loss_ref) / np.maximum(np.abs(loss_ref), FLOOR_WGAN))))
         for i in sample:
             worst["step"] = max(worst["step"], pair.member_errors(i, binding.ARR_W32, "theta")[0])
         assert worst["step"] <= TOL_BF16 and worst["loss"] <= TOL_BF16, (s, worst, loss, loss_ref)

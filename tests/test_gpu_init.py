@@ -69,3 +69,26 @@ def test_init_population_transformer_matches_oracle():
     for s in range(1, 40):
         pop.step(d_pool, s)
     assert np.all(np.isfinite(l0)) and np.all(pop.get(binding.ARR_LOSS) < l0)
+
+
+def test_init_population_gan_two_networks_match_oracle():
+    """Generator and discriminator live in one flat vector; every layer of both is drawn with its own fan-in."""
+    wl = workloads.GAN_MLP.replace(P=4, dims=[16, 72, 40], dims2=[40, 136, 24, 1], batch=24, n_train=1024, n_eval=200, n_trunc=1)
+    seed = 0x77aa
+    pop = binding.Population(binding.make_config(wl, seed))
+    pop.init_population(wl.priors)
+    lay = pop.layout
+    Lg, Ld = len(wl.dims) - 1, len(wl.dims2) - 1
+    off_g = [(lay.w_off[l], lay.b_off[l]) for l in range(Lg)]
+    off_d = [(lay.w_off[Lg + l], lay.b_off[Lg + l]) for l in range(Ld)]
+    W = pop.get(binding.ARR_W32)
+    for i in range(wl.P):
+        layers = opbt.init_weights(seed, i, wl.dims, off_g) + opbt.init_weights(seed, i, wl.dims2, off_d)
+        assert W[i].tobytes() == binding.pack_params(lay, layers).tobytes()
+        # the first discriminator layer really uses its own fan-in (40), not the generator's
+        Wd0 = W[i][lay.w_off[Lg]:lay.w_off[Lg] + 40 * 136]
+        assert 0.9 / np.sqrt(40) < np.abs(Wd0).max() <= 1.0 / np.sqrt(40)
+    H, Href = pop.get(binding.ARR_HYPER), opbt.init_hyperparameters(seed, wl.P, wl.priors)
+    assert np.all(np.abs(H.view(np.int32) - Href.view(np.int32)) <= 1)
+    import torch
+    assert np.array_equal(pop.get(binding.ARR_W16), torch.from_numpy(W).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))

@@ -10,7 +10,7 @@ from tests.harness import TransformerPair
 pytestmark = pytest.mark.gpu
 
 TOL_BF16 = 1e-2
-FLOOR = 1.0
+FLOOR = 1e-2    # |gpu - ref| / max(|ref|, FLOOR) for the loss (ln V = 9 at the start)
 # Gradients of the reduced networks: where no stored bf16 value rounds differently under fp32 and fp64
 # accumulation the two sides agree to ~1e-7; one value rounding the other way (about two are expected
 # per forward pass of these sizes) moves every gradient of a 64-row batch by up to a few percent (the
