@@ -330,7 +330,7 @@ enum {
   PBT_K_HEAD = 2,       /* output layer + loss + its backward kernels        */
   PBT_K_GEMM_WGRAD = 3, /* weight-gradient GEMMs                             */
   PBT_K_GEMM_DGRAD = 4, /* input-gradient GEMMs                              */
-  PBT_K_BIAS_GRAD = 5,  /* bias-gradient column sums (transformer workload; the MLP workloads get them from the weight-gradient GEMM) */
+  PBT_K_BIAS_GRAD = 5,  /* (no launches of their own any more: bias gradients are column sums taken inside the weight-gradient GEMMs) */
   PBT_K_OPTIMIZER = 6,  /* fused per-member optimiser                        */
   PBT_K_RANK = 7,       /* rank + truncation select + perturb                */
   PBT_K_COPY = 8,       /* exploit gather-copy                               */

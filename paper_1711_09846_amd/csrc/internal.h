@@ -66,9 +66,6 @@ hipError_t head_fwd_loss(const bf16_t* A, int64_t sa, const bf16_t* W16, int64_t
 // dZprev[P][rows][K] = (dlogits W^T) * act'(Zprev)
 hipError_t head_dgrad(const bf16_t* dlogits, const bf16_t* W16, int64_t sw, const bf16_t* Zprev, bf16_t* dZprev, int P,
                       int rows, int K, int C, int act, hipStream_t s);
-// db[n] = sum over rows of dZ[P][rows][ld], first N columns
-constexpr int BIAS_GRAD_MAX_SLABS = 16;  // row slabs of bias_grad's optional two-pass form
-hipError_t bias_grad(const bf16_t* dZ, int P, int rows, int N, int64_t ld, float* db, int64_t sg, hipStream_t s, float* part = nullptr);
 // out[i * out_stride] = scale * sum_r rowval[i][r]   (one wavefront per member, fixed order)
 hipError_t row_reduce(const float* rowval, int64_t srow, int P, int rows, float scale, float* out, int out_stride,
                       hipStream_t s);

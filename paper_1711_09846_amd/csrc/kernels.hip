@@ -103,93 +103,6 @@ hipError_t gather_batch(const float* train_x, const int32_t* train_y, int n_trai
   return hipGetLastError();
 }
 
-// db[n] = sum_r dZ[r][n].  A workgroup covers 64 columns of one slab of rows: 8 threads x 8 columns (one
-// 16-byte load per row) times 32 row groups; the 32 partial sums are combined through LDS in fixed
-// order.  With one slab the result goes straight to db; with several (tall inputs, so that the grid
-// fills the chip) to slab_out[member][slab][n], which bias_combine_kernel adds up in slab order.
-__global__ __launch_bounds__(256) void bias_grad_kernel(const bf16_t* __restrict__ dZ, int rows, int N, int64_t ld,
-                                                        float* __restrict__ db, int64_t sg, int rows_per_slab) {
-  __shared__ float part[32][65];
-  const int i = blockIdx.z, slab = blockIdx.y;
-  const int r_end = min(rows, (slab + 1) * rows_per_slab);
-  const int cg = threadIdx.x & 7, rg = threadIdx.x >> 3;
-  const int n0 = blockIdx.x * 64 + cg * 8;
-  float acc[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-  if (n0 < N) {
-    const bf16_t* __restrict__ p = dZ + (int64_t)i * rows * ld + n0;
-    const bool full = n0 + 8 <= N;
-    int r = slab * rows_per_slab + rg;
-    if (full) {
-      // four rows' loads go out together (the sums still run in row order)
-      for (; r + 96 < r_end; r += 128) {
-        uint4 v[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint4*>(p + (int64_t)(r + 32 * u) * ld);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            acc[2 * q] += __uint_as_float(w[q] << 16);
-            acc[2 * q + 1] += __uint_as_float(w[q] & 0xffff0000u);
-          }
-        }
-      }
-    }
-    for (; r < r_end; r += 32) {
-      if (full) {
-        const uint4 v = *reinterpret_cast<const uint4*>(p + (int64_t)r * ld);
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          acc[2 * q] += __uint_as_float(w[q] << 16);
-          acc[2 * q + 1] += __uint_as_float(w[q] & 0xffff0000u);
-        }
-      } else {
-        for (int e = 0; e < N - n0; ++e) acc[e] += bf2f(p[(int64_t)r * ld + e]);
-      }
-    }
-  }
-#pragma unroll
-  for (int e = 0; e < 8; ++e) part[rg][cg * 8 + e] = acc[e];
-  __syncthreads();
-  if (threadIdx.x < 64) {
-    const int n = blockIdx.x * 64 + threadIdx.x;
-    float sum = 0.f;
-#pragma unroll
-    for (int g = 0; g < 32; ++g) sum += part[g][threadIdx.x];
-    if (n < N) db[((int64_t)i * gridDim.y + slab) * sg + n] = sum;
-  }
-}
-__global__ __launch_bounds__(256) void bias_combine_kernel(const float* __restrict__ part, int slabs, int N, float* __restrict__ db, int64_t sg) {
-  const int i = blockIdx.y;
-  const int n = blockIdx.x * 256 + threadIdx.x;
-  if (n >= N) return;
-  float sum = 0.f;
-  for (int k = 0; k < slabs; ++k) sum += part[((int64_t)i * slabs + k) * N + n];
-  db[(int64_t)i * sg + n] = sum;
-}
-// part: optional scratch of P * BIAS_GRAD_MAX_SLABS * N floats; without it every member's rows are one slab
-hipError_t bias_grad(const bf16_t* dZ, int P, int rows, int N, int64_t ld, float* db, int64_t sg, hipStream_t s, float* part) {
-  if (ld % 8) return hipErrorInvalidValue;
-  int slabs = 1;
-  if (part && (int64_t)((N + 63) / 64) * P < 2048) {
-    slabs = rows / 256;
-    if (slabs > BIAS_GRAD_MAX_SLABS) slabs = BIAS_GRAD_MAX_SLABS;
-    if (slabs < 1) slabs = 1;
-  }
-  const int rows_per_slab = (rows + slabs - 1) / slabs;
-  if (slabs == 1) {
-    hipLaunchKernelGGL(bias_grad_kernel, dim3((N + 63) / 64, 1, P), dim3(256), 0, s, dZ, rows, N, ld, db, sg, rows_per_slab);
-  } else {
-    hipLaunchKernelGGL(bias_grad_kernel, dim3((N + 63) / 64, slabs, P), dim3(256), 0, s, dZ, rows, N, ld, part, (int64_t)N, rows_per_slab);
-    hipLaunchKernelGGL(bias_combine_kernel, dim3((N + 255) / 256, P), dim3(256), 0, s, part, slabs, N, db, sg);
-  }
-  return hipGetLastError();
-}
-
 // Per-member reduction of per-row values with wavefront shuffles: lane l adds rows l, l+64, ...
 // in order, then a butterfly over the 64 lanes.
 __global__ __launch_bounds__(64) void row_reduce_kernel(const float* __restrict__ rowval, int64_t srow, int rows,
@@ -209,7 +122,9 @@ hipError_t row_reduce(const float* rowval, int64_t srow, int P, int rows, float 
 
 // ---- fused per-member optimiser --------------------------------------------------------------
 // Streams a range of every member's parameters once: reads theta, gradient and state, writes theta,
-// state and the bf16 shadow (update rules in optim_math.h).  One float4 per thread per array.
+// state and the bf16 shadow (update rules in optim_math.h).  One float4 per thread per array (two or four per
+// thread, all loads issued first, were slower on every workload: 397 -> 416 -> 431 us on the wide MLP's separate
+// pass, 1820 -> 1876 / 1855 us on the transformer).
 constexpr int OPT_VEC_PER_THREAD = 1;
 
 template <int OPT>

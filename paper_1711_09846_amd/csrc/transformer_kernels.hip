@@ -324,14 +324,22 @@ __global__ __launch_bounds__(256) void layernorm_param_grad_kernel(const bf16_t*
     out[d + c] = ((pb[0][cl] + pb[1][cl]) + pb[2][cl]) + pb[3][cl];
   }
 }
+// adds the slabs' partial sums in a fixed order: a workgroup covers 64 of the 2 d columns (gains, then biases), its
+// four thread groups each add a quarter of the slabs in slab order, and the four results are added in group order
 __global__ __launch_bounds__(256) void layernorm_param_combine_kernel(const float* __restrict__ part, int n_slabs, int d,
                                                                       float* __restrict__ G, int64_t stride, int64_t g_off, int64_t b_off) {
+  __shared__ float red[4][64];
   const int i = blockIdx.y;
-  const int c = blockIdx.x * 256 + threadIdx.x;  // 0..2d-1: gains, then biases
-  if (c >= 2 * d) return;
+  const int cl = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;  // 0..2d-1
+  const int per = (n_slabs + 3) / 4;
   float acc = 0.f;
-  for (int k = 0; k < n_slabs; ++k) acc += part[((int64_t)i * n_slabs + k) * 2 * d + c];
-  G[(int64_t)i * stride + (c < d ? g_off + c : b_off + c - d)] = acc;
+  if (c < 2 * d)
+    for (int k = grp * per; k < min(n_slabs, (grp + 1) * per); ++k) acc += part[((int64_t)i * n_slabs + k) * 2 * d + c];
+  red[grp][cl] = acc;
+  __syncthreads();
+  if (grp == 0 && c < 2 * d)
+    G[(int64_t)i * stride + (c < d ? g_off + c : b_off + c - d)] = ((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl];
 }
 // part: float [P][LN_MAX_SLABS][2][d] (scratch)
 hipError_t layernorm_param_grad(const bf16_t* dy, const bf16_t* x, const float* mean, const float* rstd, int P, int rows, int d,
@@ -341,7 +349,7 @@ hipError_t layernorm_param_grad(const bf16_t* dy, const bf16_t* x, const float* 
   const int rows_per_slab = (rows + n_slabs - 1) / n_slabs;
   hipLaunchKernelGGL(layernorm_param_grad_kernel, dim3((d + 63) / 64, n_slabs, P), dim3(256), 0, s, dy, x, mean, rstd, rows, d,
                      rows_per_slab, part);
-  hipLaunchKernelGGL(layernorm_param_combine_kernel, dim3((2 * d + 255) / 256, P), dim3(256), 0, s, part, n_slabs, d, G, stride, g_off, b_off);
+  hipLaunchKernelGGL(layernorm_param_combine_kernel, dim3((2 * d + 63) / 64, P), dim3(256), 0, s, part, n_slabs, d, G, stride, g_off, b_off);
   return hipGetLastError();
 }
 
@@ -466,7 +474,7 @@ hipError_t layernorm_bwd_with_param_grad(const bf16_t* dy, const bf16_t* x, cons
     hipLaunchKernelGGL(layernorm_bwd_fused_kernel<4>, grid, dim3(256), lds, s, dy, x, mean, rstd, rows, d, rows_per_slab, W32, stride, g_off, res, out, part, out2, drop);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(layernorm_param_combine_kernel, dim3((2 * d + 255) / 256, P), dim3(256), 0, s, part, n_slabs, d, G, stride, g_off, b_off);
+  hipLaunchKernelGGL(layernorm_param_combine_kernel, dim3((2 * d + 63) / 64, P), dim3(256), 0, s, part, n_slabs, d, G, stride, g_off, b_off);
   return hipGetLastError();
 }
 
@@ -528,16 +536,21 @@ __global__ __launch_bounds__(256) void softmax_fwd_kernel(const bf16_t* __restri
 #pragma unroll
       for (int k = 0; k < 4; ++k) if (c + k <= t) p[k] = expf(v[k] * scale - mx) * inv;
     }
-    drop_factors4(d, dr, i, site, (uint32_t)(((uint64_t)r * S + c) >> 2), f);
     *reinterpret_cast<uint2*>(pq + base + c) = pack4(p);
+    // (beyond the diagonal p is zero whatever the keep factors are: no Philox call for those groups)
+    if (c <= t) {
+      drop_factors4(d, dr, i, site, (uint32_t)(((uint64_t)r * S + c) >> 2), f);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) p[k] *= f[k];
+      for (int k = 0; k < 4; ++k) p[k] *= f[k];
+    }
     *reinterpret_cast<uint2*>(pd + base + c) = pack4(p);
   }
 }
 
-// ds = p (dp - sum_c dp p) * scale with dp = dpd * keep; in place over dpd.
-template <int LPR>
+// ds = p (dp - sum_c dp p) * scale with dp = dpd * keep; in place over dpd.  NG = groups of four keys per lane
+// (S <= 4 NG LPR): the lane's part of the row (p and dp) stays in registers between the dot product and the
+// result, so every keep factor is drawn once.
+template <int LPR, int NG>
 __global__ __launch_bounds__(256) void softmax_bwd_kernel(const bf16_t* __restrict__ pq, bf16_t* __restrict__ dpd, int64_t rows_per_member,
                                                           int S, float scale, DropArgs d, int site) {
   constexpr int RPW = 64 / LPR;
@@ -549,27 +562,32 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(const bf16_t* __restri
   const int64_t base = ((int64_t)i * rows_per_member + r) * S;
   const DropRate dr = drop_rate(d.H, d.n_hyper, d.col, i, d.active);
   // p is zero beyond the diagonal, so the dot product and the non-zero results stop there
+  float p[NG][4], dp[NG][4];
   float dot = 0.f;
-  for (int c = l * 4; c <= t; c += LPR * 4) {
-    float p[4], g[4], f[4];
-    unpack4(*reinterpret_cast<const uint2*>(pq + base + c), p);
-    unpack4(*reinterpret_cast<const uint2*>(dpd + base + c), g);
-    drop_factors4(d, dr, i, site, (uint32_t)(((uint64_t)r * S + c) >> 2), f);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) dot = fmaf(g[k] * f[k], p[k], dot);
-  }
-  dot = group_sum<LPR>(dot);
-  for (int c = l * 4; c < S; c += LPR * 4) {
-    float o[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int j = 0; j < NG; ++j) {
+    const int c = (l + j * LPR) * 4;
     if (c <= t) {
-      float p[4], g[4], f[4];
-      unpack4(*reinterpret_cast<const uint2*>(pq + base + c), p);
+      float g[4], f[4];
+      unpack4(*reinterpret_cast<const uint2*>(pq + base + c), p[j]);
       unpack4(*reinterpret_cast<const uint2*>(dpd + base + c), g);
       drop_factors4(d, dr, i, site, (uint32_t)(((uint64_t)r * S + c) >> 2), f);
 #pragma unroll
-      for (int k = 0; k < 4; ++k) o[k] = p[k] * (g[k] * f[k] - dot) * scale;
+      for (int k = 0; k < 4; ++k) { dp[j][k] = g[k] * f[k]; dot = fmaf(dp[j][k], p[j][k], dot); }
     }
-    *reinterpret_cast<uint2*>(dpd + base + c) = pack4(o);
+  }
+  dot = group_sum<LPR>(dot);
+#pragma unroll
+  for (int j = 0; j < NG; ++j) {
+    const int c = (l + j * LPR) * 4;
+    if (c < S) {
+      float o[4] = {0.f, 0.f, 0.f, 0.f};
+      if (c <= t) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = p[j][k] * (dp[j][k] - dot) * scale;
+      }
+      *reinterpret_cast<uint2*>(dpd + base + c) = pack4(o);
+    }
   }
 }
 
@@ -578,10 +596,12 @@ static void launch_softmax(bool fwd, const bf16_t* a, bf16_t* b, bf16_t* c, int 
   const int64_t rows_per_block = 4 * (64 / LPR);
   const dim3 grid((unsigned)((rows + rows_per_block - 1) / rows_per_block), P);
   if (fwd) hipLaunchKernelGGL(softmax_fwd_kernel<LPR>, grid, dim3(256), 0, s, a, rows, S, scale, d, site, b, c);
-  else hipLaunchKernelGGL(softmax_bwd_kernel<LPR>, grid, dim3(256), 0, s, a, b, rows, S, scale, d, site);
+  else if (S <= 4 * LPR) hipLaunchKernelGGL((softmax_bwd_kernel<LPR, 1>), grid, dim3(256), 0, s, a, b, rows, S, scale, d, site);
+  else if (S <= 16 * LPR) hipLaunchKernelGGL((softmax_bwd_kernel<LPR, 4>), grid, dim3(256), 0, s, a, b, rows, S, scale, d, site);
+  else hipLaunchKernelGGL((softmax_bwd_kernel<LPR, 16>), grid, dim3(256), 0, s, a, b, rows, S, scale, d, site);
 }
 static hipError_t softmax_dispatch(bool fwd, const bf16_t* a, bf16_t* b, bf16_t* c, int P, int64_t rows, int S, float scale, const DropArgs& d, int site, hipStream_t s) {
-  if (S % 4) return hipErrorInvalidValue;
+  if (S % 4 || S > 4096) return hipErrorInvalidValue;   // (the backward kernel keeps a row in registers: at most 16 groups of four keys per lane)
   if (S <= 64) launch_softmax<16>(fwd, a, b, c, P, rows, S, scale, d, site, s);
   else if (S <= 128) launch_softmax<32>(fwd, a, b, c, P, rows, S, scale, d, site, s);
   else launch_softmax<64>(fwd, a, b, c, P, rows, S, scale, d, site, s);
