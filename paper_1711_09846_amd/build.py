@@ -11,7 +11,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpbt.so")
-SOURCES = ["abi.hip", "gemm.hip", "kernels.hip", "fused_small.hip", "head.hip", "gan_host.hip", "a2c_host.hip", "transformer_kernels.hip", "transformer_host.hip"]
+SOURCES = ["abi.hip", "gemm.hip", "kernels.hip", "fused_small.hip", "head.hip", "gan_host.hip", "a2c_host.hip", "transformer_kernels.hip", "attention.hip", "transformer_host.hip"]
 # -packed-fp32-ops off: scalar float code must not be turned into packed FP32 instructions.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -32,6 +32,21 @@ __device__ __forceinline__ bf16_t d2bf(double v) {
   return f2bf(f);
 }
 
+// bf16(x * s) with a single round-to-nearest-even of the exact product, in float arithmetic: hi = fl(x s) and the
+// exact remainder lo = x s - hi (one fma).  Rounding hi to bf16 can only differ from rounding the exact product
+// when hi sits exactly half way between two bf16 values; the sign of lo then says on which side the product lies.
+// (Products so small that lo could underflow take the double route.)
+__device__ __forceinline__ bf16_t bf16_times_float(bf16_t x, float s) {
+  const float xf = bf2f(x);
+  const float hi = xf * s;
+  const uint32_t b = __float_as_uint(hi);
+  if ((b & 0xffffu) != 0x8000u) return f2bf(hi);
+  if ((b & 0x7f800000u) < (40u << 23)) return d2bf((double)xf * (double)s);
+  const float lo = fmaf(xf, s, -hi);
+  if (lo == 0.f) return f2bf(hi);                                  // a true tie: to even
+  const bool away = (lo > 0.f) == (hi > 0.f);                      // the product is larger in magnitude than hi
+  return (bf16_t)((b >> 16) + (away ? 1u : 0u));
+}
 
 enum { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2, ACT_LEAKY_RELU = 3, ACT_TANH = 4 };
 

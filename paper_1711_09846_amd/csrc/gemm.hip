@@ -34,8 +34,10 @@ hipError_t gemm_bias_f32(const GemmOperands& o, const float* bias, int64_t sbias
   return run(o, EpiBiasF32{bias, sbias, C, ldc, sc}, s);
 }
 hipError_t gemm_bias_act(const GemmOperands& o, const float* bias, int64_t sbias, bf16_t* Z, bf16_t* Aout, int64_t ld,
-                         int64_t so, int act, hipStream_t s) {
-  return run(o, EpiBiasAct{bias, sbias, Z, Aout, ld, so, act}, s);
+                         int64_t so, int act, hipStream_t s, const DropSite& site) {
+  if (!site.record) return run(o, EpiBiasAct{bias, sbias, Z, Aout, ld, so, act}, s);
+  if (Z || o.N % 8 || ld % 8 || so % 8 || sbias % 4 || (reinterpret_cast<uintptr_t>(bias) & 15)) return hipErrorInvalidValue;
+  return run(o, EpiBiasActDrop{bias, sbias, Aout, ld, so, act, site.record, site.record_stride, site.args, site.site}, s);
 }
 hipError_t gemm_dgrad_act(const GemmOperands& o, const bf16_t* Zprev, bf16_t* dZ, int64_t ld, int64_t so, int act,
                           hipStream_t s, const DropRecord& drop) {

@@ -21,6 +21,7 @@
 #include <type_traits>
 
 #include "common.h"
+#include "dropout.h"
 #include "optim_math.h"
 
 namespace pbt {
@@ -401,13 +402,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_bf16_kernel(GemmArgs g, Epi
         if (i + 1 < TM && m + 32 < g.M && n < g.N) pre[q] = epi.fetch(m + 32, n, g.N - n < 4 ? g.N - n : 4);
       }
     } else {
-      uint4 rund[32 * RUNS / 64];
+      typename Epilogue::RunData rund[32 * RUNS / 64];
       if constexpr (Epilogue::HAS_RUNDATA) {
 #pragma unroll
         for (int q = 0; q < 32 * RUNS / 64; ++q) {
           const int run = q * 64 + lane;
           const int m = m0 + wm * (BM / WM) + i * 32 + run / RUNS, n = n0 + wn * WCOLS + (run % RUNS) * 8;
-          rund[q] = make_uint4(0, 0, 0, 0);
+          rund[q] = typename Epilogue::RunData{};
           if (m < g.M && n < g.N) rund[q] = epi.load_run(m, n, g.N - n < 8 ? g.N - n : 8);
         }
       }
@@ -470,6 +471,7 @@ struct EpiStoreF32 {
   static constexpr bool HAS_COLS = false;
   static constexpr bool HAS_RUNDATA = false;
   struct Fetched {};
+  struct RunData {};
   float* C;
   int64_t ldc, sc;
   __device__ __forceinline__ void begin(int member) { C += (int64_t)member * sc; }
@@ -491,6 +493,7 @@ struct EpiStoreBF16 {
   static constexpr bool HAS_COLS = false;
   static constexpr bool HAS_RUNDATA = false;
   struct Fetched {};
+  struct RunData {};
   bf16_t* C;
   int64_t ldc, sc;
   int inner = 1;       // two-level batch index as in GemmArgs
@@ -501,7 +504,8 @@ struct EpiStoreBF16 {
   }
 };
 
-// Output layer over a large vocabulary: logits = acc + b[n], kept in float.
+// Output layer over a large vocabulary: logits = acc + b[n], kept in float.  (Streaming stores for the logits made
+// this launch 4 % faster and the two that follow it slower by more: plain stores.)
 struct EpiBiasF32 {
   static constexpr bool HAS_FINISH = false;
   static constexpr bool PREFETCH = false;
@@ -509,6 +513,7 @@ struct EpiBiasF32 {
   static constexpr bool HAS_COLS = true;
   static constexpr bool HAS_RUNDATA = false;
   struct Fetched {};
+  struct RunData {};
   const float* bias;
   int64_t sbias;
   float* C;
@@ -545,6 +550,7 @@ struct EpiBiasAct {
   static constexpr bool HAS_COLS = true;
   static constexpr bool HAS_RUNDATA = false;
   struct Fetched {};
+  struct RunData {};
   const float* bias;  // + member * sbias + n
   int64_t sbias;
   bf16_t* Z;
@@ -577,6 +583,58 @@ struct EpiBiasAct {
   }
 };
 
+// Forward layer followed by a dropout site: the stored activation is act(acc + b[n]), rounded, times the keep factor
+// of its element (Philox block (m ld + n) / 4 of the site, as the stand-alone dropout kernel draws it), rounded
+// again; the keep bits go to the site's record (bit e % 8 of byte e / 8 of the member's [rows][ld] array).  N and ld
+// are multiples of 8.  (A functor of its own: inside EpiBiasAct the extra state cost the 256x256 kernel its
+// registers, 156 -> 860 us per launch.)
+struct EpiBiasActDrop {
+  static constexpr bool HAS_FINISH = false;
+  static constexpr bool PREFETCH = false;
+  static constexpr bool COLSUM = false;
+  static constexpr bool HAS_COLS = true;
+  static constexpr bool HAS_RUNDATA = false;
+  struct Fetched {};
+  struct RunData {};
+  const float* bias;
+  int64_t sbias;
+  bf16_t* Aout;
+  int64_t ld, so;
+  int act;
+  uint8_t* rec;
+  int64_t rec_stride;   // bytes of record per member
+  DropArgs drop;
+  int site;
+  int member_ = 0;
+  DropRate rate = {0u, 1.f};
+  __device__ __forceinline__ void begin(int member) {
+    bias += (int64_t)member * sbias;
+    Aout += (int64_t)member * so;
+    rec += (int64_t)member * rec_stride;
+    rate = drop_rate(drop.H, drop.n_hyper, drop.col, member, drop.active);
+    member_ = member;
+  }
+  __device__ __forceinline__ void load_cols(int n, int N, float* b) const {
+    const float4 lo = *reinterpret_cast<const float4*>(bias + n), hi = *reinterpret_cast<const float4*>(bias + n + 4);
+    b[0] = lo.x; b[1] = lo.y; b[2] = lo.z; b[3] = lo.w; b[4] = hi.x; b[5] = hi.y; b[6] = hi.z; b[7] = hi.w;
+  }
+  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int, const float* b) const {
+    float z[8], a[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) z[e] = v[e] + b[e];
+    act_fwd8(z, a, act);
+    const int64_t o = (int64_t)m * ld + n;
+    const uint32_t b0 = drop_bits4(drop, rate, member_, site, (uint32_t)(o >> 2)), b1 = drop_bits4(drop, rate, member_, site, (uint32_t)(o >> 2) + 1u);
+    const uint32_t bits = b0 | (b1 << 4);
+    bf16_t out[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) out[e] = (bits >> e) & 1u ? bf16_times_float(f2bf(a[e]), rate.scale) : (bf16_t)(f2bf(a[e]) & 0x8000u);
+    *reinterpret_cast<uint4*>(Aout + o) = make_uint4(out[0] | ((uint32_t)out[1] << 16), out[2] | ((uint32_t)out[3] << 16),
+                                                     out[4] | ((uint32_t)out[5] << 16), out[6] | ((uint32_t)out[7] << 16));
+    rec[o >> 3] = (uint8_t)bits;
+  }
+};
+
 // Input gradient: dz_prev = acc * act'(z_prev), bf16.  With a dropout record (mask != null) the result is then
 // multiplied by the keep factor of the site that followed the activation in the forward pass: the value is
 // rounded to bf16, multiplied by 0 or by the member's scale (the float nearest 1 / (1 - p), p from column col
@@ -589,6 +647,7 @@ struct EpiDgradAct {
   static constexpr bool HAS_COLS = false;
   static constexpr bool HAS_RUNDATA = true;
   struct Fetched {};
+  struct RunData { uint4 z = {0u, 0u, 0u, 0u}; uint32_t bits = 0u; };
   const bf16_t* Zprev;
   bf16_t* dZ;
   int64_t ld, so;
@@ -606,28 +665,30 @@ struct EpiDgradAct {
       scale = p > 0.f ? (float)(1.0 / (1.0 - (double)p)) : 1.f;
     }
   }
-  // the run of z the result is scaled by: requested for all runs of a strip before the first is applied
-  // (read inside apply8, after the store of the run before, every run paid a memory latency of its own)
-  __device__ __forceinline__ uint4 load_run(int m, int n, int count) const {
+  // the run of z the result is scaled by (and the run's eight record bits): requested for all runs of a strip
+  // before the first is applied (read inside apply8, after the store of the run before, every run paid a memory
+  // latency of its own)
+  __device__ __forceinline__ RunData load_run(int m, int n, int count) const {
     const int64_t o = (int64_t)m * ld + n;
-    if (count == 8 && aligned16(Zprev + o)) return *reinterpret_cast<const uint4*>(Zprev + o);
+    RunData r;
+    r.bits = mask ? mask[o >> 3] : 0u;   // (the launcher only attaches a record to arrays whose rows are whole runs of eight)
+    if (count == 8 && aligned16(Zprev + o)) { r.z = *reinterpret_cast<const uint4*>(Zprev + o); return r; }
     uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int e = 0; e < 8; ++e)
       if (e < count) w[e >> 1] |= (uint32_t)Zprev[o + e] << (16 * (e & 1));
-    return make_uint4(w[0], w[1], w[2], w[3]);
+    r.z = make_uint4(w[0], w[1], w[2], w[3]);
+    return r;
   }
-  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count, uint4 zrun) const {
+  __device__ __forceinline__ void apply8(int, int m, int n, const float* v, int count, const RunData& run) const {
     const int64_t o = (int64_t)m * ld + n;
     float z[8], d[8];
-    unpack_bf16x8(zrun, z);
+    unpack_bf16x8(run.z, z);
     act_bwd_scale8(v, z, d, act);
     if (mask) {
-      // (the launcher only attaches a record to arrays whose rows are whole runs of eight)
-      const uint32_t bits = mask[o >> 3];
       bf16_t out[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) out[e] = (bits >> e) & 1u ? d2bf((double)bf2f(f2bf(d[e])) * (double)scale) : (bf16_t)(f2bf(d[e]) & 0x8000u);  // x * 0 keeps the sign
+      for (int e = 0; e < 8; ++e) out[e] = (run.bits >> e) & 1u ? bf16_times_float(f2bf(d[e]), scale) : (bf16_t)(f2bf(d[e]) & 0x8000u);  // x * 0 keeps the sign
       *reinterpret_cast<uint4*>(dZ + o) = make_uint4(out[0] | ((uint32_t)out[1] << 16), out[2] | ((uint32_t)out[3] << 16),
                                                      out[4] | ((uint32_t)out[5] << 16), out[6] | ((uint32_t)out[7] << 16));
       return;
@@ -648,6 +709,7 @@ struct EpiOptimizer {
   static constexpr bool HAS_COLS = false;
   static constexpr bool HAS_RUNDATA = false;
   struct Fetched { float w[4], s0[4], s1[4]; };  // one run of theta and its state, read ahead of use
+  struct RunData {};
   float* W32; float* S0; float* S1; bf16_t* W16;
   int64_t stride, off, ldc;   // member stride, offset of the matrix in the member's vector, row pitch
   OptHyper hy;
@@ -721,6 +783,8 @@ inline GemmTile choose_tile(int M, int N, int K, int batch) {
   // left in the caches, the same launches came out 9 % slower (forward class 206 -> 225 us, step +0.6 ms; for the
   // feed-forward layers alone +0.8 ms, for the vocabulary head alone +0.15 ms).
   if (K >= 1024 && M > 128 && N > 128 && tile_count(M, N, batch, 256, 256) >= CUS * 3 / 4) return TILE_256x256;
+  // (double-buffered 128x128 and 128x64 variants were tried for the long, narrow weight gradients (K >= 2048 with at
+  // most two tiles per compute unit) and for all 128x128 launches: no change for the former, 3 % slower for the latter)
   if ((tile_count(M, N, batch, 128, 128) < 4 * CUS && N > 64) || (N <= 64 && N > 32)) return TILE_128x64;
   return TILE_128x128;
 }
@@ -763,6 +827,7 @@ struct EpiRbfSum {
   static constexpr bool HAS_COLS = false;
   static constexpr bool HAS_RUNDATA = false;
   struct Fetched {};
+  struct RunData {};
   __device__ __forceinline__ void begin(int member) { na += (int64_t)member * sna; nb += (int64_t)member * snb; }
   const float* na;  // squared norms of the A rows, + member * sna
   int64_t sna;

@@ -155,7 +155,7 @@ __global__ __launch_bounds__(NTL_THREADS) void gemm_nt_lds_kernel(GemmArgs g, Ep
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    uint4 rund[32 * RUNS / 64];
+    typename Epilogue::RunData rund[32 * RUNS / 64];
     if constexpr (Epilogue::HAS_RUNDATA) {
 #pragma unroll
       for (int q = 0; q < 32 * RUNS / 64; ++q) {

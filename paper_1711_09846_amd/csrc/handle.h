@@ -59,6 +59,9 @@ struct TfPlan {
   size_t o_u[PBT_MAX_DIMS], o_qkv[PBT_MAX_DIMS], o_pq[PBT_MAX_DIMS], o_pd[PBT_MAX_DIMS], o_o[PBT_MAX_DIMS];
   size_t o_u2[PBT_MAX_DIMS], o_z1[PBT_MAX_DIMS], o_fd[PBT_MAX_DIMS];
   size_t o_mask[PBT_MAX_DIMS][3];   // keep bits of the block's three dropout sites outside attention
+  bool fused_attn;                  // one attention kernel per pass: no score / probability arrays, o_keep instead
+  size_t o_keep[PBT_MAX_DIMS];      // keep bits of the attention dropout site (fused attention only)
+  size_t o_attn_stats;              // softmax row statistics between the two backward kernels (fused attention only)
   size_t o_score, o_tmp_d[3], o_tmp_f[2], o_dqkv, o_uf, o_logits, o_dlogits, o_rowloss, o_evalrow, o_tokstart, o_tokcursor, o_tokorder, o_lnpart;
 };
 

@@ -27,8 +27,17 @@ hipError_t gemm_store_bf16_heads(const GemmOperands& o, bf16_t* C, int64_t ldc, 
 // C (float) = acc + bias
 hipError_t gemm_bias_f32(const GemmOperands& o, const float* bias, int64_t sbias, float* C, int64_t ldc, int64_t sc, hipStream_t s);
 // z = acc + bias; Z (may be null) <- z, Aout <- act(z); both [batch][M][ld] bf16 with batch stride so
+struct DropArgs {  // where a kernel finds the member's dropout rate and the Philox counter base
+  const float* H; int n_hyper; int col;  // column of H holding the rate, -1 = no dropout
+  int active;                            // 0 = eval: keep everything
+  uint32_t c0; uint64_t seed;            // step index, Philox key
+};
+// a dropout site applied by the kernel that produces the site's input: Philox site number, where the keep bits go
+// (one bit per element of the member's array, record_stride bytes per member; null = no dropout here)
+struct DropSite { DropArgs args = {}; int site = 0; uint8_t* record = nullptr; int64_t record_stride = 0; };
+// (with a site: N, ld and so multiples of 8; Aout receives act(z), rounded, times the keep factors, rounded)
 hipError_t gemm_bias_act(const GemmOperands& o, const float* bias, int64_t sbias, bf16_t* Z, bf16_t* Aout, int64_t ld,
-                         int64_t so, int act, hipStream_t s);
+                         int64_t so, int act, hipStream_t s, const DropSite& site = DropSite());
 // dZ <- acc * act'(Zprev); with a dropout record (drop.mask != null; needs N and ld multiples of 8) the result is
 // rounded and then multiplied by the recorded keep factors of the member (rate in column drop.col of drop.H)
 struct DropRecord { const uint8_t* mask = nullptr; int64_t mask_stride = 0; const float* H = nullptr; int n_hyper = 0, col = -1; };
@@ -117,11 +126,6 @@ hipError_t mmd_combine(const float* pxx, int txx, const float* pyy, int tyy, con
                        float* score, hipStream_t s);
 
 // ---- transformer_kernels.hip ------------------------------------------------------------------
-struct DropArgs {  // where a kernel finds the member's dropout rate and the Philox counter base
-  const float* H; int n_hyper; int col;  // column of H holding the rate, -1 = no dropout
-  int active;                            // 0 = eval: keep everything
-  uint32_t c0; uint64_t seed;            // step index, Philox key
-};
 hipError_t embed_fwd(const int32_t* pool, int n_pool, int S, int B, int d, int V, int P, const bf16_t* W16, int64_t stride,
                      int64_t tok_off, int64_t pos_off, uint32_t c0, uint64_t seed, int draw, bf16_t* h, int32_t* tokens,
                      int32_t* targets, int32_t* t, hipStream_t s);
@@ -146,6 +150,23 @@ hipError_t softmax_fwd(const bf16_t* sc, int P, int64_t rows, int S, float scale
                        bf16_t* pd, hipStream_t s);
 hipError_t softmax_bwd(const bf16_t* pq, bf16_t* dpd, int P, int64_t rows, int S, float scale, const DropArgs& d, int site,
                        hipStream_t s);
+// h = res + x * keep and y = LayerNorm(h) in one pass (d <= 2048, rows * d a multiple of 16); record as dropout_apply's mask_out
+hipError_t residual_dropout_layernorm(const bf16_t* x, const bf16_t* res, int P, int rows, int d, const DropArgs& dr, int site, bf16_t* h,
+                                      uint16_t* record, const float* W32, int64_t stride, int64_t g_off, int64_t b_off, bf16_t* y, float* mean,
+                                      float* rstd, hipStream_t s);
+// Attention of one (member, sequence, head) per workgroup without score or probability arrays in memory, for
+// 64-wide heads and sequences of 32, 64, 96 or 128 positions (attention_fused_applies).  qkv: [P][Bc*S][3d]
+// (queries, keys, values side by side, heads side by side inside each); o, dO: [P][Bc*S][d]; dqkv like qkv.
+// The forward pass leaves the keep bits of its dropout site in `record` (attention_record_bytes; null = not
+// wanted); the backward pass (two kernels: dQ, then dK and dV) needs them and attention_stats_bytes of scratch.
+constexpr int ATTN_FUSED_HEAD = 64, ATTN_FUSED_MAX_SEQ = 128;
+bool attention_fused_applies(int d_model, int heads, int seq);
+size_t attention_record_bytes(int P, int Bc, int heads);
+size_t attention_stats_bytes(int P, int Bc, int heads);
+hipError_t attention_fwd(const bf16_t* qkv, int P, int Bc, int S, int d, int H, float scale, const DropArgs& dr, int site, bf16_t* o,
+                         uint32_t* record, hipStream_t s);
+hipError_t attention_bwd(const bf16_t* qkv, const bf16_t* dO, int P, int Bc, int S, int d, int H, float scale, const DropArgs& dr,
+                         const uint32_t* record, float* stats, bf16_t* dqkv, hipStream_t s);
 // out = x * keep (+ res); mask_out (optional) receives the keep bits, mask_in (optional) supplies them (the
 // backward pass of a site reads what its forward pass recorded); dropout_mask_bytes sizes such a record
 hipError_t dropout_apply(const bf16_t* x, const bf16_t* res, int P, int64_t per_member, const DropArgs& d, int site, bf16_t* out,

@@ -14,19 +14,23 @@ namespace pbt {
 namespace {
 
 struct Dim { int V, d, H, dh, f, S, L; };
+// LayerNorm, dropout and residual steps ride on neighbouring kernels when a row fits the fused kernels' registers
+// and the keep-bit records are whole bytes per row
+bool tf_fused_elementwise(const pbt_config& c) { return c.tf_d_model <= 2048 && c.tf_d_model % 16 == 0 && c.tf_d_ff % 16 == 0; }
 Dim dim_of(const pbt_config& c) { return Dim{c.tf_vocab, c.tf_d_model, c.tf_heads, c.tf_d_model / c.tf_heads, c.tf_d_ff, c.tf_seq, c.n_layers}; }
 
 struct Ctx {
   pbt_handle* h; hipStream_t s; Dim D; int P, Bc, n;  // Bc sequences per member in this pass, n = Bc * S rows
   int64_t S_; const float* W32; const bf16_t* W16; float* G;
-  bool fused_bwd;   // LayerNorm backward + its parameter gradients + the next dropout site's backward in one kernel (d_model <= 2048)
+  bool fused_bwd;   // elementwise steps ride on neighbouring kernels (tf_fused_elementwise): residual + dropout + LayerNorm forward in one kernel, hidden-layer dropout in its GEMM, LayerNorm backward + parameter gradients + the next dropout site in one kernel
   template <class T> T* sc(size_t off) const { return h->sc<T>(off); }
 };
 
 // out[P][n][N] = act(in[P][n][K] W[K][N] + b)
-pbt_status dense(const Ctx& x, const bf16_t* in, int K, int N, int64_t w, int64_t b, bf16_t* Z, bf16_t* out, int act) {
+pbt_status dense(const Ctx& x, const bf16_t* in, int K, int N, int64_t w, int64_t b, bf16_t* Z, bf16_t* out, int act,
+                 const DropSite& site = DropSite()) {
   GemmOperands o{in, K, (int64_t)x.n * K, false, x.W16 + w, N, x.S_, false, x.n, N, K, x.P};
-  PBT_LAUNCH(x.h, PBT_K_GEMM_FWD, x.s, gemm_bias_act(o, x.W32 + b, x.S_, Z, out, N, (int64_t)x.n * N, act, x.s));
+  PBT_LAUNCH(x.h, PBT_K_GEMM_FWD, x.s, gemm_bias_act(o, x.W32 + b, x.S_, Z, out, N, (int64_t)x.n * N, act, x.s, site));
   return PBT_OK;
 }
 // G[w] = in^T dout, G[b] = column sums of dout
@@ -100,24 +104,49 @@ pbt_status forward(const Ctx& x, const int32_t* pool, int n_pool, uint32_t c0, i
     bf16_t* pq = x.sc<bf16_t>(t.o_pq[l]);
     bf16_t* pd = x.sc<bf16_t>(t.o_pd[l]);
     bf16_t* o = x.sc<bf16_t>(t.o_o[l]);
-    PBT_HIP(h, layernorm_fwd(hin, x.P, x.n, D.d, x.W32, x.S_, b.ln1g, b.ln1b, u, x.sc<float>(t.o_mean1[l]), x.sc<float>(t.o_rstd1[l]), x.s));
+    // (on the fused path the LayerNorm at the head of a block rides on the kernel that closes the block before it)
+    if (!x.fused_bwd || l == 0)
+      PBT_HIP(h, layernorm_fwd(hin, x.P, x.n, D.d, x.W32, x.S_, b.ln1g, b.ln1b, u, x.sc<float>(t.o_mean1[l]), x.sc<float>(t.o_rstd1[l]), x.s));
     TF_TRY(dense(x, u, D.d, 3 * D.d, b.wqkv, b.bqkv, nullptr, qkv, PBT_ACT_NONE));
-    TF_TRY(attn_gemm(x, in_rows(qkv, 0, 3 * D.d, D), false, in_rows(qkv, D.d, 3 * D.d, D), true, in_scores(score, D), D.S, D.S, D.dh));
-    PBT_HIP(h, softmax_fwd(score, x.P, (int64_t)x.Bc * D.H * D.S, D.S, 1.f / sqrtf((float)D.dh), dr, 4 * l + 0, pq, pd, x.s));
-    TF_TRY(attn_gemm(x, in_scores(pd, D), false, in_rows(qkv, 2 * D.d, 3 * D.d, D), false, in_rows(o, 0, D.d, D), D.S, D.dh, D.S));
+    if (t.fused_attn) {
+      PBT_LAUNCH(h, PBT_K_HEAD, x.s, attention_fwd(qkv, x.P, x.Bc, D.S, D.d, D.H, 1.f / sqrtf((float)D.dh), dr, 4 * l + 0, o,
+                                                   train ? x.sc<uint32_t>(t.o_keep[l]) : nullptr, x.s));
+    } else {
+      TF_TRY(attn_gemm(x, in_rows(qkv, 0, 3 * D.d, D), false, in_rows(qkv, D.d, 3 * D.d, D), true, in_scores(score, D), D.S, D.S, D.dh));
+      PBT_HIP(h, softmax_fwd(score, x.P, (int64_t)x.Bc * D.H * D.S, D.S, 1.f / sqrtf((float)D.dh), dr, 4 * l + 0, pq, pd, x.s));
+      TF_TRY(attn_gemm(x, in_scores(pd, D), false, in_rows(qkv, 2 * D.d, 3 * D.d, D), false, in_rows(o, 0, D.d, D), D.S, D.dh, D.S));
+    }
     TF_TRY(dense(x, o, D.d, D.d, b.wo, b.bo, nullptr, tmp_d, PBT_ACT_NONE));
-    PBT_HIP(h, dropout_apply(tmp_d, hin, x.P, per_d, dr, 4 * l + 1, hmid, x.s, nullptr, x.sc<uint16_t>(t.o_mask[l][0])));
     bf16_t* u2 = x.sc<bf16_t>(t.o_u2[l]);
+    bf16_t* fd = x.sc<bf16_t>(t.o_fd[l]);
+    if (x.fused_bwd) {
+      // residual + dropout + the next LayerNorm in one kernel; the feed-forward hidden layer's dropout in the epilogue of
+      // its GEMM (only the dropped-out activation is kept: it is positive exactly where the pre-activation is positive and
+      // the element was kept, and the backward pass multiplies by the keep factor anyway)
+      PBT_HIP(h, residual_dropout_layernorm(tmp_d, hin, x.P, x.n, D.d, dr, 4 * l + 1, hmid, x.sc<uint16_t>(t.o_mask[l][0]), x.W32, x.S_, b.ln2g,
+                                            b.ln2b, u2, x.sc<float>(t.o_mean2[l]), x.sc<float>(t.o_rstd2[l]), x.s));
+      DropSite site;
+      if (train) site = DropSite{dr, 4 * l + 2, x.sc<uint8_t>(t.o_mask[l][1]), (int64_t)dropout_mask_bytes(1, per_f)};
+      TF_TRY(dense(x, u2, D.d, D.f, b.w1, b.b1, nullptr, fd, PBT_ACT_RELU, site));
+      TF_TRY(dense(x, fd, D.f, D.d, b.w2, b.b2, nullptr, tmp_d, PBT_ACT_NONE));
+      const bool last = l + 1 == D.L;
+      const int64_t ng = last ? t.lnfg : t.blk[l + 1].ln1g, nb = last ? t.lnfb : t.blk[l + 1].ln1b;
+      PBT_HIP(h, residual_dropout_layernorm(tmp_d, hmid, x.P, x.n, D.d, dr, 4 * l + 3, hout, x.sc<uint16_t>(t.o_mask[l][2]), x.W32, x.S_, ng, nb,
+                                            last ? x.sc<bf16_t>(t.o_uf) : x.sc<bf16_t>(t.o_u[l + 1]),
+                                            x.sc<float>(last ? t.o_meanf : t.o_mean1[l + 1]), x.sc<float>(last ? t.o_rstdf : t.o_rstd1[l + 1]), x.s));
+      continue;
+    }
+    PBT_HIP(h, dropout_apply(tmp_d, hin, x.P, per_d, dr, 4 * l + 1, hmid, x.s, nullptr, x.sc<uint16_t>(t.o_mask[l][0])));
     PBT_HIP(h, layernorm_fwd(hmid, x.P, x.n, D.d, x.W32, x.S_, b.ln2g, b.ln2b, u2, x.sc<float>(t.o_mean2[l]), x.sc<float>(t.o_rstd2[l]), x.s));
     // only relu(z) is kept: it is positive exactly where z is, which is all the backward pass needs
     TF_TRY(dense(x, u2, D.d, D.f, b.w1, b.b1, nullptr, x.sc<bf16_t>(t.o_z1[l]), PBT_ACT_RELU));
-    PBT_HIP(h, dropout_apply(x.sc<bf16_t>(t.o_z1[l]), nullptr, x.P, per_f, dr, 4 * l + 2, x.sc<bf16_t>(t.o_fd[l]), x.s, nullptr,
-                             x.sc<uint16_t>(t.o_mask[l][1])));
-    TF_TRY(dense(x, x.sc<bf16_t>(t.o_fd[l]), D.f, D.d, b.w2, b.b2, nullptr, tmp_d, PBT_ACT_NONE));
+    PBT_HIP(h, dropout_apply(x.sc<bf16_t>(t.o_z1[l]), nullptr, x.P, per_f, dr, 4 * l + 2, fd, x.s, nullptr, x.sc<uint16_t>(t.o_mask[l][1])));
+    TF_TRY(dense(x, fd, D.f, D.d, b.w2, b.b2, nullptr, tmp_d, PBT_ACT_NONE));
     PBT_HIP(h, dropout_apply(tmp_d, hmid, x.P, per_d, dr, 4 * l + 3, hout, x.s, nullptr, x.sc<uint16_t>(t.o_mask[l][2])));
   }
   bf16_t* uf = x.sc<bf16_t>(t.o_uf);
-  PBT_HIP(h, layernorm_fwd(x.sc<bf16_t>(t.o_h[D.L]), x.P, x.n, D.d, x.W32, x.S_, t.lnfg, t.lnfb, uf, x.sc<float>(t.o_meanf), x.sc<float>(t.o_rstdf), x.s));
+  if (!x.fused_bwd)
+    PBT_HIP(h, layernorm_fwd(x.sc<bf16_t>(t.o_h[D.L]), x.P, x.n, D.d, x.W32, x.S_, t.lnfg, t.lnfb, uf, x.sc<float>(t.o_meanf), x.sc<float>(t.o_rstdf), x.s));
   GemmOperands o{uf, D.d, (int64_t)x.n * D.d, false, x.W16 + t.whead, D.V, x.S_, false, x.n, D.V, D.d, x.P};
   PBT_LAUNCH(h, PBT_K_GEMM_FWD, x.s, gemm_bias_f32(o, x.W32 + t.bhead, x.S_, x.sc<float>(t.o_logits), D.V, (int64_t)x.n * D.V, x.s));
   return PBT_OK;
@@ -126,7 +155,7 @@ pbt_status forward(const Ctx& x, const int32_t* pool, int n_pool, uint32_t c0, i
 Ctx make_ctx(pbt_handle* h, int Bc, hipStream_t s) {
   const Plan& p = h->plan;
   Ctx x{h, s, dim_of(h->cfg), h->cfg.P, Bc, Bc * h->cfg.tf_seq, p.lay.stride, h->st<float>(p.o_w32), h->st<bf16_t>(p.o_w16), h->sc<float>(p.o_grad), false};
-  x.fused_bwd = h->cfg.tf_d_model <= 2048;
+  x.fused_bwd = tf_fused_elementwise(h->cfg);
   return x;
 }
 
@@ -170,6 +199,7 @@ pbt_status tf_check_and_plan(const pbt_config* c, Plan* pl, Carver* w) {
   TfPlan& t = pl->tf;
   const Dim D{c->tf_vocab, c->tf_d_model, c->tf_heads, c->tf_d_model / c->tf_heads, c->tf_d_ff, c->tf_seq, c->n_layers};
   const size_t P = c->P, n = (size_t)c->batch * D.S;
+  t.fused_attn = attention_fused_applies(D.d, D.H, D.S);
   const size_t nd = P * n * D.d * 2, nf = P * n * D.f * 2, ns = P * (size_t)c->batch * D.H * D.S * D.S * 2;
   t.o_tokens = w->take(P * n * 4);
   t.o_targets = w->take(P * n * 4);
@@ -178,14 +208,22 @@ pbt_status tf_check_and_plan(const pbt_config* c, Plan* pl, Carver* w) {
     t.o_hmid[l] = w->take(nd);
     t.o_mean1[l] = w->take(P * n * 4); t.o_rstd1[l] = w->take(P * n * 4);
     t.o_mean2[l] = w->take(P * n * 4); t.o_rstd2[l] = w->take(P * n * 4);
-    t.o_u[l] = w->take(nd); t.o_qkv[l] = w->take(3 * nd); t.o_pq[l] = w->take(ns); t.o_pd[l] = w->take(ns); t.o_o[l] = w->take(nd);
-    t.o_u2[l] = w->take(nd); t.o_z1[l] = w->take(nf); t.o_fd[l] = w->take(nf);
+    t.o_u[l] = w->take(nd); t.o_qkv[l] = w->take(3 * nd); t.o_o[l] = w->take(nd);
+    if (t.fused_attn) {
+      t.o_keep[l] = w->take(attention_record_bytes((int)P, c->batch, D.H));
+      t.o_pq[l] = t.o_pd[l] = 0;
+    } else {
+      t.o_pq[l] = w->take(ns); t.o_pd[l] = w->take(ns);
+      t.o_keep[l] = 0;
+    }
+    t.o_u2[l] = w->take(nd); t.o_z1[l] = tf_fused_elementwise(*c) ? 0 : w->take(nf); t.o_fd[l] = w->take(nf);
     t.o_mask[l][0] = w->take(dropout_mask_bytes((int)P, (int64_t)n * D.d));
     t.o_mask[l][1] = w->take(dropout_mask_bytes((int)P, (int64_t)n * D.f));
     t.o_mask[l][2] = w->take(dropout_mask_bytes((int)P, (int64_t)n * D.d));
   }
   t.o_meanf = w->take(P * n * 4); t.o_rstdf = w->take(P * n * 4);
-  t.o_score = w->take(ns);
+  t.o_score = t.fused_attn ? 0 : w->take(ns);
+  t.o_attn_stats = t.fused_attn ? w->take(attention_stats_bytes((int)P, c->batch, D.H)) : 0;
   for (int k = 0; k < 3; ++k) t.o_tmp_d[k] = w->take(nd);
   for (int k = 0; k < 2; ++k) t.o_tmp_f[k] = w->take(nf);
   t.o_dqkv = w->take(3 * nd);
@@ -247,7 +285,7 @@ pbt_status tf_step(pbt_handle* h, const int32_t* pool, uint32_t step, hipStream_
     if (!fb) PBT_HIP(h, dropout_apply(dh, nullptr, x.P, per_d, dr, 4 * l + 3, dd, s, x.sc<uint16_t>(t.o_mask[l][2])));
     TF_TRY(wgrad(x, x.sc<bf16_t>(t.o_fd[l]), D.f, dd, D.d, b.w2, b.b2));
     if (fb) {
-      TF_TRY(dgrad(x, dd, D.d, D.f, b.w2, x.sc<bf16_t>(t.o_z1[l]), PBT_ACT_RELU, df1, record(l, 1, per_f)));
+      TF_TRY(dgrad(x, dd, D.d, D.f, b.w2, x.sc<bf16_t>(t.o_fd[l]), PBT_ACT_RELU, df1, record(l, 1, per_f)));   // (the forward pass kept no separate relu(z))
     } else {
       TF_TRY(dgrad(x, dd, D.d, D.f, b.w2, x.sc<bf16_t>(t.o_z1[l]), PBT_ACT_RELU, df0));
       PBT_HIP(h, dropout_apply(df0, nullptr, x.P, per_f, dr, 4 * l + 2, df1, s, x.sc<uint16_t>(t.o_mask[l][1])));
@@ -260,12 +298,17 @@ pbt_status tf_step(pbt_handle* h, const int32_t* pool, uint32_t step, hipStream_
     if (!fb) PBT_HIP(h, dropout_apply(dh2, nullptr, x.P, per_d, dr, 4 * l + 1, dd, s, x.sc<uint16_t>(t.o_mask[l][0])));
     TF_TRY(wgrad(x, x.sc<bf16_t>(t.o_o[l]), D.d, dd, D.d, b.wo, b.bo));
     TF_TRY(dgrad(x, dd, D.d, D.d, b.wo, nullptr, 0, du));  // du = gradient of the merged head outputs
-    const bf16_t* pd = x.sc<bf16_t>(t.o_pd[l]);
-    TF_TRY(attn_gemm(x, in_scores(pd, D), true, in_rows(du, 0, D.d, D), false, in_rows(dqkv, 2 * D.d, 3 * D.d, D), D.S, D.dh, D.S));           // dV = Pd^T dO
-    TF_TRY(attn_gemm(x, in_rows(du, 0, D.d, D), false, in_rows(qkv, 2 * D.d, 3 * D.d, D), true, in_scores(dscore, D), D.S, D.S, D.dh));          // dPd = dO V^T
-    PBT_HIP(h, softmax_bwd(x.sc<bf16_t>(t.o_pq[l]), dscore, x.P, (int64_t)x.Bc * D.H * D.S, D.S, att_scale, dr, 4 * l + 0, s));
-    TF_TRY(attn_gemm(x, in_scores(dscore, D), false, in_rows(qkv, D.d, 3 * D.d, D), false, in_rows(dqkv, 0, 3 * D.d, D), D.S, D.dh, D.S));       // dQ = dS K
-    TF_TRY(attn_gemm(x, in_scores(dscore, D), true, in_rows(qkv, 0, 3 * D.d, D), false, in_rows(dqkv, D.d, 3 * D.d, D), D.S, D.dh, D.S));        // dK = dS^T Q
+    if (t.fused_attn) {
+      PBT_LAUNCH(h, PBT_K_HEAD, s, attention_bwd(qkv, du, x.P, x.Bc, D.S, D.d, D.H, att_scale, dr, x.sc<uint32_t>(t.o_keep[l]),
+                                                 x.sc<float>(t.o_attn_stats), dqkv, s));
+    } else {
+      const bf16_t* pd = x.sc<bf16_t>(t.o_pd[l]);
+      TF_TRY(attn_gemm(x, in_scores(pd, D), true, in_rows(du, 0, D.d, D), false, in_rows(dqkv, 2 * D.d, 3 * D.d, D), D.S, D.dh, D.S));           // dV = Pd^T dO
+      TF_TRY(attn_gemm(x, in_rows(du, 0, D.d, D), false, in_rows(qkv, 2 * D.d, 3 * D.d, D), true, in_scores(dscore, D), D.S, D.S, D.dh));          // dPd = dO V^T
+      PBT_HIP(h, softmax_bwd(x.sc<bf16_t>(t.o_pq[l]), dscore, x.P, (int64_t)x.Bc * D.H * D.S, D.S, att_scale, dr, 4 * l + 0, s));
+      TF_TRY(attn_gemm(x, in_scores(dscore, D), false, in_rows(qkv, D.d, 3 * D.d, D), false, in_rows(dqkv, 0, 3 * D.d, D), D.S, D.dh, D.S));       // dQ = dS K
+      TF_TRY(attn_gemm(x, in_scores(dscore, D), true, in_rows(qkv, 0, 3 * D.d, D), false, in_rows(dqkv, D.d, 3 * D.d, D), D.S, D.dh, D.S));        // dK = dS^T Q
+    }
     TF_TRY(wgrad(x, x.sc<bf16_t>(t.o_u[l]), D.d, dqkv, 3 * D.d, b.wqkv, b.bqkv));
     TF_TRY(dgrad(x, dqkv, 3 * D.d, D.d, b.wqkv, nullptr, 0, du));
     const bool next = fb && l > 0;   // the block below starts with the backward of its feed-forward output site

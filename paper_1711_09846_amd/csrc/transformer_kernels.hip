@@ -13,33 +13,9 @@
 #include "common.h"
 #include "internal.h"
 #include "philox.h"
+#include "dropout.h"
 
 namespace pbt {
-
-struct DropRate { uint32_t thr; float scale; };
-
-__device__ __forceinline__ DropRate drop_rate(const float* H, int n_hyper, int col, int member, int active) {
-  DropRate r{0u, 1.f};
-  if (active && col >= 0) {
-    const float p = H[(int64_t)member * n_hyper + col];
-    if (p > 0.f) {
-      const double t = floor((double)p * 4294967296.0);
-      r.thr = t >= 4294967295.0 ? 4294967295u : (uint32_t)t;
-      r.scale = (float)(1.0 / (1.0 - (double)p));
-    }
-  }
-  return r;
-}
-
-// keep factors (0 or scale) of the four elements 4*blk .. 4*blk+3 of a site
-__device__ __forceinline__ void drop_factors4(const DropArgs& d, const DropRate& r, int member, int site, uint32_t blk, float* f) {
-  if (r.thr == 0u) { f[0] = f[1] = f[2] = f[3] = r.scale; return; }
-  const u32x4 w = philox4x32_10(d.c0, (uint32_t)member, (uint32_t)(DOMAIN_DROPOUT + site), blk, (uint32_t)d.seed, (uint32_t)(d.seed >> 32));
-  f[0] = w.x >= r.thr ? r.scale : 0.f;
-  f[1] = w.y >= r.thr ? r.scale : 0.f;
-  f[2] = w.z >= r.thr ? r.scale : 0.f;
-  f[3] = w.w >= r.thr ? r.scale : 0.f;
-}
 
 // tokens outside the vocabulary are mapped to its ends so that no table read leaves its array
 __device__ __forceinline__ int32_t clamp_token(int32_t tok, int V) { return tok < 0 ? 0 : tok >= V ? V - 1 : tok; }
@@ -632,13 +608,6 @@ __device__ __forceinline__ void dropout_group(uint2 xv, bool has_res, uint2 rv, 
   out->x = d2bf(v[0]) | ((uint32_t)d2bf(v[1]) << 16);
   out->y = d2bf(v[2]) | ((uint32_t)d2bf(v[3]) << 16);
 }
-// keep bits (bit k = element 4*blk + k kept) of one group, from the Philox words or, when the pass that made
-// them left them behind, from its record
-__device__ __forceinline__ uint32_t drop_bits4(const DropArgs& d, const DropRate& r, int member, int site, uint32_t blk) {
-  if (r.thr == 0u) return 15u;
-  const u32x4 w = philox4x32_10(d.c0, (uint32_t)member, (uint32_t)(DOMAIN_DROPOUT + site), blk, (uint32_t)d.seed, (uint32_t)(d.seed >> 32));
-  return (w.x >= r.thr ? 1u : 0u) | (w.y >= r.thr ? 2u : 0u) | (w.z >= r.thr ? 4u : 0u) | (w.w >= r.thr ? 8u : 0u);
-}
 __device__ __forceinline__ void bits_to_factors(uint32_t bits, float scale, float* f) {
 #pragma unroll
   for (int k = 0; k < 4; ++k) f[k] = (bits >> k) & 1u ? scale : 0.f;
@@ -705,6 +674,87 @@ hipError_t dropout_apply(const bf16_t* x, const bf16_t* res, int P, int64_t per_
   const int64_t threads = (per_member / 4 + DROP_GROUPS - 1) / DROP_GROUPS;
   hipLaunchKernelGGL(dropout_kernel, dim3((unsigned)((threads + 255) / 256), P), dim3(256), 0, s, x, res, per_member, d, site, out,
                      mask_in, mask_out);
+  return hipGetLastError();
+}
+
+// h = res + x * keep (one rounding, as dropout_kernel) followed by the LayerNorm of h, in one pass: a wavefront
+// per row, a lane owns the same 8 J columns (J = ceil(d / 512)); h is written for the residual stream and the
+// backward pass, the keep bits go to the site's record (bit e % 8 of byte e / 8 of the member's array), and the
+// normalised row is formed from the rounded h while it is still in registers, so h is not read back.
+template <int J>
+__global__ __launch_bounds__(256) void residual_dropout_layernorm_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ res,
+                                                                         int rows_per_member, int d, DropArgs dr, int site,
+                                                                         bf16_t* __restrict__ h, uint8_t* __restrict__ record, int64_t record_stride,
+                                                                         const float* __restrict__ W32, int64_t stride, int64_t g_off, int64_t b_off,
+                                                                         bf16_t* __restrict__ y, float* __restrict__ mean, float* __restrict__ rstd) {
+  const int i = blockIdx.y;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (r >= rows_per_member) return;
+  const int64_t row = (int64_t)i * rows_per_member + r;
+  const DropRate rate = drop_rate(dr.H, dr.n_hyper, dr.col, i, dr.active);
+  float v[J][8];
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int c = lane * 8 + 512 * j;
+    if (c < d) {
+      const int64_t e = (int64_t)r * d + c;   // element index inside the member's array
+      const uint4 xv = *reinterpret_cast<const uint4*>(x + row * d + c), rv = *reinterpret_cast<const uint4*>(res + row * d + c);
+      const uint32_t b0 = drop_bits4(dr, rate, i, site, (uint32_t)(e >> 2)), b1 = drop_bits4(dr, rate, i, site, (uint32_t)(e >> 2) + 1u);
+      float f[4];
+      uint2 lo, hi;
+      bits_to_factors(b0, rate.scale, f);
+      dropout_group(make_uint2(xv.x, xv.y), true, make_uint2(rv.x, rv.y), f, &lo);
+      bits_to_factors(b1, rate.scale, f);
+      dropout_group(make_uint2(xv.z, xv.w), true, make_uint2(rv.z, rv.w), f, &hi);
+      const uint4 hv = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      *reinterpret_cast<uint4*>(h + row * d + c) = hv;
+      if (record) record[(int64_t)i * record_stride + (e >> 3)] = (uint8_t)(b0 | (b1 << 4));
+      const uint32_t w[4] = {hv.x, hv.y, hv.z, hv.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { v[j][2 * q] = __uint_as_float(w[q] << 16); v[j][2 * q + 1] = __uint_as_float(w[q] & 0xffff0000u); }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) s += v[j][k];
+    }
+  }
+  const float mu = wave_sum(s) / (float)d;
+  float var = 0.f;
+#pragma unroll
+  for (int j = 0; j < J; ++j)
+    if (lane * 8 + 512 * j < d) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { const float t = v[j][k] - mu; var = fmaf(t, t, var); }
+    }
+  const float rs = rsqrtf(wave_sum(var) / (float)d + LN_EPS);
+  const float* __restrict__ g = W32 + (int64_t)i * stride + g_off;
+  const float* __restrict__ b = W32 + (int64_t)i * stride + b_off;
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int c = lane * 8 + 512 * j;
+    if (c < d) {
+      float gv[8], bv[8], o[8];
+      load8(g + c, gv);
+      load8(b + c, bv);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) o[k] = (v[j][k] - mu) * rs * gv[k] + bv[k];
+      store8(y + row * d + c, o);
+    }
+  }
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+}
+hipError_t residual_dropout_layernorm(const bf16_t* x, const bf16_t* res, int P, int rows, int d, const DropArgs& dr, int site, bf16_t* h,
+                                      uint16_t* record, const float* W32, int64_t stride, int64_t g_off, int64_t b_off, bf16_t* y, float* mean,
+                                      float* rstd, hipStream_t s) {
+  // (the record is the bit array dropout_kernel writes, which has no padding between members when their size is a multiple of 16)
+  if (d % 8 || ((int64_t)rows * d) % 16 || g_off % 4 || b_off % 4 || stride % 4 || d > 2048) return hipErrorInvalidValue;
+  const dim3 grid((rows + 3) / 4, P);
+  uint8_t* rec = reinterpret_cast<uint8_t*>(record);
+  const int64_t rstride = (int64_t)rows * d / 8;
+#define PBT_RDL(J) hipLaunchKernelGGL(residual_dropout_layernorm_kernel<J>, grid, dim3(256), 0, s, x, res, rows, d, dr, site, h, rec, rstride, W32, stride, g_off, b_off, y, mean, rstd)
+  if (d <= 512) PBT_RDL(1);
+  else if (d <= 1024) PBT_RDL(2);
+  else PBT_RDL(4);
+#undef PBT_RDL
   return hipGetLastError();
 }
 

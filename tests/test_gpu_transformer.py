@@ -31,7 +31,7 @@ def _reduced(P=3, **kw):
     return workloads.TRANSFORMER.replace(**base)
 
 
-def _teacher_forced(pair, steps, members, grad_floor=0.0, tol_grad=TOL_GRAD_SMALL):
+def _teacher_forced(pair, steps, members, grad_floor=0.0, tol_grad=TOL_GRAD_SMALL, tol_w=TOL_BF16):
     """Before every step the oracle takes over the GPU's state; compares the loss, the gradient of
     every parameter array and the updated weights of that one step."""
     g, ot = pair.gpu, pair.ot
@@ -52,7 +52,7 @@ def _teacher_forced(pair, steps, members, grad_floor=0.0, tol_grad=TOL_GRAD_SMAL
             worst["grad"] = max(worst["grad"], ge.max())
             cases.append(ge.max())
             we = pair.array_errors(i, binding.ARR_W32, m.theta, rms_floor=W_FLOOR, skip_key_bias=True)
-            assert we.max() <= TOL_BF16, (s, i, names[int(we.argmax())], we.max())
+            assert we.max() <= tol_w, (s, i, names[int(we.argmax())], we.max())
             worst["step"] = max(worst["step"], we.max())
             worst["s0"] = max(worst["s0"], pair.array_errors(i, binding.ARR_OPT0, m.opt["s0"], skip_key_bias=True).max())
             worst["s1"] = max(worst["s1"], pair.array_errors(i, binding.ARR_OPT1, m.opt["s1"], skip_key_bias=True).max())
@@ -77,6 +77,28 @@ def test_transformer_reduced_ragged_shapes():
     pair = TransformerPair(wl, H=np.array([[1e-3, 0.1, 0.05], [5e-4, 0.3, 0.0]], dtype=np.float32))
     worst = _teacher_forced(pair, range(4), range(2))
     print("transformer ragged:", {k: float("%.3g" % v) for k, v in worst.items()}, flush=True)
+
+
+@pytest.mark.parametrize("seq,batch", [(96, 2), (128, 2), (32, 3)])
+def test_transformer_reduced_one_kernel_attention(seq, batch):
+    """Heads of width 64 and sequences of 32, 96 and 128 positions take the attention kernels that keep the
+    score and probability matrices on the chip (one, three and four query blocks); one member without
+    dropout, two with."""
+    wl = _reduced(P=3, vocab=64, d_model=128, heads=2, d_ff=64, n_blocks=2, seq=seq, batch=batch, n_train=16, n_eval=2 * batch)
+    H = np.array([[1e-3, 0.0, 0.0], [5e-4, 0.3, 0.05], [1e-3, 0.1, 0.1]], dtype=np.float32)
+    pair = TransformerPair(wl, H=H)
+    # (Adam's first updates are +-lr per element whatever the gradient's size: in the zero-initialised LayerNorm
+    # biases every element whose gradient is small enough to change sign within TOL_GRAD_SMALL is off by 2 lr,
+    # so the updated weights are only held to the gradients' bound here, which is twice that of the smaller
+    # networks above: with 64 to 256 rows per batch one differently rounded activation moves the second block's
+    # feed-forward gradients by up to 5 %, and the kernels that compute attention in several launches give the
+    # same distances at these shapes)
+    worst = _teacher_forced(pair, range(3), range(3), tol_grad=2 * TOL_GRAD_SMALL, tol_w=2 * TOL_GRAD_SMALL)
+    pair.gpu.eval(pair.d_eval)
+    sc, sc_ref = pair.gpu.get(binding.ARR_SCORE), pair.eval_ref()
+    worst["score"] = float(np.max(np.abs(sc - sc_ref) / np.abs(sc_ref)))
+    assert worst["score"] <= TOL_BF16, (sc, sc_ref)
+    print("transformer one-kernel attention, seq %d:" % seq, {k: float("%.3g" % v) for k, v in worst.items()}, flush=True)
 
 
 def test_transformer_free_running_eval_and_exploit():
