@@ -184,7 +184,10 @@ pbt_status a2c_check_and_plan(const pbt_config* c, Plan* pl, Carver* w) {
   a.o_lat = a.o_gout = 0;
   if (c->on_policy) {
     if (c->latent_dim < 1 || c->latent_dim > 64) return fail(nullptr, PBT_EINVAL, "latent_dim outside 1..64");
-    if ((int64_t)c->batch * (c->latent_dim * 8 + 4) > 48 * 1024) return fail(nullptr, PBT_EUNSUPPORTED, "batch x latent_dim too large for the transition kernel's LDS");
+    // (LDS of the generator's kernels: the latents of a member's trajectories, plus an action each in the transition
+    // kernel or a 64-component slab of the observation matrix, 65 doubles per latent component, in the observation kernel)
+    if ((int64_t)c->batch * (c->latent_dim * 8 + 4) + (int64_t)c->latent_dim * 65 * 8 > 64 * 1024)
+      return fail(nullptr, PBT_EUNSUPPORTED, "batch x latent_dim too large for the trajectory generator's LDS");
     if ((int64_t)R * c->dims[0] >= (1LL << 31)) return fail(nullptr, PBT_EUNSUPPORTED, "more than 2^31 observation elements per member");
     a.o_lat = w->take((size_t)P * c->batch * c->latent_dim * 8);
     for (int l = 1; l < L; ++l) a.o_ga[l] = w->take((size_t)P * c->batch * c->dims[l] * 2);
@@ -265,6 +268,30 @@ __device__ __forceinline__ void env_normal4(uint32_t step, uint32_t member, uint
   sincospi(2.0 * philox_unit(w.w), &s2, &c2);
   v[0] = r1 * c1; v[1] = r1 * s1; v[2] = r2 * c2; v[3] = r2 * s2;
 }
+// The same four normals to float accuracy (relative error about 2e-7), for values that are stored as bf16 anyway
+// (the observation noise: 512 of them per trajectory and time step, where the double-precision log, sqrt and
+// sincospi above were the whole cost of the generator).  The uniforms and the argument reductions stay in double:
+// -log(u) through log1p(u - 1) above one half (u - 1 is exact in double, so no digits are lost next to 1), and the
+// angle 2 pi u reduced to pi f with |f| <= 1/4 before it is rounded to float, then rotated back by quadrant.
+__device__ __forceinline__ void env_normal_pair_f32(uint32_t wr, uint32_t wa, float* cosv, float* sinv) {
+  const double u = philox_unit(wr);
+  const float nl = u > 0.5 ? -log1pf((float)(u - 1.0)) : -logf((float)u);
+  const float r = sqrtf(2.f * nl);
+  const double x = 2.0 * philox_unit(wa);          // angle / pi, in (0, 2)
+  const double q = rint(2.0 * x);                  // nearest multiple of 1/2
+  const float f = (float)(x - 0.5 * q);
+  const float s0 = sinpif(f), c0 = cospif(f);
+  const int k = (int)q & 3;
+  const float s = k == 0 ? s0 : k == 1 ? c0 : k == 2 ? -s0 : -c0;
+  const float c = k == 0 ? c0 : k == 1 ? -s0 : k == 2 ? -c0 : s0;
+  *cosv = r * c; *sinv = r * s;
+}
+__device__ __forceinline__ void env_normal4_f32(uint32_t step, uint32_t member, uint32_t domain, uint32_t counter, uint32_t k0,
+                                                uint32_t k1, float* v) {
+  const u32x4 w = philox4x32_10(step, member, domain, counter, k0, k1);
+  env_normal_pair_f32(w.x, w.y, &v[0], &v[1]);
+  env_normal_pair_f32(w.z, w.w, &v[2], &v[3]);
+}
 __device__ __forceinline__ double env_normal(uint32_t step, uint32_t member, uint32_t domain, uint32_t e, uint32_t k0, uint32_t k1) {
   double v[4];
   env_normal4(step, member, domain, e >> 2, k0, k1, v);
@@ -341,25 +368,39 @@ __global__ __launch_bounds__(256) void a2c_env_transition_kernel(EnvArgs a, int 
   if (t == 0 && threadIdx.x == 0) a.t_count[i] += 1;
 }
 
-// The observation o_t of one trajectory (blockIdx.x) of one member (blockIdx.y), written where the step (and
-// the policy's next forward pass) reads it; a thread handles runs of four elements, i.e. one Philox counter.
-__global__ __launch_bounds__(128) void a2c_env_observe_kernel(EnvArgs a, int t) {
-  __shared__ double zs[64];
-  const int r = blockIdx.x, i = blockIdx.y;
-  const int nz = a.nz;
-  if ((int)threadIdx.x < nz) zs[threadIdx.x] = a.z[((int64_t)i * a.B + r) * nz + threadIdx.x];
+// The observations o_t of all trajectories of one member (blockIdx.y) for a slab of 64 observation components
+// (blockIdx.x), written where the step (and the policy's next forward pass) reads them.  The slab's rows of C go
+// through LDS, transposed, so that neighbouring lanes read neighbouring addresses there (read from memory in the
+// order the sum wants them, a wavefront's load touched 64 separate lines and the L1's access rate set the time);
+// a thread handles runs of four components, i.e. one Philox counter.
+constexpr int OBS_SLAB = 64;   // (the plan's LDS check assumes 64)
+__global__ __launch_bounds__(256) void a2c_env_observe_kernel(EnvArgs a, int t) {
+  extern __shared__ double obs_lds[];
+  const int nz = a.nz, B = a.B, i = blockIdx.y, j_first = blockIdx.x * OBS_SLAB;
+  double* Ct = obs_lds;                         // [nz][OBS_SLAB + 1]
+  double* zs = obs_lds + nz * (OBS_SLAB + 1);   // [B][nz]
+  for (int e = threadIdx.x; e < OBS_SLAB * nz; e += blockDim.x) {
+    const int j = e / nz, k = e - j * nz;
+    Ct[k * (OBS_SLAB + 1) + j] = j_first + j < a.d ? a.env.C[(int64_t)(j_first + j) * nz + k] : 0.0;
+  }
+  for (int e = threadIdx.x; e < B * nz; e += blockDim.x) zs[e] = a.z[(int64_t)i * B * nz + e];
   __syncthreads();
-  const int64_t row = (int64_t)r * (a.T + 1) + t;
-  for (int j0 = threadIdx.x * 4; j0 < a.d; j0 += blockDim.x * 4) {
-    double v[4];
-    env_normal4(a.step, i, DOMAIN_ENV + 1, (uint32_t)((row * a.d + j0) >> 2), a.k0, a.k1, v);
+  constexpr int RUNS = OBS_SLAB / 4;
+  for (int item = threadIdx.x; item < B * RUNS; item += blockDim.x) {
+    const int r = item / RUNS, g = item - r * RUNS, j0 = j_first + 4 * g;
+    if (j0 >= a.d) continue;
+    const int64_t row = (int64_t)r * (a.T + 1) + t;
+    float v[4];
+    env_normal4_f32(a.step, i, DOMAIN_ENV + 1, (uint32_t)((row * a.d + j0) >> 2), a.k0, a.k1, v);
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int k = 0; k < nz; ++k) {
+      const double zk = zs[r * nz + k];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[e] += Ct[k * (OBS_SLAB + 1) + 4 * g + e] * zk;
+    }
     float o[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      double acc = 0.0;
-      for (int k = 0; k < nz; ++k) acc += a.env.C[(j0 + e) * nz + k] * zs[k];
-      o[e] = (float)(acc + a.env.noise[0] * v[e]);
-    }
+    for (int e = 0; e < 4; ++e) o[e] = (float)(acc[e] + a.env.noise[0] * (double)v[e]);
     *reinterpret_cast<uint2*>(a.obs + ((int64_t)i * a.rows + row) * a.d + j0) = make_uint2(f2bf_pair(o[0], o[1]), f2bf_pair(o[2], o[3]));
   }
 }
@@ -405,7 +446,8 @@ pbt_status a2c_step_on_policy(pbt_handle* h, const A2CEnv& env, uint32_t step, h
   for (int t = 0; t <= T; ++t) {
     hipLaunchKernelGGL(a2c_env_transition_kernel, dim3(P), dim3(256), (size_t)B * c.latent_dim * sizeof(double) + (size_t)B * sizeof(int), s, ea, t);
     PBT_HIP(h, hipGetLastError());
-    hipLaunchKernelGGL(a2c_env_observe_kernel, dim3(B, P), dim3(128), 0, s, ea, t);
+    hipLaunchKernelGGL(a2c_env_observe_kernel, dim3((d + OBS_SLAB - 1) / OBS_SLAB, P), dim3(256),
+                       ((size_t)c.latent_dim * (OBS_SLAB + 1) + (size_t)B * c.latent_dim) * sizeof(double), s, ea, t);
     PBT_HIP(h, hipGetLastError());
     if (t == T) break;
     // the policy on the B observations of time t: rows t, t + (T+1), ... of the member's observation buffer
