@@ -26,6 +26,15 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
 ALU_FP32_PEAK_TFLOPS = 78.6      # 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz, no packed math
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, scaled by what the same counters
+# read for the exploit copy (a plain copy of known size): keyed by (workload, fused optimiser, variant) and kernel class.
+# They describe the kernels as they were when the counters were taken; a kernel that changes loses its entry.
+_W4 = "profiles/population_step_transformer_bf16_hbm_counters.md"
+_W2 = "profiles/population_step_mlp_wide_bf16_hbm_counters.md"
+TRAFFIC = {
+    (4, False, None): {"optimizer": (10.115e9, _W4), "copy": (1.770e9, _W4), "gemm": (0.478e9, _W4)},
+    (2, True, None): {"gemm_wgrad": (1.1188e9, _W2), "copy": (0.4446e9, _W2)},
+}
 TARGET = {"mfma": 0.5, "hbm": 0.7}   # the fractions aimed at for the GEMMs and for the optimiser / exploit copy
 
 # steps timed for the workloads that are not the top-level record (their own warm-up in brackets)
@@ -231,6 +240,7 @@ def run_workload(key, steps, warmup, fused, baseline_budget_s, variant=None):
 
     timed["copy"] = pop.timing_read_class(K["copy"])
     rooflines = []
+    measured = TRAFFIC.get((key, bool(fused), variant), {})
     for name, (bound, w, launches) in work.items():
         ms, n_rec = timed[name]
         if not n_rec:
@@ -246,6 +256,8 @@ def run_workload(key, steps, warmup, fused, baseline_budget_s, variant=None):
         r = {"kernel": name, "bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
              "traffic": None, "avg_launch_us": avg_s * 1e6, "launches_timed": n_rec, "launches_per_step": launches,
              "work_per_launch": per_launch}
+        if name in measured:
+            r["traffic"], r["traffic_source"] = measured[name]
         if bound in TARGET:
             r["target_frac"] = TARGET[bound]
             r["meets_target"] = bool(ach / peak >= TARGET[bound])
@@ -263,6 +275,8 @@ def run_workload(key, steps, warmup, fused, baseline_budget_s, variant=None):
                              "traffic": None, "avg_launch_us": t_all / n_all, "launches_timed": sum(r["launches_timed"] for r in gemms),
                              "launches_per_step": n_all, "work_per_launch": w_all / n_all, "target_frac": TARGET["mfma"],
                              "meets_target": bool(ach / MFMA_BF16_PEAK_TFLOPS >= TARGET["mfma"])})
+        if "gemm" in measured:
+            rooflines[0]["traffic"], rooflines[0]["traffic_source"] = measured["gemm"]
     dominant = {1: "fused_step", 2: "gemm_wgrad" if fused else "optimizer", 3: "optimizer", 4: "gemm (", 5: "optimizer"}[key]
     roofline = next((r for r in rooflines if r["kernel"].startswith(dominant)), None)
 
