@@ -405,6 +405,300 @@ __global__ __launch_bounds__(256) void a2c_env_observe_kernel(EnvArgs a, int t) 
   }
 }
 
+// ---- the whole unroll of one member in one kernel -------------------------------------------------------------
+// One workgroup per member runs the T + 1 rounds of (transition and action draw, observation, policy) back to
+// back: latents, the round's observations and the hidden activations stay in LDS, the member's bf16 weights are
+// streamed through LDS a 64-deep slab at a time (fetched with eight neighbouring lanes on 128 contiguous bytes,
+// transposed on the way in through a lane exchange, the next slab's loads in flight while this one is multiplied),
+// and every layer is a 32 x N x K product on the matrix cores with the trajectories as one 32-row block.  The same
+// arithmetic as the kernels above and the batched GEMMs (bf16 operands, float accumulation, bias and activation in
+// float, activations rounded to bf16 between layers, float head outputs); sums run in a different order.
+// Shapes: at most 32 trajectories, observation width a multiple of 64, hidden widths 64, 128 or 256, at most 32
+// head outputs.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 ro_frag_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float ro_acc_t;
+constexpr int RO_WP = 64 + 4;     // LDS pitch (elements) of a transposed weight slab [N][64]
+constexpr int RO_MAX_HIDDEN = 3;
+constexpr int RO_THREADS = 512;   // 8 wavefronts: with one workgroup per compute unit, two per SIMD to overlap each other's latencies
+
+struct RolloutArgs {
+  EnvArgs e;
+  const bf16_t* W16; const float* W32; int64_t stride;
+  int n_hidden, act, hmax;
+  int dims[RO_MAX_HIDDEN + 2];
+  int64_t w_off[RO_MAX_HIDDEN + 1], b_off[RO_MAX_HIDDEN + 1];
+};
+
+// Wt[n][k] (pitch RO_WP) = W[k0 + k][n] for k < 64, n < N: rows of N contiguous values in memory.  A thread
+// holds N / 32 pieces of 16 bytes; piece `it` is row (it % 512) / 8, columns 64 (it / 512) + 8 (it % 8) ...
+struct RoStaged { uint4 v[4]; };
+template <int N>
+__device__ __forceinline__ void ro_fetch(const bf16_t* __restrict__ W, int k0, RoStaged& r) {
+#pragma unroll
+  for (int j = 0; j < N / 64; ++j) {
+    const int it = threadIdx.x + RO_THREADS * j;
+    r.v[j] = *reinterpret_cast<const uint4*>(W + (int64_t)(k0 + ((it & 511) >> 3)) * N + 64 * (it >> 9) + 8 * (it & 7));
+  }
+}
+template <int N>
+__device__ __forceinline__ void ro_put(const RoStaged& r, bf16_t* Wt) {
+#pragma unroll
+  for (int j = 0; j < N / 64; ++j) {
+    const int it = threadIdx.x + RO_THREADS * j;
+    const int row = (it & 511) >> 3, n0 = 64 * (it >> 9) + 8 * (it & 7), odd = row & 1;
+    const uint4 v = r.v[j];
+    // lanes 8 apart hold rows k and k ^ 1: they exchange halves so that each writes four (k, k + 1) pairs
+    const uint32_t g0 = __shfl_xor(odd ? v.x : v.z, 8), g1 = __shfl_xor(odd ? v.y : v.w, 8);
+    const uint32_t e0 = odd ? g0 : v.x, e1 = odd ? g1 : v.y, o0 = odd ? v.z : g0, o1 = odd ? v.w : g1;
+    uint32_t* out = reinterpret_cast<uint32_t*>(Wt) + (n0 + 4 * odd) * (RO_WP / 2) + (row >> 1);
+    out[0] = (e0 & 0xffffu) | (o0 << 16);
+    out[RO_WP / 2] = (e0 >> 16) | (o0 & 0xffff0000u);
+    out[2 * (RO_WP / 2)] = (e1 & 0xffffu) | (o1 << 16);
+    out[3 * (RO_WP / 2)] = (e1 >> 16) | (o1 & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ ro_frag_t ro_wfrag(const bf16_t* Wt, int n, int c, int hf) {
+  const bf16_t* p = Wt + n * RO_WP + 16 * c + 8 * hf;   // 8-byte aligned
+  const uint2 lo = *reinterpret_cast<const uint2*>(p), hi = *reinterpret_cast<const uint2*>(p + 4);
+  const uint4 v = make_uint4(lo.x, lo.y, hi.x, hi.y);
+  return __builtin_bit_cast(ro_frag_t, v);
+}
+
+// out[r][n] = act(sum_k in[r][k] W[k][n] + b[n]) for the 32 rows in LDS; N in {64, 128, 256}, K a multiple of 64
+template <int N>
+__device__ __forceinline__ void ro_dense(const bf16_t* in, int pin, int K, const bf16_t* __restrict__ W, const float* __restrict__ bias,
+                                         int act, bf16_t* out, int pout, bf16_t* Wt) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, lr = lane & 31, hf = lane >> 5;
+  const bool mine = w < N / 32;   // wavefront w owns columns 32 w .. 32 w + 31
+  ro_acc_t acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  // Three register sets: the slabs k0 + 64 and k0 + 128 are on their way while slab k0 is written to LDS and
+  // multiplied (one workgroup per compute unit: nothing else hides the memory latency).  Every slab step issues
+  // the same loads, past the end of W's rows too (the last slab again, never multiplied), so that the number of
+  // loads in flight at each wait is known when the kernel is compiled; with conditional loads every wait was for
+  // all of them, i.e. a full memory latency per slab.
+  const int last = K - 64;
+  RoStaged st[3];
+  ro_fetch<N>(W, 0, st[0]);
+  ro_fetch<N>(W, min(64, last), st[1]);
+  ro_fetch<N>(W, min(128, last), st[2]);
+  auto slab = [&](RoStaged& r, int k0) {
+    ro_put<N>(r, Wt);
+    __syncthreads();
+    ro_fetch<N>(W, min(k0 + 192, last), r);
+    if (mine && k0 < K) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const ro_frag_t af = *reinterpret_cast<const ro_frag_t*>(in + lr * pin + k0 + 16 * c + 8 * hf);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ro_wfrag(Wt, 32 * w + lr, c, hf), af, acc, 0, 0, 0);
+      }
+    }
+    __syncthreads();
+  };
+  for (int k0 = 0; k0 < K; k0 += 192) {
+    slab(st[0], k0);
+    slab(st[1], k0 + 64);
+    slab(st[2], k0 + 128);
+  }
+  // accumulator register e of lane (lr, hf): row lr, column 32 w + 8 (e / 4) + 4 hf + e % 4
+  if (mine) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int n0 = 32 * w + 8 * g + 4 * hf;
+      const float4 b = *reinterpret_cast<const float4*>(bias + n0);
+      const float a0 = act_fwd(acc[4 * g] + b.x, act), a1 = act_fwd(acc[4 * g + 1] + b.y, act);
+      const float a2 = act_fwd(acc[4 * g + 2] + b.z, act), a3 = act_fwd(acc[4 * g + 3] + b.w, act);
+      *reinterpret_cast<uint2*>(out + lr * pout + n0) = make_uint2(f2bf_pair(a0, a1), f2bf_pair(a2, a3));
+    }
+  }
+  __syncthreads();
+}
+
+// hout[r][c] = sum_k in[r][k] W[k][c] + b[c] for c < C <= 32 (float): the whole K x C matrix is staged at once
+__device__ __forceinline__ void ro_head(const bf16_t* in, int pin, int K, const bf16_t* __restrict__ W, const float* __restrict__ bias, int C,
+                                        float* hout, bf16_t* Wt) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, lr = lane & 31, hf = lane >> 5;
+  const int pw = K + 8;
+  for (int e = threadIdx.x; e < 32 * K; e += RO_THREADS) {
+    const int c = e / K, k = e - c * K;
+    Wt[c * pw + k] = c < C ? W[(int64_t)k * C + c] : (bf16_t)0;
+  }
+  __syncthreads();
+  // the eight wavefronts share the contraction (k-blocks of 16 in turn); partial sums are added in wavefront order
+  ro_acc_t acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  for (int kb = w; kb < K / 16; kb += RO_THREADS / 64) {
+    const ro_frag_t af = *reinterpret_cast<const ro_frag_t*>(in + lr * pin + 16 * kb + 8 * hf);
+    const ro_frag_t wf = *reinterpret_cast<const ro_frag_t*>(Wt + lr * pw + 16 * kb + 8 * hf);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, af, acc, 0, 0, 0);
+  }
+  __syncthreads();   // the staged weights are not needed any more: their space takes the partial sums
+  float* part = reinterpret_cast<float*>(Wt);   // [8][32][33]
+#pragma unroll
+  for (int e = 0; e < 16; ++e) part[(w * 32 + lr) * 33 + 8 * (e / 4) + 4 * hf + e % 4] = acc[e];
+  __syncthreads();
+  for (int e = threadIdx.x; e < 32 * 32; e += RO_THREADS) {
+    const int r = e >> 5, c = e & 31;
+    float sum = part[r * 33 + c];
+    for (int v = 1; v < RO_THREADS / 64; ++v) sum += part[(32 * v + r) * 33 + c];
+    hout[e] = sum + (c < C ? bias[c] : 0.f);
+  }
+  __syncthreads();
+}
+
+// bytes of the kernel's LDS ahead of the 16-byte aligned activation buffers
+__host__ __device__ inline size_t ro_front_bytes(int nz, int n_act, int d) {
+  const size_t b = (size_t)(2 * 32 * nz + nz * nz + nz * n_act + nz) * 8 + (size_t)(nz * (d + 1) + 32 * nz + 32 * 32 + 32) * 4;
+  return (b + 15) & ~(size_t)15;
+}
+__global__ __launch_bounds__(RO_THREADS) void a2c_rollout_kernel(RolloutArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char ro_lds[];
+  const EnvArgs& e = a.e;
+  const int i = blockIdx.x, nz = e.nz, B = e.B, T = e.T, d = e.d, n_act = e.n_act;
+  // LDS.  doubles: latents (two copies), A, B, w of the latent system; floats: C transposed (kept for the whole
+  // unroll), the round's latents, head outputs; actions; then, 16-byte aligned, the observations, two activation
+  // buffers and the weight slab (which doubles as scratch of the action draw and of the head)
+  double* zs = reinterpret_cast<double*>(ro_lds);                 // [2][32][nz]
+  double* As = zs + 2 * 32 * nz;                                  // [nz][nz]
+  double* Bs = As + nz * nz;                                      // [nz][n_act]
+  double* ws = Bs + nz * n_act;                                   // [nz]
+  float* Ct = reinterpret_cast<float*>(ws + nz);                  // [nz][d + 1]
+  float* zf = Ct + nz * (d + 1);                                  // [32][nz]
+  float* hout = zf + 32 * nz;                                     // [32][32]
+  int* action = reinterpret_cast<int*>(hout + 32 * 32);           // [32]
+  bf16_t* X0 = reinterpret_cast<bf16_t*>(ro_lds + ro_front_bytes(nz, n_act, d));   // [32][d + 8]
+  bf16_t* XA = X0 + 32 * (d + 8);                                 // [32][hmax + 8]
+  bf16_t* XB = XA + 32 * (a.hmax + 8);
+  bf16_t* Wt = XB + 32 * (a.hmax + 8);                            // [256][RO_WP]
+  double* ex = reinterpret_cast<double*>(Wt);                     // [32][32] during the action draw
+  const bf16_t* W16 = a.W16 + (int64_t)i * a.stride;
+  const float* W32 = a.W32 + (int64_t)i * a.stride;
+  if (threadIdx.x == 0) e.t_count[i] += 1;
+  for (int x = threadIdx.x; x < nz * nz; x += RO_THREADS) As[x] = e.env.A[x];
+  for (int x = threadIdx.x; x < nz * n_act; x += RO_THREADS) Bs[x] = e.env.B[x];
+  for (int x = threadIdx.x; x < nz; x += RO_THREADS) ws[x] = e.env.w[x];
+  for (int x = threadIdx.x; x < d * nz; x += RO_THREADS) {
+    const int j = x / nz, k = x - j * nz;
+    Ct[k * (d + 1) + j] = (float)e.env.C[x];
+  }
+  const double noise_obs = e.env.noise[0], noise_rew = e.env.noise[1], noise_lat = e.env.noise[2];
+  // rows past the last trajectory stay zero in every activation buffer
+  for (int x = threadIdx.x; x < 32 * (d + 8) / 2; x += RO_THREADS) reinterpret_cast<uint32_t*>(X0)[x] = 0u;
+  const int quads = (nz + 3) / 4;
+  __syncthreads();
+  for (int t = 0; t <= T; ++t) {
+    const int tt = t - 1;
+    double* zo = zs + (t & 1) * 32 * nz;          // latents before this round's transition
+    double* zn_ = zs + ((t + 1) & 1) * 32 * nz;   // and after
+    if (t > 0) {
+      // a_{t-1} from the head outputs: the exponentials with one thread per (trajectory, action), then the
+      // cumulative distribution with one thread per trajectory
+      for (int x = threadIdx.x; x < B * 32; x += RO_THREADS) {
+        const int r = x >> 5, c = x & 31;
+        const float* lg = hout + r * 32;
+        float mx = -INFINITY;
+        for (int q = 0; q < n_act; ++q) mx = fmaxf(mx, lg[q]);
+        ex[x] = c < n_act ? exp((double)lg[c] - (double)mx) : 0.0;
+      }
+      __syncthreads();
+      for (int r = threadIdx.x; r < B; r += RO_THREADS) {
+        double se = 0.0;
+        for (int c = 0; c < n_act; ++c) se += ex[r * 32 + c];
+        const double u = philox_unit(philox4x32_10(e.step, i, DOMAIN_ENV + 2, (uint32_t)(r * T + tt), e.k0, e.k1).x);
+        double cdf = 0.0;
+        int act = 0;
+        for (int c = 0; c < n_act; ++c) { cdf += ex[r * 32 + c] / se; act += cdf <= u ? 1 : 0; }
+        act = act < n_act - 1 ? act : n_act - 1;
+        double rw = 0.0;
+        for (int k = 0; k < nz; ++k) rw += ws[k] * zo[r * nz + k];
+        rw += noise_rew * env_normal(e.step, i, DOMAIN_ENV + 3, (uint32_t)(r * T + tt), e.k0, e.k1);
+        e.act[((int64_t)i * B + r) * T + tt] = act;
+        e.rew[((int64_t)i * B + r) * T + tt] = (float)rw;
+        action[r] = act;
+      }
+      __syncthreads();
+    }
+    const uint32_t domain = t == 0 ? DOMAIN_ENV + 0 : DOMAIN_ENV + 4;
+    for (int item = threadIdx.x; item < B * quads; item += RO_THREADS) {
+      const int r = item / quads, k0 = (item - r * quads) * 4;
+      const uint32_t e0 = (uint32_t)((t == 0 ? r : r * T + tt) * nz + k0);
+      double v[4];
+      if ((e0 & 3u) == 0) {
+        env_normal4(e.step, i, domain, e0 >> 2, e.k0, e.k1, v);
+      } else {
+        for (int q = 0; q < 4; ++q) v[q] = env_normal(e.step, i, domain, e0 + q, e.k0, e.k1);
+      }
+      for (int q = 0; q < 4 && k0 + q < nz; ++q) {
+        const int k = k0 + q;
+        double zv = v[q];
+        if (t > 0) {
+          double acc = 0.0;
+          for (int j = 0; j < nz; ++j) acc += As[k * nz + j] * zo[r * nz + j];
+          zv = acc + Bs[k * n_act + action[r]] + noise_lat * v[q];
+        }
+        zn_[r * nz + k] = zv;
+        zf[r * nz + k] = (float)zv;
+      }
+    }
+    __syncthreads();
+    // observations of round t: to memory (the update reads them) and to X0 (the policy's input).  The sum C z runs
+    // in float (the result is stored as bf16; the latents themselves stay in double from round to round).
+    {
+      const int runs = d / 4;
+      for (int item = threadIdx.x; item < B * runs; item += RO_THREADS) {
+        const int r = item / runs, g = item - r * runs, j0 = 4 * g;
+        const int64_t row = (int64_t)r * (T + 1) + t;
+        float v[4];
+        env_normal4_f32(e.step, i, DOMAIN_ENV + 1, (uint32_t)((row * d + j0) >> 2), e.k0, e.k1, v);
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < nz; ++k) {
+          const float zk = zf[r * nz + k];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) acc[q] = fmaf(Ct[k * (d + 1) + j0 + q], zk, acc[q]);
+        }
+        float o[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) o[q] = fmaf((float)noise_obs, v[q], acc[q]);
+        const uint2 packed = make_uint2(f2bf_pair(o[0], o[1]), f2bf_pair(o[2], o[3]));
+        *reinterpret_cast<uint2*>(e.obs + ((int64_t)i * e.rows + row) * d + j0) = packed;
+        *reinterpret_cast<uint2*>(X0 + r * (d + 8) + j0) = packed;
+      }
+      __syncthreads();
+    }
+    if (t == T) break;
+    // the policy on the round's observations
+    const bf16_t* in = X0;
+    int pin = d + 8, K = d;
+    for (int l = 0; l < a.n_hidden; ++l) {
+      bf16_t* out = l & 1 ? XB : XA;
+      const int N = a.dims[l + 1];
+      if (N == 256) ro_dense<256>(in, pin, K, W16 + a.w_off[l], W32 + a.b_off[l], a.act, out, a.hmax + 8, Wt);
+      else if (N == 128) ro_dense<128>(in, pin, K, W16 + a.w_off[l], W32 + a.b_off[l], a.act, out, a.hmax + 8, Wt);
+      else ro_dense<64>(in, pin, K, W16 + a.w_off[l], W32 + a.b_off[l], a.act, out, a.hmax + 8, Wt);
+      in = out; pin = a.hmax + 8; K = a.dims[l + 1];
+    }
+    ro_head(in, pin, K, W16 + a.w_off[a.n_hidden], W32 + a.b_off[a.n_hidden], a.dims[a.n_hidden + 1], hout, Wt);
+  }
+}
+
+// LDS of the kernel above for a shape, 0 if the shape is not covered
+static size_t rollout_lds_bytes(const pbt_config& c) {
+  const int L = c.n_layers, d = c.dims[0], C = c.dims[L];
+  if (c.batch > 32 || d % 64 || L - 1 < 1 || L - 1 > RO_MAX_HIDDEN || C > 32) return 0;
+  int hmax = 0;
+  for (int l = 1; l < L; ++l) {
+    if (c.dims[l] != 64 && c.dims[l] != 128 && c.dims[l] != 256) return 0;
+    hmax = c.dims[l] > hmax ? c.dims[l] : hmax;
+  }
+  const size_t wt = (size_t)256 * RO_WP * 2;   // also holds the head's [32][K + 8] bf16 and its 8 x 32 x 33 partial sums
+  if ((size_t)32 * (hmax + 8) * 2 > wt || (size_t)(RO_THREADS / 64) * 32 * 33 * 4 > wt) return 0;
+  if ((size_t)32 * 32 * 8 > wt) return 0;      // (and the exponentials of the action draw)
+  const size_t bytes = ro_front_bytes(c.latent_dim, C - 1, d) + (size_t)32 * (d + 8) * 2 + (size_t)2 * 32 * (hmax + 8) * 2 + wt;
+  return bytes <= 160 * 1024 ? bytes : 0;
+}
+
 // Pushes the unroll's return (mean over trajectories of the summed rewards, in double, trajectories in order)
 // into the member's history ring.
 __global__ __launch_bounds__(64) void a2c_push_return_kernel(const float* __restrict__ rew, int B, int T, float* __restrict__ hist) {
@@ -443,6 +737,20 @@ pbt_status a2c_step_on_policy(pbt_handle* h, const A2CEnv& env, uint32_t step, h
   float* gout = h->sc<float>(a.o_gout);
   EnvArgs ea{env, c.latent_dim, C - 1, d, B, T, R, step, (uint32_t)c.seed, (uint32_t)(c.seed >> 32), h->sc<double>(a.o_lat), gout,
              h->sc<int32_t>(a.o_act), h->sc<float>(a.o_rew), obs, h->st<int32_t>(p.o_t)};
+  if (const size_t lds = rollout_lds_bytes(c)) {
+    RolloutArgs ra{};
+    ra.e = ea; ra.W16 = W16; ra.W32 = W32; ra.stride = S; ra.n_hidden = L - 1; ra.act = c.act; ra.hmax = 0;
+    for (int l = 0; l <= L; ++l) ra.dims[l] = c.dims[l];
+    for (int l = 1; l < L; ++l) ra.hmax = c.dims[l] > ra.hmax ? c.dims[l] : ra.hmax;
+    for (int l = 0; l < L; ++l) { ra.w_off[l] = p.lay.w_off[l]; ra.b_off[l] = p.lay.b_off[l]; }
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(a2c_rollout_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    PBT_HIP(h, attr);
+    hipLaunchKernelGGL(a2c_rollout_kernel, dim3(P), dim3(RO_THREADS), lds, s, ra);
+    PBT_HIP(h, hipGetLastError());
+    hipLaunchKernelGGL(a2c_push_return_kernel, dim3(P), dim3(64), 0, s, h->sc<float>(a.o_rew), B, T, h->st<float>(p.o_hist));
+    PBT_HIP(h, hipGetLastError());
+    return a2c_update(h, s);
+  }
   for (int t = 0; t <= T; ++t) {
     hipLaunchKernelGGL(a2c_env_transition_kernel, dim3(P), dim3(256), (size_t)B * c.latent_dim * sizeof(double) + (size_t)B * sizeof(int), s, ea, t);
     PBT_HIP(h, hipGetLastError());

@@ -136,14 +136,22 @@ def test_a2c_ttest_selection_bit_exact(alpha):
     print("t-test selection alpha %.2f: %d copies, %d of them from a member that was itself overwritten" % (alpha, n_copy, n_chain), flush=True)
 
 
-def test_a2c_on_policy_unrolls_against_the_oracle():
+def _one_kernel_unroll_shape():
+    """A shape the single-kernel unroll covers (at most 32 trajectories, hidden widths 64 / 128 / 256, observation
+    width a multiple of 64), with fewer than 32 trajectories, an odd latent size and two different hidden widths."""
+    return workloads.A2C_MLP.replace(P=4, dims=[64, 128, 64, 7], n_actions=6, batch=20, unroll=5, n_train=50, n_trunc=1, latent=5,
+                                     priors=[("log", 1e-4, 2e-3), ("log", 1e-4, 1e-2)])
+
+
+@pytest.mark.parametrize("shape", ["kernel_per_round", "one_kernel"])
+def test_a2c_on_policy_unrolls_against_the_oracle(shape):
     """Section 4.1.1: agents act with their current policy.  Every step the GPU generates the unroll; the oracle
     (a) replays the latent system along the GPU's actions and must reproduce observations and rewards, (b) makes
     its own choice at every transition from its own logits: it may differ from the GPU's only where the uniform
     draw lies within 1e-3 of an edge of the cdf (float32 against float64 logits), and on fewer than 1 % of the
     choices, (c) takes its step on the GPU's unroll and must stay within the bf16 tolerance, free-running."""
     from oracle import nets
-    wl = _reduced().replace(on_policy=1)
+    wl = (_reduced() if shape == "kernel_per_round" else _one_kernel_unroll_shape()).replace(on_policy=1)
     pair = A2CPair(wl)
     g, P = pair.gpu, wl.P
     n_choices = n_differ = n_obs = n_obs_differ = 0
@@ -163,7 +171,9 @@ def test_a2c_on_policy_unrolls_against_the_oracle():
             n_differ += int(differ.sum())
             obs_o16 = nets.round_bf16(obs_o.astype(np.float64))
             off = obs_o16 != obs_g
-            assert np.all(np.abs(obs_o16 - obs_g)[off] <= 2.0 ** -7 * np.abs(obs_g)[off]), (s, i)     # one bf16 step at most
+            # one bf16 step at most (the device draws the observation noise to float accuracy, about 2e-7 of a value
+            # of order one: next to zero, where bf16 is finer than that, the absolute distance is what is bounded)
+            assert np.all(np.abs(obs_o16 - obs_g)[off] <= np.maximum(2.0 ** -7 * np.abs(obs_g)[off], 2e-6)), (s, i)
             n_obs += obs_g.size
             n_obs_differ += int(off.sum())
             worst["reward"] = max(worst["reward"], float(np.max(np.abs(rew_o.astype(np.float64) - rew_g))))
