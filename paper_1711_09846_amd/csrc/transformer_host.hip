@@ -168,6 +168,7 @@ pbt_status tf_layout(const pbt_config* c, Plan* pl) {
   if (c->tf_d_model % c->tf_heads || (c->tf_d_model / c->tf_heads) % 8 || c->tf_d_model % 8 || c->tf_d_ff % 8 || c->tf_vocab % 8 || c->tf_seq % 8)
     return fail(nullptr, PBT_EUNSUPPORTED, "d_model, head width, d_ff, vocabulary and sequence length must be multiples of 8");
   if (c->tf_seq > 4096) return fail(nullptr, PBT_EUNSUPPORTED, "sequence length above 4096");
+  if ((int64_t)c->batch * c->tf_seq > 16000) return fail(nullptr, PBT_EUNSUPPORTED, "more than 16000 positions per member and step");
   if (2 + 12 * L + 4 > PBT_MAX_SEGMENTS || L >= PBT_MAX_DIMS) return fail(nullptr, PBT_EUNSUPPORTED, "too many blocks");
   pbt_layout& lay = pl->lay;
   TfPlan& t = pl->tf;

@@ -51,8 +51,8 @@ hipError_t embed_fwd(const int32_t* pool, int n_pool, int S, int B, int d, int V
 }
 
 // Gradient of the embedding tables, in a fixed summation order (no floating-point atomics):
-//   1. count the positions of every token (integer atomics), 2. one workgroup per member turns the
-//   counts into list starts and files every position under its token, positions ascending,
+//   1. count the positions of every token (integer atomics), 2. the counts become list starts and every position
+//   is filed under its token, positions ascending,
 //   3. one workgroup per (token, member) adds up the rows of its list; tokens that do not occur get
 //   zeros.  The position table's gradient sums the B rows that share a position.
 __global__ __launch_bounds__(256) void tok_count_kernel(const int32_t* __restrict__ tokens, int n, int V, int32_t* __restrict__ start) {
@@ -61,17 +61,12 @@ __global__ __launch_bounds__(256) void tok_count_kernel(const int32_t* __restric
   if (r < n) atomicAdd(&start[(int64_t)i * (V + 1) + tokens[(int64_t)i * n + r]], 1);
 }
 
-__global__ __launch_bounds__(256) void tok_place_kernel(const int32_t* __restrict__ tokens, int n, int V, int32_t* __restrict__ start,
-                                                        int32_t* __restrict__ cursor, int32_t* __restrict__ order) {
+// counts -> list starts (exclusive prefix sum over the vocabulary), one workgroup per member
+__global__ __launch_bounds__(256) void tok_start_kernel(int V, int n, int32_t* __restrict__ start) {
   __shared__ int32_t part[256];
-  __shared__ int32_t s_tok[256];
   const int i = blockIdx.x, tid = threadIdx.x;
   int32_t* __restrict__ st = start + (int64_t)i * (V + 1);
-  int32_t* cur = cursor + (int64_t)i * V;
-  const int32_t* __restrict__ tk = tokens + (int64_t)i * n;
-  int32_t* __restrict__ ord = order + (int64_t)i * n;
-  // exclusive prefix sum of the counts: a span of consecutive tokens per thread
-  const int span = (V + 255) / 256;
+  const int span = (V + 255) / 256;   // a span of consecutive tokens per thread
   const int v0 = tid * span, v1 = min(V, v0 + span);
   int32_t sum = 0;
   for (int v = v0; v < v1; ++v) sum += st[v];
@@ -83,27 +78,38 @@ __global__ __launch_bounds__(256) void tok_place_kernel(const int32_t* __restric
   }
   __syncthreads();
   int32_t run = part[tid];
-  for (int v = v0; v < v1; ++v) { const int32_t c = st[v]; st[v] = run; cur[v] = run; run += c; }
+  for (int v = v0; v < v1; ++v) { const int32_t c = st[v]; st[v] = run; run += c; }
   if (tid == 255) st[V] = n;
+}
+
+// Files every position under its token, positions ascending: position r goes to start[token] + (number of earlier
+// positions of the member with the same token).  A workgroup takes 256 positions and counts by looking at all earlier
+// tokens of the member, staged in LDS (n^2 / 2 integer compares per member, spread over the whole device: with one
+// workgroup per member walking the positions in order this step took 150 us on 16 of 256 compute units).
+__global__ __launch_bounds__(256) void tok_place_kernel(const int32_t* __restrict__ tokens, int n, int V, const int32_t* __restrict__ start,
+                                                        int32_t* __restrict__ order) {
+  extern __shared__ __attribute__((aligned(16))) int32_t s_tok[];   // tokens of positions 0 .. base + 255
+  const int i = blockIdx.y, base = blockIdx.x * 256, tid = threadIdx.x;
+  const int32_t* __restrict__ tk = tokens + (int64_t)i * n;
+  const int upto = min(n, base + 256);
+  // (16-byte loads, several in flight: n is a multiple of 4 and so is upto)
+#pragma unroll 4
+  for (int r = tid * 4; r < upto; r += 1024) *reinterpret_cast<int4*>(s_tok + r) = *reinterpret_cast<const int4*>(tk + r);
+  for (int r = upto + tid; r < base + 256; r += 256) s_tok[r] = -1;   // (a ragged last workgroup reads its whole 256)
   __syncthreads();
-  // file the positions, 256 at a time; inside a batch a position's place among equal tokens is the
-  // number of earlier positions of the batch with the same token
-  for (int base = 0; base < n; base += 256) {
-    const int r = base + tid;
-    const int32_t tok = r < n ? tk[r] : -1;
-    s_tok[tid] = tok;
-    __syncthreads();
-    int rank = 0, later = 0;
-    for (int j = 0; j < 256; ++j) {
-      const bool same = s_tok[j] == tok;
-      rank += (same && j < tid) ? 1 : 0;
-      later += (same && j > tid) ? 1 : 0;
-    }
-    if (tok >= 0) ord[cur[tok] + rank] = r;
-    __syncthreads();
-    if (tok >= 0 && later == 0) cur[tok] += rank + 1;
-    __syncthreads();
+  const int r = base + tid;
+  if (r >= n) return;
+  const int32_t tok = s_tok[r];
+  int rank = 0;
+  // (whole groups of four below the workgroup's first position: the same 16-byte LDS read for every lane)
+#pragma unroll 8
+  for (int j = 0; j < base; j += 4) {   // (base is a multiple of 256; unrolled so that several reads are in flight)
+    const int4 q = *reinterpret_cast<const int4*>(s_tok + j);
+    rank += (q.x == tok ? 1 : 0) + (q.y == tok ? 1 : 0) + (q.z == tok ? 1 : 0) + (q.w == tok ? 1 : 0);
   }
+#pragma unroll 8
+  for (int j = 0; j < 256; ++j) rank += (base + j < r && s_tok[base + j] == tok) ? 1 : 0;
+  order[(int64_t)i * n + start[(int64_t)i * (V + 1) + tok] + rank] = r;
 }
 
 __global__ __launch_bounds__(128) void tok_sum_kernel(const bf16_t* __restrict__ dh, const int32_t* __restrict__ start,
@@ -147,7 +153,10 @@ hipError_t embed_bwd(const bf16_t* dh, const int32_t* tokens, int B, int S, int 
   hipError_t e = fill_u32(reinterpret_cast<uint32_t*>(start), 0u, (int64_t)P * (V + 1), s);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(tok_count_kernel, dim3((n + 255) / 256, P), dim3(256), 0, s, tokens, n, V, start);
-  hipLaunchKernelGGL(tok_place_kernel, dim3(P), dim3(256), 0, s, tokens, n, V, start, cursor, order);
+  (void)cursor;
+  if ((size_t)(n + 255) * sizeof(int32_t) > 64 * 1024 || n % 4) return hipErrorInvalidValue;   // (a member's tokens are staged in LDS)
+  hipLaunchKernelGGL(tok_start_kernel, dim3(P), dim3(256), 0, s, V, n, start);
+  hipLaunchKernelGGL(tok_place_kernel, dim3((n + 255) / 256, P), dim3(256), (size_t)((n + 255) / 256 * 256) * sizeof(int32_t), s, tokens, n, V, start, order);
   hipLaunchKernelGGL(tok_sum_kernel, dim3(V, P), dim3(128), 0, s, dh, start, order, n, d, V, G, stride, tok_off);
   hipLaunchKernelGGL(pos_sum_kernel, dim3(S, P), dim3(128), 0, s, dh, B, S, d, G, stride, pos_off);
   return hipGetLastError();
