@@ -127,7 +127,8 @@ typedef struct {
   float gamma, value_cost;          /* discount; weight of the squared value error (0.5) */
   /* PBT_WL_TRANSFORMER only: decoder-only transformer with n_layers pre-LayerNorm blocks; `batch`
      sequences of tf_seq tokens per step (the pool rows hold tf_seq + 1 tokens: inputs and next-token
-     targets); dims[] unused. */
+     targets); dims[] unused.  Limits (PBT_EUNSUPPORTED otherwise): tf_d_model, the head width tf_d_model / tf_heads,
+     tf_d_ff, tf_vocab and tf_seq multiples of 8; tf_seq <= 4096; batch * tf_seq <= 16000. */
   int32_t tf_vocab, tf_d_model, tf_heads, tf_d_ff, tf_seq;
   int32_t n_train, n_eval;          /* rows (classifier, GAN) or trajectories (actor-critic) of the training set; rows of the held-out set */
   int32_t eval_chunk;               /* rows of the held-out set scored per pass (bounds scratch); 0 = library picks */
