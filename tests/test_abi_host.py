@@ -98,7 +98,8 @@ def test_transformer_layout_lists_every_parameter_array_in_order():
 
 
 @pytest.mark.parametrize("change", [dict(d_model=500), dict(heads=3), dict(seq=100), dict(n_eval=250), dict(h_max=[math.inf, 1.0, 0.9]),
-                                    dict(optimizer=workloads.OPT_RMSPROP, opt_const=dict(rho=0.9, eps=1e-5))])
+                                    dict(optimizer=workloads.OPT_RMSPROP, opt_const=dict(rho=0.9, eps=1e-5)),
+                                    dict(seq=4104, batch=1, n_eval=1), dict(seq=1024, batch=16, n_eval=16)])
 def test_transformer_bad_configurations_are_rejected(change):
     cfg = binding.make_config(workloads.TRANSFORMER.replace(**change), 1)
     with pytest.raises(binding.PbtError):
