@@ -79,10 +79,10 @@ def test_transformer_reduced_ragged_shapes():
     print("transformer ragged:", {k: float("%.3g" % v) for k, v in worst.items()}, flush=True)
 
 
-@pytest.mark.parametrize("seq,batch", [(96, 2), (128, 2), (32, 3)])
+@pytest.mark.parametrize("seq,batch", [(96, 2), (128, 2), (64, 2), (32, 3)])
 def test_transformer_reduced_one_kernel_attention(seq, batch):
     """Heads of width 64 and sequences of 32, 96 and 128 positions take the attention kernels that keep the
-    score and probability matrices on the chip (one, three and four query blocks); one member without
+    score and probability matrices on the chip (one to four query blocks); one member without
     dropout, two with."""
     wl = _reduced(P=3, vocab=64, d_model=128, heads=2, d_ff=64, n_blocks=2, seq=seq, batch=batch, n_train=16, n_eval=2 * batch)
     H = np.array([[1e-3, 0.0, 0.0], [5e-4, 0.3, 0.05], [1e-3, 0.1, 0.1]], dtype=np.float32)
