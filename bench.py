@@ -228,7 +228,8 @@ def run_workload(key, steps, warmup, fused, baseline_budget_s, variant=None):
     torch.cuda.synchronize()
     dt_steps = time.perf_counter() - t0
     timed = {name: pop.timing_read_class(K[name]) for name in work if name != "copy"}
-    pop.timing_enable_classes([K["copy"]], 4)
+    pop.timing_enable_classes([K["copy"]], 8)
+    pop.timing_stride(1)
     t0 = time.perf_counter()
     pop.eval(d_eval)
     torch.cuda.synchronize()
@@ -237,6 +238,11 @@ def run_workload(key, steps, warmup, fused, baseline_budget_s, variant=None):
     pop.exploit_explore(0)
     torch.cuda.synchronize()
     dt_exploit = time.perf_counter() - t0
+    # (two more rounds outside every clock above: the scores have not changed, so the same members copy again; a
+    # single launch of the copy kernel is too noisy a sample for its roofline entry)
+    for rnd in (1, 2):
+        pop.exploit_explore(rnd)
+    torch.cuda.synchronize()
 
     timed["copy"] = pop.timing_read_class(K["copy"])
     rooflines = []
