@@ -62,6 +62,8 @@ struct TfPlan {
   bool fused_attn;                  // one attention kernel per pass: no score / probability arrays, o_keep instead
   size_t o_keep[PBT_MAX_DIMS];      // keep bits of the attention dropout site (fused attention only)
   size_t o_attn_stats;              // softmax row statistics between the two backward kernels (fused attention only)
+  size_t o_wpart, o_wcolpart;       // partial weight gradients of contractions cut into pieces (transformer_host.hip: wgrad)
+  int64_t wpart_elems, wcol_elems;  // elements per (member, piece) these buffers hold (0: no matrix of this workload is cut)
   size_t o_score, o_tmp_d[3], o_tmp_f[2], o_dqkv, o_uf, o_logits, o_dlogits, o_rowloss, o_evalrow, o_tokstart, o_tokcursor, o_tokorder, o_lnpart;
 };
 

@@ -154,6 +154,10 @@ hipError_t softmax_bwd(const bf16_t* pq, bf16_t* dpd, int P, int64_t rows, int S
 hipError_t residual_dropout_layernorm(const bf16_t* x, const bf16_t* res, int P, int rows, int d, const DropArgs& dr, int site, bf16_t* h,
                                       uint16_t* record, const float* W32, int64_t stride, int64_t g_off, int64_t b_off, bf16_t* y, float* mean,
                                       float* rstd, hipStream_t s);
+// adds up the n_parts partial weight gradients part[P * n_parts][count] (and their column sums colpart[P * n_parts][N])
+// of a contraction that was cut into pieces, in piece order, into G at w_off (b_off)
+hipError_t wgrad_combine(const float* part, const float* colpart, int n_parts, int P, int64_t count, int N, float* G, int64_t stride,
+                         int64_t w_off, int64_t b_off, hipStream_t s);
 // Attention of one (member, sequence, head) per workgroup without score or probability arrays in memory, for
 // 64-wide heads and sequences of 32, 64, 96 or 128 positions (attention_fused_applies).  qkv: [P][Bc*S][3d]
 // (queries, keys, values side by side, heads side by side inside each); o, dO: [P][Bc*S][d]; dqkv like qkv.

@@ -33,8 +33,27 @@ pbt_status dense(const Ctx& x, const bf16_t* in, int K, int N, int64_t w, int64_
   PBT_LAUNCH(x.h, PBT_K_GEMM_FWD, x.s, gemm_bias_act(o, x.W32 + b, x.S_, Z, out, N, (int64_t)x.n * N, act, x.s, site));
   return PBT_OK;
 }
+// A small weight matrix over many rows (the attention output projection: 512 x 512 from 4096 rows) gives 256 x 256 tiles
+// to a quarter of the compute units, and smaller tiles spend the long contraction on loop overhead (12 % of the MFMA peak):
+// its contraction is cut into WGRAD_PARTS pieces, each a tile of its own, and the pieces are added up in order afterwards.
+constexpr int WGRAD_PARTS = 4;
+bool wgrad_in_parts(int P, int rows, int K, int N) {
+  return (int64_t)((K + 255) / 256) * ((N + 255) / 256) * P <= 64 && K >= 256 && N >= 256 && N % 4 == 0 && ((int64_t)K * N) % 4 == 0 &&
+         rows % (WGRAD_PARTS * 64) == 0 && rows / WGRAD_PARTS >= 1024;
+}
 // G[w] = in^T dout, G[b] = column sums of dout
 pbt_status wgrad(const Ctx& x, const bf16_t* in, int K, const bf16_t* dout, int N, int64_t w, int64_t b) {
+  if ((int64_t)K * N <= x.h->plan.tf.wpart_elems && N <= x.h->plan.tf.wcol_elems && wgrad_in_parts(x.P, x.n, K, N)) {
+    float* part = x.sc<float>(x.h->plan.tf.o_wpart);
+    float* colpart = x.sc<float>(x.h->plan.tf.o_wcolpart);
+    const int rows = x.n / WGRAD_PARTS;
+    GemmOperands o{in, K, (int64_t)x.n * K, true, dout, N, (int64_t)x.n * N, false, K, N, rows, x.P * WGRAD_PARTS};
+    o.inner = WGRAD_PARTS; o.sa_in = (int64_t)rows * K; o.sb_in = (int64_t)rows * N;
+    o.colsum = colpart; o.colsum_stride = N;
+    PBT_LAUNCH(x.h, PBT_K_GEMM_WGRAD, x.s, gemm_store_f32(o, part, N, (int64_t)K * N, x.s));
+    PBT_HIP(x.h, wgrad_combine(part, colpart, WGRAD_PARTS, x.P, (int64_t)K * N, N, x.G, x.S_, w, b, x.s));
+    return PBT_OK;
+  }
   // The column sums are a by-product of the GEMM (its first tile row adds up the dout slabs it stages anyway).
   // That tile row finishes last and the launch takes 17 % longer (146 -> 171 us), which is still cheaper than a
   // pass of its own over dout (41 us per layer): 16.78 -> 16.43 ms per population step.
@@ -225,6 +244,20 @@ pbt_status tf_check_and_plan(const pbt_config* c, Plan* pl, Carver* w) {
   t.o_meanf = w->take(P * n * 4); t.o_rstdf = w->take(P * n * 4);
   t.o_score = t.fused_attn ? 0 : w->take(ns);
   t.o_attn_stats = t.fused_attn ? w->take(attention_stats_bytes((int)P, c->batch, D.H)) : 0;
+  t.o_wpart = t.o_wcolpart = 0;
+  t.wpart_elems = t.wcol_elems = 0;
+  {
+    const int shapes[5][2] = {{D.d, 3 * D.d}, {D.d, D.d}, {D.d, D.f}, {D.f, D.d}, {D.d, D.V}};   // (rows in, columns out) of every weight matrix
+    for (const auto& sh : shapes)
+      if (wgrad_in_parts((int)P, (int)n, sh[0], sh[1])) {
+        t.wpart_elems = std::max<int64_t>(t.wpart_elems, (int64_t)sh[0] * sh[1]);
+        t.wcol_elems = std::max<int64_t>(t.wcol_elems, sh[1]);
+      }
+    if (t.wpart_elems) {
+      t.o_wpart = w->take(P * WGRAD_PARTS * (size_t)t.wpart_elems * 4);
+      t.o_wcolpart = w->take(P * WGRAD_PARTS * (size_t)t.wcol_elems * 4);
+    }
+  }
   for (int k = 0; k < 3; ++k) t.o_tmp_d[k] = w->take(nd);
   for (int k = 0; k < 2; ++k) t.o_tmp_f[k] = w->take(nf);
   t.o_dqkv = w->take(3 * nd);

@@ -767,6 +767,38 @@ hipError_t residual_dropout_layernorm(const bf16_t* x, const bf16_t* res, int P,
   return hipGetLastError();
 }
 
+// ---- weight gradients formed in several parts of the contraction -------------------------------------------
+// G[i][w_off + e] = sum over parts q (in order) of part[(i * n_parts + q)][e], e < count (a multiple of 4), and
+// likewise the bias gradient from the parts' column sums: the second half of a weight-gradient product whose
+// contraction was cut into n_parts pieces so that a small matrix still gives every compute unit a tile.
+__global__ __launch_bounds__(256) void wgrad_combine_kernel(const float* __restrict__ part, const float* __restrict__ colpart, int n_parts,
+                                                            int64_t count, int N, float* __restrict__ G, int64_t stride, int64_t w_off, int64_t b_off) {
+  const int i = blockIdx.y;
+  const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (e < count) {
+    float4 a = *reinterpret_cast<const float4*>(part + (int64_t)i * n_parts * count + e);
+    for (int q = 1; q < n_parts; ++q) {
+      const float4 b = *reinterpret_cast<const float4*>(part + ((int64_t)i * n_parts + q) * count + e);
+      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    *reinterpret_cast<float4*>(G + (int64_t)i * stride + w_off + e) = a;
+  }
+  if (e < N) {   // (N is a multiple of 4 too)
+    float4 a = *reinterpret_cast<const float4*>(colpart + (int64_t)i * n_parts * N + e);
+    for (int q = 1; q < n_parts; ++q) {
+      const float4 b = *reinterpret_cast<const float4*>(colpart + ((int64_t)i * n_parts + q) * N + e);
+      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    *reinterpret_cast<float4*>(G + (int64_t)i * stride + b_off + e) = a;
+  }
+}
+hipError_t wgrad_combine(const float* part, const float* colpart, int n_parts, int P, int64_t count, int N, float* G, int64_t stride,
+                         int64_t w_off, int64_t b_off, hipStream_t s) {
+  if (count % 4 || N % 4 || w_off % 4 || b_off % 4 || stride % 4 || n_parts < 1 || N > count) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(wgrad_combine_kernel, dim3((unsigned)((count / 4 + 255) / 256), P), dim3(256), 0, s, part, colpart, n_parts, count, N, G, stride, w_off, b_off);
+  return hipGetLastError();
+}
+
 // ---- label-smoothed cross-entropy over the vocabulary -----------------------------------------
 // One workgroup per row of float logits[rows][V].  loss = lse - (1-e) l_y - (e/V) sum l;
 // dlogits = (softmax - ((1-e) onehot + e/V)) * gscale as bf16 (when dlogits != null).

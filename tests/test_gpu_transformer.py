@@ -101,6 +101,16 @@ def test_transformer_reduced_one_kernel_attention(seq, batch):
     print("transformer one-kernel attention, seq %d:" % seq, {k: float("%.3g" % v) for k, v in worst.items()}, flush=True)
 
 
+def test_transformer_reduced_weight_gradient_in_parts():
+    """4096 rows per member and a 256 x 256 output projection: the weight gradients of the small matrices are formed
+    in four pieces of the contraction and added up (here the attention projections and, with d_ff = 256, the
+    feed-forward matrices too)."""
+    wl = _reduced(P=2, vocab=64, d_model=256, heads=4, d_ff=256, n_blocks=1, seq=128, batch=32, n_train=64, n_eval=32)
+    pair = TransformerPair(wl, H=np.array([[1e-3, 0.1, 0.05], [5e-4, 0.0, 0.0]], dtype=np.float32))
+    worst = _teacher_forced(pair, range(2), range(2), tol_grad=2 * TOL_GRAD_SMALL, tol_w=2 * TOL_GRAD_SMALL)
+    print("transformer weight gradient in parts:", {k: float("%.3g" % v) for k, v in worst.items()}, flush=True)
+
+
 def test_transformer_free_running_eval_and_exploit():
     pair = TransformerPair(_reduced(P=4))
     g, P = pair.gpu, 4
